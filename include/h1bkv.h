@@ -1,0 +1,185 @@
+/*
+ * h1bkv.h -- C ABI of the MI355X (gfx950) H1B-KV library: decode-step attention over a hybrid
+ * compressed KV cache (keys = packed 1-bit random-projection sketches, values = 4-bit
+ * group-quantised codes), and the cache-append step that produces it (arxiv 2510.05529, Sec. IV).
+ *
+ * Conventions that hold for every entry point
+ *   - Return value: H1BKV_OK (0) or a negative H1BKV_E* code; nothing throws, aborts or prints.
+ *   - "dev" pointers are device (HIP global memory) addresses on the handle's device; "host" pointers
+ *     are ordinary host memory.  The caller owns every buffer it passes (pool, Q/K/V, out, workspace)
+ *     and the stream; the library owns only the host-side handle and its page bookkeeping.
+ *   - All arguments are validated on the host before any device work; a call that returns an error
+ *     has changed neither the cache contents nor the bookkeeping.
+ *   - h1bkv_append_kv and h1bkv_decode_attn only enqueue kernels on `hip_stream` (a hipStream_t, NULL
+ *     for the default stream) and return without synchronising.  All calls on one handle must be
+ *     ordered by the caller (one stream, or explicit dependencies) and made from one thread at a time.
+ *   - The calling thread's current HIP device must be the handle's device.
+ *   - Layouts are row-major with the last index fastest.  Notation: b = sketch_bits, W = b/64,
+ *     d = head_dim, G = group_size, n_g = d/G, r = n_q_heads / n_kv_heads.
+ */
+#ifndef H1BKV_H
+#define H1BKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct h1bkv_cache h1bkv_cache; /* opaque host-side handle */
+
+enum { H1BKV_F32 = 0, H1BKV_F16 = 1 };  /* dtype of Q, K, V at the boundary */
+
+enum {
+    H1BKV_OK = 0,
+    H1BKV_EINVAL = -1,     /* an argument value is not allowed (bad dtype, tau <= 0, duplicate seq id ...) */
+    H1BKV_ENULL = -2,      /* a required pointer is NULL */
+    H1BKV_ESHAPE = -3,     /* a shape/config constraint is violated (see h1bkv_config) */
+    H1BKV_ENOSPACE = -4,   /* page pool exhausted, or a sequence would exceed max_pages_per_seq */
+    H1BKV_ERANGE = -5,     /* sequence id / head / token range out of bounds */
+    H1BKV_EWORKSPACE = -6, /* workspace or pool smaller than required */
+    H1BKV_EHIP = -7,       /* a HIP runtime call failed (launch, copy, wrong current device) */
+    H1BKV_ENODEVICE = -8   /* the handle is bookkeeping-only (device == H1BKV_DEVICE_NONE) and the call needs a GPU */
+};
+
+#define H1BKV_DEVICE_NONE (-1)
+#define H1BKV_PAGE_TOKENS 256
+
+/*
+ * Cache geometry.  Constraints (violations give H1BKV_ESHAPE):
+ *   n_kv_heads >= 1, n_q_heads a multiple of n_kv_heads (query head h reads KV head h / r);
+ *   head_dim in {64, 128, 256};  sketch_bits in {64, 128, 256, 512} (the paper's ablation puts the
+ *   useful lower bound at b = 64, Sec. VI-E/F);  group_size in {32, 64, 128} and dividing head_dim;
+ *   in_dtype H1BKV_F32 or H1BKV_F16;  page_tokens 0 (= default) or H1BKV_PAGE_TOKENS;
+ *   max_seqs, max_pages, max_pages_per_seq >= 1.
+ * device: HIP device ordinal, or H1BKV_DEVICE_NONE for a bookkeeping-only handle that runs all
+ * validation and page accounting but never touches a GPU (capacity planning, host-side tests).
+ */
+typedef struct {
+    int32_t n_q_heads, n_kv_heads, head_dim;
+    int32_t sketch_bits;
+    int32_t group_size;
+    int32_t in_dtype;
+    int32_t page_tokens;
+    int32_t max_seqs, max_pages, max_pages_per_seq;
+    int32_t device;
+} h1bkv_config;
+
+/* Library version, major*10000 + minor*100 + patch. */
+int h1bkv_version(void);
+
+/* Static description of an error code (never NULL). */
+const char *h1bkv_strerror(int code);
+
+/*
+ * Device bytes the caller must provide as the pool for this geometry (0 if cfg is NULL or invalid).
+ * The pool holds R and its transpose, the block table, and three planes per page:
+ * sketches [page][H_kv][256][W] u64 (Eq.(2)), codes [page][H_kv][256][d/2] u8 and
+ * {fp16 scale, fp16 zero} pairs [page][H_kv][256][n_g] (Eq.(4)).
+ */
+size_t h1bkv_pool_bytes(const h1bkv_config *cfg);
+
+/*
+ * Create a handle over `pool_dev` (pool_bytes >= h1bkv_pool_bytes(cfg), 256-byte aligned; ignored and
+ * may be NULL for a bookkeeping-only handle).  R_host [b][d] fp32 is the fixed Gaussian projection of
+ * Eq.(2) (Sec. III: R_ij ~ N(0,1), drawn once, shared by keys and queries of every head); it is
+ * copied to the device here, synchronously.  All sequences start empty, all pages free.
+ */
+int h1bkv_create(const h1bkv_config *cfg, void *pool_dev, size_t pool_bytes, const float *R_host,
+                 h1bkv_cache **out);
+
+/* Free the host handle.  The pool stays the caller's.  NULL is accepted. */
+int h1bkv_destroy(h1bkv_cache *c);
+
+/* Copy R [b][d] back to host memory (from the handle's host copy). */
+int h1bkv_get_projection(const h1bkv_cache *c, float *R_host_out);
+
+/* Bookkeeping (host only, no device work). */
+int h1bkv_seq_len(const h1bkv_cache *c, int32_t seq_id, int32_t *len_out);
+int h1bkv_free_pages(const h1bkv_cache *c, int32_t *n_out);
+int h1bkv_reset_seq(h1bkv_cache *c, int32_t seq_id);                      /* length 0, pages returned */
+int h1bkv_truncate_seq(h1bkv_cache *c, int32_t seq_id, int32_t new_len);  /* 0 <= new_len <= length   */
+
+/*
+ * Cache append (Sec. IV-A Eq.(2) and Sec. IV-B Eq.(4)): for each of the n_seqs sequences named in
+ * seq_ids_host (distinct ids), append n_new >= 1 tokens at positions [len, len + n_new).
+ * For every (sequence, token, KV head):
+ *   sketch bit i = ( sum_j R[i][j] k[j] >= 0 ), the sum taken in fp32 as a chain of fused multiply-adds
+ *   over j = 0..d-1 from +0; bit i is stored in word i/64 at bit position i%64;
+ *   per group of G channels of v: zero = fp16(min), scale = fp16((max - min)/15),
+ *   code = clamp(round_half_even((v - zero)/scale), 0, 15) in fp32 (code 0 when scale is 0).
+ * k_dev, v_dev: [n_seqs][n_new][n_kv_heads][d] in in_dtype, addressed with the given strides (in
+ * elements; the channel stride is 1).  Inputs must be finite.  Pages are taken from the free list as
+ * needed (H1BKV_ENOSPACE if they do not suffice; then nothing is appended).
+ */
+int h1bkv_append_kv(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n_seqs, int32_t n_new,
+                    const void *k_dev, const void *v_dev, int64_t stride_seq, int64_t stride_tok,
+                    int64_t stride_head, void *hip_stream);
+
+/*
+ * Workspace bytes h1bkv_decode_attn needs for up to n_seqs sequences of up to max_ctx tokens
+ * (query sketches plus per-chunk partial results); monotone in both arguments.
+ */
+size_t h1bkv_decode_workspace_bytes(const h1bkv_cache *c, int32_t n_seqs, int32_t max_ctx);
+
+/*
+ * Decode-step attention (Sec. IV-A Eq.(3), Sec. IV-C Eq.(5)): for every sequence s in seq_ids_host
+ * and every query head h, with T = current length of s:
+ *   s_q = sign(R q) (same recipe as the keys);  alpha_t = (b - 2 popcount(s_q xor s_t)) / b;
+ *   out = sum_t softmax_t(alpha_t / tau) * (scale_t * code_t + zero_t)   over all T cached tokens
+ * (no mask; T == 0 gives zeros).  q_dev [n_seqs][n_q_heads][d] in in_dtype, dense;
+ * out_dev [n_seqs][n_q_heads][d] fp32; tau > 0 and finite.  The context is processed in chunks whose
+ * partial (max, sum, weighted sum) results are merged by a log-sum-exp step; accumulation is fp32.
+ * workspace_dev: >= h1bkv_decode_workspace_bytes(c, n_seqs, longest T), 256-byte aligned.
+ */
+int h1bkv_decode_attn(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n_seqs, const void *q_dev,
+                      float tau, float *out_dev, void *workspace_dev, size_t workspace_bytes,
+                      void *hip_stream);
+
+/*
+ * Tuning override for the context chunk of h1bkv_decode_attn: tokens per chunk, a multiple of
+ * H1BKV_PAGE_TOKENS up to 2048, or 0 for the built-in choice.  Results do not depend on it beyond
+ * fp32 summation order.
+ */
+int h1bkv_set_decode_chunk(h1bkv_cache *c, int32_t chunk_tokens);
+
+/*
+ * Canonical, layout-independent view of cached records (synchronous: waits for the device first).
+ * Tokens [t0, t0+n) of (seq_id, kv_head) to host arrays: sketch_out [n][W] u64, codes_out [n][d/2] u8
+ * (channel 2m low nibble, 2m+1 high nibble of byte m), scale_out / zero_out [n][n_g] fp16 bit patterns.
+ * Any output pointer may be NULL to skip that plane.  h1bkv_import_tokens is the mirror image and
+ * overwrites existing positions; h1bkv_extend_seq reserves n_new uninitialised positions (pages and
+ * block-table update on `hip_stream`) so that a saved cache can be restored with import.
+ */
+int h1bkv_export_tokens(const h1bkv_cache *c, int32_t seq_id, int32_t kv_head, int32_t t0, int32_t n,
+                        uint64_t *sketch_out, uint8_t *codes_out, uint16_t *scale_out, uint16_t *zero_out);
+int h1bkv_import_tokens(h1bkv_cache *c, int32_t seq_id, int32_t kv_head, int32_t t0, int32_t n,
+                        const uint64_t *sketch_in, const uint8_t *codes_in, const uint16_t *scale_in,
+                        const uint16_t *zero_in);
+int h1bkv_extend_seq(h1bkv_cache *c, int32_t seq_id, int32_t n_new, void *hip_stream);
+
+/*
+ * Per-kernel timing for benchmarks.  After h1bkv_profile_enable(c, capacity > 0), every launch of the
+ * library's kernels on this handle is bracketed by a pair of HIP events on the launch stream (up to
+ * `capacity` launches per kernel kind; later ones are not recorded).  h1bkv_profile_read waits for the
+ * recorded events and writes the elapsed milliseconds of each recorded launch of `kernel` to ms_out
+ * (at most cap values) and their number to n_out, then clears that kind's records.
+ * capacity == 0 disables recording and releases the events.
+ */
+enum { H1BKV_K_APPEND = 0, H1BKV_K_QSKETCH = 1, H1BKV_K_DECODE_SPLIT = 2, H1BKV_K_MERGE = 3, H1BKV_K_COUNT = 4 };
+int h1bkv_profile_enable(h1bkv_cache *c, int32_t capacity);
+int h1bkv_profile_read(h1bkv_cache *c, int32_t kernel, float *ms_out, int32_t cap, int32_t *n_out);
+
+/*
+ * Plain device-to-device streaming copy of n_bytes (a multiple of 16; both pointers 16-byte aligned)
+ * with the library's own 16-byte-per-lane grid-stride kernel, enqueued on hip_stream.  It exists as
+ * the known-size reference against which hardware traffic counters and the achievable HBM rate are
+ * calibrated; it is not part of the attention path.
+ */
+int h1bkv_stream_copy(void *dst_dev, const void *src_dev, size_t n_bytes, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* H1BKV_H */

@@ -1,0 +1,557 @@
+// Host side of the H1B-KV library: handle, argument validation, page bookkeeping, launch sequencing,
+// canonical export/import and the per-kernel event timer.  No arithmetic of the method lives here.
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "internal.h"
+
+using namespace h1bkv;
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+struct Layout {
+    size_t off_R, off_RT, off_bt, off_sketch, off_codes, off_meta, total;
+};
+
+bool config_ok(const h1bkv_config *c) {
+    if (!c) return false;
+    if (c->n_kv_heads < 1 || c->n_q_heads < 1 || c->n_q_heads % c->n_kv_heads != 0) return false;
+    if (c->head_dim != 64 && c->head_dim != 128 && c->head_dim != 256) return false;
+    if (c->sketch_bits != 64 && c->sketch_bits != 128 && c->sketch_bits != 256 && c->sketch_bits != 512) return false;
+    if (c->group_size != 32 && c->group_size != 64 && c->group_size != 128) return false;
+    if (c->head_dim % c->group_size != 0) return false;
+    if (c->in_dtype != H1BKV_F32 && c->in_dtype != H1BKV_F16) return false;
+    if (c->page_tokens != 0 && c->page_tokens != kPage) return false;
+    if (c->max_seqs < 1 || c->max_pages < 1 || c->max_pages_per_seq < 1) return false;
+    if (c->device < H1BKV_DEVICE_NONE) return false;
+    return true;
+}
+
+Layout make_layout(const h1bkv_config &c) {
+    Layout L{};
+    const size_t b = c.sketch_bits, d = c.head_dim, W = b / 64, ng = d / c.group_size;
+    const size_t rec = (size_t)c.max_pages * c.n_kv_heads * kPage;
+    size_t o = 0;
+    L.off_R = o;       o = align_up(o + b * d * sizeof(float));
+    L.off_RT = o;      o = align_up(o + b * d * sizeof(float));
+    L.off_bt = o;      o = align_up(o + (size_t)c.max_seqs * c.max_pages_per_seq * sizeof(int32_t));
+    L.off_sketch = o;  o = align_up(o + rec * W * 8);
+    L.off_codes = o;   o = align_up(o + rec * (d / 2));
+    L.off_meta = o;    o = align_up(o + rec * ng * 4);
+    L.total = o;
+    return L;
+}
+
+struct EventPair {
+    hipEvent_t a, b;
+};
+
+}  // namespace
+
+struct h1bkv_cache {
+    h1bkv_config cfg;
+    Layout lay;
+    int W, ng, r;
+    bool dry;
+    char *pool;
+    std::vector<float> R;
+    std::vector<int32_t> seq_len;
+    std::vector<std::vector<int32_t>> seq_pages;
+    std::vector<int32_t> free_list;     // stack of free page ids
+    int32_t chunk_override;
+    // profiling
+    int32_t prof_cap;
+    std::vector<EventPair> prof_events[H1BKV_K_COUNT];
+    int32_t prof_used[H1BKV_K_COUNT];
+
+    PoolView view() const {
+        PoolView v{};
+        v.R = reinterpret_cast<const float *>(pool + lay.off_R);
+        v.RT = reinterpret_cast<const float *>(pool + lay.off_RT);
+        v.block_table = reinterpret_cast<int32_t *>(pool + lay.off_bt);
+        v.sketch = reinterpret_cast<uint64_t *>(pool + lay.off_sketch);
+        v.codes = reinterpret_cast<uint8_t *>(pool + lay.off_codes);
+        v.meta = reinterpret_cast<uint32_t *>(pool + lay.off_meta);
+        v.max_pages_per_seq = cfg.max_pages_per_seq;
+        v.n_kv_heads = cfg.n_kv_heads;
+        v.n_q_heads = cfg.n_q_heads;
+        v.head_dim = cfg.head_dim;
+        v.sketch_bits = cfg.sketch_bits;
+        v.group_size = cfg.group_size;
+        return v;
+    }
+};
+
+namespace {
+
+int check_device(const h1bkv_cache *c) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev != c->cfg.device) return H1BKV_EHIP;
+    return H1BKV_OK;
+}
+
+// Event bracket around one kernel launch; inert unless profiling is enabled.
+struct Timed {
+    h1bkv_cache *c;
+    int kind;
+    hipStream_t st;
+    int slot;
+    Timed(h1bkv_cache *c_, int kind_, hipStream_t st_) : c(c_), kind(kind_), st(st_), slot(-1) {
+        if (c->prof_cap > 0 && c->prof_used[kind] < c->prof_cap) {
+            slot = c->prof_used[kind]++;
+            (void)hipEventRecord(c->prof_events[kind][slot].a, st);
+        }
+    }
+    ~Timed() {
+        if (slot >= 0) (void)hipEventRecord(c->prof_events[kind][slot].b, st);
+    }
+};
+
+void release_events(h1bkv_cache *c) {
+    for (int k = 0; k < H1BKV_K_COUNT; ++k) {
+        for (auto &e : c->prof_events[k]) {
+            (void)hipEventDestroy(e.a);
+            (void)hipEventDestroy(e.b);
+        }
+        c->prof_events[k].clear();
+        c->prof_used[k] = 0;
+    }
+    c->prof_cap = 0;
+}
+
+int pages_for(int32_t len) { return (len + kPage - 1) / kPage; }
+
+// Pages that must be newly taken so that seq can hold new_len tokens, or a negative error.
+int pages_needed(const h1bkv_cache *c, int32_t seq, int64_t new_len) {
+    if (new_len > (int64_t)c->cfg.max_pages_per_seq * kPage) return H1BKV_ENOSPACE;
+    return pages_for((int32_t)new_len) - (int)c->seq_pages[seq].size();
+}
+
+// Take pages for seq up to new_len and queue the block-table updates.
+void take_pages(h1bkv_cache *c, int32_t seq, int32_t new_len, std::vector<int32_t> &upd_index,
+                std::vector<int32_t> &upd_page) {
+    auto &pg = c->seq_pages[seq];
+    while ((int)pg.size() < pages_for(new_len)) {
+        int32_t p = c->free_list.back();
+        c->free_list.pop_back();
+        upd_index.push_back(seq * c->cfg.max_pages_per_seq + (int32_t)pg.size());
+        upd_page.push_back(p);
+        pg.push_back(p);
+    }
+}
+
+int publish(h1bkv_cache *c, const std::vector<int32_t> &idx, const std::vector<int32_t> &page, hipStream_t st) {
+    if (c->dry) return H1BKV_OK;
+    size_t done = 0;
+    while (done < idx.size()) {
+        TablePairs tp;
+        tp.n = (int32_t)std::min<size_t>(kPublishPairs, idx.size() - done);
+        for (int i = 0; i < tp.n; ++i) {
+            tp.index[i] = idx[done + i];
+            tp.page[i] = page[done + i];
+        }
+        if (launch_publish(tp, c->view().block_table, st) != hipSuccess) return H1BKV_EHIP;
+        done += tp.n;
+    }
+    return H1BKV_OK;
+}
+
+int check_seq_ids(const h1bkv_cache *c, const int32_t *ids, int32_t n) {
+    if (!ids) return H1BKV_ENULL;
+    if (n < 1) return H1BKV_EINVAL;
+    std::vector<char> seen(c->cfg.max_seqs, 0);
+    for (int i = 0; i < n; ++i) {
+        if (ids[i] < 0 || ids[i] >= c->cfg.max_seqs) return H1BKV_ERANGE;
+        if (seen[ids[i]]) return H1BKV_EINVAL;
+        seen[ids[i]] = 1;
+    }
+    return H1BKV_OK;
+}
+
+// Chunk (tokens) the decode uses for a call of n_seqs sequences whose longest context is max_ctx:
+// the largest page multiple (<= kMaxChunk) that still leaves enough workgroups to fill the chip.
+int choose_chunk(const h1bkv_cache *c, int n_seqs, int max_ctx) {
+    if (c->chunk_override > 0) return c->chunk_override;
+    const int64_t heads = (int64_t)n_seqs * c->cfg.n_kv_heads;
+    const int64_t target_wgs = 4096;
+    int chunk = kMaxChunk;
+    while (chunk > kPage && heads * ((max_ctx + chunk - 1) / chunk) < target_wgs) chunk /= 2;
+    return chunk;
+}
+
+}  // namespace
+
+extern "C" {
+
+int h1bkv_version(void) { return 100; }
+
+const char *h1bkv_strerror(int code) {
+    switch (code) {
+        case H1BKV_OK: return "ok";
+        case H1BKV_EINVAL: return "invalid argument value";
+        case H1BKV_ENULL: return "required pointer is NULL";
+        case H1BKV_ESHAPE: return "shape or configuration constraint violated";
+        case H1BKV_ENOSPACE: return "page pool exhausted or sequence page limit reached";
+        case H1BKV_ERANGE: return "sequence id, head or token range out of bounds";
+        case H1BKV_EWORKSPACE: return "workspace or pool too small";
+        case H1BKV_EHIP: return "HIP runtime call failed or wrong current device";
+        case H1BKV_ENODEVICE: return "bookkeeping-only handle: call needs a GPU";
+        default: return "unknown error code";
+    }
+}
+
+size_t h1bkv_pool_bytes(const h1bkv_config *cfg) {
+    if (!config_ok(cfg)) return 0;
+    return make_layout(*cfg).total;
+}
+
+int h1bkv_create(const h1bkv_config *cfg, void *pool_dev, size_t pool_bytes, const float *R_host, h1bkv_cache **out) {
+    if (!cfg || !R_host || !out) return H1BKV_ENULL;
+    if (!config_ok(cfg)) return H1BKV_ESHAPE;
+    const bool dry = cfg->device == H1BKV_DEVICE_NONE;
+    Layout lay = make_layout(*cfg);
+    if (!dry) {
+        if (!pool_dev) return H1BKV_ENULL;
+        if (reinterpret_cast<uintptr_t>(pool_dev) % kAlign != 0) return H1BKV_EINVAL;
+        if (pool_bytes < lay.total) return H1BKV_EWORKSPACE;
+    }
+    h1bkv_cache *c = new (std::nothrow) h1bkv_cache();
+    if (!c) return H1BKV_EINVAL;
+    c->cfg = *cfg;
+    c->cfg.page_tokens = kPage;
+    c->lay = lay;
+    c->W = cfg->sketch_bits / 64;
+    c->ng = cfg->head_dim / cfg->group_size;
+    c->r = cfg->n_q_heads / cfg->n_kv_heads;
+    c->dry = dry;
+    c->pool = static_cast<char *>(pool_dev);
+    const size_t nR = (size_t)cfg->sketch_bits * cfg->head_dim;
+    c->R.assign(R_host, R_host + nR);
+    c->seq_len.assign(cfg->max_seqs, 0);
+    c->seq_pages.assign(cfg->max_seqs, {});
+    c->free_list.resize(cfg->max_pages);
+    for (int i = 0; i < cfg->max_pages; ++i) c->free_list[i] = cfg->max_pages - 1 - i;  // page 0 is taken first
+    c->chunk_override = 0;
+    c->prof_cap = 0;
+    for (int k = 0; k < H1BKV_K_COUNT; ++k) c->prof_used[k] = 0;
+    if (!dry) {
+        if (check_device(c) != H1BKV_OK) {
+            delete c;
+            return H1BKV_EHIP;
+        }
+        std::vector<float> RT(nR);
+        for (int i = 0; i < cfg->sketch_bits; ++i)
+            for (int j = 0; j < cfg->head_dim; ++j) RT[(size_t)j * cfg->sketch_bits + i] = R_host[(size_t)i * cfg->head_dim + j];
+        bool ok = hipDeviceSynchronize() == hipSuccess;
+        ok = ok && hipMemcpy(c->pool + lay.off_R, R_host, nR * sizeof(float), hipMemcpyHostToDevice) == hipSuccess;
+        ok = ok && hipMemcpy(c->pool + lay.off_RT, RT.data(), nR * sizeof(float), hipMemcpyHostToDevice) == hipSuccess;
+        ok = ok && hipMemset(c->pool + lay.off_bt, 0, (size_t)cfg->max_seqs * cfg->max_pages_per_seq * sizeof(int32_t)) == hipSuccess;
+        ok = ok && hipDeviceSynchronize() == hipSuccess;
+        if (!ok) {
+            delete c;
+            return H1BKV_EHIP;
+        }
+    }
+    *out = c;
+    return H1BKV_OK;
+}
+
+int h1bkv_destroy(h1bkv_cache *c) {
+    if (!c) return H1BKV_OK;
+    release_events(c);
+    delete c;
+    return H1BKV_OK;
+}
+
+int h1bkv_get_projection(const h1bkv_cache *c, float *R_host_out) {
+    if (!c || !R_host_out) return H1BKV_ENULL;
+    std::memcpy(R_host_out, c->R.data(), c->R.size() * sizeof(float));
+    return H1BKV_OK;
+}
+
+int h1bkv_seq_len(const h1bkv_cache *c, int32_t seq_id, int32_t *len_out) {
+    if (!c || !len_out) return H1BKV_ENULL;
+    if (seq_id < 0 || seq_id >= c->cfg.max_seqs) return H1BKV_ERANGE;
+    *len_out = c->seq_len[seq_id];
+    return H1BKV_OK;
+}
+
+int h1bkv_free_pages(const h1bkv_cache *c, int32_t *n_out) {
+    if (!c || !n_out) return H1BKV_ENULL;
+    *n_out = (int32_t)c->free_list.size();
+    return H1BKV_OK;
+}
+
+int h1bkv_truncate_seq(h1bkv_cache *c, int32_t seq_id, int32_t new_len) {
+    if (!c) return H1BKV_ENULL;
+    if (seq_id < 0 || seq_id >= c->cfg.max_seqs) return H1BKV_ERANGE;
+    if (new_len < 0 || new_len > c->seq_len[seq_id]) return H1BKV_ERANGE;
+    auto &pg = c->seq_pages[seq_id];
+    while ((int)pg.size() > pages_for(new_len)) {
+        c->free_list.push_back(pg.back());
+        pg.pop_back();
+    }
+    c->seq_len[seq_id] = new_len;
+    return H1BKV_OK;
+}
+
+int h1bkv_reset_seq(h1bkv_cache *c, int32_t seq_id) { return h1bkv_truncate_seq(c, seq_id, 0); }
+
+int h1bkv_set_decode_chunk(h1bkv_cache *c, int32_t chunk_tokens) {
+    if (!c) return H1BKV_ENULL;
+    if (chunk_tokens != 0 && (chunk_tokens < kPage || chunk_tokens > kMaxChunk || chunk_tokens % kPage != 0)) return H1BKV_EINVAL;
+    c->chunk_override = chunk_tokens;
+    return H1BKV_OK;
+}
+
+int h1bkv_extend_seq(h1bkv_cache *c, int32_t seq_id, int32_t n_new, void *hip_stream) {
+    if (!c) return H1BKV_ENULL;
+    if (seq_id < 0 || seq_id >= c->cfg.max_seqs) return H1BKV_ERANGE;
+    if (n_new < 1) return H1BKV_EINVAL;
+    const int64_t new_len = (int64_t)c->seq_len[seq_id] + n_new;
+    const int need = pages_needed(c, seq_id, new_len);
+    if (need < 0) return need;
+    if (need > (int)c->free_list.size()) return H1BKV_ENOSPACE;
+    if (!c->dry) {
+        int rc = check_device(c);
+        if (rc != H1BKV_OK) return rc;
+    }
+    std::vector<int32_t> ui, up;
+    take_pages(c, seq_id, (int32_t)new_len, ui, up);
+    c->seq_len[seq_id] = (int32_t)new_len;
+    return publish(c, ui, up, static_cast<hipStream_t>(hip_stream));
+}
+
+int h1bkv_append_kv(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n_seqs, int32_t n_new, const void *k_dev,
+                    const void *v_dev, int64_t stride_seq, int64_t stride_tok, int64_t stride_head, void *hip_stream) {
+    if (!c) return H1BKV_ENULL;
+    int rc = check_seq_ids(c, seq_ids_host, n_seqs);
+    if (rc != H1BKV_OK) return rc;
+    if (n_new < 1) return H1BKV_EINVAL;
+    if (!c->dry && (!k_dev || !v_dev)) return H1BKV_ENULL;
+    if (stride_seq < 0 || stride_tok < 0 || stride_head < c->cfg.head_dim) return H1BKV_EINVAL;
+    const int elt = c->cfg.in_dtype == H1BKV_F16 ? 2 : 4;
+    if (!c->dry) {
+        // rows are read with 16-byte loads
+        if (reinterpret_cast<uintptr_t>(k_dev) % 16 || reinterpret_cast<uintptr_t>(v_dev) % 16) return H1BKV_EINVAL;
+        if ((stride_seq * elt) % 16 || (stride_tok * elt) % 16 || (stride_head * elt) % 16) return H1BKV_EINVAL;
+    }
+    int64_t need_total = 0;
+    for (int i = 0; i < n_seqs; ++i) {
+        const int need = pages_needed(c, seq_ids_host[i], (int64_t)c->seq_len[seq_ids_host[i]] + n_new);
+        if (need < 0) return need;
+        need_total += need;
+    }
+    if (need_total > (int64_t)c->free_list.size()) return H1BKV_ENOSPACE;
+    if (!c->dry) {
+        rc = check_device(c);
+        if (rc != H1BKV_OK) return rc;
+    }
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+
+    std::vector<int32_t> ui, up;
+    for (int i = 0; i < n_seqs; ++i) take_pages(c, seq_ids_host[i], c->seq_len[seq_ids_host[i]] + n_new, ui, up);
+    rc = publish(c, ui, up, st);
+    if (!c->dry && rc == H1BKV_OK) {
+        AppendArgs a{};
+        a.pool = c->view();
+        a.stride_seq = stride_seq;
+        a.stride_tok = stride_tok;
+        a.stride_head = stride_head;
+        a.n_new = n_new;
+        a.f16 = c->cfg.in_dtype == H1BKV_F16;
+        for (int s0 = 0; s0 < n_seqs && rc == H1BKV_OK; s0 += kMaxSeqsPerLaunch) {
+            const int n = std::min(kMaxSeqsPerLaunch, n_seqs - s0);
+            BatchDesc desc;
+            for (int i = 0; i < n; ++i) desc.s[i] = SeqDesc{seq_ids_host[s0 + i], c->seq_len[seq_ids_host[s0 + i]]};
+            a.k = static_cast<const char *>(k_dev) + (size_t)s0 * stride_seq * elt;
+            a.v = static_cast<const char *>(v_dev) + (size_t)s0 * stride_seq * elt;
+            Timed t(c, H1BKV_K_APPEND, st);
+            if (launch_append(a, desc, n, st) != hipSuccess) rc = H1BKV_EHIP;
+        }
+    }
+    if (rc != H1BKV_OK) {
+        // A launch failed: give the pages taken above back, so the bookkeeping is as it was before the call.
+        for (int i = 0; i < n_seqs; ++i) h1bkv_truncate_seq(c, seq_ids_host[i], c->seq_len[seq_ids_host[i]]);
+        return rc;
+    }
+    for (int i = 0; i < n_seqs; ++i) c->seq_len[seq_ids_host[i]] += n_new;
+    return H1BKV_OK;
+}
+
+size_t h1bkv_decode_workspace_bytes(const h1bkv_cache *c, int32_t n_seqs, int32_t max_ctx) {
+    if (!c || n_seqs < 1 || max_ctx < 0) return 0;
+    const size_t heads = (size_t)n_seqs * c->cfg.n_q_heads;
+    const size_t max_splits = std::max(1, pages_for(max_ctx));   // worst case: one page per chunk
+    size_t o = align_up(heads * c->W * 8);
+    o = align_up(o + heads * max_splits * 2 * sizeof(float));
+    o = align_up(o + heads * max_splits * c->cfg.head_dim * sizeof(float));
+    return o;
+}
+
+int h1bkv_decode_attn(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n_seqs, const void *q_dev, float tau,
+                      float *out_dev, void *workspace_dev, size_t workspace_bytes, void *hip_stream) {
+    if (!c) return H1BKV_ENULL;
+    int rc = check_seq_ids(c, seq_ids_host, n_seqs);
+    if (rc != H1BKV_OK) return rc;
+    if (!(tau > 0.0f) || !std::isfinite(tau)) return H1BKV_EINVAL;
+    if (c->dry) return H1BKV_ENODEVICE;
+    if (!q_dev || !out_dev || !workspace_dev) return H1BKV_ENULL;
+    if (reinterpret_cast<uintptr_t>(workspace_dev) % kAlign || reinterpret_cast<uintptr_t>(q_dev) % 16 ||
+        reinterpret_cast<uintptr_t>(out_dev) % 16)
+        return H1BKV_EINVAL;
+    int max_ctx = 0;
+    for (int i = 0; i < n_seqs; ++i) max_ctx = std::max(max_ctx, c->seq_len[seq_ids_host[i]]);
+    if (workspace_bytes < h1bkv_decode_workspace_bytes(c, n_seqs, max_ctx)) return H1BKV_EWORKSPACE;
+    rc = check_device(c);
+    if (rc != H1BKV_OK) return rc;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+
+    const int chunk = choose_chunk(c, n_seqs, max_ctx);
+    const int S = std::max(1, (max_ctx + chunk - 1) / chunk);
+    const size_t heads = (size_t)n_seqs * c->cfg.n_q_heads;
+    char *ws = static_cast<char *>(workspace_dev);
+    DecodeArgs a{};
+    a.pool = c->view();
+    a.q = q_dev;
+    a.q_sketch = reinterpret_cast<uint64_t *>(ws);
+    size_t o = align_up(heads * c->W * 8);
+    a.part_ml = reinterpret_cast<float *>(ws + o);
+    o = align_up(o + heads * S * 2 * sizeof(float));
+    a.part_o = reinterpret_cast<float *>(ws + o);
+    a.out = out_dev;
+    a.n_splits = S;
+    a.chunk = chunk;
+    a.f16 = c->cfg.in_dtype == H1BKV_F16;
+    a.exp2_scale = (float)(2.0 * 1.4426950408889634 / ((double)c->cfg.sketch_bits * (double)tau));
+
+    for (int s0 = 0; s0 < n_seqs; s0 += kMaxSeqsPerLaunch) {
+        const int n = std::min(kMaxSeqsPerLaunch, n_seqs - s0);
+        BatchDesc desc;
+        for (int i = 0; i < n; ++i) desc.s[i] = SeqDesc{seq_ids_host[s0 + i], c->seq_len[seq_ids_host[s0 + i]]};
+        {
+            Timed t(c, H1BKV_K_QSKETCH, st);
+            if (launch_qsketch(a, s0, n, st) != hipSuccess) return H1BKV_EHIP;
+        }
+        {
+            Timed t(c, H1BKV_K_DECODE_SPLIT, st);
+            if (launch_decode_split(a, desc, s0, n, st) != hipSuccess) return H1BKV_EHIP;
+        }
+        {
+            Timed t(c, H1BKV_K_MERGE, st);
+            if (launch_merge(a, desc, s0, n, st) != hipSuccess) return H1BKV_EHIP;
+        }
+    }
+    return H1BKV_OK;
+}
+
+static int xfer_tokens(const h1bkv_cache *c, int32_t seq_id, int32_t kv_head, int32_t t0, int32_t n, bool to_host,
+                       uint64_t *sk, uint8_t *codes, uint16_t *scale, uint16_t *zero) {
+    if (!c) return H1BKV_ENULL;
+    if (seq_id < 0 || seq_id >= c->cfg.max_seqs || kv_head < 0 || kv_head >= c->cfg.n_kv_heads) return H1BKV_ERANGE;
+    if (t0 < 0 || n < 0 || (int64_t)t0 + n > c->seq_len[seq_id]) return H1BKV_ERANGE;
+    if (c->dry) return H1BKV_ENODEVICE;
+    if ((scale == nullptr) != (zero == nullptr)) return H1BKV_ENULL;
+    int rc = check_device(c);
+    if (rc != H1BKV_OK) return rc;
+    if (hipDeviceSynchronize() != hipSuccess) return H1BKV_EHIP;
+    const PoolView pv = c->view();
+    const size_t W = c->W, hb = c->cfg.head_dim / 2, ng = c->ng;
+    std::vector<uint32_t> meta;
+    const hipMemcpyKind kind = to_host ? hipMemcpyDeviceToHost : hipMemcpyHostToDevice;
+    int32_t t = t0;
+    while (t < t0 + n) {
+        const int32_t page = c->seq_pages[seq_id][t / kPage];
+        const int32_t slot = t % kPage;
+        const int32_t run = std::min(kPage - slot, t0 + n - t);
+        const size_t rec = ((size_t)page * c->cfg.n_kv_heads + kv_head) * kPage + slot;
+        const size_t i = (size_t)(t - t0);
+        bool ok = true;
+        if (sk) {
+            void *dev = pv.sketch + rec * W;
+            ok = ok && hipMemcpy(to_host ? (void *)(sk + i * W) : dev, to_host ? dev : (void *)(sk + i * W), run * W * 8, kind) == hipSuccess;
+        }
+        if (codes) {
+            void *dev = pv.codes + rec * hb;
+            ok = ok && hipMemcpy(to_host ? (void *)(codes + i * hb) : dev, to_host ? dev : (void *)(codes + i * hb), run * hb, kind) == hipSuccess;
+        }
+        if (scale) {
+            void *dev = pv.meta + rec * ng;
+            meta.resize(run * ng);
+            if (to_host) {
+                ok = ok && hipMemcpy(meta.data(), dev, run * ng * 4, kind) == hipSuccess;
+                for (size_t e = 0; e < run * ng; ++e) {
+                    scale[i * ng + e] = (uint16_t)(meta[e] & 0xFFFFu);
+                    zero[i * ng + e] = (uint16_t)(meta[e] >> 16);
+                }
+            } else {
+                for (size_t e = 0; e < run * ng; ++e) meta[e] = (uint32_t)scale[i * ng + e] | ((uint32_t)zero[i * ng + e] << 16);
+                ok = ok && hipMemcpy(dev, meta.data(), run * ng * 4, kind) == hipSuccess;
+            }
+        }
+        if (!ok) return H1BKV_EHIP;
+        t += run;
+    }
+    return H1BKV_OK;
+}
+
+int h1bkv_export_tokens(const h1bkv_cache *c, int32_t seq_id, int32_t kv_head, int32_t t0, int32_t n,
+                        uint64_t *sketch_out, uint8_t *codes_out, uint16_t *scale_out, uint16_t *zero_out) {
+    return xfer_tokens(c, seq_id, kv_head, t0, n, true, sketch_out, codes_out, scale_out, zero_out);
+}
+
+int h1bkv_import_tokens(h1bkv_cache *c, int32_t seq_id, int32_t kv_head, int32_t t0, int32_t n,
+                        const uint64_t *sketch_in, const uint8_t *codes_in, const uint16_t *scale_in,
+                        const uint16_t *zero_in) {
+    return xfer_tokens(c, seq_id, kv_head, t0, n, false, const_cast<uint64_t *>(sketch_in), const_cast<uint8_t *>(codes_in),
+                       const_cast<uint16_t *>(scale_in), const_cast<uint16_t *>(zero_in));
+}
+
+int h1bkv_profile_enable(h1bkv_cache *c, int32_t capacity) {
+    if (!c) return H1BKV_ENULL;
+    if (capacity < 0) return H1BKV_EINVAL;
+    if (c->dry) return capacity == 0 ? H1BKV_OK : H1BKV_ENODEVICE;
+    release_events(c);
+    if (capacity == 0) return H1BKV_OK;
+    int rc = check_device(c);
+    if (rc != H1BKV_OK) return rc;
+    for (int k = 0; k < H1BKV_K_COUNT; ++k) {
+        c->prof_events[k].resize(capacity);
+        for (auto &e : c->prof_events[k]) {
+            if (hipEventCreate(&e.a) != hipSuccess || hipEventCreate(&e.b) != hipSuccess) return H1BKV_EHIP;
+        }
+    }
+    c->prof_cap = capacity;
+    return H1BKV_OK;
+}
+
+int h1bkv_profile_read(h1bkv_cache *c, int32_t kernel, float *ms_out, int32_t cap, int32_t *n_out) {
+    if (!c || !n_out || (!ms_out && cap > 0)) return H1BKV_ENULL;
+    if (kernel < 0 || kernel >= H1BKV_K_COUNT || cap < 0) return H1BKV_EINVAL;
+    int n = 0;
+    for (int i = 0; i < c->prof_used[kernel]; ++i) {
+        auto &e = c->prof_events[kernel][i];
+        if (hipEventSynchronize(e.b) != hipSuccess) return H1BKV_EHIP;
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, e.a, e.b) != hipSuccess) return H1BKV_EHIP;
+        if (n < cap) ms_out[n++] = ms;
+    }
+    c->prof_used[kernel] = 0;
+    *n_out = n;
+    return H1BKV_OK;
+}
+
+int h1bkv_stream_copy(void *dst_dev, const void *src_dev, size_t n_bytes, void *hip_stream) {
+    if (!dst_dev || !src_dev) return H1BKV_ENULL;
+    if (n_bytes % 16 || reinterpret_cast<uintptr_t>(dst_dev) % 16 || reinterpret_cast<uintptr_t>(src_dev) % 16) return H1BKV_EINVAL;
+    if (n_bytes == 0) return H1BKV_OK;
+    return launch_stream_copy(dst_dev, src_dev, n_bytes, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? H1BKV_OK : H1BKV_EHIP;
+}
+
+}  // extern "C"

@@ -1,0 +1,74 @@
+// Shared declarations between the host side (cache.cpp) and the kernel translation units.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "h1bkv.h"
+
+namespace h1bkv {
+
+constexpr int kPage = H1BKV_PAGE_TOKENS;   // tokens per page
+constexpr int kMaxSeqsPerLaunch = 128;     // sequences described by one kernel-argument block
+constexpr int kMaxChunk = 2048;            // largest context chunk one decode workgroup handles
+constexpr int kPublishPairs = 240;         // block-table updates carried by one publish launch
+
+// Per-launch sequence descriptors travel as a kernel argument (no host->device copy, nothing to keep
+// alive after the launch returns).  `pos` is the first new position for append and the context length
+// for decode.
+struct SeqDesc {
+    int32_t seq_id;
+    int32_t pos;
+};
+struct BatchDesc {
+    SeqDesc s[kMaxSeqsPerLaunch];
+};
+
+struct TablePairs {
+    int32_t n;
+    int32_t index[kPublishPairs];   // flat index into block_table [max_seqs][max_pages_per_seq]
+    int32_t page[kPublishPairs];
+};
+
+// Device view of the pool.
+struct PoolView {
+    const float *R;          // [b][d]
+    const float *RT;         // [d][b]
+    int32_t *block_table;    // [max_seqs][max_pages_per_seq]
+    uint64_t *sketch;        // [page][H_kv][256][W]
+    uint8_t *codes;          // [page][H_kv][256][d/2]
+    uint32_t *meta;          // [page][H_kv][256][n_g]  low half = fp16 scale, high half = fp16 zero
+    int32_t max_pages_per_seq;
+    int32_t n_kv_heads, n_q_heads, head_dim, sketch_bits, group_size;
+};
+
+struct AppendArgs {
+    PoolView pool;
+    const void *k, *v;
+    int64_t stride_seq, stride_tok, stride_head;
+    int32_t n_new;
+    int32_t f16;
+};
+
+struct DecodeArgs {
+    PoolView pool;
+    const void *q;            // [n_seqs][H_q][d]
+    uint64_t *q_sketch;       // workspace: [n_seqs][H_q][W]
+    float *part_ml;           // workspace: [n_seqs][H_q][S][2]  (min Hamming distance as int bits, sum of p)
+    float *part_o;            // workspace: [n_seqs][H_q][S][d]
+    float *out;               // [n_seqs][H_q][d]
+    int32_t n_splits;         // S: chunks of the longest context in the call
+    int32_t chunk;            // tokens per chunk (multiple of the page size)
+    int32_t f16;
+    float exp2_scale;         // 2 log2(e) / (b tau): p = exp2(exp2_scale * (ham_min - ham))
+};
+
+// Launchers (kernels_*.hip).  Each returns hipGetLastError() of its launch.
+hipError_t launch_publish(const TablePairs &pairs, int32_t *block_table, hipStream_t st);
+hipError_t launch_append(const AppendArgs &a, const BatchDesc &desc, int n_seqs, hipStream_t st);
+hipError_t launch_qsketch(const DecodeArgs &a, int seq0, int n_seqs, hipStream_t st);
+hipError_t launch_decode_split(const DecodeArgs &a, const BatchDesc &desc, int seq0, int n_seqs, hipStream_t st);
+hipError_t launch_merge(const DecodeArgs &a, const BatchDesc &desc, int seq0, int n_seqs, hipStream_t st);
+hipError_t launch_stream_copy(void *dst, const void *src, size_t n_bytes, hipStream_t st);
+
+}  // namespace h1bkv

@@ -1,0 +1,189 @@
+// Cache append: key sketch (Sec. IV-A Eq.(2)) and 4-bit group quantisation of values (Sec. IV-B Eq.(4)),
+// written into the paged planes.
+//
+// Work unit: a workgroup of 4 waves takes kTile consecutive records of one sequence, records ordered
+// head-major (rec = head * n_new + token) so that a tile is a run of consecutive tokens of one head:
+// its outputs are contiguous runs inside a page and its inputs are whole head rows.
+//
+// Sketch: lane i of a wave owns sketch bit (64*word + i): it keeps row R[bit][0..d) in registers and
+// runs the fp32 chain y = fma(R[bit][j], k[j], y), j ascending from +0 -- the order that fixes every
+// bit -- with k[j] broadcast from an fp32 copy of the tile in LDS.  The 64-lane ballot of (y >= 0) IS the
+// packed sketch word (bit i of the word = lane i), so packing costs nothing.
+//
+// Quantiser: one lane per (record, 32-channel slice): min/max over the slice, combined across the
+// group's lanes with wave shuffles, then zero = fp16(min), scale = fp16((max-min)/15) and
+// code = clamp(rne((v - zero)/scale), 0, 15) with IEEE fp32 subtract and divide; 32 codes = one 16-byte store.
+#include <hip/hip_fp16.h>
+
+#include "internal.h"
+
+namespace h1bkv {
+
+namespace {
+
+constexpr int kTile = 64;      // records per workgroup pass
+constexpr int kThreads = 256;
+
+__device__ __forceinline__ void load8(const __half *p, float *out) {
+    const uint4 raw = *reinterpret_cast<const uint4 *>(p);
+    const __half2 *h = reinterpret_cast<const __half2 *>(&raw);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const float2 f = __half22float2(h[i]);
+        out[2 * i] = f.x;
+        out[2 * i + 1] = f.y;
+    }
+}
+__device__ __forceinline__ void load8(const float *p, float *out) {
+    const float4 a = *reinterpret_cast<const float4 *>(p);
+    const float4 b = *reinterpret_cast<const float4 *>(p + 4);
+    out[0] = a.x; out[1] = a.y; out[2] = a.z; out[3] = a.w;
+    out[4] = b.x; out[5] = b.y; out[6] = b.z; out[7] = b.w;
+}
+
+struct RecDst {
+    size_t rec;   // index of the record inside the planes: (page * H_kv + head) * 256 + slot
+};
+
+template <int D, typename T>
+__global__ __launch_bounds__(kThreads) void append_kernel(AppendArgs a, BatchDesc desc) {
+    __shared__ float ks[kTile][D];          // fp32 copy of the key tile
+    __shared__ uint64_t words[kTile][8];    // sketch words of the tile (W <= 8)
+    __shared__ size_t dst[kTile];           // destination record index of each tile record
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const SeqDesc sd = desc.s[blockIdx.y];
+    const PoolView &pv = a.pool;
+    const int H = pv.n_kv_heads, W = pv.sketch_bits >> 6, G = pv.group_size, ng = D / G;
+    const int n_new = a.n_new;
+    const int n_rec = n_new * H;
+    const T *kbase = static_cast<const T *>(a.k) + (size_t)blockIdx.y * a.stride_seq;
+    const T *vbase = static_cast<const T *>(a.v) + (size_t)blockIdx.y * a.stride_seq;
+
+    for (int rec0 = blockIdx.x * kTile; rec0 < n_rec; rec0 += gridDim.x * kTile) {
+        const int n_valid = min(kTile, n_rec - rec0);
+        __syncthreads();   // previous pass is done with the LDS tile
+
+        // ---- stage the key tile as fp32; resolve destinations ----
+        for (int e = tid * 8; e < n_valid * D; e += kThreads * 8) {
+            const int rl = e / D, ch = e % D;
+            const int rec = rec0 + rl, h = rec / n_new, t = rec - h * n_new;
+            float f[8];
+            load8(kbase + (size_t)t * a.stride_tok + (size_t)h * a.stride_head + ch, f);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) ks[rl][ch + i] = f[i];
+        }
+        if (tid < n_valid) {
+            const int rec = rec0 + tid, h = rec / n_new, t = rec - h * n_new;
+            const int pos = sd.pos + t;
+            const int page = pv.block_table[(size_t)sd.seq_id * pv.max_pages_per_seq + pos / kPage];
+            dst[tid] = ((size_t)page * H + h) * kPage + (pos % kPage);
+        }
+        __syncthreads();
+
+        // ---- Eq.(2): lane = sketch bit; y = fma chain over j; ballot = packed word ----
+        const int wslots = W < 4 ? W : 4, tslots = 4 / wslots;
+        for (int word = wave % wslots; word < W; word += wslots) {
+            float r[D];
+            const float *row = pv.R + (size_t)(word * 64 + lane) * D;
+#pragma unroll
+            for (int j = 0; j < D; j += 4) {
+                const float4 x = *reinterpret_cast<const float4 *>(row + j);
+                r[j] = x.x; r[j + 1] = x.y; r[j + 2] = x.z; r[j + 3] = x.w;
+            }
+            for (int t = wave / wslots; t < n_valid; t += tslots) {
+                float y = 0.0f;
+#pragma unroll
+                for (int j = 0; j < D; j += 4) {
+                    const float4 kk = *reinterpret_cast<const float4 *>(&ks[t][j]);
+                    y = __builtin_fmaf(r[j], kk.x, y);
+                    y = __builtin_fmaf(r[j + 1], kk.y, y);
+                    y = __builtin_fmaf(r[j + 2], kk.z, y);
+                    y = __builtin_fmaf(r[j + 3], kk.w, y);
+                }
+                const uint64_t mask = __ballot(y >= 0.0f);
+                if (lane == 0) words[t][word] = mask;
+            }
+        }
+
+        // ---- Eq.(4): one lane per (record, 32-channel slice) ----
+        constexpr int LPT = D / 32;
+        const int lanes_per_group = G / 32;
+        for (int item = tid; item < kTile * LPT; item += kThreads) {      // uniform trip count: shuffles below need all lanes
+            const int rl = item / LPT, slice = item % LPT;
+            const bool valid = rl < n_valid;
+            float x[32];
+            if (valid) {
+                const int rec = rec0 + rl, h = rec / n_new, t = rec - h * n_new;
+                const T *src = vbase + (size_t)t * a.stride_tok + (size_t)h * a.stride_head + slice * 32;
+#pragma unroll
+                for (int i = 0; i < 32; i += 8) load8(src + i, x + i);
+            } else {
+#pragma unroll
+                for (int i = 0; i < 32; ++i) x[i] = 0.0f;
+            }
+            float mn = x[0], mx = x[0];
+#pragma unroll
+            for (int i = 1; i < 32; ++i) {
+                mn = fminf(mn, x[i]);
+                mx = fmaxf(mx, x[i]);
+            }
+            for (int off = 1; off < lanes_per_group; off <<= 1) {
+                mn = fminf(mn, __shfl_xor(mn, off));
+                mx = fmaxf(mx, __shfl_xor(mx, off));
+            }
+            const float delta = (mx - mn) / 15.0f;
+            unsigned short sh = __half_as_ushort(__float2half_rn(delta));
+            unsigned short zh = __half_as_ushort(__float2half_rn(mn));
+            if ((zh & 0x7FFFu) == 0) zh = 0;
+            const float sc = __half2float(__ushort_as_half(sh));
+            const float zp = __half2float(__ushort_as_half(zh));
+            uint32_t packed[4] = {0u, 0u, 0u, 0u};
+            if (sc != 0.0f) {
+#pragma unroll
+                for (int i = 0; i < 32; ++i) {
+                    float q = rintf((x[i] - zp) / sc);
+                    q = fminf(fmaxf(q, 0.0f), 15.0f);
+                    packed[i >> 3] |= (uint32_t)(int)q << (4 * (i & 7));
+                }
+            }
+            if (valid) {
+                const size_t rec = dst[rl];
+                *reinterpret_cast<uint4 *>(pv.codes + rec * (D / 2) + slice * 16) = make_uint4(packed[0], packed[1], packed[2], packed[3]);
+                if (slice % lanes_per_group == 0) pv.meta[rec * ng + slice / lanes_per_group] = (uint32_t)sh | ((uint32_t)zh << 16);
+            }
+        }
+        __syncthreads();
+
+        // ---- store sketch words ----
+        for (int i = tid; i < n_valid * W; i += kThreads) {
+            const int rl = i / W, w = i - rl * W;
+            pv.sketch[dst[rl] * W + w] = words[rl][w];
+        }
+    }
+}
+
+}  // namespace
+
+hipError_t launch_append(const AppendArgs &a, const BatchDesc &desc, int n_seqs, hipStream_t st) {
+    const long n_rec = (long)a.n_new * a.pool.n_kv_heads;
+    long tiles = (n_rec + kTile - 1) / kTile;
+    // Each workgroup re-reads R once; with many tiles let one workgroup walk several of them.
+    const long max_wgs_x = 4096 / n_seqs > 0 ? 4096 / n_seqs : 1;
+    const dim3 grid((unsigned)(tiles < max_wgs_x ? tiles : max_wgs_x), (unsigned)n_seqs);
+    const int D = a.pool.head_dim;
+#define H1BKV_LAUNCH(DD, TT) hipLaunchKernelGGL((append_kernel<DD, TT>), grid, dim3(kThreads), 0, st, a, desc)
+    if (a.f16) {
+        if (D == 64) H1BKV_LAUNCH(64, __half);
+        else if (D == 128) H1BKV_LAUNCH(128, __half);
+        else H1BKV_LAUNCH(256, __half);
+    } else {
+        if (D == 64) H1BKV_LAUNCH(64, float);
+        else if (D == 128) H1BKV_LAUNCH(128, float);
+        else H1BKV_LAUNCH(256, float);
+    }
+#undef H1BKV_LAUNCH
+    return hipGetLastError();
+}
+
+}  // namespace h1bkv

@@ -1,0 +1,197 @@
+"""GPU parity: the HIP library against the CPU oracle, element by element, through the C ABI.
+Cache contents (sketch words, int4 codes, fp16 scale/zero) must be bit-exact; attention outputs within 2e-3."""
+import numpy as np
+import pytest
+
+from oracle import cref
+from paper_2510_05529_amd import binding as B
+from paper_2510_05529_amd import workloads as wl
+from tests.gpu_util import TOL, assert_cache_equal, make_cache, rel_err, to_dev
+
+pytestmark = pytest.mark.gpu
+
+CASES = {
+    # the tiny configuration as stated: 1 x 4 heads x 256 tokens, d = 64, b = 64, G = 32, fp32
+    "tiny": wl.WORKLOADS["tiny"],
+    # shrunken 7B decode: several pages and a ragged tail, per-head scales
+    "7b_small": wl.WORKLOADS["decode_7b_8k"].scaled(n_q_heads=8, n_kv_heads=8, context=1337),
+    # batched: several chunks per sequence
+    "batched_small": wl.WORKLOADS["decode_b16_32k"].scaled(batch=3, n_q_heads=4, n_kv_heads=4, context=2500),
+    # append workload's outlier channels
+    "outliers_small": wl.WORKLOADS["append_prefill_8k"].scaled(batch=2, n_q_heads=32, n_kv_heads=32, context=300),
+    # GQA, b = 256, G = 64
+    "gqa_small": wl.WORKLOADS["decode_gqa_128k"].scaled(batch=2, n_q_heads=8, n_kv_heads=2, context=1100),
+    # other template instantiations
+    "d256_b512_g128": wl.Workload("d256", 1, 2, 1, 256, 700, 512, 128, "f16", seed=1),
+    "d64_b128_g64_r2": wl.Workload("d64", 2, 4, 2, 64, 530, 128, 64, "f32", seed=2),
+    "d128_b64_r3": wl.Workload("r3", 1, 6, 2, 128, 300, 64, 32, "f16", seed=3),
+}
+
+
+def run_case(w: wl.Workload, append_steps, tau=None):
+    R = wl.projection(w.sketch_bits, w.head_dim)
+    seqs = list(range(w.batch))
+    k = wl.kv_slab(w, "k", seqs, 0, w.context)
+    v = wl.kv_slab(w, "v", seqs, 0, w.context)
+    q = wl.queries(w)
+    tau = tau or w.default_tau()
+    oc = cref.Cache(R, w.batch, w.n_kv_heads, w.context, w.group_size)
+    oc.append(k, v)
+    ref = oc.decode(q, tau)
+
+    cache = make_cache(w, R)
+    kd, vd = to_dev(k), to_dev(v)
+    t = 0
+    for n in append_steps:
+        n = min(n, w.context - t)
+        if n <= 0:
+            break
+        cache.append(seqs, kd[:, t:t + n], vd[:, t:t + n])
+        t += n
+    assert t == w.context
+    assert_cache_equal(cache, oc, seqs, w.context)
+    out = cache.decode(seqs, to_dev(q), tau).cpu().numpy()
+    err = rel_err(out, ref)
+    print(f"{w.name}: rel err {err:.3e}")
+    assert err <= TOL
+    cache.close()
+    return out, ref
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_append_then_decode_matches_oracle(name):
+    w = CASES[name]
+    run_case(w, [w.context])
+
+
+def test_tiny_token_by_token_append_gives_identical_cache():
+    w = CASES["tiny"]
+    run_case(w, [1] * w.context)
+
+
+def test_ragged_append_steps_cross_page_boundaries():
+    w = CASES["7b_small"]
+    run_case(w, [255, 2, 300, 1, 1, 511, 10_000])
+
+
+@pytest.mark.parametrize("tau", [1.0, 0.25, 0.02, 0.004])
+def test_temperatures(tau):
+    run_case(CASES["batched_small"], [2500], tau=tau)
+
+
+def test_split_count_does_not_change_the_result():
+    w = CASES["batched_small"]
+    R = wl.projection(w.sketch_bits, w.head_dim)
+    seqs = list(range(w.batch))
+    cache = make_cache(w, R)
+    cache.append(seqs, to_dev(wl.kv_slab(w, "k", seqs, 0, w.context)), to_dev(wl.kv_slab(w, "v", seqs, 0, w.context)))
+    q = to_dev(wl.queries(w))
+    outs = []
+    for chunk in (256, 512, 1024, 2048, 0):
+        assert B.h1bkv_set_decode_chunk(cache.h, chunk) == B.H1BKV_OK
+        outs.append(cache.decode(seqs, q, w.default_tau()).cpu().numpy())
+    for o in outs[1:]:
+        assert rel_err(o, outs[0]) < 1e-5
+    cache.close()
+
+
+def test_per_sequence_lengths_empty_sequences_and_subsets():
+    w = CASES["batched_small"].scaled(batch=4, context=700)
+    R = wl.projection(w.sketch_bits, w.head_dim)
+    lens = [700, 0, 1, 257]
+    cache = make_cache(w, R)
+    oc = cref.Cache(R, w.batch, w.n_kv_heads, w.context, w.group_size)
+    k, v = wl.kv_slab(w, "k", range(4), 0, 700), wl.kv_slab(w, "v", range(4), 0, 700)
+    oc.append(k, v)
+    for s, n in enumerate(lens):
+        if n:
+            cache.append([s], to_dev(k[s:s + 1, :n]), to_dev(v[s:s + 1, :n]))
+    q = wl.queries(w)
+    ref = oc.decode(q, 0.07, np.array(lens, dtype=np.int32))
+    out = cache.decode([0, 1, 2, 3], to_dev(q), 0.07).cpu().numpy()
+    assert np.array_equal(out[1], np.zeros_like(out[1]))                # empty context -> zeros
+    assert rel_err(out, ref) <= TOL
+    # a subset of sequences, in a different order
+    out2 = cache.decode([3, 0], to_dev(q[[3, 0]]), 0.07).cpu().numpy()
+    assert rel_err(out2, ref[[3, 0]]) <= TOL
+    cache.close()
+
+
+def test_page_assignment_does_not_matter_and_pages_are_reused():
+    """Fill, reset and refill in another order: the free list hands out different pages, the export is identical."""
+    w = CASES["batched_small"].scaled(batch=2, context=600)
+    R = wl.projection(w.sketch_bits, w.head_dim)
+    cache = make_cache(w, R)
+    k, v = to_dev(wl.kv_slab(w, "k", [0, 1], 0, 600)), to_dev(wl.kv_slab(w, "v", [0, 1], 0, 600))
+    cache.append([0, 1], k, v)
+    first = [cache.export(s, 1, 0, 600) for s in (0, 1)]
+    q = to_dev(wl.queries(w))
+    out1 = cache.decode([0, 1], q, 0.06).cpu().numpy()
+    assert B.h1bkv_reset_seq(cache.h, 0) == 0 and B.h1bkv_reset_seq(cache.h, 1) == 0
+    cache.append([1], k[1:2, :300], v[1:2, :300])
+    cache.append([0], k[0:1], v[0:1])
+    cache.append([1], k[1:2, 300:], v[1:2, 300:])
+    second = [cache.export(s, 1, 0, 600) for s in (0, 1)]
+    for a, b in zip(first, second):
+        for x, y in zip(a, b):
+            assert np.array_equal(x, y)
+    out2 = cache.decode([0, 1], q, 0.06).cpu().numpy()
+    assert rel_err(out2, out1) < 1e-5
+    cache.close()
+
+
+def test_strided_inputs():
+    """K and V handed over as slices of a fused [.., 2, H, d] tensor (non-dense token and sequence strides)."""
+    torch = __import__("torch")
+    w = CASES["7b_small"].scaled(context=400)
+    R = wl.projection(w.sketch_bits, w.head_dim)
+    k, v = wl.kv_slab(w, "k", [0], 0, 400), wl.kv_slab(w, "v", [0], 0, 400)
+    fused = torch.stack([to_dev(k), to_dev(v)], dim=2)                   # [1][400][2][H][d]
+    cache = make_cache(w, R)
+    cache.append([0], fused[:, :, 0], fused[:, :, 1])
+    oc = cref.Cache(R, 1, w.n_kv_heads, 400, w.group_size)
+    oc.append(k, v)
+    assert_cache_equal(cache, oc, [0], 400)
+    cache.close()
+
+
+def test_import_export_round_trip_and_decode_from_imported_cache():
+    """A cache restored with extend + import from the oracle's planes decodes like the oracle."""
+    w = CASES["gqa_small"].scaled(batch=1, context=520)
+    R = wl.projection(w.sketch_bits, w.head_dim)
+    oc = cref.Cache(R, 1, w.n_kv_heads, 520, w.group_size)
+    oc.append(wl.kv_slab(w, "k", [0], 0, 520), wl.kv_slab(w, "v", [0], 0, 520))
+    cache = make_cache(w, R)
+    assert B.h1bkv_extend_seq(cache.h, 0, 520) == B.H1BKV_OK
+    for h in range(w.n_kv_heads):
+        assert B.h1bkv_import_tokens(cache.h, 0, h, 0, oc.sketches[0, h], oc.codes[0, h], oc.scale[0, h], oc.zero[0, h]) == 0
+    assert_cache_equal(cache, oc, [0], 520)
+    q = wl.queries(w)
+    out = cache.decode([0], to_dev(q), 0.05).cpu().numpy()
+    assert rel_err(out, oc.decode(q, 0.05)) <= TOL
+    cache.close()
+
+
+def test_special_inputs_zero_keys_constant_values_and_ties():
+    """All-zero keys sketch to all ones; constant value groups store scale 0; .5 ties round to even."""
+    w = wl.Workload("special", 1, 2, 2, 64, 260, 64, 32, "f32", seed=5)
+    R = wl.projection(64, 64)
+    k = wl.kv_slab(w, "k", [0], 0, 260)
+    v = wl.kv_slab(w, "v", [0], 0, 260)
+    k[0, 3] = 0.0
+    k[0, 4] = -0.0
+    v[0, 5] = 1.25
+    v[0, 6, :, :31] = (np.arange(31) / 2 - 3)[None, :]
+    v[0, 6, :, 31] = 12.0
+    v[0, 7] = 0.0
+    v[0, 8, :, ::2] = -0.0
+    oc = cref.Cache(R, 1, 2, 260, 32)
+    oc.append(k, v)
+    cache = make_cache(w, R)
+    cache.append([0], to_dev(k), to_dev(v))
+    assert_cache_equal(cache, oc, [0], 260)
+    sk, codes, scale, zero = cache.export(0, 0, 0, 10)
+    assert int(sk[3, 0]) == (1 << 64) - 1 and int(sk[4, 0]) == (1 << 64) - 1
+    assert np.all(scale[5] == 0) and np.all(codes[5] == 0)
+    assert bytes(codes[6][:16]) == bytes.fromhex("002122434465668788A9AACBCCEDEEFF")   # tests/golden/record_layout.txt
+    cache.close()

@@ -1,0 +1,145 @@
+"""Argument validation and page bookkeeping of the library, exercised on a bookkeeping-only handle
+(device = H1BKV_DEVICE_NONE): no GPU is touched and no kernel is launched."""
+import ctypes as C
+
+import numpy as np
+import pytest
+
+from paper_2510_05529_amd import binding as B
+from paper_2510_05529_amd import workloads as wl
+
+
+def cfg(**kw):
+    base = dict(n_q_heads=8, n_kv_heads=4, head_dim=128, sketch_bits=128, group_size=32, in_dtype=B.H1BKV_F16,
+                page_tokens=0, max_seqs=4, max_pages=10, max_pages_per_seq=6, device=B.H1BKV_DEVICE_NONE)
+    base.update(kw)
+    return B.h1bkv_config(**base)
+
+
+def make(**kw):
+    c = cfg(**kw)
+    R = wl.projection(c.sketch_bits, c.head_dim)
+    rc, h = B.h1bkv_create(c, None, 0, R)
+    assert rc == B.H1BKV_OK
+    return c, h, R
+
+
+@pytest.mark.parametrize("bad", [dict(n_q_heads=6), dict(head_dim=96), dict(sketch_bits=32), dict(sketch_bits=192),
+                                 dict(group_size=16), dict(group_size=128, head_dim=64), dict(in_dtype=2),
+                                 dict(page_tokens=128), dict(max_seqs=0), dict(max_pages=0), dict(max_pages_per_seq=0),
+                                 dict(n_kv_heads=0), dict(device=-2)])
+def test_bad_geometry_is_rejected(bad):
+    c = cfg(**bad)
+    assert B.h1bkv_pool_bytes(c) == 0
+    rc, _ = B.h1bkv_create(c, None, 0, wl.projection(128, 128))
+    assert rc == B.H1BKV_ESHAPE
+
+
+def test_pool_bytes_formula():
+    """sketch + nibbles + fp16 scale/zero per record (Sec. IV-B: a b-bit sketch and d 4-bit values per token),
+    plus R, its transpose and the block table, each rounded up to 256 bytes."""
+    for w in (wl.WORKLOADS["tiny"], wl.WORKLOADS["decode_b16_32k"], wl.WORKLOADS["decode_gqa_128k"]):
+        c = cfg(n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim, sketch_bits=w.sketch_bits,
+                group_size=w.group_size, max_seqs=3, max_pages=7, max_pages_per_seq=5)
+        al = lambda x: (x + 255) // 256 * 256
+        rec = 7 * w.n_kv_heads * 256
+        want = (2 * al(w.sketch_bits * w.head_dim * 4) + al(3 * 5 * 4) + al(rec * w.sketch_bits // 8)
+                + al(rec * w.head_dim // 2) + al(rec * w.n_groups * 4))
+        assert B.h1bkv_pool_bytes(c) == want
+        assert (w.sketch_bits // 8 + w.head_dim // 2 + 4 * w.n_groups) == w.record_bytes
+
+
+def test_create_null_arguments():
+    c = cfg()
+    rc, _ = B.h1bkv_create(c, None, 0, None)
+    assert rc == B.H1BKV_ENULL
+    assert B.lib().h1bkv_create(None, None, 0, None, None) == B.H1BKV_ENULL
+    # a real device handle needs a pool pointer
+    rc, _ = B.h1bkv_create(cfg(device=0), None, 0, wl.projection(128, 128))
+    assert rc == B.H1BKV_ENULL
+
+
+def test_projection_round_trips():
+    c, h, R = make()
+    rc, back = B.h1bkv_get_projection(h, c.sketch_bits, c.head_dim)
+    assert rc == B.H1BKV_OK and np.array_equal(back, R)
+    B.h1bkv_destroy(h)
+
+
+def test_append_bookkeeping_and_page_accounting():
+    c, h, _ = make()
+    S = (128 * 4, 128 * 4 * 300, 128)      # strides of a dense [n_seqs][300][4][128] tensor: seq, tok, head
+    assert B.h1bkv_free_pages(h) == (0, 10)
+    assert B.h1bkv_append_kv(h, [0, 2], 300, None, None, 300 * 512, 512, 128) == B.H1BKV_OK
+    assert B.h1bkv_seq_len(h, 0) == (0, 300) and B.h1bkv_seq_len(h, 2) == (0, 300) and B.h1bkv_seq_len(h, 1) == (0, 0)
+    assert B.h1bkv_free_pages(h) == (0, 6)               # two pages each
+    assert B.h1bkv_append_kv(h, [0], 212, None, None, 0, 512, 128) == B.H1BKV_OK     # fills page 2 exactly
+    assert B.h1bkv_seq_len(h, 0) == (0, 512) and B.h1bkv_free_pages(h) == (0, 6)
+    assert B.h1bkv_append_kv(h, [0], 1, None, None, 0, 512, 128) == B.H1BKV_OK       # needs a third page
+    assert B.h1bkv_free_pages(h) == (0, 5)
+    # pool exhaustion leaves everything unchanged: 5 free pages, request needs 3 + 3
+    assert B.h1bkv_append_kv(h, [1, 3], 700, None, None, 700 * 512, 512, 128) == B.H1BKV_ENOSPACE
+    assert B.h1bkv_seq_len(h, 1) == (0, 0) and B.h1bkv_seq_len(h, 3) == (0, 0) and B.h1bkv_free_pages(h) == (0, 5)
+    # per-sequence page cap: 6 pages = 1536 tokens
+    assert B.h1bkv_append_kv(h, [2], 1536 - 300 + 1, None, None, 0, 512, 128) == B.H1BKV_ENOSPACE
+    assert B.h1bkv_seq_len(h, 2) == (0, 300)
+    # truncate / reset give pages back
+    assert B.h1bkv_truncate_seq(h, 0, 513) == B.H1BKV_OK and B.h1bkv_free_pages(h) == (0, 5)
+    assert B.h1bkv_truncate_seq(h, 0, 256) == B.H1BKV_OK and B.h1bkv_free_pages(h) == (0, 7)
+    assert B.h1bkv_truncate_seq(h, 0, 257) == B.H1BKV_ERANGE and B.h1bkv_truncate_seq(h, 0, -1) == B.H1BKV_ERANGE
+    assert B.h1bkv_reset_seq(h, 2) == B.H1BKV_OK and B.h1bkv_free_pages(h) == (0, 9)
+    assert B.h1bkv_extend_seq(h, 3, 257, 0) == B.H1BKV_OK and B.h1bkv_seq_len(h, 3) == (0, 257)
+    assert B.h1bkv_free_pages(h) == (0, 7)
+    B.h1bkv_destroy(h)
+
+
+def test_append_argument_errors():
+    c, h, _ = make()
+    ok = (512, 512, 128)
+    assert B.lib().h1bkv_append_kv(h, None, 1, 1, None, None, *ok, None) == B.H1BKV_ENULL
+    assert B.lib().h1bkv_append_kv(None, None, 1, 1, None, None, *ok, None) == B.H1BKV_ENULL
+    assert B.h1bkv_append_kv(h, [4], 1, None, None, *ok) == B.H1BKV_ERANGE
+    assert B.h1bkv_append_kv(h, [-1], 1, None, None, *ok) == B.H1BKV_ERANGE
+    assert B.h1bkv_append_kv(h, [1, 1], 1, None, None, *ok) == B.H1BKV_EINVAL       # duplicate id
+    assert B.h1bkv_append_kv(h, [1], 0, None, None, *ok) == B.H1BKV_EINVAL
+    assert B.h1bkv_append_kv(h, [1], 1, None, None, 512, 512, 64) == B.H1BKV_EINVAL  # head stride < head_dim
+    assert B.h1bkv_append_kv(h, [1], 1, None, None, -1, 512, 128) == B.H1BKV_EINVAL
+    assert B.h1bkv_seq_len(h, 1) == (0, 0)
+    assert B.h1bkv_seq_len(h, 9)[0] == B.H1BKV_ERANGE
+    B.h1bkv_destroy(h)
+
+
+def test_decode_argument_errors_and_workspace_size():
+    c, h, _ = make()
+    assert B.h1bkv_decode_attn(h, [0], None, 0.0, None, None, 0) == B.H1BKV_EINVAL
+    assert B.h1bkv_decode_attn(h, [0], None, -1.0, None, None, 0) == B.H1BKV_EINVAL
+    assert B.h1bkv_decode_attn(h, [0], None, float("nan"), None, None, 0) == B.H1BKV_EINVAL
+    assert B.h1bkv_decode_attn(h, [0], None, float("inf"), None, None, 0) == B.H1BKV_EINVAL
+    assert B.h1bkv_decode_attn(h, [7], None, 0.1, None, None, 0) == B.H1BKV_ERANGE
+    assert B.h1bkv_decode_attn(h, [0, 0], None, 0.1, None, None, 0) == B.H1BKV_EINVAL
+    assert B.h1bkv_decode_attn(h, [0], None, 0.1, None, None, 0) == B.H1BKV_ENODEVICE   # valid, but no GPU behind it
+    # workspace: query sketches + per-page partials, monotone
+    al = lambda x: (x + 255) // 256 * 256
+    heads = 3 * 8
+    want = al(heads * 2 * 8) + al(heads * 5 * 2 * 4) + al(heads * 5 * 128 * 4)
+    assert B.h1bkv_decode_workspace_bytes(h, 3, 1025) == want
+    sizes = [B.h1bkv_decode_workspace_bytes(h, 3, t) for t in (0, 1, 256, 257, 5000)]
+    assert sizes == sorted(sizes) and sizes[0] > 0
+    assert B.h1bkv_decode_workspace_bytes(h, 0, 10) == 0
+    B.h1bkv_destroy(h)
+
+
+def test_misc_errors():
+    c, h, _ = make()
+    assert B.h1bkv_set_decode_chunk(h, 100) == B.H1BKV_EINVAL
+    assert B.h1bkv_set_decode_chunk(h, 4096) == B.H1BKV_EINVAL
+    assert B.h1bkv_set_decode_chunk(h, 512) == B.H1BKV_OK and B.h1bkv_set_decode_chunk(h, 0) == B.H1BKV_OK
+    assert B.h1bkv_export_tokens(h, 0, 0, 0, 1, 2, 128, 4)[0] == B.H1BKV_ERANGE      # nothing cached yet
+    assert B.h1bkv_append_kv(h, [0], 5, None, None, 0, 512, 128) == B.H1BKV_OK
+    assert B.h1bkv_export_tokens(h, 0, 4, 0, 1, 2, 128, 4)[0] == B.H1BKV_ERANGE      # head out of range
+    assert B.h1bkv_export_tokens(h, 0, 0, 3, 3, 2, 128, 4)[0] == B.H1BKV_ERANGE      # runs past the length
+    assert B.h1bkv_export_tokens(h, 0, 0, 0, 5, 2, 128, 4)[0] == B.H1BKV_ENODEVICE
+    assert B.h1bkv_profile_enable(h, 4) == B.H1BKV_ENODEVICE and B.h1bkv_profile_enable(h, 0) == B.H1BKV_OK
+    assert B.h1bkv_stream_copy(None, None, 16) == B.H1BKV_ENULL
+    assert B.h1bkv_stream_copy(4096, 8192, 24) == B.H1BKV_EINVAL
+    assert B.h1bkv_destroy(h) == B.H1BKV_OK and B.h1bkv_destroy(None) == B.H1BKV_OK
