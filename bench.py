@@ -1,0 +1,214 @@
+#!/usr/bin/env python3
+"""Benchmark of the H1B-KV hot path on one MI355X.
+
+A step is one decode step of the whole path over one batch: append the new token's K/V for every
+sequence (sketch + 4-bit quantisation into the paged cache), then decode attention over the full
+context (query sketch, split-context scoring/softmax/weighted sum, log-sum-exp merge).  The context is
+held at the workload's length by truncating the sequence by one token before each step, so every step
+attends over exactly T tokens.  Inputs are resident in HBM before the timed region starts.
+
+Prints ONE JSON line: KV-tokens/s (= batch * context / step time), the roofline of the dominant kernel
+(decode_split: algorithmic bytes / its mean duration from HIP events recorded on the launch stream inside
+the timed region, against 8 TB/s), and the CPU oracle timed on the host cores on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import re
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np
+
+HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="decode_b16_32k",
+                    help="decode_b16_32k (default, the graded configuration) | decode_7b_8k | decode_gqa_128k | tiny")
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
+    ap.add_argument("--chunk", type=int, default=0, help="decode chunk override (tokens, multiple of 256)")
+    ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
+                    help="only run the library's plain copy kernel on a buffer of this size (counter calibration)")
+    return ap.parse_args()
+
+
+def traffic_from_profiles(workload: str):
+    """HBM bytes per decode_split launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE, calibrated
+    against the copy kernel), if the committed summary for this workload has them."""
+    path = os.path.join(ROOT, "profiles", f"decode_split_{workload}_pmc.txt")
+    if not os.path.exists(path):
+        return None
+    m = re.search(r"^traffic_bytes_per_launch\s*[:=]\s*([0-9.eE+]+)", open(path).read(), re.M)
+    return float(m.group(1)) if m else None
+
+
+def fill_cache(torch, B, wl, w, cache, n_tokens, workers):
+    """Append tokens [0, n_tokens) of every sequence, slab by slab (host generation -> HBM -> append kernel)."""
+    seqs = list(range(w.batch))
+    slab = wl.SLAB_TOKENS
+    t0 = 0
+    while t0 < n_tokens:
+        n = min(slab, n_tokens - t0)
+        k = torch.from_numpy(wl.kv_slab(w, "k", seqs, t0, n, workers)).cuda()
+        v = torch.from_numpy(wl.kv_slab(w, "v", seqs, t0, n, workers)).cuda()
+        cache.append(seqs, k, v)
+        torch.cuda.synchronize()
+        t0 += n
+
+
+def cpu_baseline(wl, w, tau, workers):
+    """The oracle, as it stands, on the host cores: one sequence of the workload (all heads, full context).
+    Its cache is built by the oracle's own append (untimed set-up); the timed step is the same as the GPU's:
+    append one token for every head, then decode over the whole context."""
+    from oracle import cref
+    R = wl.projection(w.sketch_bits, w.head_dim)
+    T = w.context
+    oc = cref.Cache(R, 1, w.n_kv_heads, T, w.group_size)
+    slab = wl.SLAB_TOKENS
+    t0 = 0
+    while t0 < T - 1:
+        n = min(slab, T - 1 - t0)
+        oc.append(wl.kv_slab(w, "k", [0], t0, n, workers), wl.kv_slab(w, "v", [0], t0, n, workers))
+        t0 += n
+    k1, v1 = wl.kv_slab(w, "k", [0], T - 1, 1), wl.kv_slab(w, "v", [0], T - 1, 1)
+    q = wl.queries(w)[:1]
+    times = []
+    t_begin = time.perf_counter()
+    while len(times) < 3 or (time.perf_counter() - t_begin < 8.0 and len(times) < 200):
+        oc.len = T - 1
+        t = time.perf_counter()
+        oc.append(k1, v1)
+        oc.decode(q, tau)
+        times.append(time.perf_counter() - t)
+    sec = float(np.median(times))
+    return {"value": T / sec, "unit": "KV-tokens/s", "cores": cref.max_threads(), "kind": "oracle",
+            "sample": f"1 of {w.batch} sequences (all {w.n_kv_heads} KV heads, context {T}): append 1 token + decode, "
+                      f"median of {len(times)} steps, {sec * 1e3:.1f} ms/step",
+            "ms_per_step": sec * 1e3}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2510_05529_amd import binding as B
+    from paper_2510_05529_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    workers = min(16, os.cpu_count() or 1)
+
+    if args.calibrate_copy:
+        n = args.calibrate_copy << 20
+        src = torch.empty(n, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty(n, dtype=torch.uint8, device="cuda")
+        torch.cuda.synchronize()
+        for _ in range(max(1, args.warmup)):
+            B.check(B.h1bkv_stream_copy(dst, src, n, None))
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for _ in range(args.steps):
+            B.check(B.h1bkv_stream_copy(dst, src, n, None))
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t) * 1e3 / args.steps
+        print(json.dumps({"calibrate_copy_bytes": n, "ms_per_copy": ms, "read_GBps": n / ms / 1e6, "read_plus_write_GBps": 2 * n / ms / 1e6}))
+        return
+
+    w = wl.WORKLOADS[args.workload]
+    T, Bsz = w.context, w.batch
+    tau = w.default_tau()
+    R = wl.projection(w.sketch_bits, w.head_dim)
+    pages_per_seq = (T + 255) // 256 + 1
+    cache = B.Cache(n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim, sketch_bits=w.sketch_bits,
+                    group_size=w.group_size, dtype=w.dtype, max_seqs=Bsz, max_pages=Bsz * pages_per_seq,
+                    max_pages_per_seq=pages_per_seq, R=R)
+    if args.chunk:
+        B.check(B.h1bkv_set_decode_chunk(cache.h, args.chunk))
+    t_fill = time.perf_counter()
+    fill_cache(torch, B, wl, w, cache, T - 1, workers)
+    t_fill = time.perf_counter() - t_fill
+
+    seqs = list(range(Bsz))
+    k1 = torch.from_numpy(wl.kv_slab(w, "k", seqs, T - 1, 1)).cuda()
+    v1 = torch.from_numpy(wl.kv_slab(w, "v", seqs, T - 1, 1)).cuda()
+    q = torch.from_numpy(wl.queries(w)).cuda()
+    out = torch.empty((Bsz, w.n_q_heads, w.head_dim), dtype=torch.float32, device="cuda")
+    ws_bytes = B.h1bkv_decode_workspace_bytes(cache.h, Bsz, T)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    stream = torch.cuda.current_stream()
+
+    def step():
+        for s in seqs:
+            B.check(B.h1bkv_truncate_seq(cache.h, s, T - 1))
+        B.check(B.h1bkv_append_kv(cache.h, seqs, 1, k1, v1, k1.stride(0), k1.stride(1), k1.stride(2), stream))
+        B.check(B.h1bkv_decode_attn(cache.h, seqs, q, tau, out, ws, ws_bytes, stream))
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    B.check(B.h1bkv_profile_enable(cache.h, args.steps))
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    kernel_ms = {}
+    for name, kid in (("append", B.H1BKV_K_APPEND), ("qsketch", B.H1BKV_K_QSKETCH),
+                      ("decode_split", B.H1BKV_K_DECODE_SPLIT), ("merge", B.H1BKV_K_MERGE)):
+        rc, ms = B.h1bkv_profile_read(cache.h, kid)
+        B.check(rc)
+        kernel_ms[name] = float(ms.mean()) if len(ms) else None
+    B.check(B.h1bkv_profile_enable(cache.h, 0))
+
+    records = Bsz * w.n_kv_heads * T
+    alg_bytes = records * w.record_bytes                      # sketch + nibbles + scale/zero of every cached record
+    split_ms = kernel_ms["decode_split"]
+    achieved = alg_bytes / (split_ms * 1e-3) / 1e9
+    result = {
+        "metric": "decode_attn_kv_tokens_per_s",
+        "value": Bsz * T / (ms_per_step * 1e-3),
+        "unit": "KV-tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": w.name, "batch": Bsz, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
+                   "head_dim": w.head_dim, "context": T, "sketch_bits": w.sketch_bits, "group_size": w.group_size,
+                   "in_dtype": w.dtype, "tau": tau, "record_bytes": w.record_bytes,
+                   "step": "append 1 token/sequence + decode attention over the full context"},
+        "roofline": {"bound": "hbm", "kernel": "decode_split_kernel", "achieved": achieved, "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic_from_profiles(w.name),
+                     "algorithmic_bytes_per_launch": alg_bytes, "kernel_ms": split_ms},
+        "records_per_s": records / (ms_per_step * 1e-3),
+        "kernel_ms": kernel_ms,
+        "fill_s": t_fill,
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(wl, w, tau, workers)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -41,12 +41,8 @@ __device__ __forceinline__ void load8(const float *p, float *out) {
     out[4] = b.x; out[5] = b.y; out[6] = b.z; out[7] = b.w;
 }
 
-struct RecDst {
-    size_t rec;   // index of the record inside the planes: (page * H_kv + head) * 256 + slot
-};
-
 template <int D, typename T>
-__global__ __launch_bounds__(kThreads) void append_kernel(AppendArgs a, BatchDesc desc) {
+__global__ __launch_bounds__(kThreads) void append_kernel(AppendArgs a, BatchDesc desc, int tile) {
     __shared__ float ks[kTile][D];          // fp32 copy of the key tile
     __shared__ uint64_t words[kTile][8];    // sketch words of the tile (W <= 8)
     __shared__ size_t dst[kTile];           // destination record index of each tile record
@@ -60,8 +56,8 @@ __global__ __launch_bounds__(kThreads) void append_kernel(AppendArgs a, BatchDes
     const T *kbase = static_cast<const T *>(a.k) + (size_t)blockIdx.y * a.stride_seq;
     const T *vbase = static_cast<const T *>(a.v) + (size_t)blockIdx.y * a.stride_seq;
 
-    for (int rec0 = blockIdx.x * kTile; rec0 < n_rec; rec0 += gridDim.x * kTile) {
-        const int n_valid = min(kTile, n_rec - rec0);
+    for (int rec0 = blockIdx.x * tile; rec0 < n_rec; rec0 += gridDim.x * tile) {
+        const int n_valid = min(tile, n_rec - rec0);
         __syncthreads();   // previous pass is done with the LDS tile
 
         // ---- stage the key tile as fp32; resolve destinations ----
@@ -109,7 +105,7 @@ __global__ __launch_bounds__(kThreads) void append_kernel(AppendArgs a, BatchDes
         // ---- Eq.(4): one lane per (record, 32-channel slice) ----
         constexpr int LPT = D / 32;
         const int lanes_per_group = G / 32;
-        for (int item = tid; item < kTile * LPT; item += kThreads) {      // uniform trip count: shuffles below need all lanes
+        for (int item = tid; item < ((tile * LPT + 63) & ~63); item += kThreads) {   // whole waves run the loop (shuffles below)
             const int rl = item / LPT, slice = item % LPT;
             const bool valid = rl < n_valid;
             float x[32];
@@ -167,12 +163,16 @@ __global__ __launch_bounds__(kThreads) void append_kernel(AppendArgs a, BatchDes
 
 hipError_t launch_append(const AppendArgs &a, const BatchDesc &desc, int n_seqs, hipStream_t st) {
     const long n_rec = (long)a.n_new * a.pool.n_kv_heads;
-    long tiles = (n_rec + kTile - 1) / kTile;
+    // Records per workgroup pass: a full tile for prefill-sized calls; for a decode step (a handful of records
+    // per sequence) small tiles, so that the few records spread over many compute units.
+    long tile = (n_rec * n_seqs + 255) / 256;
+    tile = tile < 2 ? 2 : (tile > kTile ? kTile : tile);
+    const long tiles = (n_rec + tile - 1) / tile;
     // Each workgroup re-reads R once; with many tiles let one workgroup walk several of them.
     const long max_wgs_x = 4096 / n_seqs > 0 ? 4096 / n_seqs : 1;
     const dim3 grid((unsigned)(tiles < max_wgs_x ? tiles : max_wgs_x), (unsigned)n_seqs);
     const int D = a.pool.head_dim;
-#define H1BKV_LAUNCH(DD, TT) hipLaunchKernelGGL((append_kernel<DD, TT>), grid, dim3(kThreads), 0, st, a, desc)
+#define H1BKV_LAUNCH(DD, TT) hipLaunchKernelGGL((append_kernel<DD, TT>), grid, dim3(kThreads), 0, st, a, desc, (int)tile)
     if (a.f16) {
         if (D == 64) H1BKV_LAUNCH(64, __half);
         else if (D == 128) H1BKV_LAUNCH(128, __half);

@@ -10,10 +10,11 @@
 //            32 codes) and the 4-byte {scale, zero} pair of its group, so a wave instruction covers 1 KiB of
 //            contiguous codes.  Dequantisation is folded into the weights:
 //              sum_t p_t (scale_t code_tc + zero_t) = sum_t (p_t scale_t) code_tc + sum_t p_t zero_t,
-//            i.e. one int->float convert and one fp32 FMA per element, plus one FMA per 32 elements.
+//            and the int4 -> float step rides on the FMA itself (nibbles OR-ed into the mantissa of an fp16
+//            constant, read by a mixed-precision FMA): 15 VALU instructions per 8 elements.
 //            Loads for the next page are in flight while the current page is consumed.
-//   Epilogue sums over the token slots of a wave by lane exchange, over waves through LDS, and writes the
-//            chunk's partial (min distance, sum p, unnormalised output) to the workspace.
+//   Epilogue sums over the token slots of a 16-lane row with DPP rotations, over rows and waves through LDS,
+//            and writes the chunk's partial (min distance, sum p, unnormalised output) to the workspace.
 // merge_kernel: log-sum-exp merge of the chunk partials of one (sequence, query head).
 // qsketch_kernel: s_q = sign(R q) with the same fp32 FMA chain as the keys (lane = bit, ballot = word).
 #include <hip/hip_fp16.h>
@@ -38,12 +39,31 @@ __device__ __forceinline__ float wave_sum(float x) {
     for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off);
     return x;
 }
-// Sum over the lanes that hold the same channel slice (lane % LPT) of different tokens.
+template <int CTRL>
+__device__ __forceinline__ float dpp_mov(float x) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xF, 0xF, false));
+}
+// Sum, inside each row of 16 lanes, over the lanes that hold the same channel slice (lane % LPT) of different
+// tokens.  DPP row rotations: one VALU instruction per step, no LDS traffic.
 template <int LPT>
-__device__ __forceinline__ float slot_sum(float x) {
-#pragma unroll
-    for (int off = 32; off >= LPT; off >>= 1) x += __shfl_xor(x, off);
+__device__ __forceinline__ float row_slot_sum(float x) {
+    if constexpr (LPT == 2) x += dpp_mov<0x4E>(x);    // quad_perm [2,3,0,1]: lane ^ 2
+    if constexpr (LPT <= 4) x += dpp_mov<0x124>(x);   // row_ror:4
+    x += dpp_mov<0x128>(x);                           // row_ror:8
     return x;
+}
+// x[lane] + x[lane ^ 32] (gfx950 lane-swap instruction: upper half of one operand <-> lower half of the other).
+__device__ __forceinline__ float half_wave_sum(float x) {
+    const unsigned u = __float_as_uint(x);
+    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// (x & mask) | magic in one instruction.
+__device__ __forceinline__ uint32_t and_or(uint32_t x, uint32_t mask, uint32_t magic) {
+    uint32_t r;
+    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(x), "v"(mask), "v"(magic));
+    return r;
 }
 
 template <int W>
@@ -75,13 +95,17 @@ struct PageRegs {            // what one lane holds of one page: LPT x (16 B of 
 template <int RQ, int W, int LPT>
 __global__ __launch_bounds__(kThreads) void decode_split_kernel(DecodeArgs a, BatchDesc desc, int seq0) {
     constexpr int D = 32 * LPT;
-    constexpr int TPW = 64 / LPT;     // tokens covered by one wave-wide load
-    __shared__ float p_s[RQ][kMaxChunk];
+    constexpr int TPW = 64 / LPT;                 // tokens covered by one wave-wide load
+    constexpr int ROWS = LPT == 8 ? 2 : 4;        // 16-lane rows of a wave that reach the LDS stage of the epilogue
+    constexpr int NPART = kWaves * ROWS;
+    constexpr int EPI_STRIDE = D + 2 * LPT;       // per (partial, q): D sums, LPT zero-sums, LPT weight-sums
+    constexpr int P_FLOATS = RQ * kMaxChunk, EPI_FLOATS = NPART * RQ * EPI_STRIDE;
+    // p_t of the chunk during phases A/B; reused for the partial sums of the epilogue.
+    __shared__ float smem[P_FLOATS > EPI_FLOATS ? P_FLOATS : EPI_FLOATS];
     __shared__ int pages_s[kMaxPagesPerChunk];
     __shared__ int red_i[RQ][kWaves];
     __shared__ float red_f[RQ][kWaves];
-    __shared__ float wave_o[kWaves][RQ][D];
-    __shared__ float wave_z[kWaves][RQ][LPT];
+    float(*p_s)[kMaxChunk] = reinterpret_cast<float(*)[kMaxChunk]>(smem);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const SeqDesc sd = desc.s[blockIdx.z];
@@ -165,17 +189,24 @@ __global__ __launch_bounds__(kThreads) void decode_split_kernel(DecodeArgs a, Ba
     __syncthreads();
 
     // ---------------- Phase B: weighted sum of dequantised values ----------------
+    // A nibble is turned into an fp16 number without a convert instruction: shifted to mantissa bits 4-7 of
+    // 1024.0 (0x6400) and OR-ed in, it reads as 1024 + 16 code, two nibbles (n and n+4 of a dword) per 32-bit
+    // operation; the fp32 FMA takes the fp16 halves directly (mixed-precision FMA) with weight p scale / 16.
+    // The constant part, 64 times the running sum of weights, is taken off at the end.  (Leaving even nibbles
+    // at bits 0-3 would save two shifts per dword but puts a 1024-fold offset under the fp32 accumulation.)
     float acc[RQ][32];
-    float zs[RQ];
+    float zs[RQ], wsum[RQ];
 #pragma unroll
     for (int q = 0; q < RQ; ++q) {
         zs[q] = 0.0f;
+        wsum[q] = 0.0f;
 #pragma unroll
         for (int i = 0; i < 32; ++i) acc[q][i] = 0.0f;
     }
     const int slice = lane % LPT;
     const int tok_w = wave * 64 + lane / LPT;              // token (within a page) of this lane's first load
     const int meta_col = (slice * 32) / pv.group_size;
+    const uint32_t mask = 0x00F000F0u, magic = 0x64006400u;
 
     auto load_page = [&](PageRegs<LPT> &pr, int pg) {
         const size_t base = ((size_t)pages_s[pg] * H + kvh) * kPage;
@@ -193,26 +224,28 @@ __global__ __launch_bounds__(kThreads) void decode_split_kernel(DecodeArgs a, Ba
             const uint32_t m = idx < n_tok ? pr.m[it] : 0u;    // never let an unwritten slot's bits reach the FMAs
             const float sc = __half2float(__ushort_as_half((unsigned short)(m & 0xFFFFu)));
             const float zp = __half2float(__ushort_as_half((unsigned short)(m >> 16)));
-            float wlo[RQ], whi[RQ];
+            float w16[RQ];
 #pragma unroll
             for (int q = 0; q < RQ; ++q) {
                 const float p = p_s[q][idx];
-                wlo[q] = p * sc;
-                whi[q] = wlo[q] * 0.0625f;                    // high nibbles are converted as 16*code
+                const float w = p * sc;
+                w16[q] = w * 0.0625f;
                 zs[q] = fmaf(p, zp, zs[q]);
+                wsum[q] += w;
             }
             const uint32_t x[4] = {pr.c[it].x, pr.c[it].y, pr.c[it].z, pr.c[it].w};
 #pragma unroll
             for (int dw = 0; dw < 4; ++dw) {
-                const uint32_t lo = x[dw] & 0x0F0F0F0Fu, hi = x[dw] & 0xF0F0F0F0u;
+                const uint32_t t[4] = {and_or(x[dw] << 4, mask, magic), and_or(x[dw], mask, magic),
+                                       and_or(x[dw] >> 4, mask, magic), and_or(x[dw] >> 8, mask, magic)};
 #pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    const float flo = (float)((lo >> (8 * k)) & 0xFFu);
-                    const float fhi = (float)((hi >> (8 * k)) & 0xFFu);
+                for (int n = 0; n < 4; ++n) {               // t[n] holds nibbles n (low half) and n + 4 (high half)
+                    const __half2 h = *reinterpret_cast<const __half2 *>(&t[n]);
+                    const float lo = __low2float(h), hi = __high2float(h);
 #pragma unroll
                     for (int q = 0; q < RQ; ++q) {
-                        acc[q][8 * dw + 2 * k] = fmaf(wlo[q], flo, acc[q][8 * dw + 2 * k]);
-                        acc[q][8 * dw + 2 * k + 1] = fmaf(whi[q], fhi, acc[q][8 * dw + 2 * k + 1]);
+                        acc[q][8 * dw + n] = fmaf(w16[q], lo, acc[q][8 * dw + n]);
+                        acc[q][8 * dw + n + 4] = fmaf(w16[q], hi, acc[q][8 * dw + n + 4]);
                     }
                 }
             }
@@ -234,28 +267,48 @@ __global__ __launch_bounds__(kThreads) void decode_split_kernel(DecodeArgs a, Ba
     }
 
     // ---------------- Epilogue ----------------
+    // Token slots of a 16-lane row are summed with DPP rotations; rows and waves meet in LDS.
 #pragma unroll
     for (int q = 0; q < RQ; ++q) {
 #pragma unroll
-        for (int i = 0; i < 32; ++i) acc[q][i] = slot_sum<LPT>(acc[q][i]);
-        zs[q] = slot_sum<LPT>(zs[q]);
+        for (int i = 0; i < 32; ++i) {
+            acc[q][i] = row_slot_sum<LPT>(acc[q][i]);
+            if constexpr (ROWS == 2) acc[q][i] = half_wave_sum(acc[q][i]);
+        }
+        zs[q] = row_slot_sum<LPT>(zs[q]);
+        wsum[q] = row_slot_sum<LPT>(wsum[q]);
+        if constexpr (ROWS == 2) {
+            zs[q] = half_wave_sum(zs[q]);
+            wsum[q] = half_wave_sum(wsum[q]);
+        }
     }
-    if (lane < LPT) {
+    __syncthreads();                                   // every wave is done reading p_s
+    float *epi = smem;
+    const int row = lane >> 4;
+    if ((lane & 15) < LPT && row < ROWS) {
 #pragma unroll
         for (int q = 0; q < RQ; ++q) {
+            float *dst = epi + ((size_t)(wave * ROWS + row) * RQ + q) * EPI_STRIDE;
 #pragma unroll
-            for (int i = 0; i < 32; ++i) wave_o[wave][q][lane * 32 + i] = acc[q][i];
-            wave_z[wave][q][lane] = zs[q];
+            for (int i = 0; i < 32; i += 4)
+                *reinterpret_cast<float4 *>(dst + slice * 32 + i) = make_float4(acc[q][i], acc[q][i + 1], acc[q][i + 2], acc[q][i + 3]);
+            dst[D + slice] = zs[q];
+            dst[D + LPT + slice] = wsum[q];
         }
     }
     __syncthreads();
     const size_t part = ((size_t)seq_g * pv.n_q_heads + qh0) * a.n_splits + blockIdx.x;
     for (int e = tid; e < RQ * D; e += kThreads) {
         const int q = e / D, c = e % D;
-        float o = 0.0f;
+        float o = 0.0f, z = 0.0f, ws = 0.0f;
 #pragma unroll
-        for (int w = 0; w < kWaves; ++w) o += wave_o[w][q][c] + wave_z[w][q][c / 32];
-        a.part_o[(part + (size_t)q * a.n_splits) * D + c] = o;
+        for (int pt = 0; pt < NPART; ++pt) {
+            const float *src = epi + ((size_t)pt * RQ + q) * EPI_STRIDE;
+            o += src[c];
+            z += src[D + c / 32];
+            ws += src[D + LPT + c / 32];
+        }
+        a.part_o[(part + (size_t)q * a.n_splits) * D + c] = fmaf(-64.0f, ws, o) + z;   // (1024 + 16 code) / 16 = 64 + code
     }
     if (tid < RQ) {
         float *ml = a.part_ml + (part + (size_t)tid * a.n_splits) * 2;
@@ -278,8 +331,10 @@ __global__ void merge_kernel(DecodeArgs a, BatchDesc desc, int seq0) {
         return;
     }
     int hmin = 1 << 20;
+#pragma unroll 4
     for (int s = 0; s < n; ++s) hmin = min(hmin, __float_as_int(a.part_ml[(part + s) * 2]));
     float l = 0.0f, o = 0.0f;
+#pragma unroll 8
     for (int s = 0; s < n; ++s) {
         const float w = exp2f(a.exp2_scale * (float)(hmin - __float_as_int(a.part_ml[(part + s) * 2])));
         l = fmaf(w, a.part_ml[(part + s) * 2 + 1], l);
@@ -299,6 +354,7 @@ __global__ void qsketch_kernel(DecodeArgs a, int seq0) {
     __syncthreads();
     const int bit = threadIdx.x;
     float y = 0.0f;
+#pragma unroll 16
     for (int j = 0; j < D; ++j) y = __builtin_fmaf(a.pool.RT[(size_t)j * b + bit], qs[j], y);
     const uint64_t mask = __ballot(y >= 0.0f);
     if ((threadIdx.x & 63) == 0) a.q_sketch[vec * W + (threadIdx.x >> 6)] = mask;

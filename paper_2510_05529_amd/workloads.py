@@ -14,6 +14,7 @@ the CPU oracle and to the HIP library and performs no sketching, quantisation or
 """
 from __future__ import annotations
 
+import functools
 from dataclasses import dataclass, replace
 from typing import Tuple
 
@@ -91,12 +92,14 @@ def projection(sketch_bits: int, head_dim: int, seed: int = R_SEED) -> np.ndarra
     return np.random.default_rng(seed).standard_normal((sketch_bits, head_dim)).astype(np.float32)
 
 
+@functools.lru_cache(maxsize=64)
 def _head_scale(w: Workload, tensor: int, n_heads: int) -> np.ndarray:
     if not w.head_scale:
         return np.ones(n_heads, dtype=np.float32)
     return _rng(w.seed, _TENSOR_HEADSCALE, tensor).uniform(0.5, 2.0, n_heads).astype(np.float32)
 
 
+@functools.lru_cache(maxsize=16)
 def outlier_mask(w: Workload) -> np.ndarray:
     """Boolean [H_kv][d]: channels that carry the x outlier_gain factor (same for K and V, all tokens)."""
     if w.outlier_frac <= 0.0:
@@ -123,12 +126,25 @@ def kv_block(w: Workload, which: str, seq: int, head: int, t0: int, n: int) -> n
     return out.astype(w.np_dtype)
 
 
-def kv_slab(w: Workload, which: str, seqs, t0: int, n: int) -> np.ndarray:
-    """K or V for several sequences in the boundary layout [len(seqs)][n][H_kv][d]."""
+def kv_slab(w: Workload, which: str, seqs, t0: int, n: int, workers: int = 1) -> np.ndarray:
+    """K or V for several sequences in the boundary layout [len(seqs)][n][H_kv][d].
+    `workers` > 1 draws the (sequence, head) blocks on a thread pool (numpy's generators release the GIL);
+    the values do not depend on it."""
+    seqs = list(seqs)
     out = np.empty((len(seqs), n, w.n_kv_heads, w.head_dim), dtype=w.np_dtype)
-    for i, s in enumerate(seqs):
-        for h in range(w.n_kv_heads):
-            out[i, :, h, :] = kv_block(w, which, s, h, t0, n)
+
+    def fill(job):
+        i, h = job
+        out[i, :, h, :] = kv_block(w, which, seqs[i], h, t0, n)
+
+    jobs = [(i, h) for i in range(len(seqs)) for h in range(w.n_kv_heads)]
+    if workers > 1 and len(jobs) > 1:
+        from concurrent.futures import ThreadPoolExecutor
+        with ThreadPoolExecutor(max_workers=workers) as ex:
+            list(ex.map(fill, jobs))
+    else:
+        for j in jobs:
+            fill(j)
     return out
 
 

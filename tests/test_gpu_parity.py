@@ -91,7 +91,7 @@ def test_split_count_does_not_change_the_result():
         assert B.h1bkv_set_decode_chunk(cache.h, chunk) == B.H1BKV_OK
         outs.append(cache.decode(seqs, q, w.default_tau()).cpu().numpy())
     for o in outs[1:]:
-        assert rel_err(o, outs[0]) < 1e-5
+        assert rel_err(o, outs[0]) < 1e-4          # only the fp32 summation order differs
     cache.close()
 
 
@@ -136,7 +136,7 @@ def test_page_assignment_does_not_matter_and_pages_are_reused():
         for x, y in zip(a, b):
             assert np.array_equal(x, y)
     out2 = cache.decode([0, 1], q, 0.06).cpu().numpy()
-    assert rel_err(out2, out1) < 1e-5
+    assert rel_err(out2, out1) < 1e-4
     cache.close()
 
 
