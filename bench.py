@@ -126,7 +126,17 @@ def main():
             B.check(B.h1bkv_stream_copy(dst, src, n, None))
         torch.cuda.synchronize()
         ms = (time.perf_counter() - t) * 1e3 / args.steps
-        print(json.dumps({"calibrate_copy_bytes": n, "ms_per_copy": ms, "read_GBps": n / ms / 1e6, "read_plus_write_GBps": 2 * n / ms / 1e6}))
+        sink = torch.zeros(128 << 10, dtype=torch.uint8, device="cuda")
+        for _ in range(max(1, args.warmup)):
+            B.check(B.h1bkv_stream_read(src, n, sink, None))
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for _ in range(args.steps):
+            B.check(B.h1bkv_stream_read(src, n, sink, None))
+        torch.cuda.synchronize()
+        ms_r = (time.perf_counter() - t) * 1e3 / args.steps
+        print(json.dumps({"calibrate_copy_bytes": n, "ms_per_copy": ms, "copy_read_plus_write_GBps": 2 * n / ms / 1e6,
+                          "ms_per_read": ms_r, "read_only_GBps": n / ms_r / 1e6}))
         return
 
     w = wl.WORKLOADS[args.workload]

@@ -179,6 +179,13 @@ int h1bkv_profile_read(h1bkv_cache *c, int32_t kernel, float *ms_out, int32_t ca
  */
 int h1bkv_stream_copy(void *dst_dev, const void *src_dev, size_t n_bytes, void *hip_stream);
 
+/*
+ * Read-only counterpart: streams n_bytes (a multiple of 16, 16-byte aligned) from src_dev with 16-byte loads,
+ * XOR-folds them and writes 16 bytes per workgroup to sink_dev (>= 128 KiB).  Its rate is the HBM read
+ * ceiling a streaming kernel can reach on this device, against which the decode kernel is also reported.
+ */
+int h1bkv_stream_read(const void *src_dev, size_t n_bytes, void *sink_dev, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -70,6 +70,7 @@ def lib() -> C.CDLL:
             "h1bkv_profile_enable": (C.c_int, [vp, i32]),
             "h1bkv_profile_read": (C.c_int, [vp, i32, vp, i32, C.POINTER(i32)]),
             "h1bkv_stream_copy": (C.c_int, [vp, vp, sz, vp]),
+            "h1bkv_stream_read": (C.c_int, [vp, sz, vp, vp]),
         }
         for name, (res, args) in sig.items():
             fn = getattr(L, name)
@@ -208,6 +209,10 @@ def h1bkv_profile_read(h, kernel: int, cap: int = 4096):
 
 def h1bkv_stream_copy(dst, src, n_bytes: int, stream=0) -> int:
     return lib().h1bkv_stream_copy(_dev_ptr(dst), _dev_ptr(src), n_bytes, _stream(stream))
+
+
+def h1bkv_stream_read(src, n_bytes: int, sink, stream=0) -> int:
+    return lib().h1bkv_stream_read(_dev_ptr(src), n_bytes, _dev_ptr(sink), _stream(stream))
 
 
 def check(code: int, what: str = "h1bkv") -> None:

@@ -554,4 +554,11 @@ int h1bkv_stream_copy(void *dst_dev, const void *src_dev, size_t n_bytes, void *
     return launch_stream_copy(dst_dev, src_dev, n_bytes, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? H1BKV_OK : H1BKV_EHIP;
 }
 
+int h1bkv_stream_read(const void *src_dev, size_t n_bytes, void *sink_dev, void *hip_stream) {
+    if (!src_dev || !sink_dev) return H1BKV_ENULL;
+    if (n_bytes % 16 || reinterpret_cast<uintptr_t>(src_dev) % 16 || reinterpret_cast<uintptr_t>(sink_dev) % 16) return H1BKV_EINVAL;
+    if (n_bytes == 0) return H1BKV_OK;
+    return launch_stream_read(src_dev, n_bytes, sink_dev, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? H1BKV_OK : H1BKV_EHIP;
+}
+
 }  // extern "C"

@@ -70,5 +70,6 @@ hipError_t launch_qsketch(const DecodeArgs &a, int seq0, int n_seqs, hipStream_t
 hipError_t launch_decode_split(const DecodeArgs &a, const BatchDesc &desc, int seq0, int n_seqs, hipStream_t st);
 hipError_t launch_merge(const DecodeArgs &a, const BatchDesc &desc, int seq0, int n_seqs, hipStream_t st);
 hipError_t launch_stream_copy(void *dst, const void *src, size_t n_bytes, hipStream_t st);
+hipError_t launch_stream_read(const void *src, size_t n_bytes, void *sink, hipStream_t st);
 
 }  // namespace h1bkv

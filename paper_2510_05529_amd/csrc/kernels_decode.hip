@@ -132,6 +132,22 @@ __global__ __launch_bounds__(kThreads) void decode_split_kernel(DecodeArgs a, Ba
         for (int w = 0; w < W; ++w) sq[q][w] = a.q_sketch[((size_t)seq_g * pv.n_q_heads + qh0 + q) * W + w];
     __syncthreads();
 
+    const int slice = lane % LPT;
+    const int tok_w = wave * 64 + lane / LPT;              // token (within a page) of this lane's first load
+    const int meta_col = (slice * 32) / pv.group_size;
+    const uint32_t mask = 0x00F000F0u, magic = 0x64006400u;
+
+    auto load_page = [&](PageRegs<LPT> &pr, int pg) {
+        const size_t base = ((size_t)pages_s[pg] * H + kvh) * kPage;
+        const uint4 *cp = reinterpret_cast<const uint4 *>(pv.codes) + (base * LPT + wave * 64 * LPT + lane);
+#pragma unroll
+        for (int it = 0; it < LPT; ++it) {
+            pr.c[it] = cp[it * 64];
+            pr.m[it] = pv.meta[(base + tok_w + it * TPW) * ng + meta_col];
+        }
+    };
+    PageRegs<LPT> A, B;
+
     // ---------------- Phase A: scores ----------------
     int ham[RQ][kMaxPagesPerChunk];
     int hmin[RQ];
@@ -142,6 +158,9 @@ __global__ __launch_bounds__(kThreads) void decode_split_kernel(DecodeArgs a, Ba
 #pragma unroll
         for (int k = 0; k < kMaxPagesPerChunk; ++k)
             if (k < n_pages) s[k] = load_sketch<W>(pv.sketch + (((size_t)pages_s[k] * H + kvh) * kPage + tid) * W);
+        // The first page of values is requested right behind the sketches, before any score is computed, so
+        // that its latency is covered by phase A instead of being paid after it.
+        load_page(A, 0);
 #pragma unroll
         for (int k = 0; k < kMaxPagesPerChunk; ++k) {
             if (k < n_pages) {
@@ -203,20 +222,6 @@ __global__ __launch_bounds__(kThreads) void decode_split_kernel(DecodeArgs a, Ba
 #pragma unroll
         for (int i = 0; i < 32; ++i) acc[q][i] = 0.0f;
     }
-    const int slice = lane % LPT;
-    const int tok_w = wave * 64 + lane / LPT;              // token (within a page) of this lane's first load
-    const int meta_col = (slice * 32) / pv.group_size;
-    const uint32_t mask = 0x00F000F0u, magic = 0x64006400u;
-
-    auto load_page = [&](PageRegs<LPT> &pr, int pg) {
-        const size_t base = ((size_t)pages_s[pg] * H + kvh) * kPage;
-        const uint4 *cp = reinterpret_cast<const uint4 *>(pv.codes) + (base * LPT + wave * 64 * LPT + lane);
-#pragma unroll
-        for (int it = 0; it < LPT; ++it) {
-            pr.c[it] = cp[it * 64];
-            pr.m[it] = pv.meta[(base + tok_w + it * TPW) * ng + meta_col];
-        }
-    };
     auto consume_page = [&](const PageRegs<LPT> &pr, int pg) {
 #pragma unroll
         for (int it = 0; it < LPT; ++it) {
@@ -253,8 +258,6 @@ __global__ __launch_bounds__(kThreads) void decode_split_kernel(DecodeArgs a, Ba
     };
 
     {
-        PageRegs<LPT> A, B;
-        load_page(A, 0);
         int pg = 0;
         while (true) {
             if (pg + 1 < n_pages) load_page(B, pg + 1);
