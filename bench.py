@@ -98,6 +98,56 @@ def cpu_baseline(wl, w, tau, workers):
             "ms_per_step": sec * 1e3}
 
 
+FP32_VALU_PEAK_TFLOPS = 78.6    # 256 CUs x 4 SIMDs x 16 lanes x 2 flop x 2.4 GHz: plain (non-packed) fp32 FMA issue
+
+
+def bench_append(args, torch, B, wl, w, workers):
+    """Secondary line: prefill-sized cache append (all new tokens of every sequence in one call)."""
+    n_new, Bsz = w.context, w.batch
+    R = wl.projection(w.sketch_bits, w.head_dim)
+    pages_per_seq = (n_new + 255) // 256 + 1
+    cache = B.Cache(n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim, sketch_bits=w.sketch_bits,
+                    group_size=w.group_size, dtype=w.dtype, max_seqs=Bsz, max_pages=Bsz * pages_per_seq,
+                    max_pages_per_seq=pages_per_seq, R=R)
+    seqs = list(range(Bsz))
+    k = torch.from_numpy(wl.kv_slab(w, "k", seqs, 0, n_new, workers)).cuda()
+    v = torch.from_numpy(wl.kv_slab(w, "v", seqs, 0, n_new, workers)).cuda()
+    stream = torch.cuda.current_stream()
+
+    def step():
+        for s in seqs:
+            B.check(B.h1bkv_reset_seq(cache.h, s))
+        B.check(B.h1bkv_append_kv(cache.h, seqs, n_new, k, v, k.stride(0), k.stride(1), k.stride(2), stream))
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    B.check(B.h1bkv_profile_enable(cache.h, args.steps))
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    rc, ms = B.h1bkv_profile_read(cache.h, B.H1BKV_K_APPEND)
+    B.check(rc)
+    kernel_ms = float(ms.mean())
+    records = Bsz * n_new * w.n_kv_heads
+    flops = 2.0 * records * w.sketch_bits * w.head_dim          # the projection's multiply-adds (Eq. 2)
+    elt = 2 if w.dtype == "f16" else 4
+    bytes_moved = records * (2 * w.head_dim * elt + w.record_bytes)
+    achieved = flops / (kernel_ms * 1e-3) / 1e12
+    print(json.dumps({
+        "metric": "append_tokens_per_s", "value": Bsz * n_new / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w.name, "batch": Bsz, "new_tokens": n_new, "n_kv_heads": w.n_kv_heads, "head_dim": w.head_dim,
+                   "sketch_bits": w.sketch_bits, "group_size": w.group_size, "in_dtype": w.dtype},
+        "roofline": {"bound": "alu", "kernel": "append_kernel", "achieved": achieved, "peak": FP32_VALU_PEAK_TFLOPS,
+                     "unit": "TFLOP/s", "frac": achieved / FP32_VALU_PEAK_TFLOPS, "traffic": None, "kernel_ms": kernel_ms,
+                     "hbm_GBps": bytes_moved / (kernel_ms * 1e-3) / 1e9},
+        "records_per_s": records / (ms_per_step * 1e-3)}))
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -140,6 +190,9 @@ def main():
         return
 
     w = wl.WORKLOADS[args.workload]
+    if args.workload == "append_prefill_8k":
+        bench_append(args, torch, B, wl, w, workers)
+        return
     T, Bsz = w.context, w.batch
     tau = w.default_tau()
     R = wl.projection(w.sketch_bits, w.head_dim)

@@ -93,7 +93,7 @@ struct PageRegs {            // what one lane holds of one page: LPT x (16 B of 
 };
 
 template <int RQ, int W, int LPT>
-__global__ __launch_bounds__(kThreads) void decode_split_kernel(DecodeArgs a, BatchDesc desc, int seq0) {
+__global__ __launch_bounds__(kThreads, RQ >= 4 ? 2 : 1) void decode_split_kernel(DecodeArgs a, BatchDesc desc, int seq0) {
     constexpr int D = 32 * LPT;
     constexpr int TPW = 64 / LPT;                 // tokens covered by one wave-wide load
     constexpr int ROWS = LPT == 8 ? 2 : 4;        // 16-lane rows of a wave that reach the LDS stage of the epilogue
@@ -146,7 +146,11 @@ __global__ __launch_bounds__(kThreads) void decode_split_kernel(DecodeArgs a, Ba
             pr.m[it] = pv.meta[(base + tok_w + it * TPW) * ng + meta_col];
         }
     };
-    PageRegs<LPT> A, B;
+    // With 4 query heads per lane the 128 accumulators leave no room for a second page buffer: those variants run
+    // single-buffered at 2 waves per SIMD and rely on the other resident waves to cover the load latency.
+    constexpr bool kDoubleBuffer = RQ < 4;
+    PageRegs<LPT> A;
+    [[maybe_unused]] PageRegs<LPT> B;
 
     // ---------------- Phase A: scores ----------------
     int ham[RQ][kMaxPagesPerChunk];
@@ -257,7 +261,7 @@ __global__ __launch_bounds__(kThreads) void decode_split_kernel(DecodeArgs a, Ba
         }
     };
 
-    {
+    if constexpr (kDoubleBuffer) {
         int pg = 0;
         while (true) {
             if (pg + 1 < n_pages) load_page(B, pg + 1);
@@ -266,6 +270,11 @@ __global__ __launch_bounds__(kThreads) void decode_split_kernel(DecodeArgs a, Ba
             if (pg + 1 < n_pages) load_page(A, pg + 1);
             consume_page(B, pg);
             if (++pg >= n_pages) break;
+        }
+    } else {
+        for (int pg = 0; pg < n_pages; ++pg) {
+            if (pg > 0) load_page(A, pg);
+            consume_page(A, pg);
         }
     }
 
