@@ -160,15 +160,15 @@ int h1bkv_import_tokens(h1bkv_cache *c, int32_t seq_id, int32_t kv_head, int32_t
 int h1bkv_extend_seq(h1bkv_cache *c, int32_t seq_id, int32_t n_new, void *hip_stream);
 
 /*
- * Per-kernel timing for benchmarks.  After h1bkv_profile_enable(c, capacity > 0), every launch of the
- * library's kernels on this handle is bracketed by a pair of HIP events on the launch stream (up to
- * `capacity` launches per kernel kind; later ones are not recorded).  h1bkv_profile_read waits for the
- * recorded events and writes the elapsed milliseconds of each recorded launch of `kernel` to ms_out
- * (at most cap values) and their number to n_out, then clears that kind's records.
+ * Per-kernel timing for benchmarks.  After h1bkv_profile_enable(c, capacity > 0, kernel_mask), every launch of
+ * the library's kernels whose kind is in kernel_mask (bit 1 << H1BKV_K_*) on this handle is bracketed by a pair
+ * of HIP events on the launch stream (up to `capacity` launches per kind; later ones are not recorded).
+ * h1bkv_profile_read waits for the recorded events and writes the elapsed milliseconds of each recorded launch
+ * of `kernel` to ms_out (at most cap values) and their number to n_out, then clears that kind's records.
  * capacity == 0 disables recording and releases the events.
  */
 enum { H1BKV_K_APPEND = 0, H1BKV_K_QSKETCH = 1, H1BKV_K_DECODE_SPLIT = 2, H1BKV_K_MERGE = 3, H1BKV_K_COUNT = 4 };
-int h1bkv_profile_enable(h1bkv_cache *c, int32_t capacity);
+int h1bkv_profile_enable(h1bkv_cache *c, int32_t capacity, uint32_t kernel_mask);
 int h1bkv_profile_read(h1bkv_cache *c, int32_t kernel, float *ms_out, int32_t cap, int32_t *n_out);
 
 /*

@@ -67,7 +67,7 @@ def lib() -> C.CDLL:
             "h1bkv_export_tokens": (C.c_int, [vp, i32, i32, i32, i32, vp, vp, vp, vp]),
             "h1bkv_import_tokens": (C.c_int, [vp, i32, i32, i32, i32, vp, vp, vp, vp]),
             "h1bkv_extend_seq": (C.c_int, [vp, i32, i32, vp]),
-            "h1bkv_profile_enable": (C.c_int, [vp, i32]),
+            "h1bkv_profile_enable": (C.c_int, [vp, i32, C.c_uint32]),
             "h1bkv_profile_read": (C.c_int, [vp, i32, vp, i32, C.POINTER(i32)]),
             "h1bkv_stream_copy": (C.c_int, [vp, vp, sz, vp]),
             "h1bkv_stream_read": (C.c_int, [vp, sz, vp, vp]),
@@ -196,8 +196,8 @@ def h1bkv_extend_seq(h, seq_id: int, n_new: int, stream=0) -> int:
     return lib().h1bkv_extend_seq(h, seq_id, n_new, _stream(stream))
 
 
-def h1bkv_profile_enable(h, capacity: int) -> int:
-    return lib().h1bkv_profile_enable(h, capacity)
+def h1bkv_profile_enable(h, capacity: int, kernel_mask: int = 0xF) -> int:
+    return lib().h1bkv_profile_enable(h, capacity, kernel_mask)
 
 
 def h1bkv_profile_read(h, kernel: int, cap: int = 4096):

@@ -67,6 +67,7 @@ struct h1bkv_cache {
     int32_t chunk_override;
     // profiling
     int32_t prof_cap;
+    uint32_t prof_mask;
     std::vector<EventPair> prof_events[H1BKV_K_COUNT];
     int32_t prof_used[H1BKV_K_COUNT];
 
@@ -103,7 +104,7 @@ struct Timed {
     hipStream_t st;
     int slot;
     Timed(h1bkv_cache *c_, int kind_, hipStream_t st_) : c(c_), kind(kind_), st(st_), slot(-1) {
-        if (c->prof_cap > 0 && c->prof_used[kind] < c->prof_cap) {
+        if (c->prof_cap > 0 && ((c->prof_mask >> kind) & 1u) && c->prof_used[kind] < c->prof_cap) {
             slot = c->prof_used[kind]++;
             (void)hipEventRecord(c->prof_events[kind][slot].a, st);
         }
@@ -239,6 +240,7 @@ int h1bkv_create(const h1bkv_config *cfg, void *pool_dev, size_t pool_bytes, con
     for (int i = 0; i < cfg->max_pages; ++i) c->free_list[i] = cfg->max_pages - 1 - i;  // page 0 is taken first
     c->chunk_override = 0;
     c->prof_cap = 0;
+    c->prof_mask = 0;
     for (int k = 0; k < H1BKV_K_COUNT; ++k) c->prof_used[k] = 0;
     if (!dry) {
         if (check_device(c) != H1BKV_OK) {
@@ -513,7 +515,7 @@ int h1bkv_import_tokens(h1bkv_cache *c, int32_t seq_id, int32_t kv_head, int32_t
                        const_cast<uint16_t *>(scale_in), const_cast<uint16_t *>(zero_in));
 }
 
-int h1bkv_profile_enable(h1bkv_cache *c, int32_t capacity) {
+int h1bkv_profile_enable(h1bkv_cache *c, int32_t capacity, uint32_t kernel_mask) {
     if (!c) return H1BKV_ENULL;
     if (capacity < 0) return H1BKV_EINVAL;
     if (c->dry) return capacity == 0 ? H1BKV_OK : H1BKV_ENODEVICE;
@@ -521,7 +523,9 @@ int h1bkv_profile_enable(h1bkv_cache *c, int32_t capacity) {
     if (capacity == 0) return H1BKV_OK;
     int rc = check_device(c);
     if (rc != H1BKV_OK) return rc;
+    c->prof_mask = kernel_mask;
     for (int k = 0; k < H1BKV_K_COUNT; ++k) {
+        if (!((kernel_mask >> k) & 1u)) continue;
         c->prof_events[k].resize(capacity);
         for (auto &e : c->prof_events[k]) {
             if (hipEventCreate(&e.a) != hipSuccess || hipEventCreate(&e.b) != hipSuccess) return H1BKV_EHIP;

@@ -330,29 +330,47 @@ __global__ __launch_bounds__(kThreads, RQ >= 4 ? 2 : 1) void decode_split_kernel
 }
 
 // out = sum_s e^{(alpha_s - alpha_max)/tau} o_s / sum_s e^{(alpha_s - alpha_max)/tau} l_s over the chunks of one head.
-__global__ void merge_kernel(DecodeArgs a, BatchDesc desc, int seq0) {
+// One block per (sequence, query head); thread = (channel, chunk lane): the chunks are strided over
+// kMergeThreads / d lanes and met in LDS, so a 128k context (64 chunks) costs 16 dependent steps, not 64.
+constexpr int kMergeThreads = 512;
+__global__ __launch_bounds__(kMergeThreads) void merge_kernel(DecodeArgs a, BatchDesc desc, int seq0) {
+    __shared__ int hmin_s[kMergeThreads / 64];
+    __shared__ float lo_s[kMergeThreads][2];
     const int D = a.pool.head_dim;
     const int qh = blockIdx.x, seq_g = seq0 + blockIdx.y;
     const int ctx = desc.s[blockIdx.y].pos;
     const int n = (ctx + a.chunk - 1) / a.chunk;
     const size_t part = ((size_t)seq_g * a.pool.n_q_heads + qh) * a.n_splits;
-    const int c = threadIdx.x;
+    const int tid = threadIdx.x, c = tid % D, sl = tid / D, n_sl = kMergeThreads / D;
     float *out = a.out + ((size_t)seq_g * a.pool.n_q_heads + qh) * D;
     if (n == 0) {
-        out[c] = 0.0f;
+        if (sl == 0) out[c] = 0.0f;
         return;
     }
     int hmin = 1 << 20;
-#pragma unroll 4
-    for (int s = 0; s < n; ++s) hmin = min(hmin, __float_as_int(a.part_ml[(part + s) * 2]));
+    for (int s = tid; s < n; s += kMergeThreads) hmin = min(hmin, __float_as_int(a.part_ml[(part + s) * 2]));
+    hmin = wave_min(hmin);
+    if ((tid & 63) == 0) hmin_s[tid >> 6] = hmin;
+    __syncthreads();
+#pragma unroll
+    for (int w = 0; w < kMergeThreads / 64; ++w) hmin = min(hmin, hmin_s[w]);
     float l = 0.0f, o = 0.0f;
-#pragma unroll 8
-    for (int s = 0; s < n; ++s) {
+#pragma unroll 4
+    for (int s = sl; s < n; s += n_sl) {
         const float w = exp2f(a.exp2_scale * (float)(hmin - __float_as_int(a.part_ml[(part + s) * 2])));
         l = fmaf(w, a.part_ml[(part + s) * 2 + 1], l);
         o = fmaf(w, a.part_o[(part + s) * D + c], o);
     }
-    out[c] = o / l;
+    lo_s[tid][0] = l;
+    lo_s[tid][1] = o;
+    __syncthreads();
+    if (sl == 0) {
+        for (int k = 1; k < n_sl; ++k) {
+            l += lo_s[k * D + c][0];
+            o += lo_s[k * D + c][1];
+        }
+        out[c] = o / l;
+    }
 }
 
 // One wave per (query vector, sketch word): lane = bit.
@@ -409,7 +427,7 @@ hipError_t launch_decode_split(const DecodeArgs &a, const BatchDesc &desc, int s
 }
 
 hipError_t launch_merge(const DecodeArgs &a, const BatchDesc &desc, int seq0, int n_seqs, hipStream_t st) {
-    hipLaunchKernelGGL(merge_kernel, dim3((unsigned)a.pool.n_q_heads, (unsigned)n_seqs), dim3((unsigned)a.pool.head_dim), 0, st, a, desc, seq0);
+    hipLaunchKernelGGL(merge_kernel, dim3((unsigned)a.pool.n_q_heads, (unsigned)n_seqs), dim3(kMergeThreads), 0, st, a, desc, seq0);
     return hipGetLastError();
 }
 

@@ -139,7 +139,7 @@ def test_misc_errors():
     assert B.h1bkv_export_tokens(h, 0, 4, 0, 1, 2, 128, 4)[0] == B.H1BKV_ERANGE      # head out of range
     assert B.h1bkv_export_tokens(h, 0, 0, 3, 3, 2, 128, 4)[0] == B.H1BKV_ERANGE      # runs past the length
     assert B.h1bkv_export_tokens(h, 0, 0, 0, 5, 2, 128, 4)[0] == B.H1BKV_ENODEVICE
-    assert B.h1bkv_profile_enable(h, 4) == B.H1BKV_ENODEVICE and B.h1bkv_profile_enable(h, 0) == B.H1BKV_OK
+    assert B.h1bkv_profile_enable(h, 4, 0xF) == B.H1BKV_ENODEVICE and B.h1bkv_profile_enable(h, 0, 0) == B.H1BKV_OK
     assert B.h1bkv_stream_copy(None, None, 16) == B.H1BKV_ENULL
     assert B.h1bkv_stream_copy(4096, 8192, 24) == B.H1BKV_EINVAL
     assert B.h1bkv_destroy(h) == B.H1BKV_OK and B.h1bkv_destroy(None) == B.H1BKV_OK
