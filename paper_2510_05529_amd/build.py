@@ -19,12 +19,13 @@ LIB = os.path.join(LIBDIR, "libh1bkv.so")
 
 COMMON = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-I", os.path.join(ROOT, "include"), "-I", CSRC,
           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-          "-fhip-fp32-correctly-rounded-divide-sqrt", "-fno-fast-math", "-Wall", "-Wno-unused-command-line-argument"]
+          "-fhip-fp32-correctly-rounded-divide-sqrt", "-fno-fast-math", "-fno-strict-aliasing", "-Wall", "-Wno-unused-command-line-argument"]
 SOURCES = {
     "cache.cpp": ["-x", "hip"],
     "kernels_misc.hip": [],
     "kernels_append.hip": ["-ffp-contract=off"],
     "kernels_decode.hip": [],
+    "kernels_decode_mfma.hip": [],
 }
 
 
@@ -38,7 +39,8 @@ def _stale(target: str, deps) -> bool:
 def build(force: bool = False, verbose: bool = False) -> str:
     os.makedirs(LIBDIR, exist_ok=True)
     os.makedirs(OBJDIR, exist_ok=True)
-    headers = [os.path.join(ROOT, "include", "h1bkv.h"), os.path.join(CSRC, "internal.h"), os.path.abspath(__file__)]
+    headers = [os.path.join(ROOT, "include", "h1bkv.h"), os.path.join(CSRC, "internal.h"), os.path.join(CSRC, "decode_common.h"),
+               os.path.abspath(__file__)]
     jobs = []
     objs = []
     for src, extra in SOURCES.items():

@@ -58,6 +58,7 @@ struct h1bkv_cache {
     h1bkv_config cfg;
     Layout lay;
     int W, ng, r;
+    int code_layout;   // 0 record-major, 1 token-interleaved (matrix-core decode); see internal.h
     bool dry;
     char *pool;
     std::vector<float> R;
@@ -85,6 +86,7 @@ struct h1bkv_cache {
         v.head_dim = cfg.head_dim;
         v.sketch_bits = cfg.sketch_bits;
         v.group_size = cfg.group_size;
+        v.code_layout = code_layout;
         return v;
     }
 };
@@ -181,7 +183,7 @@ int choose_chunk(const h1bkv_cache *c, int n_seqs, int max_ctx) {
     if (c->chunk_override > 0) return c->chunk_override;
     const int64_t heads = (int64_t)n_seqs * c->cfg.n_kv_heads;
     const int64_t target_wgs = 4096;
-    int chunk = kMaxChunk;
+    int chunk = max_decode_chunk(c->r, c->code_layout);
     while (chunk > kPage && heads * ((max_ctx + chunk - 1) / chunk) < target_wgs) chunk /= 2;
     return chunk;
 }
@@ -230,6 +232,7 @@ int h1bkv_create(const h1bkv_config *cfg, void *pool_dev, size_t pool_bytes, con
     c->W = cfg->sketch_bits / 64;
     c->ng = cfg->head_dim / cfg->group_size;
     c->r = cfg->n_q_heads / cfg->n_kv_heads;
+    c->code_layout = mfma_decode_supported(cfg->n_q_heads / cfg->n_kv_heads, cfg->head_dim, cfg->group_size) ? 1 : 0;
     c->dry = dry;
     c->pool = static_cast<char *>(pool_dev);
     const size_t nR = (size_t)cfg->sketch_bits * cfg->head_dim;
@@ -307,7 +310,7 @@ int h1bkv_reset_seq(h1bkv_cache *c, int32_t seq_id) { return h1bkv_truncate_seq(
 
 int h1bkv_set_decode_chunk(h1bkv_cache *c, int32_t chunk_tokens) {
     if (!c) return H1BKV_ENULL;
-    if (chunk_tokens != 0 && (chunk_tokens < kPage || chunk_tokens > kMaxChunk || chunk_tokens % kPage != 0)) return H1BKV_EINVAL;
+    if (chunk_tokens != 0 && (chunk_tokens < kPage || chunk_tokens > max_decode_chunk(c->r, c->code_layout) || chunk_tokens % kPage != 0)) return H1BKV_EINVAL;
     c->chunk_override = chunk_tokens;
     return H1BKV_OK;
 }
@@ -443,7 +446,8 @@ int h1bkv_decode_attn(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n_seq
         }
         {
             Timed t(c, H1BKV_K_DECODE_SPLIT, st);
-            if (launch_decode_split(a, desc, s0, n, st) != hipSuccess) return H1BKV_EHIP;
+            const hipError_t e = c->code_layout == 1 ? launch_decode_split_mfma(a, desc, s0, n, st) : launch_decode_split(a, desc, s0, n, st);
+            if (e != hipSuccess) return H1BKV_EHIP;
         }
         {
             Timed t(c, H1BKV_K_MERGE, st);
@@ -479,9 +483,33 @@ static int xfer_tokens(const h1bkv_cache *c, int32_t seq_id, int32_t kv_head, in
             void *dev = pv.sketch + rec * W;
             ok = ok && hipMemcpy(to_host ? (void *)(sk + i * W) : dev, to_host ? dev : (void *)(sk + i * W), run * W * 8, kind) == hipSuccess;
         }
-        if (codes) {
+        if (codes && c->code_layout == 0) {
             void *dev = pv.codes + rec * hb;
             ok = ok && hipMemcpy(to_host ? (void *)(codes + i * hb) : dev, to_host ? dev : (void *)(codes + i * hb), run * hb, kind) == hipSuccess;
+        }
+        if (codes && c->code_layout == 1) {
+            // token-interleaved words: move whole 8-token blocks and pick / patch the nibbles of the requested tokens
+            const int d = c->cfg.head_dim;
+            const int32_t b0 = slot / 8 * 8, b1 = (slot + run + 7) / 8 * 8;
+            std::vector<uint32_t> blk((size_t)(b1 - b0) / 8 * d);
+            void *dev = pv.codes + (rec - slot + b0) * hb;
+            ok = ok && hipMemcpy(blk.data(), dev, blk.size() * 4, hipMemcpyDeviceToHost) == hipSuccess;
+            for (int32_t s = slot; s < slot + run; ++s) {
+                uint32_t *w = blk.data() + (size_t)(s - b0) / 8 * d;
+                const int sh = 4 * code_nibble_pos(s & 7);
+                uint8_t *canon = codes + (i + (s - slot)) * hb;
+                for (int ch = 0; ch < d; ++ch) {
+                    uint32_t &word = w[code_word_index(ch)];
+                    if (to_host) {
+                        const uint8_t nib = (word >> sh) & 0xF;
+                        canon[ch / 2] = (ch & 1) ? (uint8_t)((canon[ch / 2] & 0x0F) | (nib << 4)) : (uint8_t)((canon[ch / 2] & 0xF0) | nib);
+                    } else {
+                        const uint32_t nib = (canon[ch / 2] >> (4 * (ch & 1))) & 0xF;
+                        word = (word & ~(0xFu << sh)) | (nib << sh);
+                    }
+                }
+            }
+            if (!to_host) ok = ok && hipMemcpy(dev, blk.data(), blk.size() * 4, hipMemcpyHostToDevice) == hipSuccess;
         }
         if (scale) {
             void *dev = pv.meta + rec * ng;

@@ -40,7 +40,20 @@ struct PoolView {
     uint32_t *meta;          // [page][H_kv][256][n_g]  low half = fp16 scale, high half = fp16 zero
     int32_t max_pages_per_seq;
     int32_t n_kv_heads, n_q_heads, head_dim, sketch_bits, group_size;
+    int32_t code_layout;     // 0: record-major nibbles; 1: token-interleaved words (see below)
 };
+
+// Code plane layout 1 (used when several query heads share a KV head and the weighted sum runs on the matrix
+// cores): per (page, head) the 256 tokens form 32 blocks of 8 tokens; a block is d 32-bit words, one per
+// channel, each holding the channel's 8 codes.  Token j of the block sits at nibble j/2 (j even) or 4 + j/2
+// (j odd), so that nibbles n and n+4 -- which one AND-OR turns into the two fp16/bf16 halves of a register --
+// are consecutive tokens, i.e. consecutive K indices of an MFMA operand.  Channel c = 16*cb + n is word
+// (cb/4)*64 + n*4 + cb%4: the 16 lanes n of an MFMA column block read 16 bytes each (4 column blocks), contiguously.
+__host__ __device__ inline int code_nibble_pos(int j) { return (j & 1) ? 4 + (j >> 1) : (j >> 1); }
+__host__ __device__ inline int code_word_index(int c) {
+    const int cb = c >> 4, n = c & 15;
+    return (cb >> 2) * 64 + n * 4 + (cb & 3);
+}
 
 struct AppendArgs {
     PoolView pool;
@@ -63,11 +76,24 @@ struct DecodeArgs {
     float exp2_scale;         // 2 log2(e) / (b tau): p = exp2(exp2_scale * (ham_min - ham))
 };
 
+// Query heads one matrix-core decode workgroup serves: the largest divisor of r that is at most 8.
+inline int mfma_heads_per_wg(int r) {
+    for (int q = 8; q > 1; --q)
+        if (r % q == 0) return q;
+    return 1;
+}
+// The matrix-core decode path (and with it code layout 1) is used from 3 query heads per KV head on; it keeps
+// up to 4 groups of scale/zero per token in registers.
+inline bool mfma_decode_supported(int r, int head_dim, int group_size) { return r >= 3 && head_dim / group_size <= 4; }
+// Largest context chunk of one decode workgroup: its softmax weights (heads x chunk floats) live in LDS.
+inline int max_decode_chunk(int r, int code_layout) { return code_layout == 1 && mfma_heads_per_wg(r) > 4 ? kMaxChunk / 2 : kMaxChunk; }
+
 // Launchers (kernels_*.hip).  Each returns hipGetLastError() of its launch.
 hipError_t launch_publish(const TablePairs &pairs, int32_t *block_table, hipStream_t st);
 hipError_t launch_append(const AppendArgs &a, const BatchDesc &desc, int n_seqs, hipStream_t st);
 hipError_t launch_qsketch(const DecodeArgs &a, int seq0, int n_seqs, hipStream_t st);
 hipError_t launch_decode_split(const DecodeArgs &a, const BatchDesc &desc, int seq0, int n_seqs, hipStream_t st);
+hipError_t launch_decode_split_mfma(const DecodeArgs &a, const BatchDesc &desc, int seq0, int n_seqs, hipStream_t st);
 hipError_t launch_merge(const DecodeArgs &a, const BatchDesc &desc, int seq0, int n_seqs, hipStream_t st);
 hipError_t launch_stream_copy(void *dst, const void *src, size_t n_bytes, hipStream_t st);
 hipError_t launch_stream_read(const void *src, size_t n_bytes, void *sink, hipStream_t st);

@@ -1,9 +1,11 @@
 // Cache append: key sketch (Sec. IV-A Eq.(2)) and 4-bit group quantisation of values (Sec. IV-B Eq.(4)),
 // written into the paged planes.
 //
-// Work unit: a workgroup of 4 waves takes kTile consecutive records of one sequence, records ordered
-// head-major (rec = head * n_new + token) so that a tile is a run of consecutive tokens of one head:
-// its outputs are contiguous runs inside a page and its inputs are whole head rows.
+// Work unit: a workgroup of 4 waves takes a tile of consecutive record slots of one sequence.  Slots are ordered
+// head-major and, per head, start at the 8-token boundary at or below the first new position, so that a tile is
+// a run of consecutive tokens of one head (contiguous output runs inside a page, whole head rows as input) and no
+// 8-token block of a head is ever split between two workgroups (the token-interleaved code layout is written
+// per block).  Slots before the first new token or after the last one are padding and are skipped.
 //
 // Sketch: lane i of a wave owns sketch bit (64*word + i): it keeps row R[bit][0..d) in registers and
 // runs the fp32 chain y = fma(R[bit][j], k[j], y), j ascending from +0 -- the order that fixes every
@@ -12,7 +14,11 @@
 //
 // Quantiser: one lane per (record, 32-channel slice): min/max over the slice, combined across the
 // group's lanes with wave shuffles, then zero = fp16(min), scale = fp16((max-min)/15) and
-// code = clamp(rne((v - zero)/scale), 0, 15) with IEEE fp32 subtract and divide; 32 codes = one 16-byte store.
+// code = clamp(rne((v - zero)/scale), 0, 15) with IEEE fp32 subtract and divide.
+// Code plane layouts (PoolView::code_layout):
+//   0  record-major: the 32 codes of a slice are one 16-byte store; byte m of a record = channels 2m (low), 2m+1 (high);
+//   1  token-interleaved: per block of 8 tokens one 32-bit word per channel with that channel's 8 codes
+//      (code_word_index / code_nibble_pos); words of partially filled blocks are read-modified-written.
 #include <hip/hip_fp16.h>
 
 #include "internal.h"
@@ -21,7 +27,7 @@ namespace h1bkv {
 
 namespace {
 
-constexpr int kTile = 64;      // records per workgroup pass
+constexpr int kTile = 64;      // record slots per workgroup pass (a multiple of 8)
 constexpr int kThreads = 256;
 
 __device__ __forceinline__ void load8(const __half *p, float *out) {
@@ -43,37 +49,47 @@ __device__ __forceinline__ void load8(const float *p, float *out) {
 
 template <int D, typename T>
 __global__ __launch_bounds__(kThreads) void append_kernel(AppendArgs a, BatchDesc desc, int tile) {
-    __shared__ float ks[kTile][D];          // fp32 copy of the key tile
-    __shared__ uint64_t words[kTile][8];    // sketch words of the tile (W <= 8)
-    __shared__ size_t dst[kTile];           // destination record index of each tile record
+    __shared__ float ks[kTile][D];                    // fp32 copy of the key tile
+    __shared__ uint64_t words[kTile][8];              // sketch words of the tile (W <= 8)
+    __shared__ size_t dst[kTile];                     // plane index of each slot: (page * H_kv + head) * 256 + slot in page
+    __shared__ uint32_t codes_s[kTile][D / 8 + 1];    // layout 1: codes of the tile in canonical nibble order (+1: bank spread)
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const SeqDesc sd = desc.s[blockIdx.y];
     const PoolView &pv = a.pool;
     const int H = pv.n_kv_heads, W = pv.sketch_bits >> 6, G = pv.group_size, ng = D / G;
     const int n_new = a.n_new;
-    const int n_rec = n_new * H;
+    const int off = sd.pos & 7;                       // slots of a head's first block that lie before the first new token
+    const int L = (off + n_new + 7) & ~7;             // slots per head
+    const int n_slots = L * H;
     const T *kbase = static_cast<const T *>(a.k) + (size_t)blockIdx.y * a.stride_seq;
     const T *vbase = static_cast<const T *>(a.v) + (size_t)blockIdx.y * a.stride_seq;
 
-    for (int rec0 = blockIdx.x * tile; rec0 < n_rec; rec0 += gridDim.x * tile) {
-        const int n_valid = min(tile, n_rec - rec0);
+    for (int slot0 = blockIdx.x * tile; slot0 < n_slots; slot0 += gridDim.x * tile) {
         __syncthreads();   // previous pass is done with the LDS tile
+        // slot -> (head, token); a token < 0 or >= n_new marks padding
+        auto head_of = [&](int rl) { return (slot0 + rl) / L; };
+        auto token_of = [&](int rl) { return (slot0 + rl) % L - off; };
+        auto valid_slot = [&](int rl) {
+            const int t = token_of(rl);
+            return slot0 + rl < n_slots && t >= 0 && t < n_new;
+        };
 
         // ---- stage the key tile as fp32; resolve destinations ----
-        for (int e = tid * 8; e < n_valid * D; e += kThreads * 8) {
+        for (int e = tid * 8; e < tile * D; e += kThreads * 8) {
             const int rl = e / D, ch = e % D;
-            const int rec = rec0 + rl, h = rec / n_new, t = rec - h * n_new;
+            if (!valid_slot(rl)) continue;
             float f[8];
-            load8(kbase + (size_t)t * a.stride_tok + (size_t)h * a.stride_head + ch, f);
+            load8(kbase + (size_t)token_of(rl) * a.stride_tok + (size_t)head_of(rl) * a.stride_head + ch, f);
 #pragma unroll
             for (int i = 0; i < 8; ++i) ks[rl][ch + i] = f[i];
         }
-        if (tid < n_valid) {
-            const int rec = rec0 + tid, h = rec / n_new, t = rec - h * n_new;
-            const int pos = sd.pos + t;
+        if (tid < tile && slot0 + tid < n_slots) {
+            // padding slots too: a block's words start at its first slot.  Every block of a head holds at least
+            // one new token, so its page has been assigned.
+            const int pos = sd.pos + token_of(tid);
             const int page = pv.block_table[(size_t)sd.seq_id * pv.max_pages_per_seq + pos / kPage];
-            dst[tid] = ((size_t)page * H + h) * kPage + (pos % kPage);
+            dst[tid] = ((size_t)page * H + head_of(tid)) * kPage + (pos % kPage);
         }
         __syncthreads();
 
@@ -87,7 +103,8 @@ __global__ __launch_bounds__(kThreads) void append_kernel(AppendArgs a, BatchDes
                 const float4 x = *reinterpret_cast<const float4 *>(row + j);
                 r[j] = x.x; r[j + 1] = x.y; r[j + 2] = x.z; r[j + 3] = x.w;
             }
-            for (int t = wave / wslots; t < n_valid; t += tslots) {
+            for (int t = wave / wslots; t < tile; t += tslots) {
+                if (!valid_slot(t)) continue;          // uniform over the wave
                 float y = 0.0f;
 #pragma unroll
                 for (int j = 0; j < D; j += 4) {
@@ -102,16 +119,15 @@ __global__ __launch_bounds__(kThreads) void append_kernel(AppendArgs a, BatchDes
             }
         }
 
-        // ---- Eq.(4): one lane per (record, 32-channel slice) ----
+        // ---- Eq.(4): one lane per (slot, 32-channel slice) ----
         constexpr int LPT = D / 32;
         const int lanes_per_group = G / 32;
         for (int item = tid; item < ((tile * LPT + 63) & ~63); item += kThreads) {   // whole waves run the loop (shuffles below)
             const int rl = item / LPT, slice = item % LPT;
-            const bool valid = rl < n_valid;
+            const bool valid = rl < tile && valid_slot(rl);
             float x[32];
             if (valid) {
-                const int rec = rec0 + rl, h = rec / n_new, t = rec - h * n_new;
-                const T *src = vbase + (size_t)t * a.stride_tok + (size_t)h * a.stride_head + slice * 32;
+                const T *src = vbase + (size_t)token_of(rl) * a.stride_tok + (size_t)head_of(rl) * a.stride_head + slice * 32;
 #pragma unroll
                 for (int i = 0; i < 32; i += 8) load8(src + i, x + i);
             } else {
@@ -124,9 +140,9 @@ __global__ __launch_bounds__(kThreads) void append_kernel(AppendArgs a, BatchDes
                 mn = fminf(mn, x[i]);
                 mx = fmaxf(mx, x[i]);
             }
-            for (int off = 1; off < lanes_per_group; off <<= 1) {
-                mn = fminf(mn, __shfl_xor(mn, off));
-                mx = fmaxf(mx, __shfl_xor(mx, off));
+            for (int o = 1; o < lanes_per_group; o <<= 1) {
+                mn = fminf(mn, __shfl_xor(mn, o));
+                mx = fmaxf(mx, __shfl_xor(mx, o));
             }
             const float delta = (mx - mn) / 15.0f;
             unsigned short sh = __half_as_ushort(__float2half_rn(delta));
@@ -145,16 +161,41 @@ __global__ __launch_bounds__(kThreads) void append_kernel(AppendArgs a, BatchDes
             }
             if (valid) {
                 const size_t rec = dst[rl];
-                *reinterpret_cast<uint4 *>(pv.codes + rec * (D / 2) + slice * 16) = make_uint4(packed[0], packed[1], packed[2], packed[3]);
+                if (pv.code_layout == 0) {
+                    *reinterpret_cast<uint4 *>(pv.codes + rec * (D / 2) + slice * 16) = make_uint4(packed[0], packed[1], packed[2], packed[3]);
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) codes_s[rl][slice * 4 + i] = packed[i];
+                }
                 if (slice % lanes_per_group == 0) pv.meta[rec * ng + slice / lanes_per_group] = (uint32_t)sh | ((uint32_t)zh << 16);
             }
         }
         __syncthreads();
 
         // ---- store sketch words ----
-        for (int i = tid; i < n_valid * W; i += kThreads) {
+        for (int i = tid; i < tile * W; i += kThreads) {
             const int rl = i / W, w = i - rl * W;
-            pv.sketch[dst[rl] * W + w] = words[rl][w];
+            if (valid_slot(rl)) pv.sketch[dst[rl] * W + w] = words[rl][w];
+        }
+
+        // ---- layout 1: one word per (8-token block, channel) ----
+        if (pv.code_layout == 1) {
+            for (int item = tid; item < (tile / 8) * D; item += kThreads) {
+                const int blk = item / D, c = item % D;
+                uint32_t val = 0, have = 0;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const int rl = blk * 8 + j;
+                    if (!valid_slot(rl)) continue;
+                    const uint32_t nib = (codes_s[rl][c >> 3] >> (4 * (c & 7))) & 0xFu;
+                    val |= nib << (4 * code_nibble_pos(j));
+                    have |= 0xFu << (4 * code_nibble_pos(j));
+                }
+                if (have == 0) continue;
+                // the block's 8 tokens are consecutive slots of one page: its words start at the first slot's record
+                uint32_t *wp = reinterpret_cast<uint32_t *>(pv.codes + dst[blk * 8] * (D / 2)) + code_word_index(c);
+                *wp = have == 0xFFFFFFFFu ? val : ((*wp & ~have) | val);
+            }
         }
     }
 }
@@ -162,12 +203,17 @@ __global__ __launch_bounds__(kThreads) void append_kernel(AppendArgs a, BatchDes
 }  // namespace
 
 hipError_t launch_append(const AppendArgs &a, const BatchDesc &desc, int n_seqs, hipStream_t st) {
-    const long n_rec = (long)a.n_new * a.pool.n_kv_heads;
-    // Records per workgroup pass: a full tile for prefill-sized calls; for a decode step (a handful of records
-    // per sequence) small tiles, so that the few records spread over many compute units.
-    long tile = (n_rec * n_seqs + 255) / 256;
-    tile = tile < 2 ? 2 : (tile > kTile ? kTile : tile);
-    const long tiles = (n_rec + tile - 1) / tile;
+    // Slots per head: the new tokens plus the padding down to / up to 8-token boundaries.
+    int max_off = 0;
+    for (int i = 0; i < n_seqs; ++i) max_off = desc.s[i].pos % 8 > max_off ? desc.s[i].pos % 8 : max_off;
+    const long L = ((long)max_off + a.n_new + 7) / 8 * 8;
+    const long n_slots = L * a.pool.n_kv_heads;
+    // Slots per workgroup pass: a full tile for prefill-sized calls; for a decode step (one block per head) a single
+    // block, so that the few records spread over many compute units.
+    long tile = (n_slots * n_seqs + 255) / 256;
+    tile = (tile + 7) / 8 * 8;
+    tile = tile > kTile ? kTile : tile;
+    const long tiles = (n_slots + tile - 1) / tile;
     // Each workgroup re-reads R once; with many tiles let one workgroup walk several of them.
     const long max_wgs_x = 4096 / n_seqs > 0 ? 4096 / n_seqs : 1;
     const dim3 grid((unsigned)(tiles < max_wgs_x ? tiles : max_wgs_x), (unsigned)n_seqs);

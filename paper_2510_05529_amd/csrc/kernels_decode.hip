@@ -17,74 +17,11 @@
 //            and writes the chunk's partial (min distance, sum p, unnormalised output) to the workspace.
 // merge_kernel: log-sum-exp merge of the chunk partials of one (sequence, query head).
 // qsketch_kernel: s_q = sign(R q) with the same fp32 FMA chain as the keys (lane = bit, ballot = word).
-#include <hip/hip_fp16.h>
-
-#include "internal.h"
+#include "decode_common.h"
 
 namespace h1bkv {
 
 namespace {
-
-constexpr int kThreads = 256;
-constexpr int kWaves = kThreads / 64;
-constexpr int kMaxPagesPerChunk = kMaxChunk / kPage;
-
-__device__ __forceinline__ int wave_min(int x) {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) x = min(x, __shfl_xor(x, off));
-    return x;
-}
-__device__ __forceinline__ float wave_sum(float x) {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off);
-    return x;
-}
-template <int CTRL>
-__device__ __forceinline__ float dpp_mov(float x) {
-    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xF, 0xF, false));
-}
-// Sum, inside each row of 16 lanes, over the lanes that hold the same channel slice (lane % LPT) of different
-// tokens.  DPP row rotations: one VALU instruction per step, no LDS traffic.
-template <int LPT>
-__device__ __forceinline__ float row_slot_sum(float x) {
-    if constexpr (LPT == 2) x += dpp_mov<0x4E>(x);    // quad_perm [2,3,0,1]: lane ^ 2
-    if constexpr (LPT <= 4) x += dpp_mov<0x124>(x);   // row_ror:4
-    x += dpp_mov<0x128>(x);                           // row_ror:8
-    return x;
-}
-// x[lane] + x[lane ^ 32] (gfx950 lane-swap instruction: upper half of one operand <-> lower half of the other).
-__device__ __forceinline__ float half_wave_sum(float x) {
-    const unsigned u = __float_as_uint(x);
-    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
-    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
-}
-
-// (x & mask) | magic in one instruction.
-__device__ __forceinline__ uint32_t and_or(uint32_t x, uint32_t mask, uint32_t magic) {
-    uint32_t r;
-    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(x), "v"(mask), "v"(magic));
-    return r;
-}
-
-template <int W>
-struct SketchRow {
-    uint64_t w[W];
-};
-template <int W>
-__device__ __forceinline__ SketchRow<W> load_sketch(const uint64_t *p) {
-    SketchRow<W> s;
-    if constexpr (W == 1) {
-        s.w[0] = *p;
-    } else {
-#pragma unroll
-        for (int i = 0; i < W; i += 2) {
-            const uint4 v = *reinterpret_cast<const uint4 *>(p + i);
-            s.w[i] = (uint64_t)v.x | ((uint64_t)v.y << 32);
-            s.w[i + 1] = (uint64_t)v.z | ((uint64_t)v.w << 32);
-        }
-    }
-    return s;
-}
 
 template <int LPT>
 struct PageRegs {            // what one lane holds of one page: LPT x (16 B of codes + 4 B of scale/zero)
@@ -135,7 +72,7 @@ __global__ __launch_bounds__(kThreads, RQ >= 4 ? 2 : 1) void decode_split_kernel
     const int slice = lane % LPT;
     const int tok_w = wave * 64 + lane / LPT;              // token (within a page) of this lane's first load
     const int meta_col = (slice * 32) / pv.group_size;
-    const uint32_t mask = 0x00F000F0u, magic = 0x64006400u;
+    const uint32_t mask = opaque_vgpr(0x00F000F0u), magic = opaque_vgpr(0x64006400u);
 
     auto load_page = [&](PageRegs<LPT> &pr, int pg) {
         const size_t base = ((size_t)pages_s[pg] * H + kvh) * kPage;
