@@ -182,7 +182,8 @@ int check_seq_ids(const h1bkv_cache *c, const int32_t *ids, int32_t n) {
 int choose_chunk(const h1bkv_cache *c, int n_seqs, int max_ctx) {
     if (c->chunk_override > 0) return c->chunk_override;
     const int64_t heads = (int64_t)n_seqs * c->cfg.n_kv_heads;
-    const int64_t target_wgs = 4096;
+    // the matrix-core kernel has no per-chunk scoring pass to amortise but gains from long streams per workgroup
+    const int64_t target_wgs = c->code_layout == 1 ? 1536 : 4096;
     int chunk = max_decode_chunk(c->r, c->code_layout);
     while (chunk > kPage && heads * ((max_ctx + chunk - 1) / chunk) < target_wgs) chunk /= 2;
     return chunk;
@@ -232,7 +233,7 @@ int h1bkv_create(const h1bkv_config *cfg, void *pool_dev, size_t pool_bytes, con
     c->W = cfg->sketch_bits / 64;
     c->ng = cfg->head_dim / cfg->group_size;
     c->r = cfg->n_q_heads / cfg->n_kv_heads;
-    c->code_layout = mfma_decode_supported(cfg->n_q_heads / cfg->n_kv_heads, cfg->head_dim, cfg->group_size) ? 1 : 0;
+    c->code_layout = mfma_decode_supported(cfg->n_q_heads / cfg->n_kv_heads, cfg->head_dim, cfg->group_size, cfg->sketch_bits) ? 1 : 0;
     c->dry = dry;
     c->pool = static_cast<char *>(pool_dev);
     const size_t nR = (size_t)cfg->sketch_bits * cfg->head_dim;

@@ -82,11 +82,13 @@ inline int mfma_heads_per_wg(int r) {
         if (r % q == 0) return q;
     return 1;
 }
-// The matrix-core decode path (and with it code layout 1) is used from 3 query heads per KV head on; it keeps
-// up to 4 groups of scale/zero per token in registers.
-inline bool mfma_decode_supported(int r, int head_dim, int group_size) { return r >= 3 && head_dim / group_size <= 4; }
-// Largest context chunk of one decode workgroup: its softmax weights (heads x chunk floats) live in LDS.
-inline int max_decode_chunk(int r, int code_layout) { return code_layout == 1 && mfma_heads_per_wg(r) > 4 ? kMaxChunk / 2 : kMaxChunk; }
+// The matrix-core decode path (and with it code layout 1) is used from 3 query heads per KV head on, for the
+// geometries its kernel keeps in registers: head_dim 64 or 128, sketches of up to 256 bits, up to 4 groups.
+inline bool mfma_decode_supported(int r, int head_dim, int group_size, int sketch_bits) {
+    return r >= 3 && head_dim <= 128 && head_dim / group_size <= 4 && sketch_bits <= 256;
+}
+// Largest context chunk of one decode workgroup.
+inline int max_decode_chunk(int, int) { return kMaxChunk; }
 
 // Launchers (kernels_*.hip).  Each returns hipGetLastError() of its launch.
 hipError_t launch_publish(const TablePairs &pairs, int32_t *block_table, hipStream_t st);
