@@ -139,7 +139,7 @@ int h1bkv_decode_attn(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n_seq
 
 /*
  * Tuning override for the context chunk of h1bkv_decode_attn: tokens per chunk, a multiple of
- * H1BKV_PAGE_TOKENS up to 2048, or 0 for the built-in choice.  Results do not depend on it beyond
+ * H1BKV_PAGE_TOKENS up to 8192, or 0 for the built-in choice.  Results do not depend on it beyond
  * fp32 summation order.
  */
 int h1bkv_set_decode_chunk(h1bkv_cache *c, int32_t chunk_tokens);

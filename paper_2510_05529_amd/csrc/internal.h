@@ -10,7 +10,7 @@ namespace h1bkv {
 
 constexpr int kPage = H1BKV_PAGE_TOKENS;   // tokens per page
 constexpr int kMaxSeqsPerLaunch = 128;     // sequences described by one kernel-argument block
-constexpr int kMaxChunk = 2048;            // largest context chunk one decode workgroup handles
+constexpr int kMaxChunk = 8192;            // largest context chunk one decode workgroup handles
 constexpr int kPublishPairs = 240;         // block-table updates carried by one publish launch
 
 // Per-launch sequence descriptors travel as a kernel argument (no host->device copy, nothing to keep

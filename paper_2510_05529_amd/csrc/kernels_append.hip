@@ -9,8 +9,10 @@
 //
 // Sketch: lane i of a wave owns sketch bit (64*word + i): it keeps row R[bit][0..d) in registers and
 // runs the fp32 chain y = fma(R[bit][j], k[j], y), j ascending from +0 -- the order that fixes every
-// bit -- with k[j] broadcast from an fp32 copy of the tile in LDS.  The 64-lane ballot of (y >= 0) IS the
-// packed sketch word (bit i of the word = lane i), so packing costs nothing.
+// bit -- with k[j] broadcast from the tile in LDS.  fp16 keys stay fp16 there: the widening to fp32 is exact and
+// rides on the FMA (mixed-precision FMA with an fp16 operand), which halves the LDS bytes per multiply-add -- the
+// broadcast reads, not the ALUs, are what this loop saturates first.  The 64-lane ballot of (y >= 0) IS the packed
+// sketch word (bit i of the word = lane i), so packing costs nothing.
 //
 // Quantiser: one lane per (record, 32-channel slice): min/max over the slice, combined across the
 // group's lanes with wave shuffles, then zero = fp16(min), scale = fp16((max-min)/15) and
@@ -29,6 +31,7 @@ namespace {
 
 constexpr int kTile = 64;      // record slots per workgroup pass (a multiple of 8)
 constexpr int kThreads = 256;
+constexpr size_t kNoRow = ~(size_t)0;
 
 __device__ __forceinline__ void load8(const __half *p, float *out) {
     const uint4 raw = *reinterpret_cast<const uint4 *>(p);
@@ -47,11 +50,18 @@ __device__ __forceinline__ void load8(const float *p, float *out) {
     out[4] = b.x; out[5] = b.y; out[6] = b.z; out[7] = b.w;
 }
 
+__device__ __forceinline__ void copy8(const __half *src, __half *dst) { *reinterpret_cast<uint4 *>(dst) = *reinterpret_cast<const uint4 *>(src); }
+__device__ __forceinline__ void copy8(const float *src, float *dst) {
+    *reinterpret_cast<float4 *>(dst) = *reinterpret_cast<const float4 *>(src);
+    *reinterpret_cast<float4 *>(dst + 4) = *reinterpret_cast<const float4 *>(src + 4);
+}
+
 template <int D, typename T>
 __global__ __launch_bounds__(kThreads) void append_kernel(AppendArgs a, BatchDesc desc, int tile) {
-    __shared__ float ks[kTile][D];                    // fp32 copy of the key tile
+    __shared__ __attribute__((aligned(16))) T ks[kTile][D];   // the key tile in its boundary dtype
     __shared__ uint64_t words[kTile][8];              // sketch words of the tile (W <= 8)
     __shared__ size_t dst[kTile];                     // plane index of each slot: (page * H_kv + head) * 256 + slot in page
+    __shared__ size_t src_off[kTile];                 // element offset of each slot's K / V row; kNoRow marks padding
     __shared__ uint32_t codes_s[kTile][D / 8 + 1];    // layout 1: codes of the tile in canonical nibble order (+1: bank spread)
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -59,60 +69,68 @@ __global__ __launch_bounds__(kThreads) void append_kernel(AppendArgs a, BatchDes
     const PoolView &pv = a.pool;
     const int H = pv.n_kv_heads, W = pv.sketch_bits >> 6, G = pv.group_size, ng = D / G;
     const int n_new = a.n_new;
-    const int off = sd.pos & 7;                       // slots of a head's first block that lie before the first new token
-    const int L = (off + n_new + 7) & ~7;             // slots per head
+    const int off8 = sd.pos & 7;                      // slots of a head's first block that lie before the first new token
+    const int L = (off8 + n_new + 7) & ~7;            // slots per head
     const int n_slots = L * H;
     const T *kbase = static_cast<const T *>(a.k) + (size_t)blockIdx.y * a.stride_seq;
     const T *vbase = static_cast<const T *>(a.v) + (size_t)blockIdx.y * a.stride_seq;
 
+    // Row R[64 word + lane][0..d) of this lane's sketch bit lives in registers across all tiles of the workgroup.
+    const int wslots = W < 4 ? W : 4, tslots = 4 / wslots;
+    float r[D];
+    int r_word = wave % wslots;
+    auto load_row = [&](int word) {
+        const float *row = pv.R + (size_t)(word * 64 + lane) * D;
+#pragma unroll
+        for (int j = 0; j < D; j += 4) {
+            const float4 x = *reinterpret_cast<const float4 *>(row + j);
+            r[j] = x.x; r[j + 1] = x.y; r[j + 2] = x.z; r[j + 3] = x.w;
+        }
+    };
+    load_row(r_word);
+
     for (int slot0 = blockIdx.x * tile; slot0 < n_slots; slot0 += gridDim.x * tile) {
         __syncthreads();   // previous pass is done with the LDS tile
-        // slot -> (head, token); a token < 0 or >= n_new marks padding
-        auto head_of = [&](int rl) { return (slot0 + rl) / L; };
-        auto token_of = [&](int rl) { return (slot0 + rl) % L - off; };
-        auto valid_slot = [&](int rl) {
-            const int t = token_of(rl);
-            return slot0 + rl < n_slots && t >= 0 && t < n_new;
-        };
+        // ---- resolve the tile once: slot -> (head, token) -> source row, destination record ----
+        // (the divisions by the runtime slot count per head are done here, by one thread per slot, not in the loops)
+        if (tid < tile) {
+            size_t off = kNoRow;
+            if (slot0 + tid < n_slots) {
+                const int head = (slot0 + tid) / L, t = (slot0 + tid) % L - off8;
+                // padding slots too: a block's words start at its first slot.  Every block of a head holds at
+                // least one new token, so its page has been assigned.
+                const int pos = sd.pos + t;
+                const int page = pv.block_table[(size_t)sd.seq_id * pv.max_pages_per_seq + pos / kPage];
+                dst[tid] = ((size_t)page * H + head) * kPage + (pos % kPage);
+                if (t >= 0 && t < n_new) off = (size_t)t * a.stride_tok + (size_t)head * a.stride_head;
+            }
+            src_off[tid] = off;
+        }
+        __syncthreads();
+        auto valid_slot = [&](int rl) { return src_off[rl] != kNoRow; };
 
-        // ---- stage the key tile as fp32; resolve destinations ----
+        // ---- stage the key tile ----
         for (int e = tid * 8; e < tile * D; e += kThreads * 8) {
             const int rl = e / D, ch = e % D;
-            if (!valid_slot(rl)) continue;
-            float f[8];
-            load8(kbase + (size_t)token_of(rl) * a.stride_tok + (size_t)head_of(rl) * a.stride_head + ch, f);
-#pragma unroll
-            for (int i = 0; i < 8; ++i) ks[rl][ch + i] = f[i];
-        }
-        if (tid < tile && slot0 + tid < n_slots) {
-            // padding slots too: a block's words start at its first slot.  Every block of a head holds at least
-            // one new token, so its page has been assigned.
-            const int pos = sd.pos + token_of(tid);
-            const int page = pv.block_table[(size_t)sd.seq_id * pv.max_pages_per_seq + pos / kPage];
-            dst[tid] = ((size_t)page * H + head_of(tid)) * kPage + (pos % kPage);
+            if (valid_slot(rl)) copy8(kbase + src_off[rl] + ch, &ks[rl][ch]);
         }
         __syncthreads();
 
         // ---- Eq.(2): lane = sketch bit; y = fma chain over j; ballot = packed word ----
-        const int wslots = W < 4 ? W : 4, tslots = 4 / wslots;
         for (int word = wave % wslots; word < W; word += wslots) {
-            float r[D];
-            const float *row = pv.R + (size_t)(word * 64 + lane) * D;
-#pragma unroll
-            for (int j = 0; j < D; j += 4) {
-                const float4 x = *reinterpret_cast<const float4 *>(row + j);
-                r[j] = x.x; r[j + 1] = x.y; r[j + 2] = x.z; r[j + 3] = x.w;
+            if (word != r_word) {                      // only when a wave owns more than one word (b = 512)
+                load_row(word);
+                r_word = word;
             }
             for (int t = wave / wslots; t < tile; t += tslots) {
                 if (!valid_slot(t)) continue;          // uniform over the wave
                 float y = 0.0f;
 #pragma unroll
-                for (int j = 0; j < D; j += 4) {
-                    const float4 kk = *reinterpret_cast<const float4 *>(&ks[t][j]);
-                    y = __builtin_fmaf(r[j], kk.x, y);
-                    y = __builtin_fmaf(r[j + 1], kk.y, y);
-                    y = __builtin_fmaf(r[j + 2], kk.z, y);
-                    y = __builtin_fmaf(r[j + 3], kk.w, y);
+                for (int j = 0; j < D; j += 8) {
+                    float kk[8];
+                    load8(&ks[t][j], kk);              // same address in every lane: an LDS broadcast
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) y = __builtin_fmaf(r[j + i], kk[i], y);
                 }
                 const uint64_t mask = __ballot(y >= 0.0f);
                 if (lane == 0) words[t][word] = mask;
@@ -127,7 +145,7 @@ __global__ __launch_bounds__(kThreads) void append_kernel(AppendArgs a, BatchDes
             const bool valid = rl < tile && valid_slot(rl);
             float x[32];
             if (valid) {
-                const T *src = vbase + (size_t)token_of(rl) * a.stride_tok + (size_t)head_of(rl) * a.stride_head + slice * 32;
+                const T *src = vbase + src_off[rl] + slice * 32;
 #pragma unroll
                 for (int i = 0; i < 32; i += 8) load8(src + i, x + i);
             } else {
@@ -214,8 +232,9 @@ hipError_t launch_append(const AppendArgs &a, const BatchDesc &desc, int n_seqs,
     tile = (tile + 7) / 8 * 8;
     tile = tile > kTile ? kTile : tile;
     const long tiles = (n_slots + tile - 1) / tile;
-    // Each workgroup re-reads R once; with many tiles let one workgroup walk several of them.
-    const long max_wgs_x = 4096 / n_seqs > 0 ? 4096 / n_seqs : 1;
+    // Each workgroup reads its rows of R once and keeps them in registers: with many tiles, a few resident
+    // workgroups per compute unit walk all of them.
+    const long max_wgs_x = 1024 / n_seqs > 0 ? 1024 / n_seqs : 1;
     const dim3 grid((unsigned)(tiles < max_wgs_x ? tiles : max_wgs_x), (unsigned)n_seqs);
     const int D = a.pool.head_dim;
 #define H1BKV_LAUNCH(DD, TT) hipLaunchKernelGGL((append_kernel<DD, TT>), grid, dim3(kThreads), 0, st, a, desc, (int)tile)

@@ -1,20 +1,21 @@
 // Decode-step attention over the compressed cache (Sec. IV-A Eq.(3), Sec. IV-C Eq.(5)).
 //
-// decode_split_kernel: one workgroup (4 waves) per (context chunk, KV head [x query-head pass], sequence).
-//   Phase A  thread = token: stream the chunk's packed sketches (16 B/lane at b = 128), Hamming distance
-//            by XOR + popcount against the RQ query sketches that share this KV head, block-wide minimum
-//            distance (= maximum score alpha), then p_t = exp((alpha_t - alpha_max)/tau) into LDS and sum p.
-//            Scores only take b+1 values and alpha_max is known before any value byte is touched, so the
-//            accumulators are never rescaled.
-//   Phase B  lane = (token, 32-channel slice): each lane reads one aligned 16-byte run of nibbles (exactly
+// decode_split_kernel: one workgroup (4 waves) per (context chunk, KV head [x query-head pass], sequence); every
+//   wave streams on its own over its 64 tokens of each page of the chunk, with no workgroup barrier until the end.
+//   Scoring role  lane = token: packed sketch (16 B/lane at b = 128), Hamming distance by XOR + popcount against the
+//            RQ query sketches that share this KV head, wave-wide minimum (= maximum score alpha) by DPP.  The wave
+//            keeps a running maximum per head; when a page raises it the accumulators are rescaled (scores only
+//            take b+1 values, so this happens a handful of times per chunk).  p_t = exp((alpha_t - alpha_max)/tau).
+//   Value role    lane = (token, 32-channel slice): each lane reads one aligned 16-byte run of nibbles (exactly
 //            32 codes) and the 4-byte {scale, zero} pair of its group, so a wave instruction covers 1 KiB of
-//            contiguous codes.  Dequantisation is folded into the weights:
-//              sum_t p_t (scale_t code_tc + zero_t) = sum_t (p_t scale_t) code_tc + sum_t p_t zero_t,
+//            contiguous codes; p_t comes from the scoring lane by a lane permute.  Dequantisation is folded into
+//            the weights:  sum_t p_t (scale_t code_tc + zero_t) = sum_t (p_t scale_t) code_tc + sum_t p_t zero_t,
 //            and the int4 -> float step rides on the FMA itself (nibbles OR-ed into the mantissa of an fp16
 //            constant, read by a mixed-precision FMA): 15 VALU instructions per 8 elements.
-//            Loads for the next page are in flight while the current page is consumed.
-//   Epilogue sums over the token slots of a 16-lane row with DPP rotations, over rows and waves through LDS,
-//            and writes the chunk's partial (min distance, sum p, unnormalised output) to the workspace.
+//            Loads for the next page (sketches, codes, scale/zero) are in flight while the current page is consumed.
+//   Epilogue sums over the token slots of a 16-lane row with DPP rotations, over rows and waves through LDS (each
+//            wave's part scaled to the common maximum), and writes the chunk's partial (min distance, sum p,
+//            unnormalised output) to the workspace.
 // merge_kernel: log-sum-exp merge of the chunk partials of one (sequence, query head).
 // qsketch_kernel: s_q = sign(R q) with the same fp32 FMA chain as the keys (lane = bit, ballot = word).
 #include "decode_common.h"
@@ -23,26 +24,34 @@ namespace h1bkv {
 
 namespace {
 
-template <int LPT>
-struct PageRegs {            // what one lane holds of one page: LPT x (16 B of codes + 4 B of scale/zero)
-    uint4 c[LPT];
-    uint32_t m[LPT];
+template <int W, int LPT>
+struct PageRegs {            // what one lane holds of its wave's 64 tokens of one page
+    SketchRow<W> sk;         // sketch of token `lane` (scoring role)
+    uint4 c[LPT];            // LPT x 16 B of codes and
+    uint32_t m[LPT];         //       4 B of scale/zero of token it * TPW + lane / LPT, slice lane % LPT (value role)
 };
+
+// Minimum over the wave, result in every lane: DPP inside the 16-lane rows, two lane exchanges across them.
+__device__ __forceinline__ int wave_min_dpp(int x) {
+    x = min(x, __builtin_amdgcn_update_dpp(0, x, 0xB1, 0xF, 0xF, false));    // quad_perm [1,0,3,2]
+    x = min(x, __builtin_amdgcn_update_dpp(0, x, 0x4E, 0xF, 0xF, false));    // quad_perm [2,3,0,1]
+    x = min(x, __builtin_amdgcn_update_dpp(0, x, 0x124, 0xF, 0xF, false));   // row_ror:4
+    x = min(x, __builtin_amdgcn_update_dpp(0, x, 0x128, 0xF, 0xF, false));   // row_ror:8
+    x = min(x, __shfl_xor(x, 16));
+    return min(x, __shfl_xor(x, 32));
+}
 
 template <int RQ, int W, int LPT>
 __global__ __launch_bounds__(kThreads, RQ >= 4 ? 2 : 1) void decode_split_kernel(DecodeArgs a, BatchDesc desc, int seq0) {
     constexpr int D = 32 * LPT;
-    constexpr int TPW = 64 / LPT;                 // tokens covered by one wave-wide load
+    constexpr int TPW = 64 / LPT;                 // tokens covered by one wave-wide load of codes
     constexpr int ROWS = LPT == 8 ? 2 : 4;        // 16-lane rows of a wave that reach the LDS stage of the epilogue
     constexpr int NPART = kWaves * ROWS;
     constexpr int EPI_STRIDE = D + 2 * LPT;       // per (partial, q): D sums, LPT zero-sums, LPT weight-sums
-    constexpr int P_FLOATS = RQ * kMaxChunk, EPI_FLOATS = NPART * RQ * EPI_STRIDE;
-    // p_t of the chunk during phases A/B; reused for the partial sums of the epilogue.
-    __shared__ float smem[P_FLOATS > EPI_FLOATS ? P_FLOATS : EPI_FLOATS];
+    __shared__ float epi[NPART * RQ * EPI_STRIDE];
     __shared__ int pages_s[kMaxPagesPerChunk];
-    __shared__ int red_i[RQ][kWaves];
-    __shared__ float red_f[RQ][kWaves];
-    float(*p_s)[kMaxChunk] = reinterpret_cast<float(*)[kMaxChunk]>(smem);
+    __shared__ int m_s[kWaves][RQ];
+    __shared__ float l_s[kWaves][RQ];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const SeqDesc sd = desc.s[blockIdx.z];
@@ -69,114 +78,78 @@ __global__ __launch_bounds__(kThreads, RQ >= 4 ? 2 : 1) void decode_split_kernel
         for (int w = 0; w < W; ++w) sq[q][w] = a.q_sketch[((size_t)seq_g * pv.n_q_heads + qh0 + q) * W + w];
     __syncthreads();
 
+    // Every wave streams on its own: it owns tokens [64 wave, 64 wave + 64) of each page of the chunk.
     const int slice = lane % LPT;
-    const int tok_w = wave * 64 + lane / LPT;              // token (within a page) of this lane's first load
+    const int tok_v = lane / LPT;                          // value role: token (within a 64-token share) of the first load
     const int meta_col = (slice * 32) / pv.group_size;
     const uint32_t mask = opaque_vgpr(0x00F000F0u), magic = opaque_vgpr(0x64006400u);
 
-    auto load_page = [&](PageRegs<LPT> &pr, int pg) {
-        const size_t base = ((size_t)pages_s[pg] * H + kvh) * kPage;
-        const uint4 *cp = reinterpret_cast<const uint4 *>(pv.codes) + (base * LPT + wave * 64 * LPT + lane);
+    float acc[RQ][32];
+    float zs[RQ], wsum[RQ], lsum[RQ];
+    int run_min[RQ];
+#pragma unroll
+    for (int q = 0; q < RQ; ++q) {
+        zs[q] = 0.0f;
+        wsum[q] = 0.0f;
+        lsum[q] = 0.0f;
+        run_min[q] = 1 << 20;
+#pragma unroll
+        for (int i = 0; i < 32; ++i) acc[q][i] = 0.0f;
+    }
+
+    auto load_page = [&](PageRegs<W, LPT> &pr, int pg) {
+        const size_t base = ((size_t)pages_s[pg] * H + kvh) * kPage + wave * 64;
+        pr.sk = load_sketch<W>(pv.sketch + (base + lane) * W);
+        const uint4 *cp = reinterpret_cast<const uint4 *>(pv.codes) + (base * LPT + lane);
 #pragma unroll
         for (int it = 0; it < LPT; ++it) {
             pr.c[it] = cp[it * 64];
-            pr.m[it] = pv.meta[(base + tok_w + it * TPW) * ng + meta_col];
+            pr.m[it] = pv.meta[(base + tok_v + it * TPW) * ng + meta_col];
         }
     };
-    // With 4 query heads per lane the 128 accumulators leave no room for a second page buffer: those variants run
-    // single-buffered at 2 waves per SIMD and rely on the other resident waves to cover the load latency.
-    constexpr bool kDoubleBuffer = RQ < 4;
-    PageRegs<LPT> A;
-    [[maybe_unused]] PageRegs<LPT> B;
 
-    // ---------------- Phase A: scores ----------------
-    int ham[RQ][kMaxPagesPerChunk];
-    int hmin[RQ];
-#pragma unroll
-    for (int q = 0; q < RQ; ++q) hmin[q] = 1 << 20;
-    {
-        SketchRow<W> s[kMaxPagesPerChunk];
-#pragma unroll
-        for (int k = 0; k < kMaxPagesPerChunk; ++k)
-            if (k < n_pages) s[k] = load_sketch<W>(pv.sketch + (((size_t)pages_s[k] * H + kvh) * kPage + tid) * W);
-        // The first page of values is requested right behind the sketches, before any score is computed, so
-        // that its latency is covered by phase A instead of being paid after it.
-        load_page(A, 0);
-#pragma unroll
-        for (int k = 0; k < kMaxPagesPerChunk; ++k) {
-            if (k < n_pages) {
-                const bool valid = k * kPage + tid < n_tok;
-#pragma unroll
-                for (int q = 0; q < RQ; ++q) {
-                    int h = 0;
-#pragma unroll
-                    for (int w = 0; w < W; ++w) h += __popcll(sq[q][w] ^ s[k].w[w]);
-                    ham[q][k] = h;
-                    if (valid) hmin[q] = min(hmin[q], h);
-                }
-            }
-        }
-    }
-#pragma unroll
-    for (int q = 0; q < RQ; ++q) {
-        const int m = wave_min(hmin[q]);
-        if (lane == 0) red_i[q][wave] = m;
-    }
-    __syncthreads();
-    float lsum[RQ];
-#pragma unroll
-    for (int q = 0; q < RQ; ++q) {
-        hmin[q] = min(min(red_i[q][0], red_i[q][1]), min(red_i[q][2], red_i[q][3]));
-        lsum[q] = 0.0f;
-    }
-#pragma unroll
-    for (int k = 0; k < kMaxPagesPerChunk; ++k) {
-        if (k < n_pages) {
-            const bool valid = k * kPage + tid < n_tok;
-#pragma unroll
-            for (int q = 0; q < RQ; ++q) {
-                const float p = valid ? exp2f(a.exp2_scale * (float)(hmin[q] - ham[q][k])) : 0.0f;
-                p_s[q][k * kPage + tid] = p;
-                lsum[q] += p;
-            }
-        }
-    }
-#pragma unroll
-    for (int q = 0; q < RQ; ++q) {
-        const float l = wave_sum(lsum[q]);
-        if (lane == 0) red_f[q][wave] = l;
-    }
-    __syncthreads();
-
-    // ---------------- Phase B: weighted sum of dequantised values ----------------
     // A nibble is turned into an fp16 number without a convert instruction: shifted to mantissa bits 4-7 of
     // 1024.0 (0x6400) and OR-ed in, it reads as 1024 + 16 code, two nibbles (n and n+4 of a dword) per 32-bit
     // operation; the fp32 FMA takes the fp16 halves directly (mixed-precision FMA) with weight p scale / 16.
     // The constant part, 64 times the running sum of weights, is taken off at the end.  (Leaving even nibbles
     // at bits 0-3 would save two shifts per dword but puts a 1024-fold offset under the fp32 accumulation.)
-    float acc[RQ][32];
-    float zs[RQ], wsum[RQ];
+    auto consume_page = [&](const PageRegs<W, LPT> &pr, int pg) {
+        // ---- scoring role: lane = token (Eq. 3), running maximum per query head ----
+        const bool valid = pg * kPage + wave * 64 + lane < n_tok;
+        float p[RQ];
 #pragma unroll
-    for (int q = 0; q < RQ; ++q) {
-        zs[q] = 0.0f;
-        wsum[q] = 0.0f;
+        for (int q = 0; q < RQ; ++q) {
+            int h = 0;
 #pragma unroll
-        for (int i = 0; i < 32; ++i) acc[q][i] = 0.0f;
-    }
-    auto consume_page = [&](const PageRegs<LPT> &pr, int pg) {
+            for (int w = 0; w < W; ++w) h += __popcll(sq[q][w] ^ pr.sk.w[w]);
+            const int pmin = wave_min_dpp(valid ? h : (1 << 20));
+            if (pmin < run_min[q]) {                       // uniform over the wave; rare after the first pages
+                const float f = exp2f(a.exp2_scale * (float)(pmin - run_min[q]));   // 0 while nothing has been accumulated
+                run_min[q] = pmin;
+                lsum[q] *= f;
+                zs[q] *= f;
+                wsum[q] *= f;
+#pragma unroll
+                for (int i = 0; i < 32; ++i) acc[q][i] *= f;
+            }
+            p[q] = valid ? exp2f(a.exp2_scale * (float)(run_min[q] - h)) : 0.0f;
+            lsum[q] += p[q];
+        }
+        // ---- value role: lane = (token, 32-channel slice) ----
 #pragma unroll
         for (int it = 0; it < LPT; ++it) {
-            const int idx = pg * kPage + tok_w + it * TPW;
-            const uint32_t m = idx < n_tok ? pr.m[it] : 0u;    // never let an unwritten slot's bits reach the FMAs
+            const int src_lane = it * TPW + tok_v;         // the lane that scored this lane's token
+            const bool vvalid = pg * kPage + wave * 64 + src_lane < n_tok;
+            const uint32_t m = vvalid ? pr.m[it] : 0u;     // never let an unwritten slot's bits reach the FMAs
             const float sc = __half2float(__ushort_as_half((unsigned short)(m & 0xFFFFu)));
             const float zp = __half2float(__ushort_as_half((unsigned short)(m >> 16)));
             float w16[RQ];
 #pragma unroll
             for (int q = 0; q < RQ; ++q) {
-                const float p = p_s[q][idx];
-                const float w = p * sc;
+                const float pt = __shfl(p[q], src_lane);
+                const float w = pt * sc;
                 w16[q] = w * 0.0625f;
-                zs[q] = fmaf(p, zp, zs[q]);
+                zs[q] = fmaf(pt, zp, zs[q]);
                 wsum[q] += w;
             }
             const uint32_t x[4] = {pr.c[it].x, pr.c[it].y, pr.c[it].z, pr.c[it].w};
@@ -198,6 +171,12 @@ __global__ __launch_bounds__(kThreads, RQ >= 4 ? 2 : 1) void decode_split_kernel
         }
     };
 
+    // With 4 query heads per lane the 128 accumulators leave no room for a second page buffer: those variants run
+    // single-buffered at 2 waves per SIMD and rely on the other resident waves to cover the load latency.
+    constexpr bool kDoubleBuffer = RQ < 4;
+    PageRegs<W, LPT> A;
+    [[maybe_unused]] PageRegs<W, LPT> B;
+    load_page(A, 0);
     if constexpr (kDoubleBuffer) {
         int pg = 0;
         while (true) {
@@ -215,7 +194,7 @@ __global__ __launch_bounds__(kThreads, RQ >= 4 ? 2 : 1) void decode_split_kernel
         }
     }
 
-    // ---------------- Epilogue ----------------
+    // ---------------- Epilogue: the four waves meet ----------------
     // Token slots of a 16-lane row are summed with DPP rotations; rows and waves meet in LDS.
 #pragma unroll
     for (int q = 0; q < RQ; ++q) {
@@ -230,9 +209,8 @@ __global__ __launch_bounds__(kThreads, RQ >= 4 ? 2 : 1) void decode_split_kernel
             zs[q] = half_wave_sum(zs[q]);
             wsum[q] = half_wave_sum(wsum[q]);
         }
+        lsum[q] = wave_sum(lsum[q]);
     }
-    __syncthreads();                                   // every wave is done reading p_s
-    float *epi = smem;
     const int row = lane >> 4;
     if ((lane & 15) < LPT && row < ROWS) {
 #pragma unroll
@@ -245,24 +223,41 @@ __global__ __launch_bounds__(kThreads, RQ >= 4 ? 2 : 1) void decode_split_kernel
             dst[D + LPT + slice] = wsum[q];
         }
     }
+    if (lane == 0) {
+#pragma unroll
+        for (int q = 0; q < RQ; ++q) {
+            m_s[wave][q] = run_min[q];
+            l_s[wave][q] = lsum[q];
+        }
+    }
     __syncthreads();
     const size_t part = ((size_t)seq_g * pv.n_q_heads + qh0) * a.n_splits + blockIdx.x;
     for (int e = tid; e < RQ * D; e += kThreads) {
         const int q = e / D, c = e % D;
-        float o = 0.0f, z = 0.0f, ws = 0.0f;
+        int hm = 1 << 20;
 #pragma unroll
-        for (int pt = 0; pt < NPART; ++pt) {
-            const float *src = epi + ((size_t)pt * RQ + q) * EPI_STRIDE;
-            o += src[c];
-            z += src[D + c / 32];
-            ws += src[D + LPT + c / 32];
+        for (int w = 0; w < kWaves; ++w) hm = min(hm, m_s[w][q]);
+        float o = 0.0f, l = 0.0f;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) {
+            const float f = exp2f(a.exp2_scale * (float)(hm - m_s[w][q]));      // 0 for a wave that saw no valid token
+            float ow = 0.0f, z = 0.0f, ws = 0.0f;
+#pragma unroll
+            for (int rw = 0; rw < ROWS; ++rw) {
+                const float *src = epi + ((size_t)(w * ROWS + rw) * RQ + q) * EPI_STRIDE;
+                ow += src[c];
+                z += src[D + c / 32];
+                ws += src[D + LPT + c / 32];
+            }
+            o = fmaf(f, fmaf(-64.0f, ws, ow) + z, o);      // (1024 + 16 code) / 16 = 64 + code
+            l = fmaf(f, l_s[w][q], l);
         }
-        a.part_o[(part + (size_t)q * a.n_splits) * D + c] = fmaf(-64.0f, ws, o) + z;   // (1024 + 16 code) / 16 = 64 + code
-    }
-    if (tid < RQ) {
-        float *ml = a.part_ml + (part + (size_t)tid * a.n_splits) * 2;
-        ml[0] = __int_as_float(hmin[tid]);
-        ml[1] = red_f[tid][0] + red_f[tid][1] + red_f[tid][2] + red_f[tid][3];
+        a.part_o[(part + (size_t)q * a.n_splits) * D + c] = o;
+        if (c == 0) {
+            float *ml = a.part_ml + (part + (size_t)q * a.n_splits) * 2;
+            ml[0] = __int_as_float(hm);
+            ml[1] = l;
+        }
     }
 }
 

@@ -87,7 +87,7 @@ def test_split_count_does_not_change_the_result():
     cache.append(seqs, to_dev(wl.kv_slab(w, "k", seqs, 0, w.context)), to_dev(wl.kv_slab(w, "v", seqs, 0, w.context)))
     q = to_dev(wl.queries(w))
     outs = []
-    for chunk in (256, 512, 1024, 2048, 0):
+    for chunk in (256, 512, 1024, 2048, 8192, 0):
         assert B.h1bkv_set_decode_chunk(cache.h, chunk) == B.H1BKV_OK
         outs.append(cache.decode(seqs, q, w.default_tau()).cpu().numpy())
     for o in outs[1:]:

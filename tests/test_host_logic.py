@@ -132,7 +132,7 @@ def test_decode_argument_errors_and_workspace_size():
 def test_misc_errors():
     c, h, _ = make()
     assert B.h1bkv_set_decode_chunk(h, 100) == B.H1BKV_EINVAL
-    assert B.h1bkv_set_decode_chunk(h, 4096) == B.H1BKV_EINVAL
+    assert B.h1bkv_set_decode_chunk(h, 16384) == B.H1BKV_EINVAL
     assert B.h1bkv_set_decode_chunk(h, 512) == B.H1BKV_OK and B.h1bkv_set_decode_chunk(h, 0) == B.H1BKV_OK
     assert B.h1bkv_export_tokens(h, 0, 0, 0, 1, 2, 128, 4)[0] == B.H1BKV_ERANGE      # nothing cached yet
     assert B.h1bkv_append_kv(h, [0], 5, None, None, 0, 512, 128) == B.H1BKV_OK
