@@ -305,19 +305,24 @@ __global__ __launch_bounds__(kMergeThreads) void merge_kernel(DecodeArgs a, Batc
     }
 }
 
-// One wave per (query vector, sketch word): lane = bit.
-template <typename T>
+// One wave per (query vector, sketch word): lane = bit.  All d loads of the lane's column of R^T are issued before
+// the FMA chain starts (the chain itself must stay sequential: its order fixes the bits), so the kernel costs
+// one memory round trip, not d of them.
+template <typename T, int D>
 __global__ void qsketch_kernel(DecodeArgs a, int seq0) {
-    __shared__ float qs[256];
-    const int D = a.pool.head_dim, b = a.pool.sketch_bits, W = b >> 6;
+    __shared__ float qs[D];
+    const int b = a.pool.sketch_bits, W = b >> 6;
     const size_t vec = (size_t)seq0 * a.pool.n_q_heads + blockIdx.x;
     const T *q = static_cast<const T *>(a.q) + vec * D;
+    const int bit = threadIdx.x;
+    float rt[D];
+#pragma unroll
+    for (int j = 0; j < D; ++j) rt[j] = a.pool.RT[(size_t)j * b + bit];
     for (int j = threadIdx.x; j < D; j += blockDim.x) qs[j] = (float)q[j];
     __syncthreads();
-    const int bit = threadIdx.x;
     float y = 0.0f;
-#pragma unroll 16
-    for (int j = 0; j < D; ++j) y = __builtin_fmaf(a.pool.RT[(size_t)j * b + bit], qs[j], y);
+#pragma unroll
+    for (int j = 0; j < D; ++j) y = __builtin_fmaf(rt[j], qs[j], y);
     const uint64_t mask = __ballot(y >= 0.0f);
     if ((threadIdx.x & 63) == 0) a.q_sketch[vec * W + (threadIdx.x >> 6)] = mask;
 }
@@ -363,11 +368,19 @@ hipError_t launch_merge(const DecodeArgs &a, const BatchDesc &desc, int seq0, in
     return hipGetLastError();
 }
 
-hipError_t launch_qsketch(const DecodeArgs &a, int seq0, int n_seqs, hipStream_t st) {
+template <typename T>
+static hipError_t launch_qsketch_t(const DecodeArgs &a, int seq0, int n_seqs, hipStream_t st) {
     const dim3 grid((unsigned)(n_seqs * a.pool.n_q_heads)), block((unsigned)a.pool.sketch_bits);
-    if (a.f16) hipLaunchKernelGGL((qsketch_kernel<__half>), grid, block, 0, st, a, seq0);
-    else hipLaunchKernelGGL((qsketch_kernel<float>), grid, block, 0, st, a, seq0);
+    switch (a.pool.head_dim) {
+        case 64: hipLaunchKernelGGL((qsketch_kernel<T, 64>), grid, block, 0, st, a, seq0); break;
+        case 128: hipLaunchKernelGGL((qsketch_kernel<T, 128>), grid, block, 0, st, a, seq0); break;
+        default: hipLaunchKernelGGL((qsketch_kernel<T, 256>), grid, block, 0, st, a, seq0); break;
+    }
     return hipGetLastError();
+}
+
+hipError_t launch_qsketch(const DecodeArgs &a, int seq0, int n_seqs, hipStream_t st) {
+    return a.f16 ? launch_qsketch_t<__half>(a, seq0, n_seqs, st) : launch_qsketch_t<float>(a, seq0, n_seqs, st);
 }
 
 }  // namespace h1bkv
