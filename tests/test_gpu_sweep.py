@@ -1,0 +1,60 @@
+"""GPU parity over a sweep of geometries: every supported (head_dim, sketch bits, group size, heads per KV head,
+dtype) family at small context lengths that still span several pages and ragged tails, with the cache built
+in uneven append steps (including single-token steps that cross 8-token block and page boundaries)."""
+import itertools
+
+import numpy as np
+import pytest
+
+from oracle import cref
+from paper_2510_05529_amd import binding as B
+from paper_2510_05529_amd import workloads as wl
+from tests.gpu_util import TOL, assert_cache_equal, make_cache, rel_err, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def geometries():
+    out = []
+    for d, b, g, r, dt in itertools.product((64, 128, 256), (64, 128, 256, 512), (32, 64, 128), (1, 2, 3, 4, 8), ("f16", "f32")):
+        if g > d:
+            continue
+        # thin the product out deterministically: keep roughly one in five, but every value of every axis
+        if (d // 64 + b // 64 + g // 32 + r + (dt == "f32")) % 5 != 0:
+            continue
+        out.append((d, b, g, r, dt))
+    return out
+
+
+GEOS = geometries()
+
+
+def test_sweep_covers_every_axis_value():
+    for axis, values in enumerate([(64, 128, 256), (64, 128, 256, 512), (32, 64, 128), (1, 2, 3, 4, 8), ("f16", "f32")]):
+        assert {g[axis] for g in GEOS} == set(values)
+    assert 30 <= len(GEOS) <= 80
+
+
+@pytest.mark.parametrize("d,b,g,r,dt", GEOS)
+def test_geometry(d, b, g, r, dt):
+    T = 300 + 7 * r + (d // 64)
+    w = wl.Workload(f"sweep_d{d}_b{b}_g{g}_r{r}_{dt}", 2, 2 * r, 2, d, T, b, g, dt, seed=d + b + g + r)
+    R = wl.projection(b, d)
+    seqs = [0, 1]
+    k, v, q = wl.kv_slab(w, "k", seqs, 0, T), wl.kv_slab(w, "v", seqs, 0, T), wl.queries(w)
+    oc = cref.Cache(R, 2, 2, T, g)
+    oc.append(k, v)
+    cache = make_cache(w, R)
+    kd, vd = to_dev(k), to_dev(v)
+    t = 0
+    for n in [5, 1, 1, 1, 250, 1, 3, 10_000]:            # crosses 8-token blocks and the page boundary in small steps
+        n = min(n, T - t)
+        cache.append(seqs, kd[:, t:t + n], vd[:, t:t + n])
+        t += n
+    assert t == T
+    assert_cache_equal(cache, oc, seqs, T)
+    for tau, chunk in ((w.default_tau(), 0), (0.3, 256)):
+        assert B.h1bkv_set_decode_chunk(cache.h, chunk) == B.H1BKV_OK
+        out = cache.decode(seqs, to_dev(q), tau).cpu().numpy()
+        assert rel_err(out, oc.decode(q, tau)) <= TOL
+    cache.close()
