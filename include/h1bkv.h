@@ -138,6 +138,18 @@ int h1bkv_decode_attn(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n_seq
                       void *hip_stream);
 
 /*
+ * One decode step in one call: h1bkv_append_kv with n_new = 1 (k_dev, v_dev: [n_seqs][n_kv_heads][d], sequence
+ * and head strides in elements) followed by h1bkv_decode_attn over the grown context, with the same results as
+ * the two calls (Sec. IV: a generated token's key and value are cached, then its query attends to the cache).
+ * The new token's append and the query sketches do not depend on each other and share one kernel launch, so the
+ * step costs three launches instead of four.  workspace as for h1bkv_decode_attn with the lengths after the append.
+ * Validation covers both halves before anything is changed or enqueued.
+ */
+int h1bkv_decode_step(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n_seqs, const void *k_dev,
+                      const void *v_dev, int64_t stride_seq, int64_t stride_head, const void *q_dev, float tau,
+                      float *out_dev, void *workspace_dev, size_t workspace_bytes, void *hip_stream);
+
+/*
  * Tuning override for the context chunk of h1bkv_decode_attn: tokens per chunk, a multiple of
  * H1BKV_PAGE_TOKENS up to 8192, or 0 for the built-in choice.  Results do not depend on it beyond
  * fp32 summation order.
@@ -169,6 +181,9 @@ int h1bkv_extend_seq(h1bkv_cache *c, int32_t seq_id, int32_t n_new, void *hip_st
  */
 enum { H1BKV_K_APPEND = 0, H1BKV_K_QSKETCH = 1, H1BKV_K_DECODE_SPLIT = 2, H1BKV_K_MERGE = 3, H1BKV_K_COUNT = 4 };
 int h1bkv_profile_enable(h1bkv_cache *c, int32_t capacity, uint32_t kernel_mask);
+/* Bracket only every `stride`-th launch of each selected kind (stride >= 1; 1 = every launch, the default): an
+ * event pair costs a few microseconds on the stream, which a benchmark of sub-millisecond steps can thin out. */
+int h1bkv_profile_stride(h1bkv_cache *c, int32_t stride);
 int h1bkv_profile_read(h1bkv_cache *c, int32_t kernel, float *ms_out, int32_t cap, int32_t *n_out);
 
 /*

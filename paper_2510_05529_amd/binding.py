@@ -63,11 +63,13 @@ def lib() -> C.CDLL:
             "h1bkv_append_kv": (C.c_int, [vp, vp, i32, i32, vp, vp, i64, i64, i64, vp]),
             "h1bkv_decode_workspace_bytes": (sz, [vp, i32, i32]),
             "h1bkv_decode_attn": (C.c_int, [vp, vp, i32, vp, C.c_float, vp, vp, sz, vp]),
+            "h1bkv_decode_step": (C.c_int, [vp, vp, i32, vp, vp, i64, i64, vp, C.c_float, vp, vp, sz, vp]),
             "h1bkv_set_decode_chunk": (C.c_int, [vp, i32]),
             "h1bkv_export_tokens": (C.c_int, [vp, i32, i32, i32, i32, vp, vp, vp, vp]),
             "h1bkv_import_tokens": (C.c_int, [vp, i32, i32, i32, i32, vp, vp, vp, vp]),
             "h1bkv_extend_seq": (C.c_int, [vp, i32, i32, vp]),
             "h1bkv_profile_enable": (C.c_int, [vp, i32, C.c_uint32]),
+            "h1bkv_profile_stride": (C.c_int, [vp, i32]),
             "h1bkv_profile_read": (C.c_int, [vp, i32, vp, i32, C.POINTER(i32)]),
             "h1bkv_stream_copy": (C.c_int, [vp, vp, sz, vp]),
             "h1bkv_stream_read": (C.c_int, [vp, sz, vp, vp]),
@@ -169,6 +171,13 @@ def h1bkv_decode_attn(h, seq_ids, q, tau: float, out, workspace, workspace_bytes
                                    _stream(stream))
 
 
+def h1bkv_decode_step(h, seq_ids, k, v, stride_seq: int, stride_head: int, q, tau: float, out, workspace, workspace_bytes: int,
+                      stream=0) -> int:
+    ids, p = _ids(seq_ids)
+    return lib().h1bkv_decode_step(h, p, len(ids), _dev_ptr(k), _dev_ptr(v), stride_seq, stride_head, _dev_ptr(q), tau,
+                                   _dev_ptr(out), _dev_ptr(workspace), workspace_bytes, _stream(stream))
+
+
 def h1bkv_set_decode_chunk(h, chunk_tokens: int) -> int:
     return lib().h1bkv_set_decode_chunk(h, chunk_tokens)
 
@@ -198,6 +207,10 @@ def h1bkv_extend_seq(h, seq_id: int, n_new: int, stream=0) -> int:
 
 def h1bkv_profile_enable(h, capacity: int, kernel_mask: int = 0xF) -> int:
     return lib().h1bkv_profile_enable(h, capacity, kernel_mask)
+
+
+def h1bkv_profile_stride(h, stride: int) -> int:
+    return lib().h1bkv_profile_stride(h, stride)
 
 
 def h1bkv_profile_read(h, kernel: int, cap: int = 4096):

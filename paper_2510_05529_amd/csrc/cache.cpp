@@ -69,6 +69,8 @@ struct h1bkv_cache {
     // profiling
     int32_t prof_cap;
     uint32_t prof_mask;
+    int32_t prof_stride;
+    int32_t prof_seen[H1BKV_K_COUNT];
     std::vector<EventPair> prof_events[H1BKV_K_COUNT];
     int32_t prof_used[H1BKV_K_COUNT];
 
@@ -106,7 +108,8 @@ struct Timed {
     hipStream_t st;
     int slot;
     Timed(h1bkv_cache *c_, int kind_, hipStream_t st_) : c(c_), kind(kind_), st(st_), slot(-1) {
-        if (c->prof_cap > 0 && ((c->prof_mask >> kind) & 1u) && c->prof_used[kind] < c->prof_cap) {
+        if (c->prof_cap > 0 && ((c->prof_mask >> kind) & 1u) && c->prof_used[kind] < c->prof_cap &&
+            c->prof_seen[kind]++ % c->prof_stride == 0) {
             slot = c->prof_used[kind]++;
             (void)hipEventRecord(c->prof_events[kind][slot].a, st);
         }
@@ -245,6 +248,8 @@ int h1bkv_create(const h1bkv_config *cfg, void *pool_dev, size_t pool_bytes, con
     c->chunk_override = 0;
     c->prof_cap = 0;
     c->prof_mask = 0;
+    c->prof_stride = 1;
+    for (int k = 0; k < H1BKV_K_COUNT; ++k) c->prof_seen[k] = 0;
     for (int k = 0; k < H1BKV_K_COUNT; ++k) c->prof_used[k] = 0;
     if (!dry) {
         if (check_device(c) != H1BKV_OK) {
@@ -334,9 +339,9 @@ int h1bkv_extend_seq(h1bkv_cache *c, int32_t seq_id, int32_t n_new, void *hip_st
     return publish(c, ui, up, static_cast<hipStream_t>(hip_stream));
 }
 
-int h1bkv_append_kv(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n_seqs, int32_t n_new, const void *k_dev,
-                    const void *v_dev, int64_t stride_seq, int64_t stride_tok, int64_t stride_head, void *hip_stream) {
-    if (!c) return H1BKV_ENULL;
+// Everything h1bkv_append_kv checks before it touches the bookkeeping.
+static int validate_append(const h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n_seqs, int32_t n_new, const void *k_dev,
+                           const void *v_dev, int64_t stride_seq, int64_t stride_tok, int64_t stride_head) {
     int rc = check_seq_ids(c, seq_ids_host, n_seqs);
     if (rc != H1BKV_OK) return rc;
     if (n_new < 1) return H1BKV_EINVAL;
@@ -355,15 +360,18 @@ int h1bkv_append_kv(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n_seqs,
         need_total += need;
     }
     if (need_total > (int64_t)c->free_list.size()) return H1BKV_ENOSPACE;
-    if (!c->dry) {
-        rc = check_device(c);
-        if (rc != H1BKV_OK) return rc;
-    }
-    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    return c->dry ? H1BKV_OK : check_device(c);
+}
 
+// Takes pages, publishes them and launches the append kernel(s).  With q_dev != nullptr each launch also sketches
+// the queries of its sequences into q_sketch_dev (fused decode-step prologue).  Arguments are already validated.
+static int enqueue_append(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n_seqs, int32_t n_new, const void *k_dev,
+                          const void *v_dev, int64_t stride_seq, int64_t stride_tok, int64_t stride_head, const void *q_dev,
+                          uint64_t *q_sketch_dev, hipStream_t st) {
+    const int elt = c->cfg.in_dtype == H1BKV_F16 ? 2 : 4;
     std::vector<int32_t> ui, up;
     for (int i = 0; i < n_seqs; ++i) take_pages(c, seq_ids_host[i], c->seq_len[seq_ids_host[i]] + n_new, ui, up);
-    rc = publish(c, ui, up, st);
+    int rc = publish(c, ui, up, st);
     if (!c->dry && rc == H1BKV_OK) {
         AppendArgs a{};
         a.pool = c->view();
@@ -378,8 +386,15 @@ int h1bkv_append_kv(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n_seqs,
             for (int i = 0; i < n; ++i) desc.s[i] = SeqDesc{seq_ids_host[s0 + i], c->seq_len[seq_ids_host[s0 + i]]};
             a.k = static_cast<const char *>(k_dev) + (size_t)s0 * stride_seq * elt;
             a.v = static_cast<const char *>(v_dev) + (size_t)s0 * stride_seq * elt;
+            QueryArgs qa{};
+            if (q_dev) {
+                const size_t vec0 = (size_t)s0 * c->cfg.n_q_heads;
+                qa.q = static_cast<const char *>(q_dev) + vec0 * c->cfg.head_dim * elt;
+                qa.q_sketch = q_sketch_dev + vec0 * c->W;
+                qa.n_vec = n * c->cfg.n_q_heads;
+            }
             Timed t(c, H1BKV_K_APPEND, st);
-            if (launch_append(a, desc, n, st) != hipSuccess) rc = H1BKV_EHIP;
+            if (launch_append(a, desc, n, q_dev ? &qa : nullptr, st) != hipSuccess) rc = H1BKV_EHIP;
         }
     }
     if (rc != H1BKV_OK) {
@@ -389,6 +404,15 @@ int h1bkv_append_kv(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n_seqs,
     }
     for (int i = 0; i < n_seqs; ++i) c->seq_len[seq_ids_host[i]] += n_new;
     return H1BKV_OK;
+}
+
+int h1bkv_append_kv(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n_seqs, int32_t n_new, const void *k_dev,
+                    const void *v_dev, int64_t stride_seq, int64_t stride_tok, int64_t stride_head, void *hip_stream) {
+    if (!c) return H1BKV_ENULL;
+    const int rc = validate_append(c, seq_ids_host, n_seqs, n_new, k_dev, v_dev, stride_seq, stride_tok, stride_head);
+    if (rc != H1BKV_OK) return rc;
+    return enqueue_append(c, seq_ids_host, n_seqs, n_new, k_dev, v_dev, stride_seq, stride_tok, stride_head, nullptr, nullptr,
+                          static_cast<hipStream_t>(hip_stream));
 }
 
 size_t h1bkv_decode_workspace_bytes(const h1bkv_cache *c, int32_t n_seqs, int32_t max_ctx) {
@@ -401,9 +425,9 @@ size_t h1bkv_decode_workspace_bytes(const h1bkv_cache *c, int32_t n_seqs, int32_
     return o;
 }
 
-int h1bkv_decode_attn(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n_seqs, const void *q_dev, float tau,
-                      float *out_dev, void *workspace_dev, size_t workspace_bytes, void *hip_stream) {
-    if (!c) return H1BKV_ENULL;
+// Everything h1bkv_decode_attn checks; `grow` tokens are about to be appended to every sequence first.
+static int validate_decode(const h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n_seqs, const void *q_dev, float tau,
+                           const float *out_dev, const void *workspace_dev, size_t workspace_bytes, int grow) {
     int rc = check_seq_ids(c, seq_ids_host, n_seqs);
     if (rc != H1BKV_OK) return rc;
     if (!(tau > 0.0f) || !std::isfinite(tau)) return H1BKV_EINVAL;
@@ -413,12 +437,16 @@ int h1bkv_decode_attn(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n_seq
         reinterpret_cast<uintptr_t>(out_dev) % 16)
         return H1BKV_EINVAL;
     int max_ctx = 0;
-    for (int i = 0; i < n_seqs; ++i) max_ctx = std::max(max_ctx, c->seq_len[seq_ids_host[i]]);
+    for (int i = 0; i < n_seqs; ++i) max_ctx = std::max(max_ctx, c->seq_len[seq_ids_host[i]] + grow);
     if (workspace_bytes < h1bkv_decode_workspace_bytes(c, n_seqs, max_ctx)) return H1BKV_EWORKSPACE;
-    rc = check_device(c);
-    if (rc != H1BKV_OK) return rc;
-    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    return check_device(c);
+}
 
+// Launches (query sketch,) split decode and merge for validated arguments.
+static int enqueue_decode(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n_seqs, const void *q_dev, float tau,
+                          float *out_dev, void *workspace_dev, bool sketches_done, hipStream_t st) {
+    int max_ctx = 0;
+    for (int i = 0; i < n_seqs; ++i) max_ctx = std::max(max_ctx, c->seq_len[seq_ids_host[i]]);
     const int chunk = choose_chunk(c, n_seqs, max_ctx);
     const int S = std::max(1, (max_ctx + chunk - 1) / chunk);
     const size_t heads = (size_t)n_seqs * c->cfg.n_q_heads;
@@ -441,7 +469,7 @@ int h1bkv_decode_attn(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n_seq
         const int n = std::min(kMaxSeqsPerLaunch, n_seqs - s0);
         BatchDesc desc;
         for (int i = 0; i < n; ++i) desc.s[i] = SeqDesc{seq_ids_host[s0 + i], c->seq_len[seq_ids_host[s0 + i]]};
-        {
+        if (!sketches_done) {
             Timed t(c, H1BKV_K_QSKETCH, st);
             if (launch_qsketch(a, s0, n, st) != hipSuccess) return H1BKV_EHIP;
         }
@@ -456,6 +484,31 @@ int h1bkv_decode_attn(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n_seq
         }
     }
     return H1BKV_OK;
+}
+
+int h1bkv_decode_attn(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n_seqs, const void *q_dev, float tau,
+                      float *out_dev, void *workspace_dev, size_t workspace_bytes, void *hip_stream) {
+    if (!c) return H1BKV_ENULL;
+    const int rc = validate_decode(c, seq_ids_host, n_seqs, q_dev, tau, out_dev, workspace_dev, workspace_bytes, 0);
+    if (rc != H1BKV_OK) return rc;
+    return enqueue_decode(c, seq_ids_host, n_seqs, q_dev, tau, out_dev, workspace_dev, false, static_cast<hipStream_t>(hip_stream));
+}
+
+int h1bkv_decode_step(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n_seqs, const void *k_dev, const void *v_dev,
+                      int64_t stride_seq, int64_t stride_head, const void *q_dev, float tau, float *out_dev,
+                      void *workspace_dev, size_t workspace_bytes, void *hip_stream) {
+    if (!c) return H1BKV_ENULL;
+    // both halves are validated before anything changes
+    int rc = validate_decode(c, seq_ids_host, n_seqs, q_dev, tau, out_dev, workspace_dev, workspace_bytes, 1);
+    if (rc != H1BKV_OK) return rc;
+    rc = validate_append(c, seq_ids_host, n_seqs, 1, k_dev, v_dev, stride_seq, 0, stride_head);
+    if (rc != H1BKV_OK) return rc;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    // the query sketches sit at the start of the workspace (see enqueue_decode)
+    rc = enqueue_append(c, seq_ids_host, n_seqs, 1, k_dev, v_dev, stride_seq, 0, stride_head, q_dev,
+                        static_cast<uint64_t *>(workspace_dev), st);
+    if (rc != H1BKV_OK) return rc;
+    return enqueue_decode(c, seq_ids_host, n_seqs, q_dev, tau, out_dev, workspace_dev, true, st);
 }
 
 static int xfer_tokens(const h1bkv_cache *c, int32_t seq_id, int32_t kv_head, int32_t t0, int32_t n, bool to_host,
@@ -561,6 +614,14 @@ int h1bkv_profile_enable(h1bkv_cache *c, int32_t capacity, uint32_t kernel_mask)
         }
     }
     c->prof_cap = capacity;
+    return H1BKV_OK;
+}
+
+int h1bkv_profile_stride(h1bkv_cache *c, int32_t stride) {
+    if (!c) return H1BKV_ENULL;
+    if (stride < 1) return H1BKV_EINVAL;
+    c->prof_stride = stride;
+    for (int k = 0; k < H1BKV_K_COUNT; ++k) c->prof_seen[k] = 0;
     return H1BKV_OK;
 }
 

@@ -63,6 +63,12 @@ struct AppendArgs {
     int32_t f16;
 };
 
+struct QueryArgs {            // query vectors sketched by the fused decode-step prologue
+    const void *q;            // [n_vec][d] in the cache's input dtype
+    uint64_t *q_sketch;       // [n_vec][W]
+    int32_t n_vec;
+};
+
 struct DecodeArgs {
     PoolView pool;
     const void *q;            // [n_seqs][H_q][d]
@@ -92,7 +98,7 @@ inline int max_decode_chunk(int, int) { return kMaxChunk; }
 
 // Launchers (kernels_*.hip).  Each returns hipGetLastError() of its launch.
 hipError_t launch_publish(const TablePairs &pairs, int32_t *block_table, hipStream_t st);
-hipError_t launch_append(const AppendArgs &a, const BatchDesc &desc, int n_seqs, hipStream_t st);
+hipError_t launch_append(const AppendArgs &a, const BatchDesc &desc, int n_seqs, const QueryArgs *qa, hipStream_t st);
 hipError_t launch_qsketch(const DecodeArgs &a, int seq0, int n_seqs, hipStream_t st);
 hipError_t launch_decode_split(const DecodeArgs &a, const BatchDesc &desc, int seq0, int n_seqs, hipStream_t st);
 hipError_t launch_decode_split_mfma(const DecodeArgs &a, const BatchDesc &desc, int seq0, int n_seqs, hipStream_t st);

@@ -56,8 +56,10 @@ __device__ __forceinline__ void copy8(const float *src, float *dst) {
     *reinterpret_cast<float4 *>(dst + 4) = *reinterpret_cast<const float4 *>(src + 4);
 }
 
+// bx, by, gx: the workgroup's tile index, its sequence (index into desc) and the number of workgroups that share
+// the sequence's tiles -- blockIdx.x, blockIdx.y, gridDim.x when the kernel does nothing else.
 template <int D, typename T>
-__global__ __launch_bounds__(kThreads) void append_kernel(AppendArgs a, BatchDesc desc, int tile) {
+__device__ __forceinline__ void append_body(const AppendArgs &a, const BatchDesc &desc, int tile, int bx, int by, int gx) {
     __shared__ __attribute__((aligned(16))) T ks[kTile][D];   // the key tile in its boundary dtype
     __shared__ uint64_t words[kTile][8];              // sketch words of the tile (W <= 8)
     __shared__ size_t dst[kTile];                     // plane index of each slot: (page * H_kv + head) * 256 + slot in page
@@ -65,15 +67,15 @@ __global__ __launch_bounds__(kThreads) void append_kernel(AppendArgs a, BatchDes
     __shared__ uint32_t codes_s[kTile][D / 8 + 1];    // layout 1: codes of the tile in canonical nibble order (+1: bank spread)
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const SeqDesc sd = desc.s[blockIdx.y];
+    const SeqDesc sd = desc.s[by];
     const PoolView &pv = a.pool;
     const int H = pv.n_kv_heads, W = pv.sketch_bits >> 6, G = pv.group_size, ng = D / G;
     const int n_new = a.n_new;
     const int off8 = sd.pos & 7;                      // slots of a head's first block that lie before the first new token
     const int L = (off8 + n_new + 7) & ~7;            // slots per head
     const int n_slots = L * H;
-    const T *kbase = static_cast<const T *>(a.k) + (size_t)blockIdx.y * a.stride_seq;
-    const T *vbase = static_cast<const T *>(a.v) + (size_t)blockIdx.y * a.stride_seq;
+    const T *kbase = static_cast<const T *>(a.k) + (size_t)by * a.stride_seq;
+    const T *vbase = static_cast<const T *>(a.v) + (size_t)by * a.stride_seq;
 
     // Row R[64 word + lane][0..d) of this lane's sketch bit lives in registers across all tiles of the workgroup.
     const int wslots = W < 4 ? W : 4, tslots = 4 / wslots;
@@ -89,7 +91,7 @@ __global__ __launch_bounds__(kThreads) void append_kernel(AppendArgs a, BatchDes
     };
     load_row(r_word);
 
-    for (int slot0 = blockIdx.x * tile; slot0 < n_slots; slot0 += gridDim.x * tile) {
+    for (int slot0 = bx * tile; slot0 < n_slots; slot0 += gx * tile) {
         __syncthreads();   // previous pass is done with the LDS tile
         // ---- resolve the tile once: slot -> (head, token) -> source row, destination record ----
         // (the divisions by the runtime slot count per head are done here, by one thread per slot, not in the loops)
@@ -218,9 +220,50 @@ __global__ __launch_bounds__(kThreads) void append_kernel(AppendArgs a, BatchDes
     }
 }
 
+template <int D, typename T>
+__global__ __launch_bounds__(kThreads) void append_kernel(AppendArgs a, BatchDesc desc, int tile) {
+    append_body<D, T>(a, desc, tile, blockIdx.x, blockIdx.y, gridDim.x);
+}
+
+// Prologue of a fused decode step: rows [0, n_seqs) of the grid append the step's new token of each sequence,
+// the remaining rows sketch the step's queries (Eq.(2) applied to q, same FMA chain: thread = (query, bit), all
+// loads of the thread's column of R^T issued ahead of the chain, ballot = packed word).  Neither half depends on
+// the other, so one launch replaces two.
+template <int D, typename T>
+__global__ __launch_bounds__(kThreads) void step_prologue_kernel(AppendArgs a, BatchDesc desc, int tile, int n_seqs, QueryArgs qa) {
+    if ((int)blockIdx.y < n_seqs) {
+        append_body<D, T>(a, desc, tile, blockIdx.x, blockIdx.y, gridDim.x);
+        return;
+    }
+    __shared__ float qs[4][D];
+    const int b = a.pool.sketch_bits, W = b >> 6;
+    const int per_block = b <= kThreads ? kThreads / b : 1;           // whole queries per workgroup pass
+    const int vec0 = (((int)blockIdx.y - n_seqs) * gridDim.x + blockIdx.x) * per_block;
+    const T *qbase = static_cast<const T *>(qa.q);
+    for (int e = threadIdx.x; e < per_block * D; e += kThreads) {
+        const int qi = e / D, vec = vec0 + qi;
+        qs[qi][e % D] = vec < qa.n_vec ? (float)qbase[(size_t)vec * D + e % D] : 0.0f;
+    }
+    __syncthreads();
+    for (int bit0 = 0; bit0 < b; bit0 += kThreads) {                  // one pass unless b = 512
+        const int qi = b <= kThreads ? threadIdx.x / b : 0;
+        const int bit = b <= kThreads ? threadIdx.x % b : bit0 + threadIdx.x;
+        const int vec = vec0 + qi;
+        float y = 0.0f;
+        float rt[D];
+#pragma unroll
+        for (int j = 0; j < D; ++j) rt[j] = a.pool.RT[(size_t)j * b + bit];
+#pragma unroll
+        for (int j = 0; j < D; ++j) y = __builtin_fmaf(rt[j], qs[qi][j], y);
+        const uint64_t mask = __ballot(y >= 0.0f);
+        if ((threadIdx.x & 63) == 0 && vec < qa.n_vec) qa.q_sketch[(size_t)vec * W + (bit >> 6)] = mask;
+    }
+}
+
 }  // namespace
 
-hipError_t launch_append(const AppendArgs &a, const BatchDesc &desc, int n_seqs, hipStream_t st) {
+// With qa != nullptr the launch also sketches qa->n_vec query vectors (fused decode-step prologue).
+hipError_t launch_append(const AppendArgs &a, const BatchDesc &desc, int n_seqs, const QueryArgs *qa, hipStream_t st) {
     // Slots per head: the new tokens plus the padding down to / up to 8-token boundaries.
     int max_off = 0;
     for (int i = 0; i < n_seqs; ++i) max_off = desc.s[i].pos % 8 > max_off ? desc.s[i].pos % 8 : max_off;
@@ -235,9 +278,21 @@ hipError_t launch_append(const AppendArgs &a, const BatchDesc &desc, int n_seqs,
     // Each workgroup reads its rows of R once and keeps them in registers: with many tiles, a few resident
     // workgroups per compute unit walk all of them.
     const long max_wgs_x = 1024 / n_seqs > 0 ? 1024 / n_seqs : 1;
-    const dim3 grid((unsigned)(tiles < max_wgs_x ? tiles : max_wgs_x), (unsigned)n_seqs);
+    const unsigned gx = (unsigned)(tiles < max_wgs_x ? tiles : max_wgs_x);
+    unsigned q_rows = 0;
+    if (qa) {
+        const int per_block = a.pool.sketch_bits <= kThreads ? kThreads / a.pool.sketch_bits : 1;
+        const unsigned q_blocks = (unsigned)((qa->n_vec + per_block - 1) / per_block);
+        q_rows = (q_blocks + gx - 1) / gx;
+    }
+    const dim3 grid(gx, (unsigned)n_seqs + q_rows);
     const int D = a.pool.head_dim;
-#define H1BKV_LAUNCH(DD, TT) hipLaunchKernelGGL((append_kernel<DD, TT>), grid, dim3(kThreads), 0, st, a, desc, (int)tile)
+    const QueryArgs qargs = qa ? *qa : QueryArgs{nullptr, nullptr, 0};
+#define H1BKV_LAUNCH(DD, TT)                                                                                        \
+    do {                                                                                                            \
+        if (qa) hipLaunchKernelGGL((step_prologue_kernel<DD, TT>), grid, dim3(kThreads), 0, st, a, desc, (int)tile, n_seqs, qargs); \
+        else hipLaunchKernelGGL((append_kernel<DD, TT>), grid, dim3(kThreads), 0, st, a, desc, (int)tile);          \
+    } while (0)
     if (a.f16) {
         if (D == 64) H1BKV_LAUNCH(64, __half);
         else if (D == 128) H1BKV_LAUNCH(128, __half);

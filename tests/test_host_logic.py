@@ -143,3 +143,19 @@ def test_misc_errors():
     assert B.h1bkv_stream_copy(None, None, 16) == B.H1BKV_ENULL
     assert B.h1bkv_stream_copy(4096, 8192, 24) == B.H1BKV_EINVAL
     assert B.h1bkv_destroy(h) == B.H1BKV_OK and B.h1bkv_destroy(None) == B.H1BKV_OK
+
+
+def test_decode_step_validates_both_halves_before_changing_anything():
+    c, h, _ = make()
+    assert B.h1bkv_append_kv(h, [0, 1], 10, None, None, 10 * 512, 512, 128) == B.H1BKV_OK
+    free = B.h1bkv_free_pages(h)
+    args = dict(stride_seq=512, stride_head=128)
+    # bad decode arguments are reported although the append half would be fine, and nothing is appended
+    assert B.h1bkv_decode_step(h, [0, 1], None, None, 512, 128, None, 0.0, None, None, 0) == B.H1BKV_EINVAL
+    assert B.h1bkv_decode_step(h, [0, 0], None, None, 512, 128, None, 0.1, None, None, 0) == B.H1BKV_EINVAL
+    assert B.h1bkv_decode_step(h, [0, 5], None, None, 512, 128, None, 0.1, None, None, 0) == B.H1BKV_ERANGE
+    # a bookkeeping-only handle cannot decode: the step is refused as a whole
+    assert B.h1bkv_decode_step(h, [0, 1], None, None, 512, 128, None, 0.1, None, None, 0) == B.H1BKV_ENODEVICE
+    assert B.h1bkv_seq_len(h, 0) == (0, 10) and B.h1bkv_seq_len(h, 1) == (0, 10) and B.h1bkv_free_pages(h) == free
+    assert B.lib().h1bkv_decode_step(None, None, 1, None, None, 512, 128, None, 0.1, None, None, 0, None) == B.H1BKV_ENULL
+    B.h1bkv_destroy(h)
