@@ -25,7 +25,8 @@ def lib():
         L.h1bkv_oracle_max_threads.restype = C.c_int
         for name in ("h1bkv_oracle_sketch", "h1bkv_oracle_quantize", "h1bkv_oracle_dequantize",
                      "h1bkv_oracle_hamming", "h1bkv_oracle_decode_one", "h1bkv_oracle_decode_batch",
-                     "h1bkv_oracle_append_batch"):
+                     "h1bkv_oracle_append_batch", "h1bkv_oracle_decode_one_f16v",
+                     "h1bkv_oracle_decode_batch_f16v", "h1bkv_oracle_append_batch_f16v"):
             getattr(L, name).restype = None
         _lib = L
     return _lib
@@ -110,18 +111,35 @@ def decode_one(sq, sk, codes, scale, zero, b: int, G: int, tau: float) -> np.nda
     return out
 
 
+def decode_one_f16v(sq, sk, v16, b: int, tau: float) -> np.ndarray:
+    """Eq.(3)+(5) with fp16 values (the "1-bit key only" variant): v16 [T][d] fp16 bit patterns -> out [d] float32."""
+    sq = np.ascontiguousarray(sq, dtype=np.uint64)
+    sk = np.ascontiguousarray(sk, dtype=np.uint64)
+    v16 = np.ascontiguousarray(v16, dtype=np.uint16)
+    T, d = v16.shape
+    out = np.zeros(d, dtype=np.float32)
+    lib().h1bkv_oracle_decode_one_f16v(_p(sq), _p(sk), _p(v16), C.c_int64(T), C.c_int(b), C.c_int(d),
+                                       C.c_double(tau), _p(out))
+    return out
+
+
 class Cache:
     """Canonical-layout compressed cache on the host: planes [B][H_kv][Tcap][...], filled by the oracle."""
 
-    def __init__(self, R: np.ndarray, B: int, Hkv: int, Tcap: int, G: int):
+    def __init__(self, R: np.ndarray, B: int, Hkv: int, Tcap: int, G: int, value_bits: int = 4):
+        assert value_bits in (4, 16)
         self.R = _f32(R)
         self.b, self.d = self.R.shape
         self.B, self.Hkv, self.Tcap, self.G = B, Hkv, Tcap, G
+        self.value_bits = value_bits
         self.W, self.ng = self.b // 64, self.d // G
         self.sketches = np.zeros((B, Hkv, Tcap, self.W), dtype=np.uint64)
-        self.codes = np.zeros((B, Hkv, Tcap, self.d // 2), dtype=np.uint8)
-        self.scale = np.zeros((B, Hkv, Tcap, self.ng), dtype=np.uint16)
-        self.zero = np.zeros((B, Hkv, Tcap, self.ng), dtype=np.uint16)
+        if value_bits == 4:
+            self.codes = np.zeros((B, Hkv, Tcap, self.d // 2), dtype=np.uint8)
+            self.scale = np.zeros((B, Hkv, Tcap, self.ng), dtype=np.uint16)
+            self.zero = np.zeros((B, Hkv, Tcap, self.ng), dtype=np.uint16)
+        else:
+            self.v16 = np.zeros((B, Hkv, Tcap, self.d), dtype=np.uint16)     # fp16 bit patterns
         self.len = 0
 
     def append(self, k: np.ndarray, v: np.ndarray) -> None:
@@ -130,6 +148,12 @@ class Cache:
         n_new = k.shape[1]
         assert k.shape == v.shape == (self.B, n_new, self.Hkv, self.d)
         assert self.len + n_new <= self.Tcap
+        if self.value_bits == 16:
+            lib().h1bkv_oracle_append_batch_f16v(_p(self.R), C.c_int(self.b), C.c_int(self.d), C.c_int(self.B),
+                                                 C.c_int(self.Hkv), C.c_int64(self.Tcap), C.c_int64(self.len),
+                                                 C.c_int64(n_new), _p(k), _p(v), _p(self.sketches), _p(self.v16))
+            self.len += n_new
+            return
         lib().h1bkv_oracle_append_batch(_p(self.R), C.c_int(self.b), C.c_int(self.d), C.c_int(self.G),
                                         C.c_int(self.B), C.c_int(self.Hkv), C.c_int64(self.Tcap),
                                         C.c_int64(self.len), C.c_int64(n_new), _p(k), _p(v), _p(self.sketches),
@@ -142,6 +166,11 @@ class Cache:
         Hq = q.shape[1]
         lens = np.full(self.B, self.len, dtype=np.int32) if ctx_len is None else np.ascontiguousarray(ctx_len, dtype=np.int32)
         out = np.zeros((self.B, Hq, self.d), dtype=np.float32)
+        if self.value_bits == 16:
+            lib().h1bkv_oracle_decode_batch_f16v(_p(self.R), C.c_int(self.b), C.c_int(self.d), C.c_int(self.B),
+                                                 C.c_int(Hq), C.c_int(self.Hkv), C.c_int64(self.Tcap), _p(lens), _p(q),
+                                                 _p(self.sketches), _p(self.v16), C.c_double(tau), _p(out))
+            return out
         lib().h1bkv_oracle_decode_batch(_p(self.R), C.c_int(self.b), C.c_int(self.d), C.c_int(self.G),
                                         C.c_int(self.B), C.c_int(Hq), C.c_int(self.Hkv), C.c_int64(self.Tcap),
                                         _p(lens), _p(q), _p(self.sketches), _p(self.codes), _p(self.scale),

@@ -30,7 +30,9 @@
  * Parity pins (tests/test_oracle_*.py): brute-force +-1 dot products, the identity
  * <s_q,s_k> = b - 2 popcount(s_q xor s_k), Prop. 1's expectation 1 - 2 theta/pi, round-trip error
  * <= scale/2, closed forms of Eq.(5) (T=1, equal sketches, tau -> inf, two-level), exact rational
- * arithmetic on tiny cases, and numpy's float16 for the half conversions.
+ * arithmetic on tiny cases, and numpy's float16 for the half conversions.  The fp16-value variant at the end
+ * of the file is pinned by tests/test_oracle_f16v.py (numpy float16 storage, closed forms, agreement with the
+ * 4-bit functions on values both formats hold exactly, the explicit +-1 rendering).
  */
 #include <math.h>
 #include <stdint.h>
@@ -245,6 +247,72 @@ void h1bkv_oracle_append_batch(const float *R, int b, int d, int G, int B, int H
                 int64_t dst = ((int64_t)s * Hkv + h) * Tcap + t0 + t;
                 sketch_one(R, b, d, k + src, sketches + dst * W);
                 quantize_one(v + src, d, G, codes + dst * (d / 2), scale + dst * ng, zero + dst * ng);
+            }
+}
+
+/*
+ * ---------- "1-bit key only" variant (Table V ablation, Sec. VI-E): sketched keys, fp16 values ----------
+ * Keys and scores are exactly as above (Eq.(2), Eq.(3)); values skip Eq.(4) and are kept as IEEE binary16
+ * numbers (the paper's FP16 value storage), so Eq.(5) reads  out = softmax(alpha / tau) fp16(V).
+ * A stored value is the input rounded to nearest-even binary16 (unchanged if the input already is fp16).
+ */
+void h1bkv_oracle_decode_one_f16v(const uint64_t *sq /*[W]*/, const uint64_t *sk /*[T][W]*/,
+                                  const uint16_t *v16 /*[T][d] fp16 bit patterns*/, int64_t T, int b, int d,
+                                  double tau, float *out /*[d]*/) {
+    int W = b / 64;
+    double acc[1024];
+    for (int c = 0; c < d; ++c) acc[c] = 0.0;
+    if (T <= 0) {
+        for (int c = 0; c < d; ++c) out[c] = 0.0f;
+        return;
+    }
+    double m = -2.0;
+    for (int64_t t = 0; t < T; ++t) {
+        int h = 0;
+        for (int w = 0; w < W; ++w) h += __builtin_popcountll(sq[w] ^ sk[t * W + w]);
+        double alpha = (double)(b - 2 * h) / (double)b;
+        if (alpha > m) m = alpha;
+    }
+    double l = 0.0;
+    for (int64_t t = 0; t < T; ++t) {
+        int h = 0;
+        for (int w = 0; w < W; ++w) h += __builtin_popcountll(sq[w] ^ sk[t * W + w]);
+        double alpha = (double)(b - 2 * h) / (double)b;
+        double p = exp((alpha - m) / tau);
+        l += p;
+        for (int c = 0; c < d; ++c) acc[c] += p * (double)h1bkv_oracle_half_to_float(v16[t * d + c]);
+    }
+    for (int c = 0; c < d; ++c) out[c] = (float)(acc[c] / l);
+}
+
+/* Batch forms in canonical layout: sketches [B][H_kv][Tcap][W], values [B][H_kv][Tcap][d] fp16 bit patterns. */
+void h1bkv_oracle_decode_batch_f16v(const float *R, int b, int d, int B, int Hq, int Hkv, int64_t Tcap,
+                                    const int32_t *ctx_len, const float *q, const uint64_t *sketches,
+                                    const uint16_t *v16, double tau, float *out) {
+    int W = b / 64, r = Hq / Hkv;
+#pragma omp parallel for schedule(dynamic, 1) collapse(2)
+    for (int s = 0; s < B; ++s)
+        for (int h = 0; h < Hq; ++h) {
+            uint64_t sq[16];
+            sketch_one(R, b, d, q + ((int64_t)s * Hq + h) * d, sq);
+            int64_t base = ((int64_t)s * Hkv + h / r) * Tcap;
+            h1bkv_oracle_decode_one_f16v(sq, sketches + base * W, v16 + base * d, ctx_len[s], b, d, tau,
+                                         out + ((int64_t)s * Hq + h) * d);
+        }
+}
+
+void h1bkv_oracle_append_batch_f16v(const float *R, int b, int d, int B, int Hkv, int64_t Tcap, int64_t t0,
+                                    int64_t n_new, const float *k, const float *v, uint64_t *sketches,
+                                    uint16_t *v16) {
+    int W = b / 64;
+#pragma omp parallel for schedule(dynamic, 16) collapse(3)
+    for (int s = 0; s < B; ++s)
+        for (int h = 0; h < Hkv; ++h)
+            for (int64_t t = 0; t < n_new; ++t) {
+                int64_t src = (((int64_t)s * n_new + t) * Hkv + h) * d;
+                int64_t dst = ((int64_t)s * Hkv + h) * Tcap + t0 + t;
+                sketch_one(R, b, d, k + src, sketches + dst * W);
+                for (int c = 0; c < d; ++c) v16[dst * d + c] = h1bkv_oracle_float_to_half(v[src + c]);
             }
 }
 
