@@ -37,6 +37,8 @@ def parse_args():
     ap.add_argument("--workload", default="decode_b16_32k",
                     help="decode_b16_32k (default, the graded configuration) | decode_7b_8k | decode_gqa_128k | tiny")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
+    ap.add_argument("--value-bits", type=int, default=4, choices=(4, 16),
+                    help="16: the '1-bit key only' variant (fp16 values, Table V ablation) instead of the method's 4-bit values")
     ap.add_argument("--chunk", type=int, default=0, help="decode chunk override (tokens, multiple of 256)")
     ap.add_argument("--per-token-layers", type=int, default=0, metavar="L",
                     help="secondary line: per-token attention latency of L layers (one cache each), every layer one fused "
@@ -70,14 +72,14 @@ def fill_cache(torch, B, wl, w, cache, n_tokens, workers):
         t0 += n
 
 
-def cpu_baseline(wl, w, tau, workers):
+def cpu_baseline(wl, w, tau, workers, value_bits=4):
     """The oracle, as it stands, on the host cores: one sequence of the workload (all heads, full context).
     Its cache is built by the oracle's own append (untimed set-up); the timed step is the same as the GPU's:
     append one token for every head, then decode over the whole context."""
     from oracle import cref
     R = wl.projection(w.sketch_bits, w.head_dim)
     T = w.context
-    oc = cref.Cache(R, 1, w.n_kv_heads, T, w.group_size)
+    oc = cref.Cache(R, 1, w.n_kv_heads, T, w.group_size, value_bits=value_bits)
     slab = wl.SLAB_TOKENS
     t0 = 0
     while t0 < T - 1:
@@ -265,7 +267,12 @@ def main():
     pages_per_seq = (T + 255) // 256 + 1
     cache = B.Cache(n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim, sketch_bits=w.sketch_bits,
                     group_size=w.group_size, dtype=w.dtype, max_seqs=Bsz, max_pages=Bsz * pages_per_seq,
-                    max_pages_per_seq=pages_per_seq, R=R)
+                    max_pages_per_seq=pages_per_seq, R=R, value_bits=args.value_bits)
+    f16v = args.value_bits == 16
+    r = w.n_q_heads // w.n_kv_heads
+    mfma = not f16v and r >= 3 and w.head_dim <= 128 and w.head_dim // w.group_size <= 4 and w.sketch_bits <= 256
+    split_kernel = "decode_split_f16v_kernel" if f16v else ("decode_split_mfma_kernel" if mfma else "decode_split_kernel")
+    record_bytes = w.sketch_bits // 8 + 2 * w.head_dim if f16v else w.record_bytes
     if args.chunk:
         B.check(B.h1bkv_set_decode_chunk(cache.h, args.chunk))
     t_fill = time.perf_counter()
@@ -333,7 +340,7 @@ def main():
     kernel_ms["decode_split"] = float(split_ms_all.mean())
 
     records = Bsz * w.n_kv_heads * T
-    alg_bytes = records * w.record_bytes                      # sketch + nibbles + scale/zero of every cached record
+    alg_bytes = records * record_bytes                        # sketch + nibbles + scale/zero (or fp16 values) of every cached record
     split_ms = kernel_ms["decode_split"]
     achieved = alg_bytes / (split_ms * 1e-3) / 1e9
     result = {
@@ -351,10 +358,10 @@ def main():
         "data": "synthetic",
         "config": {"workload": w.name, "batch": Bsz, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
                    "head_dim": w.head_dim, "context": T, "sketch_bits": w.sketch_bits, "group_size": w.group_size,
-                   "in_dtype": w.dtype, "tau": tau, "record_bytes": w.record_bytes,
+                   "in_dtype": w.dtype, "tau": tau, "record_bytes": record_bytes, "value_bits": args.value_bits,
                    "step": "append 1 token/sequence + decode attention over the full context"},
-        "roofline": {"bound": "hbm", "kernel": "decode_split_kernel", "achieved": achieved, "peak": HBM_PEAK_GBPS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic_from_profiles(w.name),
+        "roofline": {"bound": "hbm", "kernel": split_kernel, "achieved": achieved, "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic_from_profiles(w.name + ("_f16v" if f16v else "")),
                      "algorithmic_bytes_per_launch": alg_bytes, "kernel_ms": split_ms},
         "records_per_s": records / (ms_per_step * 1e-3),
         "kernel_ms": kernel_ms,
@@ -362,7 +369,7 @@ def main():
         "fill_s": t_fill,
     }
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(wl, w, tau, workers)
+        result["cpu_baseline"] = cpu_baseline(wl, w, tau, workers, args.value_bits)
     print(json.dumps(result))
 
 

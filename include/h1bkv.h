@@ -52,7 +52,9 @@ enum {
  *   head_dim in {64, 128, 256};  sketch_bits in {64, 128, 256, 512} (the paper's ablation puts the
  *   useful lower bound at b = 64, Sec. VI-E/F);  group_size in {32, 64, 128} and dividing head_dim;
  *   in_dtype H1BKV_F32 or H1BKV_F16;  page_tokens 0 (= default) or H1BKV_PAGE_TOKENS;
- *   max_seqs, max_pages, max_pages_per_seq >= 1.
+ *   max_seqs, max_pages, max_pages_per_seq >= 1;
+ *   value_bits 0 or 4 (= the method: 4-bit group-quantised values, Eq.(4)) or 16 (the "1-bit key only" ablation of
+ *   Table V / Sec. VI-E: keys are sketches, values are kept as fp16; group_size is then unused but still checked).
  * device: HIP device ordinal, or H1BKV_DEVICE_NONE for a bookkeeping-only handle that runs all
  * validation and page accounting but never touches a GPU (capacity planning, host-side tests).
  */
@@ -64,6 +66,7 @@ typedef struct {
     int32_t page_tokens;
     int32_t max_seqs, max_pages, max_pages_per_seq;
     int32_t device;
+    int32_t value_bits;
 } h1bkv_config;
 
 /* Library version, major*10000 + minor*100 + patch. */
@@ -76,7 +79,8 @@ const char *h1bkv_strerror(int code);
  * Device bytes the caller must provide as the pool for this geometry (0 if cfg is NULL or invalid).
  * The pool holds R and its transpose, the block table, and three planes per page:
  * sketches [page][H_kv][256][W] u64 (Eq.(2)), codes [page][H_kv][256][d/2] u8 and
- * {fp16 scale, fp16 zero} pairs [page][H_kv][256][n_g] (Eq.(4)).
+ * {fp16 scale, fp16 zero} pairs [page][H_kv][256][n_g] (Eq.(4)).  With value_bits = 16 the last two planes are
+ * replaced by one plane of fp16 values [page][H_kv][256][d].
  */
 size_t h1bkv_pool_bytes(const h1bkv_config *cfg);
 
@@ -108,7 +112,8 @@ int h1bkv_truncate_seq(h1bkv_cache *c, int32_t seq_id, int32_t new_len);  /* 0 <
  *   sketch bit i = ( sum_j R[i][j] k[j] >= 0 ), the sum taken in fp32 as a chain of fused multiply-adds
  *   over j = 0..d-1 from +0; bit i is stored in word i/64 at bit position i%64;
  *   per group of G channels of v: zero = fp16(min), scale = fp16((max - min)/15),
- *   code = clamp(round_half_even((v - zero)/scale), 0, 15) in fp32 (code 0 when scale is 0).
+ *   code = clamp(round_half_even((v - zero)/scale), 0, 15) in fp32 (code 0 when scale is 0);
+ *   with value_bits = 16 instead: the value rounded to nearest-even fp16 (an fp16 input is stored unchanged).
  * k_dev, v_dev: [n_seqs][n_new][n_kv_heads][d] in in_dtype, addressed with the given strides (in
  * elements; the channel stride is 1).  Inputs must be finite.  Pages are taken from the free list as
  * needed (H1BKV_ENOSPACE if they do not suffice; then nothing is appended).
@@ -128,7 +133,7 @@ size_t h1bkv_decode_workspace_bytes(const h1bkv_cache *c, int32_t n_seqs, int32_
  * and every query head h, with T = current length of s:
  *   s_q = sign(R q) (same recipe as the keys);  alpha_t = (b - 2 popcount(s_q xor s_t)) / b;
  *   out = sum_t softmax_t(alpha_t / tau) * (scale_t * code_t + zero_t)   over all T cached tokens
- * (no mask; T == 0 gives zeros).  q_dev [n_seqs][n_q_heads][d] in in_dtype, dense;
+ * (no mask; T == 0 gives zeros; with value_bits = 16 the bracket is the stored fp16 value).  q_dev [n_seqs][n_q_heads][d] in in_dtype, dense;
  * out_dev [n_seqs][n_q_heads][d] fp32; tau > 0 and finite.  The context is processed in chunks whose
  * partial (max, sum, weighted sum) results are merged by a log-sum-exp step; accumulation is fp32.
  * workspace_dev: >= h1bkv_decode_workspace_bytes(c, n_seqs, longest T), 256-byte aligned.
@@ -160,6 +165,8 @@ int h1bkv_set_decode_chunk(h1bkv_cache *c, int32_t chunk_tokens);
  * Canonical, layout-independent view of cached records (synchronous: waits for the device first).
  * Tokens [t0, t0+n) of (seq_id, kv_head) to host arrays: sketch_out [n][W] u64, codes_out [n][d/2] u8
  * (channel 2m low nibble, 2m+1 high nibble of byte m), scale_out / zero_out [n][n_g] fp16 bit patterns.
+ * With value_bits = 16, codes_out / codes_in is the value plane instead, [n][d] fp16 bit patterns (2d bytes per
+ * token), and scale/zero must be NULL (H1BKV_EINVAL otherwise).
  * Any output pointer may be NULL to skip that plane.  h1bkv_import_tokens is the mirror image and
  * overwrites existing positions; h1bkv_extend_seq reserves n_new uninitialised positions (pages and
  * block-table update on `hip_stream`) so that a saved cache can be restored with import.

@@ -25,7 +25,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "lib", "libh
 
 class h1bkv_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_q_heads", "n_kv_heads", "head_dim", "sketch_bits", "group_size", "in_dtype",
-                                         "page_tokens", "max_seqs", "max_pages", "max_pages_per_seq", "device")]
+                                         "page_tokens", "max_seqs", "max_pages", "max_pages_per_seq", "device", "value_bits")]
 
 
 class H1BKVError(RuntimeError):
@@ -182,9 +182,14 @@ def h1bkv_set_decode_chunk(h, chunk_tokens: int) -> int:
     return lib().h1bkv_set_decode_chunk(h, chunk_tokens)
 
 
-def h1bkv_export_tokens(h, seq_id: int, kv_head: int, t0: int, n: int, W: int, d: int, n_g: int):
-    """Returns (code, sketches [n][W] u64, codes [n][d/2] u8, scale [n][n_g] u16, zero [n][n_g] u16)."""
+def h1bkv_export_tokens(h, seq_id: int, kv_head: int, t0: int, n: int, W: int, d: int, n_g: int, value_bits: int = 4):
+    """Returns (code, sketches [n][W] u64, codes [n][d/2] u8, scale [n][n_g] u16, zero [n][n_g] u16); for a cache
+    with fp16 values (value_bits = 16): (code, sketches, values [n][d] u16 fp16 bit patterns, None, None)."""
     sk = np.zeros((n, W), dtype=np.uint64)
+    if value_bits == 16:
+        vals = np.zeros((n, d), dtype=np.uint16)
+        rc = lib().h1bkv_export_tokens(h, seq_id, kv_head, t0, n, _np_ptr(sk), _np_ptr(vals), None, None)
+        return rc, sk, vals, None, None
     codes = np.zeros((n, d // 2), dtype=np.uint8)
     scale = np.zeros((n, n_g), dtype=np.uint16)
     zero = np.zeros((n, n_g), dtype=np.uint16)
@@ -194,7 +199,8 @@ def h1bkv_export_tokens(h, seq_id: int, kv_head: int, t0: int, n: int, W: int, d
 
 def h1bkv_import_tokens(h, seq_id: int, kv_head: int, t0: int, sk, codes, scale, zero) -> int:
     sk = None if sk is None else np.ascontiguousarray(sk, dtype=np.uint64)
-    codes = None if codes is None else np.ascontiguousarray(codes, dtype=np.uint8)
+    if codes is not None:      # u8 nibble pairs, or u16 fp16 bit patterns for a cache with fp16 values
+        codes = np.ascontiguousarray(codes, dtype=np.uint16 if np.asarray(codes).dtype == np.uint16 else np.uint8)
     scale = None if scale is None else np.ascontiguousarray(scale, dtype=np.uint16)
     zero = None if zero is None else np.ascontiguousarray(zero, dtype=np.uint16)
     n = next(a.shape[0] for a in (sk, codes, scale, zero) if a is not None)
@@ -237,9 +243,14 @@ class Cache:
     """Convenience owner of a handle plus the torch buffers it needs.  Forwards to the functions above."""
 
     def __init__(self, *, n_q_heads: int, n_kv_heads: int, head_dim: int, sketch_bits: int, group_size: int, dtype: str,
-                 max_seqs: int, max_pages: int, max_pages_per_seq: int, R: np.ndarray, device: int = 0):
+                 max_seqs: int, max_pages: int, max_pages_per_seq: int, R: np.ndarray, device: int = 0, value_bits: int = 4,
+                 pool_fill: Optional[int] = None):
+        """pool_fill: byte value written over the whole pool before the handle is created (never-written slots then hold
+        that pattern instead of whatever the allocator returned)."""
         self.cfg = h1bkv_config(n_q_heads, n_kv_heads, head_dim, sketch_bits, group_size,
-                                H1BKV_F16 if dtype == "f16" else H1BKV_F32, 0, max_seqs, max_pages, max_pages_per_seq, device)
+                                H1BKV_F16 if dtype == "f16" else H1BKV_F32, 0, max_seqs, max_pages, max_pages_per_seq, device,
+                                value_bits)
+        self.value_bits = value_bits
         self.W, self.d, self.n_g = sketch_bits // 64, head_dim, head_dim // group_size
         self.pool = None
         self.workspace = None
@@ -250,6 +261,9 @@ class Cache:
             import torch
             torch.cuda.set_device(device)
             self.pool = torch.empty(nbytes, dtype=torch.uint8, device=f"cuda:{device}")
+            if pool_fill is not None:
+                self.pool.fill_(pool_fill)
+                torch.cuda.synchronize()
         rc, self.h = h1bkv_create(self.cfg, self.pool, nbytes, R)
         check(rc, "h1bkv_create")
 
@@ -283,6 +297,6 @@ class Cache:
         return out
 
     def export(self, seq_id: int, kv_head: int, t0: int, n: int):
-        rc, sk, codes, scale, zero = h1bkv_export_tokens(self.h, seq_id, kv_head, t0, n, self.W, self.d, self.n_g)
+        rc, sk, codes, scale, zero = h1bkv_export_tokens(self.h, seq_id, kv_head, t0, n, self.W, self.d, self.n_g, self.value_bits)
         check(rc, "h1bkv_export_tokens")
         return sk, codes, scale, zero

@@ -25,6 +25,7 @@ SOURCES = {
     "kernels_misc.hip": [],
     "kernels_append.hip": ["-ffp-contract=off"],
     "kernels_decode.hip": [],
+    "kernels_decode_f16v.hip": [],
     # accumulators of the MFMA kernel stay in ordinary VGPRs: they are also touched by vector-ALU code (rescaling)
     "kernels_decode_mfma.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
 }

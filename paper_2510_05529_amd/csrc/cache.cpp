@@ -30,6 +30,7 @@ bool config_ok(const h1bkv_config *c) {
     if (c->page_tokens != 0 && c->page_tokens != kPage) return false;
     if (c->max_seqs < 1 || c->max_pages < 1 || c->max_pages_per_seq < 1) return false;
     if (c->device < H1BKV_DEVICE_NONE) return false;
+    if (c->value_bits != 0 && c->value_bits != 4 && c->value_bits != 16) return false;
     return true;
 }
 
@@ -42,8 +43,9 @@ Layout make_layout(const h1bkv_config &c) {
     L.off_RT = o;      o = align_up(o + b * d * sizeof(float));
     L.off_bt = o;      o = align_up(o + (size_t)c.max_seqs * c.max_pages_per_seq * sizeof(int32_t));
     L.off_sketch = o;  o = align_up(o + rec * W * 8);
-    L.off_codes = o;   o = align_up(o + rec * (d / 2));
-    L.off_meta = o;    o = align_up(o + rec * ng * 4);
+    const bool f16v = c.value_bits == 16;
+    L.off_codes = o;   o = align_up(o + rec * (f16v ? 2 * d : d / 2));
+    L.off_meta = o;    o = align_up(o + (f16v ? 0 : rec * ng * 4));
     L.total = o;
     return L;
 }
@@ -236,7 +238,8 @@ int h1bkv_create(const h1bkv_config *cfg, void *pool_dev, size_t pool_bytes, con
     c->W = cfg->sketch_bits / 64;
     c->ng = cfg->head_dim / cfg->group_size;
     c->r = cfg->n_q_heads / cfg->n_kv_heads;
-    c->code_layout = mfma_decode_supported(cfg->n_q_heads / cfg->n_kv_heads, cfg->head_dim, cfg->group_size, cfg->sketch_bits) ? 1 : 0;
+    c->cfg.value_bits = cfg->value_bits == 16 ? 16 : 4;
+    c->code_layout = c->cfg.value_bits == 16 ? 2 : mfma_decode_supported(cfg->n_q_heads / cfg->n_kv_heads, cfg->head_dim, cfg->group_size, cfg->sketch_bits) ? 1 : 0;
     c->dry = dry;
     c->pool = static_cast<char *>(pool_dev);
     const size_t nR = (size_t)cfg->sketch_bits * cfg->head_dim;
@@ -475,7 +478,9 @@ static int enqueue_decode(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n
         }
         {
             Timed t(c, H1BKV_K_DECODE_SPLIT, st);
-            const hipError_t e = c->code_layout == 1 ? launch_decode_split_mfma(a, desc, s0, n, st) : launch_decode_split(a, desc, s0, n, st);
+            const hipError_t e = c->code_layout == 2   ? launch_decode_split_f16v(a, desc, s0, n, st)
+                                 : c->code_layout == 1 ? launch_decode_split_mfma(a, desc, s0, n, st)
+                                                       : launch_decode_split(a, desc, s0, n, st);
             if (e != hipSuccess) return H1BKV_EHIP;
         }
         {
@@ -518,11 +523,12 @@ static int xfer_tokens(const h1bkv_cache *c, int32_t seq_id, int32_t kv_head, in
     if (t0 < 0 || n < 0 || (int64_t)t0 + n > c->seq_len[seq_id]) return H1BKV_ERANGE;
     if (c->dry) return H1BKV_ENODEVICE;
     if ((scale == nullptr) != (zero == nullptr)) return H1BKV_ENULL;
+    if (c->code_layout == 2 && scale) return H1BKV_EINVAL;          // fp16 values carry no scale/zero
     int rc = check_device(c);
     if (rc != H1BKV_OK) return rc;
     if (hipDeviceSynchronize() != hipSuccess) return H1BKV_EHIP;
     const PoolView pv = c->view();
-    const size_t W = c->W, hb = c->cfg.head_dim / 2, ng = c->ng;
+    const size_t W = c->W, hb = c->code_layout == 2 ? 2 * (size_t)c->cfg.head_dim : c->cfg.head_dim / 2, ng = c->ng;
     std::vector<uint32_t> meta;
     const hipMemcpyKind kind = to_host ? hipMemcpyDeviceToHost : hipMemcpyHostToDevice;
     int32_t t = t0;
@@ -537,7 +543,7 @@ static int xfer_tokens(const h1bkv_cache *c, int32_t seq_id, int32_t kv_head, in
             void *dev = pv.sketch + rec * W;
             ok = ok && hipMemcpy(to_host ? (void *)(sk + i * W) : dev, to_host ? dev : (void *)(sk + i * W), run * W * 8, kind) == hipSuccess;
         }
-        if (codes && c->code_layout == 0) {
+        if (codes && c->code_layout != 1) {
             void *dev = pv.codes + rec * hb;
             ok = ok && hipMemcpy(to_host ? (void *)(codes + i * hb) : dev, to_host ? dev : (void *)(codes + i * hb), run * hb, kind) == hipSuccess;
         }

@@ -40,7 +40,8 @@ struct PoolView {
     uint32_t *meta;          // [page][H_kv][256][n_g]  low half = fp16 scale, high half = fp16 zero
     int32_t max_pages_per_seq;
     int32_t n_kv_heads, n_q_heads, head_dim, sketch_bits, group_size;
-    int32_t code_layout;     // 0: record-major nibbles; 1: token-interleaved words (see below)
+    int32_t code_layout;     // 0: record-major nibbles; 1: token-interleaved words (see below);
+                             // 2: no codes -- `codes` holds fp16 values [page][H_kv][256][d], `meta` is unused
 };
 
 // Code plane layout 1 (used when several query heads share a KV head and the weighted sum runs on the matrix
@@ -102,6 +103,7 @@ hipError_t launch_append(const AppendArgs &a, const BatchDesc &desc, int n_seqs,
 hipError_t launch_qsketch(const DecodeArgs &a, int seq0, int n_seqs, hipStream_t st);
 hipError_t launch_decode_split(const DecodeArgs &a, const BatchDesc &desc, int seq0, int n_seqs, hipStream_t st);
 hipError_t launch_decode_split_mfma(const DecodeArgs &a, const BatchDesc &desc, int seq0, int n_seqs, hipStream_t st);
+hipError_t launch_decode_split_f16v(const DecodeArgs &a, const BatchDesc &desc, int seq0, int n_seqs, hipStream_t st);
 hipError_t launch_merge(const DecodeArgs &a, const BatchDesc &desc, int seq0, int n_seqs, hipStream_t st);
 hipError_t launch_stream_copy(void *dst, const void *src, size_t n_bytes, hipStream_t st);
 hipError_t launch_stream_read(const void *src, size_t n_bytes, void *sink, hipStream_t st);

@@ -20,7 +20,8 @@
 // Code plane layouts (PoolView::code_layout):
 //   0  record-major: the 32 codes of a slice are one 16-byte store; byte m of a record = channels 2m (low), 2m+1 (high);
 //   1  token-interleaved: per block of 8 tokens one 32-bit word per channel with that channel's 8 codes
-//      (code_word_index / code_nibble_pos); words of partially filled blocks are read-modified-written.
+//      (code_word_index / code_nibble_pos); words of partially filled blocks are read-modified-written;
+//   2  the "1-bit key only" variant (Table V): no quantiser, the plane holds the values as fp16, record-major.
 #include <hip/hip_fp16.h>
 
 #include "internal.h"
@@ -139,10 +140,25 @@ __device__ __forceinline__ void append_body(const AppendArgs &a, const BatchDesc
             }
         }
 
+        // ---- fp16-value variant: no quantiser, the value rounded to nearest-even fp16 ----
+        if (pv.code_layout == 2) {
+            __half *values = reinterpret_cast<__half *>(pv.codes);
+            for (int e = tid * 8; e < tile * D; e += kThreads * 8) {
+                const int rl = e / D, ch = e % D;
+                if (!valid_slot(rl)) continue;
+                float x[8];
+                load8(vbase + src_off[rl] + ch, x);
+                __half2 h[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) h[i] = __halves2half2(__float2half_rn(x[2 * i]), __float2half_rn(x[2 * i + 1]));
+                *reinterpret_cast<uint4 *>(values + dst[rl] * D + ch) = *reinterpret_cast<const uint4 *>(h);
+            }
+        }
+
         // ---- Eq.(4): one lane per (slot, 32-channel slice) ----
         constexpr int LPT = D / 32;
         const int lanes_per_group = G / 32;
-        for (int item = tid; item < ((tile * LPT + 63) & ~63); item += kThreads) {   // whole waves run the loop (shuffles below)
+        for (int item = tid; pv.code_layout != 2 && item < ((tile * LPT + 63) & ~63); item += kThreads) {   // whole waves run the loop (shuffles below)
             const int rl = item / LPT, slice = item % LPT;
             const bool valid = rl < tile && valid_slot(rl);
             float x[32];

@@ -13,12 +13,12 @@ def torch_cuda():
     return torch
 
 
-def make_cache(w: wl.Workload, R, max_seqs=None, extra_pages=2):
+def make_cache(w: wl.Workload, R, max_seqs=None, extra_pages=2, value_bits=4, pool_fill=None):
     pages_per_seq = (w.context + 255) // 256 + extra_pages
     max_seqs = max_seqs or w.batch
     return B.Cache(n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim, sketch_bits=w.sketch_bits,
                    group_size=w.group_size, dtype=w.dtype, max_seqs=max_seqs, max_pages=max_seqs * pages_per_seq,
-                   max_pages_per_seq=pages_per_seq, R=R)
+                   max_pages_per_seq=pages_per_seq, R=R, value_bits=value_bits, pool_fill=pool_fill)
 
 
 def to_dev(a: np.ndarray):
@@ -42,6 +42,10 @@ def assert_cache_equal(cache: B.Cache, ocache, seq_ids, n_tokens, heads=None):
         for h in heads:
             sk, codes, scale, zero = cache.export(s, h, 0, n_tokens)
             assert np.array_equal(sk, ocache.sketches[i, h, :n_tokens]), f"sketch mismatch seq {s} head {h}"
+            if ocache.value_bits == 16:
+                assert scale is None and zero is None
+                assert np.array_equal(codes, ocache.v16[i, h, :n_tokens]), f"fp16 value mismatch seq {s} head {h}"
+                continue
             assert np.array_equal(zero, ocache.zero[i, h, :n_tokens]), f"zero mismatch seq {s} head {h}"
             assert np.array_equal(scale, ocache.scale[i, h, :n_tokens]), f"scale mismatch seq {s} head {h}"
             assert np.array_equal(codes, ocache.codes[i, h, :n_tokens]), f"codes mismatch seq {s} head {h}"

@@ -159,3 +159,14 @@ def test_decode_step_validates_both_halves_before_changing_anything():
     assert B.h1bkv_seq_len(h, 0) == (0, 10) and B.h1bkv_seq_len(h, 1) == (0, 10) and B.h1bkv_free_pages(h) == free
     assert B.lib().h1bkv_decode_step(None, None, 1, None, None, 512, 128, None, 0.1, None, None, 0, None) == B.H1BKV_ENULL
     B.h1bkv_destroy(h)
+
+
+def test_value_bits_configuration():
+    """The fp16-value variant replaces the code and scale/zero planes (d/2 + 4 n_g bytes per record) by 2d bytes."""
+    c4, c16, cbad = cfg(), cfg(value_bits=16), cfg(value_bits=8)
+    assert B.h1bkv_pool_bytes(cbad) == 0
+    assert B.h1bkv_pool_bytes(cfg(value_bits=0)) == B.h1bkv_pool_bytes(cfg(value_bits=4)) == B.h1bkv_pool_bytes(c4)
+    rec = c4.max_pages * c4.n_kv_heads * 256
+    d, ng = c4.head_dim, c4.head_dim // c4.group_size
+    diff = B.h1bkv_pool_bytes(c16) - B.h1bkv_pool_bytes(c4)
+    assert abs(diff - rec * (2 * d - d // 2 - 4 * ng)) <= 512       # plane starts are 256-byte aligned
