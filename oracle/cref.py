@@ -26,7 +26,8 @@ def lib():
         for name in ("h1bkv_oracle_sketch", "h1bkv_oracle_quantize", "h1bkv_oracle_dequantize",
                      "h1bkv_oracle_hamming", "h1bkv_oracle_decode_one", "h1bkv_oracle_decode_batch",
                      "h1bkv_oracle_append_batch", "h1bkv_oracle_decode_one_f16v",
-                     "h1bkv_oracle_decode_batch_f16v", "h1bkv_oracle_append_batch_f16v"):
+                     "h1bkv_oracle_decode_batch_f16v", "h1bkv_oracle_append_batch_f16v",
+                     "h1bkv_oracle_prefill_batch"):
             getattr(L, name).restype = None
         _lib = L
     return _lib
@@ -175,4 +176,19 @@ class Cache:
                                         C.c_int(self.B), C.c_int(Hq), C.c_int(self.Hkv), C.c_int64(self.Tcap),
                                         _p(lens), _p(q), _p(self.sketches), _p(self.codes), _p(self.scale),
                                         _p(self.zero), C.c_double(tau), _p(out))
+        return out
+
+    def prefill(self, q: np.ndarray, tau: float, ctx_len=None) -> np.ndarray:
+        """q [B][n_q][H_q][d]: the last n_q cached positions of every sequence attend causally (each to the tokens up
+        to and including its own position) -> out [B][n_q][H_q][d] float32."""
+        assert self.value_bits == 4
+        q = _f32(q)
+        n_q, Hq = q.shape[1], q.shape[2]
+        lens = np.full(self.B, self.len, dtype=np.int32) if ctx_len is None else np.ascontiguousarray(ctx_len, dtype=np.int32)
+        assert (lens >= n_q).all()
+        out = np.zeros((self.B, n_q, Hq, self.d), dtype=np.float32)
+        lib().h1bkv_oracle_prefill_batch(_p(self.R), C.c_int(self.b), C.c_int(self.d), C.c_int(self.G), C.c_int(self.B),
+                                         C.c_int(Hq), C.c_int(self.Hkv), C.c_int64(self.Tcap), _p(lens), C.c_int64(n_q),
+                                         _p(q), _p(self.sketches), _p(self.codes), _p(self.scale), _p(self.zero),
+                                         C.c_double(tau), _p(out))
         return out

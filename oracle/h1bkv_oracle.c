@@ -232,6 +232,32 @@ void h1bkv_oracle_decode_batch(const float *R, int b, int d, int G, int B, int H
 }
 
 /*
+ * Prefill attention (Eq.(3) + Eq.(5) applied to every position of a prompt chunk): the last n_q cached positions
+ * of each sequence are the queries; query i of sequence s (absolute position ctx_len[s] - n_q + i) attends to the
+ * cached tokens up to and including its own position, i.e. to the first ctx_len[s] - n_q + i + 1 tokens -- the
+ * decode step it would have seen had the prompt been fed one token at a time.
+ *   q [B][n_q][H_q][d] (fp32 values), out [B][n_q][H_q][d]; planes as in h1bkv_oracle_decode_batch.
+ */
+void h1bkv_oracle_prefill_batch(const float *R, int b, int d, int G, int B, int Hq, int Hkv, int64_t Tcap,
+                                const int32_t *ctx_len, int64_t n_q, const float *q, const uint64_t *sketches,
+                                const uint8_t *codes, const uint16_t *scale, const uint16_t *zero, double tau,
+                                float *out) {
+    int W = b / 64, ng = d / G, r = Hq / Hkv;
+#pragma omp parallel for schedule(dynamic, 4) collapse(3)
+    for (int s = 0; s < B; ++s)
+        for (int64_t i = 0; i < n_q; ++i)
+            for (int h = 0; h < Hq; ++h) {
+                uint64_t sq[16];
+                int64_t vec = ((int64_t)s * n_q + i) * Hq + h;
+                sketch_one(R, b, d, q + vec * d, sq);
+                int64_t base = ((int64_t)s * Hkv + h / r) * Tcap;
+                int64_t visible = (int64_t)ctx_len[s] - n_q + i + 1;
+                h1bkv_oracle_decode_one(sq, sketches + base * W, codes + base * (d / 2), scale + base * ng,
+                                        zero + base * ng, visible, b, d, G, tau, out + vec * d);
+            }
+}
+
+/*
  * Cache append for a batch in boundary layout k, v [B][n_new][H_kv][d] (fp32 values) into canonical
  * planes at token positions [t0, t0+n_new): sketches [B][H_kv][Tcap][W] etc.
  */
