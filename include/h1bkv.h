@@ -155,6 +155,23 @@ int h1bkv_decode_step(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n_seq
                       float *out_dev, void *workspace_dev, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * Prefill attention (Sec. IV-A Eq.(3), Sec. IV-C Eq.(5) applied to every position of a prompt chunk): the n_q most
+ * recent cached positions of every sequence are the queries.  Query i of sequence s (absolute position
+ * len_s - n_q + i) attends to the cached tokens up to and including its own position, with the same scores, softmax
+ * and dequantised values as h1bkv_decode_attn -- the result of feeding the chunk one token at a time
+ * (append the chunk's keys and values with h1bkv_append_kv first).  Every sequence must hold at least n_q tokens
+ * (H1BKV_ERANGE otherwise).  q_dev [n_seqs][n_q][n_q_heads][d] in in_dtype with strides in elements (channel
+ * stride 1, rows 16-byte aligned); out_dev [n_seqs][n_q][n_q_heads][d] fp32, dense.  The weighted sum runs on the
+ * matrix cores with fp16 operands (weights and dequantised values rounded to fp16, fp32 accumulation).
+ * Supported for 4-bit values and head_dim <= 128 (H1BKV_ESHAPE otherwise).
+ * workspace_dev: >= h1bkv_prefill_workspace_bytes(c, n_seqs, n_q) (the chunk's query sketches), 256-byte aligned.
+ */
+size_t h1bkv_prefill_workspace_bytes(const h1bkv_cache *c, int32_t n_seqs, int32_t n_q);
+int h1bkv_prefill_attn(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n_seqs, int32_t n_q, const void *q_dev,
+                       int64_t stride_seq, int64_t stride_tok, int64_t stride_head, float tau, float *out_dev,
+                       void *workspace_dev, size_t workspace_bytes, void *hip_stream);
+
+/*
  * Tuning override for the context chunk of h1bkv_decode_attn: tokens per chunk, a multiple of
  * H1BKV_PAGE_TOKENS up to 8192, or 0 for the built-in choice.  Results do not depend on it beyond
  * fp32 summation order.
@@ -186,7 +203,8 @@ int h1bkv_extend_seq(h1bkv_cache *c, int32_t seq_id, int32_t n_new, void *hip_st
  * of `kernel` to ms_out (at most cap values) and their number to n_out, then clears that kind's records.
  * capacity == 0 disables recording and releases the events.
  */
-enum { H1BKV_K_APPEND = 0, H1BKV_K_QSKETCH = 1, H1BKV_K_DECODE_SPLIT = 2, H1BKV_K_MERGE = 3, H1BKV_K_COUNT = 4 };
+enum { H1BKV_K_APPEND = 0, H1BKV_K_QSKETCH = 1, H1BKV_K_DECODE_SPLIT = 2, H1BKV_K_MERGE = 3, H1BKV_K_PREFILL = 4,
+       H1BKV_K_COUNT = 5 };
 int h1bkv_profile_enable(h1bkv_cache *c, int32_t capacity, uint32_t kernel_mask);
 /* Bracket only every `stride`-th launch of each selected kind (stride >= 1; 1 = every launch, the default): an
  * event pair costs a few microseconds on the stream, which a benchmark of sub-millisecond steps can thin out. */

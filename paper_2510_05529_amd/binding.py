@@ -18,7 +18,7 @@ H1BKV_EINVAL, H1BKV_ENULL, H1BKV_ESHAPE, H1BKV_ENOSPACE = -1, -2, -3, -4
 H1BKV_ERANGE, H1BKV_EWORKSPACE, H1BKV_EHIP, H1BKV_ENODEVICE = -5, -6, -7, -8
 H1BKV_DEVICE_NONE = -1
 H1BKV_PAGE_TOKENS = 256
-H1BKV_K_APPEND, H1BKV_K_QSKETCH, H1BKV_K_DECODE_SPLIT, H1BKV_K_MERGE = 0, 1, 2, 3
+H1BKV_K_APPEND, H1BKV_K_QSKETCH, H1BKV_K_DECODE_SPLIT, H1BKV_K_MERGE, H1BKV_K_PREFILL = 0, 1, 2, 3, 4
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "lib", "libh1bkv.so")
 
@@ -64,6 +64,8 @@ def lib() -> C.CDLL:
             "h1bkv_decode_workspace_bytes": (sz, [vp, i32, i32]),
             "h1bkv_decode_attn": (C.c_int, [vp, vp, i32, vp, C.c_float, vp, vp, sz, vp]),
             "h1bkv_decode_step": (C.c_int, [vp, vp, i32, vp, vp, i64, i64, vp, C.c_float, vp, vp, sz, vp]),
+            "h1bkv_prefill_workspace_bytes": (sz, [vp, i32, i32]),
+            "h1bkv_prefill_attn": (C.c_int, [vp, vp, i32, i32, vp, i64, i64, i64, C.c_float, vp, vp, sz, vp]),
             "h1bkv_set_decode_chunk": (C.c_int, [vp, i32]),
             "h1bkv_export_tokens": (C.c_int, [vp, i32, i32, i32, i32, vp, vp, vp, vp]),
             "h1bkv_import_tokens": (C.c_int, [vp, i32, i32, i32, i32, vp, vp, vp, vp]),
@@ -176,6 +178,17 @@ def h1bkv_decode_step(h, seq_ids, k, v, stride_seq: int, stride_head: int, q, ta
     ids, p = _ids(seq_ids)
     return lib().h1bkv_decode_step(h, p, len(ids), _dev_ptr(k), _dev_ptr(v), stride_seq, stride_head, _dev_ptr(q), tau,
                                    _dev_ptr(out), _dev_ptr(workspace), workspace_bytes, _stream(stream))
+
+
+def h1bkv_prefill_workspace_bytes(h, n_seqs: int, n_q: int) -> int:
+    return lib().h1bkv_prefill_workspace_bytes(h, n_seqs, n_q)
+
+
+def h1bkv_prefill_attn(h, seq_ids, n_q: int, q, stride_seq: int, stride_tok: int, stride_head: int, tau: float, out, workspace,
+                       workspace_bytes: int, stream=0) -> int:
+    ids, p = _ids(seq_ids)
+    return lib().h1bkv_prefill_attn(h, p, len(ids), n_q, _dev_ptr(q), stride_seq, stride_tok, stride_head, tau, _dev_ptr(out),
+                                    _dev_ptr(workspace), workspace_bytes, _stream(stream))
 
 
 def h1bkv_set_decode_chunk(h, chunk_tokens: int) -> int:
@@ -294,6 +307,20 @@ class Cache:
         if out is None:
             out = torch.empty((n, self.cfg.n_q_heads, self.d), dtype=torch.float32, device=q.device)
         check(h1bkv_decode_attn(self.h, seq_ids, q, tau, out, self.workspace, self.workspace.numel(), stream), "h1bkv_decode_attn")
+        return out
+
+    def prefill(self, seq_ids, q, tau: float, out=None, stream=None):
+        """q: torch tensor [n_seqs][n_q][H_q][d] (dense last axis): the last n_q cached positions attend causally."""
+        import torch
+        n, n_q = len(seq_ids), q.shape[1]
+        need = h1bkv_prefill_workspace_bytes(self.h, n, n_q)
+        if self.workspace is None or self.workspace.numel() < need:
+            self.workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+        if out is None:
+            out = torch.empty((n, n_q, self.cfg.n_q_heads, self.d), dtype=torch.float32, device=q.device)
+        assert q.stride(3) == 1
+        check(h1bkv_prefill_attn(self.h, seq_ids, n_q, q, q.stride(0), q.stride(1), q.stride(2), tau, out, self.workspace,
+                                 self.workspace.numel(), stream), "h1bkv_prefill_attn")
         return out
 
     def export(self, seq_id: int, kv_head: int, t0: int, n: int):

@@ -516,6 +516,58 @@ int h1bkv_decode_step(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n_seq
     return enqueue_decode(c, seq_ids_host, n_seqs, q_dev, tau, out_dev, workspace_dev, true, st);
 }
 
+size_t h1bkv_prefill_workspace_bytes(const h1bkv_cache *c, int32_t n_seqs, int32_t n_q) {
+    if (!c || n_seqs < 1 || n_q < 1) return 0;
+    return align_up((size_t)n_seqs * n_q * c->cfg.n_q_heads * c->W * 8);
+}
+
+int h1bkv_prefill_attn(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n_seqs, int32_t n_q, const void *q_dev,
+                       int64_t stride_seq, int64_t stride_tok, int64_t stride_head, float tau, float *out_dev,
+                       void *workspace_dev, size_t workspace_bytes, void *hip_stream) {
+    if (!c) return H1BKV_ENULL;
+    int rc = check_seq_ids(c, seq_ids_host, n_seqs);
+    if (rc != H1BKV_OK) return rc;
+    if (n_q < 1 || !(tau > 0.0f) || !std::isfinite(tau)) return H1BKV_EINVAL;
+    if (!prefill_supported(c->cfg.head_dim, c->code_layout)) return H1BKV_ESHAPE;
+    for (int i = 0; i < n_seqs; ++i)
+        if (c->seq_len[seq_ids_host[i]] < n_q) return H1BKV_ERANGE;
+    if (stride_seq < 0 || stride_tok < 0 || stride_head < c->cfg.head_dim) return H1BKV_EINVAL;
+    if (c->dry) return H1BKV_ENODEVICE;
+    if (!q_dev || !out_dev || !workspace_dev) return H1BKV_ENULL;
+    const int elt = c->cfg.in_dtype == H1BKV_F16 ? 2 : 4;
+    if (reinterpret_cast<uintptr_t>(workspace_dev) % kAlign || reinterpret_cast<uintptr_t>(q_dev) % 16 ||
+        reinterpret_cast<uintptr_t>(out_dev) % 16 || (stride_seq * elt) % 16 || (stride_tok * elt) % 16 || (stride_head * elt) % 16)
+        return H1BKV_EINVAL;
+    if (workspace_bytes < h1bkv_prefill_workspace_bytes(c, n_seqs, n_q)) return H1BKV_EWORKSPACE;
+    rc = check_device(c);
+    if (rc != H1BKV_OK) return rc;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+
+    PrefillArgs a{};
+    a.pool = c->view();
+    a.q = q_dev;
+    a.stride_seq = stride_seq;
+    a.stride_tok = stride_tok;
+    a.stride_head = stride_head;
+    a.q_sketch = static_cast<uint64_t *>(workspace_dev);
+    a.out = out_dev;
+    a.n_q = n_q;
+    a.f16 = c->cfg.in_dtype == H1BKV_F16;
+    a.exp2_scale = (float)(2.0 * 1.4426950408889634 / ((double)c->cfg.sketch_bits * (double)tau));
+    {
+        Timed t(c, H1BKV_K_QSKETCH, st);
+        if (launch_sketch_rows(a, n_seqs, st) != hipSuccess) return H1BKV_EHIP;
+    }
+    for (int s0 = 0; s0 < n_seqs; s0 += kMaxSeqsPerLaunch) {
+        const int n = std::min(kMaxSeqsPerLaunch, n_seqs - s0);
+        BatchDesc desc;
+        for (int i = 0; i < n; ++i) desc.s[i] = SeqDesc{seq_ids_host[s0 + i], c->seq_len[seq_ids_host[s0 + i]]};
+        Timed t(c, H1BKV_K_PREFILL, st);
+        if (launch_prefill(a, desc, s0, n, st) != hipSuccess) return H1BKV_EHIP;
+    }
+    return H1BKV_OK;
+}
+
 static int xfer_tokens(const h1bkv_cache *c, int32_t seq_id, int32_t kv_head, int32_t t0, int32_t n, bool to_host,
                        uint64_t *sk, uint8_t *codes, uint16_t *scale, uint16_t *zero) {
     if (!c) return H1BKV_ENULL;

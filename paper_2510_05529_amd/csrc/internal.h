@@ -83,6 +83,20 @@ struct DecodeArgs {
     float exp2_scale;         // 2 log2(e) / (b tau): p = exp2(exp2_scale * (ham_min - ham))
 };
 
+struct PrefillArgs {
+    PoolView pool;
+    const void *q;            // [n_seqs][n_q][H_q][d] in the cache's input dtype, addressed with the strides below
+    int64_t stride_seq, stride_tok, stride_head;
+    uint64_t *q_sketch;       // workspace: [n_seqs][n_q][H_q][W]
+    float *out;               // [n_seqs][n_q][H_q][d]
+    int32_t n_q;              // query positions per sequence: the last n_q cached positions
+    int32_t f16;
+    float exp2_scale;         // 2 log2(e) / (b tau)
+};
+
+// The prefill kernel keeps a row block's accumulators (d/16 MFMA tiles) in registers and reads 4-bit codes.
+inline bool prefill_supported(int head_dim, int code_layout) { return head_dim <= 128 && code_layout != 2; }
+
 // Query heads one matrix-core decode workgroup serves: the largest divisor of r that is at most 8.
 inline int mfma_heads_per_wg(int r) {
     for (int q = 8; q > 1; --q)
@@ -105,6 +119,8 @@ hipError_t launch_decode_split(const DecodeArgs &a, const BatchDesc &desc, int s
 hipError_t launch_decode_split_mfma(const DecodeArgs &a, const BatchDesc &desc, int seq0, int n_seqs, hipStream_t st);
 hipError_t launch_decode_split_f16v(const DecodeArgs &a, const BatchDesc &desc, int seq0, int n_seqs, hipStream_t st);
 hipError_t launch_merge(const DecodeArgs &a, const BatchDesc &desc, int seq0, int n_seqs, hipStream_t st);
+hipError_t launch_sketch_rows(const PrefillArgs &a, int n_seqs, hipStream_t st);
+hipError_t launch_prefill(const PrefillArgs &a, const BatchDesc &desc, int seq0, int n_seqs, hipStream_t st);
 hipError_t launch_stream_copy(void *dst, const void *src, size_t n_bytes, hipStream_t st);
 hipError_t launch_stream_read(const void *src, size_t n_bytes, void *sink, hipStream_t st);
 

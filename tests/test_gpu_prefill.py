@@ -1,0 +1,93 @@
+"""GPU parity of prefill attention over the compressed cache (Eq.(3)+(5) for every position of a prompt chunk,
+causal) against the oracle, which runs one decode step per position over that position's prefix."""
+import numpy as np
+import pytest
+
+from oracle import cref
+from paper_2510_05529_amd import binding as B
+from paper_2510_05529_amd import workloads as wl
+from tests.gpu_util import TOL, make_cache, rel_err, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def _setup(d, b, g, r, dt, T, batch=2, hkv=2, seed=0):
+    w = wl.Workload(f"prefill_d{d}_b{b}_g{g}_r{r}_{dt}", batch, hkv * r, hkv, d, T, b, g, dt, seed=seed + d + b + r + T)
+    R = wl.projection(b, d)
+    seqs = list(range(batch))
+    k, v = wl.kv_slab(w, "k", seqs, 0, T), wl.kv_slab(w, "v", seqs, 0, T)
+    oc = cref.Cache(R, batch, hkv, T, g)
+    oc.append(k, v)
+    cache = make_cache(w, R, pool_fill=0x7E)        # never-written slots hold fp16 NaN patterns in scale/zero
+    cache.append(seqs, to_dev(k), to_dev(v))
+    return w, seqs, oc, cache
+
+
+def _queries(w, n_q, seed=1):
+    rng = np.random.default_rng(seed)
+    q = rng.standard_normal((w.batch, n_q, w.n_q_heads, w.head_dim)).astype(np.float32)
+    return q.astype(np.float16) if w.dtype == "f16" else q
+
+
+# (head_dim, sketch bits, group, query heads per KV head, dtype, cached tokens, query positions)
+CASES = [(128, 128, 32, 1, "f16", 300, 300),      # a whole prompt, record-major codes
+         (128, 128, 32, 1, "f32", 517, 200),      # a chunk on top of an existing context, ragged tile tails
+         (64, 64, 32, 2, "f16", 130, 130),
+         (128, 256, 64, 4, "f16", 400, 400),      # token-interleaved codes (grouped-query geometry)
+         (64, 128, 64, 8, "f32", 260, 77),
+         (128, 512, 128, 1, "f16", 190, 190),
+         (128, 128, 32, 3, "f16", 333, 1),        # one query: the decode step
+         (64, 256, 32, 1, "f16", 1000, 129)]
+
+
+@pytest.mark.parametrize("d,b,g,r,dt,T,n_q", CASES)
+def test_prefill_matches_the_oracle(d, b, g, r, dt, T, n_q):
+    w, seqs, oc, cache = _setup(d, b, g, r, dt, T)
+    q = _queries(w, n_q)
+    for tau in (w.default_tau(), 0.3):
+        out = cache.prefill(seqs, to_dev(q), tau).cpu().numpy()
+        assert np.isfinite(out).all()
+        ref = oc.prefill(q, tau)
+        assert rel_err(out, ref) <= TOL
+    cache.close()
+
+
+def test_single_query_prefill_equals_decode():
+    w, seqs, oc, cache = _setup(128, 128, 32, 1, "f16", 700)
+    q = _queries(w, 1)
+    a = cache.prefill(seqs, to_dev(q), 0.06).cpu().numpy()[:, 0]
+    b = cache.decode(seqs, to_dev(q[:, 0]), 0.06).cpu().numpy()
+    assert rel_err(a, b) <= TOL
+    cache.close()
+
+
+def test_ragged_lengths_strided_queries_and_argument_checks():
+    import torch
+    d, b, g, r, T = 128, 128, 32, 2, 450
+    w = wl.Workload("prefill_ragged", 3, 2 * r, 2, d, T, b, g, "f16", seed=77)
+    R = wl.projection(b, d)
+    seqs = [0, 1, 2]
+    lens = [T, 150, 64]
+    k, v = wl.kv_slab(w, "k", seqs, 0, T), wl.kv_slab(w, "v", seqs, 0, T)
+    oc = cref.Cache(R, 3, 2, T, g)
+    oc.append(k, v)
+    cache = make_cache(w, R, pool_fill=0x7E)
+    kd, vd = to_dev(k), to_dev(v)
+    for s, n in zip(seqs, lens):
+        cache.append([s], kd[s:s + 1, :n], vd[s:s + 1, :n])
+    n_q = 64
+    q = _queries(w, n_q)
+    # queries as a strided view of a wider buffer (token stride larger than H_q * d)
+    wide = torch.zeros((3, n_q, w.n_q_heads + 1, d), dtype=torch.float16, device="cuda")
+    wide[:, :, :w.n_q_heads] = to_dev(q)
+    out = cache.prefill(seqs, wide[:, :, :w.n_q_heads], 0.08).cpu().numpy()
+    assert rel_err(out, oc.prefill(q, 0.08, ctx_len=lens)) <= TOL
+    # a sequence shorter than the chunk is refused, and nothing is written
+    ws = torch.empty(B.h1bkv_prefill_workspace_bytes(cache.h, 3, 65), dtype=torch.uint8, device="cuda")
+    q65 = to_dev(_queries(w, 65))
+    o65 = torch.zeros((3, 65, w.n_q_heads, d), dtype=torch.float32, device="cuda")
+    rc = B.h1bkv_prefill_attn(cache.h, seqs, 65, q65, q65.stride(0), q65.stride(1), q65.stride(2), 0.08, o65, ws, ws.numel())
+    assert rc == B.H1BKV_ERANGE
+    rc = B.h1bkv_prefill_attn(cache.h, seqs, 64, q65, q65.stride(0), q65.stride(1), q65.stride(2), 0.08, o65, ws, 16)
+    assert rc == B.H1BKV_EWORKSPACE
+    cache.close()
