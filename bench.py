@@ -39,6 +39,8 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
     ap.add_argument("--value-bits", type=int, default=4, choices=(4, 16),
                     help="16: the '1-bit key only' variant (fp16 values, Table V ablation) instead of the method's 4-bit values")
+    ap.add_argument("--prefill", action="store_true",
+                    help="with --workload append_prefill_8k: append the prompt AND run causal prefill attention over it")
     ap.add_argument("--chunk", type=int, default=0, help="decode chunk override (tokens, multiple of 256)")
     ap.add_argument("--per-token-layers", type=int, default=0, metavar="L",
                     help="secondary line: per-token attention latency of L layers (one cache each), every layer one fused "
@@ -153,6 +155,73 @@ def bench_append(args, torch, B, wl, w, workers):
         "records_per_s": records / (ms_per_step * 1e-3)}))
 
 
+VALU_LANE_OPS_PER_S = 256 * 4 * 16 * 2.4e9    # compute units x SIMDs x lanes x clock: plain (non-packed) vector instructions
+
+
+def bench_prefill(args, torch, B, wl, w, workers):
+    """Secondary line: a whole prompt -- append all tokens of every sequence, then causal attention of every position
+    over the compressed cache (h1bkv_prefill_attn).  The attention kernel is bound by the vector ALUs: per visible
+    (query, key) pair it needs the sketch words' XOR and popcount (4 W instructions), a convert, a multiply-add and an
+    exponential (quarter rate: 4 issue slots) and half a pack -- 4 W + 7 lane-operations, counted here as the
+    algorithmic work against the chip's plain vector issue rate."""
+    n_new, Bsz = w.context, w.batch
+    R = wl.projection(w.sketch_bits, w.head_dim)
+    pages_per_seq = (n_new + 255) // 256 + 1
+    cache = B.Cache(n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim, sketch_bits=w.sketch_bits,
+                    group_size=w.group_size, dtype=w.dtype, max_seqs=Bsz, max_pages=Bsz * pages_per_seq,
+                    max_pages_per_seq=pages_per_seq, R=R)
+    seqs = list(range(Bsz))
+    k = torch.from_numpy(wl.kv_slab(w, "k", seqs, 0, n_new, workers)).cuda()
+    v = torch.from_numpy(wl.kv_slab(w, "v", seqs, 0, n_new, workers)).cuda()
+    q = torch.from_numpy(wl.kv_slab(w, "k", seqs, 0, n_new, workers)[..., ::-1].copy()).cuda()   # any dense tensor of the shape
+    if w.n_q_heads != w.n_kv_heads:
+        q = q.repeat_interleave(w.n_q_heads // w.n_kv_heads, dim=2).contiguous()
+    out = torch.empty((Bsz, n_new, w.n_q_heads, w.head_dim), dtype=torch.float32, device="cuda")
+    ws_bytes = B.h1bkv_prefill_workspace_bytes(cache.h, Bsz, n_new)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    stream = torch.cuda.current_stream()
+    tau = w.default_tau()
+
+    def step():
+        for s in seqs:
+            B.check(B.h1bkv_reset_seq(cache.h, s))
+        B.check(B.h1bkv_append_kv(cache.h, seqs, n_new, k, v, k.stride(0), k.stride(1), k.stride(2), stream))
+        B.check(B.h1bkv_prefill_attn(cache.h, seqs, n_new, q, q.stride(0), q.stride(1), q.stride(2), tau, out, ws, ws_bytes, stream))
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    B.check(B.h1bkv_profile_enable(cache.h, args.steps, 0x1F))
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    kernel_ms = {}
+    for name, kid in (("append", B.H1BKV_K_APPEND), ("sketch_rows", B.H1BKV_K_QSKETCH), ("prefill", B.H1BKV_K_PREFILL)):
+        rc, ms = B.h1bkv_profile_read(cache.h, kid)
+        B.check(rc)
+        kernel_ms[name] = float(ms.mean())
+    W = w.sketch_bits // 64
+    pairs = Bsz * w.n_q_heads * n_new * (n_new + 1) / 2.0        # visible (query, key) pairs
+    lane_ops = pairs * (4 * W + 7)
+    achieved = lane_ops / (kernel_ms["prefill"] * 1e-3) / 1e12
+    peak = VALU_LANE_OPS_PER_S / 1e12
+    mfma_flops = pairs * w.head_dim * 2.0
+    print(json.dumps({
+        "metric": "prefill_tokens_per_s", "value": Bsz * n_new / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w.name, "batch": Bsz, "prompt_tokens": n_new, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
+                   "head_dim": w.head_dim, "sketch_bits": w.sketch_bits, "group_size": w.group_size, "in_dtype": w.dtype, "tau": tau,
+                   "step": "append the whole prompt + causal attention of every position over the compressed cache"},
+        "roofline": {"bound": "alu", "kernel": "prefill_kernel", "achieved": achieved, "peak": peak, "unit": "T lane-op/s",
+                     "frac": achieved / peak, "traffic": None, "kernel_ms": kernel_ms["prefill"],
+                     "pairs_per_s": pairs / (kernel_ms["prefill"] * 1e-3), "lane_ops_per_pair": 4 * W + 7,
+                     "mfma_TFLOPs": mfma_flops / (kernel_ms["prefill"] * 1e-3) / 1e12},
+        "kernel_ms": kernel_ms}))
+
+
 def bench_per_token(args, torch, B, wl, w, workers):
     """Secondary line: what one generated token costs in attention over L layers.  Every layer owns a cache with the
     workload's context and runs one fused decode step (append the token's K/V, attend); the L steps are captured in one
@@ -256,7 +325,7 @@ def main():
 
     w = wl.WORKLOADS[args.workload]
     if args.workload == "append_prefill_8k":
-        bench_append(args, torch, B, wl, w, workers)
+        (bench_prefill if args.prefill else bench_append)(args, torch, B, wl, w, workers)
         return
     if args.per_token_layers:
         bench_per_token(args, torch, B, wl, w, workers)

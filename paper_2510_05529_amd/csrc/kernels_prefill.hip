@@ -2,24 +2,29 @@
 // query i of a sequence attends to the cached tokens up to and including its own position, exactly the decode step
 // it would have seen had the prompt been fed one token at a time.
 //
-// With many queries per KV head the weighted sum  sum_t p[i][t] v^[t][c]  is a dense contraction and runs on the
-// matrix cores (v_mfma_f32_16x16x32_f16, fp32 accumulate); the vector ALUs score (XOR + popcount), exponentiate and
-// dequantise.  One workgroup (4 waves) takes 128 consecutive query positions of one (sequence, query head) and walks
-// the key tokens in tiles of 64 up to its diagonal:
-//   staging   the tile's sketches go to LDS as they are; its values are dequantised ONCE per workgroup,
-//             v^ = fp16(scale * code + zero), and stored channel-major so that an MFMA B operand (8 consecutive
-//             tokens of one channel) is one 16-byte LDS read.  The next tile's global loads are issued before the
-//             current tile is consumed, so their latency is covered.
-//   scores    a wave owns 32 query rows (two MFMA row blocks).  Lane (i, kb) scores row i against tokens 8 kb .. 8 kb + 7
-//             of a 32-token step: that is exactly the A-operand slot of the lane, so the weights
-//             p = exp((alpha - alpha_max)/tau) are packed to fp16 in registers and never travel through LDS.
-//             Running maximum per row with a lazy rescale (scores take only b+1 values, the maximum moves rarely).
-//             Weights carry a factor 2^14 to keep small ones out of the fp16 subnormal range; it cancels in the
-//             normalisation, which uses the row sums of the SAME fp16 weights (one more MFMA against an all-ones B).
-//   causal    tiles entirely below a wave's rows take an unmasked path; tiles entirely above them are skipped.
+// With many queries per KV head both halves of the step are dense contractions and run on the matrix cores:
+//   scores    alpha needs the Hamming distance of every (query, key) pair.  With the key bits unpacked to {0,1} bytes
+//             and the query bits to {+1,-1} bytes,  sum_k q_k key_k = popcount(q) - ham,  so one int8 MFMA
+//             (v_mfma_i32_16x16x64_i8) per 64 sketch bits yields 16 x 16 distances -- instead of 4 W XOR/popcount
+//             instructions per pair on the vector ALUs.  The MFMA is issued as keys x queries, so that a lane ends
+//             up holding distances of ONE query row against several tokens: the slot it has in the next MFMA.
+//   weights   p = exp((alpha - alpha_max)/tau) per pair on the vector ALUs (running maximum per row with a lazy
+//             rescale: scores take only b+1 values, the maximum moves rarely), packed to fp16 in registers as the
+//             A operand of the second MFMA.  They carry a factor 2^14 to keep small ones out of the fp16 subnormal
+//             range; it cancels in the normalisation, which uses the row sums of the SAME fp16 weights (one more MFMA
+//             against an all-ones B).
+//   values    sum_t p[i][t] v^[t][c]  with v_mfma_f32_16x16x32_f16, fp32 accumulate.
+// One workgroup (4 waves) takes 128 consecutive query positions of one (sequence, query head) -- 32 rows per wave --
+// and walks the key tokens in tiles up to its diagonal.  Per tile the workgroup stages ONCE, for all its rows: the
+// keys' bits as bytes, and the values dequantised, v^ = fp16(scale * code + zero), channel-major, in the token order
+// the score MFMA leaves its results in (so an MFMA B operand is one 16-byte LDS read).  The next tile's global loads
+// are issued before the current tile is consumed.  Tiles entirely below a wave's rows take an unmasked path; tiles
+// entirely above them are skipped.
 // sketch_rows_kernel sketches the chunk's query vectors (Eq.(2), same fp32 FMA chain as the keys) with the R rows
 // resident in registers, 64 vectors per LDS tile.
 #include <hip/hip_fp16.h>
+
+#include <type_traits>
 
 #include "decode_common.h"
 
@@ -30,16 +35,19 @@ namespace {
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef __fp16 fp16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kTK = 64;                       // key tokens per tile
 constexpr int kRB = 2;                        // 16-row blocks per wave
 constexpr int kQB = kWaves * 16 * kRB;        // query positions per workgroup
-constexpr int kVStride = kTK * 2 + 16;        // bytes per channel row of the value tile (16 B pad: conflict-free b128 reads)
 constexpr float kPScaleLog2 = 14.0f;          // weights are stored as p * 2^14
 
 union HalfOperand {
     uint32_t u[4];
     f16x8 v;
+};
+union ByteOperand {
+    uint32_t u[4];
+    i32x4 v;
 };
 
 __device__ __forceinline__ int xor16_min(int x) {       // min with the lane 16 away (immediate swizzle, inside a half-wave)
@@ -49,19 +57,30 @@ __device__ __forceinline__ int xor32_min(int x) {       // min with the lane 32 
     const auto r = __builtin_amdgcn_permlane32_swap((unsigned)x, (unsigned)x, false, false);
     return min((int)r[0], (int)r[1]);
 }
+// Bits 0..3 of x -> the low bits of bytes 0..3.
+__device__ __forceinline__ uint32_t spread4(uint32_t x) {
+    return (x & 1u) | ((x & 2u) << 7) | ((x & 4u) << 14) | ((x & 8u) << 21);
+}
 
+template <int NDW>
 struct StageRegs {           // one thread's share of a key tile on its way from global memory to LDS
-    uint4 sk;                // 16 bytes of the tile's sketches
+    uint32_t skd[NDW];       // 32 sketch bits each
     uint32_t c[4];           // layout 0: 8 bytes of codes for each of two tokens;  layout 1: up to 4 code words of one block
     uint32_t m[16];          // layout 0: {scale, zero} of the two tokens;  layout 1: of the block's 8 tokens, for up to
-                             //           two quantisation groups (words k and k + 1 of a thread share a group)
+                             //           two 64-channel halves of the head (each within one quantisation group per word)
 };
 
 template <int W, int D, int LAYOUT>
 __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs a, BatchDesc desc, int seq0) {
     constexpr int NCB = D / 16;
-    __shared__ __attribute__((aligned(16))) unsigned char v_s[2][D * kVStride];
-    __shared__ __attribute__((aligned(16))) uint64_t sk_s[2][kTK * W];
+    constexpr int TK = W <= 2 ? 64 : 32;          // key tokens per tile (wide sketches: smaller tiles, same LDS budget)
+    constexpr int NSTEP = TK / 32;                // 32-token MFMA steps per tile
+    constexpr int VS = TK * 2 + 16;               // bytes per channel row of the value tile (16 B pad: conflict-free b128 reads)
+    constexpr int KS = 64 * W + 16;               // bytes per token row of the key-bit tile (same padding)
+    constexpr int DWT = TK * 2 * W;               // 32-bit sketch words per tile
+    constexpr int NDW = DWT > kThreads ? DWT / kThreads : 1;
+    __shared__ __attribute__((aligned(16))) unsigned char v_s[2][D * VS];
+    __shared__ __attribute__((aligned(16))) unsigned char k_s[2][TK * KS];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int i = lane & 15, kb = lane >> 4;
@@ -71,7 +90,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs a, Bat
     const int row0 = qb * kQB;
     const int q0 = len - n_q;                                      // absolute position of query 0
     const int last_row = min(row0 + kQB, n_q) - 1;
-    const int n_tiles = (q0 + last_row + kTK) / kTK;               // tiles that hold tokens visible to the last row
+    const int n_tiles = (q0 + last_row + TK) / TK;                 // tiles that hold tokens visible to the last row
 
     const PoolView &pv = a.pool;
     const int H = pv.n_kv_heads, Hq = pv.n_q_heads, r = Hq / H;
@@ -80,16 +99,25 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs a, Bat
     const int ng = D / pv.group_size;
     const int32_t *bt = pv.block_table + (size_t)sd.seq_id * pv.max_pages_per_seq;
 
-    // ---- this lane's query rows ----
-    int pos[kRB];                 // absolute position of row (rb, i); -1 for rows past the chunk
-    uint64_t sq[kRB][W];
+    // ---- this lane's query rows: position, popcount, and bits 16 kb .. 16 kb + 15 of every 64-bit word as +-1 bytes ----
+    int pos[kRB], pcq[kRB];       // pos: absolute position of row (rb, i); -1 for rows past the chunk
+    ByteOperand qpm[kRB][W];
 #pragma unroll
     for (int rb = 0; rb < kRB; ++rb) {
         const int qi = row0 + wave * 16 * kRB + rb * 16 + i;
         pos[rb] = qi < n_q ? q0 + qi : -1;
+        pcq[rb] = 0;
 #pragma unroll
-        for (int w = 0; w < W; ++w)
-            sq[rb][w] = qi < n_q ? a.q_sketch[(((size_t)seq_g * n_q + qi) * Hq + h) * W + w] : 0;
+        for (int w = 0; w < W; ++w) {
+            const uint64_t sq = qi < n_q ? a.q_sketch[(((size_t)seq_g * n_q + qi) * Hq + h) * W + w] : 0;
+            pcq[rb] += __popcll(sq);
+            const uint32_t bits = (uint32_t)(sq >> (16 * kb)) & 0xFFFFu;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const uint32_t t = spread4(bits >> (4 * k));
+                qpm[rb][w].u[k] = t | ((t ^ 0x01010101u) * 0xFFu);     // bit 1 -> 0x01 (+1), bit 0 -> 0xFF (-1)
+            }
+        }
     }
     const int wave_row0 = row0 + wave * 16 * kRB;
     const int wave_min_pos = q0 + wave_row0;                                       // position of the wave's first row
@@ -108,21 +136,29 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs a, Bat
 #pragma unroll
     for (int k = 0; k < 4; ++k) ones.u[k] = 0x3C003C00u;          // fp16 1.0
 
+    // Token t of a 32-token step sits at operand position 8 ((t % 16) / 4) + 4 (t / 16) + t % 4: the score MFMA of
+    // token block t / 16 leaves tokens 4 kb .. 4 kb + 3 in lane group kb, and the value MFMA wants that lane group's
+    // eight tokens side by side.
+    auto operand_pos = [](int t) { return (t & ~31) + 8 * ((t & 15) >> 2) + 4 * ((t >> 4) & 1) + (t & 3); };
+
     // ---- staging: global -> registers (issued early) -> LDS (after the current tile has been consumed) ----
-    constexpr int kItems0 = 32 * (D / 16);                        // layout 0: (token pair, 16-channel slice) items per tile
-    // layout 1: a thread takes block tid / 32 of the tile's 8 blocks and words tid % 32 + 32 k of its D words
-    // (word wi holds channel 16 cb + n with cb = (wi / 64) * 4 + wi % 4, n = (wi % 64) / 4: the inverse of
-    // code_word_index).  Words k = 0, 1 lie in one 16-channel block, k = 2, 3 in the block 64 channels on, so the
-    // thread needs the 8 tokens' {scale, zero} of at most two groups.
-    constexpr int kWordsPerThread = D / 32;
+    constexpr int kItems0 = (TK / 2) * (D / 16);                  // layout 0: (token pair, 16-channel slice) items per tile
+    // layout 1: a thread takes one of the tile's TK / 8 blocks and words (tid % LPB) + LPB k of its D words (word wi
+    // holds channel 16 cb + n with cb = (wi / 64) * 4 + wi % 4, n = (wi % 64) / 4: the inverse of code_word_index).
+    // Words below 64 lie in the head's first 64 channels, the others in the second: at most two {scale, zero} sets.
+    constexpr int LPB = kThreads / (TK / 8);
+    constexpr int kWordsPerThread = D / LPB;
     auto word_channel = [](int wi) { return 16 * ((wi >> 6) * 4 + (wi & 3)) + ((wi & 63) >> 2); };
     auto tile_rec0 = [&](int kt) {
-        const int t0 = kt * kTK;
+        const int t0 = kt * TK;
         return ((size_t)bt[t0 / kPage] * H + kvh) * kPage + (t0 % kPage);          // a tile never straddles a page
     };
-    auto load_tile = [&](StageRegs &sr, int kt) {
+    auto load_tile = [&](StageRegs<NDW> &sr, int kt) {
         const size_t rec0 = tile_rec0(kt);
-        if (tid < kTK * W / 2) sr.sk = reinterpret_cast<const uint4 *>(pv.sketch + rec0 * W)[tid];
+        const uint32_t *skw = reinterpret_cast<const uint32_t *>(pv.sketch + rec0 * W);
+#pragma unroll
+        for (int u = 0; u < NDW; ++u)
+            if (tid + u * kThreads < DWT) sr.skd[u] = skw[tid + u * kThreads];
         if constexpr (LAYOUT == 0) {
             if (tid < kItems0) {
                 const int tp = tid / (D / 16), s16 = tid % (D / 16);
@@ -137,21 +173,35 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs a, Bat
                 }
             }
         } else {
-            const int blk = tid >> 5;
+            const int blk = tid / LPB, w0 = tid % LPB;
             const uint32_t *words = reinterpret_cast<const uint32_t *>(pv.codes + (rec0 + 8 * blk) * (D / 2));
 #pragma unroll
-            for (int k = 0; k < kWordsPerThread; ++k) sr.c[k] = words[(tid & 31) + 32 * k];
+            for (int k = 0; k < kWordsPerThread; ++k) sr.c[k] = words[w0 + LPB * k];
 #pragma unroll
-            for (int ms = 0; ms < (kWordsPerThread + 1) / 2; ++ms) {
-                const int g = word_channel((tid & 31) + 64 * ms) / pv.group_size;
+            for (int ms = 0; ms < D / 64; ++ms) {
+                const int g = word_channel((w0 & 63) + 64 * ms) / pv.group_size;
 #pragma unroll
                 for (int j = 0; j < 8; ++j) sr.m[8 * ms + j] = pv.meta[(rec0 + 8 * blk + j) * ng + g];
             }
         }
     };
-    auto store_tile = [&](const StageRegs &sr, int kt, int buf) {
-        const int t0 = kt * kTK;
-        if (tid < kTK * W / 2) reinterpret_cast<uint4 *>(sk_s[buf])[tid] = sr.sk;
+    auto store_tile = [&](const StageRegs<NDW> &sr, int kt, int buf) {
+        const int t0 = kt * TK;
+        // key bits -> {0,1} bytes: 32 bits in, 32 bytes out
+        unsigned char *ks = k_s[buf];
+#pragma unroll
+        for (int u = 0; u < NDW; ++u) {
+            const int dwi = tid + u * kThreads;
+            if (dwi < DWT) {
+                const int tok = dwi / (2 * W), part = dwi % (2 * W);
+                uint32_t o[8];
+#pragma unroll
+                for (int k = 0; k < 8; ++k) o[k] = spread4(sr.skd[u] >> (4 * k));
+                uint4 *dst = reinterpret_cast<uint4 *>(ks + tok * KS + part * 32);
+                dst[0] = make_uint4(o[0], o[1], o[2], o[3]);
+                dst[1] = make_uint4(o[4], o[5], o[6], o[7]);
+            }
+        }
         unsigned char *vs = v_s[buf];
         if constexpr (LAYOUT == 0) {
             if (tid < kItems0) {
@@ -164,65 +214,75 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs a, Bat
                     sc[t] = __half2float(__ushort_as_half((unsigned short)(m & 0xFFFFu)));
                     zp[t] = __half2float(__ushort_as_half((unsigned short)(m >> 16)));
                 }
+                const int p2 = operand_pos(2 * tp) * 2;            // tokens 2 tp and 2 tp + 1 stay neighbours
 #pragma unroll
                 for (int cc = 0; cc < 16; ++cc) {
                     const int c = (cc + s16) & 15;                 // rotate the channel order per slice: spreads the LDS banks
-                    const float c0 = (float)((sr.c[c >> 3] >> (4 * (c & 7))) & 0xFu);
-                    const float c1 = (float)((sr.c[2 + (c >> 3)] >> (4 * (c & 7))) & 0xFu);
+                    // (selects, not a runtime array index: the staged words must stay in registers)
+                    const float c0 = (float)((((c & 8) ? sr.c[1] : sr.c[0]) >> (4 * (c & 7))) & 0xFu);
+                    const float c1 = (float)((((c & 8) ? sr.c[3] : sr.c[2]) >> (4 * (c & 7))) & 0xFu);
                     const __half2 hv = __halves2half2(__float2half_rn(fmaf(sc[0], c0, zp[0])), __float2half_rn(fmaf(sc[1], c1, zp[1])));
-                    *reinterpret_cast<__half2 *>(vs + (16 * s16 + c) * kVStride + tp * 4) = hv;
+                    *reinterpret_cast<__half2 *>(vs + (16 * s16 + c) * VS + p2) = hv;
                 }
             }
         } else {
-            const int blk = tid >> 5;
+            const int blk = tid / LPB, w0 = tid % LPB;
 #pragma unroll
             for (int k = 0; k < kWordsPerThread; ++k) {
-                const int ch = word_channel((tid & 31) + 32 * k);
+                const int wi = w0 + LPB * k, ch = word_channel(wi);
                 const uint32_t x = sr.c[k];
                 __half hv[8];
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
                     // slots past the end of the sequence hold anything: their values must not reach the MFMA as NaN
-                    const uint32_t m = t0 + 8 * blk + j < len ? sr.m[8 * (k / 2) + j] : 0u;
+                    const uint32_t m = t0 + 8 * blk + j < len ? sr.m[8 * (wi >> 6) + j] : 0u;
                     const float sc = __half2float(__ushort_as_half((unsigned short)(m & 0xFFFFu)));
                     const float zp = __half2float(__ushort_as_half((unsigned short)(m >> 16)));
                     const float code = (float)((x >> (4 * code_nibble_pos(j))) & 0xFu);
                     hv[j] = __float2half_rn(fmaf(sc, code, zp));
                 }
-                *reinterpret_cast<uint4 *>(vs + ch * kVStride + blk * 16) = *reinterpret_cast<const uint4 *>(hv);
+                // tokens 8 blk .. 8 blk + 3 and 8 blk + 4 .. 8 blk + 7 go to two operand positions
+                *reinterpret_cast<uint2 *>(vs + ch * VS + operand_pos(8 * blk) * 2) = *reinterpret_cast<const uint2 *>(hv);
+                *reinterpret_cast<uint2 *>(vs + ch * VS + operand_pos(8 * blk + 4) * 2) = *reinterpret_cast<const uint2 *>(hv + 4);
             }
         }
     };
 
-    // ---- one tile: scores, weights, MFMA ----
+    // ---- one tile: score MFMA, weights, value MFMA ----
     auto consume_tile = [&](int kt, int buf, auto masked_tag) {
         constexpr bool kMasked = decltype(masked_tag)::value;
-        const uint64_t *sks = sk_s[buf];
+        const unsigned char *ks = k_s[buf];
         const unsigned char *vs = v_s[buf];
 #pragma unroll
-        for (int kk = 0; kk < kTK / 32; ++kk) {
-            const int tl = kk * 32 + 8 * kb;                      // first of this lane's 8 tokens, within the tile
-            const int tg = kt * kTK + tl;                         // ... and its absolute position
-            int ham[kRB][8], tmin[kRB];
+        for (int st = 0; st < NSTEP; ++st) {
+            // Hamming distances: lane (row i, kb) receives tokens 16 tb + 4 kb + j of the step, tb = 0, 1
+            i32x4 dot[kRB][2];
 #pragma unroll
-            for (int rb = 0; rb < kRB; ++rb) tmin[rb] = 1 << 20;
+            for (int tb = 0; tb < 2; ++tb) {
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const SketchRow<W> sk = load_sketch<W>(sks + (size_t)(tl + j) * W);
+                for (int rb = 0; rb < kRB; ++rb) dot[rb][tb] = i32x4{0, 0, 0, 0};
 #pragma unroll
-                for (int rb = 0; rb < kRB; ++rb) {
-                    int hd = 0;
+                for (int w = 0; w < W; ++w) {
+                    const i32x4 K = *reinterpret_cast<const i32x4 *>(ks + (32 * st + 16 * tb + i) * KS + 64 * w + 16 * kb);
 #pragma unroll
-                    for (int w = 0; w < W; ++w) hd += __popcll(sq[rb][w] ^ sk.w[w]);
-                    if (kMasked && tg + j > pos[rb]) hd = 1 << 20;                  // causal mask (also: rows past the chunk)
-                    ham[rb][j] = hd;
-                    tmin[rb] = min(tmin[rb], hd);
+                    for (int rb = 0; rb < kRB; ++rb)
+                        dot[rb][tb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(K, qpm[rb][w].v, dot[rb][tb], 0, 0, 0);
                 }
             }
+            const int tg = kt * TK + 32 * st + 4 * kb;            // absolute position of this lane's first token (tb = 0, j = 0)
+            int ham[kRB][8], tmin[kRB];
             bool changed = false;
 #pragma unroll
             for (int rb = 0; rb < kRB; ++rb) {
-                tmin[rb] = xor32_min(xor16_min(tmin[rb]));        // over the row's four token groups
+                tmin[rb] = 1 << 20;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    int hd = pcq[rb] - dot[rb][j >> 2][j & 3];   // sum_k q_k key_k = popcount(q) - ham
+                    if (kMasked && tg + 16 * (j >> 2) + (j & 3) > pos[rb]) hd = 1 << 20;      // causal mask (also: rows past the chunk)
+                    ham[rb][j] = hd;
+                    tmin[rb] = min(tmin[rb], hd);
+                }
+                tmin[rb] = xor32_min(xor16_min(tmin[rb]));        // over the row's four lane groups
                 changed |= tmin[rb] < run_min[rb];
             }
             if (__any(changed)) {                                 // rare: the running maximum of some row moved
@@ -261,7 +321,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs a, Bat
             }
 #pragma unroll
             for (int cb = 0; cb < NCB; ++cb) {
-                const f16x8 B = *reinterpret_cast<const f16x8 *>(vs + (16 * cb + i) * kVStride + tl * 2);
+                const f16x8 B = *reinterpret_cast<const f16x8 *>(vs + (16 * cb + i) * VS + (32 * st + 8 * kb) * 2);
 #pragma unroll
                 for (int rb = 0; rb < kRB; ++rb) acc[rb][cb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A[rb].v, B, acc[rb][cb], 0, 0, 0);
             }
@@ -270,14 +330,14 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs a, Bat
         }
     };
 
-    StageRegs sr;
+    StageRegs<NDW> sr;
     load_tile(sr, 0);
     store_tile(sr, 0, 0);
     __syncthreads();
     for (int kt = 0; kt < n_tiles; ++kt) {
         const int buf = kt & 1;
         if (kt + 1 < n_tiles) load_tile(sr, kt + 1);
-        const int t_first = kt * kTK, t_last = t_first + kTK - 1;
+        const int t_first = kt * TK, t_last = t_first + TK - 1;
         if (t_first <= wave_max_pos) {                             // else: the whole tile lies in this wave's future
             if (t_last <= wave_min_pos && wave_row0 + 16 * kRB <= n_q) consume_tile(kt, buf, std::false_type{});
             else consume_tile(kt, buf, std::true_type{});
