@@ -161,7 +161,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs a, Bat
             if (tid + u * kThreads < DWT) sr.skd[u] = skw[tid + u * kThreads];
         if constexpr (LAYOUT == 0) {
             if (tid < kItems0) {
-                const int tp = tid / (D / 16), s16 = tid % (D / 16);
+                const int tp = tid % (TK / 2), s16 = tid / (TK / 2);        // token pair fastest: see the LDS writes below
                 const int g = (16 * s16) / pv.group_size;
 #pragma unroll
                 for (int t = 0; t < 2; ++t) {
@@ -205,7 +205,9 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs a, Bat
         unsigned char *vs = v_s[buf];
         if constexpr (LAYOUT == 0) {
             if (tid < kItems0) {
-                const int tp = tid / (D / 16), s16 = tid % (D / 16);
+                // lanes of a half-wave hold different token pairs of one 16-channel slice: their 4-byte writes into a
+                // channel row fall into different LDS banks
+                const int tp = tid % (TK / 2), s16 = tid / (TK / 2);
                 float sc[2], zp[2];
 #pragma unroll
                 for (int t = 0; t < 2; ++t) {
@@ -216,11 +218,9 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs a, Bat
                 }
                 const int p2 = operand_pos(2 * tp) * 2;            // tokens 2 tp and 2 tp + 1 stay neighbours
 #pragma unroll
-                for (int cc = 0; cc < 16; ++cc) {
-                    const int c = (cc + s16) & 15;                 // rotate the channel order per slice: spreads the LDS banks
-                    // (selects, not a runtime array index: the staged words must stay in registers)
-                    const float c0 = (float)((((c & 8) ? sr.c[1] : sr.c[0]) >> (4 * (c & 7))) & 0xFu);
-                    const float c1 = (float)((((c & 8) ? sr.c[3] : sr.c[2]) >> (4 * (c & 7))) & 0xFu);
+                for (int c = 0; c < 16; ++c) {
+                    const float c0 = (float)((sr.c[c >> 3] >> (4 * (c & 7))) & 0xFu);
+                    const float c1 = (float)((sr.c[2 + (c >> 3)] >> (4 * (c & 7))) & 0xFu);
                     const __half2 hv = __halves2half2(__float2half_rn(fmaf(sc[0], c0, zp[0])), __float2half_rn(fmaf(sc[1], c1, zp[1])));
                     *reinterpret_cast<__half2 *>(vs + (16 * s16 + c) * VS + p2) = hv;
                 }
