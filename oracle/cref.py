@@ -27,7 +27,7 @@ def lib():
                      "h1bkv_oracle_hamming", "h1bkv_oracle_decode_one", "h1bkv_oracle_decode_batch",
                      "h1bkv_oracle_append_batch", "h1bkv_oracle_decode_one_f16v",
                      "h1bkv_oracle_decode_batch_f16v", "h1bkv_oracle_append_batch_f16v",
-                     "h1bkv_oracle_prefill_batch"):
+                     "h1bkv_oracle_prefill_batch", "h1bkv_oracle_decode_one_dtau", "h1bkv_oracle_decode_batch_dtau"):
             getattr(L, name).restype = None
         _lib = L
     return _lib
@@ -112,6 +112,22 @@ def decode_one(sq, sk, codes, scale, zero, b: int, G: int, tau: float) -> np.nda
     return out
 
 
+def decode_one_dtau(sq, sk, codes, scale, zero, b: int, G: int, tau: float):
+    """Eq.(5) and d out / d tau for one (sequence, query head): returns (out [d], dout [d]) float32."""
+    sq = np.ascontiguousarray(sq, dtype=np.uint64)
+    sk = np.ascontiguousarray(sk, dtype=np.uint64)
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    scale = np.ascontiguousarray(scale, dtype=np.uint16)
+    zero = np.ascontiguousarray(zero, dtype=np.uint16)
+    T = sk.shape[0]
+    d = codes.shape[-1] * 2
+    out = np.zeros(d, dtype=np.float32)
+    dout = np.zeros(d, dtype=np.float32)
+    lib().h1bkv_oracle_decode_one_dtau(_p(sq), _p(sk), _p(codes), _p(scale), _p(zero), C.c_int64(T), C.c_int(b),
+                                       C.c_int(d), C.c_int(G), C.c_double(tau), _p(out), _p(dout))
+    return out, dout
+
+
 def decode_one_f16v(sq, sk, v16, b: int, tau: float) -> np.ndarray:
     """Eq.(3)+(5) with fp16 values (the "1-bit key only" variant): v16 [T][d] fp16 bit patterns -> out [d] float32."""
     sq = np.ascontiguousarray(sq, dtype=np.uint64)
@@ -177,6 +193,20 @@ class Cache:
                                         _p(lens), _p(q), _p(self.sketches), _p(self.codes), _p(self.scale),
                                         _p(self.zero), C.c_double(tau), _p(out))
         return out
+
+    def decode_dtau(self, q: np.ndarray, tau: float, ctx_len=None):
+        """q [B][H_q][d] -> (out, d out / d tau), each [B][H_q][d] float32."""
+        assert self.value_bits == 4
+        q = _f32(q)
+        Hq = q.shape[1]
+        lens = np.full(self.B, self.len, dtype=np.int32) if ctx_len is None else np.ascontiguousarray(ctx_len, dtype=np.int32)
+        out = np.zeros((self.B, Hq, self.d), dtype=np.float32)
+        dout = np.zeros((self.B, Hq, self.d), dtype=np.float32)
+        lib().h1bkv_oracle_decode_batch_dtau(_p(self.R), C.c_int(self.b), C.c_int(self.d), C.c_int(self.G),
+                                             C.c_int(self.B), C.c_int(Hq), C.c_int(self.Hkv), C.c_int64(self.Tcap),
+                                             _p(lens), _p(q), _p(self.sketches), _p(self.codes), _p(self.scale),
+                                             _p(self.zero), C.c_double(tau), _p(out), _p(dout))
+        return out, dout
 
     def prefill(self, q: np.ndarray, tau: float, ctx_len=None) -> np.ndarray:
         """q [B][n_q][H_q][d]: the last n_q cached positions of every sequence attend causally (each to the tokens up

@@ -210,6 +210,71 @@ void h1bkv_oracle_decode_one(const uint64_t *sq /*[W]*/, const uint64_t *sk /*[T
 }
 
 /*
+ * Eq.(5) and its derivative with respect to the temperature, the one scalar the finetuning stage trains next to
+ * V_proj (Sec. IV-C):  with p_t = exp(alpha_t / tau), l = sum p_t, out = sum p_t v_t / l,
+ *   d out / d tau = -(1 / tau^2) ( sum p_t alpha_t v_t / l  -  (sum p_t alpha_t / l) out ),
+ * i.e. minus the softmax-weighted covariance of the scores with the values, over tau^2.  Same inputs as
+ * h1bkv_oracle_decode_one; dout [d] is zero for T <= 1.
+ */
+void h1bkv_oracle_decode_one_dtau(const uint64_t *sq, const uint64_t *sk, const uint8_t *codes, const uint16_t *scale,
+                                  const uint16_t *zero, int64_t T, int b, int d, int G, double tau, float *out,
+                                  float *dout) {
+    int W = b / 64, ng = d / G;
+    double acc[1024], acca[1024];
+    for (int c = 0; c < d; ++c) acc[c] = acca[c] = 0.0;
+    if (T <= 0) {
+        for (int c = 0; c < d; ++c) out[c] = dout[c] = 0.0f;
+        return;
+    }
+    double m = -2.0;
+    for (int64_t t = 0; t < T; ++t) {
+        int h = 0;
+        for (int w = 0; w < W; ++w) h += __builtin_popcountll(sq[w] ^ sk[t * W + w]);
+        double alpha = (double)(b - 2 * h) / (double)b;
+        if (alpha > m) m = alpha;
+    }
+    double l = 0.0, la = 0.0;
+    for (int64_t t = 0; t < T; ++t) {
+        int h = 0;
+        for (int w = 0; w < W; ++w) h += __builtin_popcountll(sq[w] ^ sk[t * W + w]);
+        double alpha = (double)(b - 2 * h) / (double)b;
+        double p = exp((alpha - m) / tau);
+        l += p;
+        la += p * alpha;
+        for (int c = 0; c < d; ++c) {
+            int q = (codes[t * (d / 2) + c / 2] >> (4 * (c & 1))) & 0xF;
+            double sc = (double)h1bkv_oracle_half_to_float(scale[t * ng + c / G]);
+            double zp = (double)h1bkv_oracle_half_to_float(zero[t * ng + c / G]);
+            double v = sc * (double)q + zp;
+            acc[c] += p * v;
+            acca[c] += p * alpha * v;
+        }
+    }
+    for (int c = 0; c < d; ++c) {
+        double o = acc[c] / l;
+        out[c] = (float)o;
+        dout[c] = (float)(-(acca[c] / l - (la / l) * o) / (tau * tau));
+    }
+}
+
+void h1bkv_oracle_decode_batch_dtau(const float *R, int b, int d, int G, int B, int Hq, int Hkv, int64_t Tcap,
+                                    const int32_t *ctx_len, const float *q, const uint64_t *sketches,
+                                    const uint8_t *codes, const uint16_t *scale, const uint16_t *zero, double tau,
+                                    float *out, float *dout) {
+    int W = b / 64, ng = d / G, r = Hq / Hkv;
+#pragma omp parallel for schedule(dynamic, 1) collapse(2)
+    for (int s = 0; s < B; ++s)
+        for (int h = 0; h < Hq; ++h) {
+            uint64_t sq[16];
+            sketch_one(R, b, d, q + ((int64_t)s * Hq + h) * d, sq);
+            int64_t base = ((int64_t)s * Hkv + h / r) * Tcap;
+            int64_t o = ((int64_t)s * Hq + h) * d;
+            h1bkv_oracle_decode_one_dtau(sq, sketches + base * W, codes + base * (d / 2), scale + base * ng,
+                                         zero + base * ng, ctx_len[s], b, d, G, tau, out + o, dout + o);
+        }
+}
+
+/*
  * One decode step over a whole batch held in canonical layout:
  *   sketches [B][H_kv][Tcap][W], codes [B][H_kv][Tcap][d/2], scale/zero [B][H_kv][Tcap][d/G],
  *   q [B][H_q][d] (fp32 values), ctx_len[B] <= Tcap, out [B][H_q][d].
