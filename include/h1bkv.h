@@ -155,6 +155,20 @@ int h1bkv_decode_step(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n_seq
                       float *out_dev, void *workspace_dev, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * Decode-step attention together with its derivative with respect to the temperature (Sec. IV-C: tau is the scalar the
+ * finetuning stage trains; Eq.(5)):  out as h1bkv_decode_attn, and
+ *   dout_dtau = -(1/tau^2) ( sum_t p_t alpha_t v_t / l - (sum_t p_t alpha_t / l) out ),  p_t = exp(alpha_t / tau), l = sum_t p_t
+ * -- the softmax-weighted covariance of scores and dequantised values over -tau^2; zero for T <= 1.
+ * out_dev, dout_dtau_dev: [n_seqs][n_q_heads][d] fp32.  Supported for 4-bit values with at most 2 query heads per KV
+ * head (the record-major code layout; H1BKV_ESHAPE otherwise).  workspace_dev: >=
+ * h1bkv_decode_dtau_workspace_bytes(c, n_seqs, longest T), 256-byte aligned.  Other arguments as h1bkv_decode_attn.
+ */
+size_t h1bkv_decode_dtau_workspace_bytes(const h1bkv_cache *c, int32_t n_seqs, int32_t max_ctx);
+int h1bkv_decode_attn_dtau(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n_seqs, const void *q_dev, float tau,
+                           float *out_dev, float *dout_dtau_dev, void *workspace_dev, size_t workspace_bytes,
+                           void *hip_stream);
+
+/*
  * Prefill attention (Sec. IV-A Eq.(3), Sec. IV-C Eq.(5) applied to every position of a prompt chunk): the n_q most
  * recent cached positions of every sequence are the queries.  Query i of sequence s (absolute position
  * len_s - n_q + i) attends to the cached tokens up to and including its own position, with the same scores, softmax

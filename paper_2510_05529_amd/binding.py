@@ -64,6 +64,8 @@ def lib() -> C.CDLL:
             "h1bkv_decode_workspace_bytes": (sz, [vp, i32, i32]),
             "h1bkv_decode_attn": (C.c_int, [vp, vp, i32, vp, C.c_float, vp, vp, sz, vp]),
             "h1bkv_decode_step": (C.c_int, [vp, vp, i32, vp, vp, i64, i64, vp, C.c_float, vp, vp, sz, vp]),
+            "h1bkv_decode_dtau_workspace_bytes": (sz, [vp, i32, i32]),
+            "h1bkv_decode_attn_dtau": (C.c_int, [vp, vp, i32, vp, C.c_float, vp, vp, vp, sz, vp]),
             "h1bkv_prefill_workspace_bytes": (sz, [vp, i32, i32]),
             "h1bkv_prefill_attn": (C.c_int, [vp, vp, i32, i32, vp, i64, i64, i64, C.c_float, vp, vp, sz, vp]),
             "h1bkv_set_decode_chunk": (C.c_int, [vp, i32]),
@@ -178,6 +180,16 @@ def h1bkv_decode_step(h, seq_ids, k, v, stride_seq: int, stride_head: int, q, ta
     ids, p = _ids(seq_ids)
     return lib().h1bkv_decode_step(h, p, len(ids), _dev_ptr(k), _dev_ptr(v), stride_seq, stride_head, _dev_ptr(q), tau,
                                    _dev_ptr(out), _dev_ptr(workspace), workspace_bytes, _stream(stream))
+
+
+def h1bkv_decode_dtau_workspace_bytes(h, n_seqs: int, max_ctx: int) -> int:
+    return lib().h1bkv_decode_dtau_workspace_bytes(h, n_seqs, max_ctx)
+
+
+def h1bkv_decode_attn_dtau(h, seq_ids, q, tau: float, out, dout, workspace, workspace_bytes: int, stream=0) -> int:
+    ids, p = _ids(seq_ids)
+    return lib().h1bkv_decode_attn_dtau(h, p, len(ids), _dev_ptr(q), tau, _dev_ptr(out), _dev_ptr(dout), _dev_ptr(workspace),
+                                        workspace_bytes, _stream(stream))
 
 
 def h1bkv_prefill_workspace_bytes(h, n_seqs: int, n_q: int) -> int:
@@ -308,6 +320,20 @@ class Cache:
             out = torch.empty((n, self.cfg.n_q_heads, self.d), dtype=torch.float32, device=q.device)
         check(h1bkv_decode_attn(self.h, seq_ids, q, tau, out, self.workspace, self.workspace.numel(), stream), "h1bkv_decode_attn")
         return out
+
+    def decode_dtau(self, seq_ids, q, tau: float, stream=None):
+        """Returns (out, d out / d tau), each [n_seqs][H_q][d] float32."""
+        import torch
+        n = len(seq_ids)
+        max_ctx = max(self.seq_len(s) for s in seq_ids)
+        need = h1bkv_decode_dtau_workspace_bytes(self.h, n, max_ctx)
+        if self.workspace is None or self.workspace.numel() < need:
+            self.workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+        out = torch.empty((n, self.cfg.n_q_heads, self.d), dtype=torch.float32, device=q.device)
+        dout = torch.empty_like(out)
+        check(h1bkv_decode_attn_dtau(self.h, seq_ids, q, tau, out, dout, self.workspace, self.workspace.numel(), stream),
+              "h1bkv_decode_attn_dtau")
+        return out, dout
 
     def prefill(self, seq_ids, q, tau: float, out=None, stream=None):
         """q: torch tensor [n_seqs][n_q][H_q][d] (dense last axis): the last n_q cached positions attend causally."""

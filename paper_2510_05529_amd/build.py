@@ -27,6 +27,7 @@ SOURCES = {
     "kernels_decode.hip": [],
     "kernels_decode_f16v.hip": [],
     "kernels_prefill.hip": [],
+    "kernels_decode_dtau.hip": [],
     # accumulators of the MFMA kernel stay in ordinary VGPRs: they are also touched by vector-ALU code (rescaling)
     "kernels_decode_mfma.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
 }

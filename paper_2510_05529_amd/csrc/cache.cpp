@@ -516,6 +516,78 @@ int h1bkv_decode_step(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n_seq
     return enqueue_decode(c, seq_ids_host, n_seqs, q_dev, tau, out_dev, workspace_dev, true, st);
 }
 
+size_t h1bkv_decode_dtau_workspace_bytes(const h1bkv_cache *c, int32_t n_seqs, int32_t max_ctx) {
+    if (!c || n_seqs < 1 || max_ctx < 0) return 0;
+    const size_t heads = (size_t)n_seqs * c->cfg.n_q_heads;
+    const size_t max_splits = std::max(1, pages_for(max_ctx));   // worst case: one page per chunk
+    size_t o = align_up(heads * c->W * 8);
+    o = align_up(o + heads * max_splits * 4 * sizeof(float));
+    o = align_up(o + heads * max_splits * c->cfg.head_dim * sizeof(float));
+    o = align_up(o + heads * max_splits * c->cfg.head_dim * sizeof(float));
+    return o;
+}
+
+int h1bkv_decode_attn_dtau(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n_seqs, const void *q_dev, float tau,
+                           float *out_dev, float *dout_dtau_dev, void *workspace_dev, size_t workspace_bytes,
+                           void *hip_stream) {
+    if (!c) return H1BKV_ENULL;
+    int rc = check_seq_ids(c, seq_ids_host, n_seqs);
+    if (rc != H1BKV_OK) return rc;
+    if (!(tau > 0.0f) || !std::isfinite(tau)) return H1BKV_EINVAL;
+    if (c->code_layout != 0) return H1BKV_ESHAPE;
+    if (c->dry) return H1BKV_ENODEVICE;
+    if (!q_dev || !out_dev || !dout_dtau_dev || !workspace_dev) return H1BKV_ENULL;
+    if (reinterpret_cast<uintptr_t>(workspace_dev) % kAlign || reinterpret_cast<uintptr_t>(q_dev) % 16 ||
+        reinterpret_cast<uintptr_t>(out_dev) % 16 || reinterpret_cast<uintptr_t>(dout_dtau_dev) % 16)
+        return H1BKV_EINVAL;
+    int max_ctx = 0;
+    for (int i = 0; i < n_seqs; ++i) max_ctx = std::max(max_ctx, c->seq_len[seq_ids_host[i]]);
+    if (workspace_bytes < h1bkv_decode_dtau_workspace_bytes(c, n_seqs, max_ctx)) return H1BKV_EWORKSPACE;
+    rc = check_device(c);
+    if (rc != H1BKV_OK) return rc;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+
+    const int chunk = choose_chunk(c, n_seqs, max_ctx);
+    const int S = std::max(1, (max_ctx + chunk - 1) / chunk);
+    const size_t heads = (size_t)n_seqs * c->cfg.n_q_heads;
+    char *ws = static_cast<char *>(workspace_dev);
+    DecodeArgs a{};
+    a.pool = c->view();
+    a.q = q_dev;
+    a.q_sketch = reinterpret_cast<uint64_t *>(ws);
+    size_t o = align_up(heads * c->W * 8);
+    a.part_ml = reinterpret_cast<float *>(ws + o);
+    o = align_up(o + heads * S * 4 * sizeof(float));
+    a.part_o = reinterpret_cast<float *>(ws + o);
+    o = align_up(o + heads * S * c->cfg.head_dim * sizeof(float));
+    a.part_oh = reinterpret_cast<float *>(ws + o);
+    a.out = out_dev;
+    a.dout = dout_dtau_dev;
+    a.n_splits = S;
+    a.chunk = chunk;
+    a.f16 = c->cfg.in_dtype == H1BKV_F16;
+    a.exp2_scale = (float)(2.0 * 1.4426950408889634 / ((double)c->cfg.sketch_bits * (double)tau));
+    const float dtau_scale = (float)(2.0 / ((double)c->cfg.sketch_bits * (double)tau * (double)tau));
+    for (int s0 = 0; s0 < n_seqs; s0 += kMaxSeqsPerLaunch) {
+        const int n = std::min(kMaxSeqsPerLaunch, n_seqs - s0);
+        BatchDesc desc;
+        for (int i = 0; i < n; ++i) desc.s[i] = SeqDesc{seq_ids_host[s0 + i], c->seq_len[seq_ids_host[s0 + i]]};
+        {
+            Timed t(c, H1BKV_K_QSKETCH, st);
+            if (launch_qsketch(a, s0, n, st) != hipSuccess) return H1BKV_EHIP;
+        }
+        {
+            Timed t(c, H1BKV_K_DECODE_SPLIT, st);
+            if (launch_decode_dtau_split(a, desc, s0, n, st) != hipSuccess) return H1BKV_EHIP;
+        }
+        {
+            Timed t(c, H1BKV_K_MERGE, st);
+            if (launch_merge_dtau(a, desc, s0, n, dtau_scale, st) != hipSuccess) return H1BKV_EHIP;
+        }
+    }
+    return H1BKV_OK;
+}
+
 size_t h1bkv_prefill_workspace_bytes(const h1bkv_cache *c, int32_t n_seqs, int32_t n_q) {
     if (!c || n_seqs < 1 || n_q < 1) return 0;
     return align_up((size_t)n_seqs * n_q * c->cfg.n_q_heads * c->W * 8);

@@ -77,6 +77,8 @@ struct DecodeArgs {
     float *part_ml;           // workspace: [n_seqs][H_q][S][2]  (min Hamming distance as int bits, sum of p)
     float *part_o;            // workspace: [n_seqs][H_q][S][d]
     float *out;               // [n_seqs][H_q][d]
+    float *part_oh;           // temperature-derivative path only: workspace [n_seqs][H_q][S][d], distance-weighted sums
+    float *dout;              // temperature-derivative path only: [n_seqs][H_q][d]
     int32_t n_splits;         // S: chunks of the longest context in the call
     int32_t chunk;            // tokens per chunk (multiple of the page size)
     int32_t f16;
@@ -118,6 +120,8 @@ hipError_t launch_qsketch(const DecodeArgs &a, int seq0, int n_seqs, hipStream_t
 hipError_t launch_decode_split(const DecodeArgs &a, const BatchDesc &desc, int seq0, int n_seqs, hipStream_t st);
 hipError_t launch_decode_split_mfma(const DecodeArgs &a, const BatchDesc &desc, int seq0, int n_seqs, hipStream_t st);
 hipError_t launch_decode_split_f16v(const DecodeArgs &a, const BatchDesc &desc, int seq0, int n_seqs, hipStream_t st);
+hipError_t launch_decode_dtau_split(const DecodeArgs &a, const BatchDesc &desc, int seq0, int n_seqs, hipStream_t st);
+hipError_t launch_merge_dtau(const DecodeArgs &a, const BatchDesc &desc, int seq0, int n_seqs, float dtau_scale, hipStream_t st);
 hipError_t launch_merge(const DecodeArgs &a, const BatchDesc &desc, int seq0, int n_seqs, hipStream_t st);
 hipError_t launch_sketch_rows(const PrefillArgs &a, int n_seqs, hipStream_t st);
 hipError_t launch_prefill(const PrefillArgs &a, const BatchDesc &desc, int seq0, int n_seqs, hipStream_t st);
