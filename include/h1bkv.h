@@ -77,7 +77,7 @@ const char *h1bkv_strerror(int code);
 
 /*
  * Device bytes the caller must provide as the pool for this geometry (0 if cfg is NULL or invalid).
- * The pool holds R and its transpose, the block table, and three planes per page:
+ * The pool holds R, its transpose and its fp16 pieces, the block table, and three planes per page:
  * sketches [page][H_kv][256][W] u64 (Eq.(2)), codes [page][H_kv][256][d/2] u8 and
  * {fp16 scale, fp16 zero} pairs [page][H_kv][256][n_g] (Eq.(4)).  With value_bits = 16 the last two planes are
  * replaced by one plane of fp16 values [page][H_kv][256][d].
@@ -191,6 +191,15 @@ int h1bkv_prefill_attn(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n_se
  * fp32 summation order.
  */
 int h1bkv_set_decode_chunk(h1bkv_cache *c, int32_t chunk_tokens);
+
+/*
+ * Tuning switch for the key projection of Eq.(2) in prefill-sized h1bkv_append_kv calls (fp16 inputs, n_new >= 16) and in
+ * h1bkv_prefill_attn's query sketches: 1 (default) computes the projections on the matrix cores from an exact two-piece
+ * fp16 split of R and recomputes, with the fp32 multiply-add chain stated at h1bkv_append_kv, every bit whose
+ * projection lies inside a guard band around zero that bounds the difference between the two evaluations -- the stored
+ * bits are those of the chain either way; 0 always runs the chain.
+ */
+int h1bkv_set_projection_path(h1bkv_cache *c, int32_t use_matrix_cores);
 
 /*
  * Canonical, layout-independent view of cached records (synchronous: waits for the device first).

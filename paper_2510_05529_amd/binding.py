@@ -69,6 +69,7 @@ def lib() -> C.CDLL:
             "h1bkv_prefill_workspace_bytes": (sz, [vp, i32, i32]),
             "h1bkv_prefill_attn": (C.c_int, [vp, vp, i32, i32, vp, i64, i64, i64, C.c_float, vp, vp, sz, vp]),
             "h1bkv_set_decode_chunk": (C.c_int, [vp, i32]),
+            "h1bkv_set_projection_path": (C.c_int, [vp, i32]),
             "h1bkv_export_tokens": (C.c_int, [vp, i32, i32, i32, i32, vp, vp, vp, vp]),
             "h1bkv_import_tokens": (C.c_int, [vp, i32, i32, i32, i32, vp, vp, vp, vp]),
             "h1bkv_extend_seq": (C.c_int, [vp, i32, i32, vp]),
@@ -205,6 +206,10 @@ def h1bkv_prefill_attn(h, seq_ids, n_q: int, q, stride_seq: int, stride_tok: int
 
 def h1bkv_set_decode_chunk(h, chunk_tokens: int) -> int:
     return lib().h1bkv_set_decode_chunk(h, chunk_tokens)
+
+
+def h1bkv_set_projection_path(h, use_matrix_cores: int) -> int:
+    return lib().h1bkv_set_projection_path(h, use_matrix_cores)
 
 
 def h1bkv_export_tokens(h, seq_id: int, kv_head: int, t0: int, n: int, W: int, d: int, n_g: int, value_bits: int = 4):

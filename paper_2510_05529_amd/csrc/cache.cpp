@@ -16,7 +16,7 @@ constexpr size_t kAlign = 256;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
-    size_t off_R, off_RT, off_bt, off_sketch, off_codes, off_meta, total;
+    size_t off_R, off_RT, off_R16hi, off_R16mid, off_guard, off_bt, off_sketch, off_codes, off_meta, total;
 };
 
 bool config_ok(const h1bkv_config *c) {
@@ -41,6 +41,9 @@ Layout make_layout(const h1bkv_config &c) {
     size_t o = 0;
     L.off_R = o;       o = align_up(o + b * d * sizeof(float));
     L.off_RT = o;      o = align_up(o + b * d * sizeof(float));
+    L.off_R16hi = o;   o = align_up(o + b * d * sizeof(uint16_t));
+    L.off_R16mid = o;  o = align_up(o + b * d * sizeof(uint16_t));
+    L.off_guard = o;   o = align_up(o + b * sizeof(float));
     L.off_bt = o;      o = align_up(o + (size_t)c.max_seqs * c.max_pages_per_seq * sizeof(int32_t));
     L.off_sketch = o;  o = align_up(o + rec * W * 8);
     const bool f16v = c.value_bits == 16;
@@ -48,6 +51,68 @@ Layout make_layout(const h1bkv_config &c) {
     L.off_meta = o;    o = align_up(o + (f16v ? 0 : rec * ng * 4));
     L.total = o;
     return L;
+}
+
+// IEEE binary16 <-> binary32 on the host (round to nearest even), for the fp16 pieces of R.
+uint16_t f32_to_f16(float f) {
+    uint32_t x;
+    std::memcpy(&x, &f, 4);
+    const uint16_t sign = (uint16_t)((x >> 16) & 0x8000u);
+    const uint32_t ax = x & 0x7FFFFFFFu;
+    if (ax >= 0x7F800000u) return (uint16_t)(sign | 0x7C00u | (ax > 0x7F800000u ? 0x200u : 0u));
+    if (ax >= 0x477FF000u) return (uint16_t)(sign | 0x7C00u);
+    if (ax <= 0x33000000u) return sign;
+    const int e = (int)(ax >> 23) - 127;
+    const uint32_t m = (ax & 0x7FFFFFu) | 0x800000u;
+    const int shift = e < -14 ? 13 + (-14 - e) : 13;
+    uint32_t kept = m >> shift;
+    const uint32_t rem = m & ((1u << shift) - 1u), half = 1u << (shift - 1);
+    if (rem > half || (rem == half && (kept & 1u))) kept++;
+    const uint32_t out = e < -14 ? kept : ((uint32_t)(e + 15) << 10) + (kept - 0x400u);
+    return (uint16_t)(sign | out);
+}
+double f16_to_f64(uint16_t h) {
+    const int e = (h >> 10) & 0x1F, m = h & 0x3FF;
+    double v = e == 0 ? std::ldexp((double)m, -24) : std::ldexp((double)(m | 0x400), e - 25);
+    return (h & 0x8000u) ? -v : v;
+}
+
+// Pieces of R for the matrix-core projection and the guard band that keeps the sketch bits exactly those of the
+// pinned fp32 chain (Eq.(2): bit = (y >= 0) with y = fma-chain over j).
+//   hi = fp16(R), mid = fp16((R - hi) 2^12):  R = hi + 2^-12 mid + delta, |delta| tiny.
+// The kernel computes y~ = sum_j (hi_j + 2^-12 mid_j) k_j with fp32 accumulation (products of two fp16 numbers are
+// exact in fp32).  Against the chain value y:
+//   |y~ - y| <= sum_j |delta_j| |k_j|                       (pieces)             <= ||delta||_2 ||k||_2
+//            + (rounding of the chain: d steps of 2^-24 relative to sum |R_j k_j|)  <= d 2^-24 ||R||_2 ||k||_2
+//            + (rounding of the matrix-core accumulation, any order, two piece sums and their combination;
+//               allowed three times the chain's)                                     <= 3 d 2^-24 ||R||_2 ||k||_2
+//            + (a piece that is an fp16 subnormal may be read as zero)              <= ||flush||_2 ||k||_2.
+// guard[i] is twice the sum of these row factors; a bit with |y~| <= guard[i] ||k||_2 is recomputed with the chain.
+void make_projection_pieces(const float *R, int b, int d, std::vector<uint16_t> &hi, std::vector<uint16_t> &mid,
+                            std::vector<float> &guard) {
+    hi.resize((size_t)b * d);
+    mid.resize((size_t)b * d);
+    guard.resize(b);
+    for (int i = 0; i < b; ++i) {
+        double n2 = 0.0, delta2 = 0.0, flush2 = 0.0;
+        for (int j = 0; j < d; ++j) {
+            const size_t e = (size_t)i * d + j;
+            const double r = (double)R[e];
+            hi[e] = f32_to_f16(R[e]);
+            const double h = f16_to_f64(hi[e]);
+            mid[e] = f32_to_f16((float)((r - h) * 4096.0));          // r - h is exact in double, and in float after scaling
+            const double m = f16_to_f64(mid[e]);
+            const double delta = r - (h + m / 4096.0);
+            n2 += r * r;
+            delta2 += delta * delta;
+            double fl = 0.0;
+            if ((hi[e] & 0x7C00u) == 0) fl += std::fabs(h);
+            if ((mid[e] & 0x7C00u) == 0) fl += std::fabs(m) / 4096.0;
+            flush2 += fl * fl;
+        }
+        const double g = 2.0 * (std::sqrt(delta2) + 4.0 * d * std::ldexp(1.0, -24) * std::sqrt(n2) + std::sqrt(flush2));
+        guard[i] = std::nextafter((float)g, INFINITY);
+    }
 }
 
 struct EventPair {
@@ -68,6 +133,7 @@ struct h1bkv_cache {
     std::vector<std::vector<int32_t>> seq_pages;
     std::vector<int32_t> free_list;     // stack of free page ids
     int32_t chunk_override;
+    int32_t proj_mfma;     // 1: matrix-core projection where it applies (default); 0: always the plain fp32 chain
     // profiling
     int32_t prof_cap;
     uint32_t prof_mask;
@@ -80,6 +146,9 @@ struct h1bkv_cache {
         PoolView v{};
         v.R = reinterpret_cast<const float *>(pool + lay.off_R);
         v.RT = reinterpret_cast<const float *>(pool + lay.off_RT);
+        v.R16hi = reinterpret_cast<const uint16_t *>(pool + lay.off_R16hi);
+        v.R16mid = reinterpret_cast<const uint16_t *>(pool + lay.off_R16mid);
+        v.guard = reinterpret_cast<const float *>(pool + lay.off_guard);
         v.block_table = reinterpret_cast<int32_t *>(pool + lay.off_bt);
         v.sketch = reinterpret_cast<uint64_t *>(pool + lay.off_sketch);
         v.codes = reinterpret_cast<uint8_t *>(pool + lay.off_codes);
@@ -250,6 +319,7 @@ int h1bkv_create(const h1bkv_config *cfg, void *pool_dev, size_t pool_bytes, con
     c->free_list.resize(cfg->max_pages);
     for (int i = 0; i < cfg->max_pages; ++i) c->free_list[i] = cfg->max_pages - 1 - i;  // page 0 is taken first
     c->chunk_override = 0;
+    c->proj_mfma = 1;
     c->prof_cap = 0;
     c->prof_mask = 0;
     c->prof_stride = 1;
@@ -266,6 +336,12 @@ int h1bkv_create(const h1bkv_config *cfg, void *pool_dev, size_t pool_bytes, con
         bool ok = hipDeviceSynchronize() == hipSuccess;
         ok = ok && hipMemcpy(c->pool + lay.off_R, R_host, nR * sizeof(float), hipMemcpyHostToDevice) == hipSuccess;
         ok = ok && hipMemcpy(c->pool + lay.off_RT, RT.data(), nR * sizeof(float), hipMemcpyHostToDevice) == hipSuccess;
+        std::vector<uint16_t> hi, mid;
+        std::vector<float> guard;
+        make_projection_pieces(R_host, cfg->sketch_bits, cfg->head_dim, hi, mid, guard);
+        ok = ok && hipMemcpy(c->pool + lay.off_R16hi, hi.data(), nR * sizeof(uint16_t), hipMemcpyHostToDevice) == hipSuccess;
+        ok = ok && hipMemcpy(c->pool + lay.off_R16mid, mid.data(), nR * sizeof(uint16_t), hipMemcpyHostToDevice) == hipSuccess;
+        ok = ok && hipMemcpy(c->pool + lay.off_guard, guard.data(), guard.size() * sizeof(float), hipMemcpyHostToDevice) == hipSuccess;
         ok = ok && hipMemset(c->pool + lay.off_bt, 0, (size_t)cfg->max_seqs * cfg->max_pages_per_seq * sizeof(int32_t)) == hipSuccess;
         ok = ok && hipDeviceSynchronize() == hipSuccess;
         if (!ok) {
@@ -322,6 +398,13 @@ int h1bkv_set_decode_chunk(h1bkv_cache *c, int32_t chunk_tokens) {
     if (!c) return H1BKV_ENULL;
     if (chunk_tokens != 0 && (chunk_tokens < kPage || chunk_tokens > max_decode_chunk(c->r, c->code_layout) || chunk_tokens % kPage != 0)) return H1BKV_EINVAL;
     c->chunk_override = chunk_tokens;
+    return H1BKV_OK;
+}
+
+int h1bkv_set_projection_path(h1bkv_cache *c, int32_t use_matrix_cores) {
+    if (!c) return H1BKV_ENULL;
+    if (use_matrix_cores != 0 && use_matrix_cores != 1) return H1BKV_EINVAL;
+    c->proj_mfma = use_matrix_cores;
     return H1BKV_OK;
 }
 
@@ -384,6 +467,9 @@ static int enqueue_append(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n
         a.stride_head = stride_head;
         a.n_new = n_new;
         a.f16 = c->cfg.in_dtype == H1BKV_F16;
+        // prefill-sized appends of fp16 keys take the matrix-core projection; short ones (a decode step's single
+        // token) stay on the plain chain, which is launch-bound there anyway
+        a.proj_mfma = a.f16 && n_new >= 16 && c->proj_mfma;
         for (int s0 = 0; s0 < n_seqs && rc == H1BKV_OK; s0 += kMaxSeqsPerLaunch) {
             const int n = std::min(kMaxSeqsPerLaunch, n_seqs - s0);
             BatchDesc desc;

@@ -34,6 +34,12 @@ struct TablePairs {
 struct PoolView {
     const float *R;          // [b][d]
     const float *RT;         // [d][b]
+    // Matrix-core projection (append of fp16 keys, prefill query sketches): R split into two fp16 pieces,
+    // R ~ R16hi + 2^-12 R16mid, and per row the guard band factor: a projection whose magnitude exceeds
+    // guard[i] * ||k||_2 has the sign of the pinned fp32 chain for certain (see make_projection_pieces in cache.cpp).
+    const uint16_t *R16hi;   // [b][d] fp16 bits
+    const uint16_t *R16mid;  // [b][d] fp16 bits
+    const float *guard;      // [b]
     int32_t *block_table;    // [max_seqs][max_pages_per_seq]
     uint64_t *sketch;        // [page][H_kv][256][W]
     uint8_t *codes;          // [page][H_kv][256][d/2]
@@ -62,6 +68,7 @@ struct AppendArgs {
     int64_t stride_seq, stride_tok, stride_head;
     int32_t n_new;
     int32_t f16;
+    int32_t proj_mfma;       // sketch bits from the matrix-core projection plus exact recomputation inside the guard band
 };
 
 struct QueryArgs {            // query vectors sketched by the fused decode-step prologue

@@ -58,3 +58,30 @@ def test_geometry(d, b, g, r, dt):
         out = cache.decode(seqs, to_dev(q), tau).cpu().numpy()
         assert rel_err(out, oc.decode(q, tau)) <= TOL
     cache.close()
+
+
+@pytest.mark.parametrize("scale", [2.0 ** -20, 2.0 ** -14, 300.0])
+def test_sketch_bits_stay_exact_for_tiny_and_large_fp16_keys(scale):
+    """Prefill-sized appends of fp16 keys project on the matrix cores and recompute only the bits inside a guard band
+    with the pinned fp32 chain: the stored bits must be the chain's also when the keys are fp16 subnormals (scale
+    2^-20), straddle the subnormal boundary (2^-14) or are large."""
+    d, b, g, T = 128, 256, 32, 700
+    w = wl.Workload(f"tiny_keys_{scale}", 2, 2, 2, d, T, b, g, "f16", seed=17)
+    R = wl.projection(b, d)
+    seqs = [0, 1]
+    k = (wl.kv_slab(w, "k", seqs, 0, T).astype(np.float32) * scale).astype(np.float16)
+    v = wl.kv_slab(w, "v", seqs, 0, T)
+    if scale < 1e-3:
+        assert (np.abs(k[k != 0]) < 6.2e-5).mean() > 0.3          # a good share of subnormal elements
+    oc = cref.Cache(R, 2, 2, T, g)
+    oc.append(k, v)
+    cache = make_cache(w, R)
+    cache.append(seqs, to_dev(k), to_dev(v))
+    assert_cache_equal(cache, oc, seqs, T)
+    # the plain chain on the same input gives the same cache
+    cache2 = make_cache(w, R)
+    assert B.h1bkv_set_projection_path(cache2.h, 0) == B.H1BKV_OK
+    cache2.append(seqs, to_dev(k), to_dev(v))
+    assert_cache_equal(cache2, oc, seqs, T)
+    cache.close()
+    cache2.close()
