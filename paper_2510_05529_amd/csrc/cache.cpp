@@ -712,6 +712,7 @@ int h1bkv_prefill_attn(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n_se
     a.out = out_dev;
     a.n_q = n_q;
     a.f16 = c->cfg.in_dtype == H1BKV_F16;
+    a.proj_mfma = a.f16 && c->proj_mfma && (int64_t)n_seqs * n_q * c->cfg.n_q_heads >= 64;
     a.exp2_scale = (float)(2.0 * 1.4426950408889634 / ((double)c->cfg.sketch_bits * (double)tau));
     {
         Timed t(c, H1BKV_K_QSKETCH, st);

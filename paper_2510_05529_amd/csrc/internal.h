@@ -100,6 +100,7 @@ struct PrefillArgs {
     float *out;               // [n_seqs][n_q][H_q][d]
     int32_t n_q;              // query positions per sequence: the last n_q cached positions
     int32_t f16;
+    int32_t proj_mfma;        // query sketches from the matrix-core projection (fp16 queries)
     float exp2_scale;         // 2 log2(e) / (b tau)
 };
 

@@ -25,6 +25,7 @@
 #include <hip/hip_fp16.h>
 
 #include "internal.h"
+#include "projection_mfma.h"
 
 namespace h1bkv {
 
@@ -59,9 +60,6 @@ __device__ __forceinline__ void copy8(const float *src, float *dst) {
 
 // bx, by, gx: the workgroup's tile index, its sequence (index into desc) and the number of workgroups that share
 // the sequence's tiles -- blockIdx.x, blockIdx.y, gridDim.x when the kernel does nothing else.
-typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-
 // MF: the projections come from the matrix cores (fp16 keys only) and only the bits inside the guard band are
 // recomputed with the chain; see the projection block below.
 template <int D, typename T, bool MF>
@@ -69,6 +67,7 @@ __device__ __forceinline__ void append_body(const AppendArgs &a, const BatchDesc
     constexpr int KPAD = 16 / sizeof(T);                      // 16 bytes per row: conflict-free 16-byte reads down a column
     __shared__ __attribute__((aligned(16))) T ks[kTile][D + KPAD];   // the key tile in its boundary dtype
     __shared__ uint32_t unsure[MF ? kTile : 1][16];   // matrix-core path: per token, the sketch bits that need the chain
+    static_assert(kTile == kProjTile && kThreads == kProjThreads, "projection_mfma.h assumes this tile shape");
     __shared__ uint64_t words[kTile][8];              // sketch words of the tile (W <= 8)
     __shared__ size_t dst[kTile];                     // plane index of each slot: (page * H_kv + head) * 256 + slot in page
     __shared__ size_t src_off[kTile];                 // element offset of each slot's K / V row; kNoRow marks padding
@@ -147,92 +146,9 @@ __device__ __forceinline__ void append_body(const AppendArgs &a, const BatchDesc
         __syncthreads();
 
         if constexpr (MF) {
-            // ---- Eq.(2) on the matrix cores.  y~ = sum_j (R16hi + 2^-12 R16mid)[bit][j] k[j] with fp32 accumulation
-            // differs from the pinned chain value by less than guard[bit] ||k||_2 (bound derived where the pieces are
-            // made), so sign(y~) IS the chain's bit wherever |y~| exceeds that; the few bits inside the band are
-            // recomputed with the chain itself.  (fp16 subnormals in the keys enter the matrix cores as they are:
-            // kernels run with fp16 denormals enabled; a parity test feeds keys in that range.) ----
-            uint32_t *w32 = reinterpret_cast<uint32_t *>(&words[0][0]);      // [kTile][16]: the sketch words as 32-bit halves
-            const int n = lane & 15, kb = lane >> 4;
-            const int n_tb = (tile + 15) / 16;
-            for (int bb = wave; bb < pv.sketch_bits / 16; bb += 4) {        // blocks of 16 sketch bits
-                uint4 Ahi[D / 32], Amid[D / 32];
-                const size_t arow = (size_t)(16 * bb + n) * D + 8 * kb;
-#pragma unroll
-                for (int jb = 0; jb < D / 32; ++jb) {
-                    Ahi[jb] = *reinterpret_cast<const uint4 *>(pv.R16hi + arow + 32 * jb);
-                    Amid[jb] = *reinterpret_cast<const uint4 *>(pv.R16mid + arow + 32 * jb);
-                }
-                float g[4];
-#pragma unroll
-                for (int jj = 0; jj < 4; ++jj) g[jj] = pv.guard[16 * bb + 4 * kb + jj];
-#pragma unroll 1
-                for (int tb = 0; tb < n_tb; ++tb) {
-                    f32x4 yh = {0.f, 0.f, 0.f, 0.f}, ym = {0.f, 0.f, 0.f, 0.f};
-                    const int tok = 16 * tb + n;
-                    float ss = 0.0f;
-#pragma unroll
-                    for (int jb = 0; jb < D / 32; ++jb) {
-                        const f16x8 Bk = *reinterpret_cast<const f16x8 *>(&ks[tok][32 * jb + 8 * kb]);
-                        yh = __builtin_amdgcn_mfma_f32_16x16x32_f16(*reinterpret_cast<const f16x8 *>(&Ahi[jb]), Bk, yh, 0, 0, 0);
-                        ym = __builtin_amdgcn_mfma_f32_16x16x32_f16(*reinterpret_cast<const f16x8 *>(&Amid[jb]), Bk, ym, 0, 0, 0);
-                        // 2-norm of the lane's token on the side: the lane reads a quarter of the key as its B
-                        // operands, the other quarters sit in the lanes 16, 32 and 48 away
-#pragma unroll
-                        for (int e = 0; e < 8; ++e) ss = fmaf((float)Bk[e], (float)Bk[e], ss);
-                    }
-                    ss += __shfl_xor(ss, 16);
-                    ss += __shfl_xor(ss, 32);
-                    const float band = sqrtf(ss) * 1.0000153f;        // fp32 rounding of the sum and the root stays below 2^-16
-                    // element jj of this lane: bit 16 bb + 4 kb + jj of token `tok`
-                    if (tok < tile && valid_slot(tok)) {
-                        uint32_t sbits = 0u, ubits = 0u;
-#pragma unroll
-                        for (int jj = 0; jj < 4; ++jj) {
-                            const float y = fmaf(ym[jj], 0.000244140625f, yh[jj]);
-                            sbits |= (y >= 0.0f ? 1u : 0u) << jj;
-                            ubits |= (fabsf(y) > g[jj] * band ? 0u : 1u) << jj;          // also catches a NaN
-                        }
-                        const int sh = 16 * (bb & 1) + 4 * kb;
-                        atomicOr(&w32[tok * 16 + (bb >> 1)], sbits << sh);
-                        if (ubits) atomicOr(&unsure[tok][bb >> 1], ubits << sh);
-                    }
-                }
-            }
-            __syncthreads();
-            // ---- the chain for the bits inside the guard band: one thread per (token, 32 bits) ----
-            const int W32 = pv.sketch_bits / 32;
-            for (int item = tid; item < tile * W32; item += kThreads) {
-                const int tok = item / W32, w = item - tok * W32;
-                if (!valid_slot(tok)) continue;
-                uint32_t m = unsure[tok][w];
-                if (m == 0u) continue;
-                uint32_t cur = w32[tok * 16 + w];
-                while (m) {
-                    const int p = __ffs(m) - 1;
-                    m &= m - 1u;
-                    const float *row = pv.R + (size_t)(32 * w + p) * D;
-                    float y = 0.0f;
-                    // 32 elements of the row at a time: all their loads are in flight before the (sequential) chain runs
-#pragma unroll 1
-                    for (int j0 = 0; j0 < D; j0 += 32) {
-                        float4 rr[8];
-#pragma unroll
-                        for (int q = 0; q < 8; ++q) rr[q] = *reinterpret_cast<const float4 *>(row + j0 + 4 * q);
-#pragma unroll
-                        for (int q = 0; q < 8; q += 2) {
-                            float kk[8];
-                            load8(&ks[tok][j0 + 4 * q], kk);
-                            y = __builtin_fmaf(rr[q].x, kk[0], y); y = __builtin_fmaf(rr[q].y, kk[1], y);
-                            y = __builtin_fmaf(rr[q].z, kk[2], y); y = __builtin_fmaf(rr[q].w, kk[3], y);
-                            y = __builtin_fmaf(rr[q + 1].x, kk[4], y); y = __builtin_fmaf(rr[q + 1].y, kk[5], y);
-                            y = __builtin_fmaf(rr[q + 1].z, kk[6], y); y = __builtin_fmaf(rr[q + 1].w, kk[7], y);
-                        }
-                    }
-                    cur = y >= 0.0f ? (cur | (1u << p)) : (cur & ~(1u << p));
-                }
-                w32[tok * 16 + w] = cur;
-            }
+            // ---- Eq.(2) on the matrix cores; the bits inside the guard band by the chain (projection_mfma.h) ----
+            project_tile_mfma<D>(pv, reinterpret_cast<const __half *>(&ks[0][0]), D + KPAD, tile, valid_slot,
+                                 reinterpret_cast<uint32_t *>(&words[0][0]), &unsure[0][0]);
         } else
         // ---- Eq.(2): lane = sketch bit; y = fma chain over j; ballot = packed word ----
         for (int word = wave % wslots; word < W; word += wslots) {

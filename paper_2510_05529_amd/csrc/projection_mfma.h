@@ -1,0 +1,125 @@
+// Eq.(2) on the matrix cores with an exactness guard band, shared by the append kernel (keys) and the prefill query
+// sketches.  For a tile of up to 64 fp16 vectors in LDS,
+//   y~[bit][vec] = sum_j (R16hi + 2^-12 R16mid)[bit][j] x[vec][j]      (v_mfma_f32_16x16x32_f16, fp32 accumulation)
+// differs from the pinned fp32 multiply-add chain's value by less than guard[bit] ||x||_2 (bound derived where the
+// pieces of R are made), so sign(y~) IS the chain's bit wherever |y~| exceeds that; the few bits inside the band are
+// recomputed with the chain itself.  fp16 subnormals in x enter the matrix cores as they are (kernels run with fp16
+// denormals enabled; a parity test feeds inputs in that range).
+#pragma once
+
+#include <hip/hip_fp16.h>
+
+#include "internal.h"
+
+namespace h1bkv {
+namespace {
+
+typedef _Float16 proj_f16x8 __attribute__((ext_vector_type(8)));
+typedef float proj_f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kProjTile = 64;      // vectors per tile
+constexpr int kProjThreads = 256;
+
+__device__ __forceinline__ void proj_load8(const __half *p, float *out) {
+    const uint4 raw = *reinterpret_cast<const uint4 *>(p);
+    const __half2 *h = reinterpret_cast<const __half2 *>(&raw);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const float2 f = __half22float2(h[i]);
+        out[2 * i] = f.x;
+        out[2 * i + 1] = f.y;
+    }
+}
+
+// xs: the tile, row-major, `stride` halves per row (rows 16-byte aligned, stride a multiple of 8 and not of 64, so
+//     that 16-byte reads down a column spread over the LDS banks);  valid(v): whether row v holds a vector.
+// w32, unsure: [kProjTile][16] 32-bit words in LDS, all zero on entry.  On return (after the caller's next barrier)
+//     w32[v][0 .. b/32) holds the packed sketch of vector v.  Must be called by all 256 threads; contains a barrier.
+template <int D, typename Valid>
+__device__ __forceinline__ void project_tile_mfma(const PoolView &pv, const __half *xs, int stride, int tile, Valid valid,
+                                                  uint32_t *w32, uint32_t *unsure) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n = lane & 15, kb = lane >> 4;
+    const int n_tb = (tile + 15) / 16;
+    for (int bb = wave; bb < pv.sketch_bits / 16; bb += 4) {        // blocks of 16 sketch bits
+        uint4 Ahi[D / 32], Amid[D / 32];
+        const size_t arow = (size_t)(16 * bb + n) * D + 8 * kb;
+#pragma unroll
+        for (int jb = 0; jb < D / 32; ++jb) {
+            Ahi[jb] = *reinterpret_cast<const uint4 *>(pv.R16hi + arow + 32 * jb);
+            Amid[jb] = *reinterpret_cast<const uint4 *>(pv.R16mid + arow + 32 * jb);
+        }
+        float g[4];
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) g[jj] = pv.guard[16 * bb + 4 * kb + jj];
+#pragma unroll 1
+        for (int tb = 0; tb < n_tb; ++tb) {
+            proj_f32x4 yh = {0.f, 0.f, 0.f, 0.f}, ym = {0.f, 0.f, 0.f, 0.f};
+            const int v = 16 * tb + n;
+            float ss = 0.0f;
+#pragma unroll
+            for (int jb = 0; jb < D / 32; ++jb) {
+                const proj_f16x8 Bx = *reinterpret_cast<const proj_f16x8 *>(xs + (size_t)v * stride + 32 * jb + 8 * kb);
+                yh = __builtin_amdgcn_mfma_f32_16x16x32_f16(*reinterpret_cast<const proj_f16x8 *>(&Ahi[jb]), Bx, yh, 0, 0, 0);
+                ym = __builtin_amdgcn_mfma_f32_16x16x32_f16(*reinterpret_cast<const proj_f16x8 *>(&Amid[jb]), Bx, ym, 0, 0, 0);
+                // 2-norm of the lane's vector on the side: the lane reads a quarter of it as its B operands, the
+                // other quarters sit in the lanes 16, 32 and 48 away
+#pragma unroll
+                for (int e = 0; e < 8; ++e) ss = fmaf((float)Bx[e], (float)Bx[e], ss);
+            }
+            ss += __shfl_xor(ss, 16);
+            ss += __shfl_xor(ss, 32);
+            const float band = sqrtf(ss) * 1.0000153f;        // fp32 rounding of the sum and the root stays below 2^-16
+            // element jj of this lane: bit 16 bb + 4 kb + jj of vector v
+            if (v < tile && valid(v)) {
+                uint32_t sbits = 0u, ubits = 0u;
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) {
+                    const float y = fmaf(ym[jj], 0.000244140625f, yh[jj]);
+                    sbits |= (y >= 0.0f ? 1u : 0u) << jj;
+                    ubits |= (fabsf(y) > g[jj] * band ? 0u : 1u) << jj;          // also catches a NaN
+                }
+                const int sh = 16 * (bb & 1) + 4 * kb;
+                atomicOr(&w32[v * 16 + (bb >> 1)], sbits << sh);
+                if (ubits) atomicOr(&unsure[v * 16 + (bb >> 1)], ubits << sh);
+            }
+        }
+    }
+    __syncthreads();
+    // ---- the chain for the bits inside the guard band: one thread per (vector, 32 bits) ----
+    const int W32 = pv.sketch_bits / 32;
+    for (int item = tid; item < tile * W32; item += kProjThreads) {
+        const int v = item / W32, w = item - v * W32;
+        if (!valid(v)) continue;
+        uint32_t m = unsure[v * 16 + w];
+        if (m == 0u) continue;
+        uint32_t cur = w32[v * 16 + w];
+        while (m) {
+            const int p = __ffs(m) - 1;
+            m &= m - 1u;
+            const float *row = pv.R + (size_t)(32 * w + p) * D;
+            float y = 0.0f;
+            // 32 elements of the row at a time: all their loads are in flight before the (sequential) chain runs
+#pragma unroll 1
+            for (int j0 = 0; j0 < D; j0 += 32) {
+                float4 rr[8];
+#pragma unroll
+                for (int q = 0; q < 8; ++q) rr[q] = *reinterpret_cast<const float4 *>(row + j0 + 4 * q);
+#pragma unroll
+                for (int q = 0; q < 8; q += 2) {
+                    float kk[8];
+                    proj_load8(xs + (size_t)v * stride + j0 + 4 * q, kk);
+                    y = __builtin_fmaf(rr[q].x, kk[0], y); y = __builtin_fmaf(rr[q].y, kk[1], y);
+                    y = __builtin_fmaf(rr[q].z, kk[2], y); y = __builtin_fmaf(rr[q].w, kk[3], y);
+                    y = __builtin_fmaf(rr[q + 1].x, kk[4], y); y = __builtin_fmaf(rr[q + 1].y, kk[5], y);
+                    y = __builtin_fmaf(rr[q + 1].z, kk[6], y); y = __builtin_fmaf(rr[q + 1].w, kk[7], y);
+                }
+            }
+            cur = y >= 0.0f ? (cur | (1u << p)) : (cur & ~(1u << p));
+        }
+        w32[v * 16 + w] = cur;
+    }
+}
+
+}  // namespace
+}  // namespace h1bkv

@@ -91,3 +91,22 @@ def test_ragged_lengths_strided_queries_and_argument_checks():
     rc = B.h1bkv_prefill_attn(cache.h, seqs, 64, q65, q65.stride(0), q65.stride(1), q65.stride(2), 0.08, o65, ws, 16)
     assert rc == B.H1BKV_EWORKSPACE
     cache.close()
+
+
+@pytest.mark.parametrize("dt,scale", [("f16", 1.0), ("f16", 2.0 ** -18), ("f32", 1.0)])
+def test_query_sketches_are_bit_exact(dt, scale):
+    """The chunk's query sketches (the workspace's content: [n_seqs][n_q][H_q][W] words) must be the oracle's bits: fp16
+    queries are projected on the matrix cores with only the guard-band bits recomputed by the pinned chain."""
+    d, b, T, n_q = 128, 256, 400, 400
+    w = wl.Workload(f"prefill_qsk_{dt}", 2, 4, 2, d, T, b, 32, dt, seed=123)
+    R = wl.projection(b, d)
+    seqs = [0, 1]
+    k, v = wl.kv_slab(w, "k", seqs, 0, T), wl.kv_slab(w, "v", seqs, 0, T)
+    cache = make_cache(w, R)
+    cache.append(seqs, to_dev(k), to_dev(v))
+    q = (_queries(w, n_q).astype(np.float32) * scale).astype(np.float16 if dt == "f16" else np.float32)
+    cache.prefill(seqs, to_dev(q), 0.1)
+    n_words = 2 * n_q * w.n_q_heads * (b // 64)
+    got = cache.workspace[: n_words * 8].cpu().numpy().view(np.uint64).reshape(2, n_q, w.n_q_heads, b // 64)
+    assert np.array_equal(got, cref.sketch(R, q))
+    cache.close()
