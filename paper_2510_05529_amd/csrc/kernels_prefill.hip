@@ -34,7 +34,8 @@ namespace h1bkv {
 namespace {
 
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
-typedef __fp16 fp16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 h16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef int i32x4 __attribute__((ext_vector_type(4)));
 
@@ -316,7 +317,9 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs a, Bat
                         p0 = ham[rb][j] >= (1 << 20) ? 0.0f : p0;
                         p1 = ham[rb][j + 1] >= (1 << 20) ? 0.0f : p1;
                     }
-                    const fp16x2 pk = __builtin_amdgcn_cvt_pkrtz(p0, p1);
+                    // round to nearest (one packed convert on gfx950), not the truncating pack: half the weight error
+                    const f32x2 pf = {p0, p1};
+                    const h16x2 pk = __builtin_convertvector(pf, h16x2);
                     A[rb].u[j / 2] = *reinterpret_cast<const uint32_t *>(&pk);
                 }
             }
