@@ -86,8 +86,8 @@ __global__ __launch_bounds__(kThreads, 1) void decode_dtau_split_kernel(DecodeAr
         const uint4 *cp = reinterpret_cast<const uint4 *>(pv.codes) + (base * LPT + lane);
 #pragma unroll
         for (int it = 0; it < LPT; ++it) {
-            pr.c[it] = cp[it * 64];
-            pr.m[it] = pv.meta[(base + tok_v + it * TPW) * ng + meta_col];
+            pr.c[it] = load_stream(cp + it * 64);
+            pr.m[it] = load_stream(pv.meta + (base + tok_v + it * TPW) * ng + meta_col);
         }
     };
 

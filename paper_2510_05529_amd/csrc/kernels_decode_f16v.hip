@@ -122,7 +122,7 @@ __global__ __launch_bounds__(kThreads, RQ >= 8 ? 2 : (RQ >= 4 ? 3 : 4)) void dec
         const uint4 *vp = reinterpret_cast<const uint4 *>(pv.codes) + (base * LPT + lane);
         uint4 v[LPB];
 #pragma unroll
-        for (int it = 0; it < LPB; ++it) v[it] = vp[it * 64];
+        for (int it = 0; it < LPB; ++it) v[it] = load_stream(vp + it * 64);
         // ---- scoring role (Eq. 3), running maximum per query head ----
         const bool valid = !kMasked || tok0 + tok_s < n_tok;
         float p[RQ];
@@ -148,7 +148,7 @@ __global__ __launch_bounds__(kThreads, RQ >= 8 ? 2 : (RQ >= 4 ? 3 : 4)) void dec
             if constexpr (nb > 0) {
                 __builtin_amdgcn_sched_barrier(0);         // keep the next batch's loads behind this point
 #pragma unroll
-                for (int it = 0; it < LPB; ++it) v[it] = vp[(nb * LPB + it) * 64];
+                for (int it = 0; it < LPB; ++it) v[it] = load_stream(vp + (nb * LPB + it) * 64);
             }
             static_for<LPB>([&](auto itc) {
                 constexpr int it = decltype(itc)::value;

@@ -134,12 +134,12 @@ __global__ __launch_bounds__(kThreads, RQH == 2 ? 3 : 2) void decode_split_mfma_
         for (int t = 0; t < 2; ++t) {
             const uint64_t *sp = pv.sketch + (base + 32 * t + tk) * W;
             if (W == 1) {
-                pr.sk[t][0] = sp[0];
+                pr.sk[t][0] = load_stream(sp);
             } else {
 #pragma unroll
                 for (int w = 0; w < kMaxW; w += 2) {
                     if (w < W) {
-                        const uint4 v = *reinterpret_cast<const uint4 *>(sp + w);
+                        const uint4 v = load_stream(reinterpret_cast<const uint4 *>(sp + w));
                         pr.sk[t][w] = (uint64_t)v.x | ((uint64_t)v.y << 32);
                         pr.sk[t][w + 1] = (uint64_t)v.z | ((uint64_t)v.w << 32);
                     }
@@ -147,10 +147,10 @@ __global__ __launch_bounds__(kThreads, RQH == 2 ? 3 : 2) void decode_split_mfma_
             }
             const uint4 *cp = reinterpret_cast<const uint4 *>(pv.codes + (base + 32 * t + 8 * kb) * (D / 2)) + n;
 #pragma unroll
-            for (int i = 0; i < NCB4; ++i) pr.c[t][i] = cp[i * 16];
+            for (int i = 0; i < NCB4; ++i) pr.c[t][i] = load_stream(cp + i * 16);
             const uint32_t *mp = pv.meta + (base + 32 * t + tk) * NG;
 #pragma unroll
-            for (int g = 0; g < NG; ++g) pr.m[t][g] = mp[g];
+            for (int g = 0; g < NG; ++g) pr.m[t][g] = load_stream(mp + g);
         }
     };
 

@@ -21,6 +21,13 @@ __global__ __launch_bounds__(256) void stream_copy_kernel(uint4 *__restrict__ ds
 // Streaming read: every workgroup walks its own contiguous span with 8 independent 16-byte loads per lane in
 // flight (contiguous spans per workgroup read ~15 % faster on this part than a grid-stride interleave), XOR-folded
 // so the loads cannot be elided.
+// Non-temporal 16-byte load: the data is read once and should not stay in the last-level caches.
+__device__ __forceinline__ uint4 nt_load16(const uint4 *p) {
+    typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+    const u32x4 t = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+    return make_uint4(t.x, t.y, t.z, t.w);
+}
+
 __global__ __launch_bounds__(256) void stream_read_kernel(const uint4 *__restrict__ src, size_t n16, uint4 *__restrict__ sink) {
     constexpr int U = 8;
     const size_t per_block = (n16 + gridDim.x - 1) / gridDim.x;
@@ -30,14 +37,14 @@ __global__ __launch_bounds__(256) void stream_read_kernel(const uint4 *__restric
     for (; i + (U - 1) * 256 < b1; i += U * 256) {
         uint4 v[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) v[u] = src[i + u * 256];
+        for (int u = 0; u < U; ++u) v[u] = nt_load16(src + i + u * 256);
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             acc.x ^= v[u].x; acc.y ^= v[u].y; acc.z ^= v[u].z; acc.w ^= v[u].w;
         }
     }
     for (; i < b1; i += 256) {
-        const uint4 v = src[i];
+        const uint4 v = nt_load16(src + i);
         acc.x ^= v.x; acc.y ^= v.y; acc.z ^= v.z; acc.w ^= v.w;
     }
     // one store per workgroup: fold the lanes through the first lane of each wave
