@@ -10,8 +10,8 @@
 //            32 codes) and the 4-byte {scale, zero} pair of its group, so a wave instruction covers 1 KiB of
 //            contiguous codes; p_t comes from the scoring lane by a lane permute.  Dequantisation is folded into
 //            the weights:  sum_t p_t (scale_t code_tc + zero_t) = sum_t (p_t scale_t) code_tc + sum_t p_t zero_t,
-//            and the int4 -> float step rides on the FMA itself (nibbles OR-ed into the mantissa of an fp16
-//            constant, read by a mixed-precision FMA): 15 VALU instructions per 8 elements.
+//            and the int4 -> float step rides on the FMA itself (a masked nibble is read as an fp16 subnormal by a
+//            mixed-precision FMA): 13 VALU instructions per 8 elements.
 //            Loads for the next page (sketches, codes, scale/zero) are in flight while the current page is consumed.
 //   Epilogue sums over the token slots of a 16-lane row with DPP rotations, over rows and waves through LDS (each
 //            wave's part scaled to the common maximum), and writes the chunk's partial (min distance, sum p,
@@ -47,7 +47,7 @@ __global__ __launch_bounds__(kThreads, RQ >= 4 ? 2 : 1) void decode_split_kernel
     constexpr int TPW = 64 / LPT;                 // tokens covered by one wave-wide load of codes
     constexpr int ROWS = LPT == 8 ? 2 : 4;        // 16-lane rows of a wave that reach the LDS stage of the epilogue
     constexpr int NPART = kWaves * ROWS;
-    constexpr int EPI_STRIDE = D + 2 * LPT;       // per (partial, q): D sums, LPT zero-sums, LPT weight-sums
+    constexpr int EPI_STRIDE = D + LPT;           // per (partial, q): D sums, LPT zero-sums
     __shared__ float epi[NPART * RQ * EPI_STRIDE];
     __shared__ int pages_s[kMaxPagesPerChunk];
     __shared__ int m_s[kWaves][RQ];
@@ -82,15 +82,14 @@ __global__ __launch_bounds__(kThreads, RQ >= 4 ? 2 : 1) void decode_split_kernel
     const int slice = lane % LPT;
     const int tok_v = lane / LPT;                          // value role: token (within a 64-token share) of the first load
     const int meta_col = (slice * 32) / pv.group_size;
-    const uint32_t mask = opaque_vgpr(0x00F000F0u), magic = opaque_vgpr(0x64006400u);
+    const uint32_t mask_a = opaque_vgpr(0x000F000Fu), mask_b = opaque_vgpr(0x00F000F0u);
 
     float acc[RQ][32];
-    float zs[RQ], wsum[RQ], lsum[RQ];
+    float zs[RQ], lsum[RQ];
     int run_min[RQ];
 #pragma unroll
     for (int q = 0; q < RQ; ++q) {
         zs[q] = 0.0f;
-        wsum[q] = 0.0f;
         lsum[q] = 0.0f;
         run_min[q] = 1 << 20;
 #pragma unroll
@@ -108,11 +107,11 @@ __global__ __launch_bounds__(kThreads, RQ >= 4 ? 2 : 1) void decode_split_kernel
         }
     };
 
-    // A nibble is turned into an fp16 number without a convert instruction: shifted to mantissa bits 4-7 of
-    // 1024.0 (0x6400) and OR-ed in, it reads as 1024 + 16 code, two nibbles (n and n+4 of a dword) per 32-bit
-    // operation; the fp32 FMA takes the fp16 halves directly (mixed-precision FMA) with weight p scale / 16.
-    // The constant part, 64 times the running sum of weights, is taken off at the end.  (Leaving even nibbles
-    // at bits 0-3 would save two shifts per dword but puts a 1024-fold offset under the fp32 accumulation.)
+    // A nibble is turned into an fp16 number without a convert instruction and without an offset: masked in place
+    // at mantissa bits 0-3 or 4-7 of an otherwise zero half-word it IS the fp16 subnormal code 2^-24 or code 2^-20
+    // (two nibbles, n and n + 4 of a dword, per AND; one shift by 8 bits reaches the other four).  The fp32 FMA takes
+    // the fp16 halves directly (mixed-precision FMA, fp16 denormals are enabled) with the weight p scale scaled by
+    // 2^24 or 2^20 -- exact powers of two, so the products are the exact p scale code.
     auto consume_page = [&](const PageRegs<W, LPT> &pr, int pg) {
         // ---- scoring role: lane = token (Eq. 3), running maximum per query head ----
         const bool valid = pg * kPage + wave * 64 + lane < n_tok;
@@ -128,7 +127,6 @@ __global__ __launch_bounds__(kThreads, RQ >= 4 ? 2 : 1) void decode_split_kernel
                 run_min[q] = pmin;
                 lsum[q] *= f;
                 zs[q] *= f;
-                wsum[q] *= f;
 #pragma unroll
                 for (int i = 0; i < 32; ++i) acc[q][i] *= f;
             }
@@ -143,28 +141,30 @@ __global__ __launch_bounds__(kThreads, RQ >= 4 ? 2 : 1) void decode_split_kernel
             const uint32_t m = vvalid ? pr.m[it] : 0u;     // never let an unwritten slot's bits reach the FMAs
             const float sc = __half2float(__ushort_as_half((unsigned short)(m & 0xFFFFu)));
             const float zp = __half2float(__ushort_as_half((unsigned short)(m >> 16)));
-            float w16[RQ];
+            float wa[RQ], wb[RQ];
 #pragma unroll
             for (int q = 0; q < RQ; ++q) {
                 const float pt = __shfl(p[q], src_lane);
                 const float w = pt * sc;
-                w16[q] = w * 0.0625f;
+                wa[q] = w * 16777216.0f;                   // a nibble at mantissa bits 0-3 reads as code 2^-24
+                wb[q] = w * 1048576.0f;                    //          at mantissa bits 4-7 as code 2^-20
                 zs[q] = fmaf(pt, zp, zs[q]);
-                wsum[q] += w;
             }
             const uint32_t x[4] = {pr.c[it].x, pr.c[it].y, pr.c[it].z, pr.c[it].w};
 #pragma unroll
             for (int dw = 0; dw < 4; ++dw) {
-                const uint32_t t[4] = {and_or(x[dw] << 4, mask, magic), and_or(x[dw], mask, magic),
-                                       and_or(x[dw] >> 4, mask, magic), and_or(x[dw] >> 8, mask, magic)};
+                const uint32_t y = x[dw] >> 8;
+                // t[n] holds nibbles n (low half) and n + 4 (high half) as fp16 subnormals
+                const uint32_t t[4] = {x[dw] & mask_a, x[dw] & mask_b, y & mask_a, y & mask_b};
 #pragma unroll
-                for (int n = 0; n < 4; ++n) {               // t[n] holds nibbles n (low half) and n + 4 (high half)
+                for (int n = 0; n < 4; ++n) {
                     const __half2 h = *reinterpret_cast<const __half2 *>(&t[n]);
                     const float lo = __low2float(h), hi = __high2float(h);
 #pragma unroll
                     for (int q = 0; q < RQ; ++q) {
-                        acc[q][8 * dw + n] = fmaf(w16[q], lo, acc[q][8 * dw + n]);
-                        acc[q][8 * dw + n + 4] = fmaf(w16[q], hi, acc[q][8 * dw + n + 4]);
+                        const float wq = (n & 1) ? wb[q] : wa[q];
+                        acc[q][8 * dw + n] = fmaf(wq, lo, acc[q][8 * dw + n]);
+                        acc[q][8 * dw + n + 4] = fmaf(wq, hi, acc[q][8 * dw + n + 4]);
                     }
                 }
             }
@@ -204,10 +204,8 @@ __global__ __launch_bounds__(kThreads, RQ >= 4 ? 2 : 1) void decode_split_kernel
             if constexpr (ROWS == 2) acc[q][i] = half_wave_sum(acc[q][i]);
         }
         zs[q] = row_slot_sum<LPT>(zs[q]);
-        wsum[q] = row_slot_sum<LPT>(wsum[q]);
         if constexpr (ROWS == 2) {
             zs[q] = half_wave_sum(zs[q]);
-            wsum[q] = half_wave_sum(wsum[q]);
         }
         lsum[q] = wave_sum(lsum[q]);
     }
@@ -220,7 +218,6 @@ __global__ __launch_bounds__(kThreads, RQ >= 4 ? 2 : 1) void decode_split_kernel
             for (int i = 0; i < 32; i += 4)
                 *reinterpret_cast<float4 *>(dst + slice * 32 + i) = make_float4(acc[q][i], acc[q][i + 1], acc[q][i + 2], acc[q][i + 3]);
             dst[D + slice] = zs[q];
-            dst[D + LPT + slice] = wsum[q];
         }
     }
     if (lane == 0) {
@@ -241,15 +238,14 @@ __global__ __launch_bounds__(kThreads, RQ >= 4 ? 2 : 1) void decode_split_kernel
 #pragma unroll
         for (int w = 0; w < kWaves; ++w) {
             const float f = exp2f(a.exp2_scale * (float)(hm - m_s[w][q]));      // 0 for a wave that saw no valid token
-            float ow = 0.0f, z = 0.0f, ws = 0.0f;
+            float ow = 0.0f, z = 0.0f;
 #pragma unroll
             for (int rw = 0; rw < ROWS; ++rw) {
                 const float *src = epi + ((size_t)(w * ROWS + rw) * RQ + q) * EPI_STRIDE;
                 ow += src[c];
                 z += src[D + c / 32];
-                ws += src[D + LPT + c / 32];
             }
-            o = fmaf(f, fmaf(-64.0f, ws, ow) + z, o);      // (1024 + 16 code) / 16 = 64 + code
+            o = fmaf(f, ow + z, o);
             l = fmaf(f, l_s[w][q], l);
         }
         a.part_o[(part + (size_t)q * a.n_splits) * D + c] = o;
