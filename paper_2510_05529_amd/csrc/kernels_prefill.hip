@@ -134,6 +134,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs a, Bat
 #pragma unroll
         for (int cb = 0; cb < NCB; ++cb) acc[rb][cb] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
+    const uint32_t mask_a = opaque_vgpr(0x000F000Fu), mask_b = opaque_vgpr(0x00F000F0u);
     HalfOperand ones;
 #pragma unroll
     for (int k = 0; k < 4; ++k) ones.u[k] = 0x3C003C00u;          // fp16 1.0
@@ -219,12 +220,24 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs a, Bat
                     zp[t] = __half2float(__ushort_as_half((unsigned short)(m >> 16)));
                 }
                 const int p2 = operand_pos(2 * tp) * 2;            // tokens 2 tp and 2 tp + 1 stay neighbours
+                // A nibble masked in place at mantissa bits 0-3 / 4-7 of a zero half-word is the fp16 subnormal
+                // code 2^-24 / code 2^-20: the mixed-precision FMA reads it directly, with the scale times 2^24 / 2^20.
+                const float sa[2] = {sc[0] * 16777216.0f, sc[1] * 16777216.0f}, sb[2] = {sc[0] * 1048576.0f, sc[1] * 1048576.0f};
 #pragma unroll
-                for (int c = 0; c < 16; ++c) {
-                    const float c0 = (float)((sr.c[c >> 3] >> (4 * (c & 7))) & 0xFu);
-                    const float c1 = (float)((sr.c[2 + (c >> 3)] >> (4 * (c & 7))) & 0xFu);
-                    const __half2 hv = __halves2half2(__float2half_rn(fmaf(sc[0], c0, zp[0])), __float2half_rn(fmaf(sc[1], c1, zp[1])));
-                    *reinterpret_cast<__half2 *>(vs + (16 * s16 + c) * VS + p2) = hv;
+                for (int k = 0; k < 2; ++k) {                      // channels 8 k .. 8 k + 7 of the slice
+                    const uint32_t x0 = sr.c[k], x1 = sr.c[2 + k], y0 = x0 >> 8, y1 = x1 >> 8;
+                    const uint32_t t0w[4] = {x0 & mask_a, x0 & mask_b, y0 & mask_a, y0 & mask_b};
+                    const uint32_t t1w[4] = {x1 & mask_a, x1 & mask_b, y1 & mask_a, y1 & mask_b};
+#pragma unroll
+                    for (int n = 0; n < 4; ++n) {                  // word n holds nibbles n (low half) and n + 4 (high half)
+                        const __half2 h0 = *reinterpret_cast<const __half2 *>(&t0w[n]), h1 = *reinterpret_cast<const __half2 *>(&t1w[n]);
+                        const float w0 = (n & 1) ? sb[0] : sa[0], w1 = (n & 1) ? sb[1] : sa[1];
+                        const f32x2 lo = {fmaf(w0, __low2float(h0), zp[0]), fmaf(w1, __low2float(h1), zp[1])};
+                        const f32x2 hi = {fmaf(w0, __high2float(h0), zp[0]), fmaf(w1, __high2float(h1), zp[1])};
+                        const h16x2 plo = __builtin_convertvector(lo, h16x2), phi = __builtin_convertvector(hi, h16x2);
+                        *reinterpret_cast<h16x2 *>(vs + (16 * s16 + 8 * k + n) * VS + p2) = plo;
+                        *reinterpret_cast<h16x2 *>(vs + (16 * s16 + 8 * k + n + 4) * VS + p2) = phi;
+                    }
                 }
             }
         } else {
@@ -232,20 +245,30 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs a, Bat
 #pragma unroll
             for (int k = 0; k < kWordsPerThread; ++k) {
                 const int wi = w0 + LPB * k, ch = word_channel(wi);
-                const uint32_t x = sr.c[k];
-                __half hv[8];
+                const uint32_t x = sr.c[k], y = x >> 8;
+                // nibble n of the word is token 2 n of the block, nibble n + 4 token 2 n + 1: word n below holds that
+                // pair as fp16 subnormals (code 2^-24 for even n, code 2^-20 for odd n)
+                const uint32_t tw[4] = {x & mask_a, x & mask_b, y & mask_a, y & mask_b};
+                h16x2 hv[4];
 #pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    // slots past the end of the sequence hold anything: their values must not reach the MFMA as NaN
-                    const uint32_t m = t0 + 8 * blk + j < len ? sr.m[8 * (wi >> 6) + j] : 0u;
-                    const float sc = __half2float(__ushort_as_half((unsigned short)(m & 0xFFFFu)));
-                    const float zp = __half2float(__ushort_as_half((unsigned short)(m >> 16)));
-                    const float code = (float)((x >> (4 * code_nibble_pos(j))) & 0xFu);
-                    hv[j] = __float2half_rn(fmaf(sc, code, zp));
+                for (int n = 0; n < 4; ++n) {
+                    float f[2];
+#pragma unroll
+                    for (int e = 0; e < 2; ++e) {
+                        const int j = 2 * n + e;
+                        // slots past the end of the sequence hold anything: their values must not reach the MFMA as NaN
+                        const uint32_t m = t0 + 8 * blk + j < len ? sr.m[8 * (wi >> 6) + j] : 0u;
+                        const float sc = __half2float(__ushort_as_half((unsigned short)(m & 0xFFFFu)));
+                        const float zp = __half2float(__ushort_as_half((unsigned short)(m >> 16)));
+                        const __half2 h = *reinterpret_cast<const __half2 *>(&tw[n]);
+                        f[e] = fmaf(sc * ((n & 1) ? 1048576.0f : 16777216.0f), e ? __high2float(h) : __low2float(h), zp);
+                    }
+                    const f32x2 pf = {f[0], f[1]};
+                    hv[n] = __builtin_convertvector(pf, h16x2);
                 }
                 // tokens 8 blk .. 8 blk + 3 and 8 blk + 4 .. 8 blk + 7 go to two operand positions
-                *reinterpret_cast<uint2 *>(vs + ch * VS + operand_pos(8 * blk) * 2) = *reinterpret_cast<const uint2 *>(hv);
-                *reinterpret_cast<uint2 *>(vs + ch * VS + operand_pos(8 * blk + 4) * 2) = *reinterpret_cast<const uint2 *>(hv + 4);
+                *reinterpret_cast<uint2 *>(vs + ch * VS + operand_pos(8 * blk) * 2) = *reinterpret_cast<const uint2 *>(&hv[0]);
+                *reinterpret_cast<uint2 *>(vs + ch * VS + operand_pos(8 * blk + 4) * 2) = *reinterpret_cast<const uint2 *>(&hv[2]);
             }
         }
     };
