@@ -177,7 +177,7 @@ int h1bkv_decode_attn_dtau(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t 
  * (H1BKV_ERANGE otherwise).  q_dev [n_seqs][n_q][n_q_heads][d] in in_dtype with strides in elements (channel
  * stride 1, rows 16-byte aligned); out_dev [n_seqs][n_q][n_q_heads][d] fp32, dense.  The weighted sum runs on the
  * matrix cores with fp16 operands (weights and dequantised values rounded to fp16, fp32 accumulation).
- * Supported for 4-bit values and head_dim <= 128 (H1BKV_ESHAPE otherwise).
+ * Supported for head_dim <= 128 (H1BKV_ESHAPE otherwise); with value_bits = 16 the stored fp16 values are used as they are.
  * workspace_dev: >= h1bkv_prefill_workspace_bytes(c, n_seqs, n_q) (the chunk's query sketches), 256-byte aligned.
  */
 size_t h1bkv_prefill_workspace_bytes(const h1bkv_cache *c, int32_t n_seqs, int32_t n_q);

@@ -211,12 +211,15 @@ class Cache:
     def prefill(self, q: np.ndarray, tau: float, ctx_len=None) -> np.ndarray:
         """q [B][n_q][H_q][d]: the last n_q cached positions of every sequence attend causally (each to the tokens up
         to and including its own position) -> out [B][n_q][H_q][d] float32."""
-        assert self.value_bits == 4
         q = _f32(q)
         n_q, Hq = q.shape[1], q.shape[2]
         lens = np.full(self.B, self.len, dtype=np.int32) if ctx_len is None else np.ascontiguousarray(ctx_len, dtype=np.int32)
         assert (lens >= n_q).all()
         out = np.zeros((self.B, n_q, Hq, self.d), dtype=np.float32)
+        if self.value_bits == 16:          # the definition itself: position i is the decode step over its own prefix
+            for i in range(n_q):
+                out[:, i] = self.decode(q[:, i], tau, ctx_len=lens - n_q + i + 1)
+            return out
         lib().h1bkv_oracle_prefill_batch(_p(self.R), C.c_int(self.b), C.c_int(self.d), C.c_int(self.G), C.c_int(self.B),
                                          C.c_int(Hq), C.c_int(self.Hkv), C.c_int64(self.Tcap), _p(lens), C.c_int64(n_q),
                                          _p(q), _p(self.sketches), _p(self.codes), _p(self.scale), _p(self.zero),

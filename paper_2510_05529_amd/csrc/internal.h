@@ -104,8 +104,8 @@ struct PrefillArgs {
     float exp2_scale;         // 2 log2(e) / (b tau)
 };
 
-// The prefill kernel keeps a row block's accumulators (d/16 MFMA tiles) in registers and reads 4-bit codes.
-inline bool prefill_supported(int head_dim, int code_layout) { return head_dim <= 128 && code_layout != 2; }
+// The prefill kernel keeps a row block's accumulators (d/16 MFMA tiles) in registers.
+inline bool prefill_supported(int head_dim, int) { return head_dim <= 128; }
 
 // Query heads one matrix-core decode workgroup serves: the largest divisor of r that is at most 8.
 inline int mfma_heads_per_wg(int r) {

@@ -69,7 +69,8 @@ struct StageRegs {           // one thread's share of a key tile on its way from
     uint32_t skd[NDW];       // 32 sketch bits each
     uint32_t c[4];           // layout 0: 8 bytes of codes for each of two tokens;  layout 1: up to 4 code words of one block
     uint32_t m[16];          // layout 0: {scale, zero} of the two tokens;  layout 1: of the block's 8 tokens, for up to
-                             //           two 64-channel halves of the head (each within one quantisation group per word)
+                             //           two 64-channel halves of the head (each within one quantisation group per word);
+                             // layout 2: 16 fp16 values of each of the two tokens
 };
 
 template <int W, int D, int LAYOUT>
@@ -175,6 +176,17 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs a, Bat
                     sr.m[t] = pv.meta[rec * ng + g];
                 }
             }
+        } else if constexpr (LAYOUT == 2) {              // fp16 values: 16 channels (32 bytes) of each of two tokens
+            if (tid < kItems0) {
+                const int tp = tid % (TK / 2), s16 = tid / (TK / 2);
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+                    const uint4 *src = reinterpret_cast<const uint4 *>(pv.codes + ((rec0 + 2 * tp + t) * D + 16 * s16) * 2);
+                    const uint4 a0 = src[0], a1 = src[1];
+                    sr.m[8 * t + 0] = a0.x; sr.m[8 * t + 1] = a0.y; sr.m[8 * t + 2] = a0.z; sr.m[8 * t + 3] = a0.w;
+                    sr.m[8 * t + 4] = a1.x; sr.m[8 * t + 5] = a1.y; sr.m[8 * t + 6] = a1.z; sr.m[8 * t + 7] = a1.w;
+                }
+            }
         } else {
             const int blk = tid / LPB, w0 = tid % LPB;
             const uint32_t *words = reinterpret_cast<const uint32_t *>(pv.codes + (rec0 + 8 * blk) * (D / 2));
@@ -238,6 +250,18 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs a, Bat
                         *reinterpret_cast<h16x2 *>(vs + (16 * s16 + 8 * k + n) * VS + p2) = plo;
                         *reinterpret_cast<h16x2 *>(vs + (16 * s16 + 8 * k + n + 4) * VS + p2) = phi;
                     }
+                }
+            }
+        } else if constexpr (LAYOUT == 2) {
+            if (tid < kItems0) {
+                const int tp = tid % (TK / 2), s16 = tid / (TK / 2);
+                const int p2 = operand_pos(2 * tp) * 2;
+                // slots past the end of the sequence hold anything: their values must not reach the MFMA as NaN
+                const uint32_t keep0 = t0 + 2 * tp < len ? 0xFFFFu : 0u, keep1 = t0 + 2 * tp + 1 < len ? 0xFFFFu : 0u;
+#pragma unroll
+                for (int c = 0; c < 16; ++c) {
+                    const uint32_t h0 = (sr.m[c >> 1] >> (16 * (c & 1))) & keep0, h1 = (sr.m[8 + (c >> 1)] >> (16 * (c & 1))) & keep1;
+                    *reinterpret_cast<uint32_t *>(vs + (16 * s16 + c) * VS + p2) = h0 | (h1 << 16);
                 }
             }
         } else {
@@ -512,7 +536,8 @@ __global__ __launch_bounds__(kThreads) void sketch_rows_kernel(PrefillArgs a, in
 template <int W, int D>
 hipError_t launch_prefill_layout(const PrefillArgs &a, const BatchDesc &desc, int seq0, dim3 grid, hipStream_t st) {
     if (a.pool.code_layout == 0) hipLaunchKernelGGL((prefill_kernel<W, D, 0>), grid, dim3(kThreads), 0, st, a, desc, seq0);
-    else hipLaunchKernelGGL((prefill_kernel<W, D, 1>), grid, dim3(kThreads), 0, st, a, desc, seq0);
+    else if (a.pool.code_layout == 1) hipLaunchKernelGGL((prefill_kernel<W, D, 1>), grid, dim3(kThreads), 0, st, a, desc, seq0);
+    else hipLaunchKernelGGL((prefill_kernel<W, D, 2>), grid, dim3(kThreads), 0, st, a, desc, seq0);
     return hipGetLastError();
 }
 

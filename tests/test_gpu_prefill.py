@@ -110,3 +110,21 @@ def test_query_sketches_are_bit_exact(dt, scale):
     got = cache.workspace[: n_words * 8].cpu().numpy().view(np.uint64).reshape(2, n_q, w.n_q_heads, b // 64)
     assert np.array_equal(got, cref.sketch(R, q))
     cache.close()
+
+
+def test_prefill_over_fp16_values():
+    """The "1-bit key only" variant (value_bits = 16): same kernel, the value tile is copied instead of dequantised."""
+    d, b, r, T, n_q = 128, 128, 2, 333, 200
+    w = wl.Workload("prefill_f16v", 2, 2 * r, 2, d, T, b, 32, "f16", seed=7)
+    R = wl.projection(b, d)
+    seqs = [0, 1]
+    k, v = wl.kv_slab(w, "k", seqs, 0, T), wl.kv_slab(w, "v", seqs, 0, T)
+    oc = cref.Cache(R, 2, 2, T, 32, value_bits=16)
+    oc.append(k, v)
+    cache = make_cache(w, R, value_bits=16, pool_fill=0x7E)
+    cache.append(seqs, to_dev(k), to_dev(v))
+    q = _queries(w, n_q)
+    out = cache.prefill(seqs, to_dev(q), 0.08).cpu().numpy()
+    assert np.isfinite(out).all()
+    assert rel_err(out, oc.prefill(q, 0.08)) <= TOL
+    cache.close()
