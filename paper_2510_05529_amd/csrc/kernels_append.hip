@@ -110,6 +110,9 @@ __device__ __forceinline__ void append_body(const AppendArgs &a, const BatchDesc
                 (&unsure[0][0])[e] = 0u;
             }
         }
+        // The source offsets need no memory access; the destination needs the block table.  That load is issued here
+        // and consumed after the key tile has been requested, so the two round trips overlap.
+        int my_page = 0, my_head = 0, my_pos = 0;
         if (tid < tile) {
             size_t off = kNoRow;
             if (slot0 + tid < n_slots) {
@@ -117,8 +120,9 @@ __device__ __forceinline__ void append_body(const AppendArgs &a, const BatchDesc
                 // padding slots too: a block's words start at its first slot.  Every block of a head holds at
                 // least one new token, so its page has been assigned.
                 const int pos = sd.pos + t;
-                const int page = pv.block_table[(size_t)sd.seq_id * pv.max_pages_per_seq + pos / kPage];
-                dst[tid] = ((size_t)page * H + head) * kPage + (pos % kPage);
+                my_page = pv.block_table[(size_t)sd.seq_id * pv.max_pages_per_seq + pos / kPage];
+                my_head = head;
+                my_pos = pos;
                 if (t >= 0 && t < n_new) off = (size_t)t * a.stride_tok + (size_t)head * a.stride_head;
             }
             src_off[tid] = off;
@@ -126,10 +130,11 @@ __device__ __forceinline__ void append_body(const AppendArgs &a, const BatchDesc
         __syncthreads();
         auto valid_slot = [&](int rl) { return src_off[rl] != kNoRow; };
 
-        // matrix-core path: the value slice this thread quantises first is requested now, so that its latency runs
-        // behind the key staging and the projection
+        // fp16 values: the slice this thread quantises first is requested now, so that its latency runs behind the key
+        // staging and the projection
+        constexpr bool kPrefetchV = MF || sizeof(T) == 2;     // (fp32 values would take 32 registers next to the R row)
         [[maybe_unused]] uint4 vpre[4];
-        if constexpr (MF) {
+        if constexpr (kPrefetchV) {
             const int rl = tid / (D / 32), slice = tid % (D / 32);
             if (rl < tile && valid_slot(rl)) {
                 const uint4 *src = reinterpret_cast<const uint4 *>(vbase + src_off[rl] + slice * 32);
@@ -143,6 +148,7 @@ __device__ __forceinline__ void append_body(const AppendArgs &a, const BatchDesc
             const int rl = e / D, ch = e % D;
             if (valid_slot(rl)) copy8(kbase + src_off[rl] + ch, &ks[rl][ch]);
         }
+        if (tid < tile) dst[tid] = ((size_t)my_page * H + my_head) * kPage + (my_pos % kPage);
         __syncthreads();
 
         if constexpr (MF) {
@@ -193,7 +199,7 @@ __device__ __forceinline__ void append_body(const AppendArgs &a, const BatchDesc
             const int rl = item / LPT, slice = item % LPT;
             const bool valid = rl < tile && valid_slot(rl);
             float x[32];
-            if (MF && valid && item == tid) {          // requested before the projection
+            if (kPrefetchV && valid && item == tid) {  // requested before the projection
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     const __half2 *h2 = reinterpret_cast<const __half2 *>(&vpre[i]);
