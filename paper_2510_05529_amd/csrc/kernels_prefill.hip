@@ -8,9 +8,10 @@
 //             (v_mfma_i32_16x16x64_i8) per 64 sketch bits yields 16 x 16 distances -- instead of 4 W XOR/popcount
 //             instructions per pair on the vector ALUs.  The MFMA is issued as keys x queries, so that a lane ends
 //             up holding distances of ONE query row against several tokens: the slot it has in the next MFMA.
-//   weights   p = exp((alpha - alpha_max)/tau) per pair on the vector ALUs (running maximum per row with a lazy
-//             rescale: scores take only b+1 values, the maximum moves rarely), packed to fp16 in registers as the
-//             A operand of the second MFMA.  They carry a factor 2^14 to keep small ones out of the fp16 subnormal
+//   weights   p = exp((alpha - alpha_max)/tau) takes only b+1 values (the distance above the row's minimum is an
+//             integer): one LDS table read per pair instead of an exponential.  Running maximum per row with a lazy
+//             rescale (the maximum moves rarely); weights packed to fp16 in registers as the A operand of the second
+//             MFMA.  They carry a factor 2^14 to keep small ones out of the fp16 subnormal
 //             range; it cancels in the normalisation, which uses the row sums of the SAME fp16 weights (one more MFMA
 //             against an all-ones B).
 //   values    sum_t p[i][t] v^[t][c]  with v_mfma_f32_16x16x32_f16, fp32 accumulate.
@@ -84,6 +85,9 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs a, Bat
     constexpr int NDW = DWT > kThreads ? DWT / kThreads : 1;
     __shared__ __attribute__((aligned(16))) unsigned char v_s[2][D * VS];
     __shared__ __attribute__((aligned(16))) unsigned char k_s[2][TK * KS];
+    // p(e) = 2^14 exp(-2 e / (b tau)) for every distance e above a row's minimum; entry b + 1 is 0.  One LDS read
+    // per pair replaces convert + multiply-add + exponential (a quarter-rate instruction).
+    __shared__ float ptab[64 * W + 2];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int i = lane & 15, kb = lane >> 4;
@@ -135,6 +139,8 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs a, Bat
 #pragma unroll
         for (int cb = 0; cb < NCB; ++cb) acc[rb][cb] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
+    for (int e = threadIdx.x; e < 64 * W + 2; e += kThreads)
+        ptab[e] = e <= 64 * W ? __builtin_amdgcn_exp2f(fmaf(-a.exp2_scale, (float)e, kPScaleLog2)) : 0.0f;
     const uint32_t mask_a = opaque_vgpr(0x000F000Fu), mask_b = opaque_vgpr(0x00F000F0u);
     HalfOperand ones;
 #pragma unroll
@@ -352,18 +358,19 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs a, Bat
                         for (int j = 0; j < 4; ++j) acc[rb][cb][j] *= fr[j];
                 }
             }
+            // Weights from the table: p depends only on e = ham - ham_min, an integer in [0, b]; masked pairs
+            // (ham = 2^20) are clamped to the table's zero entry.
             HalfOperand A[kRB];
 #pragma unroll
             for (int rb = 0; rb < kRB; ++rb) {
-                const float base = fmaf(a.exp2_scale, (float)run_min[rb], kPScaleLog2);
 #pragma unroll
                 for (int j = 0; j < 8; j += 2) {
-                    float p0 = __builtin_amdgcn_exp2f(fmaf(-a.exp2_scale, (float)ham[rb][j], base));
-                    float p1 = __builtin_amdgcn_exp2f(fmaf(-a.exp2_scale, (float)ham[rb][j + 1], base));
+                    int e0 = ham[rb][j] - run_min[rb], e1 = ham[rb][j + 1] - run_min[rb];
                     if (kMasked) {
-                        p0 = ham[rb][j] >= (1 << 20) ? 0.0f : p0;
-                        p1 = ham[rb][j + 1] >= (1 << 20) ? 0.0f : p1;
+                        e0 = min(e0, 64 * W + 1);
+                        e1 = min(e1, 64 * W + 1);
                     }
+                    const float p0 = ptab[e0], p1 = ptab[e1];
                     // round to nearest (one packed convert on gfx950), not the truncating pack: half the weight error
                     const f32x2 pf = {p0, p1};
                     const h16x2 pk = __builtin_convertvector(pf, h16x2);
