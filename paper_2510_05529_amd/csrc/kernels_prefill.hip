@@ -91,9 +91,11 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs a, Bat
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int i = lane & 15, kb = lane >> 4;
-    const SeqDesc sd = desc.s[blockIdx.z];
+    // grid (query head, sequence, query block): workgroups are dispatched x-fastest, so the longest-running (latest)
+    // query blocks of ALL heads and sequences start first and the short ones fill the tail of the launch
+    const SeqDesc sd = desc.s[blockIdx.y];
     const int len = sd.pos, n_q = a.n_q;
-    const int qb = (int)gridDim.x - 1 - (int)blockIdx.x;          // the longest-running (latest) query blocks start first
+    const int qb = (int)gridDim.z - 1 - (int)blockIdx.z;
     const int row0 = qb * kQB;
     const int q0 = len - n_q;                                      // absolute position of query 0
     const int last_row = min(row0 + kQB, n_q) - 1;
@@ -101,8 +103,8 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs a, Bat
 
     const PoolView &pv = a.pool;
     const int H = pv.n_kv_heads, Hq = pv.n_q_heads, r = Hq / H;
-    const int h = blockIdx.y, kvh = h / r;
-    const int seq_g = seq0 + blockIdx.z;
+    const int h = blockIdx.x, kvh = h / r;
+    const int seq_g = seq0 + blockIdx.y;
     const int ng = D / pv.group_size;
     const int32_t *bt = pv.block_table + (size_t)sd.seq_id * pv.max_pages_per_seq;
 
@@ -560,7 +562,7 @@ hipError_t launch_prefill_d(const PrefillArgs &a, const BatchDesc &desc, int seq
 }  // namespace
 
 hipError_t launch_prefill(const PrefillArgs &a, const BatchDesc &desc, int seq0, int n_seqs, hipStream_t st) {
-    const dim3 grid((unsigned)((a.n_q + kQB - 1) / kQB), (unsigned)a.pool.n_q_heads, (unsigned)n_seqs);
+    const dim3 grid((unsigned)a.pool.n_q_heads, (unsigned)n_seqs, (unsigned)((a.n_q + kQB - 1) / kQB));
     switch (a.pool.sketch_bits) {
         case 64: return launch_prefill_d<1>(a, desc, seq0, grid, st);
         case 128: return launch_prefill_d<2>(a, desc, seq0, grid, st);
