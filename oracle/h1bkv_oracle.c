@@ -32,7 +32,10 @@
  * <= scale/2, closed forms of Eq.(5) (T=1, equal sketches, tau -> inf, two-level), exact rational
  * arithmetic on tiny cases, and numpy's float16 for the half conversions.  The fp16-value variant at the end
  * of the file is pinned by tests/test_oracle_f16v.py (numpy float16 storage, closed forms, agreement with the
- * 4-bit functions on values both formats hold exactly, the explicit +-1 rendering).
+ * 4-bit functions on values both formats hold exactly, the explicit +-1 rendering); prefill attention by
+ * tests/test_oracle_prefill.py (per-prefix decode steps, causality, the explicit causal +-1 rendering); the
+ * temperature derivative by tests/test_oracle_dtau.py (central differences of the float64 rendering, a two-level
+ * closed form, the large-tau covariance limit, cases where it must vanish).
  */
 #include <math.h>
 #include <stdint.h>
