@@ -40,8 +40,14 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef int i32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kRB = 2;                        // 16-row blocks per wave
-constexpr int kQB = kWaves * 16 * kRB;        // query positions per workgroup
+// Eight waves of one 16-row block each: the same 128 query rows and the same LDS tiles per workgroup as four waves of
+// two blocks, at half the registers per wave, so that four waves share a SIMD and one's matrix-core phase overlaps the
+// others' vector phases.
+constexpr int kPfWaves = 8;
+constexpr int kPfThreads = kPfWaves * 64;
+constexpr int kRB = 1;                        // 16-row blocks per wave
+constexpr int kQB = kPfWaves * 16 * kRB;      // query positions per workgroup
+constexpr int kCS = 8;                        // channels per staging item of the token-major layouts
 constexpr float kPScaleLog2 = 14.0f;          // weights are stored as p * 2^14
 
 union HalfOperand {
@@ -68,22 +74,21 @@ __device__ __forceinline__ uint32_t spread4(uint32_t x) {
 
 template <int NDW>
 struct StageRegs {           // one thread's share of a key tile on its way from global memory to LDS
-    uint32_t skd[NDW];       // 32 sketch bits each
-    uint32_t c[4];           // layout 0: 8 bytes of codes for each of two tokens;  layout 1: up to 4 code words of one block
-    uint32_t m[16];          // layout 0: {scale, zero} of the two tokens;  layout 1: of the block's 8 tokens, for up to
-                             //           two 64-channel halves of the head (each within one quantisation group per word);
-                             // layout 2: 16 fp16 values of each of the two tokens
+    uint32_t skd[NDW];       // 16 sketch bits each
+    uint32_t c[2];           // layout 0: kCS / 2 bytes of codes for each of two tokens;  layout 1: up to 2 code words of one block
+    uint32_t m[16];          // layout 0: {scale, zero} of the two tokens;  layout 1: of the block's 8 tokens, for each
+                             //           of the thread's words;  layout 2: kCS fp16 values of each of the two tokens
 };
 
 template <int W, int D, int LAYOUT>
-__global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs a, BatchDesc desc, int seq0) {
+__global__ __launch_bounds__(kPfThreads, W >= 8 ? 2 : 4) void prefill_kernel(PrefillArgs a, BatchDesc desc, int seq0) {
     constexpr int NCB = D / 16;
     constexpr int TK = W <= 2 ? 64 : 32;          // key tokens per tile (wide sketches: smaller tiles, same LDS budget)
     constexpr int NSTEP = TK / 32;                // 32-token MFMA steps per tile
     constexpr int VS = TK * 2 + 16;               // bytes per channel row of the value tile (16 B pad: conflict-free b128 reads)
     constexpr int KS = 64 * W + 16;               // bytes per token row of the key-bit tile (same padding)
-    constexpr int DWT = TK * 2 * W;               // 32-bit sketch words per tile
-    constexpr int NDW = DWT > kThreads ? DWT / kThreads : 1;
+    constexpr int DWT = TK * 4 * W;               // 16-bit sketch units per tile
+    constexpr int NDW = DWT > kPfThreads ? DWT / kPfThreads : 1;
     __shared__ __attribute__((aligned(16))) unsigned char v_s[2][D * VS];
     __shared__ __attribute__((aligned(16))) unsigned char k_s[2][TK * KS];
     // p(e) = 2^14 exp(-2 e / (b tau)) for every distance e above a row's minimum; entry b + 1 is 0.  One LDS read
@@ -142,7 +147,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs a, Bat
 #pragma unroll
         for (int cb = 0; cb < NCB; ++cb) acc[rb][cb] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
-    for (int e = threadIdx.x; e < 64 * W + 2; e += kThreads)
+    for (int e = threadIdx.x; e < 64 * W + 2; e += kPfThreads)
         ptab[e] = e <= 64 * W ? __builtin_amdgcn_exp2f(fmaf(-a.exp2_scale, (float)e, kPScaleLog2)) : 0.0f;
     const uint32_t mask_a = opaque_vgpr(0x000F000Fu), mask_b = opaque_vgpr(0x00F000F0u);
     HalfOperand ones;
@@ -155,12 +160,14 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs a, Bat
     auto operand_pos = [](int t) { return (t & ~31) + 8 * ((t & 15) >> 2) + 4 * ((t >> 4) & 1) + (t & 3); };
 
     // ---- staging: global -> registers (issued early) -> LDS (after the current tile has been consumed) ----
-    constexpr int kItems0 = (TK / 2) * (D / 16);                  // layout 0: (token pair, 16-channel slice) items per tile
+    constexpr int kItems0 = (TK / 2) * (D / kCS);                 // layouts 0, 2: (token pair, channel slice) items per tile
+    static_assert(kCS == 8 && kItems0 <= kPfThreads, "one staging item per thread");
     // layout 1: a thread takes one of the tile's TK / 8 blocks and words (tid % LPB) + LPB k of its D words (word wi
     // holds channel 16 cb + n with cb = (wi / 64) * 4 + wi % 4, n = (wi % 64) / 4: the inverse of code_word_index).
-    // Words below 64 lie in the head's first 64 channels, the others in the second: at most two {scale, zero} sets.
-    constexpr int LPB = kThreads / (TK / 8);
-    constexpr int kWordsPerThread = D / LPB;
+    // A word holds eight tokens of ONE channel: its {scale, zero} sets are those of that channel's quantisation group.
+    constexpr int LPB = kPfThreads / (TK / 8);
+    constexpr int kWordsPerThread = D > LPB ? D / LPB : 1;
+    static_assert(kWordsPerThread <= 2, "StageRegs holds two words and their sets");
     auto word_channel = [](int wi) { return 16 * ((wi >> 6) * 4 + (wi & 3)) + ((wi & 63) >> 2); };
     auto tile_rec0 = [&](int kt) {
         const int t0 = kt * TK;
@@ -168,70 +175,66 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs a, Bat
     };
     auto load_tile = [&](StageRegs<NDW> &sr, int kt) {
         const size_t rec0 = tile_rec0(kt);
-        const uint32_t *skw = reinterpret_cast<const uint32_t *>(pv.sketch + rec0 * W);
+        const uint16_t *skw = reinterpret_cast<const uint16_t *>(pv.sketch + rec0 * W);
 #pragma unroll
         for (int u = 0; u < NDW; ++u)
-            if (tid + u * kThreads < DWT) sr.skd[u] = skw[tid + u * kThreads];
+            if (tid + u * kPfThreads < DWT) sr.skd[u] = skw[tid + u * kPfThreads];
         if constexpr (LAYOUT == 0) {
             if (tid < kItems0) {
-                const int tp = tid % (TK / 2), s16 = tid / (TK / 2);        // token pair fastest: see the LDS writes below
-                const int g = (16 * s16) / pv.group_size;
+                const int tp = tid % (TK / 2), sl = tid / (TK / 2);         // token pair fastest: see the LDS writes below
+                const int g = (kCS * sl) / pv.group_size;
 #pragma unroll
                 for (int t = 0; t < 2; ++t) {
                     const size_t rec = rec0 + 2 * tp + t;
-                    const uint2 c = *reinterpret_cast<const uint2 *>(pv.codes + rec * (D / 2) + s16 * 8);
-                    sr.c[2 * t] = c.x;
-                    sr.c[2 * t + 1] = c.y;
+                    sr.c[t] = *reinterpret_cast<const uint32_t *>(pv.codes + rec * (D / 2) + sl * 4);
                     sr.m[t] = pv.meta[rec * ng + g];
                 }
             }
-        } else if constexpr (LAYOUT == 2) {              // fp16 values: 16 channels (32 bytes) of each of two tokens
+        } else if constexpr (LAYOUT == 2) {              // fp16 values: 8 channels (16 bytes) of each of two tokens
             if (tid < kItems0) {
-                const int tp = tid % (TK / 2), s16 = tid / (TK / 2);
+                const int tp = tid % (TK / 2), sl = tid / (TK / 2);
 #pragma unroll
                 for (int t = 0; t < 2; ++t) {
-                    const uint4 *src = reinterpret_cast<const uint4 *>(pv.codes + ((rec0 + 2 * tp + t) * D + 16 * s16) * 2);
-                    const uint4 a0 = src[0], a1 = src[1];
-                    sr.m[8 * t + 0] = a0.x; sr.m[8 * t + 1] = a0.y; sr.m[8 * t + 2] = a0.z; sr.m[8 * t + 3] = a0.w;
-                    sr.m[8 * t + 4] = a1.x; sr.m[8 * t + 5] = a1.y; sr.m[8 * t + 6] = a1.z; sr.m[8 * t + 7] = a1.w;
+                    const uint4 a0 = *reinterpret_cast<const uint4 *>(pv.codes + ((rec0 + 2 * tp + t) * D + kCS * sl) * 2);
+                    sr.m[4 * t + 0] = a0.x; sr.m[4 * t + 1] = a0.y; sr.m[4 * t + 2] = a0.z; sr.m[4 * t + 3] = a0.w;
                 }
             }
         } else {
             const int blk = tid / LPB, w0 = tid % LPB;
             const uint32_t *words = reinterpret_cast<const uint32_t *>(pv.codes + (rec0 + 8 * blk) * (D / 2));
 #pragma unroll
-            for (int k = 0; k < kWordsPerThread; ++k) sr.c[k] = words[w0 + LPB * k];
+            for (int k = 0; k < kWordsPerThread; ++k) {
+                const int wi = w0 + LPB * k;
+                if (wi < D) {
+                    sr.c[k] = words[wi];
+                    const int g = word_channel(wi) / pv.group_size;
 #pragma unroll
-            for (int ms = 0; ms < D / 64; ++ms) {
-                const int g = word_channel((w0 & 63) + 64 * ms) / pv.group_size;
-#pragma unroll
-                for (int j = 0; j < 8; ++j) sr.m[8 * ms + j] = pv.meta[(rec0 + 8 * blk + j) * ng + g];
+                    for (int j = 0; j < 8; ++j) sr.m[8 * k + j] = pv.meta[(rec0 + 8 * blk + j) * ng + g];
+                }
             }
         }
     };
     auto store_tile = [&](const StageRegs<NDW> &sr, int kt, int buf) {
         const int t0 = kt * TK;
-        // key bits -> {0,1} bytes: 32 bits in, 32 bytes out
+        // key bits -> {0,1} bytes: 16 bits in, 16 bytes out
         unsigned char *ks = k_s[buf];
 #pragma unroll
         for (int u = 0; u < NDW; ++u) {
-            const int dwi = tid + u * kThreads;
+            const int dwi = tid + u * kPfThreads;
             if (dwi < DWT) {
-                const int tok = dwi / (2 * W), part = dwi % (2 * W);
-                uint32_t o[8];
+                const int tok = dwi / (4 * W), part = dwi % (4 * W);
+                uint32_t o[4];
 #pragma unroll
-                for (int k = 0; k < 8; ++k) o[k] = spread4(sr.skd[u] >> (4 * k));
-                uint4 *dst = reinterpret_cast<uint4 *>(ks + tok * KS + part * 32);
-                dst[0] = make_uint4(o[0], o[1], o[2], o[3]);
-                dst[1] = make_uint4(o[4], o[5], o[6], o[7]);
+                for (int k = 0; k < 4; ++k) o[k] = spread4(sr.skd[u] >> (4 * k));
+                *reinterpret_cast<uint4 *>(ks + tok * KS + part * 16) = make_uint4(o[0], o[1], o[2], o[3]);
             }
         }
         unsigned char *vs = v_s[buf];
         if constexpr (LAYOUT == 0) {
             if (tid < kItems0) {
-                // lanes of a half-wave hold different token pairs of one 16-channel slice: their 4-byte writes into a
+                // lanes of a half-wave hold different token pairs of one channel slice: their 4-byte writes into a
                 // channel row fall into different LDS banks
-                const int tp = tid % (TK / 2), s16 = tid / (TK / 2);
+                const int tp = tid % (TK / 2), sl = tid / (TK / 2);
                 float sc[2], zp[2];
 #pragma unroll
                 for (int t = 0; t < 2; ++t) {
@@ -244,9 +247,8 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs a, Bat
                 // A nibble masked in place at mantissa bits 0-3 / 4-7 of a zero half-word is the fp16 subnormal
                 // code 2^-24 / code 2^-20: the mixed-precision FMA reads it directly, with the scale times 2^24 / 2^20.
                 const float sa[2] = {sc[0] * 16777216.0f, sc[1] * 16777216.0f}, sb[2] = {sc[0] * 1048576.0f, sc[1] * 1048576.0f};
-#pragma unroll
-                for (int k = 0; k < 2; ++k) {                      // channels 8 k .. 8 k + 7 of the slice
-                    const uint32_t x0 = sr.c[k], x1 = sr.c[2 + k], y0 = x0 >> 8, y1 = x1 >> 8;
+                {
+                    const uint32_t x0 = sr.c[0], x1 = sr.c[1], y0 = x0 >> 8, y1 = x1 >> 8;
                     const uint32_t t0w[4] = {x0 & mask_a, x0 & mask_b, y0 & mask_a, y0 & mask_b};
                     const uint32_t t1w[4] = {x1 & mask_a, x1 & mask_b, y1 & mask_a, y1 & mask_b};
 #pragma unroll
@@ -256,21 +258,21 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs a, Bat
                         const f32x2 lo = {fmaf(w0, __low2float(h0), zp[0]), fmaf(w1, __low2float(h1), zp[1])};
                         const f32x2 hi = {fmaf(w0, __high2float(h0), zp[0]), fmaf(w1, __high2float(h1), zp[1])};
                         const h16x2 plo = __builtin_convertvector(lo, h16x2), phi = __builtin_convertvector(hi, h16x2);
-                        *reinterpret_cast<h16x2 *>(vs + (16 * s16 + 8 * k + n) * VS + p2) = plo;
-                        *reinterpret_cast<h16x2 *>(vs + (16 * s16 + 8 * k + n + 4) * VS + p2) = phi;
+                        *reinterpret_cast<h16x2 *>(vs + (kCS * sl + n) * VS + p2) = plo;
+                        *reinterpret_cast<h16x2 *>(vs + (kCS * sl + n + 4) * VS + p2) = phi;
                     }
                 }
             }
         } else if constexpr (LAYOUT == 2) {
             if (tid < kItems0) {
-                const int tp = tid % (TK / 2), s16 = tid / (TK / 2);
+                const int tp = tid % (TK / 2), sl = tid / (TK / 2);
                 const int p2 = operand_pos(2 * tp) * 2;
                 // slots past the end of the sequence hold anything: their values must not reach the MFMA as NaN
                 const uint32_t keep0 = t0 + 2 * tp < len ? 0xFFFFu : 0u, keep1 = t0 + 2 * tp + 1 < len ? 0xFFFFu : 0u;
 #pragma unroll
-                for (int c = 0; c < 16; ++c) {
-                    const uint32_t h0 = (sr.m[c >> 1] >> (16 * (c & 1))) & keep0, h1 = (sr.m[8 + (c >> 1)] >> (16 * (c & 1))) & keep1;
-                    *reinterpret_cast<uint32_t *>(vs + (16 * s16 + c) * VS + p2) = h0 | (h1 << 16);
+                for (int c = 0; c < kCS; ++c) {
+                    const uint32_t h0 = (sr.m[c >> 1] >> (16 * (c & 1))) & keep0, h1 = (sr.m[4 + (c >> 1)] >> (16 * (c & 1))) & keep1;
+                    *reinterpret_cast<uint32_t *>(vs + (kCS * sl + c) * VS + p2) = h0 | (h1 << 16);
                 }
             }
         } else {
@@ -278,6 +280,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs a, Bat
 #pragma unroll
             for (int k = 0; k < kWordsPerThread; ++k) {
                 const int wi = w0 + LPB * k, ch = word_channel(wi);
+                if (wi >= D) continue;
                 const uint32_t x = sr.c[k], y = x >> 8;
                 // nibble n of the word is token 2 n of the block, nibble n + 4 token 2 n + 1: word n below holds that
                 // pair as fp16 subnormals (code 2^-24 for even n, code 2^-20 for odd n)
@@ -290,7 +293,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs a, Bat
                     for (int e = 0; e < 2; ++e) {
                         const int j = 2 * n + e;
                         // slots past the end of the sequence hold anything: their values must not reach the MFMA as NaN
-                        const uint32_t m = t0 + 8 * blk + j < len ? sr.m[8 * (wi >> 6) + j] : 0u;
+                        const uint32_t m = t0 + 8 * blk + j < len ? sr.m[8 * k + j] : 0u;
                         const float sc = __half2float(__ushort_as_half((unsigned short)(m & 0xFFFFu)));
                         const float zp = __half2float(__ushort_as_half((unsigned short)(m >> 16)));
                         const __half2 h = *reinterpret_cast<const __half2 *>(&tw[n]);
@@ -311,7 +314,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs a, Bat
         constexpr bool kMasked = decltype(masked_tag)::value;
         const unsigned char *ks = k_s[buf];
         const unsigned char *vs = v_s[buf];
-#pragma unroll
+#pragma unroll 1
         for (int st = 0; st < NSTEP; ++st) {
             // Hamming distances: lane (row i, kb) receives tokens 16 tb + 4 kb + j of the step, tb = 0, 1
             i32x4 dot[kRB][2];
@@ -545,9 +548,9 @@ __global__ __launch_bounds__(kThreads) void sketch_rows_kernel(PrefillArgs a, in
 
 template <int W, int D>
 hipError_t launch_prefill_layout(const PrefillArgs &a, const BatchDesc &desc, int seq0, dim3 grid, hipStream_t st) {
-    if (a.pool.code_layout == 0) hipLaunchKernelGGL((prefill_kernel<W, D, 0>), grid, dim3(kThreads), 0, st, a, desc, seq0);
-    else if (a.pool.code_layout == 1) hipLaunchKernelGGL((prefill_kernel<W, D, 1>), grid, dim3(kThreads), 0, st, a, desc, seq0);
-    else hipLaunchKernelGGL((prefill_kernel<W, D, 2>), grid, dim3(kThreads), 0, st, a, desc, seq0);
+    if (a.pool.code_layout == 0) hipLaunchKernelGGL((prefill_kernel<W, D, 0>), grid, dim3(kPfThreads), 0, st, a, desc, seq0);
+    else if (a.pool.code_layout == 1) hipLaunchKernelGGL((prefill_kernel<W, D, 1>), grid, dim3(kPfThreads), 0, st, a, desc, seq0);
+    else hipLaunchKernelGGL((prefill_kernel<W, D, 2>), grid, dim3(kPfThreads), 0, st, a, desc, seq0);
     return hipGetLastError();
 }
 
