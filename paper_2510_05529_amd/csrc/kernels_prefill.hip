@@ -114,8 +114,10 @@ __global__ __launch_bounds__(kPfThreads, W >= 8 ? 2 : 4) void prefill_kernel(Pre
     const int ng = D / pv.group_size;
     const int32_t *bt = pv.block_table + (size_t)sd.seq_id * pv.max_pages_per_seq;
 
-    // ---- this lane's query rows: position, popcount, and bits 16 kb .. 16 kb + 15 of every 64-bit word as +-1 bytes ----
-    int pos[kRB], pcq[kRB];       // pos: absolute position of row (rb, i); -1 for rows past the chunk
+    // ---- this lane's query rows: position, popcount, and bits 16 kb .. 16 kb + 15 of every 64-bit word as +-4 bytes ----
+    // (+-4, not +-1: the score MFMA then returns 4 (popcount(q) - ham), and 4 (ham - ham_min) is the byte offset of the
+    // pair's weight in the table, with no shift and no separate distance)
+    int pos[kRB], pcq[kRB];       // pos: absolute position of row (rb, i), -1 for rows past the chunk;  pcq: 4 popcount(q)
     ByteOperand qpm[kRB][W];
 #pragma unroll
     for (int rb = 0; rb < kRB; ++rb) {
@@ -125,12 +127,12 @@ __global__ __launch_bounds__(kPfThreads, W >= 8 ? 2 : 4) void prefill_kernel(Pre
 #pragma unroll
         for (int w = 0; w < W; ++w) {
             const uint64_t sq = qi < n_q ? a.q_sketch[(((size_t)seq_g * n_q + qi) * Hq + h) * W + w] : 0;
-            pcq[rb] += __popcll(sq);
+            pcq[rb] += 4 * __popcll(sq);
             const uint32_t bits = (uint32_t)(sq >> (16 * kb)) & 0xFFFFu;
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 const uint32_t t = spread4(bits >> (4 * k));
-                qpm[rb][w].u[k] = t | ((t ^ 0x01010101u) * 0xFFu);     // bit 1 -> 0x01 (+1), bit 0 -> 0xFF (-1)
+                qpm[rb][w].u[k] = (t << 2) | ((t ^ 0x01010101u) * 0xFCu);     // bit 1 -> 0x04 (+4), bit 0 -> 0xFC (-4)
             }
         }
     }
@@ -139,10 +141,10 @@ __global__ __launch_bounds__(kPfThreads, W >= 8 ? 2 : 4) void prefill_kernel(Pre
     const int wave_max_pos = wave_row0 < n_q ? q0 + min(wave_row0 + 16 * kRB, n_q) - 1 : -1;   // ... and of its last valid row
 
     f32x4 acc[kRB][NCB], accsum[kRB];
-    int run_min[kRB];
+    int run_min[kRB];             // 4 x the smallest distance seen so far
 #pragma unroll
     for (int rb = 0; rb < kRB; ++rb) {
-        run_min[rb] = 1 << 20;
+        run_min[rb] = 1 << 22;
         accsum[rb] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int cb = 0; cb < NCB; ++cb) acc[rb][cb] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -331,26 +333,26 @@ __global__ __launch_bounds__(kPfThreads, W >= 8 ? 2 : 4) void prefill_kernel(Pre
                 }
             }
             const int tg = kt * TK + 32 * st + 4 * kb;            // absolute position of this lane's first token (tb = 0, j = 0)
-            int ham[kRB][8], tmin[kRB];
+            int dq[kRB][8], tmin[kRB];
             bool changed = false;
 #pragma unroll
             for (int rb = 0; rb < kRB; ++rb) {
-                tmin[rb] = 1 << 20;
+                int dmax = -(1 << 22);
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
-                    int hd = pcq[rb] - dot[rb][j >> 2][j & 3];   // sum_k q_k key_k = popcount(q) - ham
-                    if (kMasked && tg + 16 * (j >> 2) + (j & 3) > pos[rb]) hd = 1 << 20;      // causal mask (also: rows past the chunk)
-                    ham[rb][j] = hd;
-                    tmin[rb] = min(tmin[rb], hd);
+                    int d = dot[rb][j >> 2][j & 3];              // sum_k q_k key_k = 4 (popcount(q) - ham)
+                    if (kMasked && tg + 16 * (j >> 2) + (j & 3) > pos[rb]) d = -(1 << 22);    // causal mask (also: rows past the chunk)
+                    dq[rb][j] = d;
+                    dmax = max(dmax, d);
                 }
-                tmin[rb] = xor32_min(xor16_min(tmin[rb]));        // over the row's four lane groups
+                tmin[rb] = xor32_min(xor16_min(pcq[rb] - dmax));  // 4 x the smallest distance of the step, over the row's four lane groups
                 changed |= tmin[rb] < run_min[rb];
             }
             if (__any(changed)) {                                 // rare: the running maximum of some row moved
 #pragma unroll
                 for (int rb = 0; rb < kRB; ++rb) {
                     const int nm = min(run_min[rb], tmin[rb]);
-                    const float f = exp2f(a.exp2_scale * (float)(nm - run_min[rb]));   // 0 while nothing was accumulated
+                    const float f = exp2f(0.25f * a.exp2_scale * (float)(nm - run_min[rb]));   // 0 while nothing was accumulated
                     run_min[rb] = nm;
                     // accumulator element j of this lane belongs to row 4 kb + j, whose factor lane 4 kb + j holds
                     float fr[4];
@@ -365,18 +367,20 @@ __global__ __launch_bounds__(kPfThreads, W >= 8 ? 2 : 4) void prefill_kernel(Pre
                 }
             }
             // Weights from the table: p depends only on e = ham - ham_min, an integer in [0, b]; masked pairs
-            // (ham = 2^20) are clamped to the table's zero entry.
+            // are clamped to the table's zero entry.  4 e = 4 (popcount(q) - ham_min) - score is the entry's byte offset.
             HalfOperand A[kRB];
 #pragma unroll
             for (int rb = 0; rb < kRB; ++rb) {
 #pragma unroll
                 for (int j = 0; j < 8; j += 2) {
-                    int e0 = ham[rb][j] - run_min[rb], e1 = ham[rb][j + 1] - run_min[rb];
+                    const int base = pcq[rb] - run_min[rb];
+                    int e0 = base - dq[rb][j], e1 = base - dq[rb][j + 1];
                     if (kMasked) {
-                        e0 = min(e0, 64 * W + 1);
-                        e1 = min(e1, 64 * W + 1);
+                        e0 = min(e0, 4 * (64 * W + 1));
+                        e1 = min(e1, 4 * (64 * W + 1));
                     }
-                    const float p0 = ptab[e0], p1 = ptab[e1];
+                    const unsigned char *tab = reinterpret_cast<const unsigned char *>(ptab);
+                    const float p0 = *reinterpret_cast<const float *>(tab + e0), p1 = *reinterpret_cast<const float *>(tab + e1);
                     // round to nearest (one packed convert on gfx950), not the truncating pack: half the weight error
                     const f32x2 pf = {p0, p1};
                     const h16x2 pk = __builtin_convertvector(pf, h16x2);
