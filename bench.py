@@ -163,15 +163,20 @@ def bench_append(args, torch, B, wl, w, workers):
         "records_per_s": records / (ms_per_step * 1e-3)}))
 
 
-VALU_LANE_OPS_PER_S = 256 * 4 * 16 * 2.4e9    # compute units x SIMDs x lanes x clock: plain (non-packed) vector instructions
+# compute units x SIMDs x lanes per clock x clock = 78.6 T lane-operations/s: the fp32 vector peak of 157.3 TFLOP/s counted
+# as multiply-adds.  Plain v_fma_f32 / v_and_b32 / v_add_u32 chains were measured at one wave64 instruction per 2.5 clocks
+# per SIMD (32 lanes per clock nominal); v_fma_mix_f32, v_cvt_pk_f16_f32, v_min_i32, v_bcnt_u32_b32 and v_mul_u32_u24 issue
+# at half that rate and v_exp_f32 at a quarter, so a kernel that leans on those cannot reach this figure.
+VALU_LANE_OPS_PER_S = 256 * 4 * 32 * 2.4e9
 
 
 def bench_prefill(args, torch, B, wl, w, workers):
     """Secondary line: a whole prompt -- append all tokens of every sequence, then causal attention of every position
-    over the compressed cache (h1bkv_prefill_attn).  The attention kernel is bound by the vector ALUs: per visible
-    (query, key) pair it needs the sketch words' XOR and popcount (4 W instructions), a convert, a multiply-add and an
-    exponential (quarter rate: 4 issue slots) and half a pack -- 4 W + 7 lane-operations, counted here as the
-    algorithmic work against the chip's plain vector issue rate."""
+    over the compressed cache (h1bkv_prefill_attn).  The attention kernel is bound by instruction issue (vector ALU
+    and matrix-core instructions share the issue port and overlap little): per visible (query, key) pair the method
+    needs the sketch words' XOR and popcount (4 W instructions), a convert, a multiply-add, an exponential (quarter
+    rate: 4 issue slots) and half a pack -- 4 W + 7 lane-operations, counted here as the algorithmic work against the
+    chip's fp32 vector peak."""
     n_new, Bsz = w.context, w.batch
     R = wl.projection(w.sketch_bits, w.head_dim)
     pages_per_seq = (n_new + 255) // 256 + 1

@@ -94,6 +94,10 @@ __global__ __launch_bounds__(kPfThreads, W >= 8 ? 2 : 4) void prefill_kernel(Pre
     // p(e) = 2^14 exp(-2 e / (b tau)) for every distance e above a row's minimum; entry b + 1 is 0.  One LDS read
     // per pair replaces convert + multiply-add + exponential (a quarter-rate instruction).
     __shared__ float ptab[64 * W + 2];
+    // The sequence's page ids, read once: a block-table lookup per tile from global memory sat, with its full memory
+    // latency, in front of every tile's loads (a quarter of the kernel's time when it was measured).
+    constexpr int kPagesLds = 1024;
+    __shared__ int pages_s[kPagesLds];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int i = lane & 15, kb = lane >> 4;
@@ -171,9 +175,15 @@ __global__ __launch_bounds__(kPfThreads, W >= 8 ? 2 : 4) void prefill_kernel(Pre
     constexpr int kWordsPerThread = D > LPB ? D / LPB : 1;
     static_assert(kWordsPerThread <= 2, "StageRegs holds two words and their sets");
     auto word_channel = [](int wi) { return 16 * ((wi >> 6) * 4 + (wi & 3)) + ((wi & 63) >> 2); };
+    {
+        const int n_pages = ((n_tiles - 1) * TK) / kPage + 1;
+        for (int p = tid; p < min(n_pages, kPagesLds); p += kPfThreads) pages_s[p] = bt[p];
+        __syncthreads();
+    }
     auto tile_rec0 = [&](int kt) {
-        const int t0 = kt * TK;
-        return ((size_t)bt[t0 / kPage] * H + kvh) * kPage + (t0 % kPage);          // a tile never straddles a page
+        const int t0 = kt * TK, p = t0 / kPage;
+        const int page = p < kPagesLds ? pages_s[p] : bt[p];
+        return ((size_t)page * H + kvh) * kPage + (t0 % kPage);                    // a tile never straddles a page
     };
     auto load_tile = [&](StageRegs<NDW> &sr, int kt) {
         const size_t rec0 = tile_rec0(kt);
