@@ -48,7 +48,8 @@ constexpr int kPfThreads = kPfWaves * 64;
 constexpr int kRB = 1;                        // 16-row blocks per wave
 constexpr int kQB = kPfWaves * 16 * kRB;      // query positions per workgroup
 constexpr int kCS = 8;                        // channels per staging item of the token-major layouts
-constexpr float kPScaleLog2 = 14.0f;          // weights are stored as p * 2^14
+constexpr float kPScaleLog2 = 4.0f;           // weights are stored as p * 2^4
+constexpr float kPSlackLog2 = 11.0f;          // and may exceed 1 by up to 2^11 (p 2^4 <= 2^15 stays finite in fp16)
 
 union HalfOperand {
     uint32_t u[4];
@@ -91,9 +92,13 @@ __global__ __launch_bounds__(kPfThreads, W >= 8 ? 2 : 4) void prefill_kernel(Pre
     constexpr int NDW = DWT > kPfThreads ? DWT / kPfThreads : 1;
     __shared__ __attribute__((aligned(16))) unsigned char v_s[2][D * VS];
     __shared__ __attribute__((aligned(16))) unsigned char k_s[2][TK * KS];
-    // p(e) = 2^14 exp(-2 e / (b tau)) for every distance e above a row's minimum; entry b + 1 is 0.  One LDS read
-    // per pair replaces convert + multiply-add + exponential (a quarter-rate instruction).
-    __shared__ float ptab[64 * W + 2];
+    // p(e) = 2^4 exp(-2 e / (b tau)) for every distance e from a row's reference distance, e = -S .. b; one more
+    // entry holds 0 for masked pairs.  One LDS read per pair replaces convert + multiply-add + exponential (a
+    // quarter-rate instruction).  The reference is the smallest distance the row had seen when it was last set and
+    // is only renewed (accumulators rescaled) when a distance falls more than S below it, S the largest slack whose
+    // weights still fit fp16 (exp(2 S / (b tau)) <= 2^11): the best distance of a row improves by a few units many
+    // times over a long context, and rescaling on each of them was a tenth of the vector work.
+    __shared__ float ptab[128 * W + 2];
     // The sequence's page ids, read once: a block-table lookup per tile from global memory sat, with its full memory
     // latency, in front of every tile's loads (a quarter of the kernel's time when it was measured).
     constexpr int kPagesLds = 1024;
@@ -145,7 +150,7 @@ __global__ __launch_bounds__(kPfThreads, W >= 8 ? 2 : 4) void prefill_kernel(Pre
     const int wave_max_pos = wave_row0 < n_q ? q0 + min(wave_row0 + 16 * kRB, n_q) - 1 : -1;   // ... and of its last valid row
 
     f32x4 acc[kRB][NCB], accsum[kRB];
-    int run_min[kRB];             // 4 x the smallest distance seen so far
+    int run_min[kRB];             // 4 x the row's reference distance
 #pragma unroll
     for (int rb = 0; rb < kRB; ++rb) {
         run_min[rb] = 1 << 22;
@@ -153,8 +158,9 @@ __global__ __launch_bounds__(kPfThreads, W >= 8 ? 2 : 4) void prefill_kernel(Pre
 #pragma unroll
         for (int cb = 0; cb < NCB; ++cb) acc[rb][cb] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
-    for (int e = threadIdx.x; e < 64 * W + 2; e += kPfThreads)
-        ptab[e] = e <= 64 * W ? __builtin_amdgcn_exp2f(fmaf(-a.exp2_scale, (float)e, kPScaleLog2)) : 0.0f;
+    const int S = (int)fminf(kPSlackLog2 / a.exp2_scale, (float)(64 * W));
+    for (int e = threadIdx.x; e < 64 * W + S + 2; e += kPfThreads)
+        ptab[e] = e <= 64 * W + S ? __builtin_amdgcn_exp2f(fmaf(-a.exp2_scale, (float)(e - S), kPScaleLog2)) : 0.0f;
     const uint32_t mask_a = opaque_vgpr(0x000F000Fu), mask_b = opaque_vgpr(0x00F000F0u);
     HalfOperand ones;
 #pragma unroll
@@ -356,12 +362,12 @@ __global__ __launch_bounds__(kPfThreads, W >= 8 ? 2 : 4) void prefill_kernel(Pre
                     dmax = max(dmax, d);
                 }
                 tmin[rb] = xor32_min(xor16_min(pcq[rb] - dmax));  // 4 x the smallest distance of the step, over the row's four lane groups
-                changed |= tmin[rb] < run_min[rb];
+                changed |= tmin[rb] < run_min[rb] - 4 * S;
             }
-            if (__any(changed)) {                                 // rare: the running maximum of some row moved
+            if (__any(changed)) {                                 // rare: some row's best distance left the slack
 #pragma unroll
                 for (int rb = 0; rb < kRB; ++rb) {
-                    const int nm = min(run_min[rb], tmin[rb]);
+                    const int nm = tmin[rb] < run_min[rb] - 4 * S ? tmin[rb] : run_min[rb];
                     const float f = exp2f(0.25f * a.exp2_scale * (float)(nm - run_min[rb]));   // 0 while nothing was accumulated
                     run_min[rb] = nm;
                     // accumulator element j of this lane belongs to row 4 kb + j, whose factor lane 4 kb + j holds
@@ -376,18 +382,19 @@ __global__ __launch_bounds__(kPfThreads, W >= 8 ? 2 : 4) void prefill_kernel(Pre
                         for (int j = 0; j < 4; ++j) acc[rb][cb][j] *= fr[j];
                 }
             }
-            // Weights from the table: p depends only on e = ham - ham_min, an integer in [0, b]; masked pairs
-            // are clamped to the table's zero entry.  4 e = 4 (popcount(q) - ham_min) - score is the entry's byte offset.
+            // Weights from the table: p depends only on e = ham - reference, an integer in [-S, b]; masked pairs
+            // are clamped to the table's zero entry.  4 (e + S) = 4 (popcount(q) - reference + S) - score is the entry's
+            // byte offset.
             HalfOperand A[kRB];
 #pragma unroll
             for (int rb = 0; rb < kRB; ++rb) {
 #pragma unroll
                 for (int j = 0; j < 8; j += 2) {
-                    const int base = pcq[rb] - run_min[rb];
+                    const int base = pcq[rb] - run_min[rb] + 4 * S;
                     int e0 = base - dq[rb][j], e1 = base - dq[rb][j + 1];
                     if (kMasked) {
-                        e0 = min(e0, 4 * (64 * W + 1));
-                        e1 = min(e1, 4 * (64 * W + 1));
+                        e0 = min(e0, 4 * (64 * W + 1) + 4 * S);
+                        e1 = min(e1, 4 * (64 * W + 1) + 4 * S);
                     }
                     const unsigned char *tab = reinterpret_cast<const unsigned char *>(ptab);
                     const float p0 = *reinterpret_cast<const float *>(tab + e0), p1 = *reinterpret_cast<const float *>(tab + e1);
