@@ -4,18 +4,18 @@
 //
 // With many queries per KV head both halves of the step are dense contractions and run on the matrix cores:
 //   scores    alpha needs the Hamming distance of every (query, key) pair.  With the key bits unpacked to {0,1} bytes
-//             and the query bits to {+1,-1} bytes,  sum_k q_k key_k = popcount(q) - ham,  so one int8 MFMA
+//             and the query bits to {+4,-4} bytes,  sum_k q_k key_k = 4 (popcount(q) - ham),  so one int8 MFMA
 //             (v_mfma_i32_16x16x64_i8) per 64 sketch bits yields 16 x 16 distances -- instead of 4 W XOR/popcount
 //             instructions per pair on the vector ALUs.  The MFMA is issued as keys x queries, so that a lane ends
 //             up holding distances of ONE query row against several tokens: the slot it has in the next MFMA.
-//   weights   p = exp((alpha - alpha_max)/tau) takes only b+1 values (the distance above the row's minimum is an
-//             integer): one LDS table read per pair instead of an exponential.  Running maximum per row with a lazy
-//             rescale (the maximum moves rarely); weights packed to fp16 in registers as the A operand of the second
-//             MFMA.  They carry a factor 2^14 to keep small ones out of the fp16 subnormal
-//             range; it cancels in the normalisation, which uses the row sums of the SAME fp16 weights (one more MFMA
-//             against an all-ones B).
+//   weights   p = exp((alpha - alpha_ref)/tau) takes only a few hundred values (the distance from the row's reference
+//             distance is an integer): one LDS table read per pair instead of an exponential, at the byte offset
+//             4 (popcount(q) - ref) - score (hence the +-4).  The reference is a running minimum with slack: it is
+//             renewed, and the accumulators rescaled, only when a distance falls further below it than the fp16 range
+//             of the weights allows.  Weights are packed to fp16 in registers as the A operand of the second MFMA;
+//             the normalisation uses the row sums of the SAME fp16 weights (one more MFMA against an all-ones B).
 //   values    sum_t p[i][t] v^[t][c]  with v_mfma_f32_16x16x32_f16, fp32 accumulate.
-// One workgroup (4 waves) takes 128 consecutive query positions of one (sequence, query head) -- 32 rows per wave --
+// One workgroup (8 waves) takes 128 consecutive query positions of one (sequence, query head) -- 16 rows per wave --
 // and walks the key tokens in tiles up to its diagonal.  Per tile the workgroup stages ONCE, for all its rows: the
 // keys' bits as bytes, and the values dequantised, v^ = fp16(scale * code + zero), channel-major, in the token order
 // the score MFMA leaves its results in (so an MFMA B operand is one 16-byte LDS read).  The next tile's global loads
@@ -99,8 +99,8 @@ __global__ __launch_bounds__(kPfThreads, W >= 8 ? 2 : 4) void prefill_kernel(Pre
     // weights still fit fp16 (exp(2 S / (b tau)) <= 2^11): the best distance of a row improves by a few units many
     // times over a long context, and rescaling on each of them was a tenth of the vector work.
     __shared__ float ptab[128 * W + 2];
-    // The sequence's page ids, read once: a block-table lookup per tile from global memory sat, with its full memory
-    // latency, in front of every tile's loads (a quarter of the kernel's time when it was measured).
+    // The sequence's page ids, read once: a block-table lookup per tile from global memory sits, with its full memory
+    // latency, in front of every tile's loads.
     constexpr int kPagesLds = 1024;
     __shared__ int pages_s[kPagesLds];
 
