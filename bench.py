@@ -105,7 +105,9 @@ def cpu_baseline(wl, w, tau, workers, value_bits=4):
             "ms_per_step": sec * 1e3}
 
 
-FP32_VALU_PEAK_TFLOPS = 78.6    # 256 CUs x 4 SIMDs x 16 lanes x 2 flop x 2.4 GHz: plain (non-packed) fp32 FMA issue
+# 256 CUs x 4 SIMDs x 32 lanes x 2 flop x 2.4 GHz.  Measured on this chip: a plain v_fma_f32 issues every 2.5 clocks per
+# SIMD (0.8 of this figure); the v_fma_mix_f32 that widens fp16 keys inside the chain issues every 4.4 (0.46 of it).
+FP32_VALU_PEAK_TFLOPS = 157.3
 
 
 def bench_append(args, torch, B, wl, w, workers):
