@@ -128,3 +128,30 @@ def test_prefill_over_fp16_values():
     assert np.isfinite(out).all()
     assert rel_err(out, oc.prefill(q, 0.08)) <= TOL
     cache.close()
+
+
+@pytest.mark.parametrize("r", [1, 4])
+def test_reference_distance_renewals(r):
+    """Keys that drift towards the query over the context: every row's best distance improves again and again, so the
+    kernel's reference distance is renewed (and its accumulators rescaled) many times.  Temperatures from very sharp
+    (renewal on nearly every improvement) to flat (the slack covers the whole distance range)."""
+    d, b, g, T, hkv, batch = 128, 128, 32, 900, 2, 2
+    w = wl.Workload(f"prefill_drift_r{r}", batch, hkv * r, hkv, d, T, b, g, "f16", seed=31 + r)
+    R = wl.projection(b, d)
+    rng = np.random.default_rng(5)
+    u = rng.standard_normal((batch, 1, hkv, d))
+    mix = (np.arange(T, dtype=np.float64) / T).reshape(1, T, 1, 1) ** 2            # 0 -> far from u, 1 -> on u
+    k = (mix * u + (1.0 - mix) * rng.standard_normal((batch, T, hkv, d))).astype(np.float16)
+    v = rng.standard_normal((batch, T, hkv, d)).astype(np.float16)
+    seqs = list(range(batch))
+    oc = cref.Cache(R, batch, hkv, T, g)
+    oc.append(k, v)
+    cache = make_cache(w, R, pool_fill=0x7E)
+    cache.append(seqs, to_dev(k), to_dev(v))
+    q = np.repeat(np.broadcast_to(u, (batch, T, hkv, d)), r, axis=2).astype(np.float16)   # every position asks for u
+    q = np.ascontiguousarray(q)
+    for tau in (0.004, 0.02, 0.1, 100.0):
+        out = cache.prefill(seqs, to_dev(q), tau).cpu().numpy()
+        assert np.isfinite(out).all()
+        assert rel_err(out, oc.prefill(q, tau)) <= TOL, f"tau {tau}"
+    cache.close()
