@@ -101,6 +101,7 @@ __device__ __forceinline__ void append_body(const AppendArgs &a, const BatchDesc
     load_row(r_word);
 
     for (int slot0 = bx * tile; slot0 < n_slots; slot0 += gx * tile) {
+        const int tid = per_tile_index(threadIdx.x);   // shadows the outer one: see per_tile_index
         __syncthreads();   // previous pass is done with the LDS tile
         // ---- resolve the tile once: slot -> (head, token) -> source row, destination record ----
         // (the divisions by the runtime slot count per head are done here, by one thread per slot, not in the loops)
@@ -134,14 +135,17 @@ __device__ __forceinline__ void append_body(const AppendArgs &a, const BatchDesc
         // staging and the projection
         constexpr bool kPrefetchV = MF || sizeof(T) == 2;     // (fp32 values would take 32 registers next to the R row)
         [[maybe_unused]] uint4 vpre[4];
-        if constexpr (kPrefetchV) {
+        auto prefetch_values = [&]() {
             const int rl = tid / (D / 32), slice = tid % (D / 32);
             if (rl < tile && valid_slot(rl)) {
                 const uint4 *src = reinterpret_cast<const uint4 *>(vbase + src_off[rl] + slice * 32);
 #pragma unroll
                 for (int i = 0; i < 4; ++i) vpre[i] = src[i];
             }
-        }
+        };
+        // chain path: now; matrix-core path: after its MFMA phase (held through it, the 16 registers spill, and a
+        // spill reload waits for every load in flight)
+        if constexpr (kPrefetchV && !MF) prefetch_values();
 
         // ---- stage the key tile ----
         for (int e = tid * 8; e < tile * D; e += kThreads * 8) {
@@ -154,7 +158,7 @@ __device__ __forceinline__ void append_body(const AppendArgs &a, const BatchDesc
         if constexpr (MF) {
             // ---- Eq.(2) on the matrix cores; the bits inside the guard band by the chain (projection_mfma.h) ----
             project_tile_mfma<D>(pv, reinterpret_cast<const __half *>(&ks[0][0]), D + KPAD, tile, valid_slot,
-                                 reinterpret_cast<uint32_t *>(&words[0][0]), &unsure[0][0]);
+                                 reinterpret_cast<uint32_t *>(&words[0][0]), &unsure[0][0], prefetch_values);
         } else
         // ---- Eq.(2): lane = sketch bit; y = fma chain over j; ballot = packed word ----
         for (int word = wave % wslots; word < W; word += wslots) {

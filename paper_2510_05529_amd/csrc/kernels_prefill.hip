@@ -501,7 +501,7 @@ __global__ __launch_bounds__(kThreads, 4) void sketch_rows_mfma_kernel(PrefillAr
             copy8f(qbase + src_off[rl] + ch, &qs[rl * STRIDE + ch]);
         }
         __syncthreads();
-        project_tile_mfma<D>(pv, qs, STRIDE, n_here, [](int) { return true; }, w32, unsure);
+        project_tile_mfma<D>(pv, qs, STRIDE, n_here, [](int) { return true; }, w32, unsure, []() {});
         __syncthreads();
         // the 32-bit halves of a vector's sketch words are contiguous in w32 and in the output
         uint32_t *out = reinterpret_cast<uint32_t *>(a.q_sketch + (size_t)v0 * W);

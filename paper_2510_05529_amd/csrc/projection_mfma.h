@@ -20,6 +20,14 @@ typedef float proj_f32x4 __attribute__((ext_vector_type(4)));
 constexpr int kProjTile = 64;      // vectors per tile
 constexpr int kProjThreads = 256;
 
+// The thread index in a register the compiler cannot prove invariant across the caller's tile loop: addresses derived
+// from it are recomputed per tile (a few instructions) instead of being hoisted out of the loop into registers that
+// spill -- and a spill reload waits for every global load in flight.
+__device__ __forceinline__ int per_tile_index(int v) {
+    asm volatile("" : "+v"(v));
+    return v;
+}
+
 __device__ __forceinline__ void proj_load8(const __half *p, float *out) {
     const uint4 raw = *reinterpret_cast<const uint4 *>(p);
     const __half2 *h = reinterpret_cast<const __half2 *>(&raw);
@@ -34,42 +42,64 @@ __device__ __forceinline__ void proj_load8(const __half *p, float *out) {
 // xs: the tile, row-major, `stride` halves per row (rows 16-byte aligned, stride a multiple of 8 and not of 64, so
 //     that 16-byte reads down a column spread over the LDS banks);  valid(v): whether row v holds a vector.
 // w32, unsure: [kProjTile][16] 32-bit words in LDS, all zero on entry.  On return (after the caller's next barrier)
-//     w32[v][0 .. b/32) holds the packed sketch of vector v.  Must be called by all 256 threads; contains a barrier.
-template <int D, typename Valid>
+//     w32[v][0 .. b/32) holds the packed sketch of vector v.  Must be called by all 256 threads; contains barriers.
+// between(): called once by every thread after the matrix-core phase, before the chain: the place to issue loads whose
+//     latency the (few, long) chains can hide without their registers being held through the matrix-core phase.
+template <int D, typename Valid, typename Between>
 __device__ __forceinline__ void project_tile_mfma(const PoolView &pv, const __half *xs, int stride, int tile, Valid valid,
-                                                  uint32_t *w32, uint32_t *unsure) {
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+                                                  uint32_t *w32, uint32_t *unsure, Between between) {
+    const int tid = per_tile_index(threadIdx.x), lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int n = lane & 15, kb = lane >> 4;
     const int n_tb = (tile + 15) / 16;
-    for (int bb = wave; bb < pv.sketch_bits / 16; bb += 4) {        // blocks of 16 sketch bits
-        uint4 Ahi[D / 32], Amid[D / 32];
+    const int n_bb = pv.sketch_bits / 16;                           // blocks of 16 sketch bits: wave, wave + 4, ...
+    __shared__ float band_s[kProjTile];
+    struct AOperands {
+        uint4 hi[D / 32], mid[D / 32];
+        float g[4];
+    };
+    auto load_a = [&](AOperands &A, int bb) {
         const size_t arow = (size_t)(16 * bb + n) * D + 8 * kb;
 #pragma unroll
         for (int jb = 0; jb < D / 32; ++jb) {
-            Ahi[jb] = *reinterpret_cast<const uint4 *>(pv.R16hi + arow + 32 * jb);
-            Amid[jb] = *reinterpret_cast<const uint4 *>(pv.R16mid + arow + 32 * jb);
+            A.hi[jb] = *reinterpret_cast<const uint4 *>(pv.R16hi + arow + 32 * jb);
+            A.mid[jb] = *reinterpret_cast<const uint4 *>(pv.R16mid + arow + 32 * jb);
         }
-        float g[4];
 #pragma unroll
-        for (int jj = 0; jj < 4; ++jj) g[jj] = pv.guard[16 * bb + 4 * kb + jj];
+        for (int jj = 0; jj < 4; ++jj) A.g[jj] = pv.guard[16 * bb + 4 * kb + jj];
+    };
+    // the first block's pieces of R are requested before anything else: their latency runs behind the norms
+    AOperands A;
+    if (wave < n_bb) load_a(A, wave);
+    // ---- 2-norm of every vector, once per tile: four threads per vector, 32 elements each ----
+    {
+        const int v = tid >> 2, part = tid & 3;
+        float ss = 0.0f;
+        if (v < tile && valid(v)) {
+            for (int j = part * 8; j < D; j += 32) {
+                float x[8];
+                proj_load8(xs + (size_t)v * stride + j, x);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) ss = fmaf(x[e], x[e], ss);
+            }
+        }
+        ss += __shfl_xor(ss, 1);
+        ss += __shfl_xor(ss, 2);
+        if (part == 0) band_s[v] = sqrtf(ss) * 1.0000153f;    // fp32 rounding of the sum and the root stays below 2^-16
+    }
+    __syncthreads();
+    for (int bb = wave; bb < n_bb; bb += 4) {
+        if (bb != wave) load_a(A, bb);
 #pragma unroll 1
         for (int tb = 0; tb < n_tb; ++tb) {
             proj_f32x4 yh = {0.f, 0.f, 0.f, 0.f}, ym = {0.f, 0.f, 0.f, 0.f};
             const int v = 16 * tb + n;
-            float ss = 0.0f;
 #pragma unroll
             for (int jb = 0; jb < D / 32; ++jb) {
                 const proj_f16x8 Bx = *reinterpret_cast<const proj_f16x8 *>(xs + (size_t)v * stride + 32 * jb + 8 * kb);
-                yh = __builtin_amdgcn_mfma_f32_16x16x32_f16(*reinterpret_cast<const proj_f16x8 *>(&Ahi[jb]), Bx, yh, 0, 0, 0);
-                ym = __builtin_amdgcn_mfma_f32_16x16x32_f16(*reinterpret_cast<const proj_f16x8 *>(&Amid[jb]), Bx, ym, 0, 0, 0);
-                // 2-norm of the lane's vector on the side: the lane reads a quarter of it as its B operands, the
-                // other quarters sit in the lanes 16, 32 and 48 away
-#pragma unroll
-                for (int e = 0; e < 8; ++e) ss = fmaf((float)Bx[e], (float)Bx[e], ss);
+                yh = __builtin_amdgcn_mfma_f32_16x16x32_f16(*reinterpret_cast<const proj_f16x8 *>(&A.hi[jb]), Bx, yh, 0, 0, 0);
+                ym = __builtin_amdgcn_mfma_f32_16x16x32_f16(*reinterpret_cast<const proj_f16x8 *>(&A.mid[jb]), Bx, ym, 0, 0, 0);
             }
-            ss += __shfl_xor(ss, 16);
-            ss += __shfl_xor(ss, 32);
-            const float band = sqrtf(ss) * 1.0000153f;        // fp32 rounding of the sum and the root stays below 2^-16
+            const float band = band_s[v];
             // element jj of this lane: bit 16 bb + 4 kb + jj of vector v
             if (v < tile && valid(v)) {
                 uint32_t sbits = 0u, ubits = 0u;
@@ -77,7 +107,7 @@ __device__ __forceinline__ void project_tile_mfma(const PoolView &pv, const __ha
                 for (int jj = 0; jj < 4; ++jj) {
                     const float y = fmaf(ym[jj], 0.000244140625f, yh[jj]);
                     sbits |= (y >= 0.0f ? 1u : 0u) << jj;
-                    ubits |= (fabsf(y) > g[jj] * band ? 0u : 1u) << jj;          // also catches a NaN
+                    ubits |= (fabsf(y) > A.g[jj] * band ? 0u : 1u) << jj;        // also catches a NaN
                 }
                 const int sh = 16 * (bb & 1) + 4 * kb;
                 atomicOr(&w32[v * 16 + (bb >> 1)], sbits << sh);
@@ -86,6 +116,7 @@ __device__ __forceinline__ void project_tile_mfma(const PoolView &pv, const __ha
         }
     }
     __syncthreads();
+    between();
     // ---- the chain for the bits inside the guard band: one thread per (vector, 32 bits) ----
     const int W32 = pv.sketch_bits / 32;
     for (int item = tid; item < tile * W32; item += kProjThreads) {
