@@ -32,8 +32,10 @@ HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    # a step lasts a fraction of a millisecond and the chip needs some tens of milliseconds of continuous work to reach
+    # its steady clocks: 50 warm-up steps, 400 timed ones (0.1 s of timed work; the cache fill dominates the run)
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="decode_b16_32k",
                     help="decode_b16_32k (default, the graded configuration) | decode_7b_8k | decode_gqa_128k | tiny")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
