@@ -50,6 +50,9 @@ __device__ __forceinline__ uint32_t opaque_vgpr(uint32_t v) {
     asm volatile("" : "+v"(v));
     return v;
 }
+// 2^x for x <= 0 as the bare hardware instruction: the library routine wraps it in a range reduction for results
+// below the smallest normal number, which a softmax weight next to a weight of 1 never needs (they flush to 0 here).
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ uint32_t and_or(uint32_t x, uint32_t mask, uint32_t magic) { return (x & mask) | magic; }
 
 // Streaming loads: cache records are read once per decode step and never reused by the kernel, so the value planes

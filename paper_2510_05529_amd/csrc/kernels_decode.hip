@@ -123,14 +123,14 @@ __global__ __launch_bounds__(kThreads, RQ >= 4 ? 2 : 1) void decode_split_kernel
             for (int w = 0; w < W; ++w) h += __popcll(sq[q][w] ^ pr.sk.w[w]);
             const int pmin = wave_min_dpp(valid ? h : (1 << 20));
             if (pmin < run_min[q]) {                       // uniform over the wave; rare after the first pages
-                const float f = exp2f(a.exp2_scale * (float)(pmin - run_min[q]));   // 0 while nothing has been accumulated
+                const float f = fast_exp2(a.exp2_scale * (float)(pmin - run_min[q]));   // 0 while nothing has been accumulated
                 run_min[q] = pmin;
                 lsum[q] *= f;
                 zs[q] *= f;
 #pragma unroll
                 for (int i = 0; i < 32; ++i) acc[q][i] *= f;
             }
-            p[q] = valid ? exp2f(a.exp2_scale * (float)(run_min[q] - h)) : 0.0f;
+            p[q] = valid ? fast_exp2(a.exp2_scale * (float)(run_min[q] - h)) : 0.0f;
             lsum[q] += p[q];
         }
         // ---- value role: lane = (token, 32-channel slice) ----
@@ -237,7 +237,7 @@ __global__ __launch_bounds__(kThreads, RQ >= 4 ? 2 : 1) void decode_split_kernel
         float o = 0.0f, l = 0.0f;
 #pragma unroll
         for (int w = 0; w < kWaves; ++w) {
-            const float f = exp2f(a.exp2_scale * (float)(hm - m_s[w][q]));      // 0 for a wave that saw no valid token
+            const float f = fast_exp2(a.exp2_scale * (float)(hm - m_s[w][q]));      // 0 for a wave that saw no valid token
             float ow = 0.0f, z = 0.0f;
 #pragma unroll
             for (int rw = 0; rw < ROWS; ++rw) {
@@ -285,7 +285,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_kernel(DecodeArgs a, Batc
     float l = 0.0f, o = 0.0f;
 #pragma unroll 4
     for (int s = sl; s < n; s += n_sl) {
-        const float w = exp2f(a.exp2_scale * (float)(hmin - __float_as_int(a.part_ml[(part + s) * 2])));
+        const float w = fast_exp2(a.exp2_scale * (float)(hmin - __float_as_int(a.part_ml[(part + s) * 2])));
         l = fmaf(w, a.part_ml[(part + s) * 2 + 1], l);
         o = fmaf(w, a.part_o[(part + s) * D + c], o);
     }

@@ -133,13 +133,13 @@ __global__ __launch_bounds__(kThreads, RQ >= 8 ? 2 : (RQ >= 4 ? 3 : 4)) void dec
             for (int w = 0; w < W; ++w) h += __popcll(sq[q][w] ^ sk.w[w]);
             const int pmin = wave_min_dpp16(valid ? h : (1 << 20));
             if (pmin < run_min[q]) {                       // uniform over the wave; rare after the first pages
-                const float f = exp2f(a.exp2_scale * (float)(pmin - run_min[q]));
+                const float f = fast_exp2(a.exp2_scale * (float)(pmin - run_min[q]));
                 run_min[q] = pmin;
                 lsum[q] *= f;
 #pragma unroll
                 for (int i = 0; i < 8; ++i) acc[q][i] *= f;
             }
-            p[q] = valid ? exp2f(a.exp2_scale * (float)(run_min[q] - h)) : 0.0f;
+            p[q] = valid ? fast_exp2(a.exp2_scale * (float)(run_min[q] - h)) : 0.0f;
             lsum[q] += p[q];
         }
         // ---- value role: lane = (token, 8-channel slice) ----
@@ -212,7 +212,7 @@ __global__ __launch_bounds__(kThreads, RQ >= 8 ? 2 : (RQ >= 4 ? 3 : 4)) void dec
         float o = 0.0f, l = 0.0f;
 #pragma unroll
         for (int w = 0; w < kWaves; ++w) {
-            const float f = exp2f(a.exp2_scale * (float)(hm - m_s[w][q]));      // 0 for a wave that saw no valid token
+            const float f = fast_exp2(a.exp2_scale * (float)(hm - m_s[w][q]));      // 0 for a wave that saw no valid token
             o = fmaf(f, epi[w][q][c], o);
             l = fmaf(f, l_s[w][q], l);
         }

@@ -183,7 +183,7 @@ __global__ __launch_bounds__(kThreads, RQH == 2 ? 3 : 2) void decode_split_mfma_
 #pragma unroll
             for (int qq = 0; qq < RQH; ++qq) {
                 const int nm = min(run_min[qq], pmin[qq]);
-                const float f = exp2f(a.exp2_scale * (float)(nm - run_min[qq]));     // <= 1; 0 when nothing was accumulated yet
+                const float f = fast_exp2(a.exp2_scale * (float)(nm - run_min[qq]));     // <= 1; 0 when nothing was accumulated yet
                 run_min[qq] = nm;
                 lsum[qq] *= f;
 #pragma unroll
@@ -214,7 +214,7 @@ __global__ __launch_bounds__(kThreads, RQH == 2 ? 3 : 2) void decode_split_mfma_
 #pragma unroll
             for (int qq = 0; qq < RQH; ++qq) {
                 // heads beyond RQ have an all-zero query sketch here; their rows are never read back
-                p[qq] = valid[t] ? exp2f(a.exp2_scale * (float)(run_min[qq] - ham[t][qq])) : 0.0f;
+                p[qq] = valid[t] ? fast_exp2(a.exp2_scale * (float)(run_min[qq] - ham[t][qq])) : 0.0f;
                 lsum[qq] += p[qq];
             }
 #pragma unroll
@@ -309,7 +309,7 @@ __global__ __launch_bounds__(kThreads, RQH == 2 ? 3 : 2) void decode_split_mfma_
         float o = 0.0f, l = 0.0f;
 #pragma unroll
         for (int w = 0; w < kWaves; ++w) {
-            const float f = exp2f(a.exp2_scale * (float)(hm - m_s[w][q]));      // 0 for a wave that saw no valid token
+            const float f = fast_exp2(a.exp2_scale * (float)(hm - m_s[w][q]));      // 0 for a wave that saw no valid token
             const float ws = sum_s[w][g][q] + sum_s[w][g][RQMAX + q];
             o = fmaf(f, fmaf(-128.0f, ws, epi[w][q][c] + epi[w][RQMAX + q][c]) + zs_s[w][q][g], o);   // B held 128 + code
             l = fmaf(f, l_s[w][q], l);
