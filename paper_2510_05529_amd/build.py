@@ -43,8 +43,8 @@ def _stale(target: str, deps) -> bool:
 def build(force: bool = False, verbose: bool = False) -> str:
     os.makedirs(LIBDIR, exist_ok=True)
     os.makedirs(OBJDIR, exist_ok=True)
-    headers = [os.path.join(ROOT, "include", "h1bkv.h"), os.path.join(CSRC, "internal.h"), os.path.join(CSRC, "decode_common.h"),
-               os.path.abspath(__file__)]
+    headers = [os.path.join(ROOT, "include", "h1bkv.h"), os.path.abspath(__file__)]
+    headers += [os.path.join(CSRC, f) for f in sorted(os.listdir(CSRC)) if f.endswith(".h")]
     jobs = []
     objs = []
     for src, extra in SOURCES.items():
