@@ -677,7 +677,11 @@ int h1bkv_decode_attn_dtau(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t 
 
 size_t h1bkv_prefill_workspace_bytes(const h1bkv_cache *c, int32_t n_seqs, int32_t n_q) {
     if (!c || n_seqs < 1 || n_q < 1) return 0;
-    return align_up((size_t)n_seqs * n_q * c->cfg.n_q_heads * c->W * 8);
+    const size_t rows = (size_t)n_seqs * n_q * c->cfg.n_q_heads;
+    const int splits = prefill_max_splits(c->cfg.n_q_heads, n_seqs, n_q);
+    size_t o = align_up(rows * c->W * 8);                                        // the chunk's query sketches
+    if (splits > 1) o = align_up(o + rows * splits * (c->cfg.head_dim + 2) * sizeof(float));   // partial results per context split
+    return o;
 }
 
 int h1bkv_prefill_attn(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n_seqs, int32_t n_q, const void *q_dev,
@@ -709,8 +713,13 @@ int h1bkv_prefill_attn(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n_se
     a.stride_tok = stride_tok;
     a.stride_head = stride_head;
     a.q_sketch = static_cast<uint64_t *>(workspace_dev);
+    a.part = reinterpret_cast<float *>(static_cast<char *>(workspace_dev) + align_up((size_t)n_seqs * n_q * c->cfg.n_q_heads * c->W * 8));
     a.out = out_dev;
     a.n_q = n_q;
+    // a chunk that is short against its context is split over the context as well: every split at least a page long
+    int max_len = 0;
+    for (int i = 0; i < n_seqs; ++i) max_len = std::max(max_len, c->seq_len[seq_ids_host[i]]);
+    a.n_splits = std::max(1, std::min(prefill_max_splits(c->cfg.n_q_heads, n_seqs, n_q), max_len / kPage));
     a.f16 = c->cfg.in_dtype == H1BKV_F16;
     a.proj_mfma = a.f16 && c->proj_mfma && (int64_t)n_seqs * n_q * c->cfg.n_q_heads >= 64;
     a.exp2_scale = (float)(2.0 * 1.4426950408889634 / ((double)c->cfg.sketch_bits * (double)tau));
@@ -724,6 +733,7 @@ int h1bkv_prefill_attn(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n_se
         for (int i = 0; i < n; ++i) desc.s[i] = SeqDesc{seq_ids_host[s0 + i], c->seq_len[seq_ids_host[s0 + i]]};
         Timed t(c, H1BKV_K_PREFILL, st);
         if (launch_prefill(a, desc, s0, n, st) != hipSuccess) return H1BKV_EHIP;
+        if (a.n_splits > 1 && launch_prefill_merge(a, s0, n, st) != hipSuccess) return H1BKV_EHIP;
     }
     return H1BKV_OK;
 }

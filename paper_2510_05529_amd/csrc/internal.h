@@ -98,11 +98,24 @@ struct PrefillArgs {
     int64_t stride_seq, stride_tok, stride_head;
     uint64_t *q_sketch;       // workspace: [n_seqs][n_q][H_q][W]
     float *out;               // [n_seqs][n_q][H_q][d]
+    float *part;              // workspace: [n_seqs][n_q][H_q][n_splits][d + 2] partial results (n_splits > 1 only):
+                              //   d unnormalised sums, the weight sum, the reference distance (x 4, as int bits)
     int32_t n_q;              // query positions per sequence: the last n_q cached positions
+    int32_t n_splits;         // context splits per query block: each workgroup walks 1 / n_splits of the block's key tiles
     int32_t f16;
     int32_t proj_mfma;        // query sketches from the matrix-core projection (fp16 queries)
     float exp2_scale;         // 2 log2(e) / (b tau)
 };
+
+constexpr int kPrefillRows = 128;            // query positions per prefill workgroup
+constexpr int kPrefillMaxSplits = 16;
+// Most context splits a prefill call of n_seqs x n_q query positions can use: enough workgroups to fill the chip when
+// the chunk is short (a long prompt alone already brings thousands of workgroups: one split).
+inline int prefill_max_splits(int n_q_heads, int n_seqs, int n_q) {
+    const int64_t wgs = (int64_t)n_q_heads * n_seqs * ((n_q + kPrefillRows - 1) / kPrefillRows);
+    const int64_t s = (1024 + wgs - 1) / wgs;
+    return (int)(s < 1 ? 1 : s > kPrefillMaxSplits ? kPrefillMaxSplits : s);
+}
 
 // The prefill kernel keeps a row block's accumulators (d/16 MFMA tiles) in registers.
 inline bool prefill_supported(int head_dim, int) { return head_dim <= 128; }
@@ -132,6 +145,7 @@ hipError_t launch_decode_dtau_split(const DecodeArgs &a, const BatchDesc &desc, 
 hipError_t launch_merge_dtau(const DecodeArgs &a, const BatchDesc &desc, int seq0, int n_seqs, float dtau_scale, hipStream_t st);
 hipError_t launch_merge(const DecodeArgs &a, const BatchDesc &desc, int seq0, int n_seqs, hipStream_t st);
 hipError_t launch_sketch_rows(const PrefillArgs &a, int n_seqs, hipStream_t st);
+hipError_t launch_prefill_merge(const PrefillArgs &a, int seq0, int n_seqs, hipStream_t st);
 hipError_t launch_prefill(const PrefillArgs &a, const BatchDesc &desc, int seq0, int n_seqs, hipStream_t st);
 hipError_t launch_stream_copy(void *dst, const void *src, size_t n_bytes, hipStream_t st);
 hipError_t launch_stream_read(const void *src, size_t n_bytes, void *sink, hipStream_t st);

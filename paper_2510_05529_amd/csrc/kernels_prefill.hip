@@ -106,15 +106,19 @@ __global__ __launch_bounds__(kPfThreads, W >= 8 ? 2 : 4) void prefill_kernel(Pre
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int i = lane & 15, kb = lane >> 4;
-    // grid (query head, sequence, query block): workgroups are dispatched x-fastest, so the longest-running (latest)
-    // query blocks of ALL heads and sequences start first and the short ones fill the tail of the launch
+    // grid (query head, sequence, query block x context split): workgroups are dispatched x-fastest, so the
+    // longest-running (latest) query blocks of ALL heads and sequences start first and the short ones fill the tail of
+    // the launch.  With n_splits > 1 (a chunk that is short against its context) a workgroup walks only its share of
+    // the block's key tiles and leaves (sums, weight sum, reference distance) per row for prefill_merge_kernel.
     const SeqDesc sd = desc.s[blockIdx.y];
     const int len = sd.pos, n_q = a.n_q;
-    const int qb = (int)gridDim.z - 1 - (int)blockIdx.z;
+    const int n_splits = a.n_splits, split = (int)blockIdx.z % n_splits;
+    const int qb = (int)gridDim.z / n_splits - 1 - (int)blockIdx.z / n_splits;
     const int row0 = qb * kQB;
     const int q0 = len - n_q;                                      // absolute position of query 0
     const int last_row = min(row0 + kQB, n_q) - 1;
     const int n_tiles = (q0 + last_row + TK) / TK;                 // tiles that hold tokens visible to the last row
+    const int tile_lo = (int)((long)n_tiles * split / n_splits), tile_hi = (int)((long)n_tiles * (split + 1) / n_splits);
 
     const PoolView &pv = a.pool;
     const int H = pv.n_kv_heads, Hq = pv.n_q_heads, r = Hq / H;
@@ -416,18 +420,20 @@ __global__ __launch_bounds__(kPfThreads, W >= 8 ? 2 : 4) void prefill_kernel(Pre
     };
 
     StageRegs<NDW> sr;
-    load_tile(sr, 0);
-    store_tile(sr, 0, 0);
+    if (tile_lo < tile_hi) {                                       // (a short sequence may leave a split without tiles)
+        load_tile(sr, tile_lo);
+        store_tile(sr, tile_lo, tile_lo & 1);
+    }
     __syncthreads();
-    for (int kt = 0; kt < n_tiles; ++kt) {
+    for (int kt = tile_lo; kt < tile_hi; ++kt) {
         const int buf = kt & 1;
-        if (kt + 1 < n_tiles) load_tile(sr, kt + 1);
+        if (kt + 1 < tile_hi) load_tile(sr, kt + 1);
         const int t_first = kt * TK, t_last = t_first + TK - 1;
         if (t_first <= wave_max_pos) {                             // else: the whole tile lies in this wave's future
             if (t_last <= wave_min_pos && wave_row0 + 16 * kRB <= n_q) consume_tile(kt, buf, std::false_type{});
             else consume_tile(kt, buf, std::true_type{});
         }
-        if (kt + 1 < n_tiles) store_tile(sr, kt + 1, buf ^ 1);
+        if (kt + 1 < tile_hi) store_tile(sr, kt + 1, buf ^ 1);
         __syncthreads();
     }
 
@@ -437,12 +443,42 @@ __global__ __launch_bounds__(kPfThreads, W >= 8 ? 2 : 4) void prefill_kernel(Pre
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int qi = wave_row0 + rb * 16 + 4 * kb + j;
+            const int ref = __shfl(run_min[rb], 4 * kb + j);      // the row's reference distance sits in lane 4 kb + j
             if (qi >= n_q) continue;
-            const float inv = 1.0f / accsum[rb][j];
-            float *dst = a.out + (((size_t)seq_g * n_q + qi) * Hq + h) * D + i;
+            if (n_splits == 1) {
+                const float inv = 1.0f / accsum[rb][j];
+                float *dst = a.out + (((size_t)seq_g * n_q + qi) * Hq + h) * D + i;
 #pragma unroll
-            for (int cb = 0; cb < NCB; ++cb) dst[16 * cb] = acc[rb][cb][j] * inv;
+                for (int cb = 0; cb < NCB; ++cb) dst[16 * cb] = acc[rb][cb][j] * inv;
+            } else {
+                float *dst = a.part + ((((size_t)seq_g * n_q + qi) * Hq + h) * n_splits + split) * (D + 2);
+#pragma unroll
+                for (int cb = 0; cb < NCB; ++cb) dst[16 * cb + i] = acc[rb][cb][j];
+                if (i == 0) {
+                    dst[D] = accsum[rb][j];
+                    dst[D + 1] = __int_as_float(ref);
+                }
+            }
         }
+}
+
+// out = sum_s f_s o_s / sum_s f_s l_s over the context splits of one (query position, head), f_s = exp(-2 (ref_s -
+// ref_min) / (b tau)): the splits' sums are relative to their own reference distances.  A split that saw no visible
+// token of the row carries the initial reference (2^22) and zero sums: its factor is 0.
+__global__ void prefill_merge_kernel(PrefillArgs a, int seq0) {
+    const int D = a.pool.head_dim, S = a.n_splits, c = threadIdx.x;
+    const size_t row = (size_t)seq0 * a.n_q * a.pool.n_q_heads + blockIdx.x;        // (sequence, position, head), flattened
+    const float *p = a.part + row * S * (D + 2);
+    int ref = 1 << 22;
+    for (int s = 0; s < S; ++s) ref = min(ref, __float_as_int(p[(size_t)s * (D + 2) + D + 1]));
+    float l = 0.0f, o = 0.0f;
+    for (int s = 0; s < S; ++s) {
+        const float *ps = p + (size_t)s * (D + 2);
+        const float f = __builtin_amdgcn_exp2f(0.25f * a.exp2_scale * (float)(ref - __float_as_int(ps[D + 1])));
+        l = fmaf(f, ps[D], l);
+        o = fmaf(f, ps[c], o);
+    }
+    a.out[row * D + c] = o / l;
 }
 
 // ---- Eq.(2) for the chunk's query vectors: lane = sketch bit, R row in registers, 64 vectors per LDS tile ----
@@ -586,8 +622,15 @@ hipError_t launch_prefill_d(const PrefillArgs &a, const BatchDesc &desc, int seq
 
 }  // namespace
 
+hipError_t launch_prefill_merge(const PrefillArgs &a, int seq0, int n_seqs, hipStream_t st) {
+    const size_t rows = (size_t)n_seqs * a.n_q * a.pool.n_q_heads;
+    hipLaunchKernelGGL(prefill_merge_kernel, dim3((unsigned)rows), dim3((unsigned)a.pool.head_dim), 0, st, a, seq0);
+    return hipGetLastError();
+}
+
 hipError_t launch_prefill(const PrefillArgs &a, const BatchDesc &desc, int seq0, int n_seqs, hipStream_t st) {
-    const dim3 grid((unsigned)a.pool.n_q_heads, (unsigned)n_seqs, (unsigned)((a.n_q + kQB - 1) / kQB));
+    static_assert(kQB == kPrefillRows, "the host sizes grids and workspaces with kPrefillRows");
+    const dim3 grid((unsigned)a.pool.n_q_heads, (unsigned)n_seqs, (unsigned)((a.n_q + kQB - 1) / kQB * a.n_splits));
     switch (a.pool.sketch_bits) {
         case 64: return launch_prefill_d<1>(a, desc, seq0, grid, st);
         case 128: return launch_prefill_d<2>(a, desc, seq0, grid, st);

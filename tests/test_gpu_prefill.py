@@ -155,3 +155,28 @@ def test_reference_distance_renewals(r):
         assert np.isfinite(out).all()
         assert rel_err(out, oc.prefill(q, tau)) <= TOL, f"tau {tau}"
     cache.close()
+
+
+@pytest.mark.parametrize("dt,r", [("f16", 1), ("f16", 4), ("f32", 2)])
+def test_short_chunk_over_a_long_context_is_split_over_the_context(dt, r):
+    """A chunk of 150 positions on top of contexts of up to 2900 tokens: too few query blocks to fill the chip, so the
+    kernel splits the context as well and a merge pass combines the splits (the shortest sequence leaves most of its
+    splits without a single tile)."""
+    d, b, g, hkv, T, n_q = 128, 128, 32, 2, 2900, 150
+    w = wl.Workload(f"prefill_split_{dt}_r{r}", 3, hkv * r, hkv, d, T, b, g, dt, seed=91 + r)
+    R = wl.projection(b, d)
+    seqs = [0, 1, 2]
+    lens = [T, 700, n_q]
+    k, v = wl.kv_slab(w, "k", seqs, 0, T), wl.kv_slab(w, "v", seqs, 0, T)
+    oc = cref.Cache(R, 3, hkv, T, g)
+    oc.append(k, v)
+    cache = make_cache(w, R, pool_fill=0x7E)
+    kd, vd = to_dev(k), to_dev(v)
+    for s, n in zip(seqs, lens):
+        cache.append([s], kd[s:s + 1, :n], vd[s:s + 1, :n])
+    q = _queries(w, n_q)
+    for tau in (0.02, 0.2):
+        out = cache.prefill(seqs, to_dev(q), tau).cpu().numpy()
+        assert np.isfinite(out).all()
+        assert rel_err(out, oc.prefill(q, tau, ctx_len=lens)) <= TOL, f"tau {tau}"
+    cache.close()
