@@ -256,9 +256,10 @@ int check_seq_ids(const h1bkv_cache *c, const int32_t *ids, int32_t n) {
 int choose_chunk(const h1bkv_cache *c, int n_seqs, int max_ctx) {
     if (c->chunk_override > 0) return c->chunk_override;
     const int64_t heads = (int64_t)n_seqs * c->cfg.n_kv_heads;
-    // the matrix-core kernel gains from long streams per workgroup: two resident workgroups per compute unit (512 on the
-    // chip) are enough (measured at 4 x 8 KV heads x 131072 tokens: 86 us with 8192-token chunks, 89-90 with 2048, and a cheaper merge)
-    const int64_t target_wgs = c->code_layout == 1 ? 512 : 4096;
+    // the matrix-core kernel gains from long streams per workgroup: four resident workgroups per compute unit (1024 on
+    // the chip) are enough (measured at 4 x 8 KV heads x 131072 tokens: 77-79 us with 4096-token chunks, 86-88 with
+    // 8192, 80-82 with 2048)
+    const int64_t target_wgs = c->code_layout == 1 ? 1024 : 4096;
     int chunk = max_decode_chunk(c->r, c->code_layout);
     while (chunk > kPage && heads * ((max_ctx + chunk - 1) / chunk) < target_wgs) chunk /= 2;
     return chunk;

@@ -128,8 +128,13 @@ __global__ __launch_bounds__(kThreads, RQH == 2 ? 3 : 2) void decode_split_mfma_
 #pragma unroll
     for (int i = 0; i < 4; ++i) ones.u[i] = 0x3F803F80u;       // bf16 1.0
 
-    auto load_page = [&](PageRegs<NCB4, NG> &pr, int pg) {
-        const size_t base = ((size_t)pages_s[pg] * H + kvh) * kPage + wave * 64;
+    // One register set holds a page; each plane is requested again, for the next page, as soon as its last use in the
+    // current page is behind: the sketches after scoring, the codes and scale/zero of a 32-token step after that
+    // step's MFMAs.  (A second set handed over by copies cost a quarter of the loop's vector instructions and a third
+    // of the registers.)
+    auto page_base = [&](int pg) { return ((size_t)pages_s[pg] * H + kvh) * kPage + wave * 64; };
+    auto load_sketches = [&](PageRegs<NCB4, NG> &pr, int pg) {
+        const size_t base = page_base(pg);
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
             const uint64_t *sp = pv.sketch + (base + 32 * t + tk) * W;
@@ -145,16 +150,20 @@ __global__ __launch_bounds__(kThreads, RQH == 2 ? 3 : 2) void decode_split_mfma_
                     }
                 }
             }
-            const uint4 *cp = reinterpret_cast<const uint4 *>(pv.codes + (base + 32 * t + 8 * kb) * (D / 2)) + n;
-#pragma unroll
-            for (int i = 0; i < NCB4; ++i) pr.c[t][i] = load_stream(cp + i * 16);
-            const uint32_t *mp = pv.meta + (base + 32 * t + tk) * NG;
-#pragma unroll
-            for (int g = 0; g < NG; ++g) pr.m[t][g] = load_stream(mp + g);
         }
     };
+    auto load_step = [&](PageRegs<NCB4, NG> &pr, int pg, int t) {
+        const size_t base = page_base(pg);
+        const uint4 *cp = reinterpret_cast<const uint4 *>(pv.codes + (base + 32 * t + 8 * kb) * (D / 2)) + n;
+#pragma unroll
+        for (int i = 0; i < NCB4; ++i) pr.c[t][i] = load_stream(cp + i * 16);
+        const uint32_t *mp = pv.meta + (base + 32 * t + tk) * NG;
+#pragma unroll
+        for (int g = 0; g < NG; ++g) pr.m[t][g] = load_stream(mp + g);
+    };
 
-    auto consume_page = [&](const PageRegs<NCB4, NG> &pr, int pg) {
+    auto consume_page = [&](PageRegs<NCB4, NG> &pr, int pg) {
+        const bool more = pg + 1 < n_pages;
         // ---- scores of this lane's two tokens against its query heads (Eq. 3) ----
         int ham[2][RQH], pmin[RQH];
         bool valid[2];
@@ -175,6 +184,7 @@ __global__ __launch_bounds__(kThreads, RQH == 2 ? 3 : 2) void decode_split_mfma_
             }
             pmin[qq] = half_wave_min(min(ham[0][qq], ham[1][qq]));
         }
+        if (more) load_sketches(pr, pg + 1);
         // ---- running maximum: rescale what has been accumulated if this page raises it ----
         bool changed = false;
 #pragma unroll
@@ -253,22 +263,19 @@ __global__ __launch_bounds__(kThreads, RQH == 2 ? 3 : 2) void decode_split_mfma_
                 }
                 accsum[g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, ones.v, accsum[g], 0, 0, 0);
             }
+            if (more) load_step(pr, pg + 1, t);
             // the next step overwrites the operands: its writes must not pass these reads
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
         }
     };
 
-    // the next page's loads are in flight while the current page is consumed
     {
-        PageRegs<NCB4, NG> A;
-        load_page(A, 0);
-        for (int pg = 0; pg < n_pages; ++pg) {
-            PageRegs<NCB4, NG> nA = A;
-            if (pg + 1 < n_pages) load_page(nA, pg + 1);
-            consume_page(A, pg);
-            A = nA;
-        }
+        PageRegs<NCB4, NG> pr;
+        load_sketches(pr, 0);
+        load_step(pr, 0, 0);
+        load_step(pr, 0, 1);
+        for (int pg = 0; pg < n_pages; ++pg) consume_page(pr, pg);
     }
 
     // ---------------- Epilogue: the four waves meet ----------------
