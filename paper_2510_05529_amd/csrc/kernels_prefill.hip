@@ -41,8 +41,8 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef int i32x4 __attribute__((ext_vector_type(4)));
 
 // Eight waves of one 16-row block each: the same 128 query rows and the same LDS tiles per workgroup as four waves of
-// two blocks, at half the registers per wave, so that four waves share a SIMD and one's matrix-core phase overlaps the
-// others' vector phases.
+// two blocks, at half the registers per wave, so that four waves share a SIMD (a single wave issues a vector
+// instruction only every five clocks or so; two workgroups per compute unit also cover each other's barriers).
 constexpr int kPfWaves = 8;
 constexpr int kPfThreads = kPfWaves * 64;
 constexpr int kRB = 1;                        // 16-row blocks per wave
