@@ -90,11 +90,20 @@ __device__ __forceinline__ void append_body(const AppendArgs &a, const BatchDesc
     [[maybe_unused]] int r_word = wave % wslots;
     [[maybe_unused]] auto load_row = [&](int word) {
         if constexpr (!MF) {
-            const float *row = pv.R + (size_t)(word * 64 + lane) * D;
+            if (a.n_new == 1) {
+                // a decode step's append: a workgroup sketches a handful of records, so the row is read once and the
+                // read should be cheap -- from R^T a wave's load of element j is one 256-byte run (from R the 64 lanes
+                // read 64 different rows)
+                const float *col = pv.RT + word * 64 + lane;
 #pragma unroll
-            for (int j = 0; j < D; j += 4) {
-                const float4 x = *reinterpret_cast<const float4 *>(row + j);
-                r[j] = x.x; r[j + 1] = x.y; r[j + 2] = x.z; r[j + 3] = x.w;
+                for (int j = 0; j < D; ++j) r[j] = col[(size_t)j * pv.sketch_bits];
+            } else {
+                const float *row = pv.R + (size_t)(word * 64 + lane) * D;
+#pragma unroll
+                for (int j = 0; j < D; j += 4) {
+                    const float4 x = *reinterpret_cast<const float4 *>(row + j);
+                    r[j] = x.x; r[j + 1] = x.y; r[j + 2] = x.z; r[j + 3] = x.w;
+                }
             }
         }
     };
