@@ -112,6 +112,34 @@ def cpu_baseline(wl, w, tau, workers, value_bits=4):
 FP32_VALU_PEAK_TFLOPS = 157.3
 
 
+def cpu_baseline_prompt(wl, w, tau, workers, attend):
+    """The oracle on the host cores for the prompt workloads: the first 1024 tokens of one sequence (all heads) are
+    appended and, with `attend`, attended causally.  The attention cost per token grows with the position, so the
+    sample's tokens/s is not the full prompt's: pairs/s is the size-independent figure."""
+    from oracle import cref
+    R = wl.projection(w.sketch_bits, w.head_dim)
+    n = min(1024, w.context)
+    k, v = wl.kv_slab(w, "k", [0], 0, n, workers), wl.kv_slab(w, "v", [0], 0, n, workers)
+    q = np.ascontiguousarray(np.repeat(k[..., ::-1], w.n_q_heads // w.n_kv_heads, axis=2))
+    times = []
+    t_begin = time.perf_counter()
+    while len(times) < 2 or (time.perf_counter() - t_begin < 8.0 and len(times) < 50):
+        oc = cref.Cache(R, 1, w.n_kv_heads, n, w.group_size)
+        t = time.perf_counter()
+        oc.append(k, v)
+        if attend:
+            oc.prefill(q, tau)
+        times.append(time.perf_counter() - t)
+    sec = float(np.median(times))
+    out = {"value": n / sec, "unit": "tokens/s", "cores": cref.max_threads(), "kind": "oracle",
+           "sample": f"the first {n} tokens of 1 of {w.batch} sequences (all {w.n_kv_heads} KV heads): append"
+                     + (" + causal attention of every position" if attend else "") + f", median of {len(times)} runs, {sec * 1e3:.0f} ms",
+           "ms_per_step": sec * 1e3}
+    if attend:
+        out["pairs_per_s"] = w.n_q_heads * n * (n + 1) / 2.0 / sec
+    return out
+
+
 def bench_append(args, torch, B, wl, w, workers):
     """Secondary line: prefill-sized cache append (all new tokens of every sequence in one call)."""
     n_new, Bsz = w.context, w.batch
@@ -157,7 +185,9 @@ def bench_append(args, torch, B, wl, w, workers):
             if mfma_path else
             {"bound": "alu", "kernel": "append_kernel", "achieved": chain_tflops, "peak": FP32_VALU_PEAK_TFLOPS, "unit": "TFLOP/s",
              "frac": chain_tflops / FP32_VALU_PEAK_TFLOPS, "traffic": None, "kernel_ms": kernel_ms, "hbm_GBps": hbm_gbps})
+    extra = {} if args.no_cpu_baseline else {"cpu_baseline": cpu_baseline_prompt(wl, w, w.default_tau(), workers, attend=False)}
     print(json.dumps({
+        **extra,
         "metric": "append_tokens_per_s", "value": Bsz * n_new / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
@@ -225,7 +255,9 @@ def bench_prefill(args, torch, B, wl, w, workers):
     achieved = lane_ops / (kernel_ms["prefill"] * 1e-3) / 1e12
     peak = VALU_LANE_OPS_PER_S / 1e12
     mfma_flops = pairs * w.head_dim * 2.0
+    extra = {} if args.no_cpu_baseline else {"cpu_baseline": cpu_baseline_prompt(wl, w, tau, workers, attend=True)}
     print(json.dumps({
+        **extra,
         "metric": "prefill_tokens_per_s", "value": Bsz * n_new / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
