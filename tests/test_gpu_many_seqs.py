@@ -61,3 +61,14 @@ def test_prefill_and_dtau_over_150_sequences():
     ref, dref = oc.decode_dtau(q1, 0.12)
     assert rel_err(o.cpu().numpy(), ref[order]) <= TOL and rel_err(do.cpu().numpy(), dref[order]) <= TOL
     cache.close()
+
+
+def test_context_split_prefill_over_150_sequences():
+    """Contexts long enough for the prefill's context split (two splits here): the partial results and the merge pass
+    must follow the per-launch sequence offsets too."""
+    w, seqs, order, oc, cache = _setup(1, 600)
+    rng = np.random.default_rng(3)
+    q = rng.standard_normal((N, 5, w.n_q_heads, 64)).astype(np.float16)
+    out = cache.prefill(order, to_dev(q[order]), 0.12).cpu().numpy()
+    assert rel_err(out, oc.prefill(q, 0.12)[order]) <= TOL
+    cache.close()
