@@ -100,7 +100,7 @@ __global__ __launch_bounds__(kThreads, 1) void decode_dtau_split_kernel(DecodeAr
         const int pmin = wave_min_dpp_t(valid ? h : (1 << 20));
         if (pmin < run_min) {                          // uniform over the wave; rare after the first pages
             const float k = (float)(run_min - pmin);   // every e grows by k (all sums are still 0 the first time)
-            const float f = exp2f(a.exp2_scale * (float)(pmin - run_min));
+            const float f = fast_exp2(a.exp2_scale * (float)(pmin - run_min));
             run_min = pmin;
             lsum[1] = (lsum[1] + k * lsum[0]) * f;
             zs[1] = (zs[1] + k * zs[0]) * f;
@@ -114,7 +114,7 @@ __global__ __launch_bounds__(kThreads, 1) void decode_dtau_split_kernel(DecodeAr
                 acc[0][i] *= f;
             }
         }
-        const float p = valid ? exp2f(a.exp2_scale * (float)(run_min - h)) : 0.0f;
+        const float p = valid ? fast_exp2(a.exp2_scale * (float)(run_min - h)) : 0.0f;
         const float pe = valid ? p * (float)(h - run_min) : 0.0f;
         lsum[0] += p;
         lsum[1] += pe;
@@ -211,7 +211,7 @@ __global__ __launch_bounds__(kThreads, 1) void decode_dtau_split_kernel(DecodeAr
 #pragma unroll
         for (int w = 0; w < kWaves; ++w) {
             if (m_s[w] >= (1 << 20)) continue;                                   // a wave that saw no valid token
-            const float f = exp2f(a.exp2_scale * (float)(hm - m_s[w]));
+            const float f = fast_exp2(a.exp2_scale * (float)(hm - m_s[w]));
             const float k = (float)(m_s[w] - hm);                                // the wave counted e from its own minimum
             float val[2];
 #pragma unroll
@@ -263,7 +263,7 @@ __global__ void merge_dtau_kernel(DecodeArgs a, BatchDesc desc, int seq0, float 
     for (int s = 0; s < n; ++s) {
         const float *ml = a.part_ml + (part + s) * 4;
         const int hm = __float_as_int(ml[0]);
-        const float f = exp2f(a.exp2_scale * (float)(hmin - hm));
+        const float f = fast_exp2(a.exp2_scale * (float)(hmin - hm));
         const float k = (float)(hm - hmin);
         const float os = a.part_o[(part + s) * D + c];
         l = fmaf(f, ml[1], l);
