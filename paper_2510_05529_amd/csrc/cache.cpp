@@ -262,11 +262,11 @@ int choose_chunk(const h1bkv_cache *c, int n_seqs, int max_ctx) {
     const int64_t target_wgs = c->code_layout == 1 ? 1024 : 4096;
     int chunk = max_decode_chunk(c->r, c->code_layout);
     // Small problems: a workgroup's fixed cost (prologue, four-wave epilogue, partial results) is that of two or three
-    // pages of streaming, so below 1024-token chunks only a quarter of the target is insisted on (measured at 8 x 32
+    // pages of streaming, so below 1024-token chunks only a quarter of the target (at least 1024) is insisted on (measured at 8 x 32
     // heads x 4096 tokens: 25.8 us with one page per workgroup, 21.2 us with four).
     while (chunk > kPage) {
         const int64_t wgs = heads * ((max_ctx + chunk - 1) / chunk);
-        if (wgs >= target_wgs || (chunk <= 1024 && wgs >= target_wgs / 4)) break;
+        if (wgs >= target_wgs || (chunk <= 1024 && wgs >= std::max<int64_t>(target_wgs / 4, 1024))) break;
         chunk /= 2;
     }
     return chunk;
