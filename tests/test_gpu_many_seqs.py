@@ -28,7 +28,7 @@ def _setup(r, T, value_bits=4):
     return w, seqs, order, oc, cache
 
 
-@pytest.mark.parametrize("r,value_bits", [(1, 4), (4, 4), (2, 16)])
+@pytest.mark.parametrize("r,value_bits", [(1, 4), (4, 4), (2, 16), (8, 4)])       # r = 8: 2048 heads per launch, the few-chunk merge
 def test_append_and_decode_over_150_sequences(r, value_bits):
     w, seqs, order, oc, cache = _setup(r, 40, value_bits)
     assert_cache_equal(cache, oc, seqs, 40, heads=[1])
