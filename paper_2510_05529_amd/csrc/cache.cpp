@@ -569,7 +569,25 @@ static int enqueue_decode(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n
         for (int i = 0; i < n; ++i) desc.s[i] = SeqDesc{seq_ids_host[s0 + i], c->seq_len[seq_ids_host[s0 + i]]};
         if (!sketches_done) {
             Timed t(c, H1BKV_K_QSKETCH, st);
-            if (launch_qsketch(a, s0, n, st) != hipSuccess) return H1BKV_EHIP;
+            // Thousands of fp16 queries (large batches): the prefill path's matrix-core projection with its guard band
+            // (same bits as the chain); the queries are then one position per sequence.
+            const bool mfma_q = a.f16 && c->proj_mfma && prefill_supported(c->cfg.head_dim, c->code_layout) &&
+                                (int64_t)n * c->cfg.n_q_heads >= 2048;
+            if (mfma_q) {
+                PrefillArgs pa{};
+                pa.pool = a.pool;
+                pa.q = static_cast<const char *>(q_dev) + (size_t)s0 * c->cfg.n_q_heads * c->cfg.head_dim * 2;
+                pa.stride_seq = (int64_t)c->cfg.n_q_heads * c->cfg.head_dim;
+                pa.stride_tok = 0;
+                pa.stride_head = c->cfg.head_dim;
+                pa.q_sketch = a.q_sketch + (size_t)s0 * c->cfg.n_q_heads * c->W;
+                pa.n_q = 1;
+                pa.f16 = 1;
+                pa.proj_mfma = 1;
+                if (launch_sketch_rows(pa, n, st) != hipSuccess) return H1BKV_EHIP;
+            } else if (launch_qsketch(a, s0, n, st) != hipSuccess) {
+                return H1BKV_EHIP;
+            }
         }
         {
             Timed t(c, H1BKV_K_DECODE_SPLIT, st);

@@ -35,6 +35,11 @@ def test_append_and_decode_over_150_sequences(r, value_bits):
     q = wl.queries(w)
     out = cache.decode(order, to_dev(q[order]), 0.1).cpu().numpy()
     assert rel_err(out, oc.decode(q, 0.1)[order]) <= TOL
+    # the query sketches at the head of the workspace, bit for bit (from 2048 fp16 queries per launch on they come from
+    # the matrix-core projection and its guard band)
+    n_words = N * w.n_q_heads
+    got = cache.workspace[: n_words * 8].cpu().numpy().view(np.uint64).reshape(N, w.n_q_heads, 1)
+    assert np.array_equal(got, cref.sketch(oc.R, q[order]))
     # fused step on top: one more token for everybody
     import torch
     k1, v1 = wl.kv_slab(w, "k", seqs, 39, 1)[:, 0], wl.kv_slab(w, "v", seqs, 39, 1)[:, 0]      # any fresh-looking token
