@@ -302,7 +302,10 @@ class Cache:
             h1bkv_destroy(self.h)
             self.h = None
 
-    __del__ = close
+    def __del__(self):
+        # at interpreter shutdown the module's globals may already be gone: the handle then dies with the process
+        if h1bkv_destroy is not None:
+            self.close()
 
     def seq_len(self, seq_id: int) -> int:
         rc, n = h1bkv_seq_len(self.h, seq_id)
