@@ -41,6 +41,9 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
     ap.add_argument("--value-bits", type=int, default=4, choices=(4, 16),
                     help="16: the '1-bit key only' variant (fp16 values, Table V ablation) instead of the method's 4-bit values")
+    ap.add_argument("--prefill-chunk", type=int, default=0, metavar="N",
+                    help="with --prefill: feed the prompt in chunks of N tokens (append a chunk, attend from it), as a serving "
+                         "stack with chunked prefill does; 0 = the whole prompt in one call")
     ap.add_argument("--prefill", action="store_true",
                     help="with --workload append_prefill_8k: append the prompt AND run causal prefill attention over it")
     ap.add_argument("--chunk", type=int, default=0, help="decode chunk override (tokens, multiple of 256)")
@@ -223,8 +226,10 @@ def bench_prefill(args, torch, B, wl, w, workers):
     q = torch.from_numpy(wl.kv_slab(w, "k", seqs, 0, n_new, workers)[..., ::-1].copy()).cuda()   # any dense tensor of the shape
     if w.n_q_heads != w.n_kv_heads:
         q = q.repeat_interleave(w.n_q_heads // w.n_kv_heads, dim=2).contiguous()
-    out = torch.empty((Bsz, n_new, w.n_q_heads, w.head_dim), dtype=torch.float32, device="cuda")
-    ws_bytes = B.h1bkv_prefill_workspace_bytes(cache.h, Bsz, n_new)
+    chunk = args.prefill_chunk if 0 < args.prefill_chunk < n_new else n_new
+    n_chunks = (n_new + chunk - 1) // chunk
+    out = torch.empty((Bsz, chunk, w.n_q_heads, w.head_dim), dtype=torch.float32, device="cuda")   # one chunk's (dense) output
+    ws_bytes = B.h1bkv_prefill_workspace_bytes(cache.h, Bsz, chunk)
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
     stream = torch.cuda.current_stream()
     tau = w.default_tau()
@@ -232,13 +237,16 @@ def bench_prefill(args, torch, B, wl, w, workers):
     def step():
         for s in seqs:
             B.check(B.h1bkv_reset_seq(cache.h, s))
-        B.check(B.h1bkv_append_kv(cache.h, seqs, n_new, k, v, k.stride(0), k.stride(1), k.stride(2), stream))
-        B.check(B.h1bkv_prefill_attn(cache.h, seqs, n_new, q, q.stride(0), q.stride(1), q.stride(2), tau, out, ws, ws_bytes, stream))
+        for t0 in range(0, n_new, chunk):
+            n = min(chunk, n_new - t0)
+            kc, vc, qc = k[:, t0:t0 + n], v[:, t0:t0 + n], q[:, t0:t0 + n]
+            B.check(B.h1bkv_append_kv(cache.h, seqs, n, kc, vc, k.stride(0), k.stride(1), k.stride(2), stream))
+            B.check(B.h1bkv_prefill_attn(cache.h, seqs, n, qc, q.stride(0), q.stride(1), q.stride(2), tau, out, ws, ws_bytes, stream))
 
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    B.check(B.h1bkv_profile_enable(cache.h, args.steps, 0x1F))
+    B.check(B.h1bkv_profile_enable(cache.h, args.steps * n_chunks, 0x1F))
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
@@ -248,7 +256,7 @@ def bench_prefill(args, torch, B, wl, w, workers):
     for name, kid in (("append", B.H1BKV_K_APPEND), ("sketch_rows", B.H1BKV_K_QSKETCH), ("prefill", B.H1BKV_K_PREFILL)):
         rc, ms = B.h1bkv_profile_read(cache.h, kid)
         B.check(rc)
-        kernel_ms[name] = float(ms.mean())
+        kernel_ms[name] = float(ms.sum()) / args.steps            # per prompt: the sum over its chunks
     W = w.sketch_bits // 64
     pairs = Bsz * w.n_q_heads * n_new * (n_new + 1) / 2.0        # visible (query, key) pairs
     lane_ops = pairs * (4 * W + 7)
@@ -263,7 +271,9 @@ def bench_prefill(args, torch, B, wl, w, workers):
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name, "batch": Bsz, "prompt_tokens": n_new, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
                    "head_dim": w.head_dim, "sketch_bits": w.sketch_bits, "group_size": w.group_size, "in_dtype": w.dtype, "tau": tau,
-                   "step": "append the whole prompt + causal attention of every position over the compressed cache"},
+                   "prefill_chunk": chunk,
+                   "step": "append the whole prompt + causal attention of every position over the compressed cache"
+                           + ("" if chunk == n_new else f", fed in chunks of {chunk} tokens")},
         "roofline": {"bound": "alu", "kernel": "prefill_kernel", "achieved": achieved, "peak": peak, "unit": "T lane-op/s",
                      "frac": achieved / peak, "traffic": None, "kernel_ms": kernel_ms["prefill"],
                      "pairs_per_s": pairs / (kernel_ms["prefill"] * 1e-3), "lane_ops_per_pair": 4 * W + 7,
