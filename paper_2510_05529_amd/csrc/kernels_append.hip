@@ -327,11 +327,15 @@ __global__ __launch_bounds__(kThreads) void step_prologue_kernel(AppendArgs a, B
         const int bit = b <= kThreads ? threadIdx.x % b : bit0 + threadIdx.x;
         const int vec = vec0 + qi;
         float y = 0.0f;
-        float rt[D];
+        constexpr int CH = D < 128 ? D : 128;                         // elements of the column held at a time
+#pragma unroll 1
+        for (int j0 = 0; j0 < D; j0 += CH) {
+            float rt[CH];
 #pragma unroll
-        for (int j = 0; j < D; ++j) rt[j] = a.pool.RT[(size_t)j * b + bit];
+            for (int j = 0; j < CH; ++j) rt[j] = a.pool.RT[(size_t)(j0 + j) * b + bit];
 #pragma unroll
-        for (int j = 0; j < D; ++j) y = __builtin_fmaf(rt[j], qs[qi][j], y);
+            for (int j = 0; j < CH; ++j) y = __builtin_fmaf(rt[j], qs[qi][j0 + j], y);
+        }
         const uint64_t mask = __ballot(y >= 0.0f);
         if ((threadIdx.x & 63) == 0 && vec < qa.n_vec) qa.q_sketch[(size_t)vec * W + (bit >> 6)] = mask;
     }

@@ -352,14 +352,19 @@ __global__ void qsketch_kernel(DecodeArgs a, int seq0) {
     const size_t vec = (size_t)seq0 * a.pool.n_q_heads + blockIdx.x;
     const T *q = static_cast<const T *>(a.q) + vec * D;
     const int bit = threadIdx.x;
-    float rt[D];
-#pragma unroll
-    for (int j = 0; j < D; ++j) rt[j] = a.pool.RT[(size_t)j * b + bit];
     for (int j = threadIdx.x; j < D; j += blockDim.x) qs[j] = (float)q[j];
     __syncthreads();
+    // at most 128 elements of the column at a time (256 would not fit the register file next to anything else)
+    constexpr int CH = D < 128 ? D : 128;
     float y = 0.0f;
+#pragma unroll 1
+    for (int j0 = 0; j0 < D; j0 += CH) {
+        float rt[CH];
 #pragma unroll
-    for (int j = 0; j < D; ++j) y = __builtin_fmaf(rt[j], qs[j], y);
+        for (int j = 0; j < CH; ++j) rt[j] = a.pool.RT[(size_t)(j0 + j) * b + bit];
+#pragma unroll
+        for (int j = 0; j < CH; ++j) y = __builtin_fmaf(rt[j], qs[j0 + j], y);
+    }
     const uint64_t mask = __ballot(y >= 0.0f);
     if ((threadIdx.x & 63) == 0) a.q_sketch[vec * W + (threadIdx.x >> 6)] = mask;
 }
