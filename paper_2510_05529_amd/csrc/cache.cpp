@@ -43,7 +43,7 @@ Layout make_layout(const h1bkv_config &c) {
     L.off_RT = o;      o = align_up(o + b * d * sizeof(float));
     L.off_R16hi = o;   o = align_up(o + b * d * sizeof(uint16_t));
     L.off_R16mid = o;  o = align_up(o + b * d * sizeof(uint16_t));
-    L.off_guard = o;   o = align_up(o + b * sizeof(float));
+    L.off_guard = o;   o = align_up(o + 2 * b * sizeof(float));
     L.off_bt = o;      o = align_up(o + (size_t)c.max_seqs * c.max_pages_per_seq * sizeof(int32_t));
     L.off_sketch = o;  o = align_up(o + rec * W * 8);
     const bool f16v = c.value_bits == 16;
@@ -88,11 +88,16 @@ double f16_to_f64(uint16_t h) {
 //               allowed three times the chain's)                                     <= 3 d 2^-24 ||R||_2 ||k||_2
 //            + (a piece that is an fp16 subnormal may be read as zero)              <= ||flush||_2 ||k||_2.
 // guard[i] is twice the sum of these row factors; a bit with |y~| <= guard[i] ||k||_2 is recomputed with the chain.
+// fp32 inputs are scaled by a power of two and split the same way, k s = kh + 2^-12 km + eps (stage_f32_tile), and the
+// kernel leaves out the product of the two low pieces; guard[b + i] prices that in:
+//            + (input pieces: |eps_j| <= 2^-22 |k_j s| + 2^-37)                       <= 2^-21 ||R||_2 ||k s||_2
+//            + (dropped 2^-24 sum mid_j km_j, |mid_j| <= 2 |R_j|, |km_j| <= 2 |k_j s|) <= 2^-22 ||R||_2 ||k s||_2
+//            + (a third piece sum in the matrix-core accumulation: four times the chain's instead of three).
 void make_projection_pieces(const float *R, int b, int d, std::vector<uint16_t> &hi, std::vector<uint16_t> &mid,
                             std::vector<float> &guard) {
     hi.resize((size_t)b * d);
     mid.resize((size_t)b * d);
-    guard.resize(b);
+    guard.resize(2 * (size_t)b);
     for (int i = 0; i < b; ++i) {
         double n2 = 0.0, delta2 = 0.0, flush2 = 0.0;
         for (int j = 0; j < d; ++j) {
@@ -112,6 +117,9 @@ void make_projection_pieces(const float *R, int b, int d, std::vector<uint16_t> 
         }
         const double g = 2.0 * (std::sqrt(delta2) + 4.0 * d * std::ldexp(1.0, -24) * std::sqrt(n2) + std::sqrt(flush2));
         guard[i] = std::nextafter((float)g, INFINITY);
+        const double g32 = 2.0 * (std::sqrt(delta2) + (5.0 * d * std::ldexp(1.0, -24) + std::ldexp(1.0, -21) + std::ldexp(1.0, -22)) * std::sqrt(n2) +
+                                  std::sqrt(flush2));
+        guard[(size_t)b + i] = std::nextafter((float)g32, INFINITY);
     }
 }
 
@@ -477,7 +485,7 @@ static int enqueue_append(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n
         a.f16 = c->cfg.in_dtype == H1BKV_F16;
         // prefill-sized appends of fp16 keys take the matrix-core projection; short ones (a decode step's single
         // token) stay on the plain chain, which is launch-bound there anyway
-        a.proj_mfma = a.f16 && n_new >= 16 && c->proj_mfma;
+        a.proj_mfma = n_new >= 16 && c->proj_mfma && (a.f16 || c->cfg.head_dim <= 128);
         for (int s0 = 0; s0 < n_seqs && rc == H1BKV_OK; s0 += kMaxSeqsPerLaunch) {
             const int n = std::min(kMaxSeqsPerLaunch, n_seqs - s0);
             BatchDesc desc;
@@ -571,18 +579,18 @@ static int enqueue_decode(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n
             Timed t(c, H1BKV_K_QSKETCH, st);
             // Thousands of fp16 queries (large batches): the prefill path's matrix-core projection with its guard band
             // (same bits as the chain); the queries are then one position per sequence.
-            const bool mfma_q = a.f16 && c->proj_mfma && prefill_supported(c->cfg.head_dim, c->code_layout) &&
+            const bool mfma_q = c->proj_mfma && prefill_supported(c->cfg.head_dim, c->code_layout) &&
                                 (int64_t)n * c->cfg.n_q_heads >= 2048;
             if (mfma_q) {
                 PrefillArgs pa{};
                 pa.pool = a.pool;
-                pa.q = static_cast<const char *>(q_dev) + (size_t)s0 * c->cfg.n_q_heads * c->cfg.head_dim * 2;
+                pa.q = static_cast<const char *>(q_dev) + (size_t)s0 * c->cfg.n_q_heads * c->cfg.head_dim * (a.f16 ? 2 : 4);
                 pa.stride_seq = (int64_t)c->cfg.n_q_heads * c->cfg.head_dim;
                 pa.stride_tok = 0;
                 pa.stride_head = c->cfg.head_dim;
                 pa.q_sketch = a.q_sketch + (size_t)s0 * c->cfg.n_q_heads * c->W;
                 pa.n_q = 1;
-                pa.f16 = 1;
+                pa.f16 = a.f16;
                 pa.proj_mfma = 1;
                 if (launch_sketch_rows(pa, n, st) != hipSuccess) return H1BKV_EHIP;
             } else if (launch_qsketch(a, s0, n, st) != hipSuccess) {
@@ -747,7 +755,7 @@ int h1bkv_prefill_attn(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n_se
     for (int i = 0; i < n_seqs; ++i) max_len = std::max(max_len, c->seq_len[seq_ids_host[i]]);
     a.n_splits = std::max(1, std::min(prefill_max_splits(c->cfg.n_q_heads, n_seqs, n_q), max_len / kPage));
     a.f16 = c->cfg.in_dtype == H1BKV_F16;
-    a.proj_mfma = a.f16 && c->proj_mfma && (int64_t)n_seqs * n_q * c->cfg.n_q_heads >= 64;
+    a.proj_mfma = c->proj_mfma && (int64_t)n_seqs * n_q * c->cfg.n_q_heads >= 64;
     a.exp2_scale = (float)(2.0 * 1.4426950408889634 / ((double)c->cfg.sketch_bits * (double)tau));
     {
         Timed t(c, H1BKV_K_QSKETCH, st);

@@ -34,12 +34,12 @@ struct TablePairs {
 struct PoolView {
     const float *R;          // [b][d]
     const float *RT;         // [d][b]
-    // Matrix-core projection (append of fp16 keys, prefill query sketches): R split into two fp16 pieces,
+    // Matrix-core projection (prefill-sized appends, prefill query sketches): R split into two fp16 pieces,
     // R ~ R16hi + 2^-12 R16mid, and per row the guard band factor: a projection whose magnitude exceeds
     // guard[i] * ||k||_2 has the sign of the pinned fp32 chain for certain (see make_projection_pieces in cache.cpp).
     const uint16_t *R16hi;   // [b][d] fp16 bits
     const uint16_t *R16mid;  // [b][d] fp16 bits
-    const float *guard;      // [b]
+    const float *guard;      // [2][b]: the band factors for fp16 inputs, then those for fp32 inputs (split into two pieces too)
     int32_t *block_table;    // [max_seqs][max_pages_per_seq]
     uint64_t *sketch;        // [page][H_kv][256][W]
     uint8_t *codes;          // [page][H_kv][256][d/2]

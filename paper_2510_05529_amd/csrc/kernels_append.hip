@@ -24,6 +24,8 @@
 //   2  the "1-bit key only" variant (Table V): no quantiser, the plane holds the values as fp16, record-major.
 #include <hip/hip_fp16.h>
 
+#include <type_traits>
+
 #include "internal.h"
 #include "projection_mfma.h"
 
@@ -60,12 +62,16 @@ __device__ __forceinline__ void copy8(const float *src, float *dst) {
 
 // bx, by, gx: the workgroup's tile index, its sequence (index into desc) and the number of workgroups that share
 // the sequence's tiles -- blockIdx.x, blockIdx.y, gridDim.x when the kernel does nothing else.
-// MF: the projections come from the matrix cores (fp16 keys only) and only the bits inside the guard band are
-// recomputed with the chain; see the projection block below.
+// MF: the projections come from the matrix cores and only the bits inside the guard band are recomputed with the
+// chain; see the projection block below (fp32 keys are scaled and split into two fp16 pieces while they are staged).
 template <int D, typename T, bool MF>
 __device__ __forceinline__ void append_body(const AppendArgs &a, const BatchDesc &desc, int tile, int bx, int by, int gx) {
-    constexpr int KPAD = 16 / sizeof(T);                      // 16 bytes per row: conflict-free 16-byte reads down a column
-    __shared__ __attribute__((aligned(16))) T ks[kTile][D + KPAD];   // the key tile in its boundary dtype
+    constexpr bool F32MF = MF && sizeof(T) == 4;              // matrix-core projection of fp32 keys: two fp16 piece tiles
+    using KT = typename std::conditional<F32MF, __half, T>::type;
+    constexpr int KPAD = 16 / sizeof(KT);                     // 16 bytes per row: conflict-free 16-byte reads down a column
+    // the key tile in its boundary dtype; F32MF: rows [kTile, 2 kTile) hold the low pieces
+    __shared__ __attribute__((aligned(16))) KT ks[F32MF ? 2 * kTile : kTile][D + KPAD];
+    __shared__ float band_s[MF ? kTile : 1];          // matrix-core path: guard band norm of each key
     __shared__ uint32_t unsure[MF ? kTile : 1][16];   // matrix-core path: per token, the sketch bits that need the chain
     static_assert(kTile == kProjTile && kThreads == kProjThreads, "projection_mfma.h assumes this tile shape");
     __shared__ uint64_t words[kTile][8];              // sketch words of the tile (W <= 8)
@@ -142,7 +148,7 @@ __device__ __forceinline__ void append_body(const AppendArgs &a, const BatchDesc
 
         // fp16 values: the slice this thread quantises first is requested now, so that its latency runs behind the key
         // staging and the projection
-        constexpr bool kPrefetchV = MF || sizeof(T) == 2;     // (fp32 values would take 32 registers next to the R row)
+        constexpr bool kPrefetchV = sizeof(T) == 2;           // (fp32 values would take 32 registers next to the R row)
         [[maybe_unused]] uint4 vpre[4];
         auto prefetch_values = [&]() {
             const int rl = tid / (D / 32), slice = tid % (D / 32);
@@ -157,17 +163,27 @@ __device__ __forceinline__ void append_body(const AppendArgs &a, const BatchDesc
         if constexpr (kPrefetchV && !MF) prefetch_values();
 
         // ---- stage the key tile ----
-        for (int e = tid * 8; e < tile * D; e += kThreads * 8) {
-            const int rl = e / D, ch = e % D;
-            if (valid_slot(rl)) copy8(kbase + src_off[rl] + ch, &ks[rl][ch]);
+        if constexpr (F32MF) {
+            stage_f32_tile<D>([&](int rl) { return valid_slot(rl) ? kbase + src_off[rl] : nullptr; }, tile, &ks[0][0], &ks[kTile][0],
+                              D + KPAD, band_s);
+        } else {
+            for (int e = tid * 8; e < tile * D; e += kThreads * 8) {
+                const int rl = e / D, ch = e % D;
+                if (valid_slot(rl)) copy8(kbase + src_off[rl] + ch, &ks[rl][ch]);
+            }
         }
         if (tid < tile) dst[tid] = ((size_t)my_page * H + my_head) * kPage + (my_pos % kPage);
         __syncthreads();
 
         if constexpr (MF) {
             // ---- Eq.(2) on the matrix cores; the bits inside the guard band by the chain (projection_mfma.h) ----
-            project_tile_mfma<D>(pv, reinterpret_cast<const __half *>(&ks[0][0]), D + KPAD, tile, valid_slot,
-                                 reinterpret_cast<uint32_t *>(&words[0][0]), &unsure[0][0], prefetch_values);
+            auto between = [&]() {
+                if constexpr (kPrefetchV) prefetch_values();
+            };
+            project_tile_mfma<D, F32MF>(pv, reinterpret_cast<const __half *>(&ks[0][0]),
+                                        reinterpret_cast<const __half *>(&ks[F32MF ? kTile : 0][0]), band_s, D + KPAD, tile, valid_slot,
+                                        reinterpret_cast<uint32_t *>(&words[0][0]), &unsure[0][0], between,
+                                        [&](int rl) { return reinterpret_cast<const float *>(kbase + src_off[rl]); });
         } else
         // ---- Eq.(2): lane = sketch bit; y = fma chain over j; ballot = packed word ----
         for (int word = wave % wslots; word < W; word += wslots) {
@@ -380,6 +396,9 @@ hipError_t launch_append(const AppendArgs &a, const BatchDesc &desc, int n_seqs,
         if (D == 64) hipLaunchKernelGGL((append_kernel<64, __half, true>), grid, dim3(kThreads), 0, st, a, desc, (int)tile);
         else if (D == 128) hipLaunchKernelGGL((append_kernel<128, __half, true>), grid, dim3(kThreads), 0, st, a, desc, (int)tile);
         else hipLaunchKernelGGL((append_kernel<256, __half, true>), grid, dim3(kThreads), 0, st, a, desc, (int)tile);
+    } else if (a.proj_mfma && !qa && D <= 128) {      // fp32 keys (d = 256: two piece tiles would not leave room for a second workgroup)
+        if (D == 64) hipLaunchKernelGGL((append_kernel<64, float, true>), grid, dim3(kThreads), 0, st, a, desc, (int)tile);
+        else hipLaunchKernelGGL((append_kernel<128, float, true>), grid, dim3(kThreads), 0, st, a, desc, (int)tile);
     } else if (a.f16) {
         if (D == 64) H1BKV_LAUNCH(64, __half);
         else if (D == 128) H1BKV_LAUNCH(128, __half);

@@ -507,18 +507,20 @@ __device__ __forceinline__ void copy8f(const float *src, float *dst) {
 }
 
 // fp16 queries: the projections on the matrix cores, the bits inside the guard band by the chain (projection_mfma.h).
-template <int D>
+template <int D, typename T>
 __global__ __launch_bounds__(kThreads, 4) void sketch_rows_mfma_kernel(PrefillArgs a, int n_seqs) {
+    constexpr bool F32 = sizeof(T) == 4;                           // fp32 queries: scaled and split into two fp16 piece tiles
     constexpr int STRIDE = D + 8;                                  // halves per LDS row
-    __shared__ __attribute__((aligned(16))) __half qs[kSketchTile * STRIDE];
+    __shared__ __attribute__((aligned(16))) __half qs[(F32 ? 2 : 1) * kSketchTile * STRIDE];
     __shared__ size_t src_off[kSketchTile];
     __shared__ uint32_t w32[kSketchTile * 16], unsure[kSketchTile * 16];
+    __shared__ float band_s[kSketchTile];
     static_assert(kSketchTile == kProjTile && kThreads == kProjThreads, "projection_mfma.h assumes this tile shape");
     const int tid = threadIdx.x;
     const PoolView &pv = a.pool;
     const int W = pv.sketch_bits >> 6, Hq = pv.n_q_heads;
     const long n_vec = (long)n_seqs * a.n_q * Hq;
-    const __half *qbase = static_cast<const __half *>(a.q);
+    const T *qbase = static_cast<const T *>(a.q);
     for (long v0 = (long)blockIdx.x * kSketchTile; v0 < n_vec; v0 += (long)gridDim.x * kSketchTile) {
         __syncthreads();
         const int n_here = (int)min((long)kSketchTile, n_vec - v0);
@@ -532,12 +534,18 @@ __global__ __launch_bounds__(kThreads, 4) void sketch_rows_mfma_kernel(PrefillAr
             src_off[tid] = (size_t)s * a.stride_seq + (size_t)(rem / Hq) * a.stride_tok + (size_t)(rem % Hq) * a.stride_head;
         }
         __syncthreads();
-        for (int e = tid * 8; e < n_here * D; e += kThreads * 8) {
-            const int rl = e / D, ch = e % D;
-            copy8f(qbase + src_off[rl] + ch, &qs[rl * STRIDE + ch]);
+        if constexpr (F32) {
+            stage_f32_tile<D>([&](int rl) { return reinterpret_cast<const float *>(qbase + src_off[rl]); }, n_here, qs,
+                              qs + kSketchTile * STRIDE, STRIDE, band_s);
+        } else {
+            for (int e = tid * 8; e < n_here * D; e += kThreads * 8) {
+                const int rl = e / D, ch = e % D;
+                copy8f(reinterpret_cast<const __half *>(qbase + src_off[rl] + ch), &qs[rl * STRIDE + ch]);
+            }
         }
         __syncthreads();
-        project_tile_mfma<D>(pv, qs, STRIDE, n_here, [](int) { return true; }, w32, unsure, []() {});
+        project_tile_mfma<D, F32>(pv, qs, qs + (F32 ? kSketchTile * STRIDE : 0), band_s, STRIDE, n_here, [](int) { return true; }, w32,
+                                  unsure, []() {}, [&](int rl) { return reinterpret_cast<const float *>(qbase + src_off[rl]); });
         __syncthreads();
         // the 32-bit halves of a vector's sketch words are contiguous in w32 and in the output
         uint32_t *out = reinterpret_cast<uint32_t *>(a.q_sketch + (size_t)v0 * W);
@@ -646,10 +654,15 @@ hipError_t launch_sketch_rows(const PrefillArgs &a, int n_seqs, hipStream_t st) 
     const int D = a.pool.head_dim;
 #define H1BKV_LAUNCH(DD, TT) hipLaunchKernelGGL((sketch_rows_kernel<DD, TT>), grid, dim3(kThreads), 0, st, a, n_seqs)
     if (D != 64 && D != 128) return hipErrorInvalidValue;      // see prefill_supported
-    if (a.f16 && a.proj_mfma) {
+    if (a.proj_mfma) {
         const dim3 fine((unsigned)(tiles < 6144 ? tiles : 6144));      // nothing stays resident: short workgroups
-        if (D == 64) hipLaunchKernelGGL((sketch_rows_mfma_kernel<64>), fine, dim3(kThreads), 0, st, a, n_seqs);
-        else hipLaunchKernelGGL((sketch_rows_mfma_kernel<128>), fine, dim3(kThreads), 0, st, a, n_seqs);
+        if (a.f16) {
+            if (D == 64) hipLaunchKernelGGL((sketch_rows_mfma_kernel<64, __half>), fine, dim3(kThreads), 0, st, a, n_seqs);
+            else hipLaunchKernelGGL((sketch_rows_mfma_kernel<128, __half>), fine, dim3(kThreads), 0, st, a, n_seqs);
+        } else {
+            if (D == 64) hipLaunchKernelGGL((sketch_rows_mfma_kernel<64, float>), fine, dim3(kThreads), 0, st, a, n_seqs);
+            else hipLaunchKernelGGL((sketch_rows_mfma_kernel<128, float>), fine, dim3(kThreads), 0, st, a, n_seqs);
+        }
     } else if (a.f16) {
         if (D == 64) H1BKV_LAUNCH(64, __half);
         else H1BKV_LAUNCH(128, __half);

@@ -5,6 +5,10 @@
 // pieces of R are made), so sign(y~) IS the chain's bit wherever |y~| exceeds that; the few bits inside the band are
 // recomputed with the chain itself.  fp16 subnormals in x enter the matrix cores as they are (kernels run with fp16
 // denormals enabled; a parity test feeds inputs in that range).
+// fp32 vectors take the same route after stage_f32_tile has scaled each by a power of two (the sign of the projection
+// and the chain's rounding are invariant under it) and split it into two fp16 pieces, x s ~ xh + 2^-12 xm: three MFMAs
+// per step instead of two (the product of the two low pieces is dropped and priced into guard32), and the chain reads
+// the original fp32 vector.
 #pragma once
 
 #include <hip/hip_fp16.h>
@@ -39,20 +43,74 @@ __device__ __forceinline__ void proj_load8(const __half *p, float *out) {
     }
 }
 
+// Splits a tile of fp32 vectors for project_tile_mfma<D, true>: row(v) -> the vector's address or nullptr.  Per vector
+//   s = 2^k with max |x| s in [2^12, 2^13)  (exact in fp32; fp16 pieces then neither overflow nor lose the large elements),
+//   xh = fp16(x s),  xm = fp16((x s - xh) 2^12)  (the difference is exact),  band = ||x s||_2 (1 + 2^-16).
+// A vector whose largest magnitude lies outside [2^-100, 2^100] (or is not finite) gets band = +inf: every one of its
+// bits then counts as uncertain and comes from the chain, whose own rounding is no longer purely relative out there.
+// Must be called by all 256 threads (shuffles); the caller's barrier publishes the tile.
+template <int D, typename Row>
+__device__ __forceinline__ void stage_f32_tile(Row row, int tile, __half *xh, __half *xm, int stride, float *band) {
+    constexpr int LPR = D / 8;                                 // lanes per vector, 8 elements each
+    const int tid = per_tile_index(threadIdx.x);
+    for (int e0 = 0; e0 < kProjTile * D; e0 += kProjThreads * 8) {
+        const int e = e0 + tid * 8, v = e / D, ch = e % D;
+        const float *src = v < tile ? row(v) : nullptr;
+        float x[8];
+        if (src) {
+            const float4 a = *reinterpret_cast<const float4 *>(src + ch), b = *reinterpret_cast<const float4 *>(src + ch + 4);
+            x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w; x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) x[i] = 0.0f;
+        }
+        uint32_t m = 0u;                                       // largest magnitude, compared as bits (non-negative floats order like integers)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) m = max(m, __float_as_uint(x[i]) & 0x7FFFFFFFu);
+#pragma unroll
+        for (int o = 1; o < LPR; o <<= 1) m = max(m, (uint32_t)__shfl_xor((int)m, o));
+        const int ex = (int)(m >> 23);                         // biased exponent of the largest element
+        const bool in_range = ex >= 27 && ex <= 227;           // 2^-100 .. 2^100 (also excludes inf and NaN)
+        const float sc = in_range ? __uint_as_float((uint32_t)(266 - ex) << 23) : (m == 0u ? 1.0f : 0.0f);
+        float ss = 0.0f;
+        uint32_t ph[4], pm[4];
+#pragma unroll
+        for (int i = 0; i < 8; i += 2) {
+            const float s0 = x[i] * sc, s1 = x[i + 1] * sc;
+            ss = fmaf(s0, s0, ss);
+            ss = fmaf(s1, s1, ss);
+            const __half h0 = __float2half_rn(s0), h1 = __float2half_rn(s1);
+            const __half m0 = __float2half_rn((s0 - __half2float(h0)) * 4096.0f), m1 = __float2half_rn((s1 - __half2float(h1)) * 4096.0f);
+            ph[i / 2] = (uint32_t)__half_as_ushort(h0) | ((uint32_t)__half_as_ushort(h1) << 16);
+            pm[i / 2] = (uint32_t)__half_as_ushort(m0) | ((uint32_t)__half_as_ushort(m1) << 16);
+        }
+#pragma unroll
+        for (int o = 1; o < LPR; o <<= 1) ss += __shfl_xor(ss, o);
+        if (v < tile) {
+            *reinterpret_cast<uint4 *>(xh + (size_t)v * stride + ch) = make_uint4(ph[0], ph[1], ph[2], ph[3]);
+            *reinterpret_cast<uint4 *>(xm + (size_t)v * stride + ch) = make_uint4(pm[0], pm[1], pm[2], pm[3]);
+            if (ch == 0) band[v] = (in_range || m == 0u) ? sqrtf(ss) * 1.0000153f : __uint_as_float(0x7F800000u);
+        }
+    }
+}
+
 // xs: the tile, row-major, `stride` halves per row (rows 16-byte aligned, stride a multiple of 8 and not of 64, so
 //     that 16-byte reads down a column spread over the LDS banks);  valid(v): whether row v holds a vector.
+// F32IN: the vectors are fp32 and were split by stage_f32_tile into xs (high pieces), xm (low pieces) and band (which
+//     this function otherwise computes itself); source(v) is the original vector for the chain.
 // w32, unsure: [kProjTile][16] 32-bit words in LDS, all zero on entry.  On return (after the caller's next barrier)
 //     w32[v][0 .. b/32) holds the packed sketch of vector v.  Must be called by all 256 threads; contains barriers.
 // between(): called once by every thread after the matrix-core phase, before the chain: the place to issue loads whose
 //     latency the (few, long) chains can hide without their registers being held through the matrix-core phase.
-template <int D, typename Valid, typename Between>
-__device__ __forceinline__ void project_tile_mfma(const PoolView &pv, const __half *xs, int stride, int tile, Valid valid,
-                                                  uint32_t *w32, uint32_t *unsure, Between between) {
+template <int D, bool F32IN, typename Valid, typename Between, typename Source>
+__device__ __forceinline__ void project_tile_mfma(const PoolView &pv, const __half *xs, const __half *xm, float *band_s, int stride,
+                                                  int tile, Valid valid, uint32_t *w32, uint32_t *unsure, Between between,
+                                                  Source source) {
     const int tid = per_tile_index(threadIdx.x), lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int n = lane & 15, kb = lane >> 4;
     const int n_tb = (tile + 15) / 16;
     const int n_bb = pv.sketch_bits / 16;                           // blocks of 16 sketch bits: wave, wave + 4, ...
-    __shared__ float band_s[kProjTile];
+    const float *guard = F32IN ? pv.guard + pv.sketch_bits : pv.guard;      // the fp32-input band follows the fp16-input one
     struct AOperands {
         uint4 hi[D / 32], mid[D / 32];
         float g[4];
@@ -65,13 +123,13 @@ __device__ __forceinline__ void project_tile_mfma(const PoolView &pv, const __ha
             A.mid[jb] = *reinterpret_cast<const uint4 *>(pv.R16mid + arow + 32 * jb);
         }
 #pragma unroll
-        for (int jj = 0; jj < 4; ++jj) A.g[jj] = pv.guard[16 * bb + 4 * kb + jj];
+        for (int jj = 0; jj < 4; ++jj) A.g[jj] = guard[16 * bb + 4 * kb + jj];
     };
     // the first block's pieces of R are requested before anything else: their latency runs behind the norms
     AOperands A;
     if (wave < n_bb) load_a(A, wave);
     // ---- 2-norm of every vector, once per tile: four threads per vector, 32 elements each ----
-    {
+    if constexpr (!F32IN) {
         const int v = tid >> 2, part = tid & 3;
         float ss = 0.0f;
         if (v < tile && valid(v)) {
@@ -98,6 +156,10 @@ __device__ __forceinline__ void project_tile_mfma(const PoolView &pv, const __ha
                 const proj_f16x8 Bx = *reinterpret_cast<const proj_f16x8 *>(xs + (size_t)v * stride + 32 * jb + 8 * kb);
                 yh = __builtin_amdgcn_mfma_f32_16x16x32_f16(*reinterpret_cast<const proj_f16x8 *>(&A.hi[jb]), Bx, yh, 0, 0, 0);
                 ym = __builtin_amdgcn_mfma_f32_16x16x32_f16(*reinterpret_cast<const proj_f16x8 *>(&A.mid[jb]), Bx, ym, 0, 0, 0);
+                if constexpr (F32IN) {
+                    const proj_f16x8 Bm = *reinterpret_cast<const proj_f16x8 *>(xm + (size_t)v * stride + 32 * jb + 8 * kb);
+                    ym = __builtin_amdgcn_mfma_f32_16x16x32_f16(*reinterpret_cast<const proj_f16x8 *>(&A.hi[jb]), Bm, ym, 0, 0, 0);
+                }
             }
             const float band = band_s[v];
             // element jj of this lane: bit 16 bb + 4 kb + jj of vector v
@@ -139,7 +201,13 @@ __device__ __forceinline__ void project_tile_mfma(const PoolView &pv, const __ha
 #pragma unroll
                 for (int q = 0; q < 8; q += 2) {
                     float kk[8];
-                    proj_load8(xs + (size_t)v * stride + j0 + 4 * q, kk);
+                    if constexpr (F32IN) {
+                        const float *xv = source(v) + j0 + 4 * q;
+                        const float4 a = *reinterpret_cast<const float4 *>(xv), b = *reinterpret_cast<const float4 *>(xv + 4);
+                        kk[0] = a.x; kk[1] = a.y; kk[2] = a.z; kk[3] = a.w; kk[4] = b.x; kk[5] = b.y; kk[6] = b.z; kk[7] = b.w;
+                    } else {
+                        proj_load8(xs + (size_t)v * stride + j0 + 4 * q, kk);
+                    }
                     y = __builtin_fmaf(rr[q].x, kk[0], y); y = __builtin_fmaf(rr[q].y, kk[1], y);
                     y = __builtin_fmaf(rr[q].z, kk[2], y); y = __builtin_fmaf(rr[q].w, kk[3], y);
                     y = __builtin_fmaf(rr[q + 1].x, kk[4], y); y = __builtin_fmaf(rr[q + 1].y, kk[5], y);

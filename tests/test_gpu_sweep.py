@@ -85,3 +85,34 @@ def test_sketch_bits_stay_exact_for_tiny_and_large_fp16_keys(scale):
     assert_cache_equal(cache2, oc, seqs, T)
     cache.close()
     cache2.close()
+
+
+@pytest.mark.parametrize("scale", [1.0, 1e-30, 1e30, 1e-37, 3e37])
+def test_sketch_bits_stay_exact_for_fp32_keys_of_any_magnitude(scale):
+    """fp32 keys reach the matrix cores scaled by a power of two and split into two fp16 pieces; magnitudes outside
+    2^-100 .. 2^100 (the last two scales) are sent to the chain wholesale.  Rows mix magnitudes over many orders, hold
+    exact zeros and one all-zero vector; the stored bits must be the chain's, and so must the query sketches of a
+    prefill over the same vectors."""
+    d, b, g, T = 128, 128, 32, 400
+    w = wl.Workload(f"f32_keys_{scale}", 2, 2, 2, d, T, b, g, "f32", seed=23)
+    R = wl.projection(b, d)
+    seqs = [0, 1]
+    rng = np.random.default_rng(4)
+    k = wl.kv_slab(w, "k", seqs, 0, T).astype(np.float64)
+    k *= 10.0 ** rng.uniform(-6, 0, size=k.shape)               # elements of one vector spread over six orders of magnitude
+    k[rng.random(k.shape) < 0.05] = 0.0
+    k[0, 7] = 0.0                                                # an all-zero vector (every projection is exactly 0)
+    k = (k * scale).astype(np.float32)
+    assert np.isfinite(k).all()
+    v = wl.kv_slab(w, "v", seqs, 0, T)
+    oc = cref.Cache(R, 2, 2, T, g)
+    oc.append(k, v)
+    cache = make_cache(w, R)
+    cache.append(seqs, to_dev(k), to_dev(v))
+    assert_cache_equal(cache, oc, seqs, T)
+    # the same vectors as queries of a prefill: their sketches sit at the head of the workspace
+    cache.prefill(seqs, to_dev(k), 0.1)
+    n_words = 2 * T * w.n_q_heads * (b // 64)
+    got = cache.workspace[: n_words * 8].cpu().numpy().view(np.uint64).reshape(2, T, w.n_q_heads, b // 64)
+    assert np.array_equal(got, cref.sketch(R, k))
+    cache.close()

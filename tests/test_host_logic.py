@@ -37,14 +37,14 @@ def test_bad_geometry_is_rejected(bad):
 
 def test_pool_bytes_formula():
     """sketch + nibbles + fp16 scale/zero per record (Sec. IV-B: a b-bit sketch and d 4-bit values per token),
-    plus R, its transpose, its two fp16 pieces with the per-row guard band, and the block table, each rounded up to
-    256 bytes."""
+    plus R, its transpose, its two fp16 pieces with the per-row guard bands (one for fp16, one for fp32 inputs), and the
+    block table, each rounded up to 256 bytes."""
     for w in (wl.WORKLOADS["tiny"], wl.WORKLOADS["decode_b16_32k"], wl.WORKLOADS["decode_gqa_128k"]):
         c = cfg(n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim, sketch_bits=w.sketch_bits,
                 group_size=w.group_size, max_seqs=3, max_pages=7, max_pages_per_seq=5)
         al = lambda x: (x + 255) // 256 * 256
         rec = 7 * w.n_kv_heads * 256
-        want = (2 * al(w.sketch_bits * w.head_dim * 4) + 2 * al(w.sketch_bits * w.head_dim * 2) + al(w.sketch_bits * 4)
+        want = (2 * al(w.sketch_bits * w.head_dim * 4) + 2 * al(w.sketch_bits * w.head_dim * 2) + al(2 * w.sketch_bits * 4)
                 + al(3 * 5 * 4) + al(rec * w.sketch_bits // 8)
                 + al(rec * w.head_dim // 2) + al(rec * w.n_groups * 4))
         assert B.h1bkv_pool_bytes(c) == want
