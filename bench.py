@@ -178,9 +178,9 @@ def bench_append(args, torch, B, wl, w, workers):
     elt = 2 if w.dtype == "f16" else 4
     bytes_moved = records * (2 * w.head_dim * elt + w.record_bytes)
     chain_tflops = flops / (kernel_ms * 1e-3) / 1e12
-    # fp16 keys take the matrix-core projection: the fp32 chain's vector-ALU roof no longer binds the kernel, what is left
-    # is moving the inputs and records (and per-tile latencies), so it is priced against HBM.  fp32 keys keep the chain.
-    mfma_path = w.dtype == "f16"
+    # With the matrix-core projection the fp32 chain's vector-ALU roof no longer binds the kernel; what is left is moving the
+    # inputs and records (and per-tile latencies), so it is priced against HBM.  (fp32 keys at head_dim 256 keep the chain.)
+    mfma_path = w.dtype == "f16" or w.head_dim <= 128
     hbm_gbps = bytes_moved / (kernel_ms * 1e-3) / 1e9
     roof = ({"bound": "hbm", "kernel": "append_kernel", "achieved": hbm_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
              "frac": hbm_gbps / HBM_PEAK_GBPS, "traffic": None, "kernel_ms": kernel_ms, "algorithmic_bytes_per_launch": bytes_moved,
