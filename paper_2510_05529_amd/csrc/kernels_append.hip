@@ -64,7 +64,9 @@ __device__ __forceinline__ void copy8(const float *src, float *dst) {
 // the sequence's tiles -- blockIdx.x, blockIdx.y, gridDim.x when the kernel does nothing else.
 // MF: the projections come from the matrix cores and only the bits inside the guard band are recomputed with the
 // chain; see the projection block below (fp32 keys are scaled and split into two fp16 pieces while they are staged).
-template <int D, typename T, bool MF>
+// ONE: the call appends one token per sequence (a decode step) -- a compile-time choice, because a run-time branch
+// around the two ways of loading the projection row doubled the time of the prefill-sized launches.
+template <int D, typename T, bool MF, bool ONE>
 __device__ __forceinline__ void append_body(const AppendArgs &a, const BatchDesc &desc, int tile, int bx, int by, int gx) {
     constexpr bool F32MF = MF && sizeof(T) == 4;              // matrix-core projection of fp32 keys: two fp16 piece tiles
     using KT = typename std::conditional<F32MF, __half, T>::type;
@@ -96,7 +98,7 @@ __device__ __forceinline__ void append_body(const AppendArgs &a, const BatchDesc
     [[maybe_unused]] int r_word = wave % wslots;
     [[maybe_unused]] auto load_row = [&](int word) {
         if constexpr (!MF) {
-            if (a.n_new == 1) {
+            if constexpr (ONE) {
                 // a decode step's append: a workgroup sketches a handful of records, so the row is read once and the
                 // read should be cheap -- from R^T a wave's load of element j is one 256-byte run (from R the 64 lanes
                 // read 64 different rows)
@@ -313,9 +315,9 @@ __device__ __forceinline__ void append_body(const AppendArgs &a, const BatchDesc
     }
 }
 
-template <int D, typename T, bool MF>
+template <int D, typename T, bool MF, bool ONE = false>
 __global__ __launch_bounds__(kThreads, MF ? 4 : 1) void append_kernel(AppendArgs a, BatchDesc desc, int tile) {
-    append_body<D, T, MF>(a, desc, tile, blockIdx.x, blockIdx.y, gridDim.x);
+    append_body<D, T, MF, ONE>(a, desc, tile, blockIdx.x, blockIdx.y, gridDim.x);
 }
 
 // Prologue of a fused decode step: rows [0, n_seqs) of the grid append the step's new token of each sequence,
@@ -325,7 +327,7 @@ __global__ __launch_bounds__(kThreads, MF ? 4 : 1) void append_kernel(AppendArgs
 template <int D, typename T>
 __global__ __launch_bounds__(kThreads) void step_prologue_kernel(AppendArgs a, BatchDesc desc, int tile, int n_seqs, QueryArgs qa) {
     if ((int)blockIdx.y < n_seqs) {
-        append_body<D, T, false>(a, desc, tile, blockIdx.x, blockIdx.y, gridDim.x);
+        append_body<D, T, false, true>(a, desc, tile, blockIdx.x, blockIdx.y, gridDim.x);
         return;
     }
     __shared__ float qs[4][D];
@@ -361,6 +363,7 @@ __global__ __launch_bounds__(kThreads) void step_prologue_kernel(AppendArgs a, B
 
 // With qa != nullptr the launch also sketches qa->n_vec query vectors (fused decode-step prologue).
 hipError_t launch_append(const AppendArgs &a, const BatchDesc &desc, int n_seqs, const QueryArgs *qa, hipStream_t st) {
+    if (qa && a.n_new != 1) return hipErrorInvalidValue;   // the fused prologue is a decode step's: one token per sequence
     // Slots per head: the new tokens plus the padding down to / up to 8-token boundaries.
     int max_off = 0;
     for (int i = 0; i < n_seqs; ++i) max_off = desc.s[i].pos % 8 > max_off ? desc.s[i].pos % 8 : max_off;
@@ -390,6 +393,7 @@ hipError_t launch_append(const AppendArgs &a, const BatchDesc &desc, int n_seqs,
 #define H1BKV_LAUNCH(DD, TT)                                                                                        \
     do {                                                                                                            \
         if (qa) hipLaunchKernelGGL((step_prologue_kernel<DD, TT>), grid, dim3(kThreads), 0, st, a, desc, (int)tile, n_seqs, qargs); \
+        else if (a.n_new == 1) hipLaunchKernelGGL((append_kernel<DD, TT, false, true>), grid, dim3(kThreads), 0, st, a, desc, (int)tile); \
         else hipLaunchKernelGGL((append_kernel<DD, TT, false>), grid, dim3(kThreads), 0, st, a, desc, (int)tile);   \
     } while (0)
     if (a.f16 && a.proj_mfma && !qa) {
