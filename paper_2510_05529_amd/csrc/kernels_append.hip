@@ -66,7 +66,8 @@ __device__ __forceinline__ void copy8(const float *src, float *dst) {
 // chain; see the projection block below (fp32 keys are scaled and split into two fp16 pieces while they are staged).
 // ONE: the call appends one token per sequence (a decode step) -- a compile-time choice, because a run-time branch
 // around the two ways of loading the projection row doubled the time of the prefill-sized launches.
-template <int D, typename T, bool MF, bool ONE>
+// RES (with MF): the pieces of R stay in registers and the guard-band bits are recomputed in batches.
+template <int D, typename T, bool MF, bool ONE, bool RES = false>
 __device__ __forceinline__ void append_body(const AppendArgs &a, const BatchDesc &desc, int tile, int bx, int by, int gx) {
     constexpr bool F32MF = MF && sizeof(T) == 4;              // matrix-core projection of fp32 keys: two fp16 piece tiles
     using KT = typename std::conditional<F32MF, __half, T>::type;
@@ -75,6 +76,8 @@ __device__ __forceinline__ void append_body(const AppendArgs &a, const BatchDesc
     __shared__ __attribute__((aligned(16))) KT ks[F32MF ? 2 * kTile : kTile][D + KPAD];
     __shared__ float band_s[MF ? kTile : 1];          // matrix-core path: guard band norm of each key
     __shared__ uint32_t unsure[MF ? kTile : 1][16];   // matrix-core path: per token, the sketch bits that need the chain
+    __shared__ typename std::conditional<RES, ProjFixList, int>::type fixes;
+    static_assert(MF || !RES, "resident pieces of R belong to the matrix-core path");
     static_assert(kTile == kProjTile && kThreads == kProjThreads, "projection_mfma.h assumes this tile shape");
     __shared__ uint64_t words[kTile][8];              // sketch words of the tile (W <= 8)
     __shared__ size_t dst[kTile];                     // plane index of each slot: (page * H_kv + head) * 256 + slot in page
@@ -116,10 +119,27 @@ __device__ __forceinline__ void append_body(const AppendArgs &a, const BatchDesc
         }
     };
     load_row(r_word);
+    [[maybe_unused]] ProjResident<D> res;
+    if constexpr (RES) {
+        load_resident<D, F32MF>(pv, res);
+        if (tid == 0) fixes.n = 0;
+    }
 
-    for (int slot0 = bx * tile; slot0 < n_slots; slot0 += gx * tile) {
+    for (int slot0 = bx * tile;; slot0 += gx * tile) {
         const int tid = per_tile_index(threadIdx.x);   // shadows the outer one: see per_tile_index
         __syncthreads();   // previous pass is done with the LDS tile
+        const bool more = slot0 < n_slots;
+        if constexpr (RES) {
+            // the list of guard-band words is drained when it is half full and after the last tile (the stores of the
+            // listed words precede the barrier above)
+            const int pending = fixes.n;
+            if (pending > 0 && (!more || pending >= kProjFixCap / 2)) {
+                drain_fixes<D, T>(pv, fixes);
+                __syncthreads();
+                if (tid == 0) fixes.n = 0;             // (the barriers below come before the next entries)
+            }
+        }
+        if (!more) break;
         // ---- resolve the tile once: slot -> (head, token) -> source row, destination record ----
         // (the divisions by the runtime slot count per head are done here, by one thread per slot, not in the loops)
         if constexpr (MF) {                            // the sketch words are assembled with atomic ORs: start from zero
@@ -182,10 +202,17 @@ __device__ __forceinline__ void append_body(const AppendArgs &a, const BatchDesc
             auto between = [&]() {
                 if constexpr (kPrefetchV) prefetch_values();
             };
-            project_tile_mfma<D, F32MF>(pv, reinterpret_cast<const __half *>(&ks[0][0]),
-                                        reinterpret_cast<const __half *>(&ks[F32MF ? kTile : 0][0]), band_s, D + KPAD, tile, valid_slot,
-                                        reinterpret_cast<uint32_t *>(&words[0][0]), &unsure[0][0], between,
-                                        [&](int rl) { return reinterpret_cast<const float *>(kbase + src_off[rl]); });
+            if constexpr (RES)
+                project_tile_resident<D, F32MF>(
+                    pv, res, reinterpret_cast<const __half *>(&ks[0][0]), reinterpret_cast<const __half *>(&ks[F32MF ? kTile : 0][0]), band_s,
+                    D + KPAD, tile, valid_slot, reinterpret_cast<uint32_t *>(&words[0][0]), &unsure[0][0], between,
+                    [&](int rl) { return static_cast<const void *>(kbase + src_off[rl]); },
+                    [&](int rl) { return reinterpret_cast<uint32_t *>(pv.sketch + dst[rl] * W); }, fixes);
+            else
+                project_tile_mfma<D, F32MF>(pv, reinterpret_cast<const __half *>(&ks[0][0]),
+                                            reinterpret_cast<const __half *>(&ks[F32MF ? kTile : 0][0]), band_s, D + KPAD, tile, valid_slot,
+                                            reinterpret_cast<uint32_t *>(&words[0][0]), &unsure[0][0], between,
+                                            [&](int rl) { return reinterpret_cast<const float *>(kbase + src_off[rl]); });
         } else
         // ---- Eq.(2): lane = sketch bit; y = fma chain over j; ballot = packed word ----
         for (int word = wave % wslots; word < W; word += wslots) {
@@ -315,9 +342,9 @@ __device__ __forceinline__ void append_body(const AppendArgs &a, const BatchDesc
     }
 }
 
-template <int D, typename T, bool MF, bool ONE = false>
-__global__ __launch_bounds__(kThreads, MF ? 4 : 1) void append_kernel(AppendArgs a, BatchDesc desc, int tile) {
-    append_body<D, T, MF, ONE>(a, desc, tile, blockIdx.x, blockIdx.y, gridDim.x);
+template <int D, typename T, bool MF, bool ONE = false, bool RES = false>
+__global__ __launch_bounds__(kThreads, MF ? (RES ? 3 : 4) : 1) void append_kernel(AppendArgs a, BatchDesc desc, int tile) {
+    append_body<D, T, MF, ONE, RES>(a, desc, tile, blockIdx.x, blockIdx.y, gridDim.x);
 }
 
 // Prologue of a fused decode step: rows [0, n_seqs) of the grid append the step's new token of each sequence,
@@ -377,8 +404,12 @@ hipError_t launch_append(const AppendArgs &a, const BatchDesc &desc, int n_seqs,
     const long tiles = (n_slots + tile - 1) / tile;
     // Each workgroup reads its rows of R once and keeps them in registers: with many tiles, a few resident
     // workgroups per compute unit walk all of them.
-    // (the matrix-core path keeps nothing resident: more, shorter workgroups even out the tail of the launch)
-    const long wg_budget = a.proj_mfma && !qa ? 6144 : 1024;
+    // (the matrix-core path with streamed pieces of R keeps nothing resident: more, shorter workgroups even out the tail)
+    const int D = a.pool.head_dim;
+    const bool fits = D == 64 ? proj_resident_fits<64>(a.pool.sketch_bits)
+                              : D == 128 ? proj_resident_fits<128>(a.pool.sketch_bits) : proj_resident_fits<256>(a.pool.sketch_bits);
+    // (resident pieces: three long-lived workgroups per compute unit, all in one round)
+    const long wg_budget = a.proj_mfma && !qa ? (fits ? 768 : 6144) : 1024;
     const long max_wgs_x = wg_budget / n_seqs > 0 ? wg_budget / n_seqs : 1;
     const unsigned gx = (unsigned)(tiles < max_wgs_x ? tiles : max_wgs_x);
     unsigned q_rows = 0;
@@ -388,7 +419,6 @@ hipError_t launch_append(const AppendArgs &a, const BatchDesc &desc, int n_seqs,
         q_rows = (q_blocks + gx - 1) / gx;
     }
     const dim3 grid(gx, (unsigned)n_seqs + q_rows);
-    const int D = a.pool.head_dim;
     const QueryArgs qargs = qa ? *qa : QueryArgs{nullptr, nullptr, 0};
 #define H1BKV_LAUNCH(DD, TT)                                                                                        \
     do {                                                                                                            \
@@ -396,13 +426,18 @@ hipError_t launch_append(const AppendArgs &a, const BatchDesc &desc, int n_seqs,
         else if (a.n_new == 1) hipLaunchKernelGGL((append_kernel<DD, TT, false, true>), grid, dim3(kThreads), 0, st, a, desc, (int)tile); \
         else hipLaunchKernelGGL((append_kernel<DD, TT, false>), grid, dim3(kThreads), 0, st, a, desc, (int)tile);   \
     } while (0)
+#define H1BKV_LAUNCH_MF(DD, TT)                                                                                                \
+    do {                                                                                                                       \
+        if (fits) hipLaunchKernelGGL((append_kernel<DD, TT, true, false, true>), grid, dim3(kThreads), 0, st, a, desc, (int)tile); \
+        else hipLaunchKernelGGL((append_kernel<DD, TT, true>), grid, dim3(kThreads), 0, st, a, desc, (int)tile);              \
+    } while (0)
     if (a.f16 && a.proj_mfma && !qa) {
-        if (D == 64) hipLaunchKernelGGL((append_kernel<64, __half, true>), grid, dim3(kThreads), 0, st, a, desc, (int)tile);
-        else if (D == 128) hipLaunchKernelGGL((append_kernel<128, __half, true>), grid, dim3(kThreads), 0, st, a, desc, (int)tile);
-        else hipLaunchKernelGGL((append_kernel<256, __half, true>), grid, dim3(kThreads), 0, st, a, desc, (int)tile);
+        if (D == 64) H1BKV_LAUNCH_MF(64, __half);
+        else if (D == 128) H1BKV_LAUNCH_MF(128, __half);
+        else H1BKV_LAUNCH_MF(256, __half);
     } else if (a.proj_mfma && !qa && D <= 128) {      // fp32 keys (d = 256: two piece tiles would not leave room for a second workgroup)
-        if (D == 64) hipLaunchKernelGGL((append_kernel<64, float, true>), grid, dim3(kThreads), 0, st, a, desc, (int)tile);
-        else hipLaunchKernelGGL((append_kernel<128, float, true>), grid, dim3(kThreads), 0, st, a, desc, (int)tile);
+        if (D == 64) H1BKV_LAUNCH_MF(64, float);
+        else H1BKV_LAUNCH_MF(128, float);
     } else if (a.f16) {
         if (D == 64) H1BKV_LAUNCH(64, __half);
         else if (D == 128) H1BKV_LAUNCH(128, __half);
@@ -413,6 +448,7 @@ hipError_t launch_append(const AppendArgs &a, const BatchDesc &desc, int n_seqs,
         else H1BKV_LAUNCH(256, float);
     }
 #undef H1BKV_LAUNCH
+#undef H1BKV_LAUNCH_MF
     return hipGetLastError();
 }
 

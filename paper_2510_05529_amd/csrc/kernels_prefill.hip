@@ -506,7 +506,8 @@ __device__ __forceinline__ void copy8f(const float *src, float *dst) {
     *reinterpret_cast<float4 *>(dst + 4) = *reinterpret_cast<const float4 *>(src + 4);
 }
 
-// fp16 queries: the projections on the matrix cores, the bits inside the guard band by the chain (projection_mfma.h).
+// The projections on the matrix cores, the bits inside the guard band by the chain (projection_mfma.h); the pieces of R
+// are read per tile (any sketch width).
 template <int D, typename T>
 __global__ __launch_bounds__(kThreads, 4) void sketch_rows_mfma_kernel(PrefillArgs a, int n_seqs) {
     constexpr bool F32 = sizeof(T) == 4;                           // fp32 queries: scaled and split into two fp16 piece tiles
@@ -551,6 +552,115 @@ __global__ __launch_bounds__(kThreads, 4) void sketch_rows_mfma_kernel(PrefillAr
         uint32_t *out = reinterpret_cast<uint32_t *>(a.q_sketch + (size_t)v0 * W);
         for (int e = tid; e < n_here * 2 * W; e += kThreads) out[e] = w32[(e / (2 * W)) * 16 + e % (2 * W)];
     }
+}
+
+// The same with the pieces of R resident in registers (sketches of at most 64 * 256 / D bits): three long-lived workgroups
+// per compute unit walk the tiles; the guard-band bits are recomputed in batches; and the next tile's fp16 vectors are
+// requested into registers before the current tile's matrix-core phase, so that the stream from memory does not stop
+// while the workgroup computes.
+template <int D, typename T>
+__global__ __launch_bounds__(kThreads, 3) void sketch_rows_resident_kernel(PrefillArgs a, int n_seqs) {
+    constexpr bool F32 = sizeof(T) == 4;
+    constexpr int STRIDE = D + 8;
+    constexpr int PF = F32 ? 1 : kSketchTile * D / (kThreads * 8);  // 16-byte loads per thread and tile (fp16 vectors)
+    __shared__ __attribute__((aligned(16))) __half qs[(F32 ? 2 : 1) * kSketchTile * STRIDE];
+    __shared__ size_t src_off[2][kSketchTile];                     // this tile's and the next one's
+    __shared__ uint32_t w32[kSketchTile * 16], unsure[kSketchTile * 16];
+    __shared__ float band_s[kSketchTile];
+    __shared__ ProjFixList fixes;
+    const int tid = threadIdx.x;
+    const PoolView &pv = a.pool;
+    const int W = pv.sketch_bits >> 6, Hq = pv.n_q_heads;
+    const long n_vec = (long)n_seqs * a.n_q * Hq, step = (long)gridDim.x * kSketchTile;
+    const T *qbase = static_cast<const T *>(a.q);
+    auto resolve = [&](long v0, int buf) {
+        if (tid < kSketchTile && v0 + tid < n_vec) {
+            const long v = v0 + tid;
+            long s, rem;
+            if (n_vec <= 0x7FFFFFFFL) {             // (uniform) 32-bit division: a fraction of the 64-bit one's instructions
+                const uint32_t per_seq = (uint32_t)a.n_q * (uint32_t)Hq;
+                s = (uint32_t)v / per_seq;
+                rem = (uint32_t)v % per_seq;
+            } else {
+                s = v / ((long)a.n_q * Hq);
+                rem = v % ((long)a.n_q * Hq);
+            }
+            src_off[buf][tid] = (size_t)s * a.stride_seq + (size_t)((uint32_t)rem / (uint32_t)Hq) * a.stride_tok +
+                                (size_t)((uint32_t)rem % (uint32_t)Hq) * a.stride_head;
+        }
+    };
+    // this thread's part of a tile: 16-byte piece k is elements [pre_ch, pre_ch + 8) of row pre_row + k * (kThreads * 8 / D)
+    const int pre_row = tid * 8 / D, pre_ch = tid * 8 % D;
+    // (four named registers, not an array: the array form stayed in scratch memory)
+    [[maybe_unused]] uint4 pre0, pre1, pre2, pre3;
+    static_assert(PF <= 4, "one register set per 16-byte piece");
+    // rows past the end of the input repeat the last one: no branch around a load (the compiler makes every load behind a
+    // branch wait for the ones before it)
+#define H1BKV_REQUEST_ONE(K, REG, V0, BUF)                                                                              \
+    if constexpr (K < PF) {                                                                                             \
+        const int last = (int)min((long)kSketchTile, n_vec - (V0)) - 1, rl = pre_row + K * (kThreads * 8 / D);          \
+        REG = *reinterpret_cast<const uint4 *>(qbase + src_off[BUF][rl < last ? rl : last] + pre_ch);                   \
+    }
+#define H1BKV_REQUEST(V0, BUF)                                                                                          \
+    do {                                                                                                                \
+        H1BKV_REQUEST_ONE(0, pre0, V0, BUF) H1BKV_REQUEST_ONE(1, pre1, V0, BUF) H1BKV_REQUEST_ONE(2, pre2, V0, BUF)     \
+        H1BKV_REQUEST_ONE(3, pre3, V0, BUF)                                                                             \
+    } while (0)
+#define H1BKV_DEPOSIT_ONE(K, REG)                                                                                       \
+    if constexpr (K < PF) {                                                                                             \
+        const int rl = pre_row + K * (kThreads * 8 / D);                                                                \
+        if (rl < n_here) *reinterpret_cast<uint4 *>(&qs[rl * STRIDE + pre_ch]) = REG;                                   \
+    }
+    ProjResident<D> res;
+    load_resident<D, F32>(pv, res);
+    if (tid == 0) fixes.n = 0;
+    long v0 = (long)blockIdx.x * kSketchTile;
+    if (v0 < n_vec) resolve(v0, 0);
+    __syncthreads();
+    if constexpr (!F32) {
+        if (v0 < n_vec) H1BKV_REQUEST(v0, 0);
+    }
+    for (int buf = 0;; v0 += step, buf ^= 1) {
+        __syncthreads();
+        const bool more = v0 < n_vec;
+        // the list of guard-band words is drained when it is half full and after the last tile (the stores of the listed
+        // words precede the barrier above)
+        const int pending = fixes.n;
+        if (pending > 0 && (!more || pending >= kProjFixCap / 2)) {
+            drain_fixes<D, T>(pv, fixes);
+            __syncthreads();
+            if (tid == 0) fixes.n = 0;          // (the barriers below come before the next entries)
+        }
+        if (!more) break;
+        const int n_here = (int)min((long)kSketchTile, n_vec - v0);
+        for (int e = tid; e < kSketchTile * 16; e += kThreads) {
+            w32[e] = 0u;
+            unsure[e] = 0u;
+        }
+        if constexpr (!F32) {
+            H1BKV_DEPOSIT_ONE(0, pre0) H1BKV_DEPOSIT_ONE(1, pre1) H1BKV_DEPOSIT_ONE(2, pre2) H1BKV_DEPOSIT_ONE(3, pre3)
+        }
+        const bool next = v0 + step < n_vec;
+        if (next) resolve(v0 + step, buf ^ 1);
+        __syncthreads();
+        if constexpr (F32) {
+            stage_f32_tile<D>([&](int rl) { return reinterpret_cast<const float *>(qbase + src_off[buf][rl]); }, n_here, qs,
+                              qs + kSketchTile * STRIDE, STRIDE, band_s);
+        } else {
+            if (next) H1BKV_REQUEST(v0 + step, buf ^ 1);
+        }
+        project_tile_resident<D, F32>(
+            pv, res, qs, qs + (F32 ? kSketchTile * STRIDE : 0), band_s, STRIDE, n_here, [](int) { return true; }, w32, unsure, []() {},
+            [&](int rl) { return static_cast<const void *>(qbase + src_off[buf][rl]); },
+            [&](int rl) { return reinterpret_cast<uint32_t *>(a.q_sketch + (size_t)(v0 + rl) * W); }, fixes);
+        __syncthreads();
+        // the 32-bit halves of a vector's sketch words are contiguous in w32 and in the output
+        uint32_t *out = reinterpret_cast<uint32_t *>(a.q_sketch + (size_t)v0 * W);
+        for (int e = tid; e < n_here * 2 * W; e += kThreads) out[e] = w32[(e / (2 * W)) * 16 + e % (2 * W)];
+    }
+#undef H1BKV_REQUEST
+#undef H1BKV_REQUEST_ONE
+#undef H1BKV_DEPOSIT_ONE
 }
 
 template <int D, typename T>
@@ -656,13 +766,21 @@ hipError_t launch_sketch_rows(const PrefillArgs &a, int n_seqs, hipStream_t st) 
     if (D != 64 && D != 128) return hipErrorInvalidValue;      // see prefill_supported
     if (a.proj_mfma) {
         const dim3 fine((unsigned)(tiles < 6144 ? tiles : 6144));      // nothing stays resident: short workgroups
+        const dim3 res((unsigned)(tiles < 768 ? tiles : 768));         // resident pieces of R: three long-lived workgroups per compute unit
+        const bool fits = D == 64 ? proj_resident_fits<64>(a.pool.sketch_bits) : proj_resident_fits<128>(a.pool.sketch_bits);
+#define H1BKV_LAUNCH_MF(DD, TT)                                                                                              \
+    do {                                                                                                                     \
+        if (fits) hipLaunchKernelGGL((sketch_rows_resident_kernel<DD, TT>), res, dim3(kThreads), 0, st, a, n_seqs);          \
+        else hipLaunchKernelGGL((sketch_rows_mfma_kernel<DD, TT>), fine, dim3(kThreads), 0, st, a, n_seqs);                  \
+    } while (0)
         if (a.f16) {
-            if (D == 64) hipLaunchKernelGGL((sketch_rows_mfma_kernel<64, __half>), fine, dim3(kThreads), 0, st, a, n_seqs);
-            else hipLaunchKernelGGL((sketch_rows_mfma_kernel<128, __half>), fine, dim3(kThreads), 0, st, a, n_seqs);
+            if (D == 64) H1BKV_LAUNCH_MF(64, __half);
+            else H1BKV_LAUNCH_MF(128, __half);
         } else {
-            if (D == 64) hipLaunchKernelGGL((sketch_rows_mfma_kernel<64, float>), fine, dim3(kThreads), 0, st, a, n_seqs);
-            else hipLaunchKernelGGL((sketch_rows_mfma_kernel<128, float>), fine, dim3(kThreads), 0, st, a, n_seqs);
+            if (D == 64) H1BKV_LAUNCH_MF(64, float);
+            else H1BKV_LAUNCH_MF(128, float);
         }
+#undef H1BKV_LAUNCH_MF
     } else if (a.f16) {
         if (D == 64) H1BKV_LAUNCH(64, __half);
         else H1BKV_LAUNCH(128, __half);
