@@ -66,8 +66,11 @@ __device__ __forceinline__ void copy8(const float *src, float *dst) {
 // chain; see the projection block below (fp32 keys are scaled and split into two fp16 pieces while they are staged).
 // ONE: the call appends one token per sequence (a decode step) -- a compile-time choice, because a run-time branch
 // around the two ways of loading the projection row doubled the time of the prefill-sized launches.
-// RES (with MF): the pieces of R stay in registers and the guard-band bits are recomputed in batches.
-template <int D, typename T, bool MF, bool ONE, bool RES = false>
+// PART: kBoth, or only the keys' half (sketches) or the values' half (codes, scale/zero) of the work -- large appends run
+// the halves as two launches: the keys' workgroups are few, long-lived and heavy in registers, the values' half is a plain
+// stream that wants many light ones.
+enum AppendPart { kBoth = 0, kKeys = 1, kValues = 2 };
+template <int D, typename T, bool MF, bool ONE, AppendPart PART = kBoth>
 __device__ __forceinline__ void append_body(const AppendArgs &a, const BatchDesc &desc, int tile, int bx, int by, int gx) {
     constexpr bool F32MF = MF && sizeof(T) == 4;              // matrix-core projection of fp32 keys: two fp16 piece tiles
     using KT = typename std::conditional<F32MF, __half, T>::type;
@@ -76,8 +79,6 @@ __device__ __forceinline__ void append_body(const AppendArgs &a, const BatchDesc
     __shared__ __attribute__((aligned(16))) KT ks[F32MF ? 2 * kTile : kTile][D + KPAD];
     __shared__ float band_s[MF ? kTile : 1];          // matrix-core path: guard band norm of each key
     __shared__ uint32_t unsure[MF ? kTile : 1][16];   // matrix-core path: per token, the sketch bits that need the chain
-    __shared__ typename std::conditional<RES, ProjFixList, int>::type fixes;
-    static_assert(MF || !RES, "resident pieces of R belong to the matrix-core path");
     static_assert(kTile == kProjTile && kThreads == kProjThreads, "projection_mfma.h assumes this tile shape");
     __shared__ uint64_t words[kTile][8];              // sketch words of the tile (W <= 8)
     __shared__ size_t dst[kTile];                     // plane index of each slot: (page * H_kv + head) * 256 + slot in page
@@ -100,7 +101,7 @@ __device__ __forceinline__ void append_body(const AppendArgs &a, const BatchDesc
     [[maybe_unused]] float r[MF ? 1 : D];
     [[maybe_unused]] int r_word = wave % wslots;
     [[maybe_unused]] auto load_row = [&](int word) {
-        if constexpr (!MF) {
+        if constexpr (!MF && PART != kValues) {
             if constexpr (ONE) {
                 // a decode step's append: a workgroup sketches a handful of records, so the row is read once and the
                 // read should be cheap -- from R^T a wave's load of element j is one 256-byte run (from R the 64 lanes
@@ -119,27 +120,10 @@ __device__ __forceinline__ void append_body(const AppendArgs &a, const BatchDesc
         }
     };
     load_row(r_word);
-    [[maybe_unused]] ProjResident<D> res;
-    if constexpr (RES) {
-        load_resident<D, F32MF>(pv, res);
-        if (tid == 0) fixes.n = 0;
-    }
 
-    for (int slot0 = bx * tile;; slot0 += gx * tile) {
+    for (int slot0 = bx * tile; slot0 < n_slots; slot0 += gx * tile) {
         const int tid = per_tile_index(threadIdx.x);   // shadows the outer one: see per_tile_index
         __syncthreads();   // previous pass is done with the LDS tile
-        const bool more = slot0 < n_slots;
-        if constexpr (RES) {
-            // the list of guard-band words is drained when it is half full and after the last tile (the stores of the
-            // listed words precede the barrier above)
-            const int pending = fixes.n;
-            if (pending > 0 && (!more || pending >= kProjFixCap / 2)) {
-                drain_fixes<D, T>(pv, fixes);
-                __syncthreads();
-                if (tid == 0) fixes.n = 0;             // (the barriers below come before the next entries)
-            }
-        }
-        if (!more) break;
         // ---- resolve the tile once: slot -> (head, token) -> source row, destination record ----
         // (the divisions by the runtime slot count per head are done here, by one thread per slot, not in the loops)
         if constexpr (MF) {                            // the sketch words are assembled with atomic ORs: start from zero
@@ -182,10 +166,11 @@ __device__ __forceinline__ void append_body(const AppendArgs &a, const BatchDesc
         };
         // chain path: now; matrix-core path: after its MFMA phase (held through it, the 16 registers spill, and a
         // spill reload waits for every load in flight)
-        if constexpr (kPrefetchV && !MF) prefetch_values();
+        if constexpr (kPrefetchV && !MF && PART != kKeys) prefetch_values();
 
         // ---- stage the key tile ----
-        if constexpr (F32MF) {
+        if constexpr (PART == kValues) {
+        } else if constexpr (F32MF) {
             stage_f32_tile<D>([&](int rl) { return valid_slot(rl) ? kbase + src_off[rl] : nullptr; }, tile, &ks[0][0], &ks[kTile][0],
                               D + KPAD, band_s);
         } else {
@@ -197,22 +182,16 @@ __device__ __forceinline__ void append_body(const AppendArgs &a, const BatchDesc
         if (tid < tile) dst[tid] = ((size_t)my_page * H + my_head) * kPage + (my_pos % kPage);
         __syncthreads();
 
-        if constexpr (MF) {
+        if constexpr (PART == kValues) {
+        } else if constexpr (MF) {
             // ---- Eq.(2) on the matrix cores; the bits inside the guard band by the chain (projection_mfma.h) ----
             auto between = [&]() {
-                if constexpr (kPrefetchV) prefetch_values();
+                if constexpr (kPrefetchV && PART != kKeys) prefetch_values();
             };
-            if constexpr (RES)
-                project_tile_resident<D, F32MF>(
-                    pv, res, reinterpret_cast<const __half *>(&ks[0][0]), reinterpret_cast<const __half *>(&ks[F32MF ? kTile : 0][0]), band_s,
-                    D + KPAD, tile, valid_slot, reinterpret_cast<uint32_t *>(&words[0][0]), &unsure[0][0], between,
-                    [&](int rl) { return static_cast<const void *>(kbase + src_off[rl]); },
-                    [&](int rl) { return reinterpret_cast<uint32_t *>(pv.sketch + dst[rl] * W); }, fixes);
-            else
-                project_tile_mfma<D, F32MF>(pv, reinterpret_cast<const __half *>(&ks[0][0]),
-                                            reinterpret_cast<const __half *>(&ks[F32MF ? kTile : 0][0]), band_s, D + KPAD, tile, valid_slot,
-                                            reinterpret_cast<uint32_t *>(&words[0][0]), &unsure[0][0], between,
-                                            [&](int rl) { return reinterpret_cast<const float *>(kbase + src_off[rl]); });
+            project_tile_mfma<D, F32MF>(pv, reinterpret_cast<const __half *>(&ks[0][0]),
+                                        reinterpret_cast<const __half *>(&ks[F32MF ? kTile : 0][0]), band_s, D + KPAD, tile, valid_slot,
+                                        reinterpret_cast<uint32_t *>(&words[0][0]), &unsure[0][0], between,
+                                        [&](int rl) { return reinterpret_cast<const float *>(kbase + src_off[rl]); });
         } else
         // ---- Eq.(2): lane = sketch bit; y = fma chain over j; ballot = packed word ----
         for (int word = wave % wslots; word < W; word += wslots) {
@@ -236,7 +215,7 @@ __device__ __forceinline__ void append_body(const AppendArgs &a, const BatchDesc
         }
 
         // ---- fp16-value variant: no quantiser, the value rounded to nearest-even fp16 ----
-        if (pv.code_layout == 2) {
+        if (PART != kKeys && pv.code_layout == 2) {
             __half *values = reinterpret_cast<__half *>(pv.codes);
             for (int e = tid * 8; e < tile * D; e += kThreads * 8) {
                 const int rl = e / D, ch = e % D;
@@ -253,7 +232,7 @@ __device__ __forceinline__ void append_body(const AppendArgs &a, const BatchDesc
         // ---- Eq.(4): one lane per (slot, 32-channel slice) ----
         constexpr int LPT = D / 32;
         const int lanes_per_group = G / 32;
-        for (int item = tid; pv.code_layout != 2 && item < ((tile * LPT + 63) & ~63); item += kThreads) {   // whole waves run the loop (shuffles below)
+        for (int item = tid; PART != kKeys && pv.code_layout != 2 && item < ((tile * LPT + 63) & ~63); item += kThreads) {   // whole waves run the loop (shuffles below)
             const int rl = item / LPT, slice = item % LPT;
             const bool valid = rl < tile && valid_slot(rl);
             float x[32];
@@ -294,11 +273,42 @@ __device__ __forceinline__ void append_body(const AppendArgs &a, const BatchDesc
             const float zp = __half2float(__ushort_as_half(zh));
             uint32_t packed[4] = {0u, 0u, 0u, 0u};
             if (sc != 0.0f) {
+                // Eq.(4)'s code is clamp(rint((x - zero) / scale)) with an IEEE divide.  Fast path: with r = RN(1 / scale),
+                // u = fma(x - zero, r, 2^23) rounds the exact product to an integer in the low mantissa bits of u.  The
+                // product and the rounded quotient each lie within 16 * 2^-24 of the true quotient (codes beyond 0..15 are
+                // clamped on either route), so they can round to different integers only if a half-integer lies within
+                // 2e-6 of the product, i.e. if the product's distance e from its integer is within that of 1/2.  A lane
+                // that sees such an element anywhere in its slice (about one lane in a thousand) redoes the slice with
+                // the divide.  The codes are assembled as w = (w << 4) + bits(u): every bits(u) is 0x4B000000 + code, so the
+                // stray high bits sum to a constant that is subtracted once per word.
+                const float r = 1.0f / sc;
+                float worst = 0.0f;
 #pragma unroll
-                for (int i = 0; i < 32; ++i) {
-                    float q = rintf((x[i] - zp) / sc);
-                    q = fminf(fmaxf(q, 0.0f), 15.0f);
-                    packed[i >> 3] |= (uint32_t)(int)q << (4 * (i & 7));
+                for (int wd = 0; wd < 4; ++wd) {
+                    uint32_t w = 0u;
+#pragma unroll
+                    for (int i = 7; i >= 0; --i) {
+                        const float d = x[8 * wd + i] - zp;
+                        const float u = __builtin_fmaf(d, r, 8388608.0f);
+                        const float e = __builtin_fmaf(d, r, 8388608.0f - u);      // product minus its integer (exact difference)
+                        worst = fmaxf(worst, fabsf(e));
+                        const float uc = __builtin_amdgcn_fmed3f(u, 8388608.0f, 8388623.0f);
+                        w = (w << 4) + __float_as_uint(uc);
+                    }
+                    packed[wd] = w - 0xFB000000u;      // sum over i of 0x4B000000 << 4 i, modulo 2^32
+                }
+                if (!(worst < 0.49999f)) {             // also a NaN: the divide decides, as before
+#pragma unroll                                 // (a rolled loop would index x[] dynamically and move it out of the registers)
+                    for (int wd = 0; wd < 4; ++wd) {
+                        uint32_t w = 0u;
+#pragma unroll
+                        for (int i = 0; i < 8; ++i) {
+                            float q = rintf((x[8 * wd + i] - zp) / sc);
+                            q = fminf(fmaxf(q, 0.0f), 15.0f);
+                            w |= (uint32_t)(int)q << (4 * i);
+                        }
+                        packed[wd] = w;
+                    }
                 }
             }
             if (valid) {
@@ -315,13 +325,13 @@ __device__ __forceinline__ void append_body(const AppendArgs &a, const BatchDesc
         __syncthreads();
 
         // ---- store sketch words ----
-        for (int i = tid; i < tile * W; i += kThreads) {
+        for (int i = tid; PART != kValues && i < tile * W; i += kThreads) {
             const int rl = i / W, w = i - rl * W;
             if (valid_slot(rl)) pv.sketch[dst[rl] * W + w] = words[rl][w];
         }
 
         // ---- layout 1: one word per (8-token block, channel) ----
-        if (pv.code_layout == 1) {
+        if (PART != kKeys && pv.code_layout == 1) {
             for (int item = tid; item < (tile / 8) * D; item += kThreads) {
                 const int blk = item / D, c = item % D;
                 uint32_t val = 0, have = 0;
@@ -342,9 +352,48 @@ __device__ __forceinline__ void append_body(const AppendArgs &a, const BatchDesc
     }
 }
 
-template <int D, typename T, bool MF, bool ONE = false, bool RES = false>
-__global__ __launch_bounds__(kThreads, MF ? (RES ? 3 : 4) : 1) void append_kernel(AppendArgs a, BatchDesc desc, int tile) {
-    append_body<D, T, MF, ONE, RES>(a, desc, tile, blockIdx.x, blockIdx.y, gridDim.x);
+template <int D, typename T, bool MF, bool ONE = false>
+__global__ __launch_bounds__(kThreads, MF ? 4 : 1) void append_kernel(AppendArgs a, BatchDesc desc, int tile) {
+    append_body<D, T, MF, ONE>(a, desc, tile, blockIdx.x, blockIdx.y, gridDim.x);
+}
+
+// The values' half on its own: nothing resident, few registers.
+template <int D, typename T>
+__global__ __launch_bounds__(kThreads, 6) void append_values_kernel(AppendArgs a, BatchDesc desc, int tile) {
+    append_body<D, T, false, false, kValues>(a, desc, tile, blockIdx.x, blockIdx.y, gridDim.x);
+}
+
+// The keys' half on its own, with the pieces of R resident in registers (resident_sketch_tiles in projection_mfma.h):
+// tiles of 64 record slots of sequence blockIdx.y, in the slot order of append_body (head-major, each head's run padded
+// to 8-token blocks; the padding slots are empty).
+struct KeyRows {
+    const AppendArgs &a;
+    SeqDesc sd;
+    int L, off8, n_slots;
+    __device__ int rows_in(long tile) const { return min(kTile, n_slots - (int)tile * kTile); }
+    __device__ size_t src(long tile, int rl) const {
+        const int slot = (int)tile * kTile + rl, head = slot / L, t = slot % L - off8;
+        return t >= 0 && t < a.n_new ? (size_t)t * a.stride_tok + (size_t)head * a.stride_head : kProjNoRow;
+    }
+    __device__ int page_request(long tile, int rl) const {
+        const int slot = (int)tile * kTile + rl, pos = sd.pos + slot % L - off8;
+        return a.pool.block_table[(size_t)sd.seq_id * a.pool.max_pages_per_seq + pos / kPage];
+    }
+    __device__ uint32_t *dst(long tile, int rl, int page) const {
+        const int slot = (int)tile * kTile + rl, head = slot / L, pos = sd.pos + slot % L - off8;
+        const size_t rec = ((size_t)page * a.pool.n_kv_heads + head) * kPage + pos % kPage;
+        return reinterpret_cast<uint32_t *>(a.pool.sketch + rec * (a.pool.sketch_bits >> 6));
+    }
+};
+
+template <int D, typename T>
+__global__ __launch_bounds__(kThreads, 3) void append_keys_kernel(AppendArgs a, BatchDesc desc) {
+    static_assert(kTile == kProjTile && kThreads == kProjThreads, "projection_mfma.h assumes this tile shape");
+    const SeqDesc sd = desc.s[blockIdx.y];
+    const int off8 = sd.pos & 7, L = (off8 + a.n_new + 7) & ~7, n_slots = L * a.pool.n_kv_heads;
+    const KeyRows rows{a, sd, L, off8, n_slots};
+    resident_sketch_tiles<D, T>(a.pool, static_cast<const T *>(a.k) + (size_t)blockIdx.y * a.stride_seq, rows, (long)blockIdx.x,
+                                (long)gridDim.x, (long)((n_slots + kTile - 1) / kTile));
 }
 
 // Prologue of a fused decode step: rows [0, n_seqs) of the grid append the step's new token of each sequence,
@@ -406,10 +455,7 @@ hipError_t launch_append(const AppendArgs &a, const BatchDesc &desc, int n_seqs,
     // workgroups per compute unit walk all of them.
     // (the matrix-core path with streamed pieces of R keeps nothing resident: more, shorter workgroups even out the tail)
     const int D = a.pool.head_dim;
-    const bool fits = D == 64 ? proj_resident_fits<64>(a.pool.sketch_bits)
-                              : D == 128 ? proj_resident_fits<128>(a.pool.sketch_bits) : proj_resident_fits<256>(a.pool.sketch_bits);
-    // (resident pieces: three long-lived workgroups per compute unit, all in one round)
-    const long wg_budget = a.proj_mfma && !qa ? (fits ? 768 : 6144) : 1024;
+    const long wg_budget = a.proj_mfma && !qa ? 6144 : 1024;
     const long max_wgs_x = wg_budget / n_seqs > 0 ? wg_budget / n_seqs : 1;
     const unsigned gx = (unsigned)(tiles < max_wgs_x ? tiles : max_wgs_x);
     unsigned q_rows = 0;
@@ -419,6 +465,13 @@ hipError_t launch_append(const AppendArgs &a, const BatchDesc &desc, int n_seqs,
         q_rows = (q_blocks + gx - 1) / gx;
     }
     const dim3 grid(gx, (unsigned)n_seqs + q_rows);
+    // Large appends whose sketch width allows resident pieces of R run as two launches: the keys' half with three
+    // long-lived workgroups per compute unit (768, all in one round), the values' half as a stream of short ones.
+    const long key_tiles = (n_slots + kTile - 1) / kTile;
+    const bool split = a.proj_mfma && !qa && key_tiles * n_seqs >= 768 &&
+                       (D == 64 ? proj_resident_fits<64>(a.pool.sketch_bits) : D == 128 && proj_resident_fits<128>(a.pool.sketch_bits));
+    const long max_keys_x = 768 / n_seqs > 0 ? 768 / n_seqs : 1;
+    const dim3 grid_keys((unsigned)(key_tiles < max_keys_x ? key_tiles : max_keys_x), (unsigned)n_seqs);
     const QueryArgs qargs = qa ? *qa : QueryArgs{nullptr, nullptr, 0};
 #define H1BKV_LAUNCH(DD, TT)                                                                                        \
     do {                                                                                                            \
@@ -426,15 +479,19 @@ hipError_t launch_append(const AppendArgs &a, const BatchDesc &desc, int n_seqs,
         else if (a.n_new == 1) hipLaunchKernelGGL((append_kernel<DD, TT, false, true>), grid, dim3(kThreads), 0, st, a, desc, (int)tile); \
         else hipLaunchKernelGGL((append_kernel<DD, TT, false>), grid, dim3(kThreads), 0, st, a, desc, (int)tile);   \
     } while (0)
-#define H1BKV_LAUNCH_MF(DD, TT)                                                                                                \
-    do {                                                                                                                       \
-        if (fits) hipLaunchKernelGGL((append_kernel<DD, TT, true, false, true>), grid, dim3(kThreads), 0, st, a, desc, (int)tile); \
-        else hipLaunchKernelGGL((append_kernel<DD, TT, true>), grid, dim3(kThreads), 0, st, a, desc, (int)tile);              \
+#define H1BKV_LAUNCH_MF(DD, TT)                                                                                        \
+    do {                                                                                                               \
+        if (split) {                                                                                                   \
+            hipLaunchKernelGGL((append_keys_kernel<DD, TT>), grid_keys, dim3(kThreads), 0, st, a, desc);               \
+            hipLaunchKernelGGL((append_values_kernel<DD, TT>), grid, dim3(kThreads), 0, st, a, desc, (int)tile);       \
+        } else {                                                                                                       \
+            hipLaunchKernelGGL((append_kernel<DD, TT, true>), grid, dim3(kThreads), 0, st, a, desc, (int)tile);        \
+        }                                                                                                              \
     } while (0)
     if (a.f16 && a.proj_mfma && !qa) {
         if (D == 64) H1BKV_LAUNCH_MF(64, __half);
         else if (D == 128) H1BKV_LAUNCH_MF(128, __half);
-        else H1BKV_LAUNCH_MF(256, __half);
+        else hipLaunchKernelGGL((append_kernel<256, __half, true>), grid, dim3(kThreads), 0, st, a, desc, (int)tile);
     } else if (a.proj_mfma && !qa && D <= 128) {      // fp32 keys (d = 256: two piece tiles would not leave room for a second workgroup)
         if (D == 64) H1BKV_LAUNCH_MF(64, float);
         else H1BKV_LAUNCH_MF(128, float);

@@ -554,113 +554,39 @@ __global__ __launch_bounds__(kThreads, 4) void sketch_rows_mfma_kernel(PrefillAr
     }
 }
 
-// The same with the pieces of R resident in registers (sketches of at most 64 * 256 / D bits): three long-lived workgroups
-// per compute unit walk the tiles; the guard-band bits are recomputed in batches; and the next tile's fp16 vectors are
-// requested into registers before the current tile's matrix-core phase, so that the stream from memory does not stop
-// while the workgroup computes.
+// The same with the pieces of R resident in registers (d <= 128, sketches of at most 64 * 256 / d bits): three long-lived
+// workgroups per compute unit walk the tiles (resident_sketch_tiles in projection_mfma.h).
+struct QueryRows {
+    const PrefillArgs &a;
+    long n_vec;
+    __device__ int rows_in(long tile) const { return (int)min((long)kSketchTile, n_vec - tile * kSketchTile); }
+    __device__ size_t src(long tile, int rl) const {
+        const long v = tile * kSketchTile + rl;
+        const int Hq = a.pool.n_q_heads;
+        long s, rem;
+        if (n_vec <= 0x7FFFFFFFL) {                     // (uniform) 32-bit division: a fraction of the 64-bit one's instructions
+            const uint32_t per_seq = (uint32_t)a.n_q * (uint32_t)Hq;
+            s = (uint32_t)v / per_seq;
+            rem = (uint32_t)v % per_seq;
+        } else {
+            s = v / ((long)a.n_q * Hq);
+            rem = v % ((long)a.n_q * Hq);
+        }
+        return (size_t)s * a.stride_seq + (size_t)((uint32_t)rem / (uint32_t)Hq) * a.stride_tok +
+               (size_t)((uint32_t)rem % (uint32_t)Hq) * a.stride_head;
+    }
+    __device__ int page_request(long, int) const { return 0; }
+    __device__ uint32_t *dst(long tile, int rl, int) const {
+        return reinterpret_cast<uint32_t *>(a.q_sketch + (size_t)(tile * kSketchTile + rl) * (a.pool.sketch_bits >> 6));
+    }
+};
+
 template <int D, typename T>
 __global__ __launch_bounds__(kThreads, 3) void sketch_rows_resident_kernel(PrefillArgs a, int n_seqs) {
-    constexpr bool F32 = sizeof(T) == 4;
-    constexpr int STRIDE = D + 8;
-    constexpr int PF = F32 ? 1 : kSketchTile * D / (kThreads * 8);  // 16-byte loads per thread and tile (fp16 vectors)
-    __shared__ __attribute__((aligned(16))) __half qs[(F32 ? 2 : 1) * kSketchTile * STRIDE];
-    __shared__ size_t src_off[2][kSketchTile];                     // this tile's and the next one's
-    __shared__ uint32_t w32[kSketchTile * 16], unsure[kSketchTile * 16];
-    __shared__ float band_s[kSketchTile];
-    __shared__ ProjFixList fixes;
-    const int tid = threadIdx.x;
-    const PoolView &pv = a.pool;
-    const int W = pv.sketch_bits >> 6, Hq = pv.n_q_heads;
-    const long n_vec = (long)n_seqs * a.n_q * Hq, step = (long)gridDim.x * kSketchTile;
-    const T *qbase = static_cast<const T *>(a.q);
-    auto resolve = [&](long v0, int buf) {
-        if (tid < kSketchTile && v0 + tid < n_vec) {
-            const long v = v0 + tid;
-            long s, rem;
-            if (n_vec <= 0x7FFFFFFFL) {             // (uniform) 32-bit division: a fraction of the 64-bit one's instructions
-                const uint32_t per_seq = (uint32_t)a.n_q * (uint32_t)Hq;
-                s = (uint32_t)v / per_seq;
-                rem = (uint32_t)v % per_seq;
-            } else {
-                s = v / ((long)a.n_q * Hq);
-                rem = v % ((long)a.n_q * Hq);
-            }
-            src_off[buf][tid] = (size_t)s * a.stride_seq + (size_t)((uint32_t)rem / (uint32_t)Hq) * a.stride_tok +
-                                (size_t)((uint32_t)rem % (uint32_t)Hq) * a.stride_head;
-        }
-    };
-    // this thread's part of a tile: 16-byte piece k is elements [pre_ch, pre_ch + 8) of row pre_row + k * (kThreads * 8 / D)
-    const int pre_row = tid * 8 / D, pre_ch = tid * 8 % D;
-    // (four named registers, not an array: the array form stayed in scratch memory)
-    [[maybe_unused]] uint4 pre0, pre1, pre2, pre3;
-    static_assert(PF <= 4, "one register set per 16-byte piece");
-    // rows past the end of the input repeat the last one: no branch around a load (the compiler makes every load behind a
-    // branch wait for the ones before it)
-#define H1BKV_REQUEST_ONE(K, REG, V0, BUF)                                                                              \
-    if constexpr (K < PF) {                                                                                             \
-        const int last = (int)min((long)kSketchTile, n_vec - (V0)) - 1, rl = pre_row + K * (kThreads * 8 / D);          \
-        REG = *reinterpret_cast<const uint4 *>(qbase + src_off[BUF][rl < last ? rl : last] + pre_ch);                   \
-    }
-#define H1BKV_REQUEST(V0, BUF)                                                                                          \
-    do {                                                                                                                \
-        H1BKV_REQUEST_ONE(0, pre0, V0, BUF) H1BKV_REQUEST_ONE(1, pre1, V0, BUF) H1BKV_REQUEST_ONE(2, pre2, V0, BUF)     \
-        H1BKV_REQUEST_ONE(3, pre3, V0, BUF)                                                                             \
-    } while (0)
-#define H1BKV_DEPOSIT_ONE(K, REG)                                                                                       \
-    if constexpr (K < PF) {                                                                                             \
-        const int rl = pre_row + K * (kThreads * 8 / D);                                                                \
-        if (rl < n_here) *reinterpret_cast<uint4 *>(&qs[rl * STRIDE + pre_ch]) = REG;                                   \
-    }
-    ProjResident<D> res;
-    load_resident<D, F32>(pv, res);
-    if (tid == 0) fixes.n = 0;
-    long v0 = (long)blockIdx.x * kSketchTile;
-    if (v0 < n_vec) resolve(v0, 0);
-    __syncthreads();
-    if constexpr (!F32) {
-        if (v0 < n_vec) H1BKV_REQUEST(v0, 0);
-    }
-    for (int buf = 0;; v0 += step, buf ^= 1) {
-        __syncthreads();
-        const bool more = v0 < n_vec;
-        // the list of guard-band words is drained when it is half full and after the last tile (the stores of the listed
-        // words precede the barrier above)
-        const int pending = fixes.n;
-        if (pending > 0 && (!more || pending >= kProjFixCap / 2)) {
-            drain_fixes<D, T>(pv, fixes);
-            __syncthreads();
-            if (tid == 0) fixes.n = 0;          // (the barriers below come before the next entries)
-        }
-        if (!more) break;
-        const int n_here = (int)min((long)kSketchTile, n_vec - v0);
-        for (int e = tid; e < kSketchTile * 16; e += kThreads) {
-            w32[e] = 0u;
-            unsure[e] = 0u;
-        }
-        if constexpr (!F32) {
-            H1BKV_DEPOSIT_ONE(0, pre0) H1BKV_DEPOSIT_ONE(1, pre1) H1BKV_DEPOSIT_ONE(2, pre2) H1BKV_DEPOSIT_ONE(3, pre3)
-        }
-        const bool next = v0 + step < n_vec;
-        if (next) resolve(v0 + step, buf ^ 1);
-        __syncthreads();
-        if constexpr (F32) {
-            stage_f32_tile<D>([&](int rl) { return reinterpret_cast<const float *>(qbase + src_off[buf][rl]); }, n_here, qs,
-                              qs + kSketchTile * STRIDE, STRIDE, band_s);
-        } else {
-            if (next) H1BKV_REQUEST(v0 + step, buf ^ 1);
-        }
-        project_tile_resident<D, F32>(
-            pv, res, qs, qs + (F32 ? kSketchTile * STRIDE : 0), band_s, STRIDE, n_here, [](int) { return true; }, w32, unsure, []() {},
-            [&](int rl) { return static_cast<const void *>(qbase + src_off[buf][rl]); },
-            [&](int rl) { return reinterpret_cast<uint32_t *>(a.q_sketch + (size_t)(v0 + rl) * W); }, fixes);
-        __syncthreads();
-        // the 32-bit halves of a vector's sketch words are contiguous in w32 and in the output
-        uint32_t *out = reinterpret_cast<uint32_t *>(a.q_sketch + (size_t)v0 * W);
-        for (int e = tid; e < n_here * 2 * W; e += kThreads) out[e] = w32[(e / (2 * W)) * 16 + e % (2 * W)];
-    }
-#undef H1BKV_REQUEST
-#undef H1BKV_REQUEST_ONE
-#undef H1BKV_DEPOSIT_ONE
+    const long n_vec = (long)n_seqs * a.n_q * a.pool.n_q_heads;
+    const QueryRows rows{a, n_vec};
+    resident_sketch_tiles<D, T>(a.pool, static_cast<const T *>(a.q), rows, (long)blockIdx.x, (long)gridDim.x,
+                                (n_vec + kSketchTile - 1) / kSketchTile);
 }
 
 template <int D, typename T>

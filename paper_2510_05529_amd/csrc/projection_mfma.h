@@ -222,23 +222,61 @@ __device__ __forceinline__ void project_tile_mfma(const PoolView &pv, const __ha
 
 
 // ------------------------------------------------------------------------------------------------------------------
-// Resident form, for sketches of at most 64 * (256 / D) bits: a wave keeps the pieces of R for its blocks of 16 bits
-// in registers for the life of the workgroup (64 registers), so a tile costs no loads of R at all, every 16-byte read of
-// the tile from LDS feeds all of the wave's blocks, and the bits inside the guard band are not recomputed per tile (a
-// handful of threads each walking a chain of dependent loads while the others wait at the barrier) but collected in an
-// LDS list that all threads drain together, once per many tiles, patching the sketch words in global memory.
+// Resident form, for d <= 128 and sketches of at most 64 * (256 / d) bits: a whole kernel body.
+//  * A wave keeps the pieces of R for its blocks of 16 bits (blocks wave * W .. wave * W + W - 1, W = b / 64) in
+//    registers for the life of the workgroup (64 registers): a tile costs no loads of R, and each 16-byte read of the
+//    tile from LDS feeds all of the wave's blocks.
+//  * The next tile's fp16 vectors are requested into registers before the current tile's matrix-core phase and deposited
+//    into the other of two LDS tiles afterwards (the 2-norms are taken from the registers on the way): the stream from
+//    memory does not stop while the workgroup computes, and a tile costs ONE barrier.
+//  * A wave assembles the 16-bit blocks it owns with two lane exchanges and stores them straight to global memory: no
+//    LDS words, no atomics, no zeroing.
+//  * Words with bits inside the guard band are not recomputed on the spot (one lane walking a chain of dependent loads
+//    while its workgroup waits) but entered into an LDS list that all threads drain together every 16 tiles, patching
+//    the stored words with atomics; a full list falls back to recomputing on the spot.
+// Rows (the caller's description of its tiles of up to 64 vectors; tile indices are the caller's):
+//   int rows_in(long tile)                      number of row slots of the tile
+//   size_t src(long tile, int rl)               element offset of the vector from `base`, or kProjNoRow for an empty slot
+//   int page_request(long tile, int rl)         a value the destination depends on, loaded from global memory one tile
+//                                               ahead of its use (the page id; 0 if there is none); valid slots only
+//   uint32_t *dst(long tile, int rl, int page)  where the vector's sketch goes (32-bit words); valid slots only
 // ------------------------------------------------------------------------------------------------------------------
+
+constexpr size_t kProjNoRow = ~(size_t)0;
+
+// OR over the four 16-lane rows of a wave, in every lane: two row exchanges in the register file (v_permlane16_swap,
+// v_permlane32_swap: after exchanging rows between two copies of x, the OR of the copies joins two different rows at every
+// position), no trip through the LDS crossbar.
+__device__ __forceinline__ uint32_t proj_or_rows(uint32_t x) {
+    typedef unsigned pair_t __attribute__((ext_vector_type(2)));
+    const pair_t a = __builtin_amdgcn_permlane16_swap(x, x, false, false);
+    x = a.x | a.y;
+    const pair_t b = __builtin_amdgcn_permlane32_swap(x, x, false, false);
+    return b.x | b.y;
+}
+
+// Sum over aligned groups of LANES (8 or 16) neighbouring lanes, in every lane of the group, by DPP: the two exchanges
+// inside a quad, then the mirror of 8 lanes (quads are uniform by then), then the mirror of 16.
+template <int LANES>
+__device__ __forceinline__ float proj_sum_lanes(float s) {
+    static_assert(LANES == 8 || LANES == 16, "row-local DPP patterns");
+    s += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, s), 0xB1, 0xF, 0xF, false));   // quad_perm [1,0,3,2]
+    s += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, s), 0x4E, 0xF, 0xF, false));   // quad_perm [2,3,0,1]
+    s += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, s), 0x141, 0xF, 0xF, false));  // row_half_mirror
+    if (LANES == 16) s += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, s), 0x140, 0xF, 0xF, false));  // row_mirror
+    return s;
+}
 
 template <int D>
 struct ProjResident {
-    static constexpr int NB = 256 / D;          // blocks of 16 bits per wave: wave, wave + 4, ...
+    static constexpr int NB = 256 / D;          // blocks of 16 bits per wave
     uint4 hi[NB][D / 32], mid[NB][D / 32];
     float g[NB][4];
 };
 
 template <int D>
 __host__ __device__ constexpr bool proj_resident_fits(int sketch_bits) {
-    return sketch_bits / 64 <= 256 / D;
+    return D <= 128 && sketch_bits / 64 <= 256 / D;
 }
 
 template <int D, bool F32IN>
@@ -248,7 +286,7 @@ __device__ __forceinline__ void load_resident(const PoolView &pv, ProjResident<D
     const float *guard = F32IN ? pv.guard + pv.sketch_bits : pv.guard;
 #pragma unroll
     for (int i = 0; i < ProjResident<D>::NB; ++i) {
-        const int bb = i < W ? wave + 4 * i : wave;                  // (unused slots repeat a valid block: no branch)
+        const int bb = wave * W + (i < W ? i : 0);                   // (unused slots repeat a valid block: no branch)
         const size_t arow = (size_t)(16 * bb + n) * D + 8 * kb;
 #pragma unroll
         for (int jb = 0; jb < D / 32; ++jb) {
@@ -261,7 +299,7 @@ __device__ __forceinline__ void load_resident(const PoolView &pv, ProjResident<D
     // The loads are waited for here, once: each register passes through an (empty) assembly statement, after which the
     // compiler no longer counts it as the target of a load in flight.  Without this the first matrix-core instruction of
     // every tile waits for ALL outstanding loads (the counter cannot single out registers loaded before the tile loop) --
-    // including the next tile's vectors the caller has just requested.
+    // including the next tile's vectors that have just been requested.
 #pragma unroll
     for (int i = 0; i < ProjResident<D>::NB; ++i) {
 #pragma unroll
@@ -273,24 +311,25 @@ __device__ __forceinline__ void load_resident(const PoolView &pv, ProjResident<D
     }
 }
 
-// One entry per 32-bit sketch word that holds bits inside the guard band.
+// One entry per stored 32-bit sketch word that holds bits inside the guard band.
 struct ProjFix {
     const void *src;       // the vector, in its boundary dtype, in global memory
-    uint32_t *dst;         // the sketch word in global memory (written by the tile's store before the list is drained)
+    uint32_t *dst;         // the sketch word in global memory
     uint32_t mask;         // the bits to recompute
     uint32_t word;         // index of the word within the sketch: its bits are rows 32 word .. 32 word + 31 of R
 };
 constexpr int kProjFixCap = 256;
+constexpr int kProjDrainEvery = 16;    // tiles between two drains: about 4 entries per tile at d = b = 128
 struct ProjFixList {
-    int n;                 // entries requested so far (may run past the capacity: those were recomputed in place)
+    int n;                 // entries requested so far (may run past the capacity: those were recomputed on the spot)
     ProjFix item[kProjFixCap];
 };
 
-// The pinned chain of Eq.(2) for one row of R: y = fma(R[j], x[j], y), j ascending.  load8(j, out): elements j .. j+7 of
-// the vector as fp32.  16 elements of the row at a time: their loads are in flight together before the sequential chain
-// runs (callers hold the resident pieces of R next to this, so no more than that).
-template <int D, typename Load8>
-__device__ __forceinline__ float proj_chain(const float *row, Load8 load8) {
+// The pinned chain of Eq.(2) for row `row` of R and the vector x (boundary dtype T, global memory): y = fma(R[j], x[j], y),
+// j ascending.  16 elements at a time: their loads are in flight together before the sequential chain runs (the callers
+// hold the resident pieces of R next to this, so no more than that).
+template <int D, typename T>
+__device__ __forceinline__ float proj_chain(const float *row, const T *x) {
     float y = 0.0f;
 #pragma unroll 1
     for (int j0 = 0; j0 < D; j0 += 16) {
@@ -300,7 +339,12 @@ __device__ __forceinline__ float proj_chain(const float *row, Load8 load8) {
 #pragma unroll
         for (int q = 0; q < 4; q += 2) {
             float kk[8];
-            load8(j0 + 4 * q, kk);
+            if constexpr (sizeof(T) == 2) {
+                proj_load8(reinterpret_cast<const __half *>(x) + j0 + 4 * q, kk);
+            } else {
+                const float4 a = *reinterpret_cast<const float4 *>(x + j0 + 4 * q), b = *reinterpret_cast<const float4 *>(x + j0 + 4 * q + 4);
+                kk[0] = a.x; kk[1] = a.y; kk[2] = a.z; kk[3] = a.w; kk[4] = b.x; kk[5] = b.y; kk[6] = b.z; kk[7] = b.w;
+            }
             y = __builtin_fmaf(rr[q].x, kk[0], y); y = __builtin_fmaf(rr[q].y, kk[1], y);
             y = __builtin_fmaf(rr[q].z, kk[2], y); y = __builtin_fmaf(rr[q].w, kk[3], y);
             y = __builtin_fmaf(rr[q + 1].x, kk[4], y); y = __builtin_fmaf(rr[q + 1].y, kk[5], y);
@@ -310,141 +354,253 @@ __device__ __forceinline__ float proj_chain(const float *row, Load8 load8) {
     return y;
 }
 
-// Recomputes the listed bits with the chain and patches the words.  T: the vectors' boundary dtype.  Called by all 256
-// threads between two barriers, after the stores of the tiles the entries belong to; the caller resets list.n afterwards.
+// The bits `mask` of a word whose bit p is row `row0 + p` of R, recomputed with the chain: returns the bits to set
+// (the others of `mask` are to be cleared).
 template <int D, typename T>
-__device__ __forceinline__ void drain_fixes(const PoolView &pv, const ProjFixList &list) {
-    const int n = list.n < kProjFixCap ? list.n : kProjFixCap;
-    for (int e = per_tile_index(threadIdx.x); e < n; e += kProjThreads) {
-        const ProjFix f = list.item[e];
-        const T *x = static_cast<const T *>(f.src);
-        uint32_t m = f.mask, set = 0u, clear = 0u;
-        while (m) {
-            const int p = __ffs(m) - 1;
-            m &= m - 1u;
-            const float y = proj_chain<D>(pv.R + (size_t)(32 * f.word + p) * D, [&](int j, float *out) {
-                if constexpr (sizeof(T) == 2) {
-                    proj_load8(reinterpret_cast<const __half *>(x) + j, out);
-                } else {
-                    const float4 a = *reinterpret_cast<const float4 *>(x + j), b = *reinterpret_cast<const float4 *>(x + j + 4);
-                    out[0] = a.x; out[1] = a.y; out[2] = a.z; out[3] = a.w; out[4] = b.x; out[5] = b.y; out[6] = b.z; out[7] = b.w;
+__device__ __forceinline__ uint32_t proj_chain_bits(const PoolView &pv, int row0, uint32_t mask, const T *x) {
+    uint32_t set = 0u;
+    while (mask) {
+        const int p = __ffs(mask) - 1;
+        mask &= mask - 1u;
+        if (proj_chain<D, T>(pv.R + (size_t)(row0 + p) * D, x) >= 0.0f) set |= 1u << p;
+    }
+    return set;
+}
+
+// Drains the list: D / 16 neighbouring lanes per entry, lane c holding elements [16 c, 16 c + 16) of the vector and of the
+// row of R, so that all loads of a chain are in flight at once; the chain value then travels from lane to lane (the
+// order of the multiply-adds is the pinned one).  Called by all threads between two barriers.
+template <int D, typename T>
+__device__ __forceinline__ void proj_drain(const PoolView &pv, const ProjFixList &list) {
+    constexpr int LPE = D / 16;
+    const int n_fix = list.n < kProjFixCap ? list.n : kProjFixCap;
+    const int tid = per_tile_index(threadIdx.x), lane = tid & 63, c = tid % LPE;
+    for (int e0 = 0; e0 < n_fix; e0 += kProjThreads / LPE) {
+        const int e = e0 + tid / LPE;
+        const bool have = e < n_fix;
+        const ProjFix f = list.item[have ? e : 0];
+        uint32_t m = have ? f.mask : 0u, set = 0u;
+        float xk[16];
+        {
+            const T *x = static_cast<const T *>(f.src) + 16 * c;
+            if constexpr (sizeof(T) == 2) {
+                proj_load8(reinterpret_cast<const __half *>(x), xk);
+                proj_load8(reinterpret_cast<const __half *>(x) + 8, xk + 8);
+            } else {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float4 a = *reinterpret_cast<const float4 *>(x + 4 * q);
+                    xk[4 * q] = a.x; xk[4 * q + 1] = a.y; xk[4 * q + 2] = a.z; xk[4 * q + 3] = a.w;
                 }
-            });
-            if (y >= 0.0f) set |= 1u << p;
-            else clear |= 1u << p;
+            }
         }
-        if (set) atomicOr(f.dst, set);
-        if (clear) atomicAnd(f.dst, ~clear);
+        while (__any(m != 0u)) {                             // (entries with several bits are rare)
+            const int p = m ? __ffs(m) - 1 : 0;
+            const float *row = pv.R + (size_t)(32 * (int)f.word + p) * D + 16 * c;
+            float4 rr[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) rr[q] = *reinterpret_cast<const float4 *>(row + 4 * q);
+            float y = 0.0f;
+#pragma unroll 1
+            for (int stage = 0; stage < LPE; ++stage) {
+                float z = y;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    z = __builtin_fmaf(rr[q].x, xk[4 * q], z); z = __builtin_fmaf(rr[q].y, xk[4 * q + 1], z);
+                    z = __builtin_fmaf(rr[q].z, xk[4 * q + 2], z); z = __builtin_fmaf(rr[q].w, xk[4 * q + 3], z);
+                }
+                // the value after this stage's 16 elements is the one computed by lane `stage` of the group
+                y = __shfl(z, (lane & ~(LPE - 1)) + stage);
+            }
+            if (m) {
+                if (y >= 0.0f) set |= 1u << p;
+                m &= m - 1u;
+            }
+        }
+        if (have && c == 0) {
+            if (set) atomicOr(f.dst, set);
+            if (f.mask & ~set) atomicAnd(f.dst, ~(f.mask & ~set));
+        }
     }
 }
 
-// The tile's projections with resident pieces of R.  Arguments as project_tile_mfma, plus:
-//   src(v): the vector's address in global memory (boundary dtype);  dst(v): the address of its first 32-bit sketch word
-//   in global memory -- where the caller stores w32[v][..] after its next barrier.
-// Words with bits inside the band are entered into `list`; when the list is full they are recomputed here, in w32.
-template <int D, bool F32IN, typename Valid, typename Between, typename Src, typename Dst>
-__device__ __forceinline__ void project_tile_resident(const PoolView &pv, const ProjResident<D> &res, const __half *xs, const __half *xm,
-                                                      float *band_s, int stride, int tile, Valid valid, uint32_t *w32, uint32_t *unsure,
-                                                      Between between, Src src, Dst dst, ProjFixList &list) {
-    constexpr int NB = ProjResident<D>::NB, NJ = D / 32;
-    const int tid = per_tile_index(threadIdx.x), lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int n = lane & 15, kb = lane >> 4;
+template <int D, typename T, typename Rows>
+__device__ __forceinline__ void resident_sketch_tiles(const PoolView &pv, const T *base, const Rows &rows, long first, long step,
+                                                      long n_tiles) {
+    constexpr bool F32 = sizeof(T) == 4;
+    constexpr int STRIDE = D + 8, NJ = D / 32, NB = ProjResident<D>::NB;
+    constexpr int NBUF = F32 ? 1 : 2;                       // (two piece tiles per fp32 tile: one buffer, one more barrier)
+    constexpr int RPP = kProjThreads * 8 / D;               // rows covered by one 16-byte piece per thread
+    static_assert(D == 64 || D == 128, "up to four 16-byte pieces per thread and tile");
+    __shared__ __attribute__((aligned(16))) __half xs[NBUF][(F32 ? 2 : 1) * kProjTile * STRIDE];
+    __shared__ float band_s[NBUF][kProjTile];
+    __shared__ size_t src_s[3][kProjTile];                  // this tile's, the next one's, and the previous one's (still read by slow waves)
+    __shared__ uint32_t *dst_s[2][kProjTile];
+    __shared__ ProjFixList fixes;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = lane & 15, kb = lane >> 4;
     const int W = pv.sketch_bits >> 6;
-    if constexpr (!F32IN) {
-        const int v = tid >> 2, part = tid & 3;
-        float ss = 0.0f;
-        if (v < tile && valid(v)) {
-            for (int j = part * 8; j < D; j += 32) {
-                float x[8];
-                proj_load8(xs + (size_t)v * stride + j, x);
-#pragma unroll
-                for (int e = 0; e < 8; ++e) ss = fmaf(x[e], x[e], ss);
+    const int pre_row = tid * 8 / D, pre_ch = tid * 8 % D;  // this thread's pieces: elements [pre_ch, pre_ch + 8) of rows pre_row + k RPP
+    ProjResident<D> res;
+    load_resident<D, F32>(pv, res);
+    if (tid == 0) fixes.n = 0;
+    // (named registers, not an array: an array of these stayed in scratch memory.  Empty slots read the first vector:
+    // no branch around a load -- the compiler makes every load behind a branch wait for the ones before it.)
+    [[maybe_unused]] uint4 pre0, pre1, pre2, pre3;
+#define H1BKV_PROJ_REQUEST_ONE(K, REG, SB)                                                                  \
+    if constexpr (K * RPP < kProjTile) {                                                                    \
+        const size_t off = src_s[SB][pre_row + K * RPP];                                                    \
+        REG = *reinterpret_cast<const uint4 *>(base + (off == kProjNoRow ? 0 : off) + pre_ch);              \
+    }
+#define H1BKV_PROJ_REQUEST(SB)                                                                              \
+    do {                                                                                                    \
+        H1BKV_PROJ_REQUEST_ONE(0, pre0, SB) H1BKV_PROJ_REQUEST_ONE(1, pre1, SB)                             \
+        H1BKV_PROJ_REQUEST_ONE(2, pre2, SB) H1BKV_PROJ_REQUEST_ONE(3, pre3, SB)                             \
+    } while (0)
+    // deposit a piece into the LDS tile and leave its row's 2-norm (times 1 + 2^-16: above the fp32 rounding of the sum
+    // and the root) in band_s; the D / 8 lanes of a row are neighbours
+#define H1BKV_PROJ_DEPOSIT_ONE(K, REG, BUF)                                                                 \
+    if constexpr (K * RPP < kProjTile) {                                                                    \
+        const int rl = pre_row + K * RPP;                                                                   \
+        *reinterpret_cast<uint4 *>(&xs[BUF][rl * STRIDE + pre_ch]) = REG;                                   \
+        const __half2 *h2 = reinterpret_cast<const __half2 *>(&REG);                                        \
+        float ss = 0.0f;                                                                                    \
+        _Pragma("unroll") for (int e = 0; e < 4; ++e) {                                                     \
+            const float2 f = __half22float2(h2[e]);                                                         \
+            ss = fmaf(f.x, f.x, ss);                                                                        \
+            ss = fmaf(f.y, f.y, ss);                                                                        \
+        }                                                                                                   \
+        ss = proj_sum_lanes<D / 8>(ss);                                                                     \
+        if (pre_ch == 0) band_s[BUF][rl] = sqrtf(ss) * 1.0000153f;                                          \
+    }
+    long t = first;
+    int page = 0;
+    if (tid < kProjTile) src_s[0][tid] = (t < n_tiles && tid < rows.rows_in(t)) ? rows.src(t, tid) : kProjNoRow;
+    __syncthreads();
+    if (t < n_tiles) {
+        if (tid < kProjTile && src_s[0][tid] != kProjNoRow) page = rows.page_request(t, tid);
+        if constexpr (!F32) H1BKV_PROJ_REQUEST(0);
+    }
+    for (int it = 0;; t += step, ++it) {
+        const bool more = t < n_tiles;
+        if (!more || it % kProjDrainEvery == kProjDrainEvery - 1) {
+            __syncthreads();                                 // the stores and the entries of the tiles so far are complete
+            if (fixes.n > 0 && (!more || fixes.n >= kProjFixCap / 2)) {
+                proj_drain<D, T>(pv, fixes);
+                __syncthreads();
+                if (tid == 0) fixes.n = 0;                   // (the tile's barrier below comes before the next entries)
             }
         }
-        ss += __shfl_xor(ss, 1);
-        ss += __shfl_xor(ss, 2);
-        if (part == 0) band_s[v] = sqrtf(ss) * 1.0000153f;
-    }
-    __syncthreads();
-#pragma unroll 1
-    for (int tb = 0; tb < (tile + 15) / 16; ++tb) {
-        const int v = 16 * tb + n;
-        proj_f16x8 Bx[NJ];
-        [[maybe_unused]] proj_f16x8 Bm[F32IN ? NJ : 1];
-#pragma unroll
-        for (int jb = 0; jb < NJ; ++jb) {
-            Bx[jb] = *reinterpret_cast<const proj_f16x8 *>(xs + (size_t)v * stride + 32 * jb + 8 * kb);
-            if constexpr (F32IN) Bm[jb] = *reinterpret_cast<const proj_f16x8 *>(xm + (size_t)v * stride + 32 * jb + 8 * kb);
+        if (!more) break;
+        const int buf = NBUF == 2 ? (it & 1) : 0, sb = it % 3, sb1 = (it + 1) % 3;
+        const int n_here = rows.rows_in(t);
+        const long t1 = t + step;
+        // ---- before the barrier: this tile into LDS, its destinations, the next tile's sources ----
+        if constexpr (F32) {
+            __syncthreads();                                 // one tile buffer: the previous tile's readers are done
+            stage_f32_tile<D>(
+                [&](int rl) { return src_s[sb][rl] != kProjNoRow ? reinterpret_cast<const float *>(base + src_s[sb][rl]) : nullptr; }, n_here,
+                &xs[0][0], &xs[0][kProjTile * STRIDE], STRIDE, &band_s[0][0]);
+        } else {
+            H1BKV_PROJ_DEPOSIT_ONE(0, pre0, buf) H1BKV_PROJ_DEPOSIT_ONE(1, pre1, buf)
+            H1BKV_PROJ_DEPOSIT_ONE(2, pre2, buf) H1BKV_PROJ_DEPOSIT_ONE(3, pre3, buf)
         }
-        const float band = band_s[v];
-        const bool live = v < tile && valid(v);
-#pragma unroll
-        for (int i = 0; i < NB; ++i) {
-            if (i >= W) break;                                         // uniform
-            proj_f32x4 yh = {0.f, 0.f, 0.f, 0.f}, ym = {0.f, 0.f, 0.f, 0.f};
+        if (tid < kProjTile) {
+            dst_s[it & 1][tid] = src_s[sb][tid] != kProjNoRow ? rows.dst(t, tid, page) : nullptr;
+            src_s[sb1][tid] = (t1 < n_tiles && tid < rows.rows_in(t1)) ? rows.src(t1, tid) : kProjNoRow;
+        }
+        __syncthreads();
+        // ---- after it: the next tile's requests, then the matrix cores ----
+        if (t1 < n_tiles) {
+            if (tid < kProjTile && src_s[sb1][tid] != kProjNoRow) page = rows.page_request(t1, tid);
+            if constexpr (!F32) H1BKV_PROJ_REQUEST(sb1);
+        }
+        const __half *xt = &xs[buf][0];
+        [[maybe_unused]] const __half *xmt = &xs[buf][F32 ? kProjTile * STRIDE : 0];
+#pragma unroll 1
+        for (int tb = 0; tb < (n_here + 15) / 16; ++tb) {
+            const int v = 16 * tb + n;
+            proj_f16x8 Bx[NJ];
+            [[maybe_unused]] proj_f16x8 Bm[F32 ? NJ : 1];
 #pragma unroll
             for (int jb = 0; jb < NJ; ++jb) {
-                yh = __builtin_amdgcn_mfma_f32_16x16x32_f16(*reinterpret_cast<const proj_f16x8 *>(&res.hi[i][jb]), Bx[jb], yh, 0, 0, 0);
-                ym = __builtin_amdgcn_mfma_f32_16x16x32_f16(*reinterpret_cast<const proj_f16x8 *>(&res.mid[i][jb]), Bx[jb], ym, 0, 0, 0);
-                if constexpr (F32IN)
-                    ym = __builtin_amdgcn_mfma_f32_16x16x32_f16(*reinterpret_cast<const proj_f16x8 *>(&res.hi[i][jb]), Bm[jb], ym, 0, 0, 0);
+                Bx[jb] = *reinterpret_cast<const proj_f16x8 *>(xt + (size_t)v * STRIDE + 32 * jb + 8 * kb);
+                if constexpr (F32) Bm[jb] = *reinterpret_cast<const proj_f16x8 *>(xmt + (size_t)v * STRIDE + 32 * jb + 8 * kb);
             }
-            // element jj of this lane: bit 16 bb + 4 kb + jj of vector v.  The sign is read off the float's bit pattern:
-            // -0.0 would come out wrong, but a zero lies inside every band and is recomputed.
-            const int bb = wave + 4 * i;
-            float y[4], margin[4];
-            uint32_t sbits = 0u;
+            const float band = band_s[buf][v];
+            const size_t my_src = src_s[sb][v];
+            const bool live = my_src != kProjNoRow;
+            // the wave's blocks as 32-bit words: block i sits in half i & 1 of word i >> 1; this lane's nibble at 4 kb
+            uint32_t sw0 = 0u, sw1 = 0u, uw0 = 0u, uw1 = 0u;
 #pragma unroll
-            for (int jj = 0; jj < 4; ++jj) {
-                y[jj] = fmaf(ym[jj], 0.000244140625f, yh[jj]);
-                margin[jj] = fmaf(-res.g[i][jj], band, fabsf(y[jj]));      // one rounding: positive only if |y| > g band
-                sbits |= (__float_as_uint(y[jj]) >> 31) << jj;
-            }
-            sbits ^= 0xFu;
-            const float worst = fminf(fminf(margin[0], margin[1]), fminf(margin[2], margin[3]));
-            if (live) {
-                const int sh = 16 * (bb & 1) + 4 * kb;
-                atomicOr(&w32[v * 16 + (bb >> 1)], sbits << sh);
-                if (!(worst > 0.0f)) {                                     // rare; also catches a NaN
+            for (int i = 0; i < NB; ++i) {
+                if (i >= W) break;                                         // uniform
+                proj_f32x4 yh = {0.f, 0.f, 0.f, 0.f}, ym = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int jb = 0; jb < NJ; ++jb) {
+                    yh = __builtin_amdgcn_mfma_f32_16x16x32_f16(*reinterpret_cast<const proj_f16x8 *>(&res.hi[i][jb]), Bx[jb], yh, 0, 0, 0);
+                    ym = __builtin_amdgcn_mfma_f32_16x16x32_f16(*reinterpret_cast<const proj_f16x8 *>(&res.mid[i][jb]), Bx[jb], ym, 0, 0, 0);
+                    if constexpr (F32)
+                        ym = __builtin_amdgcn_mfma_f32_16x16x32_f16(*reinterpret_cast<const proj_f16x8 *>(&res.hi[i][jb]), Bm[jb], ym, 0, 0, 0);
+                }
+                // element jj of this lane: bit 16 (wave W + i) + 4 kb + jj of vector v.  The sign is read off the float's
+                // bit pattern: -0.0 would come out wrong, but a zero lies inside every band and is recomputed.
+                float margin[4];
+                uint32_t sbits = 0u;
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) {
+                    const float y = fmaf(ym[jj], 0.000244140625f, yh[jj]);
+                    margin[jj] = fmaf(-res.g[i][jj], band, fabsf(y));      // one rounding: positive only if |y| > g band
+                    sbits |= (__float_as_uint(y) >> 31) << jj;
+                }
+                const int sh = 16 * (i & 1) + 4 * kb;
+                if (i < 2) sw0 |= (sbits ^ 0xFu) << sh;
+                else sw1 |= (sbits ^ 0xFu) << sh;
+                const float worst = fminf(fminf(margin[0], margin[1]), fminf(margin[2], margin[3]));
+                if (__any(live && !(worst > 0.0f))) {                      // uniform, rare; also catches a NaN
                     uint32_t ubits = 0u;
 #pragma unroll
                     for (int jj = 0; jj < 4; ++jj) ubits |= (margin[jj] > 0.0f ? 0u : 1u) << jj;
-                    atomicOr(&unsure[v * 16 + (bb >> 1)], ubits << sh);
+                    if (i < 2) uw0 |= ubits << sh;
+                    else uw1 |= ubits << sh;
+                }
+            }
+            // the four lanes of a vector (kb = 0..3) hold a nibble of every block each: OR them together
+            sw0 = proj_or_rows(sw0);
+            if (NB > 2 && W > 2) sw1 = proj_or_rows(sw1);
+            if (__any(live && (uw0 | uw1) != 0u)) {
+                uw0 = proj_or_rows(uw0);
+                if (NB > 2 && W > 2) uw1 = proj_or_rows(uw1);
+            }
+            if (kb == 0 && live) {
+                uint32_t *out = dst_s[it & 1][v];
+                const T *x = base + my_src;
+                const int bit0 = 16 * wave * W;                            // first sketch bit of this wave's blocks
+#pragma unroll
+                for (int j = 0; j < (NB + 1) / 2; ++j) {
+                    if (2 * j >= W) break;                                 // uniform
+                    uint32_t word = j == 0 ? sw0 : sw1;
+                    const uint32_t mask = j == 0 ? uw0 : uw1;
+                    const int row0 = bit0 + 32 * j;                        // bit p of `word` is row row0 + p of R
+                    if (mask) {
+                        const int slot = atomicAdd(&fixes.n, 1);
+                        if (slot < kProjFixCap) {
+                            fixes.item[slot] = ProjFix{x, out + (row0 >> 5), mask << (row0 & 31), (uint32_t)(row0 >> 5)};
+                        } else {
+                            word = (word & ~mask) | proj_chain_bits<D, T>(pv, row0, mask, x);
+                        }
+                    }
+                    // (the pointer came through LDS: told that it is a global address, the compiler emits global stores --
+                    // flat ones also count as LDS operations, and the next block's wait for its LDS reads would then wait
+                    // for these stores to complete)
+                    if (W == 1) *((__attribute__((address_space(1))) uint16_t *)out + wave) = (uint16_t)word;   // one block per wave: half a word
+                    else *((__attribute__((address_space(1))) uint32_t *)out + (row0 >> 5)) = word;
                 }
             }
         }
     }
-    __syncthreads();
-    between();
-    // ---- words with bits inside the guard band: into the list; recomputed here only when the list is full ----
-    const int W32 = pv.sketch_bits / 32;
-    for (int item = tid; item < tile * W32; item += kProjThreads) {
-        const int v = item / W32, w = item - v * W32;
-        if (!valid(v)) continue;
-        uint32_t m = unsure[v * 16 + w];
-        if (m == 0u) continue;
-        const int slot = atomicAdd(&list.n, 1);
-        if (slot < kProjFixCap) {
-            list.item[slot] = ProjFix{src(v), dst(v) + w, m, (uint32_t)w};
-            continue;
-        }
-        uint32_t cur = w32[v * 16 + w];
-        while (m) {
-            const int p = __ffs(m) - 1;
-            m &= m - 1u;
-            const float y = proj_chain<D>(pv.R + (size_t)(32 * w + p) * D, [&](int j, float *out) {
-                if constexpr (F32IN) {
-                    const float *xv = static_cast<const float *>(src(v)) + j;
-                    const float4 a = *reinterpret_cast<const float4 *>(xv), b = *reinterpret_cast<const float4 *>(xv + 4);
-                    out[0] = a.x; out[1] = a.y; out[2] = a.z; out[3] = a.w; out[4] = b.x; out[5] = b.y; out[6] = b.z; out[7] = b.w;
-                } else {
-                    proj_load8(xs + (size_t)v * stride + j, out);
-                }
-            });
-            cur = y >= 0.0f ? (cur | (1u << p)) : (cur & ~(1u << p));
-        }
-        w32[v * 16 + w] = cur;
-    }
+#undef H1BKV_PROJ_REQUEST_ONE
+#undef H1BKV_PROJ_REQUEST
+#undef H1BKV_PROJ_DEPOSIT_ONE
 }
 
 }  // namespace
