@@ -60,6 +60,68 @@ __device__ __forceinline__ void copy8(const float *src, float *dst) {
     *reinterpret_cast<float4 *>(dst + 4) = *reinterpret_cast<const float4 *>(src + 4);
 }
 
+// Eq.(4) for one 32-channel slice x of a value vector whose quantisation group spans `lanes_per_group` neighbouring lanes
+// (G / 32; all lanes of the wave must call): the group's scale and zero as fp16 bits and the slice's 32 codes, 8 per word.
+__device__ __forceinline__ void quantise_slice(const float (&x)[32], int lanes_per_group, uint32_t (&packed)[4], unsigned short &sh,
+                                               unsigned short &zh) {
+    float mn = x[0], mx = x[0];
+#pragma unroll
+    for (int i = 1; i < 32; ++i) {
+        mn = fminf(mn, x[i]);
+        mx = fmaxf(mx, x[i]);
+    }
+    for (int o = 1; o < lanes_per_group; o <<= 1) {
+        mn = fminf(mn, __shfl_xor(mn, o));
+        mx = fmaxf(mx, __shfl_xor(mx, o));
+    }
+    const float delta = (mx - mn) / 15.0f;
+    sh = __half_as_ushort(__float2half_rn(delta));
+    zh = __half_as_ushort(__float2half_rn(mn));
+    if ((zh & 0x7FFFu) == 0) zh = 0;
+    const float sc = __half2float(__ushort_as_half(sh));
+    const float zp = __half2float(__ushort_as_half(zh));
+    packed[0] = packed[1] = packed[2] = packed[3] = 0u;
+    if (sc != 0.0f) {
+        // Eq.(4)'s code is clamp(rint((x - zero) / scale)) with an IEEE divide.  Fast path: with r = RN(1 / scale),
+        // u = fma(x - zero, r, 2^23) rounds the exact product to an integer in the low mantissa bits of u.  The
+        // product and the rounded quotient each lie within 16 * 2^-24 of the true quotient (codes beyond 0..15 are
+        // clamped on either route), so they can round to different integers only if a half-integer lies within
+        // 2e-6 of the product, i.e. if the product's distance e from its integer is within that of 1/2.  A lane
+        // that sees such an element anywhere in its slice (about one lane in a thousand) redoes the slice with
+        // the divide.  The codes are assembled as w = (w << 4) + bits(u): every bits(u) is 0x4B000000 + code, so the
+        // stray high bits sum to a constant that is subtracted once per word.
+        const float r = 1.0f / sc;
+        float worst = 0.0f;
+#pragma unroll
+        for (int wd = 0; wd < 4; ++wd) {
+            uint32_t w = 0u;
+#pragma unroll
+            for (int i = 7; i >= 0; --i) {
+                const float d = x[8 * wd + i] - zp;
+                const float u = __builtin_fmaf(d, r, 8388608.0f);
+                const float e = __builtin_fmaf(d, r, 8388608.0f - u);      // product minus its integer (exact difference)
+                worst = fmaxf(worst, fabsf(e));
+                const float uc = __builtin_amdgcn_fmed3f(u, 8388608.0f, 8388623.0f);
+                w = (w << 4) + __float_as_uint(uc);
+            }
+            packed[wd] = w - 0xFB000000u;      // sum over i of 0x4B000000 << 4 i, modulo 2^32
+        }
+        if (!(worst < 0.49999f)) {             // also a NaN: the divide decides, as before
+#pragma unroll                                 // (a rolled loop would index x[] dynamically and move it out of the registers)
+            for (int wd = 0; wd < 4; ++wd) {
+                uint32_t w = 0u;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    float q = rintf((x[8 * wd + i] - zp) / sc);
+                    q = fminf(fmaxf(q, 0.0f), 15.0f);
+                    w |= (uint32_t)(int)q << (4 * i);
+                }
+                packed[wd] = w;
+            }
+        }
+    }
+}
+
 // bx, by, gx: the workgroup's tile index, its sequence (index into desc) and the number of workgroups that share
 // the sequence's tiles -- blockIdx.x, blockIdx.y, gridDim.x when the kernel does nothing else.
 // MF: the projections come from the matrix cores and only the bits inside the guard band are recomputed with the
@@ -255,62 +317,9 @@ __device__ __forceinline__ void append_body(const AppendArgs &a, const BatchDesc
 #pragma unroll
                 for (int i = 0; i < 32; ++i) x[i] = 0.0f;
             }
-            float mn = x[0], mx = x[0];
-#pragma unroll
-            for (int i = 1; i < 32; ++i) {
-                mn = fminf(mn, x[i]);
-                mx = fmaxf(mx, x[i]);
-            }
-            for (int o = 1; o < lanes_per_group; o <<= 1) {
-                mn = fminf(mn, __shfl_xor(mn, o));
-                mx = fmaxf(mx, __shfl_xor(mx, o));
-            }
-            const float delta = (mx - mn) / 15.0f;
-            unsigned short sh = __half_as_ushort(__float2half_rn(delta));
-            unsigned short zh = __half_as_ushort(__float2half_rn(mn));
-            if ((zh & 0x7FFFu) == 0) zh = 0;
-            const float sc = __half2float(__ushort_as_half(sh));
-            const float zp = __half2float(__ushort_as_half(zh));
-            uint32_t packed[4] = {0u, 0u, 0u, 0u};
-            if (sc != 0.0f) {
-                // Eq.(4)'s code is clamp(rint((x - zero) / scale)) with an IEEE divide.  Fast path: with r = RN(1 / scale),
-                // u = fma(x - zero, r, 2^23) rounds the exact product to an integer in the low mantissa bits of u.  The
-                // product and the rounded quotient each lie within 16 * 2^-24 of the true quotient (codes beyond 0..15 are
-                // clamped on either route), so they can round to different integers only if a half-integer lies within
-                // 2e-6 of the product, i.e. if the product's distance e from its integer is within that of 1/2.  A lane
-                // that sees such an element anywhere in its slice (about one lane in a thousand) redoes the slice with
-                // the divide.  The codes are assembled as w = (w << 4) + bits(u): every bits(u) is 0x4B000000 + code, so the
-                // stray high bits sum to a constant that is subtracted once per word.
-                const float r = 1.0f / sc;
-                float worst = 0.0f;
-#pragma unroll
-                for (int wd = 0; wd < 4; ++wd) {
-                    uint32_t w = 0u;
-#pragma unroll
-                    for (int i = 7; i >= 0; --i) {
-                        const float d = x[8 * wd + i] - zp;
-                        const float u = __builtin_fmaf(d, r, 8388608.0f);
-                        const float e = __builtin_fmaf(d, r, 8388608.0f - u);      // product minus its integer (exact difference)
-                        worst = fmaxf(worst, fabsf(e));
-                        const float uc = __builtin_amdgcn_fmed3f(u, 8388608.0f, 8388623.0f);
-                        w = (w << 4) + __float_as_uint(uc);
-                    }
-                    packed[wd] = w - 0xFB000000u;      // sum over i of 0x4B000000 << 4 i, modulo 2^32
-                }
-                if (!(worst < 0.49999f)) {             // also a NaN: the divide decides, as before
-#pragma unroll                                 // (a rolled loop would index x[] dynamically and move it out of the registers)
-                    for (int wd = 0; wd < 4; ++wd) {
-                        uint32_t w = 0u;
-#pragma unroll
-                        for (int i = 0; i < 8; ++i) {
-                            float q = rintf((x[8 * wd + i] - zp) / sc);
-                            q = fminf(fmaxf(q, 0.0f), 15.0f);
-                            w |= (uint32_t)(int)q << (4 * i);
-                        }
-                        packed[wd] = w;
-                    }
-                }
-            }
+            uint32_t packed[4];
+            unsigned short sh, zh;
+            quantise_slice(x, lanes_per_group, packed, sh, zh);
             if (valid) {
                 const size_t rec = dst[rl];
                 if (pv.code_layout == 0) {
@@ -361,6 +370,59 @@ __global__ __launch_bounds__(kThreads, MF ? 4 : 1) void append_kernel(AppendArgs
 template <int D, typename T>
 __global__ __launch_bounds__(kThreads, 6) void append_values_kernel(AppendArgs a, BatchDesc desc, int tile) {
     append_body<D, T, false, false, kValues>(a, desc, tile, blockIdx.x, blockIdx.y, gridDim.x);
+}
+
+// The values' half for the record-major layouts (4-bit codes per record, or fp16 values): a plain stream -- one lane per
+// (record slot, 32-channel slice) in the slot order of append_body, no LDS and no barrier; the latency of the page lookup
+// and of the value rows is covered by the number of waves in flight.
+template <int D, typename T>
+__global__ __launch_bounds__(kThreads) void append_values_stream_kernel(AppendArgs a, BatchDesc desc) {
+    constexpr int LPT = D / 32;
+    const PoolView &pv = a.pool;
+    const SeqDesc sd = desc.s[blockIdx.y];
+    const int H = pv.n_kv_heads, G = pv.group_size, ng = D / G, lanes_per_group = G / 32;
+    const int off8 = sd.pos & 7, L = (off8 + a.n_new + 7) & ~7;
+    const int n_items = L * H * LPT;
+    const T *vbase = static_cast<const T *>(a.v) + (size_t)blockIdx.y * a.stride_seq;
+    // whole waves run the loop (the quantiser exchanges minima between the lanes of a group)
+    for (int item = blockIdx.x * kThreads + threadIdx.x; item < ((n_items + 63) & ~63); item += gridDim.x * kThreads) {
+        const int slot = item / LPT, slice = item % LPT;
+        const int head = slot / L, t = slot % L - off8;
+        const bool valid = item < n_items && t >= 0 && t < a.n_new;
+        float x[32];
+        size_t rec = 0;
+        if (valid) {
+            const int pos = sd.pos + t;
+            const int page = pv.block_table[(size_t)sd.seq_id * pv.max_pages_per_seq + pos / kPage];
+            rec = ((size_t)page * H + head) * kPage + pos % kPage;
+            const T *src = vbase + (size_t)t * a.stride_tok + (size_t)head * a.stride_head + slice * 32;
+#pragma unroll
+            for (int i = 0; i < 32; i += 8) load8(src + i, x + i);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 32; ++i) x[i] = 0.0f;
+        }
+        if (pv.code_layout == 2) {                      // fp16-value variant: the value rounded to nearest-even fp16
+            if (valid) {
+                __half *values = reinterpret_cast<__half *>(pv.codes) + rec * D + slice * 32;
+#pragma unroll
+                for (int i = 0; i < 32; i += 8) {
+                    __half2 h[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) h[e] = __halves2half2(__float2half_rn(x[i + 2 * e]), __float2half_rn(x[i + 2 * e + 1]));
+                    *reinterpret_cast<uint4 *>(values + i) = *reinterpret_cast<const uint4 *>(h);
+                }
+            }
+            continue;                                   // (uniform: the layout is a property of the cache)
+        }
+        uint32_t packed[4];
+        unsigned short sh, zh;
+        quantise_slice(x, lanes_per_group, packed, sh, zh);
+        if (valid) {
+            *reinterpret_cast<uint4 *>(pv.codes + rec * (D / 2) + slice * 16) = make_uint4(packed[0], packed[1], packed[2], packed[3]);
+            if (slice % lanes_per_group == 0) pv.meta[rec * ng + slice / lanes_per_group] = (uint32_t)sh | ((uint32_t)zh << 16);
+        }
+    }
 }
 
 // The keys' half on its own, with the pieces of R resident in registers (resident_sketch_tiles in projection_mfma.h):
@@ -472,6 +534,8 @@ hipError_t launch_append(const AppendArgs &a, const BatchDesc &desc, int n_seqs,
                        (D == 64 ? proj_resident_fits<64>(a.pool.sketch_bits) : D == 128 && proj_resident_fits<128>(a.pool.sketch_bits));
     const long max_keys_x = 768 / n_seqs > 0 ? 768 / n_seqs : 1;
     const dim3 grid_keys((unsigned)(key_tiles < max_keys_x ? key_tiles : max_keys_x), (unsigned)n_seqs);
+    const long stream_blocks = (n_slots * (D / 32) + kThreads - 1) / kThreads;
+    const dim3 grid_stream((unsigned)(stream_blocks < 32768 ? stream_blocks : 32768), (unsigned)n_seqs);
     const QueryArgs qargs = qa ? *qa : QueryArgs{nullptr, nullptr, 0};
 #define H1BKV_LAUNCH(DD, TT)                                                                                        \
     do {                                                                                                            \
@@ -483,7 +547,10 @@ hipError_t launch_append(const AppendArgs &a, const BatchDesc &desc, int n_seqs,
     do {                                                                                                               \
         if (split) {                                                                                                   \
             hipLaunchKernelGGL((append_keys_kernel<DD, TT>), grid_keys, dim3(kThreads), 0, st, a, desc);               \
-            hipLaunchKernelGGL((append_values_kernel<DD, TT>), grid, dim3(kThreads), 0, st, a, desc, (int)tile);       \
+            if (a.pool.code_layout == 1)                                                                               \
+                hipLaunchKernelGGL((append_values_kernel<DD, TT>), grid, dim3(kThreads), 0, st, a, desc, (int)tile);   \
+            else                                                                                                       \
+                hipLaunchKernelGGL((append_values_stream_kernel<DD, TT>), grid_stream, dim3(kThreads), 0, st, a, desc); \
         } else {                                                                                                       \
             hipLaunchKernelGGL((append_kernel<DD, TT, true>), grid, dim3(kThreads), 0, st, a, desc, (int)tile);        \
         }                                                                                                              \
