@@ -24,6 +24,8 @@
 // few times per chunk) -- and feeds the matrix cores; no workgroup barrier and no pass over the sketches ahead of
 // the values.  The four waves' (max, sum, accumulators) meet once, in the epilogue.  The partial-result format is
 // that of the vector-ALU kernel, so qsketch_kernel and merge_kernel serve both.
+#include <type_traits>
+
 #include "decode_common.h"
 
 namespace h1bkv {
@@ -66,7 +68,10 @@ __device__ __forceinline__ float half32_sum(float x) {            // over the 32
 }
 
 // RQH = 2: up to 4 query heads per workgroup (rows 0-3 high parts, 4-7 low parts); RQH = 4: up to 8 (0-7, 8-15).
-template <int RQH, int D, int NG>
+// W: sketch words per token, a compile-time choice: with the width known only at run time the refill of the sketch
+// registers sat behind branches, the registers they merge into were copied right after the loads, and that copy waited
+// for every load in flight -- once per page.
+template <int RQH, int D, int NG, int W>
 __global__ __launch_bounds__(kThreads, RQH == 2 ? 3 : 2) void decode_split_mfma_kernel(DecodeArgs a, BatchDesc desc, int seq0, int RQ) {
     constexpr int RQMAX = 2 * RQH;
     constexpr int NROWS = 2 * RQMAX;              // operand rows in use
@@ -92,7 +97,7 @@ __global__ __launch_bounds__(kThreads, RQH == 2 ? 3 : 2) void decode_split_mfma_
     const int n_pages = (n_tok + kPage - 1) / kPage;
 
     const PoolView &pv = a.pool;
-    const int H = pv.n_kv_heads, r = pv.n_q_heads / H, W = pv.sketch_bits >> 6;
+    const int H = pv.n_kv_heads, r = pv.n_q_heads / H;
     const int passes = r / RQ;
     const int kvh = blockIdx.y / passes;
     const int qh0 = kvh * r + (blockIdx.y % passes) * RQ;
@@ -162,8 +167,11 @@ __global__ __launch_bounds__(kThreads, RQH == 2 ? 3 : 2) void decode_split_mfma_
         for (int g = 0; g < NG; ++g) pr.m[t][g] = load_stream(mp + g);
     };
 
-    auto consume_page = [&](PageRegs<NCB4, NG> &pr, int pg) {
-        const bool more = pg + 1 < n_pages;
+    // more_tag: whether a page follows (std::true_type / std::false_type).  A compile-time choice, so that the refills are
+    // straight-line code: the compiler then counts the loads in flight exactly and waits for the oldest only; behind a
+    // run-time branch it waits for all of them.
+    auto consume_page = [&](PageRegs<NCB4, NG> &pr, int pg, auto more_tag) {
+        constexpr bool more = decltype(more_tag)::value;
         // ---- scores of this lane's two tokens against its query heads (Eq. 3) ----
         int ham[2][RQH], pmin[RQH];
         bool valid[2];
@@ -184,7 +192,7 @@ __global__ __launch_bounds__(kThreads, RQH == 2 ? 3 : 2) void decode_split_mfma_
             }
             pmin[qq] = half_wave_min(min(ham[0][qq], ham[1][qq]));
         }
-        if (more) load_sketches(pr, pg + 1);
+        if constexpr (more) load_sketches(pr, pg + 1);
         // ---- running maximum: rescale what has been accumulated if this page raises it ----
         bool changed = false;
 #pragma unroll
@@ -263,7 +271,7 @@ __global__ __launch_bounds__(kThreads, RQH == 2 ? 3 : 2) void decode_split_mfma_
                 }
                 accsum[g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, ones.v, accsum[g], 0, 0, 0);
             }
-            if (more) load_step(pr, pg + 1, t);
+            if constexpr (more) load_step(pr, pg + 1, t);
             // the next step overwrites the operands: its writes must not pass these reads
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
@@ -275,7 +283,8 @@ __global__ __launch_bounds__(kThreads, RQH == 2 ? 3 : 2) void decode_split_mfma_
         load_sketches(pr, 0);
         load_step(pr, 0, 0);
         load_step(pr, 0, 1);
-        for (int pg = 0; pg < n_pages; ++pg) consume_page(pr, pg);
+        for (int pg = 0; pg + 1 < n_pages; ++pg) consume_page(pr, pg, std::true_type{});
+        consume_page(pr, n_pages - 1, std::false_type{});
     }
 
     // ---------------- Epilogue: the four waves meet ----------------
@@ -330,14 +339,24 @@ __global__ __launch_bounds__(kThreads, RQH == 2 ? 3 : 2) void decode_split_mfma_
     }
 }
 
+template <int RQH, int D, int NG>
+hipError_t launch_w(const DecodeArgs &a, const BatchDesc &desc, int seq0, dim3 grid, int rq, hipStream_t st) {
+    switch (a.pool.sketch_bits) {
+        case 64: hipLaunchKernelGGL((decode_split_mfma_kernel<RQH, D, NG, 1>), grid, dim3(kThreads), 0, st, a, desc, seq0, rq); break;
+        case 128: hipLaunchKernelGGL((decode_split_mfma_kernel<RQH, D, NG, 2>), grid, dim3(kThreads), 0, st, a, desc, seq0, rq); break;
+        case 256: hipLaunchKernelGGL((decode_split_mfma_kernel<RQH, D, NG, 4>), grid, dim3(kThreads), 0, st, a, desc, seq0, rq); break;
+        default: return hipErrorInvalidValue;      // see mfma_decode_supported
+    }
+    return hipGetLastError();
+}
+
 template <int RQH, int D>
 hipError_t launch_ng(const DecodeArgs &a, const BatchDesc &desc, int seq0, dim3 grid, int rq, hipStream_t st) {
     const int ng = D / a.pool.group_size;
-    if (ng == 1) hipLaunchKernelGGL((decode_split_mfma_kernel<RQH, D, 1>), grid, dim3(kThreads), 0, st, a, desc, seq0, rq);
-    else if (ng == 2) hipLaunchKernelGGL((decode_split_mfma_kernel<RQH, D, 2>), grid, dim3(kThreads), 0, st, a, desc, seq0, rq);
-    else if (ng == 4) hipLaunchKernelGGL((decode_split_mfma_kernel<RQH, D, 4>), grid, dim3(kThreads), 0, st, a, desc, seq0, rq);
-    else return hipErrorInvalidValue;
-    return hipGetLastError();
+    if (ng == 1) return launch_w<RQH, D, 1>(a, desc, seq0, grid, rq, st);
+    if (ng == 2) return launch_w<RQH, D, 2>(a, desc, seq0, grid, rq, st);
+    if (ng == 4) return launch_w<RQH, D, 4>(a, desc, seq0, grid, rq, st);
+    return hipErrorInvalidValue;
 }
 
 template <int RQH>
