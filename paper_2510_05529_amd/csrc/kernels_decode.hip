@@ -178,14 +178,25 @@ __global__ __launch_bounds__(kThreads, RQ >= 4 ? 2 : 1) void decode_split_kernel
     [[maybe_unused]] PageRegs<W, LPT> B;
     load_page(A, 0);
     if constexpr (kDoubleBuffer) {
+        // The last page is consumed in a copy of the code without a prefetch in front of it: with the prefetch behind a
+        // run-time branch, the compiler must assume at the join that it did not happen, waits for the current page's
+        // registers as if they were the youngest loads, and so waits for most of the prefetch it has just issued.
         int pg = 0;
         while (true) {
-            if (pg + 1 < n_pages) load_page(B, pg + 1);
+            if (pg + 1 >= n_pages) {
+                consume_page(A, pg);
+                break;
+            }
+            load_page(B, pg + 1);
             consume_page(A, pg);
-            if (++pg >= n_pages) break;
-            if (pg + 1 < n_pages) load_page(A, pg + 1);
+            ++pg;
+            if (pg + 1 >= n_pages) {
+                consume_page(B, pg);
+                break;
+            }
+            load_page(A, pg + 1);
             consume_page(B, pg);
-            if (++pg >= n_pages) break;
+            ++pg;
         }
     } else {
         for (int pg = 0; pg < n_pages; ++pg) {
