@@ -229,6 +229,8 @@ int h1bkv_extend_seq(h1bkv_cache *c, int32_t seq_id, int32_t n_new, void *hip_st
  * h1bkv_profile_read waits for the recorded events and writes the elapsed milliseconds of each recorded launch
  * of `kernel` to ms_out (at most cap values) and their number to n_out, then clears that kind's records.
  * capacity == 0 disables recording and releases the events.
+ * A kind whose work takes two kernels (H1BKV_K_APPEND of a large append: the keys' half and the values' half;
+ * H1BKV_K_PREFILL with a context split: the attention kernel and its merge) is bracketed once around both.
  */
 enum { H1BKV_K_APPEND = 0, H1BKV_K_QSKETCH = 1, H1BKV_K_DECODE_SPLIT = 2, H1BKV_K_MERGE = 3, H1BKV_K_PREFILL = 4,
        H1BKV_K_COUNT = 5 };
