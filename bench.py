@@ -55,10 +55,10 @@ def parse_args():
     return ap.parse_args()
 
 
-def traffic_from_profiles(workload: str):
-    """HBM bytes per decode_split launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE, calibrated
+def traffic_from_profiles(workload: str, stem: str = "decode_split_{}_pmc.txt"):
+    """HBM bytes per launch of the dominant kernel(s) measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE, calibrated
     against the copy kernel), if the committed summary for this workload has them."""
-    path = os.path.join(ROOT, "profiles", f"decode_split_{workload}_pmc.txt")
+    path = os.path.join(ROOT, "profiles", stem.format(workload))
     if not os.path.exists(path):
         return None
     m = re.search(r"^traffic_bytes_per_launch\s*[:=]\s*([0-9.eE+]+)", open(path).read(), re.M)
@@ -184,7 +184,8 @@ def bench_append(args, torch, B, wl, w, workers):
     hbm_gbps = bytes_moved / (kernel_ms * 1e-3) / 1e9
     # (a prompt-sized append runs as two launches, the keys' half and the values' half; kernel_ms is their sum)
     roof = ({"bound": "hbm", "kernel": "append_keys_kernel + append_values_stream_kernel", "achieved": hbm_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-             "frac": hbm_gbps / HBM_PEAK_GBPS, "traffic": None, "kernel_ms": kernel_ms, "algorithmic_bytes_per_launch": bytes_moved,
+             "frac": hbm_gbps / HBM_PEAK_GBPS, "traffic": traffic_from_profiles(w.name, "append_kernel_{}.txt") if w.dtype == "f16" else None,
+             "kernel_ms": kernel_ms, "algorithmic_bytes_per_launch": bytes_moved,
              "projection_TFLOPs": chain_tflops, "projection_vs_fp32_vector_peak": chain_tflops / FP32_VALU_PEAK_TFLOPS}
             if mfma_path else
             {"bound": "alu", "kernel": "append_kernel", "achieved": chain_tflops, "peak": FP32_VALU_PEAK_TFLOPS, "unit": "TFLOP/s",
