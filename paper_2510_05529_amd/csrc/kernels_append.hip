@@ -87,14 +87,14 @@ __device__ __forceinline__ void quantise_slice(const float (&x)[32], int lanes_p
         // product and the rounded quotient each lie within 16 * 2^-24 of the true quotient (codes beyond 0..15 are
         // clamped on either route), so they can round to different integers only if a half-integer lies within
         // 2e-6 of the product, i.e. if the product's distance e from its integer is within that of 1/2.  A lane
-        // that sees such an element anywhere in its slice (about one lane in a thousand) redoes the slice with
-        // the divide.  The codes are assembled as w = (w << 4) + bits(u): every bits(u) is 0x4B000000 + code, so the
-        // stray high bits sum to a constant that is subtracted once per word.
+        // that sees such an element in a word of 8 codes redoes that word with the divide.  The codes are assembled as
+        // w = (w << 4) + bits(u): every bits(u) is 0x4B000000 + code, so the stray high bits sum to a constant that is
+        // subtracted once per word.
         const float r = 1.0f / sc;
-        float worst = 0.0f;
 #pragma unroll
         for (int wd = 0; wd < 4; ++wd) {
             uint32_t w = 0u;
+            float worst = 0.0f;
 #pragma unroll
             for (int i = 7; i >= 0; --i) {
                 const float d = x[8 * wd + i] - zp;
@@ -104,20 +104,19 @@ __device__ __forceinline__ void quantise_slice(const float (&x)[32], int lanes_p
                 const float uc = __builtin_amdgcn_fmed3f(u, 8388608.0f, 8388623.0f);
                 w = (w << 4) + __float_as_uint(uc);
             }
-            packed[wd] = w - 0xFB000000u;      // sum over i of 0x4B000000 << 4 i, modulo 2^32
-        }
-        if (!(worst < 0.49999f)) {             // also a NaN: the divide decides, as before
-#pragma unroll                                 // (a rolled loop would index x[] dynamically and move it out of the registers)
-            for (int wd = 0; wd < 4; ++wd) {
-                uint32_t w = 0u;
-#pragma unroll
+            w -= 0xFB000000u;                      // sum over i of 0x4B000000 << 4 i, modulo 2^32
+            // The redo is per word of 8 codes, not per slice: fp16 inputs put quotients EXACTLY on half-integers often
+            // enough (a few in ten thousand elements) that half of all waves hold such an element somewhere.
+            if (!(worst < 0.49999f)) {             // also a NaN: the divide decides
+                w = 0u;
+#pragma unroll                                     // (a rolled loop would index x[] dynamically and move it out of the registers)
                 for (int i = 0; i < 8; ++i) {
                     float q = rintf((x[8 * wd + i] - zp) / sc);
                     q = fminf(fmaxf(q, 0.0f), 15.0f);
                     w |= (uint32_t)(int)q << (4 * i);
                 }
-                packed[wd] = w;
             }
+            packed[wd] = w;
         }
     }
 }
