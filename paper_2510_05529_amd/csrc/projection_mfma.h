@@ -440,8 +440,6 @@ __device__ __forceinline__ void resident_sketch_tiles(const PoolView &pv, const 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = lane & 15, kb = lane >> 4;
     const int W = pv.sketch_bits >> 6;
     const int pre_row = tid * 8 / D, pre_ch = tid * 8 % D;  // this thread's pieces: elements [pre_ch, pre_ch + 8) of rows pre_row + k RPP
-    ProjResident<D> res;
-    load_resident<D, F32>(pv, res);
     if (tid == 0) fixes.n = 0;
     // (named registers, not an array: an array of these stayed in scratch memory.  Empty slots read the first vector:
     // no branch around a load -- the compiler makes every load behind a branch wait for the ones before it.)
@@ -480,6 +478,9 @@ __device__ __forceinline__ void resident_sketch_tiles(const PoolView &pv, const 
         if (tid < kProjTile && src_s[0][tid] != kProjNoRow) page = rows.page_request(t, tid);
         if constexpr (!F32) H1BKV_PROJ_REQUEST(0);
     }
+    // (after the first tile's requests: the two round trips overlap, which is most of a short launch's time)
+    ProjResident<D> res;
+    load_resident<D, F32>(pv, res);
     for (int it = 0;; t += step, ++it) {
         const bool more = t < n_tiles;
         if (!more || it % kProjDrainEvery == kProjDrainEvery - 1) {
