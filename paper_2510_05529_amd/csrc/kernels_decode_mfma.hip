@@ -144,12 +144,12 @@ __global__ __launch_bounds__(kThreads, RQH == 2 ? 3 : 2) void decode_split_mfma_
         for (int t = 0; t < 2; ++t) {
             const uint64_t *sp = pv.sketch + (base + 32 * t + tk) * W;
             if (W == 1) {
-                pr.sk[t][0] = load_stream(sp);
+                pr.sk[t][0] = *sp;
             } else {
 #pragma unroll
                 for (int w = 0; w < kMaxW; w += 2) {
                     if (w < W) {
-                        const uint4 v = load_stream(reinterpret_cast<const uint4 *>(sp + w));
+                        const uint4 v = *reinterpret_cast<const uint4 *>(sp + w);
                         pr.sk[t][w] = (uint64_t)v.x | ((uint64_t)v.y << 32);
                         pr.sk[t][w + 1] = (uint64_t)v.z | ((uint64_t)v.w << 32);
                     }
