@@ -232,8 +232,9 @@ __device__ __forceinline__ void project_tile_mfma(const PoolView &pv, const __ha
 //  * A wave assembles the 16-bit blocks it owns with two lane exchanges and stores them straight to global memory: no
 //    LDS words, no atomics, no zeroing.
 //  * Words with bits inside the guard band are not recomputed on the spot (one lane walking a chain of dependent loads
-//    while its workgroup waits) but entered into an LDS list that all threads drain together every 16 tiles, patching
-//    the stored words with atomics; a full list falls back to recomputing on the spot.
+//    while its workgroup waits) but entered into an LDS list that all threads drain together -- looked at every 16 tiles,
+//    drained when half full and after the last tile -- patching the stored words with atomics; a full list falls back to
+//    recomputing on the spot.
 // Rows (the caller's description of its tiles of up to 64 vectors; tile indices are the caller's):
 //   int rows_in(long tile)                      number of row slots of the tile
 //   size_t src(long tile, int rl)               element offset of the vector from `base`, or kProjNoRow for an empty slot
@@ -319,7 +320,7 @@ struct ProjFix {
     uint32_t word;         // index of the word within the sketch: its bits are rows 32 word .. 32 word + 31 of R
 };
 constexpr int kProjFixCap = 256;
-constexpr int kProjDrainEvery = 16;    // tiles between two drains: about 4 entries per tile at d = b = 128
+constexpr int kProjDrainEvery = 16;    // tiles between two looks at the list (a barrier each): about 4 entries per tile at d = b = 128
 struct ProjFixList {
     int n;                 // entries requested so far (may run past the capacity: those were recomputed on the spot)
     ProjFix item[kProjFixCap];
