@@ -454,7 +454,7 @@ __global__ __launch_bounds__(kThreads, 3) void append_keys_kernel(AppendArgs a, 
     const int off8 = sd.pos & 7, L = (off8 + a.n_new + 7) & ~7, n_slots = L * a.pool.n_kv_heads;
     const KeyRows rows{a, sd, L, off8, n_slots};
     resident_sketch_tiles<D, T>(a.pool, static_cast<const T *>(a.k) + (size_t)blockIdx.y * a.stride_seq, rows, (long)blockIdx.x,
-                                (long)gridDim.x, (long)((n_slots + kTile - 1) / kTile));
+                                (long)gridDim.x, (long)((n_slots + kTile - 1) / kTile), (int)blockIdx.z, (int)gridDim.z);
 }
 
 // Prologue of a fused decode step: rows [0, n_seqs) of the grid append the step's new token of each sequence,
@@ -529,10 +529,11 @@ hipError_t launch_append(const AppendArgs &a, const BatchDesc &desc, int n_seqs,
     // Large appends whose sketch width allows resident pieces of R run as two launches: the keys' half with three
     // long-lived workgroups per compute unit (768, all in one round), the values' half as a stream of short ones.
     const long key_tiles = (n_slots + kTile - 1) / kTile;
-    const bool split = a.proj_mfma && !qa && key_tiles * n_seqs >= 768 &&
-                       (D == 64 ? proj_resident_fits<64>(a.pool.sketch_bits) : D == 128 && proj_resident_fits<128>(a.pool.sketch_bits));
-    const long max_keys_x = 768 / n_seqs > 0 ? 768 / n_seqs : 1;
-    const dim3 grid_keys((unsigned)(key_tiles < max_keys_x ? key_tiles : max_keys_x), (unsigned)n_seqs);
+    // (a sketch wider than one workgroup's resident pieces is cut into parts, each with workgroups of its own)
+    const int parts = D == 64 ? proj_resident_parts<64>(a.pool.sketch_bits) : D == 128 ? proj_resident_parts<128>(a.pool.sketch_bits) : 0;
+    const bool split = a.proj_mfma && !qa && parts > 0 && key_tiles * n_seqs * parts >= 768;
+    const long max_keys_x = split && 768 / (n_seqs * parts) > 0 ? 768 / (n_seqs * parts) : 1;
+    const dim3 grid_keys((unsigned)(key_tiles < max_keys_x ? key_tiles : max_keys_x), (unsigned)n_seqs, (unsigned)(parts > 0 ? parts : 1));
     const long stream_blocks = (n_slots * (D / 32) + kThreads - 1) / kThreads;
     const dim3 grid_stream((unsigned)(stream_blocks < 32768 ? stream_blocks : 32768), (unsigned)n_seqs);
     const QueryArgs qargs = qa ? *qa : QueryArgs{nullptr, nullptr, 0};

@@ -586,7 +586,7 @@ __global__ __launch_bounds__(kThreads, 3) void sketch_rows_resident_kernel(Prefi
     const long n_vec = (long)n_seqs * a.n_q * a.pool.n_q_heads;
     const QueryRows rows{a, n_vec};
     resident_sketch_tiles<D, T>(a.pool, static_cast<const T *>(a.q), rows, (long)blockIdx.x, (long)gridDim.x,
-                                (n_vec + kSketchTile - 1) / kSketchTile);
+                                (n_vec + kSketchTile - 1) / kSketchTile, (int)blockIdx.y, (int)gridDim.y);
 }
 
 template <int D, typename T>
@@ -692,8 +692,11 @@ hipError_t launch_sketch_rows(const PrefillArgs &a, int n_seqs, hipStream_t st) 
     if (D != 64 && D != 128) return hipErrorInvalidValue;      // see prefill_supported
     if (a.proj_mfma) {
         const dim3 fine((unsigned)(tiles < 6144 ? tiles : 6144));      // nothing stays resident: short workgroups
-        const dim3 res((unsigned)(tiles < 768 ? tiles : 768));         // resident pieces of R: three long-lived workgroups per compute unit
-        const bool fits = D == 64 ? proj_resident_fits<64>(a.pool.sketch_bits) : proj_resident_fits<128>(a.pool.sketch_bits);
+        // resident pieces of R: three long-lived workgroups per compute unit (768), shared by the parts of a wide sketch
+        const int parts = D == 64 ? proj_resident_parts<64>(a.pool.sketch_bits) : proj_resident_parts<128>(a.pool.sketch_bits);
+        const bool fits = parts > 0;
+        const long res_x = parts > 0 ? 768 / parts : 1;
+        const dim3 res((unsigned)(tiles < res_x ? tiles : res_x), (unsigned)(parts > 0 ? parts : 1));
 #define H1BKV_LAUNCH_MF(DD, TT)                                                                                              \
     do {                                                                                                                     \
         if (fits) hipLaunchKernelGGL((sketch_rows_resident_kernel<DD, TT>), res, dim3(kThreads), 0, st, a, n_seqs);          \

@@ -222,10 +222,11 @@ __device__ __forceinline__ void project_tile_mfma(const PoolView &pv, const __ha
 
 
 // ------------------------------------------------------------------------------------------------------------------
-// Resident form, for d <= 128 and sketches of at most 64 * (256 / d) bits: a whole kernel body.
-//  * A wave keeps the pieces of R for its blocks of 16 bits (blocks wave * W .. wave * W + W - 1, W = b / 64) in
-//    registers for the life of the workgroup (64 registers): a tile costs no loads of R, and each 16-byte read of the
-//    tile from LDS feeds all of the wave's blocks.
+// Resident form, for d <= 128: a whole kernel body.
+//  * A wave keeps the pieces of R for up to 256 / d blocks of 16 bits in registers for the life of the workgroup (64
+//    registers): a tile costs no loads of R, and each 16-byte read of the tile from LDS feeds all of the wave's blocks.
+//    A workgroup so covers 64 * 256 / d sketch bits; wider sketches are cut into `n_parts` parts of that width, each
+//    computed by workgroups of its own (which read the same vectors again: cheaper than re-reading R per tile).
 //  * The next tile's fp16 vectors are requested into registers before the current tile's matrix-core phase and deposited
 //    into the other of two LDS tiles afterwards (the 2-norms are taken from the registers on the way): the stream from
 //    memory does not stop while the workgroup computes, and a tile costs ONE barrier.
@@ -275,19 +276,20 @@ struct ProjResident {
     float g[NB][4];
 };
 
+// Parts a sketch of `sketch_bits` bits is cut into (64 * 256 / D bits per workgroup), 0 if there is no resident form.
 template <int D>
-__host__ __device__ constexpr bool proj_resident_fits(int sketch_bits) {
-    return D <= 128 && sketch_bits / 64 <= 256 / D;
+__host__ __device__ constexpr int proj_resident_parts(int sketch_bits) {
+    return D > 128 ? 0 : (sketch_bits / 64 + 256 / D - 1) / (256 / D);
 }
 
+// W: blocks per wave;  block0: the wave's first block
 template <int D, bool F32IN>
-__device__ __forceinline__ void load_resident(const PoolView &pv, ProjResident<D> &res) {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n = lane & 15, kb = lane >> 4;
-    const int W = pv.sketch_bits >> 6;
+__device__ __forceinline__ void load_resident(const PoolView &pv, ProjResident<D> &res, int W, int block0) {
+    const int lane = threadIdx.x & 63, n = lane & 15, kb = lane >> 4;
     const float *guard = F32IN ? pv.guard + pv.sketch_bits : pv.guard;
 #pragma unroll
     for (int i = 0; i < ProjResident<D>::NB; ++i) {
-        const int bb = wave * W + (i < W ? i : 0);                   // (unused slots repeat a valid block: no branch)
+        const int bb = block0 + (i < W ? i : 0);                     // (unused slots repeat a valid block: no branch)
         const size_t arow = (size_t)(16 * bb + n) * D + 8 * kb;
 #pragma unroll
         for (int jb = 0; jb < D / 32; ++jb) {
@@ -425,9 +427,10 @@ __device__ __forceinline__ void proj_drain(const PoolView &pv, const ProjFixList
     }
 }
 
+// part, n_parts: which part of the sketch bits this workgroup computes (see above).
 template <int D, typename T, typename Rows>
 __device__ __forceinline__ void resident_sketch_tiles(const PoolView &pv, const T *base, const Rows &rows, long first, long step,
-                                                      long n_tiles) {
+                                                      long n_tiles, int part, int n_parts) {
     constexpr bool F32 = sizeof(T) == 4;
     constexpr int STRIDE = D + 8, NJ = D / 32, NB = ProjResident<D>::NB;
     constexpr int NBUF = F32 ? 1 : 2;                       // (two piece tiles per fp32 tile: one buffer, one more barrier)
@@ -439,7 +442,8 @@ __device__ __forceinline__ void resident_sketch_tiles(const PoolView &pv, const 
     __shared__ uint32_t *dst_s[2][kProjTile];
     __shared__ ProjFixList fixes;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = lane & 15, kb = lane >> 4;
-    const int W = pv.sketch_bits >> 6;
+    const int W = (pv.sketch_bits >> 6) / n_parts;          // blocks of 16 bits per wave
+    const int block0 = (4 * part + wave) * W;               // the wave's first block
     const int pre_row = tid * 8 / D, pre_ch = tid * 8 % D;  // this thread's pieces: elements [pre_ch, pre_ch + 8) of rows pre_row + k RPP
     if (tid == 0) fixes.n = 0;
     // (named registers, not an array: an array of these stayed in scratch memory.  Empty slots read the first vector:
@@ -481,7 +485,7 @@ __device__ __forceinline__ void resident_sketch_tiles(const PoolView &pv, const 
     }
     // (after the first tile's requests: the two round trips overlap, which is most of a short launch's time)
     ProjResident<D> res;
-    load_resident<D, F32>(pv, res);
+    load_resident<D, F32>(pv, res, W, block0);
     for (int it = 0;; t += step, ++it) {
         const bool more = t < n_tiles;
         if (!more || it % kProjDrainEvery == kProjDrainEvery - 1) {
@@ -544,7 +548,7 @@ __device__ __forceinline__ void resident_sketch_tiles(const PoolView &pv, const 
                     if constexpr (F32)
                         ym = __builtin_amdgcn_mfma_f32_16x16x32_f16(*reinterpret_cast<const proj_f16x8 *>(&res.hi[i][jb]), Bm[jb], ym, 0, 0, 0);
                 }
-                // element jj of this lane: bit 16 (wave W + i) + 4 kb + jj of vector v.  The sign is read off the float's
+                // element jj of this lane: bit 16 (block0 + i) + 4 kb + jj of vector v.  The sign is read off the float's
                 // bit pattern: -0.0 would come out wrong, but a zero lies inside every band and is recomputed.
                 float margin[4];
                 uint32_t sbits = 0u;
@@ -576,7 +580,7 @@ __device__ __forceinline__ void resident_sketch_tiles(const PoolView &pv, const 
             if (kb == 0 && live) {
                 uint32_t *out = dst_s[it & 1][v];
                 const T *x = base + my_src;
-                const int bit0 = 16 * wave * W;                            // first sketch bit of this wave's blocks
+                const int bit0 = 16 * block0;                              // first sketch bit of this wave's blocks
 #pragma unroll
                 for (int j = 0; j < (NB + 1) / 2; ++j) {
                     if (2 * j >= W) break;                                 // uniform
@@ -594,7 +598,7 @@ __device__ __forceinline__ void resident_sketch_tiles(const PoolView &pv, const 
                     // (the pointer came through LDS: told that it is a global address, the compiler emits global stores --
                     // flat ones also count as LDS operations, and the next block's wait for its LDS reads would then wait
                     // for these stores to complete)
-                    if (W == 1) *((__attribute__((address_space(1))) uint16_t *)out + wave) = (uint16_t)word;   // one block per wave: half a word
+                    if (W == 1) *((__attribute__((address_space(1))) uint16_t *)out + block0) = (uint16_t)word;   // one block per wave: half a word
                     else *((__attribute__((address_space(1))) uint32_t *)out + (row0 >> 5)) = word;
                 }
             }

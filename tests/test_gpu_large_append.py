@@ -14,9 +14,11 @@ from tests.gpu_util import assert_cache_equal, make_cache, to_dev
 
 pytestmark = pytest.mark.gpu
 
-# (head_dim, sketch bits, group size, dtype): the widths with resident pieces (b <= 128 at d = 128, b <= 256 at d = 64),
-# one block of 16 bits per wave (b = 64), four (d = 64, b = 256), both dtypes
-CASES = [(128, 128, 32, "f16"), (128, 64, 64, "f16"), (64, 256, 32, "f16"), (64, 128, 64, "f32"), (128, 128, 128, "f32")]
+# (head_dim, sketch bits, group size, dtype): one block of 16 bits per wave (b = 64), two, four (d = 64, b = 256); sketches
+# wider than one workgroup's resident pieces, cut into two and four parts (b = 256 and 512 at d = 128, b = 512 at d = 64);
+# both dtypes
+CASES = [(128, 128, 32, "f16"), (128, 64, 64, "f16"), (64, 256, 32, "f16"), (64, 128, 64, "f32"), (128, 128, 128, "f32"),
+         (128, 256, 64, "f16"), (128, 512, 32, "f16"), (64, 512, 32, "f32"), (128, 256, 32, "f32")]
 
 
 def _half_step_values(v, g, rng):
