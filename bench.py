@@ -179,17 +179,13 @@ def bench_append(args, torch, B, wl, w, workers):
     bytes_moved = records * (2 * w.head_dim * elt + w.record_bytes)
     chain_tflops = flops / (kernel_ms * 1e-3) / 1e12
     # With the matrix-core projection the fp32 chain's vector-ALU roof no longer binds the kernel; what is left is moving the
-    # inputs and records (and per-tile latencies), so it is priced against HBM.  (fp32 keys at head_dim 256 keep the chain.)
-    mfma_path = w.dtype == "f16" or w.head_dim <= 128
+    # inputs and records (and per-tile latencies), so it is priced against HBM.
     hbm_gbps = bytes_moved / (kernel_ms * 1e-3) / 1e9
     # (a prompt-sized append runs as two launches, the keys' half and the values' half; kernel_ms is their sum)
-    roof = ({"bound": "hbm", "kernel": "append_keys_kernel + append_values_stream_kernel", "achieved": hbm_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-             "frac": hbm_gbps / HBM_PEAK_GBPS, "traffic": traffic_from_profiles(w.name, "append_kernel_{}.txt") if w.dtype == "f16" else None,
-             "kernel_ms": kernel_ms, "algorithmic_bytes_per_launch": bytes_moved,
-             "projection_TFLOPs": chain_tflops, "projection_vs_fp32_vector_peak": chain_tflops / FP32_VALU_PEAK_TFLOPS}
-            if mfma_path else
-            {"bound": "alu", "kernel": "append_kernel", "achieved": chain_tflops, "peak": FP32_VALU_PEAK_TFLOPS, "unit": "TFLOP/s",
-             "frac": chain_tflops / FP32_VALU_PEAK_TFLOPS, "traffic": None, "kernel_ms": kernel_ms, "hbm_GBps": hbm_gbps})
+    roof = {"bound": "hbm", "kernel": "append_keys_kernel + append_values_stream_kernel", "achieved": hbm_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+            "frac": hbm_gbps / HBM_PEAK_GBPS, "traffic": traffic_from_profiles(w.name, "append_kernel_{}.txt") if w.dtype == "f16" else None,
+            "kernel_ms": kernel_ms, "algorithmic_bytes_per_launch": bytes_moved,
+            "projection_TFLOPs": chain_tflops, "projection_vs_fp32_vector_peak": chain_tflops / FP32_VALU_PEAK_TFLOPS}
     extra = {} if args.no_cpu_baseline else {"cpu_baseline": cpu_baseline_prompt(wl, w, w.default_tau(), workers, attend=False)}
     print(json.dumps({
         **extra,

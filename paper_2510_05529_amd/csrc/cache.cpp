@@ -483,9 +483,9 @@ static int enqueue_append(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n
         a.stride_head = stride_head;
         a.n_new = n_new;
         a.f16 = c->cfg.in_dtype == H1BKV_F16;
-        // prefill-sized appends of fp16 keys take the matrix-core projection; short ones (a decode step's single
-        // token) stay on the plain chain, which is launch-bound there anyway
-        a.proj_mfma = n_new >= 16 && c->proj_mfma && (a.f16 || c->cfg.head_dim <= 128);
+        // prefill-sized appends take the matrix-core projection; short ones (a decode step's single token) stay on the
+        // plain chain, which is launch-bound there anyway
+        a.proj_mfma = n_new >= 16 && c->proj_mfma;
         for (int s0 = 0; s0 < n_seqs && rc == H1BKV_OK; s0 += kMaxSeqsPerLaunch) {
             const int n = std::min(kMaxSeqsPerLaunch, n_seqs - s0);
             BatchDesc desc;

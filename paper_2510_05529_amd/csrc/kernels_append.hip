@@ -559,9 +559,10 @@ hipError_t launch_append(const AppendArgs &a, const BatchDesc &desc, int n_seqs,
         if (D == 64) H1BKV_LAUNCH_MF(64, __half);
         else if (D == 128) H1BKV_LAUNCH_MF(128, __half);
         else hipLaunchKernelGGL((append_kernel<256, __half, true>), grid, dim3(kThreads), 0, st, a, desc, (int)tile);
-    } else if (a.proj_mfma && !qa && D <= 128) {      // fp32 keys (d = 256: two piece tiles would not leave room for a second workgroup)
+    } else if (a.proj_mfma && !qa) {                  // fp32 keys
         if (D == 64) H1BKV_LAUNCH_MF(64, float);
-        else H1BKV_LAUNCH_MF(128, float);
+        else if (D == 128) H1BKV_LAUNCH_MF(128, float);
+        else hipLaunchKernelGGL((append_kernel<256, float, true>), grid, dim3(kThreads), 0, st, a, desc, (int)tile);
     } else if (a.f16) {
         if (D == 64) H1BKV_LAUNCH(64, __half);
         else if (D == 128) H1BKV_LAUNCH(128, __half);
