@@ -196,8 +196,8 @@ int h1bkv_prefill_attn(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n_se
 int h1bkv_set_decode_chunk(h1bkv_cache *c, int32_t chunk_tokens);
 
 /*
- * Tuning switch for the key projection of Eq.(2) in prefill-sized h1bkv_append_kv calls (n_new >= 16; fp32 inputs:
- * head_dim <= 128), in h1bkv_prefill_attn's query sketches and in h1bkv_decode_attn's when a call brings thousands of
+ * Tuning switch for the key projection of Eq.(2) in prefill-sized h1bkv_append_kv calls (n_new >= 16), in
+ * h1bkv_prefill_attn's query sketches and in h1bkv_decode_attn's when a call brings thousands of
  * queries: 1 (default) computes the projections on the matrix cores from a two-piece fp16 split of R (and, for fp32
  * inputs, of the vectors, each scaled by a power of two first) and recomputes, with the fp32 multiply-add chain stated
  * at h1bkv_append_kv, every bit whose projection lies inside a guard band around zero that bounds the difference
