@@ -67,6 +67,7 @@ typedef struct {
     int32_t max_seqs, max_pages, max_pages_per_seq;
     int32_t device;
     int32_t value_bits;
+    uint64_t seed;          /* used only when h1bkv_create is given no projection: seed of the library's own draw */
 } h1bkv_config;
 
 /* Library version, major*10000 + minor*100 + patch. */
@@ -89,6 +90,12 @@ size_t h1bkv_pool_bytes(const h1bkv_config *cfg);
  * may be NULL for a bookkeeping-only handle).  R_host [b][d] fp32 is the fixed Gaussian projection of
  * Eq.(2) (Sec. III: R_ij ~ N(0,1), drawn once, shared by keys and queries of every head); it is
  * copied to the device here, synchronously.  All sequences start empty, all pages free.
+ * R_host == NULL: the library draws R itself from cfg->seed -- a splitmix64 stream (state += 0x9E3779B97F4A7C15, then
+ * the two xor-shift-multiply rounds with 0xBF58476D1CE4E5B9 and 0x94D049BB133111EB and a final xor-shift by 31), a
+ * uniform u = ((x >> 11) + 0.5) 2^-53 per draw, and per pair of consecutive elements (2p, 2p+1) of the row-major
+ * array two draws u1, u2 giving sqrt(-2 ln u1) cos(2 pi u2) and sqrt(-2 ln u1) sin(2 pi u2), computed in double and
+ * rounded to fp32.  The values depend on the host's libm in the last place; read what was drawn with
+ * h1bkv_get_projection.
  */
 int h1bkv_create(const h1bkv_config *cfg, void *pool_dev, size_t pool_bytes, const float *R_host,
                  h1bkv_cache **out);
@@ -148,7 +155,12 @@ int h1bkv_decode_attn(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n_seq
  * the two calls (Sec. IV: a generated token's key and value are cached, then its query attends to the cache).
  * The new token's append and the query sketches do not depend on each other and share one kernel launch, so the
  * step costs three launches instead of four.  workspace as for h1bkv_decode_attn with the lengths after the append.
- * Validation covers both halves before anything is changed or enqueued.
+ * Validation covers both halves before anything is changed or enqueued; if a launch of the decode half fails, the
+ * appended token is taken back (lengths and page assignments as before the call).
+ * Under HIP graph capture: token positions, context lengths and page assignments travel in the kernel arguments, so a
+ * captured step is frozen at the position it was captured at -- replaying it rewrites the same slot and attends over
+ * the same length, and the host bookkeeping advanced once, at capture.  A graph is therefore valid for one position
+ * (re-capture per token, or launch eagerly).
  */
 int h1bkv_decode_step(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n_seqs, const void *k_dev,
                       const void *v_dev, int64_t stride_seq, int64_t stride_head, const void *q_dev, float tau,
@@ -204,6 +216,13 @@ int h1bkv_set_decode_chunk(h1bkv_cache *c, int32_t chunk_tokens);
  * between the two evaluations -- the stored bits are those of the chain either way; 0 always runs the chain.
  */
 int h1bkv_set_projection_path(h1bkv_cache *c, int32_t use_matrix_cores);
+
+/*
+ * Test hook for the error paths: the nth kernel launch (nth >= 1) attempted on this handle from now on is not made and
+ * is reported as a failed launch (the call returns H1BKV_EHIP after restoring the bookkeeping); 0 disarms.  A
+ * bookkeeping-only handle counts the launches it would have made.  Nothing faults: the launch is skipped on the host.
+ */
+int h1bkv_debug_fail_launch(h1bkv_cache *c, int32_t nth);
 
 /*
  * Canonical, layout-independent view of cached records (synchronous: waits for the device first).

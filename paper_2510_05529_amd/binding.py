@@ -26,6 +26,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "lib", "libh
 class h1bkv_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_q_heads", "n_kv_heads", "head_dim", "sketch_bits", "group_size", "in_dtype",
                                          "page_tokens", "max_seqs", "max_pages", "max_pages_per_seq", "device", "value_bits")]
+    _fields_ += [("seed", C.c_uint64)]
 
 
 class H1BKVError(RuntimeError):
@@ -70,6 +71,7 @@ def lib() -> C.CDLL:
             "h1bkv_prefill_attn": (C.c_int, [vp, vp, i32, i32, vp, i64, i64, i64, C.c_float, vp, vp, sz, vp]),
             "h1bkv_set_decode_chunk": (C.c_int, [vp, i32]),
             "h1bkv_set_projection_path": (C.c_int, [vp, i32]),
+            "h1bkv_debug_fail_launch": (C.c_int, [vp, i32]),
             "h1bkv_export_tokens": (C.c_int, [vp, i32, i32, i32, i32, vp, vp, vp, vp]),
             "h1bkv_import_tokens": (C.c_int, [vp, i32, i32, i32, i32, vp, vp, vp, vp]),
             "h1bkv_extend_seq": (C.c_int, [vp, i32, i32, vp]),
@@ -212,6 +214,10 @@ def h1bkv_set_projection_path(h, use_matrix_cores: int) -> int:
     return lib().h1bkv_set_projection_path(h, use_matrix_cores)
 
 
+def h1bkv_debug_fail_launch(h, nth: int) -> int:
+    return lib().h1bkv_debug_fail_launch(h, nth)
+
+
 def h1bkv_export_tokens(h, seq_id: int, kv_head: int, t0: int, n: int, W: int, d: int, n_g: int, value_bits: int = 4):
     """Returns (code, sketches [n][W] u64, codes [n][d/2] u8, scale [n][n_g] u16, zero [n][n_g] u16); for a cache
     with fp16 values (value_bits = 16): (code, sketches, values [n][d] u16 fp16 bit patterns, None, None)."""
@@ -273,13 +279,13 @@ class Cache:
     """Convenience owner of a handle plus the torch buffers it needs.  Forwards to the functions above."""
 
     def __init__(self, *, n_q_heads: int, n_kv_heads: int, head_dim: int, sketch_bits: int, group_size: int, dtype: str,
-                 max_seqs: int, max_pages: int, max_pages_per_seq: int, R: np.ndarray, device: int = 0, value_bits: int = 4,
-                 pool_fill: Optional[int] = None):
+                 max_seqs: int, max_pages: int, max_pages_per_seq: int, R: Optional[np.ndarray], device: int = 0,
+                 value_bits: int = 4, pool_fill: Optional[int] = None, seed: int = 0):
         """pool_fill: byte value written over the whole pool before the handle is created (never-written slots then hold
         that pattern instead of whatever the allocator returned)."""
         self.cfg = h1bkv_config(n_q_heads, n_kv_heads, head_dim, sketch_bits, group_size,
                                 H1BKV_F16 if dtype == "f16" else H1BKV_F32, 0, max_seqs, max_pages, max_pages_per_seq, device,
-                                value_bits)
+                                value_bits, seed)
         self.value_bits = value_bits
         self.W, self.d, self.n_g = sketch_bits // 64, head_dim, head_dim // group_size
         self.pool = None

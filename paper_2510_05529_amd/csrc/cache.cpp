@@ -53,28 +53,12 @@ Layout make_layout(const h1bkv_config &c) {
     return L;
 }
 
-// IEEE binary16 <-> binary32 on the host (round to nearest even), for the fp16 pieces of R.
-uint16_t f32_to_f16(float f) {
-    uint32_t x;
-    std::memcpy(&x, &f, 4);
-    const uint16_t sign = (uint16_t)((x >> 16) & 0x8000u);
-    const uint32_t ax = x & 0x7FFFFFFFu;
-    if (ax >= 0x7F800000u) return (uint16_t)(sign | 0x7C00u | (ax > 0x7F800000u ? 0x200u : 0u));
-    if (ax >= 0x477FF000u) return (uint16_t)(sign | 0x7C00u);
-    if (ax <= 0x33000000u) return sign;
-    const int e = (int)(ax >> 23) - 127;
-    const uint32_t m = (ax & 0x7FFFFFu) | 0x800000u;
-    const int shift = e < -14 ? 13 + (-14 - e) : 13;
-    uint32_t kept = m >> shift;
-    const uint32_t rem = m & ((1u << shift) - 1u), half = 1u << (shift - 1);
-    if (rem > half || (rem == half && (kept & 1u))) kept++;
-    const uint32_t out = e < -14 ? kept : ((uint32_t)(e + 15) << 10) + (kept - 0x400u);
-    return (uint16_t)(sign | out);
-}
-double f16_to_f64(uint16_t h) {
-    const int e = (h >> 10) & 0x1F, m = h & 0x3FF;
-    double v = e == 0 ? std::ldexp((double)m, -24) : std::ldexp((double)(m | 0x400), e - 25);
-    return (h & 0x8000u) ? -v : v;
+// fp16 pieces of R are made with the host compiler's own binary16 type: a cast to _Float16 rounds to nearest even,
+// a cast back is exact; the bit pattern is what the device reads.
+inline uint16_t half_bits(_Float16 h) {
+    uint16_t u;
+    std::memcpy(&u, &h, sizeof u);
+    return u;
 }
 
 // Pieces of R for the matrix-core projection and the guard band that keeps the sketch bits exactly those of the
@@ -103,10 +87,12 @@ void make_projection_pieces(const float *R, int b, int d, std::vector<uint16_t> 
         for (int j = 0; j < d; ++j) {
             const size_t e = (size_t)i * d + j;
             const double r = (double)R[e];
-            hi[e] = f32_to_f16(R[e]);
-            const double h = f16_to_f64(hi[e]);
-            mid[e] = f32_to_f16((float)((r - h) * 4096.0));          // r - h is exact in double, and in float after scaling
-            const double m = f16_to_f64(mid[e]);
+            const _Float16 h16 = (_Float16)R[e];
+            const double h = (double)h16;
+            const _Float16 m16 = (_Float16)(float)((r - h) * 4096.0);   // r - h is exact in double, and in float after scaling
+            const double m = (double)m16;
+            hi[e] = half_bits(h16);
+            mid[e] = half_bits(m16);
             const double delta = r - (h + m / 4096.0);
             n2 += r * r;
             delta2 += delta * delta;
@@ -120,6 +106,30 @@ void make_projection_pieces(const float *R, int b, int d, std::vector<uint16_t> 
         const double g32 = 2.0 * (std::sqrt(delta2) + (5.0 * d * std::ldexp(1.0, -24) + std::ldexp(1.0, -21) + std::ldexp(1.0, -22)) * std::sqrt(n2) +
                                   std::sqrt(flush2));
         guard[(size_t)b + i] = std::nextafter((float)g32, INFINITY);
+    }
+}
+
+// Projection drawn by the library when the caller passes none (Sec. III: R_ij ~ N(0,1), fixed once): a splitmix64
+// stream from the seed, two draws per pair of consecutive elements, Box-Muller in double, rounded to fp32.
+struct SplitMix64 {
+    uint64_t s;
+    uint64_t next() {
+        s += 0x9E3779B97F4A7C15ull;
+        uint64_t z = s;
+        z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+        z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+        return z ^ (z >> 31);
+    }
+    double uniform() { return ((double)(next() >> 11) + 0.5) * 0x1p-53; }   // in (0, 1)
+};
+
+void draw_projection(uint64_t seed, std::vector<float> &R) {
+    SplitMix64 g{seed};
+    for (size_t e = 0; e + 1 < R.size(); e += 2) {
+        const double u1 = g.uniform(), u2 = g.uniform();
+        const double rad = std::sqrt(-2.0 * std::log(u1)), ang = 6.283185307179586476925 * u2;
+        R[e] = (float)(rad * std::cos(ang));
+        R[e + 1] = (float)(rad * std::sin(ang));
     }
 }
 
@@ -142,6 +152,7 @@ struct h1bkv_cache {
     std::vector<int32_t> free_list;     // stack of free page ids
     int32_t chunk_override;
     int32_t proj_mfma;     // 1: matrix-core projection where it applies (default); 0: always the plain fp32 chain
+    int32_t fail_countdown;   // test hook: > 0 counts launch attempts down, the one that reaches 0 is skipped and reported failed
     // profiling
     int32_t prof_cap;
     uint32_t prof_mask;
@@ -210,6 +221,10 @@ void release_events(h1bkv_cache *c) {
     c->prof_cap = 0;
 }
 
+// Gate in front of every kernel launch (also the launches a bookkeeping-only handle skips): false when the failure
+// armed with h1bkv_debug_fail_launch falls on this attempt -- the launch is then not made and reported as failed.
+bool launch_allowed(h1bkv_cache *c) { return !(c->fail_countdown > 0 && --c->fail_countdown == 0); }
+
 int pages_for(int32_t len) { return (len + kPage - 1) / kPage; }
 
 // Pages that must be newly taken so that seq can hold new_len tokens, or a negative error.
@@ -232,7 +247,6 @@ void take_pages(h1bkv_cache *c, int32_t seq, int32_t new_len, std::vector<int32_
 }
 
 int publish(h1bkv_cache *c, const std::vector<int32_t> &idx, const std::vector<int32_t> &page, hipStream_t st) {
-    if (c->dry) return H1BKV_OK;
     size_t done = 0;
     while (done < idx.size()) {
         TablePairs tp;
@@ -241,7 +255,8 @@ int publish(h1bkv_cache *c, const std::vector<int32_t> &idx, const std::vector<i
             tp.index[i] = idx[done + i];
             tp.page[i] = page[done + i];
         }
-        if (launch_publish(tp, c->view().block_table, st) != hipSuccess) return H1BKV_EHIP;
+        if (!launch_allowed(c)) return H1BKV_EHIP;
+        if (!c->dry && launch_publish(tp, c->view().block_table, st) != hipSuccess) return H1BKV_EHIP;
         done += tp.n;
     }
     return H1BKV_OK;
@@ -307,7 +322,7 @@ size_t h1bkv_pool_bytes(const h1bkv_config *cfg) {
 }
 
 int h1bkv_create(const h1bkv_config *cfg, void *pool_dev, size_t pool_bytes, const float *R_host, h1bkv_cache **out) {
-    if (!cfg || !R_host || !out) return H1BKV_ENULL;
+    if (!cfg || !out) return H1BKV_ENULL;
     if (!config_ok(cfg)) return H1BKV_ESHAPE;
     const bool dry = cfg->device == H1BKV_DEVICE_NONE;
     Layout lay = make_layout(*cfg);
@@ -329,13 +344,20 @@ int h1bkv_create(const h1bkv_config *cfg, void *pool_dev, size_t pool_bytes, con
     c->dry = dry;
     c->pool = static_cast<char *>(pool_dev);
     const size_t nR = (size_t)cfg->sketch_bits * cfg->head_dim;
-    c->R.assign(R_host, R_host + nR);
+    if (R_host) {
+        c->R.assign(R_host, R_host + nR);
+    } else {
+        c->R.resize(nR);           // nR is even: b is a multiple of 64
+        draw_projection(cfg->seed, c->R);
+    }
+    R_host = c->R.data();
     c->seq_len.assign(cfg->max_seqs, 0);
     c->seq_pages.assign(cfg->max_seqs, {});
     c->free_list.resize(cfg->max_pages);
     for (int i = 0; i < cfg->max_pages; ++i) c->free_list[i] = cfg->max_pages - 1 - i;  // page 0 is taken first
     c->chunk_override = 0;
     c->proj_mfma = 1;
+    c->fail_countdown = 0;
     c->prof_cap = 0;
     c->prof_mask = 0;
     c->prof_stride = 1;
@@ -417,6 +439,13 @@ int h1bkv_set_decode_chunk(h1bkv_cache *c, int32_t chunk_tokens) {
     return H1BKV_OK;
 }
 
+int h1bkv_debug_fail_launch(h1bkv_cache *c, int32_t nth) {
+    if (!c) return H1BKV_ENULL;
+    if (nth < 0) return H1BKV_EINVAL;
+    c->fail_countdown = nth;
+    return H1BKV_OK;
+}
+
 int h1bkv_set_projection_path(h1bkv_cache *c, int32_t use_matrix_cores) {
     if (!c) return H1BKV_ENULL;
     if (use_matrix_cores != 0 && use_matrix_cores != 1) return H1BKV_EINVAL;
@@ -437,9 +466,12 @@ int h1bkv_extend_seq(h1bkv_cache *c, int32_t seq_id, int32_t n_new, void *hip_st
         if (rc != H1BKV_OK) return rc;
     }
     std::vector<int32_t> ui, up;
+    const int32_t old_len = c->seq_len[seq_id];
     take_pages(c, seq_id, (int32_t)new_len, ui, up);
     c->seq_len[seq_id] = (int32_t)new_len;
-    return publish(c, ui, up, static_cast<hipStream_t>(hip_stream));
+    const int rc = publish(c, ui, up, static_cast<hipStream_t>(hip_stream));
+    if (rc != H1BKV_OK) h1bkv_truncate_seq(c, seq_id, old_len);   // pages back, length as before
+    return rc;
 }
 
 // Everything h1bkv_append_kv checks before it touches the bookkeeping.
@@ -475,7 +507,7 @@ static int enqueue_append(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n
     std::vector<int32_t> ui, up;
     for (int i = 0; i < n_seqs; ++i) take_pages(c, seq_ids_host[i], c->seq_len[seq_ids_host[i]] + n_new, ui, up);
     int rc = publish(c, ui, up, st);
-    if (!c->dry && rc == H1BKV_OK) {
+    if (rc == H1BKV_OK) {
         AppendArgs a{};
         a.pool = c->view();
         a.stride_seq = stride_seq;
@@ -490,8 +522,10 @@ static int enqueue_append(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n
             const int n = std::min(kMaxSeqsPerLaunch, n_seqs - s0);
             BatchDesc desc;
             for (int i = 0; i < n; ++i) desc.s[i] = SeqDesc{seq_ids_host[s0 + i], c->seq_len[seq_ids_host[s0 + i]]};
-            a.k = static_cast<const char *>(k_dev) + (size_t)s0 * stride_seq * elt;
-            a.v = static_cast<const char *>(v_dev) + (size_t)s0 * stride_seq * elt;
+            if (!c->dry) {
+                a.k = static_cast<const char *>(k_dev) + (size_t)s0 * stride_seq * elt;
+                a.v = static_cast<const char *>(v_dev) + (size_t)s0 * stride_seq * elt;
+            }
             QueryArgs qa{};
             if (q_dev) {
                 const size_t vec0 = (size_t)s0 * c->cfg.n_q_heads;
@@ -499,8 +533,12 @@ static int enqueue_append(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n
                 qa.q_sketch = q_sketch_dev + vec0 * c->W;
                 qa.n_vec = n * c->cfg.n_q_heads;
             }
-            Timed t(c, H1BKV_K_APPEND, st);
-            if (launch_append(a, desc, n, q_dev ? &qa : nullptr, st) != hipSuccess) rc = H1BKV_EHIP;
+            if (!launch_allowed(c)) {
+                rc = H1BKV_EHIP;
+            } else if (!c->dry) {
+                Timed t(c, H1BKV_K_APPEND, st);
+                if (launch_append(a, desc, n, q_dev ? &qa : nullptr, st) != hipSuccess) rc = H1BKV_EHIP;
+            }
         }
     }
     if (rc != H1BKV_OK) {
@@ -592,11 +630,12 @@ static int enqueue_decode(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n
                 pa.n_q = 1;
                 pa.f16 = a.f16;
                 pa.proj_mfma = 1;
-                if (launch_sketch_rows(pa, n, st) != hipSuccess) return H1BKV_EHIP;
-            } else if (launch_qsketch(a, s0, n, st) != hipSuccess) {
+                if (!launch_allowed(c) || launch_sketch_rows(pa, n, st) != hipSuccess) return H1BKV_EHIP;
+            } else if (!launch_allowed(c) || launch_qsketch(a, s0, n, st) != hipSuccess) {
                 return H1BKV_EHIP;
             }
         }
+        if (!launch_allowed(c)) return H1BKV_EHIP;
         {
             Timed t(c, H1BKV_K_DECODE_SPLIT, st);
             const hipError_t e = c->code_layout == 2   ? launch_decode_split_f16v(a, desc, s0, n, st)
@@ -604,6 +643,7 @@ static int enqueue_decode(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n
                                                        : launch_decode_split(a, desc, s0, n, st);
             if (e != hipSuccess) return H1BKV_EHIP;
         }
+        if (!launch_allowed(c)) return H1BKV_EHIP;
         {
             Timed t(c, H1BKV_K_MERGE, st);
             if (launch_merge(a, desc, s0, n, st) != hipSuccess) return H1BKV_EHIP;
@@ -634,7 +674,13 @@ int h1bkv_decode_step(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n_seq
     rc = enqueue_append(c, seq_ids_host, n_seqs, 1, k_dev, v_dev, stride_seq, 0, stride_head, q_dev,
                         static_cast<uint64_t *>(workspace_dev), st);
     if (rc != H1BKV_OK) return rc;
-    return enqueue_decode(c, seq_ids_host, n_seqs, q_dev, tau, out_dev, workspace_dev, true, st);
+    rc = enqueue_decode(c, seq_ids_host, n_seqs, q_dev, tau, out_dev, workspace_dev, true, st);
+    if (rc != H1BKV_OK) {
+        // the decode half failed to launch: take the appended token back, so that the call has changed no length and no
+        // page assignment (the record written past the old length is invisible and will be overwritten)
+        for (int i = 0; i < n_seqs; ++i) h1bkv_truncate_seq(c, seq_ids_host[i], c->seq_len[seq_ids_host[i]] - 1);
+    }
+    return rc;
 }
 
 size_t h1bkv_decode_dtau_workspace_bytes(const h1bkv_cache *c, int32_t n_seqs, int32_t max_ctx) {
@@ -695,15 +741,15 @@ int h1bkv_decode_attn_dtau(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t 
         for (int i = 0; i < n; ++i) desc.s[i] = SeqDesc{seq_ids_host[s0 + i], c->seq_len[seq_ids_host[s0 + i]]};
         {
             Timed t(c, H1BKV_K_QSKETCH, st);
-            if (launch_qsketch(a, s0, n, st) != hipSuccess) return H1BKV_EHIP;
+            if (!launch_allowed(c) || launch_qsketch(a, s0, n, st) != hipSuccess) return H1BKV_EHIP;
         }
         {
             Timed t(c, H1BKV_K_DECODE_SPLIT, st);
-            if (launch_decode_dtau_split(a, desc, s0, n, st) != hipSuccess) return H1BKV_EHIP;
+            if (!launch_allowed(c) || launch_decode_dtau_split(a, desc, s0, n, st) != hipSuccess) return H1BKV_EHIP;
         }
         {
             Timed t(c, H1BKV_K_MERGE, st);
-            if (launch_merge_dtau(a, desc, s0, n, dtau_scale, st) != hipSuccess) return H1BKV_EHIP;
+            if (!launch_allowed(c) || launch_merge_dtau(a, desc, s0, n, dtau_scale, st) != hipSuccess) return H1BKV_EHIP;
         }
     }
     return H1BKV_OK;
@@ -759,15 +805,15 @@ int h1bkv_prefill_attn(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n_se
     a.exp2_scale = (float)(2.0 * 1.4426950408889634 / ((double)c->cfg.sketch_bits * (double)tau));
     {
         Timed t(c, H1BKV_K_QSKETCH, st);
-        if (launch_sketch_rows(a, n_seqs, st) != hipSuccess) return H1BKV_EHIP;
+        if (!launch_allowed(c) || launch_sketch_rows(a, n_seqs, st) != hipSuccess) return H1BKV_EHIP;
     }
     for (int s0 = 0; s0 < n_seqs; s0 += kMaxSeqsPerLaunch) {
         const int n = std::min(kMaxSeqsPerLaunch, n_seqs - s0);
         BatchDesc desc;
         for (int i = 0; i < n; ++i) desc.s[i] = SeqDesc{seq_ids_host[s0 + i], c->seq_len[seq_ids_host[s0 + i]]};
         Timed t(c, H1BKV_K_PREFILL, st);
-        if (launch_prefill(a, desc, s0, n, st) != hipSuccess) return H1BKV_EHIP;
-        if (a.n_splits > 1 && launch_prefill_merge(a, s0, n, st) != hipSuccess) return H1BKV_EHIP;
+        if (!launch_allowed(c) || launch_prefill(a, desc, s0, n, st) != hipSuccess) return H1BKV_EHIP;
+        if (a.n_splits > 1 && (!launch_allowed(c) || launch_prefill_merge(a, s0, n, st) != hipSuccess)) return H1BKV_EHIP;
     }
     return H1BKV_OK;
 }

@@ -53,8 +53,7 @@ def test_pool_bytes_formula():
 
 def test_create_null_arguments():
     c = cfg()
-    rc, _ = B.h1bkv_create(c, None, 0, None)
-    assert rc == B.H1BKV_ENULL
+    assert B.lib().h1bkv_create(C.byref(c), None, 0, None, None) == B.H1BKV_ENULL       # nowhere to put the handle
     assert B.lib().h1bkv_create(None, None, 0, None, None) == B.H1BKV_ENULL
     # a real device handle needs a pool pointer
     rc, _ = B.h1bkv_create(cfg(device=0), None, 0, wl.projection(128, 128))
@@ -190,4 +189,84 @@ def test_prefill_workspace_size():
         assert B.h1bkv_prefill_workspace_bytes(h, n_seqs, n_q) == want(n_seqs, n_q), (n_seqs, n_q)
     assert want(4, 8192) == al(4 * 8192 * 8 * 16)       # a long prompt: one split, sketches only
     assert B.h1bkv_prefill_workspace_bytes(h, 0, 5) == 0 and B.h1bkv_prefill_workspace_bytes(h, 2, 0) == 0
+    B.h1bkv_destroy(h)
+
+
+def splitmix_box_muller(seed, n):
+    """The draw h1bkv_create documents for R_host == NULL, written out with Python integers and numpy doubles."""
+    mask = (1 << 64) - 1
+    state = seed & mask
+    out = np.empty(n, dtype=np.float64)
+
+    def uniform():
+        nonlocal state
+        state = (state + 0x9E3779B97F4A7C15) & mask
+        z = state
+        z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) & mask
+        z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) & mask
+        z ^= z >> 31
+        return ((z >> 11) + 0.5) * 2.0 ** -53
+
+    for e in range(0, n, 2):
+        u1, u2 = uniform(), uniform()
+        rad, ang = np.sqrt(-2.0 * np.log(u1)), 2.0 * np.pi * u2
+        out[e], out[e + 1] = rad * np.cos(ang), rad * np.sin(ang)
+    return out
+
+
+def test_projection_drawn_from_the_seed():
+    """Sec. III: R_ij ~ N(0,1), drawn once.  Without a caller-supplied R the library draws it from cfg.seed with the
+    documented generator; the same seed gives the same matrix, another seed another one, and the entries look Gaussian."""
+    c = cfg(seed=0x1234ABCD5678EF01, sketch_bits=256)
+    rc, h = B.h1bkv_create(c, None, 0, None)
+    assert rc == B.H1BKV_OK
+    rc, R1 = B.h1bkv_get_projection(h, 256, 128)
+    assert rc == B.H1BKV_OK
+    want = splitmix_box_muller(0x1234ABCD5678EF01, 256 * 128).reshape(256, 128)
+    # libm may differ in the last place of log / cos / sin between this process's numpy and the library's host code
+    assert np.allclose(R1, want.astype(np.float32), rtol=3e-7, atol=1e-9)
+    rc, h2 = B.h1bkv_create(c, None, 0, None)
+    assert np.array_equal(B.h1bkv_get_projection(h2, 256, 128)[1], R1)
+    rc, h3 = B.h1bkv_create(cfg(seed=7, sketch_bits=256), None, 0, None)
+    R3 = B.h1bkv_get_projection(h3, 256, 128)[1]
+    assert not np.array_equal(R3, R1) and abs(np.corrcoef(R3.ravel(), R1.ravel())[0, 1]) < 0.03
+    n = R1.size
+    assert abs(R1.mean()) < 4 / np.sqrt(n) and abs(R1.var() - 1) < 4 * np.sqrt(2 / n)
+    assert abs((R1 ** 4).mean() - 3) < 0.25 and abs(np.mean(np.abs(R1) < 1) - 0.6827) < 0.01
+    # neighbouring elements (the cos and sin of one pair) and rows are uncorrelated
+    assert abs(np.corrcoef(R1[:, 0::2].ravel(), R1[:, 1::2].ravel())[0, 1]) < 0.03
+    for x in (h, h2, h3):
+        B.h1bkv_destroy(x)
+
+
+def test_failed_launch_leaves_the_bookkeeping_unchanged():
+    """An erroring call changes neither lengths nor page assignments: force the n-th launch attempt of a call to fail and
+    compare the bookkeeping before and after, for every launch position of append and extend."""
+    c, h, _ = make(max_pages=600, max_pages_per_seq=130)
+
+    def state():
+        return [B.h1bkv_seq_len(h, s)[1] for s in range(4)], B.h1bkv_free_pages(h)[1]
+
+    assert B.h1bkv_append_kv(h, [0, 1], 300, None, None, 300 * 512, 512, 128) == B.H1BKV_OK
+    before = state()
+    # [0,1,3] x 700 tokens: 2 + 2 + 3 new pages -> one block-table launch + one append launch
+    for nth, want in ((1, B.H1BKV_EHIP), (2, B.H1BKV_EHIP), (3, B.H1BKV_OK)):
+        assert B.h1bkv_debug_fail_launch(h, nth) == B.H1BKV_OK
+        rc = B.h1bkv_append_kv(h, [0, 1, 3], 700, None, None, 700 * 512, 512, 128)
+        assert rc == want, (nth, rc)
+        if rc != B.H1BKV_OK:
+            assert state() == before, nth
+    assert state() == ([1000, 1000, 0, 700], before[1] - 7)
+    assert B.h1bkv_debug_fail_launch(h, 0) == B.H1BKV_OK
+    # a long extension needs more block-table updates than one launch carries (240): the second launch fails
+    before = state()
+    assert B.h1bkv_debug_fail_launch(h, 2) == B.H1BKV_OK
+    assert B.h1bkv_extend_seq(h, 2, 250 * 256 - 1, 0) == B.H1BKV_ENOSPACE        # beyond 130 pages: refused up front
+    assert B.h1bkv_extend_seq(h, 2, 130 * 256, 0) == B.H1BKV_OK and state() != before   # 130 pages = one launch: attempt 1 passes
+    assert B.h1bkv_reset_seq(h, 2) == B.H1BKV_OK and state() == before
+    assert B.h1bkv_debug_fail_launch(h, 1) == B.H1BKV_OK
+    assert B.h1bkv_extend_seq(h, 2, 1000, 0) == B.H1BKV_EHIP and state() == before
+    # after the failure the same pages are handed out in the same order: a repeat succeeds and matches a fresh handle
+    assert B.h1bkv_extend_seq(h, 2, 1000, 0) == B.H1BKV_OK and state() == ([1000, 1000, 1000, 700], before[1] - 4)
+    assert B.h1bkv_debug_fail_launch(h, -1) == B.H1BKV_EINVAL and B.h1bkv_debug_fail_launch(None, 1) == B.H1BKV_ENULL
     B.h1bkv_destroy(h)
