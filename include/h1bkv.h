@@ -150,6 +150,20 @@ int h1bkv_decode_attn(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n_seq
                       void *hip_stream);
 
 /*
+ * h1bkv_decode_attn for callers that cannot allocate device memory or hand over a workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): same arguments, same kernels and same results, but
+ * the query sketches and per-chunk partial results live in a static device array of H1BKV_STATIC_SCRATCH_BYTES inside
+ * the library (one copy per GPU, held until the process ends; its address is looked up when a handle is created on
+ * the device).  The call allocates nothing on the device.  A call whose sketches and partials do not fit (they
+ * grow with n_seqs x n_q_heads x chunks of the longest context) returns H1BKV_EWORKSPACE and launches nothing.  Every
+ * call on a GPU, from any handle, uses that GPU's one array and nothing in it needs clearing between calls (each call
+ * overwrites what it reads): calls that overlap in time on one GPU -- two streams, two handles -- race; order them.
+ */
+#define H1BKV_STATIC_SCRATCH_BYTES (16u << 20)
+int h1bkv_decode_attn_static(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n_seqs, const void *q_dev,
+                             float tau, float *out_dev, void *hip_stream);
+
+/*
  * One decode step in one call: h1bkv_append_kv with n_new = 1 (k_dev, v_dev: [n_seqs][n_kv_heads][d], sequence
  * and head strides in elements) followed by h1bkv_decode_attn over the grown context, with the same results as
  * the two calls (Sec. IV: a generated token's key and value are cached, then its query attends to the cache).

@@ -18,6 +18,7 @@ H1BKV_EINVAL, H1BKV_ENULL, H1BKV_ESHAPE, H1BKV_ENOSPACE = -1, -2, -3, -4
 H1BKV_ERANGE, H1BKV_EWORKSPACE, H1BKV_EHIP, H1BKV_ENODEVICE = -5, -6, -7, -8
 H1BKV_DEVICE_NONE = -1
 H1BKV_PAGE_TOKENS = 256
+H1BKV_STATIC_SCRATCH_BYTES = 16 << 20
 H1BKV_K_APPEND, H1BKV_K_QSKETCH, H1BKV_K_DECODE_SPLIT, H1BKV_K_MERGE, H1BKV_K_PREFILL = 0, 1, 2, 3, 4
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "lib", "libh1bkv.so")
@@ -64,6 +65,7 @@ def lib() -> C.CDLL:
             "h1bkv_append_kv": (C.c_int, [vp, vp, i32, i32, vp, vp, i64, i64, i64, vp]),
             "h1bkv_decode_workspace_bytes": (sz, [vp, i32, i32]),
             "h1bkv_decode_attn": (C.c_int, [vp, vp, i32, vp, C.c_float, vp, vp, sz, vp]),
+            "h1bkv_decode_attn_static": (C.c_int, [vp, vp, i32, vp, C.c_float, vp, vp]),
             "h1bkv_decode_step": (C.c_int, [vp, vp, i32, vp, vp, i64, i64, vp, C.c_float, vp, vp, sz, vp]),
             "h1bkv_decode_dtau_workspace_bytes": (sz, [vp, i32, i32]),
             "h1bkv_decode_attn_dtau": (C.c_int, [vp, vp, i32, vp, C.c_float, vp, vp, vp, sz, vp]),
@@ -176,6 +178,11 @@ def h1bkv_decode_attn(h, seq_ids, q, tau: float, out, workspace, workspace_bytes
     ids, p = _ids(seq_ids)
     return lib().h1bkv_decode_attn(h, p, len(ids), _dev_ptr(q), tau, _dev_ptr(out), _dev_ptr(workspace), workspace_bytes,
                                    _stream(stream))
+
+
+def h1bkv_decode_attn_static(h, seq_ids, q, tau: float, out, stream=0) -> int:
+    ids, p = _ids(seq_ids)
+    return lib().h1bkv_decode_attn_static(h, p, len(ids), _dev_ptr(q), tau, _dev_ptr(out), _stream(stream))
 
 
 def h1bkv_decode_step(h, seq_ids, k, v, stride_seq: int, stride_head: int, q, tau: float, out, workspace, workspace_bytes: int,

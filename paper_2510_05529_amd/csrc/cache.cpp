@@ -133,6 +133,24 @@ void draw_projection(uint64_t seed, std::vector<float> &R) {
     }
 }
 
+// Scratch of h1bkv_decode_attn_static: one array per GPU the library runs on, resident until the process ends.  In host
+// code the array's name is only a stand-in for the symbol; its device address is looked up once per device
+// (scratch_for_device) and that pointer is what kernels and everything else receive.
+static __device__ __align__(256) unsigned char scratch[H1BKV_STATIC_SCRATCH_BYTES];
+constexpr int kMaxDevices = 64;
+unsigned char *scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device `dev` (looked up on first use), or nullptr.
+unsigned char *scratch_for_device(int dev) {
+    if (dev < 0 || dev >= kMaxDevices) return nullptr;
+    if (!scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return nullptr;
+        scratch_ptr[dev] = static_cast<unsigned char *>(p);
+    }
+    return scratch_ptr[dev];
+}
+
 struct EventPair {
     hipEvent_t a, b;
 };
@@ -150,6 +168,7 @@ struct h1bkv_cache {
     std::vector<int32_t> seq_len;
     std::vector<std::vector<int32_t>> seq_pages;
     std::vector<int32_t> free_list;     // stack of free page ids
+    mutable std::vector<char> seen;     // scratch of the duplicate-id check
     int32_t chunk_override;
     int32_t proj_mfma;     // 1: matrix-core projection where it applies (default); 0: always the plain fp32 chain
     int32_t fail_countdown;   // test hook: > 0 counts launch attempts down, the one that reaches 0 is skipped and reported failed
@@ -265,7 +284,8 @@ int publish(h1bkv_cache *c, const std::vector<int32_t> &idx, const std::vector<i
 int check_seq_ids(const h1bkv_cache *c, const int32_t *ids, int32_t n) {
     if (!ids) return H1BKV_ENULL;
     if (n < 1) return H1BKV_EINVAL;
-    std::vector<char> seen(c->cfg.max_seqs, 0);
+    std::vector<char> &seen = c->seen;        // sized max_seqs at creation: no allocation per call
+    std::fill(seen.begin(), seen.end(), 0);
     for (int i = 0; i < n; ++i) {
         if (ids[i] < 0 || ids[i] >= c->cfg.max_seqs) return H1BKV_ERANGE;
         if (seen[ids[i]]) return H1BKV_EINVAL;
@@ -353,6 +373,7 @@ int h1bkv_create(const h1bkv_config *cfg, void *pool_dev, size_t pool_bytes, con
     R_host = c->R.data();
     c->seq_len.assign(cfg->max_seqs, 0);
     c->seq_pages.assign(cfg->max_seqs, {});
+    c->seen.assign(cfg->max_seqs, 0);
     c->free_list.resize(cfg->max_pages);
     for (int i = 0; i < cfg->max_pages; ++i) c->free_list[i] = cfg->max_pages - 1 - i;  // page 0 is taken first
     c->chunk_override = 0;
@@ -372,6 +393,7 @@ int h1bkv_create(const h1bkv_config *cfg, void *pool_dev, size_t pool_bytes, con
         for (int i = 0; i < cfg->sketch_bits; ++i)
             for (int j = 0; j < cfg->head_dim; ++j) RT[(size_t)j * cfg->sketch_bits + i] = R_host[(size_t)i * cfg->head_dim + j];
         bool ok = hipDeviceSynchronize() == hipSuccess;
+        ok = ok && scratch_for_device(cfg->device) != nullptr;
         ok = ok && hipMemcpy(c->pool + lay.off_R, R_host, nR * sizeof(float), hipMemcpyHostToDevice) == hipSuccess;
         ok = ok && hipMemcpy(c->pool + lay.off_RT, RT.data(), nR * sizeof(float), hipMemcpyHostToDevice) == hipSuccess;
         std::vector<uint16_t> hi, mid;
@@ -569,20 +591,35 @@ size_t h1bkv_decode_workspace_bytes(const h1bkv_cache *c, int32_t n_seqs, int32_
     return o;
 }
 
-// Everything h1bkv_decode_attn checks; `grow` tokens are about to be appended to every sequence first.
+// Workspace bytes one decode call really uses: query sketches and the partial results of the chunks it will launch
+// (h1bkv_decode_workspace_bytes is the bound for any chunk choice).
+static size_t decode_workspace_used(const h1bkv_cache *c, int32_t n_seqs, int max_ctx) {
+    const int chunk = choose_chunk(c, n_seqs, max_ctx);
+    const size_t S = std::max(1, (max_ctx + chunk - 1) / chunk);
+    const size_t heads = (size_t)n_seqs * c->cfg.n_q_heads;
+    size_t o = align_up(heads * c->W * 8);
+    o = align_up(o + heads * S * 2 * sizeof(float));
+    o = align_up(o + heads * S * c->cfg.head_dim * sizeof(float));
+    return o;
+}
+
+// Everything h1bkv_decode_attn checks; `grow` tokens are about to be appended to every sequence first.  With
+// static_ws the workspace is the library's own scratch array: the call must fit into it.
 static int validate_decode(const h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n_seqs, const void *q_dev, float tau,
-                           const float *out_dev, const void *workspace_dev, size_t workspace_bytes, int grow) {
+                           const float *out_dev, const void *workspace_dev, size_t workspace_bytes, int grow,
+                           bool static_ws = false) {
     int rc = check_seq_ids(c, seq_ids_host, n_seqs);
     if (rc != H1BKV_OK) return rc;
     if (!(tau > 0.0f) || !std::isfinite(tau)) return H1BKV_EINVAL;
+    int max_ctx = 0;
+    for (int i = 0; i < n_seqs; ++i) max_ctx = std::max(max_ctx, c->seq_len[seq_ids_host[i]] + grow);
+    if (static_ws && decode_workspace_used(c, n_seqs, max_ctx) > (size_t)H1BKV_STATIC_SCRATCH_BYTES) return H1BKV_EWORKSPACE;
     if (c->dry) return H1BKV_ENODEVICE;
-    if (!q_dev || !out_dev || !workspace_dev) return H1BKV_ENULL;
+    if (!q_dev || !out_dev || (!static_ws && !workspace_dev)) return H1BKV_ENULL;
     if (reinterpret_cast<uintptr_t>(workspace_dev) % kAlign || reinterpret_cast<uintptr_t>(q_dev) % 16 ||
         reinterpret_cast<uintptr_t>(out_dev) % 16)
         return H1BKV_EINVAL;
-    int max_ctx = 0;
-    for (int i = 0; i < n_seqs; ++i) max_ctx = std::max(max_ctx, c->seq_len[seq_ids_host[i]] + grow);
-    if (workspace_bytes < h1bkv_decode_workspace_bytes(c, n_seqs, max_ctx)) return H1BKV_EWORKSPACE;
+    if (!static_ws && workspace_bytes < h1bkv_decode_workspace_bytes(c, n_seqs, max_ctx)) return H1BKV_EWORKSPACE;
     return check_device(c);
 }
 
@@ -658,6 +695,17 @@ int h1bkv_decode_attn(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n_seq
     const int rc = validate_decode(c, seq_ids_host, n_seqs, q_dev, tau, out_dev, workspace_dev, workspace_bytes, 0);
     if (rc != H1BKV_OK) return rc;
     return enqueue_decode(c, seq_ids_host, n_seqs, q_dev, tau, out_dev, workspace_dev, false, static_cast<hipStream_t>(hip_stream));
+}
+
+int h1bkv_decode_attn_static(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n_seqs, const void *q_dev, float tau,
+                             float *out_dev, void *hip_stream) {
+    if (!c) return H1BKV_ENULL;
+    const int rc = validate_decode(c, seq_ids_host, n_seqs, q_dev, tau, out_dev, nullptr, 0, 0, true);
+    if (rc != H1BKV_OK) return rc;
+    // the address of this device's copy of the array was looked up when the handle was created; nothing is allocated here
+    unsigned char *ws = scratch_for_device(c->cfg.device);
+    if (!ws) return H1BKV_EHIP;
+    return enqueue_decode(c, seq_ids_host, n_seqs, q_dev, tau, out_dev, ws, false, static_cast<hipStream_t>(hip_stream));
 }
 
 int h1bkv_decode_step(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n_seqs, const void *k_dev, const void *v_dev,

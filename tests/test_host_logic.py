@@ -270,3 +270,18 @@ def test_failed_launch_leaves_the_bookkeeping_unchanged():
     assert B.h1bkv_extend_seq(h, 2, 1000, 0) == B.H1BKV_OK and state() == ([1000, 1000, 1000, 700], before[1] - 4)
     assert B.h1bkv_debug_fail_launch(h, -1) == B.H1BKV_EINVAL and B.h1bkv_debug_fail_launch(None, 1) == B.H1BKV_ENULL
     B.h1bkv_destroy(h)
+
+
+def test_static_scratch_entry_point_rejects_what_does_not_fit():
+    """h1bkv_decode_attn_static keeps sketches and per-chunk partials in a fixed array: a call that needs more is
+    refused on the host (before the question of a device even arises); a call that fits is only missing a GPU here."""
+    c, h, _ = make(n_q_heads=64, n_kv_heads=8, max_seqs=64, max_pages=64 * 9, max_pages_per_seq=9)
+    for s in range(64):
+        assert B.h1bkv_extend_seq(h, s, 2304, 0) == B.H1BKV_OK
+    assert B.h1bkv_set_decode_chunk(h, 256) == B.H1BKV_OK          # 9 partials per head: 64 x 64 x 9 x (128 + 2) floats
+    assert B.h1bkv_decode_attn_static(h, list(range(64)), None, 0.1, None, 0) == B.H1BKV_EWORKSPACE
+    assert B.h1bkv_decode_attn_static(h, list(range(8)), None, 0.1, None, 0) == B.H1BKV_ENODEVICE
+    assert B.h1bkv_decode_attn_static(h, [0, 0], None, 0.1, None, 0) == B.H1BKV_EINVAL
+    assert B.h1bkv_decode_attn_static(h, [0], None, -0.1, None, 0) == B.H1BKV_EINVAL
+    assert B.lib().h1bkv_decode_attn_static(None, None, 1, None, 0.1, None, None) == B.H1BKV_ENULL
+    B.h1bkv_destroy(h)
