@@ -50,6 +50,9 @@ def parse_args():
     ap.add_argument("--per-token-layers", type=int, default=0, metavar="L",
                     help="secondary line: per-token attention latency of L layers (one cache each), every layer one fused "
                          "decode step, all captured in one HIP graph")
+    ap.add_argument("--rotate", type=int, default=-1, metavar="N",
+                    help="decode workloads: N identical caches used in turn, so that more than 512 MB (twice the 256 MB "
+                         "last-level cache) is touched between two uses of the same bytes; -1 = as many as that needs")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
                     help="only run the library's plain copy kernel on a buffer of this size (counter calibration)")
     return ap.parse_args()
@@ -95,19 +98,28 @@ def cpu_baseline(wl, w, tau, workers, value_bits=4):
         t0 += n
     k1, v1 = wl.kv_slab(w, "k", [0], T - 1, 1), wl.kv_slab(w, "v", [0], T - 1, 1)
     q = wl.queries(w)[:1]
-    times = []
-    t_begin = time.perf_counter()
-    while len(times) < 3 or (time.perf_counter() - t_begin < 8.0 and len(times) < 200):
-        oc.len = T - 1
-        t = time.perf_counter()
-        oc.append(k1, v1)
-        oc.decode(q, tau)
-        times.append(time.perf_counter() - t)
-    sec = float(np.median(times))
-    return {"value": T / sec, "unit": "KV-tokens/s", "cores": cref.max_threads(), "kind": "oracle",
+
+    def timed(budget_s, max_steps):
+        times = []
+        t_begin = time.perf_counter()
+        while len(times) < 3 or (time.perf_counter() - t_begin < budget_s and len(times) < max_steps):
+            oc.len = T - 1
+            t = time.perf_counter()
+            oc.append(k1, v1)
+            oc.decode(q, tau)
+            times.append(time.perf_counter() - t)
+        return float(np.median(times)), len(times)
+
+    cores = cref.max_threads()
+    sec, n_steps = timed(8.0, 200)
+    cref.set_threads(1)
+    sec1, n_steps1 = timed(8.0, 50)
+    cref.set_threads(cores)
+    return {"value": T / sec, "unit": "KV-tokens/s", "cores": cores, "kind": "oracle",
             "sample": f"1 of {w.batch} sequences (all {w.n_kv_heads} KV heads, context {T}): append 1 token + decode, "
-                      f"median of {len(times)} steps, {sec * 1e3:.1f} ms/step",
-            "ms_per_step": sec * 1e3}
+                      f"median of {n_steps} steps, {sec * 1e3:.1f} ms/step",
+            "ms_per_step": sec * 1e3,
+            "one_thread": {"value": T / sec1, "cores": 1, "ms_per_step": sec1 * 1e3, "steps": n_steps1}}
 
 
 # 256 CUs x 4 SIMDs x 32 lanes x 2 flop x 2.4 GHz.  Measured on this chip: a plain v_fma_f32 issues every 2.5 clocks per
@@ -134,7 +146,17 @@ def cpu_baseline_prompt(wl, w, tau, workers, attend):
             oc.prefill(q, tau)
         times.append(time.perf_counter() - t)
     sec = float(np.median(times))
-    out = {"value": n / sec, "unit": "tokens/s", "cores": cref.max_threads(), "kind": "oracle",
+    cores = cref.max_threads()
+    cref.set_threads(1)
+    oc = cref.Cache(R, 1, w.n_kv_heads, n, w.group_size)
+    t = time.perf_counter()
+    oc.append(k, v)
+    if attend:
+        oc.prefill(q, tau)
+    sec1 = time.perf_counter() - t
+    cref.set_threads(cores)
+    out = {"value": n / sec, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+           "one_thread": {"value": n / sec1, "cores": 1, "ms_per_step": sec1 * 1e3, "steps": 1},
            "sample": f"the first {n} tokens of 1 of {w.batch} sequences (all {w.n_kv_heads} KV heads): append"
                      + (" + causal attention of every position" if attend else "") + f", median of {len(times)} runs, {sec * 1e3:.0f} ms",
            "ms_per_step": sec * 1e3}
@@ -391,21 +413,41 @@ def main():
     tau = w.default_tau()
     R = wl.projection(w.sketch_bits, w.head_dim)
     pages_per_seq = (T + 255) // 256 + 1
-    cache = B.Cache(n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim, sketch_bits=w.sketch_bits,
-                    group_size=w.group_size, dtype=w.dtype, max_seqs=Bsz, max_pages=Bsz * pages_per_seq,
-                    max_pages_per_seq=pages_per_seq, R=R, value_bits=args.value_bits)
     f16v = args.value_bits == 16
+    record_bytes = w.sketch_bits // 8 + 2 * w.head_dim if f16v else w.record_bytes
+    cache_bytes = Bsz * w.n_kv_heads * T * record_bytes
+    # A cache smaller than twice the 256 MB last-level cache would be served partly from it when the same bytes are read
+    # again step after step: identical copies are then used in turn so that > 512 MB pass between two reads of a byte.
+    n_rot = args.rotate if args.rotate > 0 else (1 if cache_bytes >= (512 << 20) else max(4, -(-(512 << 20) // cache_bytes) + 1))
+
+    def new_cache():
+        return B.Cache(n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim, sketch_bits=w.sketch_bits,
+                       group_size=w.group_size, dtype=w.dtype, max_seqs=Bsz, max_pages=Bsz * pages_per_seq,
+                       max_pages_per_seq=pages_per_seq, R=R, value_bits=args.value_bits)
+
+    cache = new_cache()
     r = w.n_q_heads // w.n_kv_heads
     mfma = not f16v and r >= 3 and w.head_dim <= 128 and w.head_dim // w.group_size <= 4 and w.sketch_bits <= 256
     split_kernel = "decode_split_f16v_kernel" if f16v else ("decode_split_mfma_kernel" if mfma else "decode_split_kernel")
-    record_bytes = w.sketch_bits // 8 + 2 * w.head_dim if f16v else w.record_bytes
-    if args.chunk:
-        B.check(B.h1bkv_set_decode_chunk(cache.h, args.chunk))
     t_fill = time.perf_counter()
     fill_cache(torch, B, wl, w, cache, T - 1, workers)
-    t_fill = time.perf_counter() - t_fill
-
     seqs = list(range(Bsz))
+    caches = [cache]
+    for _ in range(n_rot - 1):
+        # a copy: the same bookkeeping (positions reserved in the same order take the same pages) over a copy of the pool
+        c2 = new_cache()
+        for t_ in range(0, T - 1, wl.SLAB_TOKENS):
+            for s_ in seqs:
+                B.check(B.h1bkv_extend_seq(c2.h, s_, min(wl.SLAB_TOKENS, T - 1 - t_), None))
+        torch.cuda.synchronize()
+        c2.pool.copy_(cache.pool)
+        caches.append(c2)
+    torch.cuda.synchronize()
+    t_fill = time.perf_counter() - t_fill
+    for c_ in caches:
+        if args.chunk:
+            B.check(B.h1bkv_set_decode_chunk(c_.h, args.chunk))
+
     k1 = torch.from_numpy(wl.kv_slab(w, "k", seqs, T - 1, 1)).cuda()
     v1 = torch.from_numpy(wl.kv_slab(w, "v", seqs, T - 1, 1)).cuda()
     q = torch.from_numpy(wl.queries(w)).cuda()
@@ -413,36 +455,55 @@ def main():
     ws_bytes = B.h1bkv_decode_workspace_bytes(cache.h, Bsz, T)
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
     stream = torch.cuda.current_stream()
+    turn = [0]
+
+    def next_cache():
+        turn[0] += 1
+        return caches[turn[0] % n_rot]
 
     def step():
+        c_ = next_cache()
         for s in seqs:
-            B.check(B.h1bkv_truncate_seq(cache.h, s, T - 1))
-        B.check(B.h1bkv_append_kv(cache.h, seqs, 1, k1, v1, k1.stride(0), k1.stride(1), k1.stride(2), stream))
-        B.check(B.h1bkv_decode_attn(cache.h, seqs, q, tau, out, ws, ws_bytes, stream))
+            B.check(B.h1bkv_truncate_seq(c_.h, s, T - 1))
+        B.check(B.h1bkv_append_kv(c_.h, seqs, 1, k1, v1, k1.stride(0), k1.stride(1), k1.stride(2), stream))
+        B.check(B.h1bkv_decode_attn(c_.h, seqs, q, tau, out, ws, ws_bytes, stream))
+
+    def profile_all(capacity, mask, stride=1):
+        for c_ in caches:
+            B.check(B.h1bkv_profile_enable(c_.h, capacity, mask))
+            B.check(B.h1bkv_profile_stride(c_.h, stride))
+
+    def profile_read_all(kid):
+        got = []
+        for c_ in caches:
+            rc, ms = B.h1bkv_profile_read(c_.h, kid)
+            B.check(rc)
+            got.append(ms)
+        return np.concatenate(got)
 
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
     # Only the dominant kernel is bracketed by events inside the timed region (its duration is the roofline's
     # denominator); the small kernels are timed in a separate, untimed pass so their events cost the step nothing.
-    B.check(B.h1bkv_profile_enable(cache.h, args.steps, 1 << B.H1BKV_K_DECODE_SPLIT))
-    B.check(B.h1bkv_profile_stride(cache.h, 5))          # every 5th launch: an event pair costs the stream a few microseconds
+    # Every 5th launch of each cache: an event pair costs the stream a few microseconds.
+    profile_all(args.steps, 1 << B.H1BKV_K_DECODE_SPLIT, 5)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
-    rc, split_ms_all = B.h1bkv_profile_read(cache.h, B.H1BKV_K_DECODE_SPLIT)
-    B.check(rc)
+    split_ms_all = profile_read_all(B.H1BKV_K_DECODE_SPLIT)
+
     # the same step through the fused entry point (append + query sketch in one launch): reported next to `value`
     def fused_step():
+        c_ = next_cache()
         for s in seqs:
-            B.check(B.h1bkv_truncate_seq(cache.h, s, T - 1))
-        B.check(B.h1bkv_decode_step(cache.h, seqs, k1, v1, k1.stride(0), k1.stride(2), q, tau, out, ws, ws_bytes, stream))
+            B.check(B.h1bkv_truncate_seq(c_.h, s, T - 1))
+        B.check(B.h1bkv_decode_step(c_.h, seqs, k1, v1, k1.stride(0), k1.stride(2), q, tau, out, ws, ws_bytes, stream))
 
-    B.check(B.h1bkv_profile_enable(cache.h, 0, 0))
-    B.check(B.h1bkv_profile_stride(cache.h, 1))
+    profile_all(0, 0)
     for _ in range(args.warmup):
         fused_step()
     torch.cuda.synchronize()
@@ -451,19 +512,33 @@ def main():
         fused_step()
     torch.cuda.synchronize()
     fused_ms = (time.perf_counter() - t0) * 1e3 / args.steps
-    B.check(B.h1bkv_profile_enable(cache.h, 10, 0xF))
-    for _ in range(10):
+    profile_all(10, 0xF)
+    for _ in range(10 * n_rot):
         step()
     torch.cuda.synchronize()
 
     kernel_ms = {}
     for name, kid in (("append", B.H1BKV_K_APPEND), ("qsketch", B.H1BKV_K_QSKETCH),
                       ("decode_split", B.H1BKV_K_DECODE_SPLIT), ("merge", B.H1BKV_K_MERGE)):
-        rc, ms = B.h1bkv_profile_read(cache.h, kid)
-        B.check(rc)
+        ms = profile_read_all(kid)
         kernel_ms[name] = float(ms.mean()) if len(ms) else None
-    B.check(B.h1bkv_profile_enable(cache.h, 0, 0))
+    profile_all(0, 0)
     kernel_ms["decode_split"] = float(split_ms_all.mean())
+
+    # the read ceiling: the library's read-only streaming kernel over 2 GiB (what a kernel that only loads can reach here)
+    n_read = 2 << 30
+    src = torch.empty(n_read, dtype=torch.uint8, device="cuda").fill_(1)
+    sink = torch.zeros(128 << 10, dtype=torch.uint8, device="cuda")
+    for _ in range(5):
+        B.check(B.h1bkv_stream_read(src, n_read, sink, stream))
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record()
+    for _ in range(20):
+        B.check(B.h1bkv_stream_read(src, n_read, sink, stream))
+    ev1.record()
+    torch.cuda.synchronize()
+    read_ceiling_gbps = n_read * 20 / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
+    del src
 
     records = Bsz * w.n_kv_heads * T
     alg_bytes = records * record_bytes                        # sketch + nibbles + scale/zero (or fp16 values) of every cached record
@@ -488,7 +563,9 @@ def main():
                    "step": "append 1 token/sequence + decode attention over the full context"},
         "roofline": {"bound": "hbm", "kernel": split_kernel, "achieved": achieved, "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic_from_profiles(w.name + ("_f16v" if f16v else "")),
-                     "algorithmic_bytes_per_launch": alg_bytes, "kernel_ms": split_ms},
+                     "algorithmic_bytes_per_launch": alg_bytes, "kernel_ms": split_ms,
+                     "read_ceiling_GBps": read_ceiling_gbps, "frac_of_read_ceiling": achieved / read_ceiling_gbps,
+                     "caches_in_rotation": n_rot, "bytes_between_reuse": n_rot * cache_bytes},
         "records_per_s": records / (ms_per_step * 1e-3),
         "kernel_ms": kernel_ms,
         "fused_step": {"entry_point": "h1bkv_decode_step", "ms_per_step": fused_ms, "value": Bsz * T / (fused_ms * 1e-3)},

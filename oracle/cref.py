@@ -45,6 +45,12 @@ def max_threads() -> int:
     return int(lib().h1bkv_oracle_max_threads())
 
 
+def set_threads(n: int) -> None:
+    """Threads the oracle's OpenMP loops use from now on (the OpenMP runtime's own call; the oracle is untouched)."""
+    lib()
+    C.CDLL("libgomp.so.1").omp_set_num_threads(C.c_int(int(n)))
+
+
 def half_to_float(h: int) -> float:
     return float(lib().h1bkv_oracle_half_to_float(int(h)))
 
