@@ -27,7 +27,8 @@ def lib():
                      "h1bkv_oracle_hamming", "h1bkv_oracle_decode_one", "h1bkv_oracle_decode_batch",
                      "h1bkv_oracle_append_batch", "h1bkv_oracle_decode_one_f16v",
                      "h1bkv_oracle_decode_batch_f16v", "h1bkv_oracle_append_batch_f16v",
-                     "h1bkv_oracle_prefill_batch", "h1bkv_oracle_decode_one_dtau", "h1bkv_oracle_decode_batch_dtau"):
+                     "h1bkv_oracle_prefill_batch", "h1bkv_oracle_decode_one_dtau", "h1bkv_oracle_decode_batch_dtau",
+                     "h1bkv_oracle_decode_one_dtau_f16v", "h1bkv_oracle_decode_batch_dtau_f16v"):
             getattr(L, name).restype = None
         _lib = L
     return _lib
@@ -146,6 +147,19 @@ def decode_one_f16v(sq, sk, v16, b: int, tau: float) -> np.ndarray:
     return out
 
 
+def decode_one_dtau_f16v(sq, sk, v16, b: int, tau: float):
+    """Eq.(5) with fp16 values and d out / d tau for one (sequence, query head): returns (out [d], dout [d]) float32."""
+    sq = np.ascontiguousarray(sq, dtype=np.uint64)
+    sk = np.ascontiguousarray(sk, dtype=np.uint64)
+    v16 = np.ascontiguousarray(v16, dtype=np.uint16)
+    T, d = v16.shape
+    out = np.zeros(d, dtype=np.float32)
+    dout = np.zeros(d, dtype=np.float32)
+    lib().h1bkv_oracle_decode_one_dtau_f16v(_p(sq), _p(sk), _p(v16), C.c_int64(T), C.c_int(b), C.c_int(d),
+                                            C.c_double(tau), _p(out), _p(dout))
+    return out, dout
+
+
 class Cache:
     """Canonical-layout compressed cache on the host: planes [B][H_kv][Tcap][...], filled by the oracle."""
 
@@ -202,12 +216,16 @@ class Cache:
 
     def decode_dtau(self, q: np.ndarray, tau: float, ctx_len=None):
         """q [B][H_q][d] -> (out, d out / d tau), each [B][H_q][d] float32."""
-        assert self.value_bits == 4
         q = _f32(q)
         Hq = q.shape[1]
         lens = np.full(self.B, self.len, dtype=np.int32) if ctx_len is None else np.ascontiguousarray(ctx_len, dtype=np.int32)
         out = np.zeros((self.B, Hq, self.d), dtype=np.float32)
         dout = np.zeros((self.B, Hq, self.d), dtype=np.float32)
+        if self.value_bits == 16:
+            lib().h1bkv_oracle_decode_batch_dtau_f16v(_p(self.R), C.c_int(self.b), C.c_int(self.d), C.c_int(self.B),
+                                                      C.c_int(Hq), C.c_int(self.Hkv), C.c_int64(self.Tcap), _p(lens), _p(q),
+                                                      _p(self.sketches), _p(self.v16), C.c_double(tau), _p(out), _p(dout))
+            return out, dout
         lib().h1bkv_oracle_decode_batch_dtau(_p(self.R), C.c_int(self.b), C.c_int(self.d), C.c_int(self.G),
                                              C.c_int(self.B), C.c_int(Hq), C.c_int(self.Hkv), C.c_int64(self.Tcap),
                                              _p(lens), _p(q), _p(self.sketches), _p(self.codes), _p(self.scale),

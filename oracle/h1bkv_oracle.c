@@ -379,6 +379,63 @@ void h1bkv_oracle_decode_one_f16v(const uint64_t *sq /*[W]*/, const uint64_t *sk
     for (int c = 0; c < d; ++c) out[c] = (float)(acc[c] / l);
 }
 
+/*
+ * The same with the temperature derivative (Sec. IV-C, Eq.(5); see h1bkv_oracle_decode_one_dtau):
+ *   d out / d tau = -(1 / tau^2) ( sum p_t alpha_t v_t / l  -  (sum p_t alpha_t / l) out ),  v_t the stored fp16 value.
+ */
+void h1bkv_oracle_decode_one_dtau_f16v(const uint64_t *sq, const uint64_t *sk, const uint16_t *v16, int64_t T, int b,
+                                       int d, double tau, float *out, float *dout) {
+    int W = b / 64;
+    double acc[1024], acca[1024];
+    for (int c = 0; c < d; ++c) acc[c] = acca[c] = 0.0;
+    if (T <= 0) {
+        for (int c = 0; c < d; ++c) out[c] = dout[c] = 0.0f;
+        return;
+    }
+    double m = -2.0;
+    for (int64_t t = 0; t < T; ++t) {
+        int h = 0;
+        for (int w = 0; w < W; ++w) h += __builtin_popcountll(sq[w] ^ sk[t * W + w]);
+        double alpha = (double)(b - 2 * h) / (double)b;
+        if (alpha > m) m = alpha;
+    }
+    double l = 0.0, la = 0.0;
+    for (int64_t t = 0; t < T; ++t) {
+        int h = 0;
+        for (int w = 0; w < W; ++w) h += __builtin_popcountll(sq[w] ^ sk[t * W + w]);
+        double alpha = (double)(b - 2 * h) / (double)b;
+        double p = exp((alpha - m) / tau);
+        l += p;
+        la += p * alpha;
+        for (int c = 0; c < d; ++c) {
+            double v = (double)h1bkv_oracle_half_to_float(v16[t * d + c]);
+            acc[c] += p * v;
+            acca[c] += p * alpha * v;
+        }
+    }
+    for (int c = 0; c < d; ++c) {
+        double o = acc[c] / l;
+        out[c] = (float)o;
+        dout[c] = (float)(-(acca[c] / l - (la / l) * o) / (tau * tau));
+    }
+}
+
+void h1bkv_oracle_decode_batch_dtau_f16v(const float *R, int b, int d, int B, int Hq, int Hkv, int64_t Tcap,
+                                         const int32_t *ctx_len, const float *q, const uint64_t *sketches,
+                                         const uint16_t *v16, double tau, float *out, float *dout) {
+    int W = b / 64, r = Hq / Hkv;
+#pragma omp parallel for schedule(dynamic, 1) collapse(2)
+    for (int s = 0; s < B; ++s)
+        for (int h = 0; h < Hq; ++h) {
+            uint64_t sq[16];
+            sketch_one(R, b, d, q + ((int64_t)s * Hq + h) * d, sq);
+            int64_t base = ((int64_t)s * Hkv + h / r) * Tcap;
+            int64_t o = ((int64_t)s * Hq + h) * d;
+            h1bkv_oracle_decode_one_dtau_f16v(sq, sketches + base * W, v16 + base * d, ctx_len[s], b, d, tau, out + o,
+                                              dout + o);
+        }
+}
+
 /* Batch forms in canonical layout: sketches [B][H_kv][Tcap][W], values [B][H_kv][Tcap][d] fp16 bit patterns. */
 void h1bkv_oracle_decode_batch_f16v(const float *R, int b, int d, int B, int Hq, int Hkv, int64_t Tcap,
                                     const int32_t *ctx_len, const float *q, const uint64_t *sketches,
