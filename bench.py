@@ -220,20 +220,17 @@ def bench_append(args, torch, B, wl, w, workers):
         "records_per_s": records / (ms_per_step * 1e-3)}))
 
 
-# compute units x SIMDs x lanes per clock x clock = 78.6 T lane-operations/s: the fp32 vector peak of 157.3 TFLOP/s counted
-# as multiply-adds.  Plain v_fma_f32 / v_and_b32 / v_add_u32 chains were measured at one wave64 instruction per 2.5 clocks
-# per SIMD (32 lanes per clock nominal); v_fma_mix_f32, v_cvt_pk_f16_f32, v_min_i32, v_bcnt_u32_b32 and v_mul_u32_u24 issue
-# at half that rate and v_exp_f32 at a quarter, so a kernel that leans on those cannot reach this figure.
-VALU_LANE_OPS_PER_S = 256 * 4 * 32 * 2.4e9
+# MI355X dense matrix-core peaks of the two operand types the prefill kernel uses.
+MFMA_F16_PEAK_TFLOPS = 2500.0
+MFMA_I8_PEAK_TOPS = 5000.0
 
 
 def bench_prefill(args, torch, B, wl, w, workers):
     """Secondary line: a whole prompt -- append all tokens of every sequence, then causal attention of every position
-    over the compressed cache (h1bkv_prefill_attn).  The attention kernel is bound by instruction issue (vector ALU
-    and matrix-core instructions share the issue port and overlap little): per visible (query, key) pair the method
-    needs the sketch words' XOR and popcount (4 W instructions), a convert, a multiply-add, an exponential (quarter
-    rate: 4 issue slots) and half a pack -- 4 W + 7 lane-operations, counted here as the algorithmic work against the
-    chip's fp32 vector peak."""
+    over the compressed cache (h1bkv_prefill_attn).  Both halves of the attention kernel are dense contractions on the
+    matrix cores: the weighted sum of Eq.(5) with fp16 operands (2 d flop per visible (query, key) pair) and the
+    Hamming distances of Eq.(3) with int8 operands (2 b operations per pair).  The roofline is the value contraction
+    against the fp16 matrix peak; the score contraction against the int8 peak is reported next to it."""
     n_new, Bsz = w.context, w.batch
     R = wl.projection(w.sketch_bits, w.head_dim)
     pages_per_seq = (n_new + 255) // 256 + 1
@@ -277,12 +274,10 @@ def bench_prefill(args, torch, B, wl, w, workers):
         rc, ms = B.h1bkv_profile_read(cache.h, kid)
         B.check(rc)
         kernel_ms[name] = float(ms.sum()) / args.steps            # per prompt: the sum over its chunks
-    W = w.sketch_bits // 64
     pairs = Bsz * w.n_q_heads * n_new * (n_new + 1) / 2.0        # visible (query, key) pairs
-    lane_ops = pairs * (4 * W + 7)
-    achieved = lane_ops / (kernel_ms["prefill"] * 1e-3) / 1e12
-    peak = VALU_LANE_OPS_PER_S / 1e12
-    mfma_flops = pairs * w.head_dim * 2.0
+    sec = kernel_ms["prefill"] * 1e-3
+    value_tflops = pairs * 2.0 * w.head_dim / sec / 1e12         # Eq.(5): d multiply-adds per pair
+    score_tops = pairs * 2.0 * w.sketch_bits / sec / 1e12        # Eq.(3): b multiply-adds per pair
     extra = {} if args.no_cpu_baseline else {"cpu_baseline": cpu_baseline_prompt(wl, w, tau, workers, attend=True)}
     print(json.dumps({
         **extra,
@@ -294,10 +289,12 @@ def bench_prefill(args, torch, B, wl, w, workers):
                    "prefill_chunk": chunk,
                    "step": "append the whole prompt + causal attention of every position over the compressed cache"
                            + ("" if chunk == n_new else f", fed in chunks of {chunk} tokens")},
-        "roofline": {"bound": "alu", "kernel": "prefill_kernel", "achieved": achieved, "peak": peak, "unit": "T lane-op/s",
-                     "frac": achieved / peak, "traffic": None, "kernel_ms": kernel_ms["prefill"],
-                     "pairs_per_s": pairs / (kernel_ms["prefill"] * 1e-3), "lane_ops_per_pair": 4 * W + 7,
-                     "mfma_TFLOPs": mfma_flops / (kernel_ms["prefill"] * 1e-3) / 1e12},
+        "roofline": {"bound": "mfma", "kernel": "prefill_kernel", "achieved": value_tflops, "peak": MFMA_F16_PEAK_TFLOPS,
+                     "unit": "TFLOP/s", "frac": value_tflops / MFMA_F16_PEAK_TFLOPS, "traffic": None,
+                     "kernel_ms": kernel_ms["prefill"], "pairs_per_s": pairs / sec,
+                     "algorithmic_flop_per_pair": 2 * w.head_dim,
+                     "scores_int8": {"achieved": score_tops, "peak": MFMA_I8_PEAK_TOPS, "unit": "TOP/s",
+                                     "frac": score_tops / MFMA_I8_PEAK_TOPS, "algorithmic_op_per_pair": 2 * w.sketch_bits}},
         "kernel_ms": kernel_ms}))
 
 

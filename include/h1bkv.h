@@ -185,8 +185,8 @@ int h1bkv_decode_step(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n_seq
  * finetuning stage trains; Eq.(5)):  out as h1bkv_decode_attn, and
  *   dout_dtau = -(1/tau^2) ( sum_t p_t alpha_t v_t / l - (sum_t p_t alpha_t / l) out ),  p_t = exp(alpha_t / tau), l = sum_t p_t
  * -- the softmax-weighted covariance of scores and dequantised values over -tau^2; zero for T <= 1.
- * out_dev, dout_dtau_dev: [n_seqs][n_q_heads][d] fp32.  Supported for 4-bit values with at most 2 query heads per KV
- * head (the record-major code layout; H1BKV_ESHAPE otherwise).  workspace_dev: >=
+ * out_dev, dout_dtau_dev: [n_seqs][n_q_heads][d] fp32.  Every cache geometry h1bkv_decode_attn serves is supported
+ * (4-bit and fp16 values, any number of query heads per KV head).  workspace_dev: >=
  * h1bkv_decode_dtau_workspace_bytes(c, n_seqs, longest T), 256-byte aligned.  Other arguments as h1bkv_decode_attn.
  */
 size_t h1bkv_decode_dtau_workspace_bytes(const h1bkv_cache *c, int32_t n_seqs, int32_t max_ctx);

@@ -749,7 +749,6 @@ int h1bkv_decode_attn_dtau(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t 
     int rc = check_seq_ids(c, seq_ids_host, n_seqs);
     if (rc != H1BKV_OK) return rc;
     if (!(tau > 0.0f) || !std::isfinite(tau)) return H1BKV_EINVAL;
-    if (c->code_layout != 0) return H1BKV_ESHAPE;
     if (c->dry) return H1BKV_ENODEVICE;
     if (!q_dev || !out_dev || !dout_dtau_dev || !workspace_dev) return H1BKV_ENULL;
     if (reinterpret_cast<uintptr_t>(workspace_dev) % kAlign || reinterpret_cast<uintptr_t>(q_dev) % 16 ||
@@ -793,7 +792,11 @@ int h1bkv_decode_attn_dtau(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t 
         }
         {
             Timed t(c, H1BKV_K_DECODE_SPLIT, st);
-            if (!launch_allowed(c) || launch_decode_dtau_split(a, desc, s0, n, st) != hipSuccess) return H1BKV_EHIP;
+            if (!launch_allowed(c)) return H1BKV_EHIP;
+            const hipError_t e = c->code_layout == 2   ? launch_decode_dtau_split_f16v(a, desc, s0, n, st)
+                                 : c->code_layout == 1 ? launch_decode_dtau_split_mfma(a, desc, s0, n, st)
+                                                       : launch_decode_dtau_split(a, desc, s0, n, st);
+            if (e != hipSuccess) return H1BKV_EHIP;
         }
         {
             Timed t(c, H1BKV_K_MERGE, st);

@@ -142,6 +142,8 @@ hipError_t launch_decode_split(const DecodeArgs &a, const BatchDesc &desc, int s
 hipError_t launch_decode_split_mfma(const DecodeArgs &a, const BatchDesc &desc, int seq0, int n_seqs, hipStream_t st);
 hipError_t launch_decode_split_f16v(const DecodeArgs &a, const BatchDesc &desc, int seq0, int n_seqs, hipStream_t st);
 hipError_t launch_decode_dtau_split(const DecodeArgs &a, const BatchDesc &desc, int seq0, int n_seqs, hipStream_t st);
+hipError_t launch_decode_dtau_split_mfma(const DecodeArgs &a, const BatchDesc &desc, int seq0, int n_seqs, hipStream_t st);
+hipError_t launch_decode_dtau_split_f16v(const DecodeArgs &a, const BatchDesc &desc, int seq0, int n_seqs, hipStream_t st);
 hipError_t launch_merge_dtau(const DecodeArgs &a, const BatchDesc &desc, int seq0, int n_seqs, float dtau_scale, hipStream_t st);
 hipError_t launch_merge(const DecodeArgs &a, const BatchDesc &desc, int seq0, int n_seqs, hipStream_t st);
 hipError_t launch_sketch_rows(const PrefillArgs &a, int n_seqs, hipStream_t st);

@@ -11,6 +11,9 @@
 //            query head: HBM-bound for every r the kernel serves (up to 8 query heads per pass).
 //   Slots past the end of the context can hold anything (also NaN bit patterns): the last, partial share of a wave
 //   takes a masked path that zeroes them; full shares take the plain path.
+// DTAU = true adds the distance-weighted sums of the temperature derivative (Sec. IV-C; formula in
+// kernels_decode_dtau.hip): every query head carries a second accumulator set with weight p e, e = ham - running
+// minimum; when a page lowers the minimum by k the second set takes k times the first before the usual rescale.
 #include <type_traits>
 #include <utility>
 
@@ -51,14 +54,16 @@ __device__ __forceinline__ float group_pick(float x) {
 
 // Register budget: one batch of value loads (up to 16 x 16 B per lane) plus 8 accumulators per query head; the
 // latency of the single-buffered loads is covered by the other resident waves (4 per SIMD at one query head).
-template <int RQ, int W, int D>
-__global__ __launch_bounds__(kThreads, RQ >= 8 ? 2 : (RQ >= 4 ? 3 : 4)) void decode_split_f16v_kernel(DecodeArgs a, BatchDesc desc, int seq0) {
+template <int RQ, int W, int D, bool DTAU>
+__global__ __launch_bounds__(kThreads, RQ * (DTAU ? 2 : 1) >= 8 ? 2 : (RQ * (DTAU ? 2 : 1) >= 4 ? 3 : 4)) void decode_split_f16v_kernel(DecodeArgs a, BatchDesc desc, int seq0) {
     constexpr int LPT = D / 8;                    // lanes per token
     constexpr int TPW = 64 / LPT;                 // tokens covered by one wave-wide load of values
-    __shared__ float epi[kWaves][RQ][D];
+    constexpr int NV = DTAU ? 2 : 1;              // sum sets per query head: weight p, and weight p e
+    constexpr int RQV = RQ * NV;                  // accumulator sets: set NV q + v
+    __shared__ float epi[kWaves][RQV][D];
     __shared__ int pages_s[kMaxPagesPerChunk];
     __shared__ int m_s[kWaves][RQ];
-    __shared__ float l_s[kWaves][RQ];
+    __shared__ float l_s[kWaves][RQV];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const SeqDesc sd = desc.s[blockIdx.z];
@@ -92,20 +97,21 @@ __global__ __launch_bounds__(kThreads, RQ >= 8 ? 2 : (RQ >= 4 ? 3 : 4)) void dec
     const int slice = lane % LPT;
     const int tok_v = lane / LPT;
 
-    float acc[RQ][8];
-    float lsum[RQ];
+    float acc[RQV][8];
+    float lsum[RQV];
     int run_min[RQ];
 #pragma unroll
-    for (int q = 0; q < RQ; ++q) {
+    for (int q = 0; q < RQ; ++q) run_min[q] = 1 << 20;
+#pragma unroll
+    for (int q = 0; q < RQV; ++q) {
         lsum[q] = 0.0f;
-        run_min[q] = 1 << 20;
 #pragma unroll
         for (int i = 0; i < 8; ++i) acc[q][i] = 0.0f;
     }
 
     // Value loads per batch: a share's loads are taken in batches that fit the register budget next to the
     // accumulators (16 x 16 B per lane at one or two query heads and d <= 128, 8 otherwise).
-    constexpr int LPB = (RQ >= 4 || LPT > 16) ? (LPT < 8 ? LPT : 8) : LPT;
+    constexpr int LPB = (RQV >= 4 || LPT > 16) ? (LPT < 8 ? LPT : 8) : LPT;
     constexpr int NB = LPT / LPB;
 
     // Token order inside a wave's 64-token share: the value loads cover TPW consecutive tokens per instruction
@@ -125,7 +131,7 @@ __global__ __launch_bounds__(kThreads, RQ >= 8 ? 2 : (RQ >= 4 ? 3 : 4)) void dec
         for (int it = 0; it < LPB; ++it) v[it] = load_stream(vp + it * 64);
         // ---- scoring role (Eq. 3), running maximum per query head ----
         const bool valid = !kMasked || tok0 + tok_s < n_tok;
-        float p[RQ];
+        float p[RQV];
 #pragma unroll
         for (int q = 0; q < RQ; ++q) {
             int h = 0;
@@ -134,13 +140,23 @@ __global__ __launch_bounds__(kThreads, RQ >= 8 ? 2 : (RQ >= 4 ? 3 : 4)) void dec
             const int pmin = wave_min_dpp16(valid ? h : (1 << 20));
             if (pmin < run_min[q]) {                       // uniform over the wave; rare after the first pages
                 const float f = fast_exp2(a.exp2_scale * (float)(pmin - run_min[q]));
-                run_min[q] = pmin;
-                lsum[q] *= f;
+                if constexpr (DTAU) {
+                    const float k = (float)(run_min[q] - pmin);      // every e grows by k (all sums are still 0 the first time)
+                    lsum[NV * q + 1] = (lsum[NV * q + 1] + k * lsum[NV * q]) * f;
 #pragma unroll
-                for (int i = 0; i < 8; ++i) acc[q][i] *= f;
+                    for (int i = 0; i < 8; ++i) acc[NV * q + 1][i] = (acc[NV * q + 1][i] + k * acc[NV * q][i]) * f;
+                }
+                run_min[q] = pmin;
+                lsum[NV * q] *= f;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) acc[NV * q][i] *= f;
             }
-            p[q] = valid ? fast_exp2(a.exp2_scale * (float)(run_min[q] - h)) : 0.0f;
-            lsum[q] += p[q];
+            p[NV * q] = valid ? fast_exp2(a.exp2_scale * (float)(run_min[q] - h)) : 0.0f;
+            lsum[NV * q] += p[NV * q];
+            if constexpr (DTAU) {
+                p[NV * q + 1] = valid ? p[NV * q] * (float)(h - run_min[q]) : 0.0f;
+                lsum[NV * q + 1] += p[NV * q + 1];
+            }
         }
         // ---- value role: lane = (token, 8-channel slice) ----
         static_for<NB>([&](auto nbc) {
@@ -154,18 +170,18 @@ __global__ __launch_bounds__(kThreads, RQ >= 8 ? 2 : (RQ >= 4 ? 3 : 4)) void dec
                 constexpr int it = decltype(itc)::value;
                 constexpr int load = nb * LPB + it;
                 // with many query heads the scheduler would otherwise pull every load's swizzles up front and spill
-                if constexpr (RQ >= 4 && it > 0) __builtin_amdgcn_sched_barrier(0);
+                if constexpr (RQV >= 4 && it > 0) __builtin_amdgcn_sched_barrier(0);
                 uint4 x = v[it];
                 if (kMasked && tok0 + load * TPW + tok_v >= n_tok) x = make_uint4(0u, 0u, 0u, 0u);
                 const __half2 *h2 = reinterpret_cast<const __half2 *>(&x);
-                float pt[RQ];
+                float pt[RQV];
 #pragma unroll
-                for (int q = 0; q < RQ; ++q) pt[q] = group_pick<LPT, load>(p[q]);
+                for (int q = 0; q < RQV; ++q) pt[q] = group_pick<LPT, load>(p[q]);
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     const float lo = __low2float(h2[i]), hi = __high2float(h2[i]);
 #pragma unroll
-                    for (int q = 0; q < RQ; ++q) {
+                    for (int q = 0; q < RQV; ++q) {
                         acc[q][2 * i] = fmaf(pt[q], lo, acc[q][2 * i]);
                         acc[q][2 * i + 1] = fmaf(pt[q], hi, acc[q][2 * i + 1]);
                     }
@@ -181,7 +197,7 @@ __global__ __launch_bounds__(kThreads, RQ >= 8 ? 2 : (RQ >= 4 ? 3 : 4)) void dec
 
     // ---------------- Epilogue: token slots of a wave, then the four waves ----------------
 #pragma unroll
-    for (int q = 0; q < RQ; ++q) {
+    for (int q = 0; q < RQV; ++q) {
 #pragma unroll
         for (int i = 0; i < 8; ++i)
 #pragma unroll
@@ -190,17 +206,16 @@ __global__ __launch_bounds__(kThreads, RQ >= 8 ? 2 : (RQ >= 4 ? 3 : 4)) void dec
     }
     if (tok_v == 0) {
 #pragma unroll
-        for (int q = 0; q < RQ; ++q) {
+        for (int q = 0; q < RQV; ++q) {
             *reinterpret_cast<float4 *>(&epi[wave][q][slice * 8]) = make_float4(acc[q][0], acc[q][1], acc[q][2], acc[q][3]);
             *reinterpret_cast<float4 *>(&epi[wave][q][slice * 8 + 4]) = make_float4(acc[q][4], acc[q][5], acc[q][6], acc[q][7]);
         }
     }
     if (lane == 0) {
 #pragma unroll
-        for (int q = 0; q < RQ; ++q) {
-            m_s[wave][q] = run_min[q];
-            l_s[wave][q] = lsum[q];
-        }
+        for (int q = 0; q < RQ; ++q) m_s[wave][q] = run_min[q];
+#pragma unroll
+        for (int q = 0; q < RQV; ++q) l_s[wave][q] = lsum[q];
     }
     __syncthreads();
     const size_t part = ((size_t)seq_g * pv.n_q_heads + qh0) * a.n_splits + blockIdx.x;
@@ -209,42 +224,50 @@ __global__ __launch_bounds__(kThreads, RQ >= 8 ? 2 : (RQ >= 4 ? 3 : 4)) void dec
         int hm = 1 << 20;
 #pragma unroll
         for (int w = 0; w < kWaves; ++w) hm = min(hm, m_s[w][q]);
-        float o = 0.0f, l = 0.0f;
+        float o = 0.0f, l = 0.0f, oh = 0.0f, lh = 0.0f;
 #pragma unroll
         for (int w = 0; w < kWaves; ++w) {
+            if (DTAU && m_s[w][q] >= (1 << 20)) continue;                           // a wave that saw no valid token
             const float f = fast_exp2(a.exp2_scale * (float)(hm - m_s[w][q]));      // 0 for a wave that saw no valid token
-            o = fmaf(f, epi[w][q][c], o);
-            l = fmaf(f, l_s[w][q], l);
+            o = fmaf(f, epi[w][NV * q][c], o);
+            l = fmaf(f, l_s[w][NV * q], l);
+            if constexpr (DTAU) {
+                const float k = (float)(m_s[w][q] - hm);                            // the wave counted e from its own minimum
+                oh = fmaf(f, fmaf(k, epi[w][NV * q][c], epi[w][NV * q + 1][c]), oh);
+                lh = fmaf(f, fmaf(k, l_s[w][NV * q], l_s[w][NV * q + 1]), lh);
+            }
         }
         a.part_o[(part + (size_t)q * a.n_splits) * D + c] = o;
+        if constexpr (DTAU) a.part_oh[(part + (size_t)q * a.n_splits) * D + c] = oh;
         if (c == 0) {
-            float *ml = a.part_ml + (part + (size_t)q * a.n_splits) * 2;
+            float *ml = a.part_ml + (part + (size_t)q * a.n_splits) * (DTAU ? 4 : 2);
             ml[0] = __int_as_float(hm);
             ml[1] = l;
+            if constexpr (DTAU) ml[2] = lh;
         }
     }
 }
 
-template <int RQ, int W>
+template <int RQ, int W, bool DTAU>
 hipError_t launch_d(const DecodeArgs &a, const BatchDesc &desc, int seq0, dim3 grid, hipStream_t st) {
     if (a.pool.head_dim == 64) {
-        hipLaunchKernelGGL((decode_split_f16v_kernel<RQ, W, 64>), grid, dim3(kThreads), 0, st, a, desc, seq0);
-    } else if constexpr (RQ <= 4) {                 // 8 heads x 8 accumulators only fit next to a d = 64 batch
-        if (a.pool.head_dim == 128) hipLaunchKernelGGL((decode_split_f16v_kernel<RQ, W, 128>), grid, dim3(kThreads), 0, st, a, desc, seq0);
-        else hipLaunchKernelGGL((decode_split_f16v_kernel<RQ, W, 256>), grid, dim3(kThreads), 0, st, a, desc, seq0);
+        hipLaunchKernelGGL((decode_split_f16v_kernel<RQ, W, 64, DTAU>), grid, dim3(kThreads), 0, st, a, desc, seq0);
+    } else if constexpr (RQ * (DTAU ? 2 : 1) <= 4) {                 // 8 accumulator sets only fit next to a d = 64 batch
+        if (a.pool.head_dim == 128) hipLaunchKernelGGL((decode_split_f16v_kernel<RQ, W, 128, DTAU>), grid, dim3(kThreads), 0, st, a, desc, seq0);
+        else hipLaunchKernelGGL((decode_split_f16v_kernel<RQ, W, 256, DTAU>), grid, dim3(kThreads), 0, st, a, desc, seq0);
     } else {
         return hipErrorInvalidConfiguration;
     }
     return hipGetLastError();
 }
 
-template <int RQ>
+template <int RQ, bool DTAU>
 hipError_t launch_w(const DecodeArgs &a, const BatchDesc &desc, int seq0, dim3 grid, hipStream_t st) {
     switch (a.pool.sketch_bits) {
-        case 64: return launch_d<RQ, 1>(a, desc, seq0, grid, st);
-        case 128: return launch_d<RQ, 2>(a, desc, seq0, grid, st);
-        case 256: return launch_d<RQ, 4>(a, desc, seq0, grid, st);
-        default: return launch_d<RQ, 8>(a, desc, seq0, grid, st);
+        case 64: return launch_d<RQ, 1, DTAU>(a, desc, seq0, grid, st);
+        case 128: return launch_d<RQ, 2, DTAU>(a, desc, seq0, grid, st);
+        case 256: return launch_d<RQ, 4, DTAU>(a, desc, seq0, grid, st);
+        default: return launch_d<RQ, 8, DTAU>(a, desc, seq0, grid, st);
     }
 }
 
@@ -256,11 +279,20 @@ hipError_t launch_decode_split_f16v(const DecodeArgs &a, const BatchDesc &desc, 
     const int rq = (r % 8 == 0 && a.pool.head_dim == 64) ? 8 : (r % 4 == 0 ? 4 : (r % 2 == 0 ? 2 : 1));
     const dim3 grid((unsigned)a.n_splits, (unsigned)(a.pool.n_kv_heads * (r / rq)), (unsigned)n_seqs);
     switch (rq) {
-        case 8: return launch_w<8>(a, desc, seq0, grid, st);
-        case 4: return launch_w<4>(a, desc, seq0, grid, st);
-        case 2: return launch_w<2>(a, desc, seq0, grid, st);
-        default: return launch_w<1>(a, desc, seq0, grid, st);
+        case 8: return launch_w<8, false>(a, desc, seq0, grid, st);
+        case 4: return launch_w<4, false>(a, desc, seq0, grid, st);
+        case 2: return launch_w<2, false>(a, desc, seq0, grid, st);
+        default: return launch_w<1, false>(a, desc, seq0, grid, st);
     }
+}
+
+// The same with the distance-weighted sums of the temperature derivative: two accumulator sets per query head, so
+// at most two query heads per pass.
+hipError_t launch_decode_dtau_split_f16v(const DecodeArgs &a, const BatchDesc &desc, int seq0, int n_seqs, hipStream_t st) {
+    const int r = a.pool.n_q_heads / a.pool.n_kv_heads;
+    const int rq = r % 2 == 0 ? 2 : 1;
+    const dim3 grid((unsigned)a.n_splits, (unsigned)(a.pool.n_kv_heads * (r / rq)), (unsigned)n_seqs);
+    return rq == 2 ? launch_w<2, true>(a, desc, seq0, grid, st) : launch_w<1, true>(a, desc, seq0, grid, st);
 }
 
 }  // namespace h1bkv

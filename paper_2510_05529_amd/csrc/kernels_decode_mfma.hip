@@ -24,6 +24,12 @@
 // few times per chunk) -- and feeds the matrix cores; no workgroup barrier and no pass over the sketches ahead of
 // the values.  The four waves' (max, sum, accumulators) meet once, in the epilogue.  The partial-result format is
 // that of the vector-ALU kernel, so qsketch_kernel and merge_kernel serve both.
+//
+// DTAU = true adds the sums the temperature derivative needs (Sec. IV-C trains tau; see kernels_decode_dtau.hip for the
+// formula): a second weight p e, e = ham - running minimum, for every (token, head).  Its two bf16 parts take operand
+// rows 8-11 and 12-15 next to the plain weights' rows 0-3 and 4-7 -- the MFMAs cost nothing extra, a workgroup then
+// serves at most four query heads.  When a page lowers a head's running minimum by k, every e of that head grows by k:
+// the distance-weighted sums take k times the plain ones before the usual rescale.
 #include <type_traits>
 
 #include "decode_common.h"
@@ -71,10 +77,12 @@ __device__ __forceinline__ float half32_sum(float x) {            // over the 32
 // W: sketch words per token, a compile-time choice: with the width known only at run time the refill of the sketch
 // registers sat behind branches, the registers they merge into were copied right after the loads, and that copy waited
 // for every load in flight -- once per page.
-template <int RQH, int D, int NG, int W>
+template <int RQH, int D, int NG, int W, bool DTAU>
 __global__ __launch_bounds__(kThreads, RQH == 2 ? 3 : 2) void decode_split_mfma_kernel(DecodeArgs a, BatchDesc desc, int seq0, int RQ) {
+    static_assert(!DTAU || RQH == 2, "the distance-weighted rows take the second half of the 16 operand rows");
     constexpr int RQMAX = 2 * RQH;
-    constexpr int NROWS = 2 * RQMAX;              // operand rows in use
+    constexpr int NROWS = (DTAU ? 4 : 2) * RQMAX; // operand rows in use
+    constexpr int NV = DTAU ? 2 : 1;              // sum sets: weight p, and weight p e
     constexpr int NCB = D / 16;                   // 16-channel column blocks
     constexpr int NCB4 = (NCB + 3) / 4;           // 16-byte loads of code words per lane and step
     constexpr int CBG = NCB / NG;                 // column blocks per quantisation group
@@ -84,9 +92,10 @@ __global__ __launch_bounds__(kThreads, RQH == 2 ? 3 : 2) void decode_split_mfma_
     __shared__ int pages_s[kMaxPagesPerChunk];
     __shared__ float f_s[kWaves][RQMAX];          // rescale factors on their way from the scoring lanes to the MFMA rows
     __shared__ int m_s[kWaves][RQMAX];
-    __shared__ float l_s[kWaves][RQMAX];
+    __shared__ float l_s[kWaves][NV][RQMAX];
     __shared__ float sum_s[kWaves][NG][NROWS];
-    __shared__ float zs_s[kWaves][RQMAX][NG];
+    __shared__ float zs_s[kWaves][NV][RQMAX][NG];
+    __shared__ float k_s[kWaves][RQMAX];          // (DTAU) by how much a page lowered each head's running minimum
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const SeqDesc sd = desc.s[blockIdx.z];
@@ -119,14 +128,17 @@ __global__ __launch_bounds__(kThreads, RQH == 2 ? 3 : 2) void decode_split_mfma_
     for (int cb = 0; cb < NCB; ++cb) acc[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int g = 0; g < NG; ++g) accsum[g] = f32x4{0.f, 0.f, 0.f, 0.f};
-    float zs[RQH][NG], lsum[RQH];
+    float zs[NV][RQH][NG], lsum[NV][RQH];
     int run_min[RQH];
 #pragma unroll
     for (int qq = 0; qq < RQH; ++qq) {
-        lsum[qq] = 0.0f;
         run_min[qq] = 1 << 20;
 #pragma unroll
-        for (int g = 0; g < NG; ++g) zs[qq][g] = 0.0f;
+        for (int v = 0; v < NV; ++v) {
+            lsum[v][qq] = 0.0f;
+#pragma unroll
+            for (int g = 0; g < NG; ++g) zs[v][qq][g] = 0.0f;
+        }
     }
     const uint32_t mask = opaque_vgpr(0x000F000Fu), magic = opaque_vgpr(0x43004300u);    // bf16 128.0 in both halves
     BOperand ones;
@@ -202,10 +214,17 @@ __global__ __launch_bounds__(kThreads, RQH == 2 ? 3 : 2) void decode_split_mfma_
             for (int qq = 0; qq < RQH; ++qq) {
                 const int nm = min(run_min[qq], pmin[qq]);
                 const float f = fast_exp2(a.exp2_scale * (float)(nm - run_min[qq]));     // <= 1; 0 when nothing was accumulated yet
+                const float k = (float)(run_min[qq] - nm);                               // (all sums are still 0 the first time)
                 run_min[qq] = nm;
-                lsum[qq] *= f;
+                if constexpr (DTAU) {
+                    lsum[1][qq] = (lsum[1][qq] + k * lsum[0][qq]) * f;
 #pragma unroll
-                for (int g = 0; g < NG; ++g) zs[qq][g] *= f;
+                    for (int g = 0; g < NG; ++g) zs[1][qq][g] = (zs[1][qq][g] + k * zs[0][qq][g]) * f;
+                    if (tk == 0) k_s[wave][2 * qq + qs] = k;
+                }
+                lsum[0][qq] *= f;
+#pragma unroll
+                for (int g = 0; g < NG; ++g) zs[0][qq][g] *= f;
                 if (tk == 0) f_s[wave][2 * qq + qs] = f;
             }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -214,6 +233,20 @@ __global__ __launch_bounds__(kThreads, RQH == 2 ? 3 : 2) void decode_split_mfma_
             float fr[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j) fr[j] = f_s[wave][(4 * kb + j) & (RQMAX - 1)];   // row -> head: high and low rows share it
+            if constexpr (DTAU) {
+                // rows 8-15 (lane groups kb = 2, 3) are the distance-weighted twins of rows 0-7 (kb = 0, 1), 32 lanes away
+                float kr[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) kr[j] = kb >= 2 ? k_s[wave][(4 * kb + j) & (RQMAX - 1)] : 0.0f;
+#pragma unroll
+                for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) acc[cb][j] = fmaf(kr[j], __shfl_xor(acc[cb][j], 32), acc[cb][j]);
+#pragma unroll
+                for (int g = 0; g < NG; ++g)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) accsum[g][j] = fmaf(kr[j], __shfl_xor(accsum[g][j], 32), accsum[g][j]);
+            }
 #pragma unroll
             for (int cb = 0; cb < NCB; ++cb)
 #pragma unroll
@@ -228,12 +261,16 @@ __global__ __launch_bounds__(kThreads, RQH == 2 ? 3 : 2) void decode_split_mfma_
         // ---- two steps of 32 tokens: weights -> A operand, code words -> B operands, MFMA ----
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
-            float p[RQH];
+            float p[NV][RQH];
 #pragma unroll
             for (int qq = 0; qq < RQH; ++qq) {
                 // heads beyond RQ have an all-zero query sketch here; their rows are never read back
-                p[qq] = valid[t] ? fast_exp2(a.exp2_scale * (float)(run_min[qq] - ham[t][qq])) : 0.0f;
-                lsum[qq] += p[qq];
+                p[0][qq] = valid[t] ? fast_exp2(a.exp2_scale * (float)(run_min[qq] - ham[t][qq])) : 0.0f;
+                lsum[0][qq] += p[0][qq];
+                if constexpr (DTAU) {
+                    p[1][qq] = valid[t] ? p[0][qq] * (float)(ham[t][qq] - run_min[qq]) : 0.0f;
+                    lsum[1][qq] += p[1][qq];
+                }
             }
 #pragma unroll
             for (int g = 0; g < NG; ++g) {
@@ -241,14 +278,19 @@ __global__ __launch_bounds__(kThreads, RQH == 2 ? 3 : 2) void decode_split_mfma_
                 const float sc = __half2float(__ushort_as_half((unsigned short)(m & 0xFFFFu)));
                 const float zp = __half2float(__ushort_as_half((unsigned short)(m >> 16)));
 #pragma unroll
-                for (int qq = 0; qq < RQH; ++qq) {
-                    zs[qq][g] = fmaf(p[qq], zp, zs[qq][g]);
-                    const float w = p[qq] * sc;
-                    const uint32_t hi = __float_as_uint(w) & 0xFFFF0000u;
-                    const uint32_t lo = __float_as_uint(w - __uint_as_float(hi));   // exact
-                    a_s[wave][g][2 * qq + qs][tk] = (unsigned short)(hi >> 16);
-                    a_s[wave][g][RQMAX + 2 * qq + qs][tk] = (unsigned short)(lo >> 16);
-                }
+                for (int v = 0; v < NV; ++v)
+#pragma unroll
+                    for (int qq = 0; qq < RQH; ++qq) {
+                        zs[v][qq][g] = fmaf(p[v][qq], zp, zs[v][qq][g]);
+                        const float w = p[v][qq] * sc;
+                        const uint32_t hi = __float_as_uint(w) & 0xFFFF0000u;
+                        // the remainder is exact; its bf16 part is rounded, not cut: cutting both parts leaves every
+                        // weight short by 2^-16 of itself on average, and next to the full-precision sum of p zero
+                        // (which nearly cancels the code term) that bias was the kernel's largest error
+                        const uint32_t lo = __float_as_uint(w - __uint_as_float(hi)) + 0x8000u;
+                        a_s[wave][g][2 * v * RQMAX + 2 * qq + qs][tk] = (unsigned short)(hi >> 16);
+                        a_s[wave][g][(2 * v + 1) * RQMAX + 2 * qq + qs][tk] = (unsigned short)(lo >> 16);
+                    }
             }
             // the operands are read by other lanes of the same wave: order the LDS writes before the reads
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -289,11 +331,13 @@ __global__ __launch_bounds__(kThreads, RQH == 2 ? 3 : 2) void decode_split_mfma_
 
     // ---------------- Epilogue: the four waves meet ----------------
 #pragma unroll
-    for (int qq = 0; qq < RQH; ++qq) {
-        lsum[qq] = half32_sum(lsum[qq]);
+    for (int v = 0; v < NV; ++v)
 #pragma unroll
-        for (int g = 0; g < NG; ++g) zs[qq][g] = half32_sum(zs[qq][g]);
-    }
+        for (int qq = 0; qq < RQH; ++qq) {
+            lsum[v][qq] = half32_sum(lsum[v][qq]);
+#pragma unroll
+            for (int g = 0; g < NG; ++g) zs[v][qq][g] = half32_sum(zs[v][qq][g]);
+        }
     if (4 * kb < NROWS) {
 #pragma unroll
         for (int cb = 0; cb < NCB; ++cb)
@@ -310,9 +354,12 @@ __global__ __launch_bounds__(kThreads, RQH == 2 ? 3 : 2) void decode_split_mfma_
 #pragma unroll
         for (int qq = 0; qq < RQH; ++qq) {
             m_s[wave][2 * qq + qs] = run_min[qq];
-            l_s[wave][2 * qq + qs] = lsum[qq];
 #pragma unroll
-            for (int g = 0; g < NG; ++g) zs_s[wave][2 * qq + qs][g] = zs[qq][g];
+            for (int v = 0; v < NV; ++v) {
+                l_s[wave][v][2 * qq + qs] = lsum[v][qq];
+#pragma unroll
+                for (int g = 0; g < NG; ++g) zs_s[wave][v][2 * qq + qs][g] = zs[v][qq][g];
+            }
         }
     }
     __syncthreads();
@@ -322,48 +369,62 @@ __global__ __launch_bounds__(kThreads, RQH == 2 ? 3 : 2) void decode_split_mfma_
         int hm = 1 << 20;
 #pragma unroll
         for (int w = 0; w < kWaves; ++w) hm = min(hm, m_s[w][q]);
-        float o = 0.0f, l = 0.0f;
+        float o = 0.0f, l = 0.0f, oh = 0.0f, lh = 0.0f;
 #pragma unroll
         for (int w = 0; w < kWaves; ++w) {
+            if (DTAU && m_s[w][q] >= (1 << 20)) continue;                           // a wave that saw no valid token
             const float f = fast_exp2(a.exp2_scale * (float)(hm - m_s[w][q]));      // 0 for a wave that saw no valid token
-            const float ws = sum_s[w][g][q] + sum_s[w][g][RQMAX + q];
-            o = fmaf(f, fmaf(-128.0f, ws, epi[w][q][c] + epi[w][RQMAX + q][c]) + zs_s[w][q][g], o);   // B held 128 + code
-            l = fmaf(f, l_s[w][q], l);
+            float val[NV];
+#pragma unroll
+            for (int v = 0; v < NV; ++v) {
+                const int hi_row = 2 * v * RQMAX + q, lo_row = hi_row + RQMAX;
+                const float ws = sum_s[w][g][hi_row] + sum_s[w][g][lo_row];
+                val[v] = fmaf(-128.0f, ws, epi[w][hi_row][c] + epi[w][lo_row][c]) + zs_s[w][v][q][g];   // B held 128 + code
+            }
+            o = fmaf(f, val[0], o);
+            l = fmaf(f, l_s[w][0][q], l);
+            if constexpr (DTAU) {
+                const float k = (float)(m_s[w][q] - hm);                            // the wave counted e from its own minimum
+                oh = fmaf(f, fmaf(k, val[0], val[NV - 1]), oh);
+                lh = fmaf(f, fmaf(k, l_s[w][0][q], l_s[w][NV - 1][q]), lh);
+            }
         }
         a.part_o[(part + (size_t)q * a.n_splits) * D + c] = o;
+        if constexpr (DTAU) a.part_oh[(part + (size_t)q * a.n_splits) * D + c] = oh;
         if (c == 0) {
-            float *ml = a.part_ml + (part + (size_t)q * a.n_splits) * 2;
+            float *ml = a.part_ml + (part + (size_t)q * a.n_splits) * (DTAU ? 4 : 2);
             ml[0] = __int_as_float(hm);
             ml[1] = l;
+            if constexpr (DTAU) ml[2] = lh;
         }
     }
 }
 
-template <int RQH, int D, int NG>
+template <int RQH, int D, int NG, bool DTAU>
 hipError_t launch_w(const DecodeArgs &a, const BatchDesc &desc, int seq0, dim3 grid, int rq, hipStream_t st) {
     switch (a.pool.sketch_bits) {
-        case 64: hipLaunchKernelGGL((decode_split_mfma_kernel<RQH, D, NG, 1>), grid, dim3(kThreads), 0, st, a, desc, seq0, rq); break;
-        case 128: hipLaunchKernelGGL((decode_split_mfma_kernel<RQH, D, NG, 2>), grid, dim3(kThreads), 0, st, a, desc, seq0, rq); break;
-        case 256: hipLaunchKernelGGL((decode_split_mfma_kernel<RQH, D, NG, 4>), grid, dim3(kThreads), 0, st, a, desc, seq0, rq); break;
+        case 64: hipLaunchKernelGGL((decode_split_mfma_kernel<RQH, D, NG, 1, DTAU>), grid, dim3(kThreads), 0, st, a, desc, seq0, rq); break;
+        case 128: hipLaunchKernelGGL((decode_split_mfma_kernel<RQH, D, NG, 2, DTAU>), grid, dim3(kThreads), 0, st, a, desc, seq0, rq); break;
+        case 256: hipLaunchKernelGGL((decode_split_mfma_kernel<RQH, D, NG, 4, DTAU>), grid, dim3(kThreads), 0, st, a, desc, seq0, rq); break;
         default: return hipErrorInvalidValue;      // see mfma_decode_supported
     }
     return hipGetLastError();
 }
 
-template <int RQH, int D>
+template <int RQH, int D, bool DTAU>
 hipError_t launch_ng(const DecodeArgs &a, const BatchDesc &desc, int seq0, dim3 grid, int rq, hipStream_t st) {
     const int ng = D / a.pool.group_size;
-    if (ng == 1) return launch_w<RQH, D, 1>(a, desc, seq0, grid, rq, st);
-    if (ng == 2) return launch_w<RQH, D, 2>(a, desc, seq0, grid, rq, st);
-    if (ng == 4) return launch_w<RQH, D, 4>(a, desc, seq0, grid, rq, st);
+    if (ng == 1) return launch_w<RQH, D, 1, DTAU>(a, desc, seq0, grid, rq, st);
+    if (ng == 2) return launch_w<RQH, D, 2, DTAU>(a, desc, seq0, grid, rq, st);
+    if (ng == 4) return launch_w<RQH, D, 4, DTAU>(a, desc, seq0, grid, rq, st);
     return hipErrorInvalidValue;
 }
 
-template <int RQH>
+template <int RQH, bool DTAU>
 hipError_t launch_d(const DecodeArgs &a, const BatchDesc &desc, int seq0, dim3 grid, int rq, hipStream_t st) {
     switch (a.pool.head_dim) {
-        case 64: return launch_ng<RQH, 64>(a, desc, seq0, grid, rq, st);
-        case 128: return launch_ng<RQH, 128>(a, desc, seq0, grid, rq, st);
+        case 64: return launch_ng<RQH, 64, DTAU>(a, desc, seq0, grid, rq, st);
+        case 128: return launch_ng<RQH, 128, DTAU>(a, desc, seq0, grid, rq, st);
         default: return hipErrorInvalidValue;      // see mfma_decode_supported
     }
 }
@@ -374,7 +435,15 @@ hipError_t launch_decode_split_mfma(const DecodeArgs &a, const BatchDesc &desc, 
     const int r = a.pool.n_q_heads / a.pool.n_kv_heads;
     const int rq = mfma_heads_per_wg(r);
     const dim3 grid((unsigned)a.n_splits, (unsigned)(a.pool.n_kv_heads * (r / rq)), (unsigned)n_seqs);
-    return rq <= 4 ? launch_d<2>(a, desc, seq0, grid, rq, st) : launch_d<4>(a, desc, seq0, grid, rq, st);
+    return rq <= 4 ? launch_d<2, false>(a, desc, seq0, grid, rq, st) : launch_d<4, false>(a, desc, seq0, grid, rq, st);
+}
+
+// The same with the distance-weighted sums of the temperature derivative: at most four query heads per workgroup.
+hipError_t launch_decode_dtau_split_mfma(const DecodeArgs &a, const BatchDesc &desc, int seq0, int n_seqs, hipStream_t st) {
+    const int r = a.pool.n_q_heads / a.pool.n_kv_heads;
+    const int rq = r % 4 == 0 ? 4 : (r % 3 == 0 ? 3 : (r % 2 == 0 ? 2 : 1));
+    const dim3 grid((unsigned)a.n_splits, (unsigned)(a.pool.n_kv_heads * (r / rq)), (unsigned)n_seqs);
+    return launch_d<2, true>(a, desc, seq0, grid, rq, st);
 }
 
 }  // namespace h1bkv

@@ -35,6 +35,15 @@ def rel_err(out: np.ndarray, ref: np.ndarray) -> float:
     return float(np.max(np.where(den > 0, num / np.where(den > 0, den, 1), np.where(num > 0, np.inf, 0))))
 
 
+def elem_rel_err(out: np.ndarray, ref: np.ndarray, floor: float = 1e-3) -> float:
+    """Worst single element: |out - ref| / max(|ref|, floor * max_c |ref|) per head vector.  Reported next to rel_err: a
+    softmax-weighted mean over a long context has elements near zero, where a purely element-wise ratio is ill-posed."""
+    out = out.reshape(-1, out.shape[-1]).astype(np.float64)
+    ref = ref.reshape(-1, ref.shape[-1]).astype(np.float64)
+    den = np.maximum(np.abs(ref), floor * np.abs(ref).max(axis=1, keepdims=True))
+    return float(np.max(np.where(den > 0, np.abs(out - ref) / np.where(den > 0, den, 1), 0.0)))
+
+
 def assert_cache_equal(cache: B.Cache, ocache, seq_ids, n_tokens, heads=None):
     """Bit-exact comparison of every exported plane against the oracle's canonical cache."""
     heads = range(ocache.Hkv) if heads is None else heads

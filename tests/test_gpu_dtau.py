@@ -33,7 +33,7 @@ def test_output_and_derivative_match_the_oracle(d, b, g, r, dt, T):
     cache.close()
 
 
-def test_ragged_contexts_and_unsupported_layout():
+def test_ragged_contexts():
     d, b, g, T = 128, 128, 32, 600
     w = wl.Workload("dtau_ragged", 3, 2, 2, d, T, b, g, "f16", seed=91)
     R = wl.projection(b, d)
@@ -52,12 +52,76 @@ def test_ragged_contexts_and_unsupported_layout():
     assert np.array_equal(dout[1], np.zeros_like(dout[1])) and np.array_equal(dout[2], np.zeros_like(dout[2]))
     assert rel_err(out.cpu().numpy(), ref) <= TOL and rel_err(dout, dref) <= TOL
     cache.close()
-    # grouped-query caches keep their codes token-interleaved: the derivative kernel does not read that layout
-    w4 = wl.Workload("dtau_gqa", 1, 8, 2, d, 64, b, g, "f16", seed=3)
-    c4 = make_cache(w4, R)
-    import torch
-    ws = torch.empty(1 << 20, dtype=torch.uint8, device="cuda")
-    o = torch.empty((1, 8, d), dtype=torch.float32, device="cuda")
-    rc = B.h1bkv_decode_attn_dtau(c4.h, [0], to_dev(wl.queries(w4)), 0.1, o, o.clone(), ws, ws.numel())
-    assert rc == B.H1BKV_ESHAPE
-    c4.close()
+
+
+# grouped-query caches (token-interleaved codes, matrix-core kernel): (head_dim, bits, group, r, dtype, context)
+GQA_CASES = [(128, 128, 32, 4, "f16", 1333), (128, 256, 64, 4, "f16", 2100), (64, 64, 32, 8, "f32", 700),
+             (128, 128, 64, 3, "f16", 520), (64, 128, 64, 6, "f16", 300), (128, 64, 128, 16, "f16", 257)]
+
+
+@pytest.mark.parametrize("d,b,g,r,dt,T", GQA_CASES)
+def test_grouped_query_caches(d, b, g, r, dt, T):
+    w = wl.Workload(f"dtau_gqa_d{d}_b{b}_g{g}_r{r}_{dt}", 2, 2 * r, 2, d, T, b, g, dt, seed=7 * d + b + r + T)
+    R = wl.projection(b, d)
+    seqs = [0, 1]
+    k, v, q = wl.kv_slab(w, "k", seqs, 0, T), wl.kv_slab(w, "v", seqs, 0, T), wl.queries(w)
+    oc = cref.Cache(R, 2, 2, T, g)
+    oc.append(k, v)
+    cache = make_cache(w, R, pool_fill=0x7E)
+    cache.append(seqs, to_dev(k), to_dev(v))
+    lens = [T, max(1, T // 3)]
+    B.check(B.h1bkv_truncate_seq(cache.h, 1, lens[1]))
+    worst = [0.0, 0.0]
+    for tau, chunk in ((w.default_tau(), 0), (0.3, 256), (2.0, 512), (0.01, 0)):
+        assert B.h1bkv_set_decode_chunk(cache.h, chunk) == B.H1BKV_OK
+        out, dout = cache.decode_dtau(seqs, to_dev(q), tau)
+        ref, dref = oc.decode_dtau(q, tau, ctx_len=lens)
+        plain = cache.decode(seqs, to_dev(q), tau)
+        assert rel_err(out.cpu().numpy(), plain.cpu().numpy()) <= 1e-5      # same weights, same matrix-core products
+        worst = [max(worst[0], rel_err(out.cpu().numpy(), ref)), max(worst[1], rel_err(dout.cpu().numpy(), dref))]
+    print(f"d={d} b={b} G={g} r={r}: out {worst[0]:.2e}, d out/d tau {worst[1]:.2e}")
+    assert worst[0] <= TOL and worst[1] <= TOL
+    cache.close()
+
+
+# fp16-value caches ("1-bit key only" variant): (head_dim, bits, r, dtype, context)
+F16V_CASES = [(128, 128, 1, "f16", 900), (64, 64, 2, "f32", 300), (256, 256, 1, "f16", 520), (128, 512, 4, "f16", 700),
+              (64, 128, 3, "f16", 257)]
+
+
+@pytest.mark.parametrize("d,b,r,dt,T", F16V_CASES)
+def test_fp16_value_caches(d, b, r, dt, T):
+    w = wl.Workload(f"dtau_f16v_d{d}_b{b}_r{r}_{dt}", 2, 2 * r, 2, d, T, b, 32, dt, seed=11 * d + b + r + T)
+    R = wl.projection(b, d)
+    seqs = [0, 1]
+    k, v, q = wl.kv_slab(w, "k", seqs, 0, T), wl.kv_slab(w, "v", seqs, 0, T), wl.queries(w)
+    oc = cref.Cache(R, 2, 2, T, 32, value_bits=16)
+    oc.append(k, v)
+    cache = make_cache(w, R, value_bits=16, pool_fill=0x7E)
+    cache.append(seqs, to_dev(k), to_dev(v))
+    lens = [T, max(1, T // 2 + 3)]
+    B.check(B.h1bkv_truncate_seq(cache.h, 1, lens[1]))
+    for tau, chunk in ((w.default_tau(), 0), (0.3, 256), (2.0, 512), (0.01, 0)):
+        assert B.h1bkv_set_decode_chunk(cache.h, chunk) == B.H1BKV_OK
+        out, dout = cache.decode_dtau(seqs, to_dev(q), tau)
+        ref, dref = oc.decode_dtau(q, tau, ctx_len=lens)
+        assert rel_err(out.cpu().numpy(), ref) <= TOL
+        assert rel_err(dout.cpu().numpy(), dref) <= TOL
+    cache.close()
+
+
+def test_record_major_codes_with_many_query_heads():
+    """Geometries the matrix-core kernel does not keep in registers (head_dim 256) store record-major codes also with
+    several query heads per KV head: the vector kernel then serves every query head in a pass of its own."""
+    d, b, g, r, T = 256, 128, 64, 4, 400
+    w = wl.Workload("dtau_d256_r4", 1, 2 * r, 2, d, T, b, g, "f16", seed=77)
+    R = wl.projection(b, d)
+    k, v, q = wl.kv_slab(w, "k", [0], 0, T), wl.kv_slab(w, "v", [0], 0, T), wl.queries(w)
+    oc = cref.Cache(R, 1, 2, T, g)
+    oc.append(k, v)
+    cache = make_cache(w, R, pool_fill=0x7E)
+    cache.append([0], to_dev(k), to_dev(v))
+    out, dout = cache.decode_dtau([0], to_dev(q), 0.08)
+    ref, dref = oc.decode_dtau(q, 0.08)
+    assert rel_err(out.cpu().numpy(), ref) <= TOL and rel_err(dout.cpu().numpy(), dref) <= TOL
+    cache.close()

@@ -9,7 +9,7 @@ import pytest
 from oracle import cref
 from paper_2510_05529_amd import binding as B
 from paper_2510_05529_amd import workloads as wl
-from tests.gpu_util import TOL, make_cache, rel_err, to_dev
+from tests.gpu_util import TOL, elem_rel_err, make_cache, rel_err, to_dev
 
 pytestmark = pytest.mark.gpu
 WORKERS = min(16, os.cpu_count() or 1)
@@ -40,7 +40,7 @@ def check_samples(w, samples):
     tau = w.default_tau()
     out = cache.decode(seqs, to_dev(q), tau).cpu().numpy()
     assert np.isfinite(out).all()
-    worst = 0.0
+    worst, worst_elem = 0.0, 0.0
     for seq, kvh in samples:
         sk, codes, scale, zero = oracle_head(w, R, seq, kvh)
         g_sk, g_codes, g_scale, g_zero = cache.export(seq, kvh, 0, w.context)
@@ -50,8 +50,13 @@ def check_samples(w, samples):
         for qh in range(kvh * w.q_per_kv, (kvh + 1) * w.q_per_kv):
             ref = cref.decode_one(cref.sketch(R, q[seq, qh][None])[0], sk, codes, scale, zero, w.sketch_bits, w.group_size, tau)
             worst = max(worst, rel_err(out[seq, qh][None], ref[None]))
-    print(f"{w.name}: {len(samples)} sampled heads, worst rel err {worst:.3e}")
+            worst_elem = max(worst_elem, elem_rel_err(out[seq, qh][None], ref[None]))
+    print(f"{w.name}: {len(samples)} sampled (sequence, KV head) pairs, worst error per head vector {worst:.3e}, "
+          f"worst element-wise relative error (floor 1e-3 of the vector's largest magnitude) {worst_elem:.3e}")
     assert worst <= TOL
+    # an element at the floor is at most 1000 times smaller than the vector's largest: the element-wise figure is
+    # bounded by 1000 times the vector figure, and in practice sits far below it
+    assert worst_elem <= 1000 * TOL
     # every head, sampled or not: finite, and bounded by the range of the fp16 inputs (a softmax-weighted mean
     # of dequantised values cannot leave the range of the values themselves)
     assert np.abs(out).max() <= 65504.0
@@ -65,12 +70,13 @@ def test_full_decode_7b_8k_every_head():
 
 def test_full_decode_b16_32k_sampled():
     w = wl.WORKLOADS["decode_b16_32k"]
-    check_samples(w, [(0, 0), (5, 17), (15, 31), (9, 8)])
+    # one head of every sequence (a different one each) and every head of one sequence: 47 of the 512 pairs
+    check_samples(w, sorted({(s, (7 * s + 3) % w.n_kv_heads) for s in range(w.batch)} | {(9, h) for h in range(w.n_kv_heads)}))
 
 
 def test_full_decode_gqa_128k_sampled():
     w = wl.WORKLOADS["decode_gqa_128k"]
-    check_samples(w, [(0, 0), (3, 7), (2, 4)])
+    check_samples(w, [(0, 0), (3, 7), (2, 4), (1, 5)])
 
 
 def test_full_append_prefill_8k_every_record():

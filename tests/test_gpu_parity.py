@@ -90,8 +90,9 @@ def test_split_count_does_not_change_the_result():
     for chunk in (256, 512, 1024, 2048, 8192, 0):
         assert B.h1bkv_set_decode_chunk(cache.h, chunk) == B.H1BKV_OK
         outs.append(cache.decode(seqs, q, w.default_tau()).cpu().numpy())
-    for o in outs[1:]:
-        assert rel_err(o, outs[0]) < 1e-4          # only the fp32 summation order differs
+    spread = max(rel_err(o, outs[0]) for o in outs[1:])
+    print(f"chunk-to-chunk spread of the outputs: {spread:.3e}")
+    assert spread < 1e-5          # only the fp32 summation order differs
     cache.close()
 
 
@@ -136,7 +137,7 @@ def test_page_assignment_does_not_matter_and_pages_are_reused():
         for x, y in zip(a, b):
             assert np.array_equal(x, y)
     out2 = cache.decode([0, 1], q, 0.06).cpu().numpy()
-    assert rel_err(out2, out1) < 1e-4
+    assert np.array_equal(out2, out1)          # which physical pages hold the tokens changes no summation order
     cache.close()
 
 
