@@ -21,7 +21,8 @@ H1BKV_PAGE_TOKENS = 256
 H1BKV_STATIC_SCRATCH_BYTES = 16 << 20
 H1BKV_K_APPEND, H1BKV_K_QSKETCH, H1BKV_K_DECODE_SPLIT, H1BKV_K_MERGE, H1BKV_K_PREFILL = 0, 1, 2, 3, 4
 
-LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "lib", "libh1bkv.so")
+# H1BKV_LIBRARY names another build of the same library (a debug or experimental build); default: the in-tree one
+LIB_PATH = os.environ.get("H1BKV_LIBRARY") or os.path.join(os.path.dirname(os.path.abspath(__file__)), "lib", "libh1bkv.so")
 
 
 class h1bkv_config(C.Structure):

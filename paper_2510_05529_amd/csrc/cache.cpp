@@ -654,8 +654,7 @@ static int enqueue_decode(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n
             Timed t(c, H1BKV_K_QSKETCH, st);
             // Thousands of fp16 queries (large batches): the prefill path's matrix-core projection with its guard band
             // (same bits as the chain); the queries are then one position per sequence.
-            const bool mfma_q = c->proj_mfma && prefill_supported(c->cfg.head_dim, c->code_layout) &&
-                                (int64_t)n * c->cfg.n_q_heads >= 2048;
+            const bool mfma_q = c->proj_mfma && c->cfg.head_dim <= 128 && (int64_t)n * c->cfg.n_q_heads >= 2048;
             if (mfma_q) {
                 PrefillArgs pa{};
                 pa.pool = a.pool;
@@ -822,7 +821,6 @@ int h1bkv_prefill_attn(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n_se
     int rc = check_seq_ids(c, seq_ids_host, n_seqs);
     if (rc != H1BKV_OK) return rc;
     if (n_q < 1 || !(tau > 0.0f) || !std::isfinite(tau)) return H1BKV_EINVAL;
-    if (!prefill_supported(c->cfg.head_dim, c->code_layout)) return H1BKV_ESHAPE;
     for (int i = 0; i < n_seqs; ++i)
         if (c->seq_len[seq_ids_host[i]] < n_q) return H1BKV_ERANGE;
     if (stride_seq < 0 || stride_tok < 0 || stride_head < c->cfg.head_dim) return H1BKV_EINVAL;

@@ -117,9 +117,6 @@ inline int prefill_max_splits(int n_q_heads, int n_seqs, int n_q) {
     return (int)(s < 1 ? 1 : s > kPrefillMaxSplits ? kPrefillMaxSplits : s);
 }
 
-// The prefill kernel keeps a row block's accumulators (d/16 MFMA tiles) in registers.
-inline bool prefill_supported(int head_dim, int) { return head_dim <= 128; }
-
 // Query heads one matrix-core decode workgroup serves: the largest divisor of r that is at most 8.
 inline int mfma_heads_per_wg(int r) {
     for (int q = 8; q > 1; --q)

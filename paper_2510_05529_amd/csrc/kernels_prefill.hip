@@ -2,25 +2,28 @@
 // query i of a sequence attends to the cached tokens up to and including its own position, exactly the decode step
 // it would have seen had the prompt been fed one token at a time.
 //
-// With many queries per KV head both halves of the step are dense contractions and run on the matrix cores:
-//   scores    alpha needs the Hamming distance of every (query, key) pair.  With the key bits unpacked to {0,1} bytes
-//             and the query bits to {+4,-4} bytes,  sum_k q_k key_k = 4 (popcount(q) - ham),  so one int8 MFMA
-//             (v_mfma_i32_16x16x64_i8) per 64 sketch bits yields 16 x 16 distances -- instead of 4 W XOR/popcount
-//             instructions per pair on the vector ALUs.  The MFMA is issued as keys x queries, so that a lane ends
-//             up holding distances of ONE query row against several tokens: the slot it has in the next MFMA.
+// With many queries per KV head both halves of the step are dense contractions and run on the matrix cores, in 32 x 32
+// tiles (32 query rows per wave: every operand read from LDS feeds twice the rows of a 16-row tile, and LDS traffic,
+// not matrix time, is what a 16-row formulation of this kernel was bound by):
+//   scores    alpha needs the Hamming distance of every (query, key) pair.  With the key bits as fp4 numbers {0, 0.5}
+//             and the negated query bits as fp4 {-4, +4},  sum_k key_k nq_k = 2 (ham - popcount(q)),  exactly, in fp32:
+//             one v_mfma_scale_f32_32x32x64_f8f6f4 per 64 sketch bits (unit scales) yields 32 x 32 distances at four
+//             times the fp16 rate -- instead of 4 W XOR/popcount instructions per pair on the vector ALUs.  The MFMA is
+//             issued as keys x queries, so that a lane ends up holding distances of ONE query row against 16 tokens:
+//             the slots it has in the next MFMA.  Its accumulator input is a per-lane constant 2^23 + 2 (popcount(q) -
+//             reference + slack): the low bits of the result ARE the byte offset of the pair's weight in a table.
 //   weights   p = exp((alpha - alpha_ref)/tau) takes only a few hundred values (the distance from the row's reference
-//             distance is an integer): one LDS table read per pair instead of an exponential, at the byte offset
-//             4 (popcount(q) - ref) - score (hence the +-4).  The reference is a running minimum with slack: it is
+//             distance is an integer): one 16-bit LDS table read per pair, straight into one half of an operand
+//             register -- no exponential, no conversion.  The reference is a running minimum with slack: it is
 //             renewed, and the accumulators rescaled, only when a distance falls further below it than the fp16 range
-//             of the weights allows.  Weights are packed to fp16 in registers as the A operand of the second MFMA;
-//             the normalisation uses the row sums of the SAME fp16 weights (one more MFMA against an all-ones B).
-//   values    sum_t p[i][t] v^[t][c]  with v_mfma_f32_16x16x32_f16, fp32 accumulate.
-// One workgroup (8 waves) takes 128 consecutive query positions of one (sequence, query head) -- 16 rows per wave --
-// and walks the key tokens in tiles up to its diagonal.  Per tile the workgroup stages ONCE, for all its rows: the
-// keys' bits as bytes, and the values dequantised, v^ = fp16(scale * code + zero), channel-major, in the token order
-// the score MFMA leaves its results in (so an MFMA B operand is one 16-byte LDS read).  The next tile's global loads
-// are issued before the current tile is consumed.  Tiles entirely below a wave's rows take an unmasked path; tiles
-// entirely above them are skipped.
+//             of the weights allows.  The normalisation uses the sums of the SAME fp16 weights (two per v_dot2).
+//   values    sum_t p[i][t] v^[t][c]  with v_mfma_f32_32x32x16_f16, fp32 accumulate.
+// One workgroup (4 waves) takes 128 consecutive query positions of one (sequence, query head) -- 32 rows per wave --
+// and walks the key tokens in tiles of 64 up to its diagonal.  Per tile the workgroup stages ONCE, for all its rows: the
+// keys' bits as fp4 nibbles, and the values dequantised, v^ = fp16(scale * code + zero), channel-major, in the token
+// order the score MFMA leaves its results in (so an MFMA B operand is one 16-byte LDS read).  The next tile's global
+// loads are issued before the current tile is consumed.  Tiles entirely below a wave's rows take an unmasked path;
+// tiles entirely above them are skipped.  A head of 256 channels is served by two workgroups of 128 channels each.
 // sketch_rows_kernel sketches the chunk's query vectors (Eq.(2), same fp32 FMA chain as the keys) with the R rows
 // resident in registers, 64 vectors per LDS tile.
 #include <hip/hip_fp16.h>
@@ -37,78 +40,73 @@ namespace {
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef _Float16 h16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef int i32x8 __attribute__((ext_vector_type(8)));
 
-// Eight waves of one 16-row block each: the same 128 query rows and the same LDS tiles per workgroup as four waves of
-// two blocks, at half the registers per wave, so that four waves share a SIMD (a single wave issues a vector
-// instruction only every five clocks or so; two workgroups per compute unit also cover each other's barriers).
-constexpr int kPfWaves = 8;
+constexpr int kPfWaves = 4;
 constexpr int kPfThreads = kPfWaves * 64;
-constexpr int kRB = 1;                        // 16-row blocks per wave
-constexpr int kQB = kPfWaves * 16 * kRB;      // query positions per workgroup
+constexpr int kQB = kPfWaves * 32;            // query positions per workgroup
 constexpr int kCS = 8;                        // channels per staging item of the token-major layouts
+constexpr int kTK = 64;                       // key tokens per tile
 constexpr float kPScaleLog2 = 4.0f;           // weights are stored as p * 2^4
 constexpr float kPSlackLog2 = 11.0f;          // and may exceed 1 by up to 2^11 (p 2^4 <= 2^15 stays finite in fp16)
+constexpr int kUnitScale = 0x7F7F7F7F;        // E8M0 block scales of the fp4 MFMA: 2^0
 
 union HalfOperand {
     uint32_t u[4];
     f16x8 v;
 };
-union ByteOperand {
-    uint32_t u[4];
-    i32x4 v;
+union NibbleOperand {        // 32 fp4 numbers in the first four dwords (the instruction's 8-dword form is for fp8)
+    uint32_t u[8];
+    i32x8 v;
 };
 
-__device__ __forceinline__ int xor16_min(int x) {       // min with the lane 16 away (immediate swizzle, inside a half-wave)
-    return min(x, __builtin_amdgcn_ds_swizzle(x, 0x1F | (0x10 << 10)));
-}
-__device__ __forceinline__ int xor32_min(int x) {       // min with the lane 32 away
-    const auto r = __builtin_amdgcn_permlane32_swap((unsigned)x, (unsigned)x, false, false);
-    return min((int)r[0], (int)r[1]);
-}
-// Bits 0..3 of x -> the low bits of bytes 0..3: the 24-bit multiply by 0x204081 puts copies of the nibble at bit
-// offsets 0, 7, 14, 21, so that bit k lands on bit 8 k (full-rate multiply; three instructions with the extract).
-__device__ __forceinline__ uint32_t spread4(uint32_t x) {
-    return __umul24(x & 0xFu, 0x00204081u) & 0x01010101u;
+__device__ __forceinline__ float xor32_min(float x) {       // min with the lane 32 away
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fminf(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
 
-template <int NDW>
+template <int NSK, int LAYOUT>
 struct StageRegs {           // one thread's share of a key tile on its way from global memory to LDS
-    uint32_t skd[NDW];       // 16 sketch bits each
-    uint32_t c[2];           // layout 0: kCS / 2 bytes of codes for each of two tokens;  layout 1: up to 2 code words of one block
-    uint32_t m[16];          // layout 0: {scale, zero} of the two tokens;  layout 1: of the block's 8 tokens, for each
-                             //           of the thread's words;  layout 2: kCS fp16 values of each of the two tokens
+    uint32_t skd[NSK];       // 32 sketch bits each
+    // layout 0: one item of (token pair, 16 channels): 8 bytes of codes per token, {scale, zero} per token
+    // layout 1: 4 code words (4 neighbouring channels, one block of 8 tokens) and the block's 8 {scale, zero}
+    // layout 2: 2 items of (token pair, 8 channels): 8 fp16 values per token
+    uint32_t c[4];
+    uint32_t m[LAYOUT == 2 ? 16 : 8];
 };
 
-template <int W, int D, int LAYOUT>
-__global__ __launch_bounds__(kPfThreads, W >= 8 ? 2 : 4) void prefill_kernel(PrefillArgs a, BatchDesc desc, int seq0) {
-    constexpr int NCB = D / 16;
-    constexpr int TK = W <= 2 ? 64 : 32;          // key tokens per tile (wide sketches: smaller tiles, same LDS budget)
+template <int W, int DTOT, int LAYOUT>
+__global__ __launch_bounds__(kPfThreads, 2) void prefill_kernel(PrefillArgs a, BatchDesc desc, int seq0) {
+    constexpr int D = DTOT > 128 ? 128 : DTOT;    // channels per workgroup
+    constexpr int NHALF = DTOT / D;               // workgroups per head
+    constexpr int NCB = D / 32;                   // 32-channel column blocks
+    constexpr int TK = kTK;
     constexpr int NSTEP = TK / 32;                // 32-token MFMA steps per tile
     constexpr int VS = TK * 2 + 16;               // bytes per channel row of the value tile (16 B pad: conflict-free b128 reads)
-    constexpr int KS = 64 * W + 16;               // bytes per token row of the key-bit tile (same padding)
-    constexpr int DWT = TK * 4 * W;               // 16-bit sketch units per tile
-    constexpr int NDW = DWT > kPfThreads ? DWT / kPfThreads : 1;
+    constexpr int KS = 32 * W + 16;               // bytes per token row of the key tile: 2 W sketch dwords, 16 B of nibbles each
+    constexpr int NSKD = TK * 2 * W;              // 32-bit sketch units per tile
+    constexpr int NSK = NSKD / kPfThreads > 0 ? NSKD / kPfThreads : 1;
+    static_assert(NSKD % kPfThreads == 0 || NSKD < kPfThreads, "sketch dwords split evenly over the threads");
     __shared__ __attribute__((aligned(16))) unsigned char v_s[2][D * VS];
     __shared__ __attribute__((aligned(16))) unsigned char k_s[2][TK * KS];
-    // p(e) = 2^4 exp(-2 e / (b tau)) for every distance e from a row's reference distance, e = -S .. b; one more
-    // entry holds 0 for masked pairs.  One LDS read per pair replaces convert + multiply-add + exponential (a
+    // p(e) = 2^4 exp(-2 e / (b tau)) as fp16 for every distance e from a row's reference distance, e = -S .. b; one
+    // more entry holds 0 for masked pairs.  One LDS read per pair replaces convert + multiply-add + exponential (a
     // quarter-rate instruction).  The reference is the smallest distance the row had seen when it was last set and
     // is only renewed (accumulators rescaled) when a distance falls more than S below it, S the largest slack whose
     // weights still fit fp16 (exp(2 S / (b tau)) <= 2^11): the best distance of a row improves by a few units many
     // times over a long context, and rescaling on each of them was a tenth of the vector work.
-    __shared__ float ptab[128 * W + 2];
+    __shared__ _Float16 ptab[128 * W + 4];
     // The sequence's page ids, read once: a block-table lookup per tile from global memory sits, with its full memory
     // latency, in front of every tile's loads.
     constexpr int kPagesLds = 1024;
     __shared__ int pages_s[kPagesLds];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int i = lane & 15, kb = lane >> 4;
-    // grid (query head, sequence, query block x context split): workgroups are dispatched x-fastest, so the
-    // longest-running (latest) query blocks of ALL heads and sequences start first and the short ones fill the tail of
-    // the launch.  With n_splits > 1 (a chunk that is short against its context) a workgroup walks only its share of
+    const int i = lane & 31, g = lane >> 5;
+    // grid (query head [x channel half], sequence, query block x context split): workgroups are dispatched x-fastest, so
+    // the longest-running (latest) query blocks of ALL heads and sequences start first and the short ones fill the tail
+    // of the launch.  With n_splits > 1 (a chunk that is short against its context) a workgroup walks only its share of
     // the block's key tiles and leaves (sums, weight sum, reference distance) per row for prefill_merge_kernel.
     const SeqDesc sd = desc.s[blockIdx.y];
     const int len = sd.pos, n_q = a.n_q;
@@ -122,141 +120,166 @@ __global__ __launch_bounds__(kPfThreads, W >= 8 ? 2 : 4) void prefill_kernel(Pre
 
     const PoolView &pv = a.pool;
     const int H = pv.n_kv_heads, Hq = pv.n_q_heads, r = Hq / H;
-    const int h = blockIdx.x, kvh = h / r;
+    const int h = (int)blockIdx.x / NHALF, half = (int)blockIdx.x % NHALF, kvh = h / r;
     const int seq_g = seq0 + blockIdx.y;
-    const int ng = D / pv.group_size;
+    const int ng = DTOT / pv.group_size;
     const int32_t *bt = pv.block_table + (size_t)sd.seq_id * pv.max_pages_per_seq;
 
-    // ---- this lane's query rows: position, popcount, and bits 16 kb .. 16 kb + 15 of every 64-bit word as +-4 bytes ----
-    // (+-4, not +-1: the score MFMA then returns 4 (popcount(q) - ham), and 4 (ham - ham_min) is the byte offset of the
-    // pair's weight in the table, with no shift and no separate distance)
-    int pos[kRB], pcq[kRB];       // pos: absolute position of row (rb, i), -1 for rows past the chunk;  pcq: 4 popcount(q)
-    ByteOperand qpm[kRB][W];
+    // ---- this lane's query row: position, popcount, and for every 64 sketch bits the lane group's 32 bits as fp4 ----
+    // Sketch dword x is spread over four operand dwords: dword j holds bits j, j + 4, ..., j + 28 of x, one per nibble --
+    // (x >> j) & 0x11111111 for the keys (fp4 0.5 = 0b0001), and -4 / +4 (0b1110 / 0b0110) for a set / clear query bit.
+    // The order of the K index inside an operand is free as long as both operands use the same one.
+    const int wave_row0 = row0 + wave * 32;
+    const int qi = wave_row0 + i;
+    const int pos = qi < n_q ? q0 + qi : -1;          // absolute position of this lane's row, -1 for rows past the chunk
+    int pcq = 0;                                      // popcount of the row's query sketch
+    NibbleOperand qop[W];
 #pragma unroll
-    for (int rb = 0; rb < kRB; ++rb) {
-        const int qi = row0 + wave * 16 * kRB + rb * 16 + i;
-        pos[rb] = qi < n_q ? q0 + qi : -1;
-        pcq[rb] = 0;
+    for (int w = 0; w < W; ++w) {
+        const uint64_t sq = qi < n_q ? a.q_sketch[(((size_t)seq_g * n_q + qi) * Hq + h) * W + w] : 0;
+        pcq += __popcll(sq);
+        const uint32_t x = (uint32_t)(sq >> (32 * g));
 #pragma unroll
-        for (int w = 0; w < W; ++w) {
-            const uint64_t sq = qi < n_q ? a.q_sketch[(((size_t)seq_g * n_q + qi) * Hq + h) * W + w] : 0;
-            pcq[rb] += 4 * __popcll(sq);
-            const uint32_t bits = (uint32_t)(sq >> (16 * kb)) & 0xFFFFu;
+        for (int j = 0; j < 4; ++j) qop[w].u[j] = 0x66666666u | (((x >> j) & 0x11111111u) << 3);
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const uint32_t t = spread4(bits >> (4 * k));
-                qpm[rb][w].u[k] = (t << 2) | ((t ^ 0x01010101u) * 0xFCu);     // bit 1 -> 0x04 (+4), bit 0 -> 0xFC (-4)
-            }
-        }
+        for (int j = 4; j < 8; ++j) qop[w].u[j] = 0u;
     }
-    const int wave_row0 = row0 + wave * 16 * kRB;
     const int wave_min_pos = q0 + wave_row0;                                       // position of the wave's first row
-    const int wave_max_pos = wave_row0 < n_q ? q0 + min(wave_row0 + 16 * kRB, n_q) - 1 : -1;   // ... and of its last valid row
+    const int wave_max_pos = wave_row0 < n_q ? q0 + min(wave_row0 + 32, n_q) - 1 : -1;   // ... and of its last valid row
 
-    f32x4 acc[kRB][NCB], accsum[kRB];
-    int run_min[kRB];             // 4 x the row's reference distance
+    f32x16 acc[NCB];
 #pragma unroll
-    for (int rb = 0; rb < kRB; ++rb) {
-        run_min[rb] = 1 << 22;
-        accsum[rb] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int cb = 0; cb < NCB; ++cb)
 #pragma unroll
-        for (int cb = 0; cb < NCB; ++cb) acc[rb][cb] = f32x4{0.f, 0.f, 0.f, 0.f};
-    }
+        for (int v = 0; v < 16; ++v) acc[cb][v] = 0.0f;
+    float lsum = 0.0f;            // this lane's share (16 of every 32 tokens) of the row's weight sum
+    int ref = 1 << 20;            // the row's reference distance (in distance units)
     const int S = (int)fminf(kPSlackLog2 / a.exp2_scale, (float)(64 * W));
     for (int e = threadIdx.x; e < 64 * W + S + 2; e += kPfThreads)
-        ptab[e] = e <= 64 * W + S ? __builtin_amdgcn_exp2f(fmaf(-a.exp2_scale, (float)(e - S), kPScaleLog2)) : 0.0f;
-    const uint32_t mask_a = opaque_vgpr(0x000F000Fu), mask_b = opaque_vgpr(0x00F000F0u);
-    HalfOperand ones;
+        ptab[e] = e <= 64 * W + S ? (_Float16)__builtin_amdgcn_exp2f(fmaf(-a.exp2_scale, (float)(e - S), kPScaleLog2)) : (_Float16)0.0f;
+    const float kMagic = 8388608.0f;                                  // 2^23: integers up to 2^23 sit in the low mantissa bits
+    const float off_zero = kMagic + (float)(2 * (64 * W + S + 1));    // the table's zero entry
+    // accumulator input of the score MFMA: result = 2^23 + 2 (ham - ref + S) = 2^23 + byte offset of the pair's weight
+    f32x16 c0;
+    auto set_c0 = [&]() {
+        const float v0 = kMagic + (float)(2 * (pcq - ref + S));
 #pragma unroll
-    for (int k = 0; k < 4; ++k) ones.u[k] = 0x3C003C00u;          // fp16 1.0
+        for (int v = 0; v < 16; ++v) c0[v] = v0;
+    };
+    set_c0();
+    const uint32_t mask_a = opaque_vgpr(0x000F000Fu), mask_b = opaque_vgpr(0x00F000F0u);
+    const h16x2 ones2 = {(_Float16)1.0f, (_Float16)1.0f};
 
-    // Token t of a 32-token step sits at operand position 8 ((t % 16) / 4) + 4 (t / 16) + t % 4: the score MFMA of
-    // token block t / 16 leaves tokens 4 kb .. 4 kb + 3 in lane group kb, and the value MFMA wants that lane group's
-    // eight tokens side by side.
-    auto operand_pos = [](int t) { return (t & ~31) + 8 * ((t & 15) >> 2) + 4 * ((t >> 4) & 1) + (t & 3); };
+    // Token t of a tile sits at operand position p(t) = t with bits 2 and 3 exchanged: the score MFMA leaves tokens
+    // 8 a + 4 g + j (a = 0..3, j = 0..3) of a 32-token step in lane group g, and the value MFMA of tokens 16 m .. 16 m + 15
+    // wants lane group g's eight tokens (a = 2 m, 2 m + 1) side by side at K = 8 g .. 8 g + 7.
+    auto operand_pos = [](int t) { return (t & ~12) | ((t & 8) >> 1) | ((t & 4) << 1); };
 
     // ---- staging: global -> registers (issued early) -> LDS (after the current tile has been consumed) ----
-    constexpr int kItems0 = (TK / 2) * (D / kCS);                 // layouts 0, 2: (token pair, channel slice) items per tile
-    static_assert(kCS == 8 && kItems0 <= kPfThreads, "one staging item per thread");
-    // layout 1: a thread takes one of the tile's TK / 8 blocks and words (tid % LPB) + LPB k of its D words (word wi
-    // holds channel 16 cb + n with cb = (wi / 64) * 4 + wi % 4, n = (wi % 64) / 4: the inverse of code_word_index).
-    // A word holds eight tokens of ONE channel: its {scale, zero} sets are those of that channel's quantisation group.
-    constexpr int LPB = kPfThreads / (TK / 8);
-    constexpr int kWordsPerThread = D > LPB ? D / LPB : 1;
-    static_assert(kWordsPerThread <= 2, "StageRegs holds two words and their sets");
-    auto word_channel = [](int wi) { return 16 * ((wi >> 6) * 4 + (wi & 3)) + ((wi & 63) >> 2); };
+    // Consecutive lanes take consecutive channel slices of one token pair, so that a wave's loads cover whole records
+    // (a lane per token pair would touch a different cache line with every lane).  Their LDS writes then go to channel
+    // rows 8 or 16 apart at one token position -- the same banks, whatever the row padding -- so the 16-byte blocks of a
+    // channel row are stored exchanged: block k of row c sits at k ^ ((c >> KSH) & 7).
+    constexpr int KSH = (LAYOUT == 2 || (LAYOUT == 0 && (TK / 2) * (D / 8) < 2 * kPfThreads)) ? 3 : 4;
+    auto row_addr = [](int ch, int pos_halves) {       // byte offset of (channel row, operand position) in a value tile
+        return ch * VS + ((((pos_halves >> 3) ^ (ch >> KSH)) & 7) << 4) + ((pos_halves & 7) << 1);
+    };
+    static_assert(TK == 64, "a channel row is eight 16-byte blocks");
+    constexpr int CS0 = (TK / 2) * (D / 8) >= 2 * kPfThreads ? 16 : 8;    // layout 0: channels per staging item
+    constexpr int kItems0 = (TK / 2) * (D / CS0);                 // layout 0: (token pair, channel slice) items per tile
+    static_assert(kItems0 <= kPfThreads, "one staging item per thread");
+    constexpr int kItems2 = (TK / 2) * (D / kCS);                 // layout 2: (token pair, 8-channel slice) items per tile
+    static_assert(kItems2 <= 2 * kPfThreads, "at most two staging items per thread");
+    constexpr int NIT = (kItems2 + kPfThreads - 1) / kPfThreads;
+    // layout 1: a thread takes one block of 8 tokens, one 16-channel column block cb and four neighbouring channels
+    // 16 cb + 4 nq .. + 3 of it (one quantisation group): words (cb / 4) * 64 + (4 nq + k) * 4 + cb % 4 (code_word_index).
+    constexpr int kItems1 = (TK / 8) * (D / 16) * 4;
+    static_assert(kItems1 <= kPfThreads, "one staging item per thread");
     {
         const int n_pages = ((n_tiles - 1) * TK) / kPage + 1;
         for (int p = tid; p < min(n_pages, kPagesLds); p += kPfThreads) pages_s[p] = bt[p];
         __syncthreads();
     }
+    // Per tile everything that depends on the tile is uniform over the workgroup (scalar registers); what depends on
+    // the lane is a 32-bit offset: the loads then take a scalar base and a 32-bit lane offset, with no 64-bit vector
+    // arithmetic.  Groups and group counts are powers of two: shifts, not multiplies.
+    const int lg_ng = __builtin_ctz((unsigned)ng), lg_G = __builtin_ctz((unsigned)pv.group_size);
     auto tile_rec0 = [&](int kt) {
         const int t0 = kt * TK, p = t0 / kPage;
-        const int page = p < kPagesLds ? pages_s[p] : bt[p];
+        const int page = __builtin_amdgcn_readfirstlane(p < kPagesLds ? pages_s[p] : bt[p]);
         return ((size_t)page * H + kvh) * kPage + (t0 % kPage);                    // a tile never straddles a page
     };
-    auto load_tile = [&](StageRegs<NDW> &sr, int kt) {
+    using Stage = StageRegs<NSK, LAYOUT>;
+    auto load_tile = [&](Stage &sr, int kt) {
         const size_t rec0 = tile_rec0(kt);
-        const uint16_t *skw = reinterpret_cast<const uint16_t *>(pv.sketch + rec0 * W);
+        const unsigned char *sk_base = reinterpret_cast<const unsigned char *>(pv.sketch + rec0 * W);
 #pragma unroll
-        for (int u = 0; u < NDW; ++u)
-            if (tid + u * kPfThreads < DWT) sr.skd[u] = skw[tid + u * kPfThreads];
+        for (int u = 0; u < NSK; ++u)
+            if (tid + u * kPfThreads < NSKD) sr.skd[u] = *reinterpret_cast<const uint32_t *>(sk_base + (uint32_t)(tid + u * kPfThreads) * 4u);
         if constexpr (LAYOUT == 0) {
             if (tid < kItems0) {
-                const int tp = tid % (TK / 2), sl = tid / (TK / 2);         // token pair fastest: see the LDS writes below
-                const int g = (kCS * sl) / pv.group_size;
+                const unsigned char *c_base = pv.codes + rec0 * (DTOT / 2) + half * (D / 2);
+                const unsigned char *m_base = reinterpret_cast<const unsigned char *>(pv.meta + (rec0 << lg_ng));
+                const uint32_t tp = tid / (D / CS0), s16 = tid % (D / CS0);
+                const uint32_t gq = (uint32_t)(D * half + CS0 * s16) >> lg_G;
 #pragma unroll
                 for (int t = 0; t < 2; ++t) {
-                    const size_t rec = rec0 + 2 * tp + t;
-                    sr.c[t] = *reinterpret_cast<const uint32_t *>(pv.codes + rec * (D / 2) + sl * 4);
-                    sr.m[t] = pv.meta[rec * ng + g];
+                    const uint32_t rl = 2 * tp + t;                         // record within the tile
+                    if constexpr (CS0 == 16) {
+                        const uint2 cc = *reinterpret_cast<const uint2 *>(c_base + (rl * (uint32_t)(DTOT / 2) + s16 * 8u));
+                        sr.c[2 * t] = cc.x;
+                        sr.c[2 * t + 1] = cc.y;
+                    } else {
+                        sr.c[2 * t] = *reinterpret_cast<const uint32_t *>(c_base + (rl * (uint32_t)(DTOT / 2) + s16 * 4u));
+                    }
+                    sr.m[t] = *reinterpret_cast<const uint32_t *>(m_base + (((rl << lg_ng) + gq) << 2));
                 }
             }
         } else if constexpr (LAYOUT == 2) {              // fp16 values: 8 channels (16 bytes) of each of two tokens
-            if (tid < kItems0) {
-                const int tp = tid % (TK / 2), sl = tid / (TK / 2);
+            const unsigned char *v_base = pv.codes + (rec0 * DTOT + D * half) * 2;
+#pragma unroll
+            for (int it = 0; it < NIT; ++it) {
+                const int id = tid + it * kPfThreads;
+                if (id >= kItems2) break;
+                const uint32_t tp = id / (D / kCS), sl = id % (D / kCS);
 #pragma unroll
                 for (int t = 0; t < 2; ++t) {
-                    const uint4 a0 = *reinterpret_cast<const uint4 *>(pv.codes + ((rec0 + 2 * tp + t) * D + kCS * sl) * 2);
-                    sr.m[4 * t + 0] = a0.x; sr.m[4 * t + 1] = a0.y; sr.m[4 * t + 2] = a0.z; sr.m[4 * t + 3] = a0.w;
+                    const uint4 a0 = *reinterpret_cast<const uint4 *>(v_base + ((2 * tp + t) * (uint32_t)DTOT + kCS * sl) * 2u);
+                    uint32_t *m = sr.m + 8 * it + 4 * t;
+                    m[0] = a0.x; m[1] = a0.y; m[2] = a0.z; m[3] = a0.w;
                 }
             }
-        } else {
-            const int blk = tid / LPB, w0 = tid % LPB;
-            const uint32_t *words = reinterpret_cast<const uint32_t *>(pv.codes + (rec0 + 8 * blk) * (D / 2));
+        } else if (tid < kItems1) {
+            const uint32_t blk = tid / (D / 4), rest = tid % (D / 4);
+            const uint32_t cb = rest / 4, nq = rest % 4;
+            const unsigned char *w_base = pv.codes + rec0 * (DTOT / 2);
+            const unsigned char *m_base = reinterpret_cast<const unsigned char *>(pv.meta + (rec0 << lg_ng));
 #pragma unroll
-            for (int k = 0; k < kWordsPerThread; ++k) {
-                const int wi = w0 + LPB * k;
-                if (wi < D) {
-                    sr.c[k] = words[wi];
-                    const int g = word_channel(wi) / pv.group_size;
+            for (int k = 0; k < 4; ++k)
+                sr.c[k] = *reinterpret_cast<const uint32_t *>(w_base + (8 * blk * (uint32_t)(DTOT / 2) + ((cb >> 2) * 64 + (4 * nq + k) * 4 + (cb & 3)) * 4u));
+            const uint32_t gq = (16 * cb + 4 * nq) >> lg_G;
 #pragma unroll
-                    for (int j = 0; j < 8; ++j) sr.m[8 * k + j] = pv.meta[(rec0 + 8 * blk + j) * ng + g];
-                }
-            }
+            for (int j = 0; j < 8; ++j) sr.m[j] = *reinterpret_cast<const uint32_t *>(m_base + ((((8 * blk + j) << lg_ng) + gq) << 2));
         }
     };
-    auto store_tile = [&](const StageRegs<NDW> &sr, int kt, int buf) {
+    auto store_tile = [&](const Stage &sr, int kt, int buf) {
         const int t0 = kt * TK;
-        // key bits -> {0,1} bytes: 16 bits in, 16 bytes out
+        // key bits -> fp4 nibbles: 32 bits in, 16 bytes out
         unsigned char *ks = k_s[buf];
 #pragma unroll
-        for (int u = 0; u < NDW; ++u) {
+        for (int u = 0; u < NSK; ++u) {
             const int dwi = tid + u * kPfThreads;
-            if (dwi < DWT) {
-                const int tok = dwi / (4 * W), part = dwi % (4 * W);
-                uint32_t o[4];
-#pragma unroll
-                for (int k = 0; k < 4; ++k) o[k] = spread4(sr.skd[u] >> (4 * k));
-                *reinterpret_cast<uint4 *>(ks + tok * KS + part * 16) = make_uint4(o[0], o[1], o[2], o[3]);
+            if (dwi < NSKD) {
+                const int tok = dwi / (2 * W), part = dwi % (2 * W);
+                const uint32_t x = sr.skd[u];
+                *reinterpret_cast<uint4 *>(ks + tok * KS + part * 16) =
+                    make_uint4(x & 0x11111111u, (x >> 1) & 0x11111111u, (x >> 2) & 0x11111111u, (x >> 3) & 0x11111111u);
             }
         }
         unsigned char *vs = v_s[buf];
         if constexpr (LAYOUT == 0) {
             if (tid < kItems0) {
-                // lanes of a half-wave hold different token pairs of one channel slice: their 4-byte writes into a
-                // channel row fall into different LDS banks
-                const int tp = tid % (TK / 2), sl = tid / (TK / 2);
+                const int tp = tid / (D / CS0), s16 = tid % (D / CS0);
                 float sc[2], zp[2];
 #pragma unroll
                 for (int t = 0; t < 2; ++t) {
@@ -265,12 +288,13 @@ __global__ __launch_bounds__(kPfThreads, W >= 8 ? 2 : 4) void prefill_kernel(Pre
                     sc[t] = __half2float(__ushort_as_half((unsigned short)(m & 0xFFFFu)));
                     zp[t] = __half2float(__ushort_as_half((unsigned short)(m >> 16)));
                 }
-                const int p2 = operand_pos(2 * tp) * 2;            // tokens 2 tp and 2 tp + 1 stay neighbours
+                const int pp = operand_pos(2 * tp);                // tokens 2 tp and 2 tp + 1 stay neighbours
                 // A nibble masked in place at mantissa bits 0-3 / 4-7 of a zero half-word is the fp16 subnormal
                 // code 2^-24 / code 2^-20: the mixed-precision FMA reads it directly, with the scale times 2^24 / 2^20.
                 const float sa[2] = {sc[0] * 16777216.0f, sc[1] * 16777216.0f}, sb[2] = {sc[0] * 1048576.0f, sc[1] * 1048576.0f};
-                {
-                    const uint32_t x0 = sr.c[0], x1 = sr.c[1], y0 = x0 >> 8, y1 = x1 >> 8;
+#pragma unroll
+                for (int k = 0; k < CS0 / 8; ++k) {                // 8 channels per code dword
+                    const uint32_t x0 = sr.c[k], x1 = sr.c[2 + k], y0 = x0 >> 8, y1 = x1 >> 8;
                     const uint32_t t0w[4] = {x0 & mask_a, x0 & mask_b, y0 & mask_a, y0 & mask_b};
                     const uint32_t t1w[4] = {x1 & mask_a, x1 & mask_b, y1 & mask_a, y1 & mask_b};
 #pragma unroll
@@ -280,29 +304,44 @@ __global__ __launch_bounds__(kPfThreads, W >= 8 ? 2 : 4) void prefill_kernel(Pre
                         const f32x2 lo = {fmaf(w0, __low2float(h0), zp[0]), fmaf(w1, __low2float(h1), zp[1])};
                         const f32x2 hi = {fmaf(w0, __high2float(h0), zp[0]), fmaf(w1, __high2float(h1), zp[1])};
                         const h16x2 plo = __builtin_convertvector(lo, h16x2), phi = __builtin_convertvector(hi, h16x2);
-                        *reinterpret_cast<h16x2 *>(vs + (kCS * sl + n) * VS + p2) = plo;
-                        *reinterpret_cast<h16x2 *>(vs + (kCS * sl + n + 4) * VS + p2) = phi;
+                        // (all channels of the item share one exchange key: the address is a lane base plus a constant)
+                        static_assert((CS0 >> KSH) <= 1, "one key per staging item");
+                        const int wbase = row_addr(CS0 * s16, pp);
+                        *reinterpret_cast<h16x2 *>(vs + wbase + (8 * k + n) * VS) = plo;
+                        *reinterpret_cast<h16x2 *>(vs + wbase + (8 * k + n + 4) * VS) = phi;
                     }
                 }
             }
         } else if constexpr (LAYOUT == 2) {
-            if (tid < kItems0) {
-                const int tp = tid % (TK / 2), sl = tid / (TK / 2);
-                const int p2 = operand_pos(2 * tp) * 2;
+#pragma unroll
+            for (int it = 0; it < NIT; ++it) {
+                const int id = tid + it * kPfThreads;
+                if (id >= kItems2) break;
+                const int tp = id / (D / kCS), sl = id % (D / kCS);
+                const int pp = operand_pos(2 * tp);
                 // slots past the end of the sequence hold anything: their values must not reach the MFMA as NaN
                 const uint32_t keep0 = t0 + 2 * tp < len ? 0xFFFFu : 0u, keep1 = t0 + 2 * tp + 1 < len ? 0xFFFFu : 0u;
+                const uint32_t *m = sr.m + 8 * it;
 #pragma unroll
                 for (int c = 0; c < kCS; ++c) {
-                    const uint32_t h0 = (sr.m[c >> 1] >> (16 * (c & 1))) & keep0, h1 = (sr.m[4 + (c >> 1)] >> (16 * (c & 1))) & keep1;
-                    *reinterpret_cast<uint32_t *>(vs + (kCS * sl + c) * VS + p2) = h0 | (h1 << 16);
+                    const uint32_t h0 = (m[c >> 1] >> (16 * (c & 1))) & keep0, h1 = (m[4 + (c >> 1)] >> (16 * (c & 1))) & keep1;
+                    *reinterpret_cast<uint32_t *>(vs + row_addr(kCS * sl + c, pp)) = h0 | (h1 << 16);
                 }
             }
-        } else {
-            const int blk = tid / LPB, w0 = tid % LPB;
+        } else if (tid < kItems1) {
+            const int blk = tid / (D / 4), rest = tid % (D / 4);
+            const int cb = rest / 4, nq = rest % 4;
+            float sc[8], zp[8];
 #pragma unroll
-            for (int k = 0; k < kWordsPerThread; ++k) {
-                const int wi = w0 + LPB * k, ch = word_channel(wi);
-                if (wi >= D) continue;
+            for (int j = 0; j < 8; ++j) {
+                // slots past the end of the sequence hold anything: their values must not reach the MFMA as NaN
+                const uint32_t m = t0 + 8 * blk + j < len ? sr.m[j] : 0u;
+                sc[j] = __half2float(__ushort_as_half((unsigned short)(m & 0xFFFFu)));
+                zp[j] = __half2float(__ushort_as_half((unsigned short)(m >> 16)));
+            }
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int ch = 16 * cb + 4 * nq + k;
                 const uint32_t x = sr.c[k], y = x >> 8;
                 // nibble n of the word is token 2 n of the block, nibble n + 4 token 2 n + 1: word n below holds that
                 // pair as fp16 subnormals (code 2^-24 for even n, code 2^-20 for odd n)
@@ -310,23 +349,14 @@ __global__ __launch_bounds__(kPfThreads, W >= 8 ? 2 : 4) void prefill_kernel(Pre
                 h16x2 hv[4];
 #pragma unroll
                 for (int n = 0; n < 4; ++n) {
-                    float f[2];
-#pragma unroll
-                    for (int e = 0; e < 2; ++e) {
-                        const int j = 2 * n + e;
-                        // slots past the end of the sequence hold anything: their values must not reach the MFMA as NaN
-                        const uint32_t m = t0 + 8 * blk + j < len ? sr.m[8 * k + j] : 0u;
-                        const float sc = __half2float(__ushort_as_half((unsigned short)(m & 0xFFFFu)));
-                        const float zp = __half2float(__ushort_as_half((unsigned short)(m >> 16)));
-                        const __half2 h = *reinterpret_cast<const __half2 *>(&tw[n]);
-                        f[e] = fmaf(sc * ((n & 1) ? 1048576.0f : 16777216.0f), e ? __high2float(h) : __low2float(h), zp);
-                    }
-                    const f32x2 pf = {f[0], f[1]};
+                    const __half2 hh = *reinterpret_cast<const __half2 *>(&tw[n]);
+                    const float mul = (n & 1) ? 1048576.0f : 16777216.0f;
+                    const f32x2 pf = {fmaf(sc[2 * n] * mul, __low2float(hh), zp[2 * n]), fmaf(sc[2 * n + 1] * mul, __high2float(hh), zp[2 * n + 1])};
                     hv[n] = __builtin_convertvector(pf, h16x2);
                 }
                 // tokens 8 blk .. 8 blk + 3 and 8 blk + 4 .. 8 blk + 7 go to two operand positions
-                *reinterpret_cast<uint2 *>(vs + ch * VS + operand_pos(8 * blk) * 2) = *reinterpret_cast<const uint2 *>(&hv[0]);
-                *reinterpret_cast<uint2 *>(vs + ch * VS + operand_pos(8 * blk + 4) * 2) = *reinterpret_cast<const uint2 *>(&hv[2]);
+                *reinterpret_cast<uint2 *>(vs + row_addr(ch, operand_pos(8 * blk))) = *reinterpret_cast<const uint2 *>(&hv[0]);
+                *reinterpret_cast<uint2 *>(vs + row_addr(ch, operand_pos(8 * blk + 4))) = *reinterpret_cast<const uint2 *>(&hv[2]);
             }
         }
     };
@@ -336,130 +366,164 @@ __global__ __launch_bounds__(kPfThreads, W >= 8 ? 2 : 4) void prefill_kernel(Pre
         constexpr bool kMasked = decltype(masked_tag)::value;
         const unsigned char *ks = k_s[buf];
         const unsigned char *vs = v_s[buf];
-#pragma unroll 1
-        for (int st = 0; st < NSTEP; ++st) {
-            // Hamming distances: lane (row i, kb) receives tokens 16 tb + 4 kb + j of the step, tb = 0, 1
-            i32x4 dot[kRB][2];
+        const unsigned char *tab = reinterpret_cast<const unsigned char *>(ptab);
+        // byte offsets of the weights of step st: lane (row i, g) receives tokens 8 a + 4 g + j of the step as element 4 a + j
+        auto scores = [&](int st) {
+            f32x16 off;
 #pragma unroll
-            for (int tb = 0; tb < 2; ++tb) {
-#pragma unroll
-                for (int rb = 0; rb < kRB; ++rb) dot[rb][tb] = i32x4{0, 0, 0, 0};
-#pragma unroll
-                for (int w = 0; w < W; ++w) {
-                    const i32x4 K = *reinterpret_cast<const i32x4 *>(ks + (32 * st + 16 * tb + i) * KS + 64 * w + 16 * kb);
-#pragma unroll
-                    for (int rb = 0; rb < kRB; ++rb)
-                        dot[rb][tb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(K, qpm[rb][w].v, dot[rb][tb], 0, 0, 0);
-                }
+            for (int w = 0; w < W; ++w) {
+                // the two 32-bit halves of sketch word w are the instruction's two K blocks of 32: lane group g takes half g
+                NibbleOperand K;
+                const uint4 kk = *reinterpret_cast<const uint4 *>(ks + (32 * st + i) * KS + (2 * w + g) * 16);
+                K.u[0] = kk.x; K.u[1] = kk.y; K.u[2] = kk.z; K.u[3] = kk.w;
+                K.u[4] = K.u[5] = K.u[6] = K.u[7] = 0u;
+                off = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(K.v, qop[w].v, w == 0 ? c0 : off, 4, 4, 0, kUnitScale, 0, kUnitScale);
             }
-            const int tg = kt * TK + 32 * st + 4 * kb;            // absolute position of this lane's first token (tb = 0, j = 0)
-            int dq[kRB][8], tmin[kRB];
-            bool changed = false;
+            return off;
+        };
+        auto mask_step = [&](f32x16 &off, int st) {                // causal mask (also: rows past the chunk)
+            const int lim = pos - (kt * TK + 32 * st + 4 * g);     // element 4 a + j is visible iff 8 a + j <= lim
 #pragma unroll
-            for (int rb = 0; rb < kRB; ++rb) {
-                int dmax = -(1 << 22);
+            for (int v = 0; v < 16; ++v)
+                if (8 * (v >> 2) + (v & 3) > lim) off[v] = off_zero;
+        };
+        auto row_min = [&](const f32x16 &off) {                    // smallest offset of the row in this step
+            float mn = fminf(fminf(off[0], off[1]), off[2]);
 #pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    int d = dot[rb][j >> 2][j & 3];              // sum_k q_k key_k = 4 (popcount(q) - ham)
-                    if (kMasked && tg + 16 * (j >> 2) + (j & 3) > pos[rb]) d = -(1 << 22);    // causal mask (also: rows past the chunk)
-                    dq[rb][j] = d;
-                    dmax = max(dmax, d);
-                }
-                tmin[rb] = xor32_min(xor16_min(pcq[rb] - dmax));  // 4 x the smallest distance of the step, over the row's four lane groups
-                changed |= tmin[rb] < run_min[rb] - 4 * S;
+            for (int v = 3; v < 15; v += 2) mn = fminf(fminf(mn, off[v]), off[v + 1]);
+            return xor32_min(fminf(mn, off[15]));                  // over the row's two lane groups
+        };
+        // rare: some row's best distance left the slack.  The step's smallest distance becomes the row's reference:
+        // every offset of the row grows by 2 delta, what has been accumulated shrinks by exp(-2 delta / (b tau)).
+        auto renew = [&](f32x16 &off, float mn) {
+            const int delta = mn < kMagic ? S - (((int)(mn - kMagic)) >> 1) : 0;      // old reference - new one (> S)
+            const float f = __builtin_amdgcn_exp2f(-a.exp2_scale * (float)delta);     // 0 while nothing was accumulated
+            ref -= delta;
+            set_c0();
+            lsum *= f;
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+                if (!kMasked || off[v] != off_zero) off[v] += (float)(2 * delta);
+            // accumulator element 4 a + j of lane (n, g) belongs to row 8 a + 4 g + j, whose factor lane 8 a + 4 g + j holds
+            float fr[16];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) fr[v] = __shfl(f, 8 * (v >> 2) + 4 * g + (v & 3));
+#pragma unroll
+            for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[cb][v] *= fr[v];
+        };
+        // Weights from the table: the low 16 bits of 2^23 + offset are the offset.
+        auto table = [&](const f32x16 &off, _Float16 *pw) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) pw[v] = *reinterpret_cast<const _Float16 *>(tab + (__float_as_uint(off[v]) & 0xFFFFu));
+        };
+        auto pack = [&](const _Float16 *pw, HalfOperand *A) {
+#pragma unroll
+            for (int v = 0; v < 16; v += 2) {
+                const h16x2 pk = {pw[v], pw[v + 1]};
+                A[v >> 3].u[(v & 7) >> 1] = *reinterpret_cast<const uint32_t *>(&pk);
+                lsum = __builtin_amdgcn_fdot2(pk, ones2, lsum, false);
             }
-            if (__any(changed)) {                                 // rare: some row's best distance left the slack
-#pragma unroll
-                for (int rb = 0; rb < kRB; ++rb) {
-                    const int nm = tmin[rb] < run_min[rb] - 4 * S ? tmin[rb] : run_min[rb];
-                    const float f = exp2f(0.25f * a.exp2_scale * (float)(nm - run_min[rb]));   // 0 while nothing was accumulated
-                    run_min[rb] = nm;
-                    // accumulator element j of this lane belongs to row 4 kb + j, whose factor lane 4 kb + j holds
-                    float fr[4];
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) fr[j] = __shfl(f, 4 * kb + j);
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) accsum[rb][j] *= fr[j];
-#pragma unroll
-                    for (int cb = 0; cb < NCB; ++cb)
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) acc[rb][cb][j] *= fr[j];
-                }
-            }
-            // Weights from the table: p depends only on e = ham - reference, an integer in [-S, b]; masked pairs
-            // are clamped to the table's zero entry.  4 (e + S) = 4 (popcount(q) - reference + S) - score is the entry's
-            // byte offset.
-            HalfOperand A[kRB];
-#pragma unroll
-            for (int rb = 0; rb < kRB; ++rb) {
-#pragma unroll
-                for (int j = 0; j < 8; j += 2) {
-                    const int base = pcq[rb] - run_min[rb] + 4 * S;
-                    int e0 = base - dq[rb][j], e1 = base - dq[rb][j + 1];
-                    if (kMasked) {
-                        e0 = min(e0, 4 * (64 * W + 1) + 4 * S);
-                        e1 = min(e1, 4 * (64 * W + 1) + 4 * S);
-                    }
-                    const unsigned char *tab = reinterpret_cast<const unsigned char *>(ptab);
-                    const float p0 = *reinterpret_cast<const float *>(tab + e0), p1 = *reinterpret_cast<const float *>(tab + e1);
-                    // round to nearest (one packed convert on gfx950), not the truncating pack: half the weight error
-                    const f32x2 pf = {p0, p1};
-                    const h16x2 pk = __builtin_convertvector(pf, h16x2);
-                    A[rb].u[j / 2] = *reinterpret_cast<const uint32_t *>(&pk);
-                }
-            }
+        };
+        // Lane bases of the value operands: row i of a column block, 16-byte block (2 m' + g) ^ (the key bits that come
+        // from i); the key bits that come from the column block and the step's bit are added as constants at the reads.
+        const int lane_key = KSH == 4 ? (i >> 4) : ((i >> 3) & 3);
+        const int bbase[2] = {i * VS + (((0 | g) ^ lane_key) << 4), i * VS + (((2 | g) ^ lane_key) << 4)};
+        auto values = [&](const HalfOperand *A, int st) {
 #pragma unroll
             for (int cb = 0; cb < NCB; ++cb) {
-                const f16x8 B = *reinterpret_cast<const f16x8 *>(vs + (16 * cb + i) * VS + (32 * st + 8 * kb) * 2);
 #pragma unroll
-                for (int rb = 0; rb < kRB; ++rb) acc[rb][cb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A[rb].v, B, acc[rb][cb], 0, 0, 0);
-            }
-#pragma unroll
-            for (int rb = 0; rb < kRB; ++rb) accsum[rb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A[rb].v, ones.v, accsum[rb], 0, 0, 0);
-        }
-    };
-
-    StageRegs<NDW> sr;
-    if (tile_lo < tile_hi) {                                       // (a short sequence may leave a split without tiles)
-        load_tile(sr, tile_lo);
-        store_tile(sr, tile_lo, tile_lo & 1);
-    }
-    __syncthreads();
-    for (int kt = tile_lo; kt < tile_hi; ++kt) {
-        const int buf = kt & 1;
-        if (kt + 1 < tile_hi) load_tile(sr, kt + 1);
-        const int t_first = kt * TK, t_last = t_first + TK - 1;
-        if (t_first <= wave_max_pos) {                             // else: the whole tile lies in this wave's future
-            if (t_last <= wave_min_pos && wave_row0 + 16 * kRB <= n_q) consume_tile(kt, buf, std::false_type{});
-            else consume_tile(kt, buf, std::true_type{});
-        }
-        if (kt + 1 < tile_hi) store_tile(sr, kt + 1, buf ^ 1);
-        __syncthreads();
-    }
-
-    // ---- epilogue: accumulator element j of lane (n = i, kb) is row 4 kb + j, channel 16 cb + n ----
-#pragma unroll
-    for (int rb = 0; rb < kRB; ++rb)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int qi = wave_row0 + rb * 16 + 4 * kb + j;
-            const int ref = __shfl(run_min[rb], 4 * kb + j);      // the row's reference distance sits in lane 4 kb + j
-            if (qi >= n_q) continue;
-            if (n_splits == 1) {
-                const float inv = 1.0f / accsum[rb][j];
-                float *dst = a.out + (((size_t)seq_g * n_q + qi) * Hq + h) * D + i;
-#pragma unroll
-                for (int cb = 0; cb < NCB; ++cb) dst[16 * cb] = acc[rb][cb][j] * inv;
-            } else {
-                float *dst = a.part + ((((size_t)seq_g * n_q + qi) * Hq + h) * n_splits + split) * (D + 2);
-#pragma unroll
-                for (int cb = 0; cb < NCB; ++cb) dst[16 * cb + i] = acc[rb][cb][j];
-                if (i == 0) {
-                    dst[D] = accsum[rb][j];
-                    dst[D + 1] = __int_as_float(ref);
+                for (int m = 0; m < 2; ++m) {
+                    // row 32 cb + i, block 4 st + 2 m + g exchanged with the row's key: what depends on (cb, st, m) is a
+                    // compile-time offset and a choice between two lane bases (see bbase)
+                    constexpr bool k4 = KSH == 4;
+                    const int mm = k4 ? (m ^ (cb & 1)) : m;
+                    const int bit2 = k4 ? (st ^ (cb >> 1)) : (st ^ (cb & 1));
+                    const f16x8 B = *reinterpret_cast<const f16x8 *>(vs + bbase[mm] + (32 * cb * VS + (bit2 << 6)));
+                    acc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(A[m].v, B, acc[cb], 0, 0, 0);
                 }
             }
+        };
+        static_assert(NSTEP == 2, "the two steps of a tile are written out");
+
+        // A wave executes in order, and a step is one long chain (scores -> minimum -> table -> value MFMAs): the second
+        // step's chain up to its table reads is therefore issued among the first step's value MFMAs -- assuming that no
+        // reference needs renewing; if one does, the weights are read again.
+        f32x16 off0 = scores(0);
+        if (kMasked) mask_step(off0, 0);
+        {
+            const float mn = row_min(off0);
+            if (__any(mn < kMagic)) renew(off0, mn);
         }
+        _Float16 pw0[16], pw1[16];
+        table(off0, pw0);
+        f32x16 off1 = scores(1);
+        HalfOperand A0[2], A1[2];
+        pack(pw0, A0);
+        if (kMasked) mask_step(off1, 1);
+        const float mn1 = row_min(off1);
+        table(off1, pw1);
+        values(A0, 0);
+        if (__any(mn1 < kMagic)) {
+            renew(off1, mn1);
+            table(off1, pw1);
+        }
+        pack(pw1, A1);
+        values(A1, 1);
+    };
+
+    // Two register sets: the loads of tile kt + 2 are issued before tile kt is consumed, so a load has two tiles of work
+    // to arrive in (one tile's work is shorter than a trip to memory).
+    Stage s0;
+    Stage s1;
+    if (tile_lo < tile_hi) {                                       // (a short sequence may leave a split without tiles)
+        load_tile(s0, tile_lo);
+        store_tile(s0, tile_lo, tile_lo & 1);
+    }
+    if (tile_lo + 1 < tile_hi) load_tile(s1, tile_lo + 1);
+    __syncthreads();
+    // `next` holds tile kt + 1 (requested one tile ago), `after` is free for tile kt + 2
+    auto tile_step = [&](int kt, Stage &next, Stage &after) {
+        const int buf = kt & 1;
+        if (kt + 2 < tile_hi) load_tile(after, kt + 2);
+        const int t_first = kt * TK, t_last = t_first + TK - 1;
+        if (t_first <= wave_max_pos) {                             // else: the whole tile lies in this wave's future
+            if (t_last <= wave_min_pos && wave_row0 + 32 <= n_q) consume_tile(kt, buf, std::false_type{});
+            else consume_tile(kt, buf, std::true_type{});
+        }
+        if (kt + 1 < tile_hi) store_tile(next, kt + 1, buf ^ 1);
+        __syncthreads();
+    };
+    for (int kt = tile_lo; kt < tile_hi; kt += 2) {
+        tile_step(kt, s1, s0);
+        if (kt + 1 < tile_hi) tile_step(kt + 1, s0, s1);
+    }
+
+    // ---- epilogue: accumulator element 4 a + j of lane (n = i, g) is row 8 a + 4 g + j, channel 32 cb + n ----
+    const float l_row = half_wave_sum(lsum);                  // the row's two lane groups hold 16 of every 32 tokens each
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        const int rw = 8 * (v >> 2) + 4 * g + (v & 3);
+        const int q_row = wave_row0 + rw;
+        const float l = __shfl(l_row, rw);                    // the row's sums and reference sit in lane rw
+        const int rref = __shfl(ref, rw);
+        if (q_row >= n_q) continue;
+        if (n_splits == 1) {
+            const float inv = 1.0f / l;
+            float *dst = a.out + (((size_t)seq_g * n_q + q_row) * Hq + h) * DTOT + D * half + i;
+#pragma unroll
+            for (int cb = 0; cb < NCB; ++cb) dst[32 * cb] = acc[cb][v] * inv;
+        } else {
+            float *dst = a.part + ((((size_t)seq_g * n_q + q_row) * Hq + h) * n_splits + split) * (DTOT + 2);
+#pragma unroll
+            for (int cb = 0; cb < NCB; ++cb) dst[D * half + 32 * cb + i] = acc[cb][v];
+            if (i == 0 && half == 0) {
+                dst[DTOT] = l;
+                dst[DTOT + 1] = __int_as_float(4 * rref);     // the merge kernel counts references in quarter units
+            }
+        }
+    }
 }
 
 // out = sum_s f_s o_s / sum_s f_s l_s over the context splits of one (query position, head), f_s = exp(-2 (ref_s -
@@ -647,6 +711,69 @@ __global__ __launch_bounds__(kThreads) void sketch_rows_kernel(PrefillArgs a, in
     }
 }
 
+// Eq.(2) for query vectors of 256 channels: a projection row does not fit the register file next to anything else, so
+// a lane holds half a row at a time and carries the chain values of 16 vectors from the first half to the second
+// (the chain still runs over j = 0 .. 255 in order for every vector).
+template <typename T>
+__global__ __launch_bounds__(kThreads) void sketch_rows_wide_kernel(PrefillArgs a, int n_seqs) {
+    constexpr int D = 256, VT = 16, HALF = 128;
+    __shared__ __attribute__((aligned(16))) float qs[VT][D];
+    __shared__ size_t src_off[VT];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const PoolView &pv = a.pool;
+    const int W = pv.sketch_bits >> 6, Hq = pv.n_q_heads;
+    const long n_vec = (long)n_seqs * a.n_q * Hq;
+    const T *qbase = static_cast<const T *>(a.q);
+    for (long v0 = (long)blockIdx.x * VT; v0 < n_vec; v0 += (long)gridDim.x * VT) {
+        __syncthreads();
+        const int n_here = (int)min((long)VT, n_vec - v0);
+        if (tid < n_here) {
+            const long v = v0 + tid;
+            const long s = v / ((long)a.n_q * Hq), rem = v % ((long)a.n_q * Hq);
+            src_off[tid] = (size_t)s * a.stride_seq + (size_t)(rem / Hq) * a.stride_tok + (size_t)(rem % Hq) * a.stride_head;
+        }
+        __syncthreads();
+        for (int e = tid; e < n_here * D; e += kThreads) qs[e / D][e % D] = (float)qbase[src_off[e / D] + e % D];
+        __syncthreads();
+        for (int word = wave; word < W; word += kWaves) {
+            float y[VT];
+#pragma unroll
+            for (int t = 0; t < VT; ++t) y[t] = 0.0f;
+#pragma unroll 1
+            for (int h0 = 0; h0 < D; h0 += HALF) {
+                float r[HALF];
+                const float *row = pv.R + (size_t)(word * 64 + lane) * D + h0;
+#pragma unroll
+                for (int j = 0; j < HALF; j += 4) {
+                    const float4 x = *reinterpret_cast<const float4 *>(row + j);
+                    r[j] = x.x; r[j + 1] = x.y; r[j + 2] = x.z; r[j + 3] = x.w;
+                }
+#pragma unroll 1
+                for (int t = 0; t < n_here; ++t) {
+                    float acc = y[0];                              // y[t], selected without dynamic register indexing
+#pragma unroll
+                    for (int u = 1; u < VT; ++u) acc = t == u ? y[u] : acc;
+#pragma unroll
+                    for (int j = 0; j < HALF; j += 4) {
+                        const float4 q4 = *reinterpret_cast<const float4 *>(&qs[t][h0 + j]);
+                        acc = __builtin_fmaf(r[j], q4.x, acc);
+                        acc = __builtin_fmaf(r[j + 1], q4.y, acc);
+                        acc = __builtin_fmaf(r[j + 2], q4.z, acc);
+                        acc = __builtin_fmaf(r[j + 3], q4.w, acc);
+                    }
+#pragma unroll
+                    for (int u = 0; u < VT; ++u) y[u] = t == u ? acc : y[u];
+                }
+            }
+#pragma unroll
+            for (int t = 0; t < VT; ++t) {
+                const uint64_t mask = __ballot(y[t] >= 0.0f);
+                if (lane == 0 && t < n_here) a.q_sketch[(size_t)(v0 + t) * W + word] = mask;
+            }
+        }
+    }
+}
+
 template <int W, int D>
 hipError_t launch_prefill_layout(const PrefillArgs &a, const BatchDesc &desc, int seq0, dim3 grid, hipStream_t st) {
     if (a.pool.code_layout == 0) hipLaunchKernelGGL((prefill_kernel<W, D, 0>), grid, dim3(kPfThreads), 0, st, a, desc, seq0);
@@ -660,7 +787,12 @@ hipError_t launch_prefill_d(const PrefillArgs &a, const BatchDesc &desc, int seq
     switch (a.pool.head_dim) {
         case 64: return launch_prefill_layout<W, 64>(a, desc, seq0, grid, st);
         case 128: return launch_prefill_layout<W, 128>(a, desc, seq0, grid, st);
-        default: return hipErrorInvalidValue;      // see prefill_supported
+        default:                                   // 256 channels: record-major codes or fp16 values (see mfma_decode_supported)
+            if (a.pool.code_layout == 1) return hipErrorInvalidValue;
+            grid.x *= 2;                           // two workgroups of 128 channels per head
+            if (a.pool.code_layout == 0) hipLaunchKernelGGL((prefill_kernel<W, 256, 0>), grid, dim3(kPfThreads), 0, st, a, desc, seq0);
+            else hipLaunchKernelGGL((prefill_kernel<W, 256, 2>), grid, dim3(kPfThreads), 0, st, a, desc, seq0);
+            return hipGetLastError();
     }
 }
 
@@ -689,7 +821,14 @@ hipError_t launch_sketch_rows(const PrefillArgs &a, int n_seqs, hipStream_t st) 
     const dim3 grid((unsigned)(tiles < 1024 ? tiles : 1024));
     const int D = a.pool.head_dim;
 #define H1BKV_LAUNCH(DD, TT) hipLaunchKernelGGL((sketch_rows_kernel<DD, TT>), grid, dim3(kThreads), 0, st, a, n_seqs)
-    if (D != 64 && D != 128) return hipErrorInvalidValue;      // see prefill_supported
+    if (D == 256) {                                            // (the chain; large prompts at this size are not the hot path)
+        const long t16 = (n_vec + 15) / 16;
+        const dim3 g16((unsigned)(t16 < 4096 ? t16 : 4096));
+        if (a.f16) hipLaunchKernelGGL((sketch_rows_wide_kernel<__half>), g16, dim3(kThreads), 0, st, a, n_seqs);
+        else hipLaunchKernelGGL((sketch_rows_wide_kernel<float>), g16, dim3(kThreads), 0, st, a, n_seqs);
+        return hipGetLastError();
+    }
+    if (D != 64 && D != 128) return hipErrorInvalidValue;
     if (a.proj_mfma) {
         const dim3 fine((unsigned)(tiles < 6144 ? tiles : 6144));      // nothing stays resident: short workgroups
         // resident pieces of R: three long-lived workgroups per compute unit (768), shared by the parts of a wide sketch

@@ -37,7 +37,10 @@ CASES = [(128, 128, 32, 1, "f16", 300, 300),      # a whole prompt, record-major
          (64, 128, 64, 8, "f32", 260, 77),
          (128, 512, 128, 1, "f16", 190, 190),
          (128, 128, 32, 3, "f16", 333, 1),        # one query: the decode step
-         (64, 256, 32, 1, "f16", 1000, 129)]
+         (64, 256, 32, 1, "f16", 1000, 129),
+         (256, 128, 64, 1, "f16", 333, 333),      # 256 channels: two workgroups of 128 channels per head
+         (256, 256, 128, 4, "f32", 450, 140),     # ... with several query heads per KV head (record-major codes at this size)
+         (256, 64, 32, 2, "f16", 2000, 64)]       # ... short chunk over a long context: split over the context, merged
 
 
 @pytest.mark.parametrize("d,b,g,r,dt,T,n_q", CASES)
@@ -112,9 +115,9 @@ def test_query_sketches_are_bit_exact(dt, scale):
     cache.close()
 
 
-def test_prefill_over_fp16_values():
+@pytest.mark.parametrize("d,b,r,T,n_q", [(128, 128, 2, 333, 200), (256, 128, 1, 300, 300), (64, 64, 4, 140, 90)])
+def test_prefill_over_fp16_values(d, b, r, T, n_q):
     """The "1-bit key only" variant (value_bits = 16): same kernel, the value tile is copied instead of dequantised."""
-    d, b, r, T, n_q = 128, 128, 2, 333, 200
     w = wl.Workload("prefill_f16v", 2, 2 * r, 2, d, T, b, 32, "f16", seed=7)
     R = wl.projection(b, d)
     seqs = [0, 1]
