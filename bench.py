@@ -300,8 +300,11 @@ def bench_prefill(args, torch, B, wl, w, workers):
 
 def bench_per_token(args, torch, B, wl, w, workers):
     """Secondary line: what one generated token costs in attention over L layers.  Every layer owns a cache with the
-    workload's context and runs one fused decode step (append the token's K/V, attend); the L steps are captured in one
-    HIP graph and replayed.  (All layers reuse the workload's synthetic tensors: the values do not matter here.)"""
+    workload's context and runs one fused decode step (append the token's K/V, attend), launched eagerly: that is the
+    per-token figure.  Token positions and page assignments travel in the kernel arguments, so a HIP graph captured around
+    the L steps is frozen at the position it was captured at; replaying it (reported next to the figure) re-does the same
+    token and only shows what the launches cost.  (All layers reuse the workload's synthetic tensors: the values do
+    not matter here.)"""
     L, T, Bsz = args.per_token_layers, w.context, w.batch
     tau = w.default_tau()
     R = wl.projection(w.sketch_bits, w.head_dim)
@@ -347,13 +350,13 @@ def bench_per_token(args, torch, B, wl, w, workers):
     torch.cuda.synchronize()
     graph_ms = (time.perf_counter() - t0) * 1e3 / args.steps
     print(json.dumps({
-        "metric": "per_token_attention_latency_ms", "value": graph_ms, "unit": "ms/token", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": graph_ms, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "metric": "per_token_attention_latency_ms", "value": eager_ms, "unit": "ms/token", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": eager_ms, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name, "layers": L, "batch": Bsz, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
                    "head_dim": w.head_dim, "context": T, "sketch_bits": w.sketch_bits, "group_size": w.group_size,
-                   "launch": f"one HIP graph of {L} fused decode steps (3 kernels each)"},
-        "eager_ms_per_token": eager_ms,
+                   "launch": f"{L} fused decode steps (3 kernels each), launched eagerly"},
+        "graph_replay_of_one_position_ms": graph_ms,
         "context_only": "the paper's Table III reports 40 ms (Raspberry Pi 5) and 21 ms (Jetson Nano) per token for the WHOLE "
                         "7B model at an 8k context; this line is the attention over the compressed cache alone"}))
 

@@ -67,6 +67,29 @@ def build(force: bool = False, verbose: bool = False) -> str:
     return LIB
 
 
+def build_host_sanitized(out_path: str) -> str:
+    """The library with its host side (cache.cpp: validation, page bookkeeping, launch sequencing) instrumented by
+    AddressSanitizer and UndefinedBehaviorSanitizer; the kernels' objects are the ordinary ones.  For the CPU test tier:
+    the process that loads it must have the clang sanitizer run-time (sanitizer_runtime()) preloaded."""
+    build()
+    o = os.path.join(OBJDIR, "cache.cpp.san.o")
+    san = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-Xarch_host", "-fno-sanitize-recover=all"]
+    subprocess.run(["hipcc"] + [f for f in COMMON if f != "-O3"] + ["-O1", "-g", "-x", "hip"] + san +
+                   ["-c", os.path.join(CSRC, "cache.cpp"), "-o", o], check=True)
+    objs = [os.path.join(OBJDIR, src + ".o") for src in SOURCES if src != "cache.cpp"] + [o]
+    subprocess.run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-shared-libsan", "-fsanitize=address,undefined",
+                    "-fno-gpu-sanitize", "-o", out_path] + objs, check=True)
+    return out_path
+
+
+def sanitizer_runtime() -> str:
+    """Path of the AddressSanitizer run-time of the compiler hipcc drives."""
+    clang = os.path.join(os.path.dirname(os.path.realpath(subprocess.run(["which", "hipcc"], capture_output=True, text=True).stdout.strip())),
+                         "..", "lib", "llvm", "bin", "clang")
+    out = subprocess.run([clang, "-print-file-name=libclang_rt.asan-x86_64.so"], capture_output=True, text=True).stdout.strip()
+    return out if os.path.isabs(out) and os.path.exists(out) else ""
+
+
 if __name__ == "__main__":
     import sys
     print(build(force="--force" in sys.argv, verbose=True))

@@ -182,15 +182,17 @@ struct h1bkv_cache {
 
     PoolView view() const {
         PoolView v{};
-        v.R = reinterpret_cast<const float *>(pool + lay.off_R);
-        v.RT = reinterpret_cast<const float *>(pool + lay.off_RT);
-        v.R16hi = reinterpret_cast<const uint16_t *>(pool + lay.off_R16hi);
-        v.R16mid = reinterpret_cast<const uint16_t *>(pool + lay.off_R16mid);
-        v.guard = reinterpret_cast<const float *>(pool + lay.off_guard);
-        v.block_table = reinterpret_cast<int32_t *>(pool + lay.off_bt);
-        v.sketch = reinterpret_cast<uint64_t *>(pool + lay.off_sketch);
-        v.codes = reinterpret_cast<uint8_t *>(pool + lay.off_codes);
-        v.meta = reinterpret_cast<uint32_t *>(pool + lay.off_meta);
+        if (pool) {              // (a bookkeeping-only handle has no pool: its view carries the geometry only)
+            v.R = reinterpret_cast<const float *>(pool + lay.off_R);
+            v.RT = reinterpret_cast<const float *>(pool + lay.off_RT);
+            v.R16hi = reinterpret_cast<const uint16_t *>(pool + lay.off_R16hi);
+            v.R16mid = reinterpret_cast<const uint16_t *>(pool + lay.off_R16mid);
+            v.guard = reinterpret_cast<const float *>(pool + lay.off_guard);
+            v.block_table = reinterpret_cast<int32_t *>(pool + lay.off_bt);
+            v.sketch = reinterpret_cast<uint64_t *>(pool + lay.off_sketch);
+            v.codes = reinterpret_cast<uint8_t *>(pool + lay.off_codes);
+            v.meta = reinterpret_cast<uint32_t *>(pool + lay.off_meta);
+        }
         v.max_pages_per_seq = cfg.max_pages_per_seq;
         v.n_kv_heads = cfg.n_kv_heads;
         v.n_q_heads = cfg.n_q_heads;
