@@ -427,7 +427,7 @@ def main():
 
     cache = new_cache()
     r = w.n_q_heads // w.n_kv_heads
-    mfma = not f16v and r >= 3 and w.head_dim <= 128 and w.head_dim // w.group_size <= 4 and w.sketch_bits <= 256
+    mfma = not f16v and r >= 3
     split_kernel = "decode_split_f16v_kernel" if f16v else ("decode_split_mfma_kernel" if mfma else "decode_split_kernel")
     t_fill = time.perf_counter()
     fill_cache(torch, B, wl, w, cache, T - 1, workers)

@@ -117,16 +117,17 @@ inline int prefill_max_splits(int n_q_heads, int n_seqs, int n_q) {
     return (int)(s < 1 ? 1 : s > kPrefillMaxSplits ? kPrefillMaxSplits : s);
 }
 
-// Query heads one matrix-core decode workgroup serves: the largest divisor of r that is at most 8.
-inline int mfma_heads_per_wg(int r) {
-    for (int q = 8; q > 1; --q)
+// Query heads one matrix-core decode workgroup serves: the largest divisor of r that is at most 8 (4 at 256 channels).
+inline int mfma_heads_per_wg(int r, int head_dim) {
+    for (int q = head_dim > 128 ? 4 : 8; q > 1; --q)
         if (r % q == 0) return q;
     return 1;
 }
-// The matrix-core decode path (and with it code layout 1) is used from 3 query heads per KV head on, for the
-// geometries its kernel keeps in registers: head_dim 64 or 128, sketches of up to 256 bits, up to 4 groups.
+// The matrix-core decode path (and with it code layout 1) is used from 3 query heads per KV head on, for every
+// geometry (256 channels: four query heads per workgroup at most, two waves per SIMD).
 inline bool mfma_decode_supported(int r, int head_dim, int group_size, int sketch_bits) {
-    return r >= 3 && head_dim <= 128 && head_dim / group_size <= 4 && sketch_bits <= 256;
+    (void)head_dim; (void)group_size; (void)sketch_bits;
+    return r >= 3;
 }
 // Largest context chunk of one decode workgroup.
 inline int max_decode_chunk(int, int) { return kMaxChunk; }

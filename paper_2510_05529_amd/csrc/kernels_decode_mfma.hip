@@ -46,11 +46,9 @@ union BOperand {
     bf16x8 v;
 };
 
-constexpr int kMaxW = 4;     // sketch words per token this kernel keeps in registers (b <= 256)
-
-template <int NCB4, int NG>
+template <int NCB4, int NG, int W>
 struct PageRegs {            // what one lane holds of its wave's 64 tokens of one page
-    uint64_t sk[2][kMaxW];   // sketches of tokens tk and 32 + tk
+    uint64_t sk[2][W];       // sketches of tokens tk and 32 + tk
     uint4 c[2][NCB4];        // code words of (channel lane n, token block kb) for the two 32-token steps
     uint32_t m[2][NG];       // {scale, zero} of tokens tk and 32 + tk
 };
@@ -78,7 +76,7 @@ __device__ __forceinline__ float half32_sum(float x) {            // over the 32
 // registers sat behind branches, the registers they merge into were copied right after the loads, and that copy waited
 // for every load in flight -- once per page.
 template <int RQH, int D, int NG, int W, bool DTAU>
-__global__ __launch_bounds__(kThreads, RQH == 2 ? 3 : 2) void decode_split_mfma_kernel(DecodeArgs a, BatchDesc desc, int seq0, int RQ) {
+__global__ __launch_bounds__(kThreads, (RQH == 2 && D <= 128) ? 3 : 2) void decode_split_mfma_kernel(DecodeArgs a, BatchDesc desc, int seq0, int RQ) {
     static_assert(!DTAU || RQH == 2, "the distance-weighted rows take the second half of the 16 operand rows");
     constexpr int RQMAX = 2 * RQH;
     constexpr int NROWS = (DTAU ? 4 : 2) * RQMAX; // operand rows in use
@@ -88,6 +86,7 @@ __global__ __launch_bounds__(kThreads, RQH == 2 ? 3 : 2) void decode_split_mfma_
     constexpr int CBG = NCB / NG;                 // column blocks per quantisation group
     __shared__ float epi[kWaves][NROWS][D];       // epilogue staging of the accumulators
     __shared__ __attribute__((aligned(16))) unsigned short a_s[kWaves][NG][16][32];   // A operands, bf16 bits
+    constexpr int kMaxW = W;                      // sketch words per token, all kept in registers
     __shared__ uint64_t sq_s[RQMAX][kMaxW];
     __shared__ int pages_s[kMaxPagesPerChunk];
     __shared__ float f_s[kWaves][RQMAX];          // rescale factors on their way from the scoring lanes to the MFMA rows
@@ -150,7 +149,7 @@ __global__ __launch_bounds__(kThreads, RQH == 2 ? 3 : 2) void decode_split_mfma_
     // step's MFMAs.  (A second set handed over by copies cost a quarter of the loop's vector instructions and a third
     // of the registers.)
     auto page_base = [&](int pg) { return ((size_t)pages_s[pg] * H + kvh) * kPage + wave * 64; };
-    auto load_sketches = [&](PageRegs<NCB4, NG> &pr, int pg) {
+    auto load_sketches = [&](PageRegs<NCB4, NG, W> &pr, int pg) {
         const size_t base = page_base(pg);
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
@@ -169,7 +168,7 @@ __global__ __launch_bounds__(kThreads, RQH == 2 ? 3 : 2) void decode_split_mfma_
             }
         }
     };
-    auto load_step = [&](PageRegs<NCB4, NG> &pr, int pg, int t) {
+    auto load_step = [&](PageRegs<NCB4, NG, W> &pr, int pg, int t) {
         const size_t base = page_base(pg);
         const uint4 *cp = reinterpret_cast<const uint4 *>(pv.codes + (base + 32 * t + 8 * kb) * (D / 2)) + n;
 #pragma unroll
@@ -182,7 +181,7 @@ __global__ __launch_bounds__(kThreads, RQH == 2 ? 3 : 2) void decode_split_mfma_
     // more_tag: whether a page follows (std::true_type / std::false_type).  A compile-time choice, so that the refills are
     // straight-line code: the compiler then counts the loads in flight exactly and waits for the oldest only; behind a
     // run-time branch it waits for all of them.
-    auto consume_page = [&](PageRegs<NCB4, NG> &pr, int pg, auto more_tag) {
+    auto consume_page = [&](PageRegs<NCB4, NG, W> &pr, int pg, auto more_tag) {
         constexpr bool more = decltype(more_tag)::value;
         // ---- scores of this lane's two tokens against its query heads (Eq. 3) ----
         int ham[2][RQH], pmin[RQH];
@@ -321,7 +320,7 @@ __global__ __launch_bounds__(kThreads, RQH == 2 ? 3 : 2) void decode_split_mfma_
     };
 
     {
-        PageRegs<NCB4, NG> pr;
+        PageRegs<NCB4, NG, W> pr;
         load_sketches(pr, 0);
         load_step(pr, 0, 0);
         load_step(pr, 0, 1);
@@ -406,7 +405,8 @@ hipError_t launch_w(const DecodeArgs &a, const BatchDesc &desc, int seq0, dim3 g
         case 64: hipLaunchKernelGGL((decode_split_mfma_kernel<RQH, D, NG, 1, DTAU>), grid, dim3(kThreads), 0, st, a, desc, seq0, rq); break;
         case 128: hipLaunchKernelGGL((decode_split_mfma_kernel<RQH, D, NG, 2, DTAU>), grid, dim3(kThreads), 0, st, a, desc, seq0, rq); break;
         case 256: hipLaunchKernelGGL((decode_split_mfma_kernel<RQH, D, NG, 4, DTAU>), grid, dim3(kThreads), 0, st, a, desc, seq0, rq); break;
-        default: return hipErrorInvalidValue;      // see mfma_decode_supported
+        case 512: hipLaunchKernelGGL((decode_split_mfma_kernel<RQH, D, NG, 8, DTAU>), grid, dim3(kThreads), 0, st, a, desc, seq0, rq); break;
+        default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
 }
@@ -417,6 +417,9 @@ hipError_t launch_ng(const DecodeArgs &a, const BatchDesc &desc, int seq0, dim3 
     if (ng == 1) return launch_w<RQH, D, 1, DTAU>(a, desc, seq0, grid, rq, st);
     if (ng == 2) return launch_w<RQH, D, 2, DTAU>(a, desc, seq0, grid, rq, st);
     if (ng == 4) return launch_w<RQH, D, 4, DTAU>(a, desc, seq0, grid, rq, st);
+    if constexpr (D == 256) {
+        if (ng == 8) return launch_w<RQH, D, 8, DTAU>(a, desc, seq0, grid, rq, st);
+    }
     return hipErrorInvalidValue;
 }
 
@@ -425,7 +428,10 @@ hipError_t launch_d(const DecodeArgs &a, const BatchDesc &desc, int seq0, dim3 g
     switch (a.pool.head_dim) {
         case 64: return launch_ng<RQH, 64, DTAU>(a, desc, seq0, grid, rq, st);
         case 128: return launch_ng<RQH, 128, DTAU>(a, desc, seq0, grid, rq, st);
-        default: return hipErrorInvalidValue;      // see mfma_decode_supported
+        case 256:                                  // four query heads per workgroup at most: the epilogue's LDS staging
+            if constexpr (RQH == 2) return launch_ng<RQH, 256, DTAU>(a, desc, seq0, grid, rq, st);
+            return hipErrorInvalidValue;
+        default: return hipErrorInvalidValue;
     }
 }
 
@@ -433,7 +439,7 @@ hipError_t launch_d(const DecodeArgs &a, const BatchDesc &desc, int seq0, dim3 g
 
 hipError_t launch_decode_split_mfma(const DecodeArgs &a, const BatchDesc &desc, int seq0, int n_seqs, hipStream_t st) {
     const int r = a.pool.n_q_heads / a.pool.n_kv_heads;
-    const int rq = mfma_heads_per_wg(r);
+    const int rq = mfma_heads_per_wg(r, a.pool.head_dim);
     const dim3 grid((unsigned)a.n_splits, (unsigned)(a.pool.n_kv_heads * (r / rq)), (unsigned)n_seqs);
     return rq <= 4 ? launch_d<2, false>(a, desc, seq0, grid, rq, st) : launch_d<4, false>(a, desc, seq0, grid, rq, st);
 }

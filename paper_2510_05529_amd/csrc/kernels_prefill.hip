@@ -254,10 +254,11 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_kernel(PrefillArgs a, B
             const uint32_t cb = rest / 4, nq = rest % 4;
             const unsigned char *w_base = pv.codes + rec0 * (DTOT / 2);
             const unsigned char *m_base = reinterpret_cast<const unsigned char *>(pv.meta + (rec0 << lg_ng));
+            const uint32_t cbg = (D / 16) * half + cb;                     // column block within the whole head
 #pragma unroll
             for (int k = 0; k < 4; ++k)
-                sr.c[k] = *reinterpret_cast<const uint32_t *>(w_base + (8 * blk * (uint32_t)(DTOT / 2) + ((cb >> 2) * 64 + (4 * nq + k) * 4 + (cb & 3)) * 4u));
-            const uint32_t gq = (16 * cb + 4 * nq) >> lg_G;
+                sr.c[k] = *reinterpret_cast<const uint32_t *>(w_base + (8 * blk * (uint32_t)(DTOT / 2) + ((cbg >> 2) * 64 + (4 * nq + k) * 4 + (cbg & 3)) * 4u));
+            const uint32_t gq = (16 * cbg + 4 * nq) >> lg_G;
 #pragma unroll
             for (int j = 0; j < 8; ++j) sr.m[j] = *reinterpret_cast<const uint32_t *>(m_base + ((((8 * blk + j) << lg_ng) + gq) << 2));
         }
@@ -787,12 +788,9 @@ hipError_t launch_prefill_d(const PrefillArgs &a, const BatchDesc &desc, int seq
     switch (a.pool.head_dim) {
         case 64: return launch_prefill_layout<W, 64>(a, desc, seq0, grid, st);
         case 128: return launch_prefill_layout<W, 128>(a, desc, seq0, grid, st);
-        default:                                   // 256 channels: record-major codes or fp16 values (see mfma_decode_supported)
-            if (a.pool.code_layout == 1) return hipErrorInvalidValue;
-            grid.x *= 2;                           // two workgroups of 128 channels per head
-            if (a.pool.code_layout == 0) hipLaunchKernelGGL((prefill_kernel<W, 256, 0>), grid, dim3(kPfThreads), 0, st, a, desc, seq0);
-            else hipLaunchKernelGGL((prefill_kernel<W, 256, 2>), grid, dim3(kPfThreads), 0, st, a, desc, seq0);
-            return hipGetLastError();
+        default:                                   // 256 channels: two workgroups of 128 channels per head
+            grid.x *= 2;
+            return launch_prefill_layout<W, 256>(a, desc, seq0, grid, st);
     }
 }
 

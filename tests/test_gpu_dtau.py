@@ -110,9 +110,8 @@ def test_fp16_value_caches(d, b, r, dt, T):
     cache.close()
 
 
-def test_record_major_codes_with_many_query_heads():
-    """Geometries the matrix-core kernel does not keep in registers (head_dim 256) store record-major codes also with
-    several query heads per KV head: the vector kernel then serves every query head in a pass of its own."""
+def test_head_dim_256_with_many_query_heads():
+    """256 channels with several query heads per KV head: four heads per workgroup of the matrix-core kernel."""
     d, b, g, r, T = 256, 128, 64, 4, 400
     w = wl.Workload("dtau_d256_r4", 1, 2 * r, 2, d, T, b, g, "f16", seed=77)
     R = wl.projection(b, d)
