@@ -41,8 +41,13 @@ __device__ __forceinline__ int wave_min_dpp(int x) {
     return min(x, __shfl_xor(x, 32));
 }
 
-template <int RQ, int W, int LPT>
-__global__ __launch_bounds__(kThreads, RQ >= 4 ? 2 : 1) void decode_split_kernel(DecodeArgs a, BatchDesc desc, int seq0) {
+// DTAU = true adds the distance-weighted sums of the temperature derivative (Sec. IV-C; formula in
+// kernels_decode_dtau.hip): every query head carries a second accumulator set with weight p e, e = ham - running
+// minimum >= 0; when a page lowers the minimum by k, the second set takes k times the first before the usual rescale.
+template <int RQH, int W, int LPT, bool DTAU>
+__global__ __launch_bounds__(kThreads, RQH * (DTAU ? 2 : 1) >= 4 ? 2 : 1) void decode_split_kernel(DecodeArgs a, BatchDesc desc, int seq0) {
+    constexpr int NV = DTAU ? 2 : 1;              // sum sets per query head: weight p, and weight p e
+    constexpr int RQ = RQH * NV;                  // accumulator sets: set NV q + v of query head q
     constexpr int D = 32 * LPT;
     constexpr int TPW = 64 / LPT;                 // tokens covered by one wave-wide load of codes
     constexpr int ROWS = LPT == 8 ? 2 : 4;        // 16-lane rows of a wave that reach the LDS stage of the epilogue
@@ -50,7 +55,7 @@ __global__ __launch_bounds__(kThreads, RQ >= 4 ? 2 : 1) void decode_split_kernel
     constexpr int EPI_STRIDE = D + LPT;           // per (partial, q): D sums, LPT zero-sums
     __shared__ float epi[NPART * RQ * EPI_STRIDE];
     __shared__ int pages_s[kMaxPagesPerChunk];
-    __shared__ int m_s[kWaves][RQ];
+    __shared__ int m_s[kWaves][RQH];
     __shared__ float l_s[kWaves][RQ];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -63,17 +68,17 @@ __global__ __launch_bounds__(kThreads, RQ >= 4 ? 2 : 1) void decode_split_kernel
 
     const PoolView &pv = a.pool;
     const int H = pv.n_kv_heads, r = pv.n_q_heads / H;
-    const int passes = r / RQ;
+    const int passes = r / RQH;
     const int kvh = blockIdx.y / passes;
-    const int qh0 = kvh * r + (blockIdx.y % passes) * RQ;
+    const int qh0 = kvh * r + (blockIdx.y % passes) * RQH;
     const int seq_g = seq0 + blockIdx.z;
     const int ng = D / pv.group_size;
 
     if (tid < n_pages) pages_s[tid] = pv.block_table[(size_t)sd.seq_id * pv.max_pages_per_seq + chunk0 / kPage + tid];
 
-    uint64_t sq[RQ][W];
+    uint64_t sq[RQH][W];
 #pragma unroll
-    for (int q = 0; q < RQ; ++q)
+    for (int q = 0; q < RQH; ++q)
 #pragma unroll
         for (int w = 0; w < W; ++w) sq[q][w] = a.q_sketch[((size_t)seq_g * pv.n_q_heads + qh0 + q) * W + w];
     __syncthreads();
@@ -86,12 +91,13 @@ __global__ __launch_bounds__(kThreads, RQ >= 4 ? 2 : 1) void decode_split_kernel
 
     float acc[RQ][32];
     float zs[RQ], lsum[RQ];
-    int run_min[RQ];
+    int run_min[RQH];
+#pragma unroll
+    for (int q = 0; q < RQH; ++q) run_min[q] = 1 << 20;
 #pragma unroll
     for (int q = 0; q < RQ; ++q) {
         zs[q] = 0.0f;
         lsum[q] = 0.0f;
-        run_min[q] = 1 << 20;
 #pragma unroll
         for (int i = 0; i < 32; ++i) acc[q][i] = 0.0f;
     }
@@ -117,21 +123,32 @@ __global__ __launch_bounds__(kThreads, RQ >= 4 ? 2 : 1) void decode_split_kernel
         const bool valid = pg * kPage + wave * 64 + lane < n_tok;
         float p[RQ];
 #pragma unroll
-        for (int q = 0; q < RQ; ++q) {
+        for (int q = 0; q < RQH; ++q) {
             int h = 0;
 #pragma unroll
             for (int w = 0; w < W; ++w) h += __popcll(sq[q][w] ^ pr.sk.w[w]);
             const int pmin = wave_min_dpp(valid ? h : (1 << 20));
             if (pmin < run_min[q]) {                       // uniform over the wave; rare after the first pages
                 const float f = fast_exp2(a.exp2_scale * (float)(pmin - run_min[q]));   // 0 while nothing has been accumulated
-                run_min[q] = pmin;
-                lsum[q] *= f;
-                zs[q] *= f;
+                if constexpr (DTAU) {
+                    const float k = (float)(run_min[q] - pmin);      // every e grows by k (all sums are still 0 the first time)
+                    lsum[NV * q + 1] = (lsum[NV * q + 1] + k * lsum[NV * q]) * f;
+                    zs[NV * q + 1] = (zs[NV * q + 1] + k * zs[NV * q]) * f;
 #pragma unroll
-                for (int i = 0; i < 32; ++i) acc[q][i] *= f;
+                    for (int i = 0; i < 32; ++i) acc[NV * q + 1][i] = (acc[NV * q + 1][i] + k * acc[NV * q][i]) * f;
+                }
+                run_min[q] = pmin;
+                lsum[NV * q] *= f;
+                zs[NV * q] *= f;
+#pragma unroll
+                for (int i = 0; i < 32; ++i) acc[NV * q][i] *= f;
             }
-            p[q] = valid ? fast_exp2(a.exp2_scale * (float)(run_min[q] - h)) : 0.0f;
-            lsum[q] += p[q];
+            p[NV * q] = valid ? fast_exp2(a.exp2_scale * (float)(run_min[q] - h)) : 0.0f;
+            lsum[NV * q] += p[NV * q];
+            if constexpr (DTAU) {
+                p[NV * q + 1] = valid ? p[NV * q] * (float)(h - run_min[q]) : 0.0f;
+                lsum[NV * q + 1] += p[NV * q + 1];
+            }
         }
         // ---- value role: lane = (token, 32-channel slice) ----
 #pragma unroll
@@ -233,37 +250,49 @@ __global__ __launch_bounds__(kThreads, RQ >= 4 ? 2 : 1) void decode_split_kernel
     }
     if (lane == 0) {
 #pragma unroll
-        for (int q = 0; q < RQ; ++q) {
-            m_s[wave][q] = run_min[q];
-            l_s[wave][q] = lsum[q];
-        }
+        for (int q = 0; q < RQH; ++q) m_s[wave][q] = run_min[q];
+#pragma unroll
+        for (int q = 0; q < RQ; ++q) l_s[wave][q] = lsum[q];
     }
     __syncthreads();
     const size_t part = ((size_t)seq_g * pv.n_q_heads + qh0) * a.n_splits + blockIdx.x;
-    for (int e = tid; e < RQ * D; e += kThreads) {
+    for (int e = tid; e < RQH * D; e += kThreads) {
         const int q = e / D, c = e % D;
         int hm = 1 << 20;
 #pragma unroll
         for (int w = 0; w < kWaves; ++w) hm = min(hm, m_s[w][q]);
-        float o = 0.0f, l = 0.0f;
+        float o = 0.0f, l = 0.0f, oh = 0.0f, lh = 0.0f;
 #pragma unroll
         for (int w = 0; w < kWaves; ++w) {
+            if (DTAU && m_s[w][q] >= (1 << 20)) continue;                           // a wave that saw no valid token
             const float f = fast_exp2(a.exp2_scale * (float)(hm - m_s[w][q]));      // 0 for a wave that saw no valid token
-            float ow = 0.0f, z = 0.0f;
+            float val[NV];
 #pragma unroll
-            for (int rw = 0; rw < ROWS; ++rw) {
-                const float *src = epi + ((size_t)(w * ROWS + rw) * RQ + q) * EPI_STRIDE;
-                ow += src[c];
-                z += src[D + c / 32];
+            for (int v = 0; v < NV; ++v) {
+                float ow = 0.0f, z = 0.0f;
+#pragma unroll
+                for (int rw = 0; rw < ROWS; ++rw) {
+                    const float *src = epi + ((size_t)(w * ROWS + rw) * RQ + NV * q + v) * EPI_STRIDE;
+                    ow += src[c];
+                    z += src[D + c / 32];
+                }
+                val[v] = ow + z;
             }
-            o = fmaf(f, ow + z, o);
-            l = fmaf(f, l_s[w][q], l);
+            o = fmaf(f, val[0], o);
+            l = fmaf(f, l_s[w][NV * q], l);
+            if constexpr (DTAU) {
+                const float k = (float)(m_s[w][q] - hm);                            // the wave counted e from its own minimum
+                oh = fmaf(f, fmaf(k, val[0], val[NV - 1]), oh);
+                lh = fmaf(f, fmaf(k, l_s[w][NV * q], l_s[w][NV * q + 1]), lh);
+            }
         }
         a.part_o[(part + (size_t)q * a.n_splits) * D + c] = o;
+        if constexpr (DTAU) a.part_oh[(part + (size_t)q * a.n_splits) * D + c] = oh;
         if (c == 0) {
-            float *ml = a.part_ml + (part + (size_t)q * a.n_splits) * 2;
+            float *ml = a.part_ml + (part + (size_t)q * a.n_splits) * (DTAU ? 4 : 2);
             ml[0] = __int_as_float(hm);
             ml[1] = l;
+            if constexpr (DTAU) ml[2] = lh;
         }
     }
 }
@@ -380,23 +409,23 @@ __global__ void qsketch_kernel(DecodeArgs a, int seq0) {
     if ((threadIdx.x & 63) == 0) a.q_sketch[vec * W + (threadIdx.x >> 6)] = mask;
 }
 
-template <int RQ, int W>
+template <int RQ, int W, bool DTAU>
 hipError_t launch_split_lpt(const DecodeArgs &a, const BatchDesc &desc, int seq0, dim3 grid, hipStream_t st) {
     switch (a.pool.head_dim) {
-        case 64: hipLaunchKernelGGL((decode_split_kernel<RQ, W, 2>), grid, dim3(kThreads), 0, st, a, desc, seq0); break;
-        case 128: hipLaunchKernelGGL((decode_split_kernel<RQ, W, 4>), grid, dim3(kThreads), 0, st, a, desc, seq0); break;
-        default: hipLaunchKernelGGL((decode_split_kernel<RQ, W, 8>), grid, dim3(kThreads), 0, st, a, desc, seq0); break;
+        case 64: hipLaunchKernelGGL((decode_split_kernel<RQ, W, 2, DTAU>), grid, dim3(kThreads), 0, st, a, desc, seq0); break;
+        case 128: hipLaunchKernelGGL((decode_split_kernel<RQ, W, 4, DTAU>), grid, dim3(kThreads), 0, st, a, desc, seq0); break;
+        default: hipLaunchKernelGGL((decode_split_kernel<RQ, W, 8, DTAU>), grid, dim3(kThreads), 0, st, a, desc, seq0); break;
     }
     return hipGetLastError();
 }
 
-template <int RQ>
+template <int RQ, bool DTAU = false>
 hipError_t launch_split_w(const DecodeArgs &a, const BatchDesc &desc, int seq0, dim3 grid, hipStream_t st) {
     switch (a.pool.sketch_bits) {
-        case 64: return launch_split_lpt<RQ, 1>(a, desc, seq0, grid, st);
-        case 128: return launch_split_lpt<RQ, 2>(a, desc, seq0, grid, st);
-        case 256: return launch_split_lpt<RQ, 4>(a, desc, seq0, grid, st);
-        default: return launch_split_lpt<RQ, 8>(a, desc, seq0, grid, st);
+        case 64: return launch_split_lpt<RQ, 1, DTAU>(a, desc, seq0, grid, st);
+        case 128: return launch_split_lpt<RQ, 2, DTAU>(a, desc, seq0, grid, st);
+        case 256: return launch_split_lpt<RQ, 4, DTAU>(a, desc, seq0, grid, st);
+        default: return launch_split_lpt<RQ, 8, DTAU>(a, desc, seq0, grid, st);
     }
 }
 
@@ -414,6 +443,13 @@ hipError_t launch_decode_split(const DecodeArgs &a, const BatchDesc &desc, int s
         case 2: return launch_split_w<2>(a, desc, seq0, grid, st);
         default: return launch_split_w<1>(a, desc, seq0, grid, st);
     }
+}
+
+// The same with the distance-weighted sums of the temperature derivative: one query head (two accumulator sets) per
+// workgroup pass.
+hipError_t launch_decode_dtau_split(const DecodeArgs &a, const BatchDesc &desc, int seq0, int n_seqs, hipStream_t st) {
+    const dim3 grid((unsigned)a.n_splits, (unsigned)a.pool.n_q_heads, (unsigned)n_seqs);
+    return launch_split_w<1, true>(a, desc, seq0, grid, st);
 }
 
 hipError_t launch_merge(const DecodeArgs &a, const BatchDesc &desc, int seq0, int n_seqs, hipStream_t st) {
