@@ -85,7 +85,7 @@ __global__ __launch_bounds__(kThreads, (RQH == 2 && D <= 128) ? 3 : 2) void deco
     constexpr int NCB4 = (NCB + 3) / 4;           // 16-byte loads of code words per lane and step
     constexpr int CBG = NCB / NG;                 // column blocks per quantisation group
     __shared__ float epi[kWaves][NROWS][D];       // epilogue staging of the accumulators
-    __shared__ __attribute__((aligned(16))) unsigned short a_s[kWaves][NG][16][32];   // A operands, bf16 bits
+    __shared__ __attribute__((aligned(16))) unsigned short a_s[kWaves][2][NG][16][32];   // A operands of a page's two steps, bf16 bits
     constexpr int kMaxW = W;                      // sketch words per token, all kept in registers
     __shared__ uint64_t sq_s[RQMAX][kMaxW];
     __shared__ int pages_s[kMaxPagesPerChunk];
@@ -117,7 +117,7 @@ __global__ __launch_bounds__(kThreads, (RQH == 2 && D <= 128) ? 3 : 2) void deco
         sq_s[q][w] = (q < RQ && w < W) ? a.q_sketch[((size_t)seq_g * pv.n_q_heads + qh0 + q) * W + w] : 0;
     }
     // rows of the A operands that no query head uses stay zero for the whole kernel
-    for (int i = tid; i < kWaves * NG * 16 * 32 / 2; i += kThreads) reinterpret_cast<uint32_t *>(a_s)[i] = 0u;
+    for (int i = tid; i < kWaves * 2 * NG * 16 * 32 / 2; i += kThreads) reinterpret_cast<uint32_t *>(a_s)[i] = 0u;
     __syncthreads();
 
     const int n = lane & 15, kb = lane >> 4;       // MFMA roles: column / row index, K block
@@ -257,7 +257,7 @@ __global__ __launch_bounds__(kThreads, (RQH == 2 && D <= 128) ? 3 : 2) void deco
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
         }
-        // ---- two steps of 32 tokens: weights -> A operand, code words -> B operands, MFMA ----
+        // ---- two steps of 32 tokens: weights -> A operands (both steps, then ONE hand-over through LDS) ----
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
             float p[NV][RQH];
@@ -287,17 +287,21 @@ __global__ __launch_bounds__(kThreads, (RQH == 2 && D <= 128) ? 3 : 2) void deco
                         // weight short by 2^-16 of itself on average, and next to the full-precision sum of p zero
                         // (which nearly cancels the code term) that bias was the kernel's largest error
                         const uint32_t lo = __float_as_uint(w - __uint_as_float(hi)) + 0x8000u;
-                        a_s[wave][g][2 * v * RQMAX + 2 * qq + qs][tk] = (unsigned short)(hi >> 16);
-                        a_s[wave][g][(2 * v + 1) * RQMAX + 2 * qq + qs][tk] = (unsigned short)(lo >> 16);
+                        a_s[wave][t][g][2 * v * RQMAX + 2 * qq + qs][tk] = (unsigned short)(hi >> 16);
+                        a_s[wave][t][g][(2 * v + 1) * RQMAX + 2 * qq + qs][tk] = (unsigned short)(lo >> 16);
                     }
             }
-            // the operands are read by other lanes of the same wave: order the LDS writes before the reads
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        }
+        // the operands are read by other lanes of the same wave: order the LDS writes before the reads
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        // ---- code words -> B operands, MFMA ----
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
 #pragma unroll
             for (int g = 0; g < NG; ++g) {
-                const bf16x8 A = *reinterpret_cast<const bf16x8 *>(&a_s[wave][g][n][8 * kb]);
+                const bf16x8 A = *reinterpret_cast<const bf16x8 *>(&a_s[wave][t][g][n][8 * kb]);
 #pragma unroll
                 for (int j = 0; j < CBG; ++j) {
                     const int cb = g * CBG + j;
@@ -313,10 +317,10 @@ __global__ __launch_bounds__(kThreads, (RQH == 2 && D <= 128) ? 3 : 2) void deco
                 accsum[g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, ones.v, accsum[g], 0, 0, 0);
             }
             if constexpr (more) load_step(pr, pg + 1, t);
-            // the next step overwrites the operands: its writes must not pass these reads
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
         }
+        // the next page overwrites the operands: its writes must not pass these reads
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
     };
 
     {
