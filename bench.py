@@ -50,6 +50,9 @@ def parse_args():
     ap.add_argument("--per-token-layers", type=int, default=0, metavar="L",
                     help="secondary line: per-token attention latency of L layers (one cache each), every layer one fused "
                          "decode step, all captured in one HIP graph")
+    ap.add_argument("--dtau", action="store_true",
+                    help="decode workloads: time h1bkv_decode_attn_dtau (output and its derivative with respect to the "
+                         "softmax temperature) in place of h1bkv_decode_attn; secondary line")
     ap.add_argument("--rotate", type=int, default=-1, metavar="N",
                     help="decode workloads: N identical caches used in turn, so that more than 512 MB (twice the 256 MB "
                          "last-level cache) is touched between two uses of the same bytes; -1 = as many as that needs")
@@ -222,15 +225,16 @@ def bench_append(args, torch, B, wl, w, workers):
 
 # MI355X dense matrix-core peaks of the two operand types the prefill kernel uses.
 MFMA_F16_PEAK_TFLOPS = 2500.0
-MFMA_I8_PEAK_TOPS = 5000.0
+MFMA_F4_PEAK_TOPS = 10100.0
 
 
 def bench_prefill(args, torch, B, wl, w, workers):
     """Secondary line: a whole prompt -- append all tokens of every sequence, then causal attention of every position
     over the compressed cache (h1bkv_prefill_attn).  Both halves of the attention kernel are dense contractions on the
     matrix cores: the weighted sum of Eq.(5) with fp16 operands (2 d flop per visible (query, key) pair) and the
-    Hamming distances of Eq.(3) with int8 operands (2 b operations per pair).  The roofline is the value contraction
-    against the fp16 matrix peak; the score contraction against the int8 peak is reported next to it."""
+    Hamming distances of Eq.(3) with 4-bit operands (a key bit as fp4 0.5, a query bit as fp4 -4 / +4; 2 b operations
+    per pair).  The roofline is the value contraction against the fp16 matrix peak; the score contraction against the
+    fp4 peak is reported next to it."""
     n_new, Bsz = w.context, w.batch
     R = wl.projection(w.sketch_bits, w.head_dim)
     pages_per_seq = (n_new + 255) // 256 + 1
@@ -293,8 +297,8 @@ def bench_prefill(args, torch, B, wl, w, workers):
                      "unit": "TFLOP/s", "frac": value_tflops / MFMA_F16_PEAK_TFLOPS, "traffic": None,
                      "kernel_ms": kernel_ms["prefill"], "pairs_per_s": pairs / sec,
                      "algorithmic_flop_per_pair": 2 * w.head_dim,
-                     "scores_int8": {"achieved": score_tops, "peak": MFMA_I8_PEAK_TOPS, "unit": "TOP/s",
-                                     "frac": score_tops / MFMA_I8_PEAK_TOPS, "algorithmic_op_per_pair": 2 * w.sketch_bits}},
+                     "scores_fp4": {"achieved": score_tops, "peak": MFMA_F4_PEAK_TOPS, "unit": "TOP/s",
+                                    "frac": score_tops / MFMA_F4_PEAK_TOPS, "algorithmic_op_per_pair": 2 * w.sketch_bits}},
         "kernel_ms": kernel_ms}))
 
 
@@ -452,8 +456,9 @@ def main():
     v1 = torch.from_numpy(wl.kv_slab(w, "v", seqs, T - 1, 1)).cuda()
     q = torch.from_numpy(wl.queries(w)).cuda()
     out = torch.empty((Bsz, w.n_q_heads, w.head_dim), dtype=torch.float32, device="cuda")
-    ws_bytes = B.h1bkv_decode_workspace_bytes(cache.h, Bsz, T)
+    ws_bytes = (B.h1bkv_decode_dtau_workspace_bytes if args.dtau else B.h1bkv_decode_workspace_bytes)(cache.h, Bsz, T)
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    dout = torch.empty_like(out) if args.dtau else None
     stream = torch.cuda.current_stream()
     turn = [0]
 
@@ -466,7 +471,10 @@ def main():
         for s in seqs:
             B.check(B.h1bkv_truncate_seq(c_.h, s, T - 1))
         B.check(B.h1bkv_append_kv(c_.h, seqs, 1, k1, v1, k1.stride(0), k1.stride(1), k1.stride(2), stream))
-        B.check(B.h1bkv_decode_attn(c_.h, seqs, q, tau, out, ws, ws_bytes, stream))
+        if args.dtau:
+            B.check(B.h1bkv_decode_attn_dtau(c_.h, seqs, q, tau, out, dout, ws, ws_bytes, stream))
+        else:
+            B.check(B.h1bkv_decode_attn(c_.h, seqs, q, tau, out, ws, ws_bytes, stream))
 
     def profile_all(capacity, mask, stride=1):
         for c_ in caches:
@@ -504,14 +512,16 @@ def main():
         B.check(B.h1bkv_decode_step(c_.h, seqs, k1, v1, k1.stride(0), k1.stride(2), q, tau, out, ws, ws_bytes, stream))
 
     profile_all(0, 0)
-    for _ in range(args.warmup):
-        fused_step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        fused_step()
-    torch.cuda.synchronize()
-    fused_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    fused_ms = None
+    if not args.dtau:                   # (the fused entry point has no derivative form)
+        for _ in range(args.warmup):
+            fused_step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            fused_step()
+        torch.cuda.synchronize()
+        fused_ms = (time.perf_counter() - t0) * 1e3 / args.steps
     profile_all(10, 0xF)
     for _ in range(10 * n_rot):
         step()
@@ -545,7 +555,7 @@ def main():
     split_ms = kernel_ms["decode_split"]
     achieved = alg_bytes / (split_ms * 1e-3) / 1e9
     result = {
-        "metric": "decode_attn_kv_tokens_per_s",
+        "metric": "decode_attn_dtau_kv_tokens_per_s" if args.dtau else "decode_attn_kv_tokens_per_s",
         "value": Bsz * T / (ms_per_step * 1e-3),
         "unit": "KV-tokens/s",
         "n_gpus": 1,
@@ -560,7 +570,8 @@ def main():
         "config": {"workload": w.name, "batch": Bsz, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
                    "head_dim": w.head_dim, "context": T, "sketch_bits": w.sketch_bits, "group_size": w.group_size,
                    "in_dtype": w.dtype, "tau": tau, "record_bytes": record_bytes, "value_bits": args.value_bits,
-                   "step": "append 1 token/sequence + decode attention over the full context"},
+                   "step": "append 1 token/sequence + decode attention over the full context"
+                           + (" with the derivative of the output with respect to the temperature" if args.dtau else "")},
         "roofline": {"bound": "hbm", "kernel": split_kernel, "achieved": achieved, "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic_from_profiles(w.name + ("_f16v" if f16v else "")),
                      "algorithmic_bytes_per_launch": alg_bytes, "kernel_ms": split_ms,
@@ -568,10 +579,11 @@ def main():
                      "caches_in_rotation": n_rot, "bytes_between_reuse": n_rot * cache_bytes},
         "records_per_s": records / (ms_per_step * 1e-3),
         "kernel_ms": kernel_ms,
-        "fused_step": {"entry_point": "h1bkv_decode_step", "ms_per_step": fused_ms, "value": Bsz * T / (fused_ms * 1e-3)},
         "fill_s": t_fill,
     }
-    if not args.no_cpu_baseline:
+    if fused_ms is not None:
+        result["fused_step"] = {"entry_point": "h1bkv_decode_step", "ms_per_step": fused_ms, "value": Bsz * T / (fused_ms * 1e-3)}
+    if not args.no_cpu_baseline and not args.dtau:
         result["cpu_baseline"] = cpu_baseline(wl, w, tau, workers, args.value_bits)
     print(json.dumps(result))
 
