@@ -203,7 +203,8 @@ int h1bkv_decode_attn_dtau(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t 
  * (H1BKV_ERANGE otherwise).  q_dev [n_seqs][n_q][n_q_heads][d] in in_dtype with strides in elements (channel
  * stride 1, rows 16-byte aligned); out_dev [n_seqs][n_q][n_q_heads][d] fp32, dense.  The weighted sum runs on the
  * matrix cores with fp16 operands (weights and dequantised values rounded to fp16, fp32 accumulation).
- * Supported for head_dim <= 128 (H1BKV_ESHAPE otherwise); with value_bits = 16 the stored fp16 values are used as they are.
+ * Every cache geometry is supported (a head of 256 channels is served as two halves of 128); with value_bits = 16 the
+ * stored fp16 values are used as they are.
  * workspace_dev: >= h1bkv_prefill_workspace_bytes(c, n_seqs, n_q), 256-byte aligned: the chunk's query sketches and, for
  * chunks too short to fill the chip with one workgroup per 128 query positions, the per-row partial results of up to
  * 16 context splits (a chunk of a few hundred positions over a long context is split over the context as well, and

@@ -8,15 +8,20 @@
 // (PoolView::code_layout == 1): one 32-bit word holds the 8 codes of one channel for 8 consecutive tokens.
 //
 //   B operand (K = 32 tokens x N = 16 channels): lane (n, kb) needs 8 consecutive tokens of channel n -- exactly
-//     one code word.  Three shifts and four AND-ORs put the nibbles into the mantissas of bf16 128.0 constants:
-//     the register pair reads as 128 + code, exact in bf16.
+//     one code word.  A nibble masked in place at bits 0-3 or 4-7 of an otherwise zero half-word IS a bf16 number:
+//     bit patterns below 2^8 (exponent field 0 or 1) are linear in their integer value, pattern m reads m 2^-133, and
+//     the matrix cores take such inputs as they are (measured).  So the operand is one shift and four ANDs per code
+//     word -- code 2^-133 for the tokens whose nibble sits at bits 0-3, code 2^-129 for those at bits 4-7 -- with no
+//     offset to remove afterwards; the weights of a token carry the matching power of two (below).
 //   A operand (M = 16 rows x K = 32 tokens): the weights w = p[q][t] * scale[t][g] of one quantisation group g,
 //     split exactly into two bf16 parts (top 16 bits, and the top 16 bits of the remainder): row q carries the high
 //     part and row q + RQMAX the low part, so the product keeps 16 bits of every weight at no extra MFMA cost (the M
 //     dimension is far from full anyway).  Each weight is computed once (lane = (token, query-head parity)),
 //     written to LDS as two half-words and read back in operand order (16 bytes per lane).
-//   The constant 128 of the B operand is removed with the row sums of A, which one more MFMA against an all-ones B
-//     delivers in the same rounding as the main products;  sum_t p zero_t  is accumulated on the vector ALU.
+//   A lane scores and weighs the same token slot of every page, so the power of two its weights carry -- 2^64 or 2^60,
+//     by where the slot's nibble sits -- is a per-lane constant folded into the exponent argument of the softmax weight;
+//     the lane's sums of p and of p zero carry it too and shed it once, in the epilogue, where the accumulators are
+//     multiplied by 2^69.  sum_t p zero_t  is accumulated on the vector ALU.
 //
 // Every wave streams on its own: it owns 64 tokens of each page of the chunk, scores them (lane = (token, query
 // head parity), XOR + popcount against the query sketches in LDS), keeps a running maximum per head -- when a
@@ -92,7 +97,6 @@ __global__ __launch_bounds__(kThreads, (RQH == 2 && D <= 128) ? 3 : 2) void deco
     __shared__ float f_s[kWaves][RQMAX];          // rescale factors on their way from the scoring lanes to the MFMA rows
     __shared__ int m_s[kWaves][RQMAX];
     __shared__ float l_s[kWaves][NV][RQMAX];
-    __shared__ float sum_s[kWaves][NG][NROWS];
     __shared__ float zs_s[kWaves][NV][RQMAX][NG];
     __shared__ float k_s[kWaves][RQMAX];          // (DTAU) by how much a page lowered each head's running minimum
 
@@ -122,11 +126,9 @@ __global__ __launch_bounds__(kThreads, (RQH == 2 && D <= 128) ? 3 : 2) void deco
 
     const int n = lane & 15, kb = lane >> 4;       // MFMA roles: column / row index, K block
     const int tk = lane & 31, qs = lane >> 5;      // scoring and weight roles: token, query-head parity
-    f32x4 acc[NCB], accsum[NG];
+    f32x4 acc[NCB];
 #pragma unroll
     for (int cb = 0; cb < NCB; ++cb) acc[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int g = 0; g < NG; ++g) accsum[g] = f32x4{0.f, 0.f, 0.f, 0.f};
     float zs[NV][RQH][NG], lsum[NV][RQH];
     int run_min[RQH];
 #pragma unroll
@@ -139,10 +141,10 @@ __global__ __launch_bounds__(kThreads, (RQH == 2 && D <= 128) ? 3 : 2) void deco
             for (int g = 0; g < NG; ++g) zs[v][qq][g] = 0.0f;
         }
     }
-    const uint32_t mask = opaque_vgpr(0x000F000Fu), magic = opaque_vgpr(0x43004300u);    // bf16 128.0 in both halves
-    BOperand ones;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) ones.u[i] = 0x3F803F80u;       // bf16 1.0
+    // Tokens 2, 3, 6, 7 of a block of 8 have their nibbles at bits 4-7 of the operand halves (code 2^-129), the others at
+    // bits 0-3 (code 2^-133): this lane's weights carry 2^60 or 2^64, so that every product is weight x code x 2^-69.
+    const float w_exp = (tk & 2) ? 60.0f : 64.0f;
+    const float w_unscale = (tk & 2) ? 0x1p-60f : 0x1p-64f;
 
     // One register set holds a page; each plane is requested again, for the next page, as soon as its last use in the
     // current page is behind: the sketches after scoring, the codes and scale/zero of a 32-token step after that
@@ -241,19 +243,11 @@ __global__ __launch_bounds__(kThreads, (RQH == 2 && D <= 128) ? 3 : 2) void deco
                 for (int cb = 0; cb < NCB; ++cb)
 #pragma unroll
                     for (int j = 0; j < 4; ++j) acc[cb][j] = fmaf(kr[j], __shfl_xor(acc[cb][j], 32), acc[cb][j]);
-#pragma unroll
-                for (int g = 0; g < NG; ++g)
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) accsum[g][j] = fmaf(kr[j], __shfl_xor(accsum[g][j], 32), accsum[g][j]);
             }
 #pragma unroll
             for (int cb = 0; cb < NCB; ++cb)
 #pragma unroll
                 for (int j = 0; j < 4; ++j) acc[cb][j] *= fr[j];
-#pragma unroll
-            for (int g = 0; g < NG; ++g)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) accsum[g][j] *= fr[j];
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
         }
@@ -264,7 +258,7 @@ __global__ __launch_bounds__(kThreads, (RQH == 2 && D <= 128) ? 3 : 2) void deco
 #pragma unroll
             for (int qq = 0; qq < RQH; ++qq) {
                 // heads beyond RQ have an all-zero query sketch here; their rows are never read back
-                p[0][qq] = valid[t] ? fast_exp2(a.exp2_scale * (float)(run_min[qq] - ham[t][qq])) : 0.0f;
+                p[0][qq] = valid[t] ? fast_exp2(fmaf(a.exp2_scale, (float)(run_min[qq] - ham[t][qq]), w_exp)) : 0.0f;
                 lsum[0][qq] += p[0][qq];
                 if constexpr (DTAU) {
                     p[1][qq] = valid[t] ? p[0][qq] * (float)(ham[t][qq] - run_min[qq]) : 0.0f;
@@ -307,14 +301,14 @@ __global__ __launch_bounds__(kThreads, (RQH == 2 && D <= 128) ? 3 : 2) void deco
                     const int cb = g * CBG + j;
                     const uint4 c4 = pr.c[t][cb >> 2];
                     const uint32_t x = (cb & 3) == 0 ? c4.x : (cb & 3) == 1 ? c4.y : (cb & 3) == 2 ? c4.z : c4.w;
+                    const uint32_t y = x >> 8;
                     BOperand b;
-                    b.u[0] = and_or(x, mask, magic);           // nibbles 0, 4 = tokens 0, 1 of the block
-                    b.u[1] = and_or(x >> 4, mask, magic);      // nibbles 1, 5 = tokens 2, 3
-                    b.u[2] = and_or(x >> 8, mask, magic);      // nibbles 2, 6 = tokens 4, 5
-                    b.u[3] = and_or(x >> 12, mask, magic);     // nibbles 3, 7 = tokens 6, 7
+                    b.u[0] = x & 0x000F000Fu;                  // nibbles 0, 4 = tokens 0, 1 of the block
+                    b.u[1] = x & 0x00F000F0u;                  // nibbles 1, 5 = tokens 2, 3
+                    b.u[2] = y & 0x000F000Fu;                  // nibbles 2, 6 = tokens 4, 5
+                    b.u[3] = y & 0x00F000F0u;                  // nibbles 3, 7 = tokens 6, 7
                     acc[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, b.v, acc[cb], 0, 0, 0);
                 }
-                accsum[g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, ones.v, accsum[g], 0, 0, 0);
             }
             if constexpr (more) load_step(pr, pg + 1, t);
         }
@@ -337,21 +331,15 @@ __global__ __launch_bounds__(kThreads, (RQH == 2 && D <= 128) ? 3 : 2) void deco
     for (int v = 0; v < NV; ++v)
 #pragma unroll
         for (int qq = 0; qq < RQH; ++qq) {
-            lsum[v][qq] = half32_sum(lsum[v][qq]);
+            lsum[v][qq] = half32_sum(lsum[v][qq] * w_unscale);
 #pragma unroll
-            for (int g = 0; g < NG; ++g) zs[v][qq][g] = half32_sum(zs[v][qq][g]);
+            for (int g = 0; g < NG; ++g) zs[v][qq][g] = half32_sum(zs[v][qq][g] * w_unscale);
         }
     if (4 * kb < NROWS) {
 #pragma unroll
         for (int cb = 0; cb < NCB; ++cb)
 #pragma unroll
             for (int j = 0; j < 4; ++j) epi[wave][4 * kb + j][16 * cb + n] = acc[cb][j];
-        if (n == 0) {
-#pragma unroll
-            for (int g = 0; g < NG; ++g)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) sum_s[wave][g][4 * kb + j] = accsum[g][j];
-        }
     }
     if (tk == 0) {
 #pragma unroll
@@ -381,8 +369,7 @@ __global__ __launch_bounds__(kThreads, (RQH == 2 && D <= 128) ? 3 : 2) void deco
 #pragma unroll
             for (int v = 0; v < NV; ++v) {
                 const int hi_row = 2 * v * RQMAX + q, lo_row = hi_row + RQMAX;
-                const float ws = sum_s[w][g][hi_row] + sum_s[w][g][lo_row];
-                val[v] = fmaf(-128.0f, ws, epi[w][hi_row][c] + epi[w][lo_row][c]) + zs_s[w][v][q][g];   // B held 128 + code
+                val[v] = fmaf(0x1p69f, epi[w][hi_row][c] + epi[w][lo_row][c], zs_s[w][v][q][g]);   // products were weight x code x 2^-69
             }
             o = fmaf(f, val[0], o);
             l = fmaf(f, l_s[w][0][q], l);

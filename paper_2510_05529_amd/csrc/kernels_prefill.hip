@@ -83,7 +83,10 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_kernel(PrefillArgs a, B
     constexpr int NCB = D / 32;                   // 32-channel column blocks
     constexpr int TK = kTK;
     constexpr int NSTEP = TK / 32;                // 32-token MFMA steps per tile
-    constexpr int VS = TK * 2 + 16;               // bytes per channel row of the value tile (16 B pad: conflict-free b128 reads)
+    // bytes per channel row of the value tile.  Ten 16-byte blocks per row: 32 consecutive rows then start on 16 different
+    // even bank groups (rows i and i + 16 on the same one), and the exchange below, whose key differs by one between
+    // those two rows, moves one of them to the odd neighbour: the 16-byte operand reads are conflict-free.
+    constexpr int VS = TK * 2 + 32;
     constexpr int KS = 32 * W + 16;               // bytes per token row of the key tile: 2 W sketch dwords, 16 B of nibbles each
     constexpr int NSKD = TK * 2 * W;              // 32-bit sketch units per tile
     constexpr int NSK = NSKD / kPfThreads > 0 ? NSKD / kPfThreads : 1;
