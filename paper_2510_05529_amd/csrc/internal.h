@@ -107,12 +107,13 @@ struct PrefillArgs {
     float exp2_scale;         // 2 log2(e) / (b tau)
 };
 
-constexpr int kPrefillRows = 128;            // query positions per prefill workgroup
+// Query positions per prefill workgroup: 256 (eight waves) for long chunks, 128 (four waves) for short ones.
+inline int prefill_rows(int n_q) { return n_q >= 1024 ? 256 : 128; }
 constexpr int kPrefillMaxSplits = 16;
 // Most context splits a prefill call of n_seqs x n_q query positions can use: enough workgroups to fill the chip when
 // the chunk is short (a long prompt alone already brings thousands of workgroups: one split).
 inline int prefill_max_splits(int n_q_heads, int n_seqs, int n_q) {
-    const int64_t wgs = (int64_t)n_q_heads * n_seqs * ((n_q + kPrefillRows - 1) / kPrefillRows);
+    const int64_t wgs = (int64_t)n_q_heads * n_seqs * ((n_q + prefill_rows(n_q) - 1) / prefill_rows(n_q));
     const int64_t s = (1024 + wgs - 1) / wgs;
     return (int)(s < 1 ? 1 : s > kPrefillMaxSplits ? kPrefillMaxSplits : s);
 }

@@ -43,9 +43,6 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef int i32x8 __attribute__((ext_vector_type(8)));
 
-constexpr int kPfWaves = 4;
-constexpr int kPfThreads = kPfWaves * 64;
-constexpr int kQB = kPfWaves * 32;            // query positions per workgroup
 constexpr int kCS = 8;                        // channels per staging item of the token-major layouts
 constexpr int kTK = 64;                       // key tokens per tile
 constexpr float kPScaleLog2 = 4.0f;           // weights are stored as p * 2^4
@@ -76,8 +73,12 @@ struct StageRegs {           // one thread's share of a key tile on its way from
     uint32_t m[LAYOUT == 2 ? 16 : 8];
 };
 
-template <int W, int DTOT, int LAYOUT>
-__global__ __launch_bounds__(kPfThreads, 2) void prefill_kernel(PrefillArgs a, BatchDesc desc, int seq0) {
+// WAVES: 4 or 8 waves of 32 query rows.  Eight share every staged key tile among twice the rows (and the staging work
+// among twice the threads); four keep short chunks, whose workgroups are few, spread over more compute units.
+template <int W, int DTOT, int LAYOUT, int WAVES>
+__global__ __launch_bounds__(WAVES * 64, 8 / WAVES) void prefill_kernel(PrefillArgs a, BatchDesc desc, int seq0) {
+    constexpr int kPfThreads = WAVES * 64;
+    constexpr int kQB = WAVES * 32;               // query positions per workgroup
     constexpr int D = DTOT > 128 ? 128 : DTOT;    // channels per workgroup
     constexpr int NHALF = DTOT / D;               // workgroups per head
     constexpr int NCB = D / 32;                   // 32-channel column blocks
@@ -778,12 +779,18 @@ __global__ __launch_bounds__(kThreads) void sketch_rows_wide_kernel(PrefillArgs 
     }
 }
 
+template <int W, int D, int WAVES>
+hipError_t launch_prefill_waves(const PrefillArgs &a, const BatchDesc &desc, int seq0, dim3 grid, hipStream_t st) {
+    if (a.pool.code_layout == 0) hipLaunchKernelGGL((prefill_kernel<W, D, 0, WAVES>), grid, dim3(WAVES * 64), 0, st, a, desc, seq0);
+    else if (a.pool.code_layout == 1) hipLaunchKernelGGL((prefill_kernel<W, D, 1, WAVES>), grid, dim3(WAVES * 64), 0, st, a, desc, seq0);
+    else hipLaunchKernelGGL((prefill_kernel<W, D, 2, WAVES>), grid, dim3(WAVES * 64), 0, st, a, desc, seq0);
+    return hipGetLastError();
+}
+
 template <int W, int D>
 hipError_t launch_prefill_layout(const PrefillArgs &a, const BatchDesc &desc, int seq0, dim3 grid, hipStream_t st) {
-    if (a.pool.code_layout == 0) hipLaunchKernelGGL((prefill_kernel<W, D, 0>), grid, dim3(kPfThreads), 0, st, a, desc, seq0);
-    else if (a.pool.code_layout == 1) hipLaunchKernelGGL((prefill_kernel<W, D, 1>), grid, dim3(kPfThreads), 0, st, a, desc, seq0);
-    else hipLaunchKernelGGL((prefill_kernel<W, D, 2>), grid, dim3(kPfThreads), 0, st, a, desc, seq0);
-    return hipGetLastError();
+    return prefill_rows(a.n_q) == 256 ? launch_prefill_waves<W, D, 8>(a, desc, seq0, grid, st)
+                                      : launch_prefill_waves<W, D, 4>(a, desc, seq0, grid, st);
 }
 
 template <int W>
@@ -806,8 +813,8 @@ hipError_t launch_prefill_merge(const PrefillArgs &a, int seq0, int n_seqs, hipS
 }
 
 hipError_t launch_prefill(const PrefillArgs &a, const BatchDesc &desc, int seq0, int n_seqs, hipStream_t st) {
-    static_assert(kQB == kPrefillRows, "the host sizes grids and workspaces with kPrefillRows");
-    const dim3 grid((unsigned)a.pool.n_q_heads, (unsigned)n_seqs, (unsigned)((a.n_q + kQB - 1) / kQB * a.n_splits));
+    const int rows = prefill_rows(a.n_q);        // (the host sizes grids and workspaces with the same function)
+    const dim3 grid((unsigned)a.pool.n_q_heads, (unsigned)n_seqs, (unsigned)((a.n_q + rows - 1) / rows * a.n_splits));
     switch (a.pool.sketch_bits) {
         case 64: return launch_prefill_d<1>(a, desc, seq0, grid, st);
         case 128: return launch_prefill_d<2>(a, desc, seq0, grid, st);

@@ -40,7 +40,13 @@ CASES = [(128, 128, 32, 1, "f16", 300, 300),      # a whole prompt, record-major
          (64, 256, 32, 1, "f16", 1000, 129),
          (256, 128, 64, 1, "f16", 333, 333),      # 256 channels: two workgroups of 128 channels per head
          (256, 256, 128, 4, "f32", 450, 140),     # ... with several query heads per KV head (record-major codes at this size)
-         (256, 64, 32, 2, "f16", 2000, 64)]       # ... short chunk over a long context: split over the context, merged
+         (256, 64, 32, 2, "f16", 2000, 64),       # ... short chunk over a long context: split over the context, merged
+         # chunks of 1024 positions and more run as workgroups of eight waves (256 query rows)
+         (128, 128, 32, 1, "f16", 1100, 1100),    # ragged last block (1100 = 4 x 256 + 76)
+         (128, 256, 64, 4, "f16", 1300, 1030),    # token-interleaved codes, a context below the chunk
+         (64, 64, 32, 2, "f32", 1024, 1024),
+         (256, 128, 64, 1, "f16", 1200, 1100),
+         (128, 512, 128, 2, "f16", 1500, 1024)]
 
 
 @pytest.mark.parametrize("d,b,g,r,dt,T,n_q", CASES)
@@ -115,7 +121,8 @@ def test_query_sketches_are_bit_exact(dt, scale):
     cache.close()
 
 
-@pytest.mark.parametrize("d,b,r,T,n_q", [(128, 128, 2, 333, 200), (256, 128, 1, 300, 300), (64, 64, 4, 140, 90)])
+@pytest.mark.parametrize("d,b,r,T,n_q", [(128, 128, 2, 333, 200), (256, 128, 1, 300, 300), (64, 64, 4, 140, 90),
+                                         (128, 128, 1, 1111, 1050)])
 def test_prefill_over_fp16_values(d, b, r, T, n_q):
     """The "1-bit key only" variant (value_bits = 16): same kernel, the value tile is copied instead of dequantised."""
     w = wl.Workload("prefill_f16v", 2, 2 * r, 2, d, T, b, 32, "f16", seed=7)
