@@ -431,29 +431,36 @@ struct KeyRows {
     const AppendArgs &a;
     SeqDesc sd;
     int L, off8, n_slots;
+    ProjDiv by_L;
     __device__ int rows_in(long tile) const { return min(kTile, n_slots - (int)tile * kTile); }
     __device__ size_t src(long tile, int rl) const {
-        const int slot = (int)tile * kTile + rl, head = slot / L, t = slot % L - off8;
+        uint32_t head, rem;
+        by_L.divmod((uint32_t)((int)tile * kTile + rl), head, rem);
+        const int t = (int)rem - off8;
         return t >= 0 && t < a.n_new ? (size_t)t * a.stride_tok + (size_t)head * a.stride_head : kProjNoRow;
     }
     __device__ int page_request(long tile, int rl) const {
-        const int slot = (int)tile * kTile + rl, pos = sd.pos + slot % L - off8;
+        uint32_t head, rem;
+        by_L.divmod((uint32_t)((int)tile * kTile + rl), head, rem);
+        const int pos = sd.pos + (int)rem - off8;
         return a.pool.block_table[(size_t)sd.seq_id * a.pool.max_pages_per_seq + pos / kPage];
     }
     __device__ uint32_t *dst(long tile, int rl, int page) const {
-        const int slot = (int)tile * kTile + rl, head = slot / L, pos = sd.pos + slot % L - off8;
+        uint32_t head, rem;
+        by_L.divmod((uint32_t)((int)tile * kTile + rl), head, rem);
+        const int pos = sd.pos + (int)rem - off8;
         const size_t rec = ((size_t)page * a.pool.n_kv_heads + head) * kPage + pos % kPage;
         return reinterpret_cast<uint32_t *>(a.pool.sketch + rec * (a.pool.sketch_bits >> 6));
     }
 };
 
-template <int D, typename T>
+template <int D, typename T, bool WIDE>
 __global__ __launch_bounds__(kThreads, 3) void append_keys_kernel(AppendArgs a, BatchDesc desc) {
     static_assert(kTile == kProjTile && kThreads == kProjThreads, "projection_mfma.h assumes this tile shape");
     const SeqDesc sd = desc.s[blockIdx.y];
     const int off8 = sd.pos & 7, L = (off8 + a.n_new + 7) & ~7, n_slots = L * a.pool.n_kv_heads;
-    const KeyRows rows{a, sd, L, off8, n_slots};
-    resident_sketch_tiles<D, T>(a.pool, static_cast<const T *>(a.k) + (size_t)blockIdx.y * a.stride_seq, rows, (long)blockIdx.x,
+    const KeyRows rows{a, sd, L, off8, n_slots, ProjDiv((uint32_t)L)};
+    resident_sketch_tiles<D, T, WIDE>(a.pool, static_cast<const T *>(a.k) + (size_t)blockIdx.y * a.stride_seq, rows, (long)blockIdx.x,
                                 (long)gridDim.x, (long)((n_slots + kTile - 1) / kTile), (int)blockIdx.z, (int)gridDim.z);
 }
 
@@ -546,7 +553,11 @@ hipError_t launch_append(const AppendArgs &a, const BatchDesc &desc, int n_seqs,
 #define H1BKV_LAUNCH_MF(DD, TT)                                                                                        \
     do {                                                                                                               \
         if (split) {                                                                                                   \
-            hipLaunchKernelGGL((append_keys_kernel<DD, TT>), grid_keys, dim3(kThreads), 0, st, a, desc);               \
+            /* 128 fp16 channels and whole groups of 128 sketch bits: the 32 x 32 form of the tile loop */            \
+            if (DD == 128 && sizeof(TT) == 2 && a.pool.sketch_bits % 128 == 0)                                         \
+                hipLaunchKernelGGL((append_keys_kernel<DD, TT, DD == 128 && sizeof(TT) == 2>), grid_keys, dim3(kThreads), 0, st, a, desc); \
+            else                                                                                                       \
+                hipLaunchKernelGGL((append_keys_kernel<DD, TT, false>), grid_keys, dim3(kThreads), 0, st, a, desc);    \
             if (a.pool.code_layout == 1)                                                                               \
                 hipLaunchKernelGGL((append_values_kernel<DD, TT>), grid, dim3(kThreads), 0, st, a, desc, (int)tile);   \
             else                                                                                                       \

@@ -628,19 +628,18 @@ __global__ __launch_bounds__(kThreads, 4) void sketch_rows_mfma_kernel(PrefillAr
 struct QueryRows {
     const PrefillArgs &a;
     long n_vec;
+    ProjDiv by_seq, by_heads;                           // (used when the vector index fits 32 bits)
     __device__ int rows_in(long tile) const { return (int)min((long)kSketchTile, n_vec - tile * kSketchTile); }
     __device__ size_t src(long tile, int rl) const {
         const long v = tile * kSketchTile + rl;
         const int Hq = a.pool.n_q_heads;
-        long s, rem;
-        if (n_vec <= 0x7FFFFFFFL) {                     // (uniform) 32-bit division: a fraction of the 64-bit one's instructions
-            const uint32_t per_seq = (uint32_t)a.n_q * (uint32_t)Hq;
-            s = (uint32_t)v / per_seq;
-            rem = (uint32_t)v % per_seq;
-        } else {
-            s = v / ((long)a.n_q * Hq);
-            rem = v % ((long)a.n_q * Hq);
+        if (n_vec <= 0x7FFFFFFFL) {                     // (uniform)
+            uint32_t s, rem, tok, head;
+            by_seq.divmod((uint32_t)v, s, rem);
+            by_heads.divmod(rem, tok, head);
+            return (size_t)s * a.stride_seq + (size_t)tok * a.stride_tok + (size_t)head * a.stride_head;
         }
+        const long s = v / ((long)a.n_q * Hq), rem = v % ((long)a.n_q * Hq);
         return (size_t)s * a.stride_seq + (size_t)((uint32_t)rem / (uint32_t)Hq) * a.stride_tok +
                (size_t)((uint32_t)rem % (uint32_t)Hq) * a.stride_head;
     }
@@ -650,11 +649,12 @@ struct QueryRows {
     }
 };
 
-template <int D, typename T>
+template <int D, typename T, bool WIDE>
 __global__ __launch_bounds__(kThreads, 3) void sketch_rows_resident_kernel(PrefillArgs a, int n_seqs) {
     const long n_vec = (long)n_seqs * a.n_q * a.pool.n_q_heads;
-    const QueryRows rows{a, n_vec};
-    resident_sketch_tiles<D, T>(a.pool, static_cast<const T *>(a.q), rows, (long)blockIdx.x, (long)gridDim.x,
+    const uint64_t per_seq = (uint64_t)a.n_q * (uint64_t)a.pool.n_q_heads;
+    const QueryRows rows{a, n_vec, ProjDiv(per_seq <= 0xFFFFFFFFull ? (uint32_t)per_seq : 1u), ProjDiv((uint32_t)a.pool.n_q_heads)};
+    resident_sketch_tiles<D, T, WIDE>(a.pool, static_cast<const T *>(a.q), rows, (long)blockIdx.x, (long)gridDim.x,
                                 (n_vec + kSketchTile - 1) / kSketchTile, (int)blockIdx.y, (int)gridDim.y);
 }
 
@@ -846,7 +846,9 @@ hipError_t launch_sketch_rows(const PrefillArgs &a, int n_seqs, hipStream_t st) 
         const dim3 res((unsigned)(tiles < res_x ? tiles : res_x), (unsigned)(parts > 0 ? parts : 1));
 #define H1BKV_LAUNCH_MF(DD, TT)                                                                                              \
     do {                                                                                                                     \
-        if (fits) hipLaunchKernelGGL((sketch_rows_resident_kernel<DD, TT>), res, dim3(kThreads), 0, st, a, n_seqs);          \
+        if (fits && DD == 128 && sizeof(TT) == 2 && a.pool.sketch_bits % 128 == 0)                                            \
+            hipLaunchKernelGGL((sketch_rows_resident_kernel<DD, TT, DD == 128 && sizeof(TT) == 2>), res, dim3(kThreads), 0, st, a, n_seqs); \
+        else if (fits) hipLaunchKernelGGL((sketch_rows_resident_kernel<DD, TT, false>), res, dim3(kThreads), 0, st, a, n_seqs); \
         else hipLaunchKernelGGL((sketch_rows_mfma_kernel<DD, TT>), fine, dim3(kThreads), 0, st, a, n_seqs);                  \
     } while (0)
         if (a.f16) {

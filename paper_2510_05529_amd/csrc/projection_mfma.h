@@ -19,7 +19,9 @@ namespace h1bkv {
 namespace {
 
 typedef _Float16 proj_f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 proj_f16x2 __attribute__((ext_vector_type(2)));
 typedef float proj_f32x4 __attribute__((ext_vector_type(4)));
+typedef float proj_f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int kProjTile = 64;      // vectors per tile
 constexpr int kProjThreads = 256;
@@ -246,6 +248,20 @@ __device__ __forceinline__ void project_tile_mfma(const PoolView &pv, const __ha
 
 constexpr size_t kProjNoRow = ~(size_t)0;
 
+// Division of a 32-bit index by a divisor that is fixed for the launch, for the Rows descriptions: the quotient from the
+// high half of a product with floor((2^32 - 1) / d), which falls short by at most two, corrected by comparing remainders.
+// (The generic division is some thirty-five vector instructions, and one wave of the workgroup does all of them.)
+struct ProjDiv {
+    uint32_t d, m;
+    __device__ explicit ProjDiv(uint32_t div) : d(div), m(0xFFFFFFFFu / div) {}
+    __device__ void divmod(uint32_t x, uint32_t &q, uint32_t &r) const {
+        q = __umulhi(x, m);
+        r = x - q * d;
+        if (r >= d) { r -= d; ++q; }
+        if (r >= d) { r -= d; ++q; }
+    }
+};
+
 // OR over the four 16-lane rows of a wave, in every lane: two row exchanges in the register file (v_permlane16_swap,
 // v_permlane32_swap: after exchanging rows between two copies of x, the OR of the copies joins two different rows at every
 // position), no trip through the LDS crossbar.
@@ -312,6 +328,40 @@ __device__ __forceinline__ void load_resident(const PoolView &pv, ProjResident<D
         }
         asm volatile("" : "+v"(res.g[i][0]), "+v"(res.g[i][1]), "+v"(res.g[i][2]), "+v"(res.g[i][3]));
     }
+}
+
+// The resident pieces of R for the 32 x 32 form (d = 128, fp16 vectors, 32 sketch bits per wave): the wave's 32 rows of R
+// are the MFMA's rows, the vectors its columns, so that a lane ends up with 16 bits of ONE vector.  Row i of the MFMA is
+// sketch bit 16 ((i >> 2) & 1) + 4 (i >> 3) + (i & 3) of the wave's 32: accumulator element e of lane (column n, half h)
+// is then bit 16 h + e -- the lane's 16 signs, shifted into a register one v_alignbit each, ARE half-word h of the
+// vector's sketch word, stored as they are (no nibble assembly, no exchange between lanes).  The guard test uses the
+// largest band factor of the wave's 32 bits: one threshold per vector, compared once against the smallest magnitude.
+struct ProjWide {
+    uint4 hi[8], mid[8];        // K steps of 16 channels
+    float gmax;
+};
+
+template <bool F32IN>
+__device__ __forceinline__ void load_wide(const PoolView &pv, ProjWide &res, int bit0) {
+    const int lane = threadIdx.x & 63, i = lane & 31, hh = lane >> 5;
+    const int bit = 16 * ((i >> 2) & 1) + 4 * (i >> 3) + (i & 3);
+    const size_t arow = (size_t)(bit0 + bit) * 128 + 8 * hh;
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+        res.hi[s] = *reinterpret_cast<const uint4 *>(pv.R16hi + arow + 16 * s);
+        res.mid[s] = *reinterpret_cast<const uint4 *>(pv.R16mid + arow + 16 * s);
+    }
+    float g = (F32IN ? pv.guard + pv.sketch_bits : pv.guard)[bit0 + i];
+#pragma unroll
+    for (int o = 16; o > 0; o >>= 1) g = fmaxf(g, __shfl_xor(g, o));
+    res.gmax = g;
+    // (waited for here, once: see load_resident)
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+        asm volatile("" : "+v"(res.hi[s].x), "+v"(res.hi[s].y), "+v"(res.hi[s].z), "+v"(res.hi[s].w));
+        asm volatile("" : "+v"(res.mid[s].x), "+v"(res.mid[s].y), "+v"(res.mid[s].z), "+v"(res.mid[s].w));
+    }
+    asm volatile("" : "+v"(res.gmax));
 }
 
 // One entry per stored 32-bit sketch word that holds bits inside the guard band.
@@ -428,10 +478,12 @@ __device__ __forceinline__ void proj_drain(const PoolView &pv, const ProjFixList
 }
 
 // part, n_parts: which part of the sketch bits this workgroup computes (see above).
-template <int D, typename T, typename Rows>
+// WIDE: the 32 x 32 form (ProjWide); needs d = 128, fp16 vectors and 32 sketch bits per wave (128 per workgroup).
+template <int D, typename T, bool WIDE, typename Rows>
 __device__ __forceinline__ void resident_sketch_tiles(const PoolView &pv, const T *base, const Rows &rows, long first, long step,
                                                       long n_tiles, int part, int n_parts) {
     constexpr bool F32 = sizeof(T) == 4;
+    static_assert(!WIDE || (D == 128 && !F32), "the 32 x 32 form is written for 128 fp16 channels");
     constexpr int STRIDE = D + 8, NJ = D / 32, NB = ProjResident<D>::NB;
     constexpr int NBUF = F32 ? 1 : 2;                       // (two piece tiles per fp32 tile: one buffer, one more barrier)
     constexpr int RPP = kProjThreads * 8 / D;               // rows covered by one 16-byte piece per thread
@@ -465,13 +517,9 @@ __device__ __forceinline__ void resident_sketch_tiles(const PoolView &pv, const 
     if constexpr (K * RPP < kProjTile) {                                                                    \
         const int rl = pre_row + K * RPP;                                                                   \
         *reinterpret_cast<uint4 *>(&xs[BUF][rl * STRIDE + pre_ch]) = REG;                                   \
-        const __half2 *h2 = reinterpret_cast<const __half2 *>(&REG);                                        \
+        const proj_f16x2 *h2 = reinterpret_cast<const proj_f16x2 *>(&REG);                                  \
         float ss = 0.0f;                                                                                    \
-        _Pragma("unroll") for (int e = 0; e < 4; ++e) {                                                     \
-            const float2 f = __half22float2(h2[e]);                                                         \
-            ss = fmaf(f.x, f.x, ss);                                                                        \
-            ss = fmaf(f.y, f.y, ss);                                                                        \
-        }                                                                                                   \
+        _Pragma("unroll") for (int e = 0; e < 4; ++e) ss = __builtin_amdgcn_fdot2(h2[e], h2[e], ss, false); \
         ss = proj_sum_lanes<D / 8>(ss);                                                                     \
         if (pre_ch == 0) band_s[BUF][rl] = sqrtf(ss) * 1.0000153f;                                          \
     }
@@ -484,8 +532,10 @@ __device__ __forceinline__ void resident_sketch_tiles(const PoolView &pv, const 
         if constexpr (!F32) H1BKV_PROJ_REQUEST(0);
     }
     // (after the first tile's requests: the two round trips overlap, which is most of a short launch's time)
-    ProjResident<D> res;
-    load_resident<D, F32>(pv, res, W, block0);
+    [[maybe_unused]] ProjResident<D> res;
+    [[maybe_unused]] ProjWide wres;
+    if constexpr (WIDE) load_wide<F32>(pv, wres, 16 * block0);
+    else load_resident<D, F32>(pv, res, W, block0);
     for (int it = 0;; t += step, ++it) {
         const bool more = t < n_tiles;
         if (!more || it % kProjDrainEvery == kProjDrainEvery - 1) {
@@ -522,6 +572,56 @@ __device__ __forceinline__ void resident_sketch_tiles(const PoolView &pv, const 
         }
         const __half *xt = &xs[buf][0];
         [[maybe_unused]] const __half *xmt = &xs[buf][F32 ? kProjTile * STRIDE : 0];
+        if constexpr (WIDE) {
+#pragma unroll 1
+            for (int vg = 0; vg < (n_here + 31) / 32; ++vg) {
+                const int v = 32 * vg + (lane & 31), hh = lane >> 5;
+                proj_f32x16 yh, ym;
+#pragma unroll
+                for (int e = 0; e < 16; ++e) yh[e] = ym[e] = 0.0f;
+#pragma unroll
+                for (int ks = 0; ks < 8; ++ks) {
+                    const proj_f16x8 Bx = *reinterpret_cast<const proj_f16x8 *>(xt + (size_t)v * STRIDE + 16 * ks + 8 * hh);
+                    yh = __builtin_amdgcn_mfma_f32_32x32x16_f16(*reinterpret_cast<const proj_f16x8 *>(&wres.hi[ks]), Bx, yh, 0, 0, 0);
+                    ym = __builtin_amdgcn_mfma_f32_32x32x16_f16(*reinterpret_cast<const proj_f16x8 *>(&wres.mid[ks]), Bx, ym, 0, 0, 0);
+                }
+                const float thr = wres.gmax * band_s[buf][v];
+                const size_t my_src = src_s[sb][v];
+                const bool live = my_src != kProjNoRow;
+                // element e of this lane: bit 16 block0 + 16 hh + e of vector v.  The sign is read off the float's bit
+                // pattern: -0.0 would come out wrong, but a zero lies inside every band and is recomputed.
+                float y[16];
+#pragma unroll
+                for (int e = 0; e < 16; ++e) y[e] = fmaf(ym[e], 0.000244140625f, yh[e]);
+                uint32_t neg = 0u;
+#pragma unroll
+                for (int e = 15; e >= 0; --e) neg = __builtin_amdgcn_alignbit(neg, __float_as_uint(y[e]), 31);   // (neg << 1) | sign
+                float worst = fminf(fabsf(y[0]), fabsf(y[1]));
+#pragma unroll
+                for (int e = 2; e < 16; e += 2) worst = fminf(fminf(worst, fabsf(y[e])), fabsf(y[e + 1]));
+                uint32_t bits16 = ~neg & 0xFFFFu;
+                uint32_t *out = live ? dst_s[it & 1][v] : nullptr;
+                const int word = block0 >> 1;                                  // the wave's 32 bits are this word of the sketch
+                if (__any(live && !(worst > thr))) {                           // uniform, rare; also catches a NaN
+                    uint32_t ub = 0u;
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) ub |= (fabsf(y[e]) > thr ? 0u : 1u) << e;
+                    if (live && ub) {
+                        const T *x = base + my_src;
+                        const uint32_t mask = ub << (16 * hh);
+                        const int slot = atomicAdd(&fixes.n, 1);
+                        if (slot < kProjFixCap) {
+                            fixes.item[slot] = ProjFix{x, out + word, mask, (uint32_t)word};
+                        } else {
+                            const uint32_t set = proj_chain_bits<D, T>(pv, 32 * word, mask, x);
+                            bits16 = (bits16 & ~ub) | ((set >> (16 * hh)) & ub);
+                        }
+                    }
+                }
+                // (a global address that came through LDS: see the note at the stores of the 16 x 16 form)
+                if (live) *((__attribute__((address_space(1))) uint16_t *)(out + word) + hh) = (uint16_t)bits16;
+            }
+        } else
 #pragma unroll 1
         for (int tb = 0; tb < (n_here + 15) / 16; ++tb) {
             const int v = 16 * tb + n;
