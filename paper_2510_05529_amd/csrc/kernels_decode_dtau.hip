@@ -32,8 +32,12 @@ __global__ void merge_dtau_kernel(DecodeArgs a, BatchDesc desc, int seq0, float 
         return;
     }
     int hmin = 1 << 20;
+#pragma unroll 8
     for (int s = 0; s < n; ++s) hmin = min(hmin, __float_as_int(a.part_ml[(part + s) * 4]));
     float l = 0.0f, lh = 0.0f, o = 0.0f, oh = 0.0f;
+    // (unrolled: the loads of several chunks are in flight together -- a long context has dozens of chunks, and one
+    // round trip per chunk was three times the plain merge's time)
+#pragma unroll 8
     for (int s = 0; s < n; ++s) {
         const float *ml = a.part_ml + (part + s) * 4;
         const int hm = __float_as_int(ml[0]);
