@@ -10,13 +10,17 @@
 //             one v_mfma_scale_f32_32x32x64_f8f6f4 per 64 sketch bits (unit scales) yields 32 x 32 distances at four
 //             times the fp16 rate -- instead of 4 W XOR/popcount instructions per pair on the vector ALUs.  The MFMA is
 //             issued as keys x queries, so that a lane ends up holding distances of ONE query row against 16 tokens:
-//             the slots it has in the next MFMA.  Its accumulator input is a per-lane constant 2^23 + 2 (popcount(q) -
-//             reference + slack): the low bits of the result ARE the byte offset of the pair's weight in a table.
+//             the slots it has in the next MFMA.  The block scales of the instruction are 2^-75 and 2^-74: every product
+//             is then +-2 units of the smallest fp32 denormal, and with the accumulator input a per-lane constant whose
+//             BIT PATTERN is (LDS address of the weight table) + 2 (popcount(q) - reference + slack), the bit pattern
+//             of the result IS the LDS address of the pair's weight (the matrix cores keep denormal inputs and results
+//             exact; measured).
 //   weights   p = exp((alpha - alpha_ref)/tau) takes only a few hundred values (the distance from the row's reference
 //             distance is an integer): one 16-bit LDS table read per pair, straight into one half of an operand
-//             register -- no exponential, no conversion.  The reference is a running minimum with slack: it is
-//             renewed, and the accumulators rescaled, only when a distance falls further below it than the fp16 range
-//             of the weights allows.  The normalisation uses the sums of the SAME fp16 weights (two per v_dot2).
+//             register -- no exponential, no conversion, no address arithmetic.  The reference is a running minimum
+//             with slack: it is renewed, and the accumulators rescaled, only when a distance falls further below it
+//             than the fp16 range of the weights allows (its address then lies in front of the table).
+//             The normalisation uses the sums of the SAME fp16 weights (two per v_dot2).
 //   values    sum_t p[i][t] v^[t][c]  with v_mfma_f32_32x32x16_f16, fp32 accumulate.
 // One workgroup (4 waves) takes 128 consecutive query positions of one (sequence, query head) -- 32 rows per wave --
 // and walks the key tokens in tiles of 64 up to its diagonal.  Per tile the workgroup stages ONCE, for all its rows: the
@@ -47,7 +51,8 @@ constexpr int kCS = 8;                        // channels per staging item of th
 constexpr int kTK = 64;                       // key tokens per tile
 constexpr float kPScaleLog2 = 4.0f;           // weights are stored as p * 2^4
 constexpr float kPSlackLog2 = 11.0f;          // and may exceed 1 by up to 2^11 (p 2^4 <= 2^15 stays finite in fp16)
-constexpr int kUnitScale = 0x7F7F7F7F;        // E8M0 block scales of the fp4 MFMA: 2^0
+constexpr int kScaleA = 0x34343434;           // E8M0 block scales of the fp4 MFMA: 2^-75 ...
+constexpr int kScaleB = 0x35353535;           // ... and 2^-74: a product of fp4 0.5 and +-4 is +-2 x 2^-149
 
 union HalfOperand {
     uint32_t u[4];
@@ -100,7 +105,10 @@ __global__ __launch_bounds__(WAVES * 64, 8 / WAVES) void prefill_kernel(PrefillA
     // is only renewed (accumulators rescaled) when a distance falls more than S below it, S the largest slack whose
     // weights still fit fp16 (exp(2 S / (b tau)) <= 2^11): the best distance of a row improves by a few units many
     // times over a long context, and rescaling on each of them was a tenth of the vector work.
-    __shared__ _Float16 ptab[128 * W + 4];
+    // In front of them sit 64 W unused entries: addresses of distances further below the reference than the slack allows
+    // (never read: the reference is renewed first) then stay non-negative wherever the table lies in LDS.
+    constexpr int kGuard = 64 * W;
+    __shared__ _Float16 ptab[192 * W + 4];
     // The sequence's page ids, read once: a block-table lookup per tile from global memory sits, with its full memory
     // latency, in front of every tile's loads.
     constexpr int kPagesLds = 1024;
@@ -157,16 +165,20 @@ __global__ __launch_bounds__(WAVES * 64, 8 / WAVES) void prefill_kernel(PrefillA
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[cb][v] = 0.0f;
     float lsum = 0.0f;            // this lane's share (16 of every 32 tokens) of the row's weight sum
-    int ref = 1 << 20;            // the row's reference distance (in distance units)
+    int ref = 64 * W;             // the row's reference distance (in distance units); the largest distance there is to begin with
     const int S = (int)fminf(kPSlackLog2 / a.exp2_scale, (float)(64 * W));
-    for (int e = threadIdx.x; e < 64 * W + S + 2; e += kPfThreads)
-        ptab[e] = e <= 64 * W + S ? (_Float16)__builtin_amdgcn_exp2f(fmaf(-a.exp2_scale, (float)(e - S), kPScaleLog2)) : (_Float16)0.0f;
-    const float kMagic = 8388608.0f;                                  // 2^23: integers up to 2^23 sit in the low mantissa bits
-    const float off_zero = kMagic + (float)(2 * (64 * W + S + 1));    // the table's zero entry
-    // accumulator input of the score MFMA: result = 2^23 + 2 (ham - ref + S) = 2^23 + byte offset of the pair's weight
+    for (int e = threadIdx.x; e < kGuard + 64 * W + S + 2; e += kPfThreads) {
+        const int d = e - kGuard;                                     // distance - reference + S
+        ptab[e] = d < 0 ? (_Float16)__builtin_inff()
+                        : d <= 64 * W + S ? (_Float16)__builtin_amdgcn_exp2f(fmaf(-a.exp2_scale, (float)(d - S), kPScaleLog2)) : (_Float16)0.0f;
+    }
+    // LDS byte address of the entry for distance - reference + S = 0: what the score MFMA's results are counted from
+    const uint32_t tab0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) _Float16 *)ptab + 2u * kGuard;
+    const float off_zero = __uint_as_float(tab0 + 2u * (64 * W + S + 1));    // the table's zero entry
+    // accumulator input of the score MFMA: bits(result) = tab0 + 2 (ham - ref + S) = LDS address of the pair's weight
     f32x16 c0;
     auto set_c0 = [&]() {
-        const float v0 = kMagic + (float)(2 * (pcq - ref + S));
+        const float v0 = __uint_as_float(tab0 + (uint32_t)(2 * (pcq - ref + S)));
 #pragma unroll
         for (int v = 0; v < 16; ++v) c0[v] = v0;
     };
@@ -371,7 +383,6 @@ __global__ __launch_bounds__(WAVES * 64, 8 / WAVES) void prefill_kernel(PrefillA
         constexpr bool kMasked = decltype(masked_tag)::value;
         const unsigned char *ks = k_s[buf];
         const unsigned char *vs = v_s[buf];
-        const unsigned char *tab = reinterpret_cast<const unsigned char *>(ptab);
         // byte offsets of the weights of step st: lane (row i, g) receives tokens 8 a + 4 g + j of the step as element 4 a + j
         auto scores = [&](int st) {
             f32x16 off;
@@ -382,7 +393,7 @@ __global__ __launch_bounds__(WAVES * 64, 8 / WAVES) void prefill_kernel(PrefillA
                 const uint4 kk = *reinterpret_cast<const uint4 *>(ks + (32 * st + i) * KS + (2 * w + g) * 16);
                 K.u[0] = kk.x; K.u[1] = kk.y; K.u[2] = kk.z; K.u[3] = kk.w;
                 K.u[4] = K.u[5] = K.u[6] = K.u[7] = 0u;
-                off = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(K.v, qop[w].v, w == 0 ? c0 : off, 4, 4, 0, kUnitScale, 0, kUnitScale);
+                off = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(K.v, qop[w].v, w == 0 ? c0 : off, 4, 4, 0, kScaleA, 0, kScaleB);
             }
             return off;
         };
@@ -392,23 +403,28 @@ __global__ __launch_bounds__(WAVES * 64, 8 / WAVES) void prefill_kernel(PrefillA
             for (int v = 0; v < 16; ++v)
                 if (8 * (v >> 2) + (v & 3) > lim) off[v] = off_zero;
         };
-        auto row_min = [&](const f32x16 &off) {                    // smallest offset of the row in this step
-            float mn = fminf(fminf(off[0], off[1]), off[2]);
+        auto row_min = [&](const f32x16 &off) {                    // smallest table address of the row in this step
+            uint32_t mn = min(min(__float_as_uint(off[0]), __float_as_uint(off[1])), __float_as_uint(off[2]));
 #pragma unroll
-            for (int v = 3; v < 15; v += 2) mn = fminf(fminf(mn, off[v]), off[v + 1]);
-            return xor32_min(fminf(mn, off[15]));                  // over the row's two lane groups
+            for (int v = 3; v < 15; v += 2) mn = min(min(mn, __float_as_uint(off[v])), __float_as_uint(off[v + 1]));
+            mn = min(mn, __float_as_uint(off[15]));
+            const auto r2 = __builtin_amdgcn_permlane32_swap(mn, mn, false, false);    // over the row's two lane groups
+            return min(r2[0], r2[1]);
         };
-        // rare: some row's best distance left the slack.  The step's smallest distance becomes the row's reference:
-        // every offset of the row grows by 2 delta, what has been accumulated shrinks by exp(-2 delta / (b tau)).
-        auto renew = [&](f32x16 &off, float mn) {
-            const int delta = mn < kMagic ? S - (((int)(mn - kMagic)) >> 1) : 0;      // old reference - new one (> S)
-            const float f = __builtin_amdgcn_exp2f(-a.exp2_scale * (float)delta);     // 0 while nothing was accumulated
+        // rare: some row's best distance left the slack (its table address lies in front of the table).  The step's smallest distance becomes
+        // the row's reference: every address of the row grows by 2 delta, what has been accumulated shrinks by
+        // exp(-2 delta / (b tau)).  Rows whose distances are all inside the slack keep their reference (delta = 0).
+        auto renew = [&](f32x16 &off, uint32_t mn) {
+            const int idx = ((int)mn - (int)tab0) >> 1;                               // smallest distance - reference + S
+            const int delta = idx < 0 ? S - idx : 0;                                  // old reference - new one (> S)
+            const float f = __builtin_amdgcn_exp2f(-a.exp2_scale * (float)delta);
             ref -= delta;
             set_c0();
             lsum *= f;
 #pragma unroll
             for (int v = 0; v < 16; ++v)
-                if (!kMasked || off[v] != off_zero) off[v] += (float)(2 * delta);
+                if (!kMasked || __float_as_uint(off[v]) != __float_as_uint(off_zero))
+                    off[v] = __uint_as_float(__float_as_uint(off[v]) + (uint32_t)(2 * delta));
             // accumulator element 4 a + j of lane (n, g) belongs to row 8 a + 4 g + j, whose factor lane 8 a + 4 g + j holds
             float fr[16];
 #pragma unroll
@@ -418,10 +434,11 @@ __global__ __launch_bounds__(WAVES * 64, 8 / WAVES) void prefill_kernel(PrefillA
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc[cb][v] *= fr[v];
         };
-        // Weights from the table: the low 16 bits of 2^23 + offset are the offset.
+        // Weights from the table: the result's bit pattern is the entry's LDS address.
         auto table = [&](const f32x16 &off, _Float16 *pw) {
 #pragma unroll
-            for (int v = 0; v < 16; ++v) pw[v] = *reinterpret_cast<const _Float16 *>(tab + (__float_as_uint(off[v]) & 0xFFFFu));
+            for (int v = 0; v < 16; ++v)
+                pw[v] = *(__attribute__((address_space(3))) const _Float16 *)(uintptr_t)__float_as_uint(off[v]);
         };
         auto pack = [&](const _Float16 *pw, HalfOperand *A) {
 #pragma unroll
@@ -458,8 +475,8 @@ __global__ __launch_bounds__(WAVES * 64, 8 / WAVES) void prefill_kernel(PrefillA
         f32x16 off0 = scores(0);
         if (kMasked) mask_step(off0, 0);
         {
-            const float mn = row_min(off0);
-            if (__any(mn < kMagic)) renew(off0, mn);
+            const uint32_t mn = row_min(off0);
+            if (__any(mn < tab0)) renew(off0, mn);
         }
         _Float16 pw0[16], pw1[16];
         table(off0, pw0);
@@ -467,10 +484,10 @@ __global__ __launch_bounds__(WAVES * 64, 8 / WAVES) void prefill_kernel(PrefillA
         HalfOperand A0[2], A1[2];
         pack(pw0, A0);
         if (kMasked) mask_step(off1, 1);
-        const float mn1 = row_min(off1);
+        const uint32_t mn1 = row_min(off1);
         table(off1, pw1);
         values(A0, 0);
-        if (__any(mn1 < kMagic)) {
+        if (__any(mn1 < tab0)) {
             renew(off1, mn1);
             table(off1, pw1);
         }
@@ -525,7 +542,8 @@ __global__ __launch_bounds__(WAVES * 64, 8 / WAVES) void prefill_kernel(PrefillA
             for (int cb = 0; cb < NCB; ++cb) dst[D * half + 32 * cb + i] = acc[cb][v];
             if (i == 0 && half == 0) {
                 dst[DTOT] = l;
-                dst[DTOT + 1] = __int_as_float(4 * rref);     // the merge kernel counts references in quarter units
+                // the merge kernel counts references in quarter units; a split that saw no token of the row says so
+                dst[DTOT + 1] = __int_as_float(l > 0.0f ? 4 * rref : 1 << 22);
             }
         }
     }
