@@ -113,8 +113,10 @@ constexpr int kPrefillMaxSplits = 16;
 // Most context splits a prefill call of n_seqs x n_q query positions can use: enough workgroups to fill the chip when
 // the chunk is short (a long prompt alone already brings thousands of workgroups: one split).
 inline int prefill_max_splits(int n_q_heads, int n_seqs, int n_q) {
-    const int64_t wgs = (int64_t)n_q_heads * n_seqs * ((n_q + prefill_rows(n_q) - 1) / prefill_rows(n_q));
-    const int64_t s = (1024 + wgs - 1) / wgs;
+    const int rows = prefill_rows(n_q);
+    const int64_t wgs = (int64_t)n_q_heads * n_seqs * ((n_q + rows - 1) / rows);
+    const int64_t fill = rows == 256 ? 512 : 1024;      // four rounds of the workgroups a chip holds at once (256 x 1 or 2)
+    const int64_t s = (fill + wgs - 1) / wgs;
     return (int)(s < 1 ? 1 : s > kPrefillMaxSplits ? kPrefillMaxSplits : s);
 }
 
