@@ -309,9 +309,15 @@ int choose_chunk(const h1bkv_cache *c, int n_seqs, int max_ctx) {
     // Small problems: a workgroup's fixed cost (prologue, four-wave epilogue, partial results) is that of two or three
     // pages of streaming, so below 1024-token chunks only a quarter of the target (at least 1024) is insisted on (measured at 8 x 32
     // heads x 4096 tokens: 25.8 us with one page per workgroup, 21.2 us with four).
+    // Tiny problems (at most 1024 (head, page) units in all: one sequence of a 7B-shaped model at 8k tokens) cannot give
+    // every compute unit four workgroups of several pages; there one workgroup per compute unit with up to four pages
+    // is best (measured at 1 x 32 heads x 8192 tokens, records from HBM: 12.4 us with one page per workgroup, 11.7 with
+    // two, 11.2 with four, 13.9 with eight).
+    const bool tiny = heads * ((max_ctx + kPage - 1) / kPage) <= 1024;
     while (chunk > kPage) {
         const int64_t wgs = heads * ((max_ctx + chunk - 1) / chunk);
         if (wgs >= target_wgs || (chunk <= 1024 && wgs >= std::max<int64_t>(target_wgs / 4, 1024))) break;
+        if (tiny && chunk <= 1024 && wgs >= 256) break;
         chunk /= 2;
     }
     return chunk;
