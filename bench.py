@@ -320,15 +320,17 @@ def measure_read_ceiling(torch, B, stream):
 
 def bench_per_token(args, torch, B, wl, w, workers):
     """Secondary line: what one generated token costs in attention over L layers.  Every layer owns a cache with the
-    workload's context and runs one fused decode step (append the token's K/V, attend), launched eagerly: that is the
-    per-token figure.  Token positions and page assignments travel in the kernel arguments, so a HIP graph captured around
-    the L steps is frozen at the position it was captured at; replaying it (reported next to the figure) re-does the same
-    token and only shows what the launches cost.  (All layers reuse the workload's synthetic tensors: the values do
-    not matter here.)"""
+    workload's context and runs one fused decode step (append the token's K/V, attend).  Three ways of launching it:
+    eagerly through h1bkv_decode_step (positions in the kernel arguments: the figure reported as `value`); as one HIP
+    graph of the L steps of h1bkv_decode_step_dev, whose kernels read the sequence lengths from device memory, so that
+    every replay generates the NEXT token (the context grows from T by one token per replay); and, for comparison, a graph
+    of the eager step, which is frozen at the position it was captured at and only re-does the same token.  (All layers
+    reuse the workload's synthetic tensors: the values do not matter here.)"""
     L, T, Bsz = args.per_token_layers, w.context, w.batch
     tau = w.default_tau()
     R = wl.projection(w.sketch_bits, w.head_dim)
-    pages_per_seq = (T + 255) // 256 + 1
+    n_grow = max(1, args.warmup) + args.steps                  # tokens the advancing graph generates
+    pages_per_seq = (T + n_grow + 255) // 256 + 1
     seqs = list(range(Bsz))
     k_all = torch.from_numpy(wl.kv_slab(w, "k", seqs, 0, T, workers)).cuda()
     v_all = torch.from_numpy(wl.kv_slab(w, "v", seqs, 0, T, workers)).cuda()
@@ -369,6 +371,32 @@ def bench_per_token(args, torch, B, wl, w, workers):
         g.replay()
     torch.cuda.synchronize()
     graph_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    del g
+    # the advancing graph: lengths on the device, pages reserved for every token it will generate
+    max_pos = T - 1 + n_grow
+    pos = []
+    for c in caches:
+        for s in seqs:
+            B.check(B.h1bkv_truncate_seq(c.h, s, T - 1))
+            B.check(B.h1bkv_reserve_seq(c.h, s, n_grow))
+        pos.append(torch.full((Bsz,), T - 1, dtype=torch.int32, device="cuda"))
+    ws_dev_bytes = B.h1bkv_decode_workspace_bytes(caches[0].h, Bsz, max_pos)
+    ws_dev = torch.empty(ws_dev_bytes, dtype=torch.uint8, device="cuda")
+    torch.cuda.synchronize()
+    g2 = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g2):
+        for c, p in zip(caches, pos):
+            B.check(B.h1bkv_decode_step_dev(c.h, seqs, k1, v1, k1.stride(0), k1.stride(1), q, tau, out, p, max_pos, ws_dev,
+                                            ws_dev_bytes, None))
+    for _ in range(max(1, args.warmup)):
+        g2.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        g2.replay()
+    torch.cuda.synchronize()
+    adv_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    assert all(int(p.min()) == max_pos for p in pos), "every replay must have generated one token per sequence and layer"
     print(json.dumps({
         "metric": "per_token_attention_latency_ms", "value": eager_ms, "unit": "ms/token", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": eager_ms, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
@@ -376,6 +404,9 @@ def bench_per_token(args, torch, B, wl, w, workers):
         "config": {"workload": w.name, "layers": L, "batch": Bsz, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
                    "head_dim": w.head_dim, "context": T, "sketch_bits": w.sketch_bits, "group_size": w.group_size,
                    "launch": f"{L} fused decode steps (3 kernels each), launched eagerly"},
+        "graph_replay_advancing_ms": adv_ms,
+        "graph_replay_advancing": f"one HIP graph of {L} steps with device-resident positions, replayed once per generated "
+                                  f"token; the context grows from {T} to {max_pos} tokens over the replays",
         "graph_replay_of_one_position_ms": graph_ms,
         "context_only": "the paper's Table III reports 40 ms (Raspberry Pi 5) and 21 ms (Jetson Nano) per token for the WHOLE "
                         "7B model at an 8k context; this line is the attention over the compressed cache alone"}))

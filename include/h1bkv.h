@@ -174,11 +174,41 @@ int h1bkv_decode_attn_static(h1bkv_cache *c, const int32_t *seq_ids_host, int32_
  * Under HIP graph capture: token positions, context lengths and page assignments travel in the kernel arguments, so a
  * captured step is frozen at the position it was captured at -- replaying it rewrites the same slot and attends over
  * the same length, and the host bookkeeping advanced once, at capture.  A graph is therefore valid for one position
- * (re-capture per token, or launch eagerly).
+ * (re-capture per token, launch eagerly, or use h1bkv_decode_step_dev below).
  */
 int h1bkv_decode_step(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n_seqs, const void *k_dev,
                       const void *v_dev, int64_t stride_seq, int64_t stride_head, const void *q_dev, float tau,
                       float *out_dev, void *workspace_dev, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * The decode step with device-resident positions, for callers that replay one captured step token after token
+ * (Sec. IV: the same append-then-attend step; only where the lengths live differs).
+ *   h1bkv_reserve_seq     assigns pages for the next n_tokens positions of a sequence now (block table updated in stream
+ *                         order); its length does not change.  H1BKV_ENOSPACE if the pool or the per-sequence page limit
+ *                         cannot hold them; nothing changes then.  h1bkv_truncate_seq / h1bkv_reset_seq give reserved
+ *                         pages beyond the new length back.  h1bkv_reserved_tokens: positions that have a page.
+ *   h1bkv_decode_step_dev as h1bkv_decode_step, but the number of tokens sequence seq_ids_host[i] holds is read by the
+ *                         kernels from pos_dev[i] (int32, device memory, 4-byte aligned) when they run: the new token is
+ *                         written at position pos_dev[i], the query attends over pos_dev[i] + 1 tokens, and the step's
+ *                         last kernel adds one to pos_dev[i].  No kernel touches a position >= max_pos: every sequence
+ *                         must have pages for max_pos tokens (H1BKV_ERANGE otherwise), launches and workspace
+ *                         (>= h1bkv_decode_workspace_bytes(c, n_seqs, max_pos)) are sized for max_pos, and a sequence
+ *                         that has reached max_pos is left as it is (no append, attention over its max_pos tokens, no
+ *                         advance).  The host's lengths are NOT changed: captured in a HIP graph, the step can be replayed
+ *                         max_pos - pos times, each replay one token further.  The caller writes the initial lengths
+ *                         into pos_dev (h1bkv_seq_len) before the first step and must not run other calls on these
+ *                         sequences in between.
+ *   h1bkv_set_seq_len     tells the host bookkeeping the length the device has reached (>= the current length, within
+ *                         the reserved pages; H1BKV_ERANGE otherwise), after which every other call sees the grown
+ *                         sequence.
+ */
+int h1bkv_reserve_seq(h1bkv_cache *c, int32_t seq_id, int32_t n_tokens, void *hip_stream);
+int h1bkv_reserved_tokens(const h1bkv_cache *c, int32_t seq_id, int32_t *n_out);
+int h1bkv_decode_step_dev(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n_seqs, const void *k_dev,
+                          const void *v_dev, int64_t stride_seq, int64_t stride_head, const void *q_dev, float tau,
+                          float *out_dev, int32_t *pos_dev, int32_t max_pos, void *workspace_dev,
+                          size_t workspace_bytes, void *hip_stream);
+int h1bkv_set_seq_len(h1bkv_cache *c, int32_t seq_id, int32_t new_len);
 
 /*
  * Decode-step attention together with its derivative with respect to the temperature (Sec. IV-C: tau is the scalar the

@@ -44,7 +44,8 @@ Layout make_layout(const h1bkv_config &c) {
     L.off_R16hi = o;   o = align_up(o + b * d * sizeof(uint16_t));
     L.off_R16mid = o;  o = align_up(o + b * d * sizeof(uint16_t));
     L.off_guard = o;   o = align_up(o + 2 * b * sizeof(float));
-    L.off_bt = o;      o = align_up(o + (size_t)c.max_seqs * c.max_pages_per_seq * sizeof(int32_t));
+    // (64 more words behind the block table: the first is the merge kernels' arrival counter)
+    L.off_bt = o;      o = align_up(o + ((size_t)c.max_seqs * c.max_pages_per_seq + 64) * sizeof(int32_t));
     L.off_sketch = o;  o = align_up(o + rec * W * 8);
     const bool f16v = c.value_bits == 16;
     L.off_codes = o;   o = align_up(o + rec * (f16v ? 2 * d : d / 2));
@@ -151,6 +152,13 @@ unsigned char *scratch_for_device(int dev) {
     return scratch_ptr[dev];
 }
 
+// Device-resident sequence positions of h1bkv_decode_step_dev: pos[i] tokens are cached for the call's i-th sequence,
+// and no kernel works beyond max_pos.
+struct DevicePositions {
+    const int32_t *pos;
+    int32_t max_pos;
+};
+
 struct EventPair {
     hipEvent_t a, b;
 };
@@ -189,6 +197,7 @@ struct h1bkv_cache {
             v.R16mid = reinterpret_cast<const uint16_t *>(pool + lay.off_R16mid);
             v.guard = reinterpret_cast<const float *>(pool + lay.off_guard);
             v.block_table = reinterpret_cast<int32_t *>(pool + lay.off_bt);
+            v.ticket = reinterpret_cast<uint32_t *>(v.block_table + (size_t)cfg.max_seqs * cfg.max_pages_per_seq);
             v.sketch = reinterpret_cast<uint64_t *>(pool + lay.off_sketch);
             v.codes = reinterpret_cast<uint8_t *>(pool + lay.off_codes);
             v.meta = reinterpret_cast<uint32_t *>(pool + lay.off_meta);
@@ -251,7 +260,7 @@ int pages_for(int32_t len) { return (len + kPage - 1) / kPage; }
 // Pages that must be newly taken so that seq can hold new_len tokens, or a negative error.
 int pages_needed(const h1bkv_cache *c, int32_t seq, int64_t new_len) {
     if (new_len > (int64_t)c->cfg.max_pages_per_seq * kPage) return H1BKV_ENOSPACE;
-    return pages_for((int32_t)new_len) - (int)c->seq_pages[seq].size();
+    return std::max(0, pages_for((int32_t)new_len) - (int)c->seq_pages[seq].size());   // (reserved pages may already cover it)
 }
 
 // Take pages for seq up to new_len and queue the block-table updates.
@@ -309,11 +318,11 @@ int choose_chunk(const h1bkv_cache *c, int n_seqs, int max_ctx) {
     // Small problems: a workgroup's fixed cost (prologue, four-wave epilogue, partial results) is that of two or three
     // pages of streaming, so below 1024-token chunks only a quarter of the target (at least 1024) is insisted on (measured at 8 x 32
     // heads x 4096 tokens: 25.8 us with one page per workgroup, 21.2 us with four).
-    // Tiny problems (at most 1024 (head, page) units in all: one sequence of a 7B-shaped model at 8k tokens) cannot give
+    // Tiny problems (up to 1280 (head, page) units in all: one sequence of a 7B-shaped model at 8k-10k tokens) cannot give
     // every compute unit four workgroups of several pages; there one workgroup per compute unit with up to four pages
     // is best (measured at 1 x 32 heads x 8192 tokens, records from HBM: 12.4 us with one page per workgroup, 11.7 with
     // two, 11.2 with four, 13.9 with eight).
-    const bool tiny = heads * ((max_ctx + kPage - 1) / kPage) <= 1024;
+    const bool tiny = heads * ((max_ctx + kPage - 1) / kPage) <= 1280;
     while (chunk > kPage) {
         const int64_t wgs = heads * ((max_ctx + chunk - 1) / chunk);
         if (wgs >= target_wgs || (chunk <= 1024 && wgs >= std::max<int64_t>(target_wgs / 4, 1024))) break;
@@ -410,7 +419,7 @@ int h1bkv_create(const h1bkv_config *cfg, void *pool_dev, size_t pool_bytes, con
         ok = ok && hipMemcpy(c->pool + lay.off_R16hi, hi.data(), nR * sizeof(uint16_t), hipMemcpyHostToDevice) == hipSuccess;
         ok = ok && hipMemcpy(c->pool + lay.off_R16mid, mid.data(), nR * sizeof(uint16_t), hipMemcpyHostToDevice) == hipSuccess;
         ok = ok && hipMemcpy(c->pool + lay.off_guard, guard.data(), guard.size() * sizeof(float), hipMemcpyHostToDevice) == hipSuccess;
-        ok = ok && hipMemset(c->pool + lay.off_bt, 0, (size_t)cfg->max_seqs * cfg->max_pages_per_seq * sizeof(int32_t)) == hipSuccess;
+        ok = ok && hipMemset(c->pool + lay.off_bt, 0, ((size_t)cfg->max_seqs * cfg->max_pages_per_seq + 64) * sizeof(int32_t)) == hipSuccess;
         ok = ok && hipDeviceSynchronize() == hipSuccess;
         if (!ok) {
             delete c;
@@ -530,12 +539,15 @@ static int validate_append(const h1bkv_cache *c, const int32_t *seq_ids_host, in
 
 // Takes pages, publishes them and launches the append kernel(s).  With q_dev != nullptr each launch also sketches
 // the queries of its sequences into q_sketch_dev (fused decode-step prologue).  Arguments are already validated.
+// With dev != nullptr the positions are device-resident (h1bkv_decode_step_dev): the pages were reserved beforehand, the
+// kernels read where each sequence ends, and the host's lengths do not change.
 static int enqueue_append(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n_seqs, int32_t n_new, const void *k_dev,
                           const void *v_dev, int64_t stride_seq, int64_t stride_tok, int64_t stride_head, const void *q_dev,
-                          uint64_t *q_sketch_dev, hipStream_t st) {
+                          uint64_t *q_sketch_dev, hipStream_t st, const DevicePositions *dev = nullptr) {
     const int elt = c->cfg.in_dtype == H1BKV_F16 ? 2 : 4;
     std::vector<int32_t> ui, up;
-    for (int i = 0; i < n_seqs; ++i) take_pages(c, seq_ids_host[i], c->seq_len[seq_ids_host[i]] + n_new, ui, up);
+    if (!dev)
+        for (int i = 0; i < n_seqs; ++i) take_pages(c, seq_ids_host[i], c->seq_len[seq_ids_host[i]] + n_new, ui, up);
     int rc = publish(c, ui, up, st);
     if (rc == H1BKV_OK) {
         AppendArgs a{};
@@ -551,7 +563,12 @@ static int enqueue_append(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n
         for (int s0 = 0; s0 < n_seqs && rc == H1BKV_OK; s0 += kMaxSeqsPerLaunch) {
             const int n = std::min(kMaxSeqsPerLaunch, n_seqs - s0);
             BatchDesc desc;
-            for (int i = 0; i < n; ++i) desc.s[i] = SeqDesc{seq_ids_host[s0 + i], c->seq_len[seq_ids_host[s0 + i]]};
+            for (int i = 0; i < n; ++i) desc.s[i] = SeqDesc{seq_ids_host[s0 + i], dev ? 0 : c->seq_len[seq_ids_host[s0 + i]]};
+            if (dev) {
+                desc.pos_dev = dev->pos + s0;
+                desc.pos_add = 0;
+                desc.pos_max = dev->max_pos;
+            }
             if (!c->dry) {
                 a.k = static_cast<const char *>(k_dev) + (size_t)s0 * stride_seq * elt;
                 a.v = static_cast<const char *>(v_dev) + (size_t)s0 * stride_seq * elt;
@@ -572,11 +589,14 @@ static int enqueue_append(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n
         }
     }
     if (rc != H1BKV_OK) {
-        // A launch failed: give the pages taken above back, so the bookkeeping is as it was before the call.
-        for (int i = 0; i < n_seqs; ++i) h1bkv_truncate_seq(c, seq_ids_host[i], c->seq_len[seq_ids_host[i]]);
+        // A launch failed: give the pages taken above back, so the bookkeeping is as it was before the call (with
+        // device-resident positions none were taken, and the reserved ones stay).
+        if (!dev)
+            for (int i = 0; i < n_seqs; ++i) h1bkv_truncate_seq(c, seq_ids_host[i], c->seq_len[seq_ids_host[i]]);
         return rc;
     }
-    for (int i = 0; i < n_seqs; ++i) c->seq_len[seq_ids_host[i]] += n_new;
+    if (!dev)
+        for (int i = 0; i < n_seqs; ++i) c->seq_len[seq_ids_host[i]] += n_new;
     return H1BKV_OK;
 }
 
@@ -632,10 +652,14 @@ static int validate_decode(const h1bkv_cache *c, const int32_t *seq_ids_host, in
 }
 
 // Launches (query sketch,) split decode and merge for validated arguments.
+// With dev != nullptr the context lengths are device-resident: every sequence attends over pos[i] + 1 tokens (the token the
+// step's prologue has just appended included), and the launch is sized for max_pos tokens.
 static int enqueue_decode(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n_seqs, const void *q_dev, float tau,
-                          float *out_dev, void *workspace_dev, bool sketches_done, hipStream_t st) {
-    int max_ctx = 0;
-    for (int i = 0; i < n_seqs; ++i) max_ctx = std::max(max_ctx, c->seq_len[seq_ids_host[i]]);
+                          float *out_dev, void *workspace_dev, bool sketches_done, hipStream_t st,
+                          const DevicePositions *dev = nullptr) {
+    int max_ctx = dev ? dev->max_pos : 0;
+    if (!dev)
+        for (int i = 0; i < n_seqs; ++i) max_ctx = std::max(max_ctx, c->seq_len[seq_ids_host[i]]);
     const int chunk = choose_chunk(c, n_seqs, max_ctx);
     const int S = std::max(1, (max_ctx + chunk - 1) / chunk);
     const size_t heads = (size_t)n_seqs * c->cfg.n_q_heads;
@@ -657,7 +681,13 @@ static int enqueue_decode(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n
     for (int s0 = 0; s0 < n_seqs; s0 += kMaxSeqsPerLaunch) {
         const int n = std::min(kMaxSeqsPerLaunch, n_seqs - s0);
         BatchDesc desc;
-        for (int i = 0; i < n; ++i) desc.s[i] = SeqDesc{seq_ids_host[s0 + i], c->seq_len[seq_ids_host[s0 + i]]};
+        for (int i = 0; i < n; ++i) desc.s[i] = SeqDesc{seq_ids_host[s0 + i], dev ? 0 : c->seq_len[seq_ids_host[s0 + i]]};
+        if (dev) {
+            desc.pos_dev = dev->pos + s0;
+            desc.pos_add = 1;
+            desc.pos_max = dev->max_pos;
+            desc.advance = 1;                 // (read by the merge kernels only)
+        }
         if (!sketches_done) {
             Timed t(c, H1BKV_K_QSKETCH, st);
             // Thousands of fp16 queries (large batches): the prefill path's matrix-core projection with its guard band
@@ -736,6 +766,72 @@ int h1bkv_decode_step(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n_seq
         for (int i = 0; i < n_seqs; ++i) h1bkv_truncate_seq(c, seq_ids_host[i], c->seq_len[seq_ids_host[i]] - 1);
     }
     return rc;
+}
+
+int h1bkv_reserve_seq(h1bkv_cache *c, int32_t seq_id, int32_t n_tokens, void *hip_stream) {
+    if (!c) return H1BKV_ENULL;
+    if (seq_id < 0 || seq_id >= c->cfg.max_seqs) return H1BKV_ERANGE;
+    if (n_tokens < 0) return H1BKV_EINVAL;
+    const int64_t upto = (int64_t)c->seq_len[seq_id] + n_tokens;
+    const int need = pages_needed(c, seq_id, upto);
+    if (need < 0) return need;
+    if (need > (int)c->free_list.size()) return H1BKV_ENOSPACE;
+    if (!c->dry) {
+        const int rc = check_device(c);
+        if (rc != H1BKV_OK) return rc;
+    }
+    std::vector<int32_t> ui, up;
+    take_pages(c, seq_id, (int32_t)upto, ui, up);
+    const int rc = publish(c, ui, up, static_cast<hipStream_t>(hip_stream));
+    if (rc != H1BKV_OK) h1bkv_truncate_seq(c, seq_id, c->seq_len[seq_id]);   // the pages taken go back
+    return rc;
+}
+
+int h1bkv_reserved_tokens(const h1bkv_cache *c, int32_t seq_id, int32_t *n_out) {
+    if (!c || !n_out) return H1BKV_ENULL;
+    if (seq_id < 0 || seq_id >= c->cfg.max_seqs) return H1BKV_ERANGE;
+    *n_out = (int32_t)c->seq_pages[seq_id].size() * kPage;
+    return H1BKV_OK;
+}
+
+int h1bkv_set_seq_len(h1bkv_cache *c, int32_t seq_id, int32_t new_len) {
+    if (!c) return H1BKV_ENULL;
+    if (seq_id < 0 || seq_id >= c->cfg.max_seqs) return H1BKV_ERANGE;
+    if (new_len < c->seq_len[seq_id] || pages_for(new_len) > (int)c->seq_pages[seq_id].size()) return H1BKV_ERANGE;
+    c->seq_len[seq_id] = new_len;
+    return H1BKV_OK;
+}
+
+int h1bkv_decode_step_dev(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n_seqs, const void *k_dev, const void *v_dev,
+                          int64_t stride_seq, int64_t stride_head, const void *q_dev, float tau, float *out_dev,
+                          int32_t *pos_dev, int32_t max_pos, void *workspace_dev, size_t workspace_bytes, void *hip_stream) {
+    if (!c) return H1BKV_ENULL;
+    int rc = check_seq_ids(c, seq_ids_host, n_seqs);
+    if (rc != H1BKV_OK) return rc;
+    if (!(tau > 0.0f) || !std::isfinite(tau) || max_pos < 1) return H1BKV_EINVAL;
+    // every position the kernels may touch has a page already: nothing is assigned while the step runs (or replays)
+    for (int i = 0; i < n_seqs; ++i)
+        if (pages_for(max_pos) > (int)c->seq_pages[seq_ids_host[i]].size()) return H1BKV_ERANGE;
+    if (stride_seq < 0 || stride_head < c->cfg.head_dim) return H1BKV_EINVAL;
+    if (c->dry) return H1BKV_ENODEVICE;
+    if (!k_dev || !v_dev || !q_dev || !out_dev || !pos_dev || !workspace_dev) return H1BKV_ENULL;
+    const int elt = c->cfg.in_dtype == H1BKV_F16 ? 2 : 4;
+    if (reinterpret_cast<uintptr_t>(k_dev) % 16 || reinterpret_cast<uintptr_t>(v_dev) % 16 ||
+        reinterpret_cast<uintptr_t>(q_dev) % 16 || reinterpret_cast<uintptr_t>(out_dev) % 16 ||
+        reinterpret_cast<uintptr_t>(pos_dev) % 4 || reinterpret_cast<uintptr_t>(workspace_dev) % kAlign ||
+        (stride_seq * elt) % 16 || (stride_head * elt) % 16)
+        return H1BKV_EINVAL;
+    if (workspace_bytes < h1bkv_decode_workspace_bytes(c, n_seqs, max_pos)) return H1BKV_EWORKSPACE;
+    rc = check_device(c);
+    if (rc != H1BKV_OK) return rc;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const DevicePositions dev{pos_dev, max_pos};
+    rc = enqueue_append(c, seq_ids_host, n_seqs, 1, k_dev, v_dev, stride_seq, 0, stride_head, q_dev,
+                        static_cast<uint64_t *>(workspace_dev), st, &dev);
+    if (rc != H1BKV_OK) return rc;
+    // (the merge, the step's last kernel, advances the positions; if a launch fails before it they stay as they are and
+    // the appended records lie past every sequence's end)
+    return enqueue_decode(c, seq_ids_host, n_seqs, q_dev, tau, out_dev, workspace_dev, true, st, &dev);
 }
 
 size_t h1bkv_decode_dtau_workspace_bytes(const h1bkv_cache *c, int32_t n_seqs, int32_t max_ctx) {

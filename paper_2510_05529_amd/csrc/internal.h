@@ -22,7 +22,36 @@ struct SeqDesc {
 };
 struct BatchDesc {
     SeqDesc s[kMaxSeqsPerLaunch];
+    // Device-resident positions (h1bkv_decode_step_dev; nullptr otherwise): pos_dev[i] is the number of tokens sequence
+    // s[i] holds, read by the kernels when they run -- a captured launch then follows the sequence as it grows.  The
+    // position a kernel works on is pos_dev[i] + pos_add, never beyond pos_max (the tokens the caller reserved pages for).
+    const int32_t *pos_dev = nullptr;
+    int32_t pos_add = 0;
+    int32_t pos_max = 0;
+    int32_t advance = 0;     // the step's last kernel (the merge) adds one to every position once all its workgroups have read theirs
 };
+
+// The position of sequence i of a launch: the descriptor's, or the device-resident one.
+__device__ __forceinline__ int desc_pos(const BatchDesc &d, int i) {
+    if (d.pos_dev) {
+        const int p = d.pos_dev[i] + d.pos_add;
+        return p < d.pos_max ? p : d.pos_max;
+    }
+    return d.s[i].pos;
+}
+
+// Device-resident positions, end of a step: called by every workgroup of the step's last kernel right after all its
+// threads have read their positions (the caller's barrier), by one thread.  The workgroup that arrives last -- every
+// other one holds its position in registers by then -- moves the n sequences of the launch one token on and leaves the
+// counter at zero for the next launch.  (No kernel of the step reads a position after this point; the next step's
+// kernels start after this one has ended.)
+__device__ __forceinline__ void advance_positions_when_all_read(const BatchDesc &d, uint32_t *ticket, unsigned n_workgroups, int n) {
+    if (atomicAdd(ticket, 1u) != n_workgroups - 1) return;
+    atomicExch(ticket, 0u);
+    int32_t *pos = const_cast<int32_t *>(d.pos_dev);
+    for (int i = 0; i < n; ++i)
+        if (pos[i] < d.pos_max) pos[i] += 1;
+}
 
 struct TablePairs {
     int32_t n;
@@ -41,6 +70,7 @@ struct PoolView {
     const uint16_t *R16mid;  // [b][d] fp16 bits
     const float *guard;      // [2][b]: the band factors for fp16 inputs, then those for fp32 inputs (split into two pieces too)
     int32_t *block_table;    // [max_seqs][max_pages_per_seq]
+    uint32_t *ticket;        // one counter (zero between launches): workgroups of a merge that have read their positions
     uint64_t *sketch;        // [page][H_kv][256][W]
     uint8_t *codes;          // [page][H_kv][256][d/2]
     uint32_t *meta;          // [page][H_kv][256][n_g]  low half = fp16 scale, high half = fp16 zero

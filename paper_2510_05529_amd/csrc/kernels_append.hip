@@ -147,7 +147,11 @@ __device__ __forceinline__ void append_body(const AppendArgs &a, const BatchDesc
     __shared__ uint32_t codes_s[kTile][D / 8 + 1];    // layout 1: codes of the tile in canonical nibble order (+1: bank spread)
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const SeqDesc sd = desc.s[by];
+    SeqDesc sd = desc.s[by];
+    if (desc.pos_dev) {                               // device-resident position: the token goes where the sequence ends now
+        sd.pos = desc.pos_dev[by] + desc.pos_add;
+        if (sd.pos >= desc.pos_max) return;           // beyond the reserved pages: nothing is written (whole workgroup)
+    }
     const PoolView &pv = a.pool;
     const int H = pv.n_kv_heads, W = pv.sketch_bits >> 6, G = pv.group_size, ng = D / G;
     const int n_new = a.n_new;

@@ -60,7 +60,7 @@ __global__ __launch_bounds__(kThreads, RQH * (DTAU ? 2 : 1) >= 4 ? 2 : 1) void d
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const SeqDesc sd = desc.s[blockIdx.z];
-    const int ctx = sd.pos;
+    const int ctx = desc_pos(desc, blockIdx.z);
     const int chunk0 = blockIdx.x * a.chunk;
     if (chunk0 >= ctx) return;
     const int n_tok = min(a.chunk, ctx - chunk0);
@@ -306,7 +306,11 @@ __global__ __launch_bounds__(kMergeThreads) void merge_kernel(DecodeArgs a, Batc
     __shared__ float lo_s[kMergeThreads][2];
     const int D = a.pool.head_dim;
     const int qh = blockIdx.x, seq_g = seq0 + blockIdx.y;
-    const int ctx = desc.s[blockIdx.y].pos;
+    const int ctx = desc_pos(desc, blockIdx.y);
+    if (desc.advance) {                       // (uniform) device-resident positions: this is the step's last kernel
+        __syncthreads();
+        if (threadIdx.x == 0) advance_positions_when_all_read(desc, a.pool.ticket, gridDim.x * gridDim.y, (int)gridDim.y);
+    }
     const int n = (ctx + a.chunk - 1) / a.chunk;
     const size_t part = ((size_t)seq_g * a.pool.n_q_heads + qh) * a.n_splits;
     const int tid = threadIdx.x, c = tid % D, sl = tid / D, n_sl = kMergeThreads / D;
@@ -349,9 +353,15 @@ __global__ __launch_bounds__(kMergeThreads) void merge_few_kernel(DecodeArgs a, 
     const int D = a.pool.head_dim, Hq = a.pool.n_q_heads;
     const int c = threadIdx.x % D;
     const int head = blockIdx.x * (kMergeThreads / D) + threadIdx.x / D;       // (sequence, query head) of this launch, flattened
-    if (head >= n_seqs * Hq) return;
+    const bool mine = head < n_seqs * Hq;
+    const int ctx = mine ? desc_pos(desc, head / Hq) : 0;
+    if (desc.advance) {                       // (uniform) device-resident positions: this is the step's last kernel
+        __syncthreads();
+        if (threadIdx.x == 0) advance_positions_when_all_read(desc, a.pool.ticket, gridDim.x, n_seqs);
+    }
+    if (!mine) return;
     const int s_local = head / Hq, qh = head % Hq, seq_g = seq0 + s_local;
-    const int n = (desc.s[s_local].pos + a.chunk - 1) / a.chunk;
+    const int n = (ctx + a.chunk - 1) / a.chunk;
     const size_t part = ((size_t)seq_g * Hq + qh) * a.n_splits;
     float *out = a.out + ((size_t)seq_g * Hq + qh) * D;
     if (n == 0) {

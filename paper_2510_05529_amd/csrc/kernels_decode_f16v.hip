@@ -67,7 +67,7 @@ __global__ __launch_bounds__(kThreads, RQ * (DTAU ? 2 : 1) >= 8 ? 2 : (RQ * (DTA
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const SeqDesc sd = desc.s[blockIdx.z];
-    const int ctx = sd.pos;
+    const int ctx = desc_pos(desc, blockIdx.z);
     const int chunk0 = blockIdx.x * a.chunk;
     if (chunk0 >= ctx) return;
     const int n_tok = min(a.chunk, ctx - chunk0);

@@ -102,7 +102,7 @@ __global__ __launch_bounds__(kThreads, (RQH == 2 && D <= 128) ? 3 : 2) void deco
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const SeqDesc sd = desc.s[blockIdx.z];
-    const int ctx = sd.pos;
+    const int ctx = desc_pos(desc, blockIdx.z);
     const int chunk0 = blockIdx.x * a.chunk;
     if (chunk0 >= ctx) return;
     const int n_tok = min(a.chunk, ctx - chunk0);

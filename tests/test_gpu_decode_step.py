@@ -86,3 +86,93 @@ def test_fused_step_under_graph_capture_replays_identically():
         torch.cuda.synchronize()
         assert np.array_equal(out_g.cpu().numpy(), ref), f"replay {i}"
     cache.close()
+
+
+DEV_CASES = [
+    (wl.Workload("dev_mha", 3, 4, 4, 128, 560, 128, 32, "f16", seed=21), [200, 250, 3]),
+    (wl.Workload("dev_gqa", 2, 8, 2, 128, 560, 256, 64, "f16", seed=22), [255, 130]),
+    (wl.Workload("dev_f16v", 2, 4, 2, 64, 560, 128, 32, "f16", seed=23), [190, 256]),
+]
+
+
+@pytest.mark.parametrize("w,starts", DEV_CASES, ids=lambda x: x.name if hasattr(x, "name") else None)
+def test_step_with_device_positions_replayed_as_one_graph(w, starts):
+    """h1bkv_decode_step_dev captured ONCE and replayed token after token (each replay one position further, across page
+    boundaries, ragged starting lengths) against the eager h1bkv_decode_step on a twin cache: outputs of every token, the
+    caches at the end, and the oracle."""
+    import torch
+    value_bits = 16 if "f16v" in w.name else 4
+    n_steps = 300
+    R = wl.projection(w.sketch_bits, w.head_dim)
+    seqs = list(range(w.batch))
+    k, v = wl.kv_slab(w, "k", seqs, 0, w.context), wl.kv_slab(w, "v", seqs, 0, w.context)
+    kd, vd = to_dev(k), to_dev(v)
+    twin, cache = make_cache(w, R, value_bits=value_bits), make_cache(w, R, value_bits=value_bits)
+    for s, n in zip(seqs, starts):
+        for c_ in (twin, cache):
+            c_.append([s], kd[s:s + 1, :n], vd[s:s + 1, :n])
+    max_pos = max(starts) + n_steps
+    assert max_pos <= w.context
+    # the device-position step needs its pages up front
+    ws_bytes = B.h1bkv_decode_workspace_bytes(cache.h, w.batch, max_pos)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    pos = torch.tensor(starts, dtype=torch.int32, device="cuda")
+    k1, v1 = torch.empty_like(kd[:, 0]), torch.empty_like(vd[:, 0])
+    q1 = torch.empty((w.batch, w.n_q_heads, w.head_dim), dtype=kd.dtype, device="cuda")
+    out_g = torch.zeros((w.batch, w.n_q_heads, w.head_dim), dtype=torch.float32, device="cuda")
+    args = (cache.h, seqs, k1, v1, k1.stride(0), k1.stride(1), q1, 0.07, out_g, pos, max_pos, ws, ws_bytes, None)
+    assert B.h1bkv_decode_step_dev(*args) == B.H1BKV_ERANGE           # no pages reserved yet
+    for s, n in zip(seqs, starts):
+        assert B.h1bkv_reserve_seq(cache.h, s, max_pos - n) == B.H1BKV_OK
+        assert B.h1bkv_reserved_tokens(cache.h, s)[1] >= max_pos and B.h1bkv_seq_len(cache.h, s)[1] == n
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    k1.copy_(kd[torch.arange(w.batch), torch.tensor(starts)])
+    v1.copy_(vd[torch.arange(w.batch), torch.tensor(starts)])
+    q_all = to_dev(np.random.default_rng(5).standard_normal((n_steps, w.batch, w.n_q_heads, w.head_dim)).astype(np.float16))
+    q1.copy_(q_all[0])
+    with torch.cuda.graph(g):
+        rc = B.h1bkv_decode_step_dev(*args)
+    assert rc == B.H1BKV_OK
+    pos.copy_(torch.tensor(starts, dtype=torch.int32))                 # (capture runs nothing; start from the true lengths)
+    out_e = torch.empty_like(out_g)
+    ws_e = torch.empty(B.h1bkv_decode_workspace_bytes(twin.h, w.batch, w.context), dtype=torch.uint8, device="cuda")
+    lens = list(starts)
+    worst = 0.0
+    for step in range(n_steps):
+        idx = torch.tensor(lens)
+        k1.copy_(kd[torch.arange(w.batch), idx])
+        v1.copy_(vd[torch.arange(w.batch), idx])
+        q1.copy_(q_all[step])
+        torch.cuda.synchronize()
+        g.replay()
+        assert B.h1bkv_decode_step(twin.h, seqs, k1, v1, k1.stride(0), k1.stride(1), q1, 0.07, out_e, ws_e, ws_e.numel(), None) == 0
+        torch.cuda.synchronize()
+        lens = [n + 1 for n in lens]
+        assert pos.cpu().tolist() == lens
+        worst = max(worst, rel_err(out_g.cpu().numpy(), out_e.cpu().numpy()))
+    assert worst <= 1e-5, worst                                        # same kernels; only the chunking (launch sized for max_pos) may differ
+    # the host learns the lengths; from here on every call sees the grown sequences
+    for s, n in zip(seqs, lens):
+        assert B.h1bkv_set_seq_len(cache.h, s, n + 10_000) == B.H1BKV_ERANGE
+        assert B.h1bkv_set_seq_len(cache.h, s, n) == B.H1BKV_OK
+    for s, n in zip(seqs, lens):
+        for h in range(w.n_kv_heads):
+            a, b = cache.export(s, h, 0, n), twin.export(s, h, 0, n)
+            for x, y in zip(a, b):
+                assert (x is None and y is None) or np.array_equal(x, y)
+    oc = cref.Cache(R, w.batch, w.n_kv_heads, w.context, w.group_size, value_bits=value_bits)
+    oc.append(k, v)
+    q_last = q_all[n_steps - 1].cpu().numpy()
+    assert rel_err(out_g.cpu().numpy(), oc.decode(q_last, 0.07, ctx_len=lens)) <= TOL
+    assert rel_err(cache.decode(seqs, q_all[n_steps - 1], 0.07).cpu().numpy(), oc.decode(q_last, 0.07, ctx_len=lens)) <= TOL
+    # a sequence that has reached max_pos is left alone: one more replay changes neither its position nor its records
+    before = cache.export(seqs[int(np.argmax(starts))], 0, 0, max_pos)
+    g.replay()
+    torch.cuda.synchronize()
+    assert pos.cpu().tolist()[int(np.argmax(starts))] == max_pos
+    after = cache.export(seqs[int(np.argmax(starts))], 0, 0, max_pos)
+    for x, y in zip(before, after):
+        assert (x is None and y is None) or np.array_equal(x, y)
+    cache.close()
+    twin.close()

@@ -38,14 +38,14 @@ def test_bad_geometry_is_rejected(bad):
 def test_pool_bytes_formula():
     """sketch + nibbles + fp16 scale/zero per record (Sec. IV-B: a b-bit sketch and d 4-bit values per token),
     plus R, its transpose, its two fp16 pieces with the per-row guard bands (one for fp16, one for fp32 inputs), and the
-    block table, each rounded up to 256 bytes."""
+    block table with 64 words behind it (the merge kernels' arrival counter), each rounded up to 256 bytes."""
     for w in (wl.WORKLOADS["tiny"], wl.WORKLOADS["decode_b16_32k"], wl.WORKLOADS["decode_gqa_128k"]):
         c = cfg(n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim, sketch_bits=w.sketch_bits,
                 group_size=w.group_size, max_seqs=3, max_pages=7, max_pages_per_seq=5)
         al = lambda x: (x + 255) // 256 * 256
         rec = 7 * w.n_kv_heads * 256
         want = (2 * al(w.sketch_bits * w.head_dim * 4) + 2 * al(w.sketch_bits * w.head_dim * 2) + al(2 * w.sketch_bits * 4)
-                + al(3 * 5 * 4) + al(rec * w.sketch_bits // 8)
+                + al((3 * 5 + 64) * 4) + al(rec * w.sketch_bits // 8)
                 + al(rec * w.head_dim // 2) + al(rec * w.n_groups * 4))
         assert B.h1bkv_pool_bytes(c) == want
         assert (w.sketch_bits // 8 + w.head_dim // 2 + 4 * w.n_groups) == w.record_bytes
@@ -286,4 +286,43 @@ def test_static_scratch_entry_point_rejects_what_does_not_fit():
     assert B.h1bkv_decode_attn_static(h, [0, 0], None, 0.1, None, 0) == B.H1BKV_EINVAL
     assert B.h1bkv_decode_attn_static(h, [0], None, -0.1, None, 0) == B.H1BKV_EINVAL
     assert B.lib().h1bkv_decode_attn_static(None, None, 1, None, 0.1, None, None) == B.H1BKV_ENULL
+    B.h1bkv_destroy(h)
+
+
+def test_reserved_pages_and_device_position_step_bookkeeping():
+    """h1bkv_reserve_seq takes pages without changing the length; appends use them up before taking new ones;
+    h1bkv_set_seq_len moves the length only inside the reservation; truncating gives reserved pages back; the
+    device-position step insists on pages for every position it may touch.  (Bookkeeping-only handle: nothing launches.)"""
+    c, h, _ = make(max_pages=10, max_pages_per_seq=6)
+    free = lambda: B.h1bkv_free_pages(h)[1]
+    length = lambda s: B.h1bkv_seq_len(h, s)[1]
+    assert B.h1bkv_append_kv(h, [0], 100, None, None, 100 * 512, 512, 128) == B.H1BKV_OK
+    assert (length(0), free(), B.h1bkv_reserved_tokens(h, 0)[1]) == (100, 9, 256)
+    assert B.h1bkv_reserve_seq(h, 0, 0) == B.H1BKV_OK and free() == 9                   # nothing to take
+    assert B.h1bkv_reserve_seq(h, 0, 156) == B.H1BKV_OK and free() == 9                 # still inside the first page
+    assert B.h1bkv_reserve_seq(h, 0, 157) == B.H1BKV_OK and free() == 8                 # position 256 needs a second one
+    assert B.h1bkv_reserve_seq(h, 0, 600) == B.H1BKV_OK and (length(0), free()) == (100, 7)
+    assert B.h1bkv_reserved_tokens(h, 0)[1] == 768
+    assert B.h1bkv_reserve_seq(h, 0, 6 * 256 - 100 + 1) == B.H1BKV_ENOSPACE and free() == 7   # beyond the per-sequence limit
+    assert B.h1bkv_reserve_seq(h, 0, -1) == B.H1BKV_EINVAL and B.h1bkv_reserve_seq(h, 9, 1) == B.H1BKV_ERANGE
+    # an append inside the reservation takes no page, one that outgrows it takes the difference
+    assert B.h1bkv_append_kv(h, [0], 500, None, None, 500 * 512, 512, 128) == B.H1BKV_OK and (length(0), free()) == (600, 7)
+    assert B.h1bkv_append_kv(h, [0], 300, None, None, 300 * 512, 512, 128) == B.H1BKV_OK and (length(0), free()) == (900, 6)
+    # lengths move forward inside the reservation only
+    assert B.h1bkv_reserve_seq(h, 0, 300) == B.H1BKV_OK and free() == 5
+    assert B.h1bkv_set_seq_len(h, 0, 899) == B.H1BKV_ERANGE                              # backwards is truncate's job
+    assert B.h1bkv_set_seq_len(h, 0, 1281) == B.H1BKV_ERANGE                             # five pages hold 1280 tokens
+    assert B.h1bkv_set_seq_len(h, 0, 1000) == B.H1BKV_OK and (length(0), free()) == (1000, 5)
+    # truncating to the length that is cached drops what was reserved beyond it
+    assert B.h1bkv_truncate_seq(h, 0, 1000) == B.H1BKV_OK and free() == 6
+    # a forced launch failure while publishing reserved pages leaves everything as it was
+    assert B.h1bkv_debug_fail_launch(h, 1) == B.H1BKV_OK
+    assert B.h1bkv_reserve_seq(h, 1, 300) == B.H1BKV_EHIP and (length(1), free(), B.h1bkv_reserved_tokens(h, 1)[1]) == (0, 6, 0)
+    assert B.h1bkv_debug_fail_launch(h, 0) == B.H1BKV_OK
+    # the device-position step: argument checks that need no device
+    step = lambda seqs, max_pos, tau=0.1: B.h1bkv_decode_step_dev(h, seqs, None, None, 512, 128, None, tau, None, None, max_pos, None, 0)
+    assert step([0], 1025) == B.H1BKV_ERANGE             # sequence 0 holds four pages
+    assert step([0], 0) == B.H1BKV_EINVAL and step([0], 100, tau=0.0) == B.H1BKV_EINVAL
+    assert step([0, 0], 100) == B.H1BKV_EINVAL and step([7], 100) == B.H1BKV_ERANGE
+    assert step([0], 1024) == B.H1BKV_ENODEVICE          # everything else is in order: only the device is missing
     B.h1bkv_destroy(h)
