@@ -60,27 +60,31 @@ __global__ __launch_bounds__(kThreads, RQH * (DTAU ? 2 : 1) >= 4 ? 2 : 1) void d
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const SeqDesc sd = desc.s[blockIdx.z];
-    const int ctx = desc_pos(desc, blockIdx.z);
-    const int chunk0 = blockIdx.x * a.chunk;
-    if (chunk0 >= ctx) return;
-    const int n_tok = min(a.chunk, ctx - chunk0);
-    const int n_pages = (n_tok + kPage - 1) / kPage;
-
     const PoolView &pv = a.pool;
+    const int chunk0 = blockIdx.x * a.chunk;
+    // The chunk's page ids and the query sketches do not depend on the context length: they are requested first, so that
+    // a length that lives in device memory (desc_pos) is one more load in flight, not a round trip in front of them.
+    // (Table entries past the sequence's pages are read too and never used.)
+    int my_page = 0;
+    if (tid < a.chunk / kPage && chunk0 / kPage + tid < pv.max_pages_per_seq)
+        my_page = pv.block_table[(size_t)sd.seq_id * pv.max_pages_per_seq + chunk0 / kPage + tid];
     const int H = pv.n_kv_heads, r = pv.n_q_heads / H;
     const int passes = r / RQH;
     const int kvh = blockIdx.y / passes;
     const int qh0 = kvh * r + (blockIdx.y % passes) * RQH;
     const int seq_g = seq0 + blockIdx.z;
     const int ng = D / pv.group_size;
-
-    if (tid < n_pages) pages_s[tid] = pv.block_table[(size_t)sd.seq_id * pv.max_pages_per_seq + chunk0 / kPage + tid];
-
     uint64_t sq[RQH][W];
 #pragma unroll
     for (int q = 0; q < RQH; ++q)
 #pragma unroll
         for (int w = 0; w < W; ++w) sq[q][w] = a.q_sketch[((size_t)seq_g * pv.n_q_heads + qh0 + q) * W + w];
+
+    const int ctx = desc_pos(desc, blockIdx.z);
+    if (chunk0 >= ctx) return;
+    const int n_tok = min(a.chunk, ctx - chunk0);
+    const int n_pages = (n_tok + kPage - 1) / kPage;
+    if (tid < n_pages) pages_s[tid] = my_page;
     __syncthreads();
 
     // Every wave streams on its own: it owns tokens [64 wave, 64 wave + 64) of each page of the chunk.
