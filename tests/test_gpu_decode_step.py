@@ -176,3 +176,61 @@ def test_step_with_device_positions_replayed_as_one_graph(w, starts):
         assert (x is None and y is None) or np.array_equal(x, y)
     cache.close()
     twin.close()
+
+
+def test_device_positions_with_more_sequences_than_one_launch_describes():
+    """150 sequences x 16 query heads: the step is two launches of each kernel (128 + 22 sequences, each with its own
+    slice of the position array), the first merging its 2048 heads with the few-chunks kernel, the second with the
+    per-head one; both must advance exactly their own sequences, once per replay."""
+    import torch
+    w = wl.Workload("dev_many", 150, 16, 16, 128, 330, 128, 32, "f16", seed=31)
+    n_steps = 40
+    R = wl.projection(w.sketch_bits, w.head_dim)
+    seqs = list(range(w.batch))
+    rng = np.random.default_rng(8)
+    starts = [int(x) for x in rng.integers(1, 280, w.batch)]
+    starts[5], starts[140] = 255, 256
+    k, v = wl.kv_slab(w, "k", seqs, 0, w.context), wl.kv_slab(w, "v", seqs, 0, w.context)
+    kd, vd = to_dev(k), to_dev(v)
+    twin, cache = make_cache(w, R), make_cache(w, R)
+    for s, n in zip(seqs, starts):
+        for c_ in (twin, cache):
+            c_.append([s], kd[s:s + 1, :n], vd[s:s + 1, :n])
+    max_pos = max(starts) + n_steps
+    for s, n in zip(seqs, starts):
+        assert B.h1bkv_reserve_seq(cache.h, s, max_pos - n) == B.H1BKV_OK
+    ws_bytes = B.h1bkv_decode_workspace_bytes(cache.h, w.batch, max_pos)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    ws_e = torch.empty(B.h1bkv_decode_workspace_bytes(twin.h, w.batch, w.context), dtype=torch.uint8, device="cuda")
+    pos = torch.tensor(starts, dtype=torch.int32, device="cuda")
+    k1, v1 = torch.empty_like(kd[:, 0]), torch.empty_like(vd[:, 0])
+    q1 = to_dev(rng.standard_normal((w.batch, w.n_q_heads, w.head_dim)).astype(np.float16))
+    out_g = torch.zeros((w.batch, w.n_q_heads, w.head_dim), dtype=torch.float32, device="cuda")
+    out_e = torch.empty_like(out_g)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        assert B.h1bkv_decode_step_dev(cache.h, seqs, k1, v1, k1.stride(0), k1.stride(1), q1, 0.07, out_g, pos, max_pos, ws,
+                                       ws_bytes, None) == B.H1BKV_OK
+    pos.copy_(torch.tensor(starts, dtype=torch.int32))
+    lens = list(starts)
+    rows = torch.arange(w.batch)
+    for step in range(n_steps):
+        idx = torch.tensor(lens)
+        k1.copy_(kd[rows, idx])
+        v1.copy_(vd[rows, idx])
+        torch.cuda.synchronize()
+        g.replay()
+        assert B.h1bkv_decode_step(twin.h, seqs, k1, v1, k1.stride(0), k1.stride(1), q1, 0.07, out_e, ws_e, ws_e.numel(), None) == 0
+        torch.cuda.synchronize()
+        lens = [n + 1 for n in lens]
+        assert pos.cpu().tolist() == lens, f"step {step}"
+        assert rel_err(out_g.cpu().numpy(), out_e.cpu().numpy()) <= 1e-5, f"step {step}"
+    for s, n in zip(seqs, lens):
+        assert B.h1bkv_set_seq_len(cache.h, s, n) == B.H1BKV_OK
+    for s in (0, 5, 127, 128, 140, 149):
+        for h in (0, 15):
+            for x, y in zip(cache.export(s, h, 0, lens[s]), twin.export(s, h, 0, lens[s])):
+                assert np.array_equal(x, y)
+    cache.close()
+    twin.close()
