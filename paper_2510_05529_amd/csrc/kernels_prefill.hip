@@ -201,14 +201,20 @@ __global__ __launch_bounds__(WAVES * 64, 8 / WAVES) void prefill_kernel(PrefillA
     // (a lane per token pair would touch a different cache line with every lane).  Their LDS writes then go to channel
     // rows 8 or 16 apart at one token position -- the same banks, whatever the row padding -- so the 16-byte blocks of a
     // channel row are stored exchanged: block k of row c sits at k ^ ((c >> KSH) & 7).
-    constexpr int KSH = (LAYOUT == 2 || (LAYOUT == 0 && (TK / 2) * (D / 8) < 2 * kPfThreads)) ? 3 : 4;
+    // What the LDS of this chip does per pass of 32 lanes (measured with address patterns of their own): 16-byte reads are
+    // conflict-free iff their blocks differ mod 32 (512 bytes), 4-byte writes iff their words differ mod 64 (256 bytes).
+    // With 160-byte rows and the key c >> 4 the operand reads of 32 consecutive rows meet that; the key c >> 3 does not
+    // (rows i and i + 16 then share a block: every operand read took two passes).
+    constexpr int KSH = LAYOUT == 2 ? 3 : 4;
     auto row_addr = [](int ch, int pos_halves) {       // byte offset of (channel row, operand position) in a value tile
         return ch * VS + ((((pos_halves >> 3) ^ (ch >> KSH)) & 7) << 4) + ((pos_halves & 7) << 1);
     };
     static_assert(TK == 64, "a channel row is eight 16-byte blocks");
-    constexpr int CS0 = (TK / 2) * (D / 8) >= 2 * kPfThreads ? 16 : 8;    // layout 0: channels per staging item
+    constexpr int CS0 = 16;                                       // layout 0: channels per staging item
     constexpr int kItems0 = (TK / 2) * (D / CS0);                 // layout 0: (token pair, channel slice) items per tile
     static_assert(kItems0 <= kPfThreads, "one staging item per thread");
+    // (with eight waves the items and the sketch words occupy the first four: spreading them over all eight -- 8-channel
+    // items, or the sketch words on the last four -- was slower)
     constexpr int kItems2 = (TK / 2) * (D / kCS);                 // layout 2: (token pair, 8-channel slice) items per tile
     static_assert(kItems2 <= 2 * kPfThreads, "at most two staging items per thread");
     constexpr int NIT = (kItems2 + kPfThreads - 1) / kPfThreads;
@@ -246,13 +252,9 @@ __global__ __launch_bounds__(WAVES * 64, 8 / WAVES) void prefill_kernel(PrefillA
 #pragma unroll
                 for (int t = 0; t < 2; ++t) {
                     const uint32_t rl = 2 * tp + t;                         // record within the tile
-                    if constexpr (CS0 == 16) {
-                        const uint2 cc = *reinterpret_cast<const uint2 *>(c_base + (rl * (uint32_t)(DTOT / 2) + s16 * 8u));
-                        sr.c[2 * t] = cc.x;
-                        sr.c[2 * t + 1] = cc.y;
-                    } else {
-                        sr.c[2 * t] = *reinterpret_cast<const uint32_t *>(c_base + (rl * (uint32_t)(DTOT / 2) + s16 * 4u));
-                    }
+                    const uint2 cc = *reinterpret_cast<const uint2 *>(c_base + (rl * (uint32_t)(DTOT / 2) + s16 * 8u));
+                    sr.c[2 * t] = cc.x;
+                    sr.c[2 * t + 1] = cc.y;
                     sr.m[t] = *reinterpret_cast<const uint32_t *>(m_base + (((rl << lg_ng) + gq) << 2));
                 }
             }
@@ -311,6 +313,8 @@ __global__ __launch_bounds__(WAVES * 64, 8 / WAVES) void prefill_kernel(PrefillA
                     zp[t] = __half2float(__ushort_as_half((unsigned short)(m >> 16)));
                 }
                 const int pp = operand_pos(2 * tp);                // tokens 2 tp and 2 tp + 1 stay neighbours
+                // (a lane's two rows n and n + 4 lie 32 banks apart and go out as one two-address write)
+                const int wbase = row_addr(CS0 * s16, pp);
                 // A nibble masked in place at mantissa bits 0-3 / 4-7 of a zero half-word is the fp16 subnormal
                 // code 2^-24 / code 2^-20: the mixed-precision FMA reads it directly, with the scale times 2^24 / 2^20.
                 const float sa[2] = {sc[0] * 16777216.0f, sc[1] * 16777216.0f}, sb[2] = {sc[0] * 1048576.0f, sc[1] * 1048576.0f};
@@ -328,7 +332,6 @@ __global__ __launch_bounds__(WAVES * 64, 8 / WAVES) void prefill_kernel(PrefillA
                         const h16x2 plo = __builtin_convertvector(lo, h16x2), phi = __builtin_convertvector(hi, h16x2);
                         // (all channels of the item share one exchange key: the address is a lane base plus a constant)
                         static_assert((CS0 >> KSH) <= 1, "one key per staging item");
-                        const int wbase = row_addr(CS0 * s16, pp);
                         *reinterpret_cast<h16x2 *>(vs + wbase + (8 * k + n) * VS) = plo;
                         *reinterpret_cast<h16x2 *>(vs + wbase + (8 * k + n + 4) * VS) = phi;
                     }
