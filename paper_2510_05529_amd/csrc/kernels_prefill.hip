@@ -200,14 +200,13 @@ __global__ __launch_bounds__(WAVES * 64, 8 / WAVES) void prefill_kernel(PrefillA
     // Consecutive lanes take consecutive channel slices of one token pair, so that a wave's loads cover whole records
     // (a lane per token pair would touch a different cache line with every lane).  Their LDS writes then go to channel
     // rows 8 or 16 apart at one token position -- the same banks, whatever the row padding -- so the 16-byte blocks of a
-    // channel row are stored exchanged: block k of row c sits at k ^ ((c >> KSH) & 7).
+    // channel row are stored exchanged: block k of row c sits at k ^ ((c >> 4) & 7).
     // What the LDS of this chip does per pass of 32 lanes (measured with address patterns of their own): 16-byte reads are
     // conflict-free iff their blocks differ mod 32 (512 bytes), 4-byte writes iff their words differ mod 64 (256 bytes).
     // With 160-byte rows and the key c >> 4 the operand reads of 32 consecutive rows meet that; the key c >> 3 does not
     // (rows i and i + 16 then share a block: every operand read took two passes).
-    constexpr int KSH = LAYOUT == 2 ? 3 : 4;
     auto row_addr = [](int ch, int pos_halves) {       // byte offset of (channel row, operand position) in a value tile
-        return ch * VS + ((((pos_halves >> 3) ^ (ch >> KSH)) & 7) << 4) + ((pos_halves & 7) << 1);
+        return ch * VS + ((((pos_halves >> 3) ^ (ch >> 4)) & 7) << 4) + ((pos_halves & 7) << 1);
     };
     static_assert(TK == 64, "a channel row is eight 16-byte blocks");
     constexpr int CS0 = 16;                                       // layout 0: channels per staging item
@@ -331,7 +330,7 @@ __global__ __launch_bounds__(WAVES * 64, 8 / WAVES) void prefill_kernel(PrefillA
                         const f32x2 hi = {fmaf(w0, __high2float(h0), zp[0]), fmaf(w1, __high2float(h1), zp[1])};
                         const h16x2 plo = __builtin_convertvector(lo, h16x2), phi = __builtin_convertvector(hi, h16x2);
                         // (all channels of the item share one exchange key: the address is a lane base plus a constant)
-                        static_assert((CS0 >> KSH) <= 1, "one key per staging item");
+                        static_assert(CS0 <= 16, "one key per staging item");
                         *reinterpret_cast<h16x2 *>(vs + wbase + (8 * k + n) * VS) = plo;
                         *reinterpret_cast<h16x2 *>(vs + wbase + (8 * k + n + 4) * VS) = phi;
                     }
@@ -459,7 +458,7 @@ __global__ __launch_bounds__(WAVES * 64, 8 / WAVES) void prefill_kernel(PrefillA
         };
         // Lane bases of the value operands: row i of a column block, 16-byte block (2 m' + g) ^ (the key bits that come
         // from i); the key bits that come from the column block and the step's bit are added as constants at the reads.
-        const int lane_key = KSH == 4 ? (i >> 4) : ((i >> 3) & 3);
+        const int lane_key = i >> 4;
         const int bbase[2] = {i * VS + (((0 | g) ^ lane_key) << 4), i * VS + (((2 | g) ^ lane_key) << 4)};
         auto values = [&](const HalfOperand *A, int st) {
             __builtin_amdgcn_s_setprio(3);
@@ -469,9 +468,7 @@ __global__ __launch_bounds__(WAVES * 64, 8 / WAVES) void prefill_kernel(PrefillA
                 for (int m = 0; m < 2; ++m) {
                     // row 32 cb + i, block 4 st + 2 m + g exchanged with the row's key: what depends on (cb, st, m) is a
                     // compile-time offset and a choice between two lane bases (see bbase)
-                    constexpr bool k4 = KSH == 4;
-                    const int mm = k4 ? (m ^ (cb & 1)) : m;
-                    const int bit2 = k4 ? (st ^ (cb >> 1)) : (st ^ (cb & 1));
+                    const int mm = m ^ (cb & 1), bit2 = st ^ (cb >> 1);
                     const f16x8 B = *reinterpret_cast<const f16x8 *>(vs + bbase[mm] + (32 * cb * VS + (bit2 << 6)));
                     acc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(A[m].v, B, acc[cb], 0, 0, 0);
                 }
