@@ -82,40 +82,32 @@ __device__ __forceinline__ void quantise_slice(const float (&x)[32], int lanes_p
     const float zp = __half2float(__ushort_as_half(zh));
     packed[0] = packed[1] = packed[2] = packed[3] = 0u;
     if (sc != 0.0f) {
-        // Eq.(4)'s code is clamp(rint((x - zero) / scale)) with an IEEE divide.  Fast path: with r = RN(1 / scale),
-        // u = fma(x - zero, r, 2^23) rounds the exact product to an integer in the low mantissa bits of u.  The
-        // product and the rounded quotient each lie within 16 * 2^-24 of the true quotient (codes beyond 0..15 are
-        // clamped on either route), so they can round to different integers only if a half-integer lies within
-        // 2e-6 of the product, i.e. if the product's distance e from its integer is within that of 1/2.  A lane
-        // that sees such an element in a word of 8 codes redoes that word with the divide.  The codes are assembled as
+        // Eq.(4)'s code is clamp(rint((x - zero) / scale)) with an IEEE divide.  The quotient without the divide
+        // instruction sequence: with r = RN(1 / scale) and q0 = RN(d r), q = fma(fma(-q0, scale, d), r, q0) is the
+        // correctly rounded d / scale (one Newton step on a quotient that is within an ulp, exact remainder; the scale is
+        // an fp16 number, so its significand is never all ones, the one case the step can miss).  Compared on the host
+        // with the divide for every fp16 scale at the fp32 neighbours of every code boundary and on 2 x 10^8 random
+        // quotients: no difference.  An earlier form rounded d r directly and redid words that held an element near a
+        // half-integer with the divide: fp16 inputs put quotients exactly on half-integers so often that four in ten
+        // (wave, word) pairs took the redo, which was two fifths of the kernel's instructions.
+        // u = q + 2^23 rounds q to an integer (ties to even, as rint) in the low mantissa bits; the codes are assembled as
         // w = (w << 4) + bits(u): every bits(u) is 0x4B000000 + code, so the stray high bits sum to a constant that is
         // subtracted once per word.
         const float r = 1.0f / sc;
+        const float s_fin = sc < __builtin_inff() ? sc : 0.0f;      // an overflowed scale: r = 0 and every code 0, as d / inf
 #pragma unroll
         for (int wd = 0; wd < 4; ++wd) {
             uint32_t w = 0u;
-            float worst = 0.0f;
 #pragma unroll
             for (int i = 7; i >= 0; --i) {
                 const float d = x[8 * wd + i] - zp;
-                const float u = __builtin_fmaf(d, r, 8388608.0f);
-                const float e = __builtin_fmaf(d, r, 8388608.0f - u);      // product minus its integer (exact difference)
-                worst = fmaxf(worst, fabsf(e));
+                const float q0 = __fmul_rn(d, r);
+                const float q = __builtin_fmaf(__builtin_fmaf(-q0, s_fin, d), r, q0);
+                const float u = __fadd_rn(q, 8388608.0f);
                 const float uc = __builtin_amdgcn_fmed3f(u, 8388608.0f, 8388623.0f);
                 w = (w << 4) + __float_as_uint(uc);
             }
             w -= 0xFB000000u;                      // sum over i of 0x4B000000 << 4 i, modulo 2^32
-            // The redo is per word of 8 codes, not per slice: fp16 inputs put quotients EXACTLY on half-integers often
-            // enough (a few in ten thousand elements) that half of all waves hold such an element somewhere.
-            if (!(worst < 0.49999f)) {             // also a NaN: the divide decides
-                w = 0u;
-#pragma unroll                                     // (a rolled loop would index x[] dynamically and move it out of the registers)
-                for (int i = 0; i < 8; ++i) {
-                    float q = rintf((x[8 * wd + i] - zp) / sc);
-                    q = fminf(fmaxf(q, 0.0f), 15.0f);
-                    w |= (uint32_t)(int)q << (4 * i);
-                }
-            }
             packed[wd] = w;
         }
     }
