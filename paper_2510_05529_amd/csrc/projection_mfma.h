@@ -512,7 +512,8 @@ __device__ __forceinline__ void resident_sketch_tiles(const PoolView &pv, const 
         H1BKV_PROJ_REQUEST_ONE(2, pre2, SB) H1BKV_PROJ_REQUEST_ONE(3, pre3, SB)                             \
     } while (0)
     // deposit a piece into the LDS tile and leave its row's 2-norm (times 1 + 2^-16: above the fp32 rounding of the sum
-    // and the root) in band_s; the D / 8 lanes of a row are neighbours
+    // and the root -- the hardware root, an ulp off at most: the correctly rounded one is an 18-instruction sequence that
+    // every lane of the wave would run four times per tile) in band_s; the D / 8 lanes of a row are neighbours
 #define H1BKV_PROJ_DEPOSIT_ONE(K, REG, BUF)                                                                 \
     if constexpr (K * RPP < kProjTile) {                                                                    \
         const int rl = pre_row + K * RPP;                                                                   \
@@ -521,7 +522,7 @@ __device__ __forceinline__ void resident_sketch_tiles(const PoolView &pv, const 
         float ss = 0.0f;                                                                                    \
         _Pragma("unroll") for (int e = 0; e < 4; ++e) ss = __builtin_amdgcn_fdot2(h2[e], h2[e], ss, false); \
         ss = proj_sum_lanes<D / 8>(ss);                                                                     \
-        if (pre_ch == 0) band_s[BUF][rl] = sqrtf(ss) * 1.0000153f;                                          \
+        if (pre_ch == 0) band_s[BUF][rl] = __builtin_amdgcn_sqrtf(ss) * 1.0000153f;                         \
     }
     long t = first;
     int page = 0;
