@@ -295,6 +295,9 @@ int h1bkv_extend_seq(h1bkv_cache *c, int32_t seq_id, int32_t n_new, void *hip_st
  * capacity == 0 disables recording and releases the events.
  * A kind whose work takes two kernels (H1BKV_K_APPEND of a large append: the keys' half and the values' half;
  * H1BKV_K_PREFILL with a context split: the attention kernel and its merge) is bracketed once around both.
+ * H1BKV_K_DECODE_SPLIT is the exception to the bracket: its two events are attached to the kernel's own dispatch and
+ * hold the kernel's start and end, the duration a kernel trace reports (events recorded around a launch also count
+ * the 2-3 microseconds between command packets, which is 4 % of a 70-microsecond kernel).
  */
 enum { H1BKV_K_APPEND = 0, H1BKV_K_QSKETCH = 1, H1BKV_K_DECODE_SPLIT = 2, H1BKV_K_MERGE = 3, H1BKV_K_PREFILL = 4,
        H1BKV_K_COUNT = 5 };
@@ -318,6 +321,12 @@ int h1bkv_stream_copy(void *dst_dev, const void *src_dev, size_t n_bytes, void *
  * ceiling a streaming kernel can reach on this device, against which the decode kernel is also reported.
  */
 int h1bkv_stream_read(const void *src_dev, size_t n_bytes, void *sink_dev, void *hip_stream);
+/*
+ * The same launch, timed: waits for the kernel (the one synchronous call among these helpers) and writes its duration
+ * in milliseconds to ms_out (host), taken from events attached to the kernel's dispatch as for H1BKV_K_DECODE_SPLIT above,
+ * so that the ceiling and the decode kernel are measured the same way.  n_bytes > 0.
+ */
+int h1bkv_stream_read_ms(const void *src_dev, size_t n_bytes, void *sink_dev, void *hip_stream, float *ms_out);
 
 #ifdef __cplusplus
 }

@@ -87,6 +87,7 @@ def lib() -> C.CDLL:
             "h1bkv_profile_read": (C.c_int, [vp, i32, vp, i32, C.POINTER(i32)]),
             "h1bkv_stream_copy": (C.c_int, [vp, vp, sz, vp]),
             "h1bkv_stream_read": (C.c_int, [vp, sz, vp, vp]),
+            "h1bkv_stream_read_ms": (C.c_int, [vp, sz, vp, vp, C.POINTER(C.c_float)]),
         }
         for name, (res, args) in sig.items():
             fn = getattr(L, name)
@@ -302,6 +303,12 @@ def h1bkv_stream_copy(dst, src, n_bytes: int, stream=0) -> int:
 
 def h1bkv_stream_read(src, n_bytes: int, sink, stream=0) -> int:
     return lib().h1bkv_stream_read(_dev_ptr(src), n_bytes, _dev_ptr(sink), _stream(stream))
+
+
+def h1bkv_stream_read_ms(src, n_bytes: int, sink, stream=0):
+    ms = C.c_float(0.0)
+    rc = lib().h1bkv_stream_read_ms(_dev_ptr(src), n_bytes, _dev_ptr(sink), _stream(stream), C.byref(ms))
+    return rc, ms.value
 
 
 def check(code: int, what: str = "h1bkv") -> None:

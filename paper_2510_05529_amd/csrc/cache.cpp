@@ -165,6 +165,18 @@ struct EventPair {
 
 }  // namespace
 
+namespace h1bkv {
+namespace {
+thread_local DispatchEvents g_dispatch_events;     // (a handle is driven by one thread at a time)
+}
+void set_dispatch_events(hipEvent_t start, hipEvent_t stop) { g_dispatch_events = DispatchEvents{start, stop}; }
+DispatchEvents take_dispatch_events() {
+    const DispatchEvents e = g_dispatch_events;
+    g_dispatch_events = DispatchEvents{};
+    return e;
+}
+}  // namespace h1bkv
+
 struct h1bkv_cache {
     h1bkv_config cfg;
     Layout lay;
@@ -221,7 +233,8 @@ int check_device(const h1bkv_cache *c) {
     return H1BKV_OK;
 }
 
-// Event bracket around one kernel launch; inert unless profiling is enabled.
+// Event bracket around one kernel launch; inert unless profiling is enabled.  The split-decode kernel's events ride on its
+// dispatch instead (see H1BKV_LAUNCH_SPLIT): recorded around the launch they only serve a launch that did not take them.
 struct Timed {
     h1bkv_cache *c;
     int kind;
@@ -231,11 +244,21 @@ struct Timed {
         if (c->prof_cap > 0 && ((c->prof_mask >> kind) & 1u) && c->prof_used[kind] < c->prof_cap &&
             c->prof_seen[kind]++ % c->prof_stride == 0) {
             slot = c->prof_used[kind]++;
-            (void)hipEventRecord(c->prof_events[kind][slot].a, st);
+            if (kind == H1BKV_K_DECODE_SPLIT) set_dispatch_events(c->prof_events[kind][slot].a, c->prof_events[kind][slot].b);
+            else (void)hipEventRecord(c->prof_events[kind][slot].a, st);
         }
     }
     ~Timed() {
-        if (slot >= 0) (void)hipEventRecord(c->prof_events[kind][slot].b, st);
+        if (slot < 0) return;
+        if (kind == H1BKV_K_DECODE_SPLIT) {
+            const DispatchEvents left = take_dispatch_events();
+            if (left.start) {                        // nothing was launched (an error path): leave valid, empty timings
+                (void)hipEventRecord(c->prof_events[kind][slot].a, st);
+                (void)hipEventRecord(c->prof_events[kind][slot].b, st);
+            }
+        } else {
+            (void)hipEventRecord(c->prof_events[kind][slot].b, st);
+        }
     }
 };
 
@@ -1114,6 +1137,26 @@ int h1bkv_stream_read(const void *src_dev, size_t n_bytes, void *sink_dev, void 
     if (n_bytes % 16 || reinterpret_cast<uintptr_t>(src_dev) % 16 || reinterpret_cast<uintptr_t>(sink_dev) % 16) return H1BKV_EINVAL;
     if (n_bytes == 0) return H1BKV_OK;
     return launch_stream_read(src_dev, n_bytes, sink_dev, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? H1BKV_OK : H1BKV_EHIP;
+}
+
+int h1bkv_stream_read_ms(const void *src_dev, size_t n_bytes, void *sink_dev, void *hip_stream, float *ms_out) {
+    if (!ms_out) return H1BKV_ENULL;
+    *ms_out = 0.0f;
+    if (!src_dev || !sink_dev) return H1BKV_ENULL;
+    if (n_bytes == 0 || n_bytes % 16 || reinterpret_cast<uintptr_t>(src_dev) % 16 || reinterpret_cast<uintptr_t>(sink_dev) % 16) return H1BKV_EINVAL;
+    hipEvent_t a = nullptr, b = nullptr;
+    if (hipEventCreate(&a) != hipSuccess) return H1BKV_EHIP;
+    if (hipEventCreate(&b) != hipSuccess) {
+        (void)hipEventDestroy(a);
+        return H1BKV_EHIP;
+    }
+    set_dispatch_events(a, b);
+    bool ok = launch_stream_read(src_dev, n_bytes, sink_dev, static_cast<hipStream_t>(hip_stream)) == hipSuccess;
+    (void)take_dispatch_events();                    // (a launch that failed early has not taken them)
+    ok = ok && hipEventSynchronize(b) == hipSuccess && hipEventElapsedTime(ms_out, a, b) == hipSuccess;
+    (void)hipEventDestroy(a);
+    (void)hipEventDestroy(b);
+    return ok ? H1BKV_OK : H1BKV_EHIP;
 }
 
 }  // extern "C"

@@ -2,6 +2,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include "h1bkv.h"
@@ -167,6 +168,22 @@ inline int max_decode_chunk(int, int) { return kMaxChunk; }
 
 // Launchers (kernels_*.hip).  Each returns hipGetLastError() of its launch.
 hipError_t launch_publish(const TablePairs &pairs, int32_t *block_table, hipStream_t st);
+// Profiling of the split-decode kernels: the events of the current profiling slot are attached to the kernel's own
+// dispatch (they then hold the start and the end of the kernel itself, what a kernel trace reports) instead of being
+// recorded around the launch, where they also count the few microseconds between command packets.  The bracket in
+// cache.cpp hands them over, the launch takes them; without profiling both are null and the launch is an ordinary one.
+struct DispatchEvents {
+    hipEvent_t start = nullptr, stop = nullptr;
+};
+void set_dispatch_events(hipEvent_t start, hipEvent_t stop);
+DispatchEvents take_dispatch_events();
+#define H1BKV_LAUNCH_SPLIT(kernel, grid, block, st, ...)                                                  \
+    do {                                                                                                   \
+        const DispatchEvents ev_ = take_dispatch_events();                                                 \
+        if (ev_.start) hipExtLaunchKernelGGL(kernel, grid, block, 0, st, ev_.start, ev_.stop, 0, __VA_ARGS__); \
+        else hipLaunchKernelGGL(kernel, grid, block, 0, st, __VA_ARGS__);   /* (the shorter path on the host) */ \
+    } while (0)
+
 hipError_t launch_append(const AppendArgs &a, const BatchDesc &desc, int n_seqs, const QueryArgs *qa, hipStream_t st);
 hipError_t launch_qsketch(const DecodeArgs &a, int seq0, int n_seqs, hipStream_t st);
 hipError_t launch_decode_split(const DecodeArgs &a, const BatchDesc &desc, int seq0, int n_seqs, hipStream_t st);

@@ -80,7 +80,8 @@ hipError_t launch_stream_read(const void *src, size_t n_bytes, void *sink, hipSt
     const size_t n16 = n_bytes / 16;
     size_t blocks = (n16 + 255) / 256;
     if (blocks > 8192) blocks = 8192;                     // sink holds 8192 x 16 bytes
-    hipLaunchKernelGGL(stream_read_kernel, dim3((unsigned)blocks), dim3(256), 0, st, static_cast<const uint4 *>(src), n16,
+    // (takes the events of h1bkv_stream_read_ms, if that is the caller, onto its dispatch)
+    H1BKV_LAUNCH_SPLIT(stream_read_kernel, dim3((unsigned)blocks), dim3(256), st, static_cast<const uint4 *>(src), n16,
                        static_cast<uint4 *>(sink));
     return hipGetLastError();
 }

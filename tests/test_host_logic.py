@@ -143,6 +143,11 @@ def test_misc_errors():
     assert B.h1bkv_profile_enable(h, 4, 0xF) == B.H1BKV_ENODEVICE and B.h1bkv_profile_enable(h, 0, 0) == B.H1BKV_OK
     assert B.h1bkv_stream_copy(None, None, 16) == B.H1BKV_ENULL
     assert B.h1bkv_stream_copy(4096, 8192, 24) == B.H1BKV_EINVAL
+    assert B.h1bkv_stream_read(None, 16, None) == B.H1BKV_ENULL
+    assert B.h1bkv_stream_read(4096, 24, 8192) == B.H1BKV_EINVAL
+    assert B.h1bkv_stream_read_ms(None, 16, None)[0] == B.H1BKV_ENULL
+    assert B.h1bkv_stream_read_ms(4096, 0, 8192)[0] == B.H1BKV_EINVAL          # nothing to time
+    assert B.h1bkv_stream_read_ms(4096, 24, 8192) == (B.H1BKV_EINVAL, 0.0)
     assert B.h1bkv_destroy(h) == B.H1BKV_OK and B.h1bkv_destroy(None) == B.H1BKV_OK
 
 
