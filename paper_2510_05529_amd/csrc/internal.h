@@ -138,8 +138,8 @@ struct PrefillArgs {
     float exp2_scale;         // 2 log2(e) / (b tau)
 };
 
-// Query positions per prefill workgroup: 256 (eight waves) for long chunks, 128 (four waves) for short ones.
-inline int prefill_rows(int n_q) { return n_q >= 1024 ? 256 : 128; }
+// Query positions per prefill workgroup: 256 (eight waves) from 512 positions per chunk on, 128 (four waves) below.
+inline int prefill_rows(int n_q) { return n_q >= 512 ? 256 : 128; }
 constexpr int kPrefillMaxSplits = 16;
 // Most context splits a prefill call of n_seqs x n_q query positions can use: enough workgroups to fill the chip when
 // the chunk is short (a long prompt alone already brings thousands of workgroups: one split).
