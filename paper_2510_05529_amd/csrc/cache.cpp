@@ -234,7 +234,7 @@ int check_device(const h1bkv_cache *c) {
 }
 
 // Event bracket around one kernel launch; inert unless profiling is enabled.  The split-decode kernel's events ride on its
-// dispatch instead (see H1BKV_LAUNCH_SPLIT): recorded around the launch they only serve a launch that did not take them.
+// dispatch instead (see H1BKV_LAUNCH_TIMED): recorded around the launch they only serve a launch that did not take them.
 struct Timed {
     h1bkv_cache *c;
     int kind;

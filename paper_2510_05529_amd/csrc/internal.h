@@ -168,7 +168,7 @@ inline int max_decode_chunk(int, int) { return kMaxChunk; }
 
 // Launchers (kernels_*.hip).  Each returns hipGetLastError() of its launch.
 hipError_t launch_publish(const TablePairs &pairs, int32_t *block_table, hipStream_t st);
-// Profiling of the split-decode kernels: the events of the current profiling slot are attached to the kernel's own
+// Profiling of the split-decode kernels (and of the timed read-only stream): the events of the current profiling slot are attached to the kernel's own
 // dispatch (they then hold the start and the end of the kernel itself, what a kernel trace reports) instead of being
 // recorded around the launch, where they also count the few microseconds between command packets.  The bracket in
 // cache.cpp hands them over, the launch takes them; without profiling both are null and the launch is an ordinary one.
@@ -177,7 +177,7 @@ struct DispatchEvents {
 };
 void set_dispatch_events(hipEvent_t start, hipEvent_t stop);
 DispatchEvents take_dispatch_events();
-#define H1BKV_LAUNCH_SPLIT(kernel, grid, block, st, ...)                                                  \
+#define H1BKV_LAUNCH_TIMED(kernel, grid, block, st, ...)                                                  \
     do {                                                                                                   \
         const DispatchEvents ev_ = take_dispatch_events();                                                 \
         if (ev_.start) hipExtLaunchKernelGGL(kernel, grid, block, 0, st, ev_.start, ev_.stop, 0, __VA_ARGS__); \

@@ -426,9 +426,9 @@ __global__ void qsketch_kernel(DecodeArgs a, int seq0) {
 template <int RQ, int W, bool DTAU>
 hipError_t launch_split_lpt(const DecodeArgs &a, const BatchDesc &desc, int seq0, dim3 grid, hipStream_t st) {
     switch (a.pool.head_dim) {
-        case 64: H1BKV_LAUNCH_SPLIT((decode_split_kernel<RQ, W, 2, DTAU>), grid, dim3(kThreads), st, a, desc, seq0); break;
-        case 128: H1BKV_LAUNCH_SPLIT((decode_split_kernel<RQ, W, 4, DTAU>), grid, dim3(kThreads), st, a, desc, seq0); break;
-        default: H1BKV_LAUNCH_SPLIT((decode_split_kernel<RQ, W, 8, DTAU>), grid, dim3(kThreads), st, a, desc, seq0); break;
+        case 64: H1BKV_LAUNCH_TIMED((decode_split_kernel<RQ, W, 2, DTAU>), grid, dim3(kThreads), st, a, desc, seq0); break;
+        case 128: H1BKV_LAUNCH_TIMED((decode_split_kernel<RQ, W, 4, DTAU>), grid, dim3(kThreads), st, a, desc, seq0); break;
+        default: H1BKV_LAUNCH_TIMED((decode_split_kernel<RQ, W, 8, DTAU>), grid, dim3(kThreads), st, a, desc, seq0); break;
     }
     return hipGetLastError();
 }

@@ -251,10 +251,10 @@ __global__ __launch_bounds__(kThreads, RQ * (DTAU ? 2 : 1) >= 8 ? 2 : (RQ * (DTA
 template <int RQ, int W, bool DTAU>
 hipError_t launch_d(const DecodeArgs &a, const BatchDesc &desc, int seq0, dim3 grid, hipStream_t st) {
     if (a.pool.head_dim == 64) {
-        H1BKV_LAUNCH_SPLIT((decode_split_f16v_kernel<RQ, W, 64, DTAU>), grid, dim3(kThreads), st, a, desc, seq0);
+        H1BKV_LAUNCH_TIMED((decode_split_f16v_kernel<RQ, W, 64, DTAU>), grid, dim3(kThreads), st, a, desc, seq0);
     } else if constexpr (RQ * (DTAU ? 2 : 1) <= 4) {                 // 8 accumulator sets only fit next to a d = 64 batch
-        if (a.pool.head_dim == 128) H1BKV_LAUNCH_SPLIT((decode_split_f16v_kernel<RQ, W, 128, DTAU>), grid, dim3(kThreads), st, a, desc, seq0);
-        else H1BKV_LAUNCH_SPLIT((decode_split_f16v_kernel<RQ, W, 256, DTAU>), grid, dim3(kThreads), st, a, desc, seq0);
+        if (a.pool.head_dim == 128) H1BKV_LAUNCH_TIMED((decode_split_f16v_kernel<RQ, W, 128, DTAU>), grid, dim3(kThreads), st, a, desc, seq0);
+        else H1BKV_LAUNCH_TIMED((decode_split_f16v_kernel<RQ, W, 256, DTAU>), grid, dim3(kThreads), st, a, desc, seq0);
     } else {
         return hipErrorInvalidConfiguration;
     }

@@ -393,10 +393,10 @@ __global__ __launch_bounds__(kThreads, (RQH == 2 && D <= 128) ? 3 : 2) void deco
 template <int RQH, int D, int NG, bool DTAU>
 hipError_t launch_w(const DecodeArgs &a, const BatchDesc &desc, int seq0, dim3 grid, int rq, hipStream_t st) {
     switch (a.pool.sketch_bits) {
-        case 64: H1BKV_LAUNCH_SPLIT((decode_split_mfma_kernel<RQH, D, NG, 1, DTAU>), grid, dim3(kThreads), st, a, desc, seq0, rq); break;
-        case 128: H1BKV_LAUNCH_SPLIT((decode_split_mfma_kernel<RQH, D, NG, 2, DTAU>), grid, dim3(kThreads), st, a, desc, seq0, rq); break;
-        case 256: H1BKV_LAUNCH_SPLIT((decode_split_mfma_kernel<RQH, D, NG, 4, DTAU>), grid, dim3(kThreads), st, a, desc, seq0, rq); break;
-        case 512: H1BKV_LAUNCH_SPLIT((decode_split_mfma_kernel<RQH, D, NG, 8, DTAU>), grid, dim3(kThreads), st, a, desc, seq0, rq); break;
+        case 64: H1BKV_LAUNCH_TIMED((decode_split_mfma_kernel<RQH, D, NG, 1, DTAU>), grid, dim3(kThreads), st, a, desc, seq0, rq); break;
+        case 128: H1BKV_LAUNCH_TIMED((decode_split_mfma_kernel<RQH, D, NG, 2, DTAU>), grid, dim3(kThreads), st, a, desc, seq0, rq); break;
+        case 256: H1BKV_LAUNCH_TIMED((decode_split_mfma_kernel<RQH, D, NG, 4, DTAU>), grid, dim3(kThreads), st, a, desc, seq0, rq); break;
+        case 512: H1BKV_LAUNCH_TIMED((decode_split_mfma_kernel<RQH, D, NG, 8, DTAU>), grid, dim3(kThreads), st, a, desc, seq0, rq); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();

@@ -81,7 +81,7 @@ hipError_t launch_stream_read(const void *src, size_t n_bytes, void *sink, hipSt
     size_t blocks = (n16 + 255) / 256;
     if (blocks > 8192) blocks = 8192;                     // sink holds 8192 x 16 bytes
     // (takes the events of h1bkv_stream_read_ms, if that is the caller, onto its dispatch)
-    H1BKV_LAUNCH_SPLIT(stream_read_kernel, dim3((unsigned)blocks), dim3(256), st, static_cast<const uint4 *>(src), n16,
+    H1BKV_LAUNCH_TIMED(stream_read_kernel, dim3((unsigned)blocks), dim3(256), st, static_cast<const uint4 *>(src), n16,
                        static_cast<uint4 *>(sink));
     return hipGetLastError();
 }
