@@ -189,8 +189,11 @@ int h1bkv_decode_step(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n_seq
  *                         pages beyond the new length back.  h1bkv_reserved_tokens: positions that have a page.
  *   h1bkv_decode_step_dev as h1bkv_decode_step, but the number of tokens sequence seq_ids_host[i] holds is read by the
  *                         kernels from pos_dev[i] (int32, device memory, 4-byte aligned) when they run: the new token is
- *                         written at position pos_dev[i], the query attends over pos_dev[i] + 1 tokens, and the step's
- *                         last kernel adds one to pos_dev[i].  No kernel touches a position >= max_pos: every sequence
+ *                         written at position pos_dev[i], the query attends over pos_dev[i] + 1 tokens, and with
+ *                         advance = 1 the step's last kernel adds one to pos_dev[i].  advance = 0 leaves the positions
+ *                         alone: the layers of a model, each with a cache of its own, share ONE position array, all but
+ *                         the last layer's step pass 0 and the last one moves the token on for all of them (anything
+ *                         but 0 or 1: H1BKV_EINVAL).  No kernel touches a position >= max_pos: every sequence
  *                         must have pages for max_pos tokens (H1BKV_ERANGE otherwise), launches and workspace
  *                         (>= h1bkv_decode_workspace_bytes(c, n_seqs, max_pos)) are sized for max_pos, and a sequence
  *                         that has reached max_pos is left as it is (no append, attention over its max_pos tokens, no
@@ -206,7 +209,7 @@ int h1bkv_reserve_seq(h1bkv_cache *c, int32_t seq_id, int32_t n_tokens, void *hi
 int h1bkv_reserved_tokens(const h1bkv_cache *c, int32_t seq_id, int32_t *n_out);
 int h1bkv_decode_step_dev(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n_seqs, const void *k_dev,
                           const void *v_dev, int64_t stride_seq, int64_t stride_head, const void *q_dev, float tau,
-                          float *out_dev, int32_t *pos_dev, int32_t max_pos, void *workspace_dev,
+                          float *out_dev, int32_t *pos_dev, int32_t max_pos, int32_t advance, void *workspace_dev,
                           size_t workspace_bytes, void *hip_stream);
 int h1bkv_set_seq_len(h1bkv_cache *c, int32_t seq_id, int32_t new_len);
 

@@ -70,7 +70,7 @@ def lib() -> C.CDLL:
             "h1bkv_decode_step": (C.c_int, [vp, vp, i32, vp, vp, i64, i64, vp, C.c_float, vp, vp, sz, vp]),
             "h1bkv_reserve_seq": (C.c_int, [vp, i32, i32, vp]),
             "h1bkv_reserved_tokens": (C.c_int, [vp, i32, C.POINTER(C.c_int32)]),
-            "h1bkv_decode_step_dev": (C.c_int, [vp, vp, i32, vp, vp, i64, i64, vp, C.c_float, vp, vp, i32, vp, sz, vp]),
+            "h1bkv_decode_step_dev": (C.c_int, [vp, vp, i32, vp, vp, i64, i64, vp, C.c_float, vp, vp, i32, i32, vp, sz, vp]),
             "h1bkv_set_seq_len": (C.c_int, [vp, i32, i32]),
             "h1bkv_decode_dtau_workspace_bytes": (sz, [vp, i32, i32]),
             "h1bkv_decode_attn_dtau": (C.c_int, [vp, vp, i32, vp, C.c_float, vp, vp, vp, sz, vp]),
@@ -209,11 +209,11 @@ def h1bkv_reserved_tokens(h, seq_id: int):
 
 
 def h1bkv_decode_step_dev(h, seq_ids, k, v, stride_seq: int, stride_head: int, q, tau: float, out, pos_dev, max_pos: int,
-                          workspace, workspace_bytes: int, stream=0) -> int:
+                          workspace, workspace_bytes: int, stream=0, advance: int = 1) -> int:
     ids, p = _ids(seq_ids)
     return lib().h1bkv_decode_step_dev(h, p, len(ids), _dev_ptr(k), _dev_ptr(v), stride_seq, stride_head, _dev_ptr(q), tau,
-                                       _dev_ptr(out), _dev_ptr(pos_dev), max_pos, _dev_ptr(workspace), workspace_bytes,
-                                       _stream(stream))
+                                       _dev_ptr(out), _dev_ptr(pos_dev), max_pos, advance, _dev_ptr(workspace),
+                                       workspace_bytes, _stream(stream))
 
 
 def h1bkv_set_seq_len(h, seq_id: int, new_len: int) -> int:

@@ -157,6 +157,7 @@ unsigned char *scratch_for_device(int dev) {
 struct DevicePositions {
     const int32_t *pos;
     int32_t max_pos;
+    int32_t advance;       // the step's last kernel moves the positions one token on
 };
 
 struct EventPair {
@@ -709,7 +710,7 @@ static int enqueue_decode(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n
             desc.pos_dev = dev->pos + s0;
             desc.pos_add = 1;
             desc.pos_max = dev->max_pos;
-            desc.advance = 1;                 // (read by the merge kernels only)
+            desc.advance = dev->advance;      // (read by the merge kernels only)
         }
         if (!sketches_done) {
             Timed t(c, H1BKV_K_QSKETCH, st);
@@ -827,11 +828,12 @@ int h1bkv_set_seq_len(h1bkv_cache *c, int32_t seq_id, int32_t new_len) {
 
 int h1bkv_decode_step_dev(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n_seqs, const void *k_dev, const void *v_dev,
                           int64_t stride_seq, int64_t stride_head, const void *q_dev, float tau, float *out_dev,
-                          int32_t *pos_dev, int32_t max_pos, void *workspace_dev, size_t workspace_bytes, void *hip_stream) {
+                          int32_t *pos_dev, int32_t max_pos, int32_t advance, void *workspace_dev, size_t workspace_bytes,
+                          void *hip_stream) {
     if (!c) return H1BKV_ENULL;
     int rc = check_seq_ids(c, seq_ids_host, n_seqs);
     if (rc != H1BKV_OK) return rc;
-    if (!(tau > 0.0f) || !std::isfinite(tau) || max_pos < 1) return H1BKV_EINVAL;
+    if (!(tau > 0.0f) || !std::isfinite(tau) || max_pos < 1 || (advance != 0 && advance != 1)) return H1BKV_EINVAL;
     // every position the kernels may touch has a page already: nothing is assigned while the step runs (or replays)
     for (int i = 0; i < n_seqs; ++i)
         if (pages_for(max_pos) > (int)c->seq_pages[seq_ids_host[i]].size()) return H1BKV_ERANGE;
@@ -848,12 +850,12 @@ int h1bkv_decode_step_dev(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t n
     rc = check_device(c);
     if (rc != H1BKV_OK) return rc;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    const DevicePositions dev{pos_dev, max_pos};
+    const DevicePositions dev{pos_dev, max_pos, advance};
     rc = enqueue_append(c, seq_ids_host, n_seqs, 1, k_dev, v_dev, stride_seq, 0, stride_head, q_dev,
                         static_cast<uint64_t *>(workspace_dev), st, &dev);
     if (rc != H1BKV_OK) return rc;
-    // (the merge, the step's last kernel, advances the positions; if a launch fails before it they stay as they are and
-    // the appended records lie past every sequence's end)
+    // (the merge, the step's last kernel, advances the positions if asked to; if a launch fails before it they stay as
+    // they are and the appended records lie past every sequence's end)
     return enqueue_decode(c, seq_ids_host, n_seqs, q_dev, tau, out_dev, workspace_dev, true, st, &dev);
 }
 

@@ -234,3 +234,57 @@ def test_device_positions_with_more_sequences_than_one_launch_describes():
                 assert np.array_equal(x, y)
     cache.close()
     twin.close()
+
+
+def test_layers_share_one_position_array_and_the_last_one_advances_it():
+    """Two caches (two layers of a model, different projections and data) step through one HIP graph on ONE position
+    array: the first layer's step leaves the positions alone (advance = 0), the second moves the token on for both."""
+    torch = __import__("torch")
+    n_steps, start = 40, 250                                  # crosses a page boundary
+    layers = []
+    for li in range(2):
+        w = wl.Workload(f"layer{li}", 3, 4, 2, 128, start + n_steps, 128, 32, "f16", seed=60 + li)
+        R = wl.projection(w.sketch_bits, w.head_dim, seed=9 + li)
+        seqs = list(range(w.batch))
+        kd, vd = to_dev(wl.kv_slab(w, "k", seqs, 0, w.context)), to_dev(wl.kv_slab(w, "v", seqs, 0, w.context))
+        cache, twin = make_cache(w, R, extra_pages=1), make_cache(w, R, extra_pages=1)
+        for c_ in (cache, twin):
+            c_.append(seqs, kd[:, :start], vd[:, :start])
+        for s in seqs:
+            assert B.h1bkv_reserve_seq(cache.h, s, n_steps) == B.H1BKV_OK
+        q = to_dev(np.random.default_rng(70 + li).standard_normal((w.batch, w.n_q_heads, w.head_dim)).astype(np.float16))
+        k1, v1 = torch.empty_like(kd[:, 0]), torch.empty_like(vd[:, 0])
+        out_g = torch.zeros((w.batch, w.n_q_heads, w.head_dim), dtype=torch.float32, device="cuda")
+        layers.append(dict(w=w, seqs=seqs, kd=kd, vd=vd, cache=cache, twin=twin, q=q, k1=k1, v1=v1, out_g=out_g,
+                           out_e=torch.empty_like(out_g)))
+    w = layers[0]["w"]
+    max_pos = start + n_steps
+    ws_bytes = B.h1bkv_decode_workspace_bytes(layers[0]["cache"].h, w.batch, max_pos)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    pos = torch.full((w.batch,), start, dtype=torch.int32, device="cuda")
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        for li, L in enumerate(layers):
+            assert B.h1bkv_decode_step_dev(L["cache"].h, L["seqs"], L["k1"], L["v1"], L["k1"].stride(0), L["k1"].stride(1), L["q"], 0.07,
+                                           L["out_g"], pos, max_pos, ws, ws_bytes, None, advance=int(li == 1)) == B.H1BKV_OK
+    pos.fill_(start)
+    for step in range(n_steps):
+        for L in layers:
+            L["k1"].copy_(L["kd"][:, start + step])
+            L["v1"].copy_(L["vd"][:, start + step])
+        torch.cuda.synchronize()
+        g.replay()
+        for L in layers:
+            assert B.h1bkv_decode_step(L["twin"].h, L["seqs"], L["k1"], L["v1"], L["k1"].stride(0), L["k1"].stride(1), L["q"], 0.07,
+                                       L["out_e"], ws, ws_bytes, None) == 0
+            torch.cuda.synchronize()
+            assert rel_err(L["out_g"].cpu().numpy(), L["out_e"].cpu().numpy()) <= 1e-5, f"step {step}"
+        assert pos.cpu().tolist() == [start + step + 1] * w.batch, f"step {step}"
+    for L in layers:
+        for s in L["seqs"]:
+            assert B.h1bkv_set_seq_len(L["cache"].h, s, max_pos) == B.H1BKV_OK
+        for x, y in zip(L["cache"].export(1, 0, 0, max_pos), L["twin"].export(1, 0, 0, max_pos)):
+            assert np.array_equal(x, y)
+        L["cache"].close()
+        L["twin"].close()

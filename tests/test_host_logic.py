@@ -325,9 +325,11 @@ def test_reserved_pages_and_device_position_step_bookkeeping():
     assert B.h1bkv_reserve_seq(h, 1, 300) == B.H1BKV_EHIP and (length(1), free(), B.h1bkv_reserved_tokens(h, 1)[1]) == (0, 6, 0)
     assert B.h1bkv_debug_fail_launch(h, 0) == B.H1BKV_OK
     # the device-position step: argument checks that need no device
-    step = lambda seqs, max_pos, tau=0.1: B.h1bkv_decode_step_dev(h, seqs, None, None, 512, 128, None, tau, None, None, max_pos, None, 0)
+    step = lambda seqs, max_pos, tau=0.1, advance=1: B.h1bkv_decode_step_dev(h, seqs, None, None, 512, 128, None, tau, None, None,
+                                                                             max_pos, None, 0, advance=advance)
     assert step([0], 1025) == B.H1BKV_ERANGE             # sequence 0 holds four pages
     assert step([0], 0) == B.H1BKV_EINVAL and step([0], 100, tau=0.0) == B.H1BKV_EINVAL
+    assert step([0], 100, advance=2) == B.H1BKV_EINVAL and step([0], 1024, advance=0) == B.H1BKV_ENODEVICE
     assert step([0, 0], 100) == B.H1BKV_EINVAL and step([7], 100) == B.H1BKV_ERANGE
     assert step([0], 1024) == B.H1BKV_ENODEVICE          # everything else is in order: only the device is missing
     B.h1bkv_destroy(h)
