@@ -295,7 +295,8 @@ int h1bkv_extend_seq(h1bkv_cache *c, int32_t seq_id, int32_t n_new, void *hip_st
  * of HIP events on the launch stream (up to `capacity` launches per kind; later ones are not recorded).
  * h1bkv_profile_read waits for the recorded events and writes the elapsed milliseconds of each recorded launch
  * of `kernel` to ms_out (at most cap values) and their number to n_out, then clears that kind's records.
- * capacity == 0 disables recording and releases the events.
+ * capacity == 0 disables recording and releases the events.  Launches enqueued while the stream is being captured into
+ * a HIP graph are not timed.
  * A kind whose work takes two kernels (H1BKV_K_APPEND of a large append: the keys' half and the values' half;
  * H1BKV_K_PREFILL with a context split: the attention kernel and its merge) is bracketed once around both.
  * H1BKV_K_DECODE_SPLIT is the exception to the bracket: its two events are attached to the kernel's own dispatch and

@@ -234,6 +234,12 @@ int check_device(const h1bkv_cache *c) {
     return H1BKV_OK;
 }
 
+// (events recorded into a graph under capture hold no times: such launches are not timed)
+inline bool capturing(hipStream_t st) {
+    hipStreamCaptureStatus s = hipStreamCaptureStatusNone;
+    return hipStreamIsCapturing(st, &s) == hipSuccess && s != hipStreamCaptureStatusNone;
+}
+
 // Event bracket around one kernel launch; inert unless profiling is enabled.  The split-decode kernel's events ride on its
 // dispatch instead (see H1BKV_LAUNCH_TIMED): recorded around the launch they only serve a launch that did not take them.
 struct Timed {
@@ -242,7 +248,7 @@ struct Timed {
     hipStream_t st;
     int slot;
     Timed(h1bkv_cache *c_, int kind_, hipStream_t st_) : c(c_), kind(kind_), st(st_), slot(-1) {
-        if (c->prof_cap > 0 && ((c->prof_mask >> kind) & 1u) && c->prof_used[kind] < c->prof_cap &&
+        if (c->prof_cap > 0 && ((c->prof_mask >> kind) & 1u) && c->prof_used[kind] < c->prof_cap && !capturing(st) &&
             c->prof_seen[kind]++ % c->prof_stride == 0) {
             slot = c->prof_used[kind]++;
             if (kind == H1BKV_K_DECODE_SPLIT) set_dispatch_events(c->prof_events[kind][slot].a, c->prof_events[kind][slot].b);

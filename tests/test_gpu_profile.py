@@ -51,3 +51,36 @@ def test_every_kind_is_timed_once_per_launch_and_the_split_kernel_from_its_own_d
     assert len(ms) == steps // 2 and np.all(ms > 0.0)
     B.check(B.h1bkv_profile_enable(cache.h, 0, 0))
     assert np.array_equal(cache.decode(seqs, q, 0.1).cpu().numpy(), ref)
+
+
+def test_launches_under_graph_capture_are_not_timed():
+    w = wl.Workload("prof_graph", 2, 4, 4, 128, 700, 128, 32, "f16", seed=78)
+    R = wl.projection(w.sketch_bits, w.head_dim)
+    seqs = list(range(w.batch))
+    cache = make_cache(w, R, extra_pages=1)
+    cache.append(seqs, to_dev(wl.kv_slab(w, "k", seqs, 0, w.context)), to_dev(wl.kv_slab(w, "v", seqs, 0, w.context)))
+    q = to_dev(wl.queries(w))
+    ws_bytes = B.h1bkv_decode_workspace_bytes(cache.h, w.batch, w.context)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    out = torch.zeros((w.batch, w.n_q_heads, w.head_dim), dtype=torch.float32, device="cuda")
+    ref = cache.decode(seqs, q, 0.1).cpu().numpy()
+    B.check(B.h1bkv_profile_enable(cache.h, 8, 0xF))
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        B.check(B.h1bkv_decode_attn(cache.h, seqs, q, 0.1, out, ws, ws_bytes, None))
+    for _ in range(3):
+        out.zero_()
+        g.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(out.cpu().numpy(), ref)
+    for kid in (B.H1BKV_K_QSKETCH, B.H1BKV_K_DECODE_SPLIT, B.H1BKV_K_MERGE):
+        rc, ms = B.h1bkv_profile_read(cache.h, kid)
+        B.check(rc)
+        assert len(ms) == 0
+    # eager launches afterwards are timed again
+    cache.decode(seqs, q, 0.1)
+    rc, ms = B.h1bkv_profile_read(cache.h, B.H1BKV_K_DECODE_SPLIT)
+    B.check(rc)
+    assert len(ms) == 1 and ms[0] > 0.0
+    B.check(B.h1bkv_profile_enable(cache.h, 0, 0))
