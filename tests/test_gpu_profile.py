@@ -84,3 +84,19 @@ def test_launches_under_graph_capture_are_not_timed():
     B.check(rc)
     assert len(ms) == 1 and ms[0] > 0.0
     B.check(B.h1bkv_profile_enable(cache.h, 0, 0))
+
+
+def test_timed_stream_read_reports_the_kernels_own_duration():
+    n = 256 << 20
+    src = torch.ones(n, dtype=torch.uint8, device="cuda")
+    sink = torch.zeros(128 << 10, dtype=torch.uint8, device="cuda")
+    B.check(B.h1bkv_stream_read(src, n, sink))
+    t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0.record()
+    rc, ms = B.h1bkv_stream_read_ms(src, n, sink)
+    t1.record()
+    torch.cuda.synchronize()
+    B.check(rc)
+    assert 0.0 < ms <= t0.elapsed_time(t1)                   # inside the events recorded around the call
+    assert n / (ms * 1e-3) / 1e12 < 8.0                       # and no faster than the memory allows (bytes partly cached: < peak)
+    assert int(sink[:16].sum()) == 0                          # XOR of an even number of equal words
