@@ -340,10 +340,12 @@ int check_seq_ids(const h1bkv_cache *c, const int32_t *ids, int32_t n) {
 int choose_chunk(const h1bkv_cache *c, int n_seqs, int max_ctx) {
     if (c->chunk_override > 0) return c->chunk_override;
     const int64_t heads = (int64_t)n_seqs * c->cfg.n_kv_heads;
-    // the matrix-core kernel gains from long streams per workgroup: four resident workgroups per compute unit (1024 on
-    // the chip) are enough (measured at 4 x 8 KV heads x 131072 tokens: 77-79 us with 4096-token chunks, 86-88 with
-    // 8192, 80-82 with 2048)
-    const int64_t target_wgs = c->code_layout == 1 ? 1024 : 4096;
+    // the matrix-core kernel gains from long streams per workgroup: two workgroups per compute unit (512 on the chip) are
+    // enough, and more of them only add prologues, epilogues and partial results (measured over eight grouped-query
+    // geometries from 50 MB to 470 MB, contexts of 4k to 128k tokens: the chunk that gives 512 workgroups was the fastest
+    // in every one -- 63.7 us against 74.6 with 1024 workgroups at 16 x 8 KV heads x 32768 tokens, 40.3 against 47.8 at
+    // 64 x 8 x 4096, 14.5 against 16.6 at 2 x 8 x 32768, 65.0 against 66.3 at 4 x 8 x 131072)
+    const int64_t target_wgs = c->code_layout == 1 ? 512 : 4096;
     int chunk = max_decode_chunk(c->r, c->code_layout);
     // Small problems: a workgroup's fixed cost (prologue, four-wave epilogue, partial results) is that of two or three
     // pages of streaming, so below 1024-token chunks only a quarter of the target (at least 1024) is insisted on (measured at 8 x 32
