@@ -345,7 +345,10 @@ int choose_chunk(const h1bkv_cache *c, int n_seqs, int max_ctx) {
     // geometries from 50 MB to 470 MB, contexts of 4k to 128k tokens: the chunk that gives 512 workgroups was the fastest
     // in every one -- 63.7 us against 74.6 with 1024 workgroups at 16 x 8 KV heads x 32768 tokens, 40.3 against 47.8 at
     // 64 x 8 x 4096, 14.5 against 16.6 at 2 x 8 x 32768, 65.0 against 66.3 at 4 x 8 x 131072)
-    const int64_t target_wgs = c->code_layout == 1 ? 512 : 4096;
+    // The vector kernel with two query heads per workgroup (r = 2) behaves the same way (8 x 16 KV heads x 32768 tokens:
+    // 69.0 us with 512 workgroups, 93.4 with 4096; 16 x 4 x 65536: 89.4 against 138.2); with one head per workgroup the
+    // chunk hardly matters from 1024 tokens on, and 4096 workgroups keep the tail of the launch short.
+    const int64_t target_wgs = (c->code_layout == 1 || (c->code_layout == 0 && c->r >= 2)) ? 512 : 4096;
     int chunk = max_decode_chunk(c->r, c->code_layout);
     // Small problems: a workgroup's fixed cost (prologue, four-wave epilogue, partial results) is that of two or three
     // pages of streaming, so below 1024-token chunks only a quarter of the target (at least 1024) is insisted on (measured at 8 x 32
