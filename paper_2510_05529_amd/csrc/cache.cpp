@@ -337,9 +337,11 @@ int check_seq_ids(const h1bkv_cache *c, const int32_t *ids, int32_t n) {
 
 // Chunk (tokens) the decode uses for a call of n_seqs sequences whose longest context is max_ctx:
 // the largest page multiple (<= kMaxChunk) that still leaves enough workgroups to fill the chip.
-int choose_chunk(const h1bkv_cache *c, int n_seqs, int max_ctx) {
+// dtau: the call also computes the temperature derivative (its vector kernel takes one QUERY head per workgroup).
+int choose_chunk(const h1bkv_cache *c, int n_seqs, int max_ctx, bool dtau = false) {
     if (c->chunk_override > 0) return c->chunk_override;
-    const int64_t heads = (int64_t)n_seqs * c->cfg.n_kv_heads;
+    const bool per_query_head = dtau && c->code_layout != 1;
+    const int64_t heads = (int64_t)n_seqs * (per_query_head ? c->cfg.n_q_heads : c->cfg.n_kv_heads);
     // the matrix-core kernel gains from long streams per workgroup: two workgroups per compute unit (512 on the chip) are
     // enough, and more of them only add prologues, epilogues and partial results (measured over eight grouped-query
     // geometries from 50 MB to 470 MB, contexts of 4k to 128k tokens: the chunk that gives 512 workgroups was the fastest
@@ -347,8 +349,11 @@ int choose_chunk(const h1bkv_cache *c, int n_seqs, int max_ctx) {
     // 64 x 8 x 4096, 14.5 against 16.6 at 2 x 8 x 32768, 65.0 against 66.3 at 4 x 8 x 131072)
     // The vector kernel with two query heads per workgroup (r = 2) behaves the same way (8 x 16 KV heads x 32768 tokens:
     // 69.0 us with 512 workgroups, 93.4 with 4096; 16 x 4 x 65536: 89.4 against 138.2); with one head per workgroup the
-    // chunk hardly matters from 1024 tokens on, and 4096 workgroups keep the tail of the launch short.
-    const int64_t target_wgs = (c->code_layout == 1 || (c->code_layout == 0 && c->r >= 2)) ? 512 : 4096;
+    // chunk hardly matters from 1024 tokens on, and 4096 workgroups keep the tail of the launch short.  The derivative's
+    // vector kernel carries two sets of sums per head, like two heads: 265.7 us with 8192-token chunks at 16 x 32 heads x
+    // 32768 tokens, 276.9 with 4096, 296.6 with 2048.
+    const bool two_sets = c->code_layout == 0 && (c->r >= 2 || dtau);
+    const int64_t target_wgs = (c->code_layout == 1 || two_sets) ? 512 : 4096;
     int chunk = max_decode_chunk(c->r, c->code_layout);
     // Small problems: a workgroup's fixed cost (prologue, four-wave epilogue, partial results) is that of two or three
     // pages of streaming, so below 1024-token chunks only a quarter of the target (at least 1024) is insisted on (measured at 8 x 32
@@ -900,7 +905,7 @@ int h1bkv_decode_attn_dtau(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t 
     if (rc != H1BKV_OK) return rc;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
 
-    const int chunk = choose_chunk(c, n_seqs, max_ctx);
+    const int chunk = choose_chunk(c, n_seqs, max_ctx, true);
     const int S = std::max(1, (max_ctx + chunk - 1) / chunk);
     const size_t heads = (size_t)n_seqs * c->cfg.n_q_heads;
     char *ws = static_cast<char *>(workspace_dev);
