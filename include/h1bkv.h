@@ -239,7 +239,7 @@ int h1bkv_decode_attn_dtau(h1bkv_cache *c, const int32_t *seq_ids_host, int32_t 
  * Every cache geometry is supported (a head of 256 channels is served as two halves of 128); with value_bits = 16 the
  * stored fp16 values are used as they are.
  * workspace_dev: >= h1bkv_prefill_workspace_bytes(c, n_seqs, n_q), 256-byte aligned: the chunk's query sketches and, for
- * chunks too short to fill the chip with one workgroup per 128 (from 512 positions on: 256) query positions, the per-row partial results of up to
+ * chunks too short to fill the chip with one workgroup per 128 (from 256 positions on: 256) query positions, the per-row partial results of up to
  * 16 context splits (a chunk of a few hundred positions over a long context is split over the context as well, and
  * the splits are merged by a second kernel -- the same exact re-association as in h1bkv_decode_attn).
  */

@@ -138,15 +138,19 @@ struct PrefillArgs {
     float exp2_scale;         // 2 log2(e) / (b tau)
 };
 
-// Query positions per prefill workgroup: 256 (eight waves) from 512 positions per chunk on, 128 (four waves) below.
-inline int prefill_rows(int n_q) { return n_q >= 512 ? 256 : 128; }
+// Query positions per prefill workgroup: 256 (eight waves) from 256 positions per chunk on, 128 (four waves) below.
+inline int prefill_rows(int n_q) { return n_q >= 256 ? 256 : 128; }
 constexpr int kPrefillMaxSplits = 16;
 // Most context splits a prefill call of n_seqs x n_q query positions can use: enough workgroups to fill the chip when
 // the chunk is short (a long prompt alone already brings thousands of workgroups: one split).
 inline int prefill_max_splits(int n_q_heads, int n_seqs, int n_q) {
     const int rows = prefill_rows(n_q);
     const int64_t wgs = (int64_t)n_q_heads * n_seqs * ((n_q + rows - 1) / rows);
-    const int64_t fill = rows == 256 ? 512 : 1024;      // four rounds of the workgroups a chip holds at once (256 x 1 or 2)
+    // One workgroup per place the chip has for them (256 compute units x 1 of eight waves or 2 of four) and no more: a split
+    // costs partial results and a merge, and halves what a workgroup gets out of its prologue (8k prompts in chunks of
+    // 512 positions: 1.80 ms of attention per prompt batch with one split, 2.36 with two; chunks of 128: 3.51 ms with
+    // four splits, 4.49 with eight, 5.97 with two).
+    const int64_t fill = rows == 256 ? 256 : 512;
     const int64_t s = (fill + wgs - 1) / wgs;
     return (int)(s < 1 ? 1 : s > kPrefillMaxSplits ? kPrefillMaxSplits : s);
 }

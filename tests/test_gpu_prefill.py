@@ -41,10 +41,13 @@ CASES = [(128, 128, 32, 1, "f16", 300, 300),      # a whole prompt, record-major
          (256, 128, 64, 1, "f16", 333, 333),      # 256 channels: two workgroups of 128 channels per head
          (256, 256, 128, 4, "f32", 450, 140),     # ... with several query heads per KV head (record-major codes at this size)
          (256, 64, 32, 2, "f16", 2000, 64),       # ... short chunk over a long context: split over the context, merged
-         # chunks of 512 positions and more run as workgroups of eight waves (256 query rows)
+         # chunks of 256 positions and more run as workgroups of eight waves (256 query rows)
          (128, 128, 32, 1, "f16", 2600, 600),     # ... split over the context as well (few workgroups), ragged last block
          (64, 64, 32, 2, "f32", 900, 513),
-         (128, 128, 32, 1, "f16", 700, 511),      # the largest chunk that still runs as four waves
+         (128, 128, 32, 1, "f16", 700, 511),
+         (128, 128, 32, 2, "f16", 1500, 256),     # the shortest such chunk: one block of rows per head, split over the context
+         (128, 256, 64, 4, "f16", 800, 257),      # ... and one row into a second block (token-interleaved codes)
+         (128, 128, 32, 1, "f16", 900, 255),      # the largest chunk that still runs as four waves
          (128, 128, 32, 1, "f16", 1100, 1100),    # ragged last block (1100 = 4 x 256 + 76)
          (128, 256, 64, 4, "f16", 1300, 1030),    # token-interleaved codes, a context below the chunk
          (64, 64, 32, 2, "f32", 1024, 1024),

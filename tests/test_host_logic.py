@@ -180,19 +180,19 @@ def test_value_bits_configuration():
 
 def test_prefill_workspace_size():
     """Query sketches of the chunk, plus per-row partial results of up to 16 context splits when the chunk alone brings
-    too few workgroups to fill the chip a few times over: fewer than 1024 of heads x sequences x blocks of 128 positions,
-    or, from 512 positions per chunk on, fewer than 512 of ... x blocks of 256 positions."""
+    too few workgroups to fill the chip once: fewer than 512 of heads x sequences x blocks of 128 positions,
+    or, from 256 positions per chunk on, fewer than 256 of ... x blocks of 256 positions."""
     c, h, _ = make()                      # 8 query heads, d = 128, b = 128 (2 words)
     al = lambda x: (x + 255) // 256 * 256
 
     def want(n_seqs, n_q):
         rows = n_seqs * n_q * 8
-        block, fill = (256, 512) if n_q >= 512 else (128, 1024)
+        block, fill = (256, 256) if n_q >= 256 else (128, 512)
         wgs = 8 * n_seqs * ((n_q + block - 1) // block)
         splits = min(16, max(1, -(-fill // wgs)))
         return al(rows * 2 * 8) + (al(rows * splits * (128 + 2) * 4) if splits > 1 else 0)
 
-    for n_seqs, n_q in [(1, 1), (1, 128), (1, 511), (1, 512), (2, 600), (2, 1000), (2, 1024), (1, 3000), (4, 4096), (4, 8192), (3, 129)]:
+    for n_seqs, n_q in [(1, 1), (1, 128), (1, 255), (1, 256), (3, 300), (1, 511), (1, 512), (2, 600), (2, 1000), (2, 1024), (1, 3000), (4, 4096), (4, 8192), (3, 129)]:
         assert B.h1bkv_prefill_workspace_bytes(h, n_seqs, n_q) == want(n_seqs, n_q), (n_seqs, n_q)
     assert want(4, 8192) == al(4 * 8192 * 8 * 16)       # a long prompt: one split, sketches only
     assert B.h1bkv_prefill_workspace_bytes(h, 0, 5) == 0 and B.h1bkv_prefill_workspace_bytes(h, 2, 0) == 0
