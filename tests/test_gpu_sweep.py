@@ -123,3 +123,38 @@ def test_sketch_bits_stay_exact_for_fp32_keys_of_any_magnitude(scale, d):
     got = cache.workspace[: n_words * 8].cpu().numpy().view(np.uint64).reshape(2, T, w.n_q_heads, b // 64)
     assert np.array_equal(got, cref.sketch(R, k))
     cache.close()
+
+
+@pytest.mark.parametrize("r,dtau", [(2, False), (1, True), (4, False), (4, True)])
+def test_long_chunks_of_32_pages(r, dtau):
+    """Chunks of 8192 tokens (32 pages per workgroup), the launch shape of large problems, on a context a little longer
+    than one chunk: the vector kernel with two query heads per workgroup, the temperature derivative's kernel and the
+    matrix-core kernel, each against the oracle and against its own result with short chunks."""
+    T = 8192 + 700
+    w = wl.Workload(f"long_chunk_r{r}_{int(dtau)}", 2, 2 * r, 2, 128, T, 128, 32, "f16", seed=400 + r + int(dtau))
+    R = wl.projection(w.sketch_bits, w.head_dim)
+    seqs = [0, 1]
+    k, v, q = wl.kv_slab(w, "k", seqs, 0, T), wl.kv_slab(w, "v", seqs, 0, T), wl.queries(w)
+    oc = cref.Cache(R, 2, 2, T, w.group_size)
+    oc.append(k, v)
+    cache = make_cache(w, R)
+    kd, vd = to_dev(k), to_dev(v)
+    for t0 in range(0, T, 2048):
+        cache.append(seqs, kd[:, t0:t0 + 2048], vd[:, t0:t0 + 2048])
+    tau = w.default_tau()
+    outs = []
+    for chunk in (8192, 1024):
+        assert B.h1bkv_set_decode_chunk(cache.h, chunk) == B.H1BKV_OK
+        if dtau:
+            out, dout = cache.decode_dtau(seqs, to_dev(q), tau)
+            ref, dref = oc.decode_dtau(q, tau)
+            assert rel_err(dout.cpu().numpy(), dref) <= TOL
+        else:
+            out = cache.decode(seqs, to_dev(q), tau)
+            ref = oc.decode(q, tau)
+        assert rel_err(out.cpu().numpy(), ref) <= TOL
+        outs.append(out.cpu().numpy())
+    # only the summation order differs: fp32 sums in the vector kernels; the matrix-core kernel's weights are two bf16
+    # pieces (its error against the oracle is 1.3e-5 at 128k tokens)
+    assert rel_err(outs[0], outs[1]) < (5e-5 if r >= 3 else 1e-5)
+    cache.close()
