@@ -352,7 +352,9 @@ int choose_chunk(const h1bkv_cache *c, int n_seqs, int max_ctx, bool dtau = fals
     // chunk hardly matters from 1024 tokens on, and 4096 workgroups keep the tail of the launch short.  The derivative's
     // vector kernel carries two sets of sums per head, like two heads: 265.7 us with 8192-token chunks at 16 x 32 heads x
     // 32768 tokens, 276.9 with 4096, 296.6 with 2048.
-    const bool two_sets = c->code_layout == 0 && (c->r >= 2 || dtau);
+    // (the fp16-value kernel with several heads per workgroup likewise, if less so: 8 x 8 KV heads x 16384 tokens, r = 4:
+    // 63.5 us with 512 workgroups, 68.2 with 4096)
+    const bool two_sets = (c->code_layout == 0 && (c->r >= 2 || dtau)) || (c->code_layout == 2 && c->r >= 2);
     const int64_t target_wgs = (c->code_layout == 1 || two_sets) ? 512 : 4096;
     int chunk = max_decode_chunk(c->r, c->code_layout);
     // Small problems: a workgroup's fixed cost (prologue, four-wave epilogue, partial results) is that of two or three
