@@ -22,8 +22,8 @@
 //             than the fp16 range of the weights allows (its address then lies in front of the table).
 //             The normalisation uses the sums of the SAME fp16 weights (two per v_dot2).
 //   values    sum_t p[i][t] v^[t][c]  with v_mfma_f32_32x32x16_f16, fp32 accumulate.
-// One workgroup (4 waves) takes 128 consecutive query positions of one (sequence, query head) -- 32 rows per wave --
-// and walks the key tokens in tiles of 64 up to its diagonal.  Per tile the workgroup stages ONCE, for all its rows: the
+// One workgroup (8 waves; 4 for chunks of fewer than 256 positions) takes 256 (128) consecutive query positions of one
+// (sequence, query head) -- 32 rows per wave -- and walks the key tokens in tiles of 64 up to its diagonal.  Per tile the workgroup stages ONCE, for all its rows: the
 // keys' bits as fp4 nibbles, and the values dequantised, v^ = fp16(scale * code + zero), channel-major, in the token
 // order the score MFMA leaves its results in (so an MFMA B operand is one 16-byte LDS read).  The next tile's global
 // loads are issued before the current tile is consumed.  Tiles entirely below a wave's rows take an unmasked path;
